@@ -1,0 +1,84 @@
+"""ctypes wrapper around the oracle library (TEST INFRASTRUCTURE ONLY)."""
+import ctypes as C
+from dataclasses import dataclass
+from typing import Optional
+
+import numpy as np
+
+from . import build as _build
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        path = _build.build(force=False)
+        L = C.CDLL(path)
+        L.gorgo_oracle_p95.restype = C.c_double
+        L.gorgo_oracle_p95.argtypes = [C.c_void_p, C.c_int64]
+        L.gorgo_oracle_replay.restype = C.c_int
+        L.gorgo_oracle_replay.argtypes = [C.c_int64] + [C.c_void_p] * 5 + [C.c_int32, C.c_int32, C.c_int32,
+                                                                          C.c_int64, C.c_double, C.c_double,
+                                                                          C.c_void_p, C.c_void_p, C.c_double] + \
+                                          [C.c_void_p] * 8
+        _lib = L
+    return _lib
+
+
+def _p(a):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+@dataclass
+class Replay:
+    route: np.ndarray        # uint8 [N]
+    hit_blocks: np.ndarray   # uint16 [N]
+    ttft_ms: np.ndarray      # float64 [N]
+    e2e_ms: np.ndarray       # float64 [N]
+    p95_ttft_ms: float
+    p95_e2e_ms: float
+    score: Optional[np.ndarray] = None   # float64 [N,R]
+    q: Optional[np.ndarray] = None       # int64 [N,R]
+    size: Optional[np.ndarray] = None    # int64 [N]
+
+
+def p95(x) -> float:
+    x = np.ascontiguousarray(x, dtype=np.float64)
+    return float(lib().gorgo_oracle_p95(_p(x), x.shape[0]))
+
+
+def replay(trace, *, R, batch, cache_blocks, prefill_ms_per_token, decode_ms_per_token, rtt_ms, w, scale=1.0,
+           block_tokens=512, debug=False) -> Replay:
+    """One sequential replay of `trace` (any object with ts_ms, in_len, out_len, blk_off, hash_ids)."""
+    N = int(trace.ts_ms.shape[0])
+    ts = np.ascontiguousarray(trace.ts_ms, dtype=np.int64)
+    il = np.ascontiguousarray(trace.in_len, dtype=np.int32)
+    ol = np.ascontiguousarray(trace.out_len, dtype=np.int32)
+    bo = np.ascontiguousarray(trace.blk_off, dtype=np.int64)
+    hi = np.ascontiguousarray(trace.hash_ids, dtype=np.int64)
+    rtt = np.ascontiguousarray(rtt_ms, dtype=np.float64)
+    wv = np.ascontiguousarray(w, dtype=np.float64)
+    assert rtt.shape == (R,) and wv.shape == (3,) and bo.shape == (N + 1,)
+    route = np.zeros(N, np.uint8)
+    hit = np.zeros(N, np.uint16)
+    ttft = np.zeros(N, np.float64)
+    e2e = np.zeros(N, np.float64)
+    p = np.zeros(2, np.float64)
+    score = np.zeros((N, R), np.float64) if debug else None
+    q = np.zeros((N, R), np.int64) if debug else None
+    size = np.zeros(N, np.int64) if debug else None
+    rc = lib().gorgo_oracle_replay(N, _p(ts), _p(il), _p(ol), _p(bo), _p(hi), block_tokens, R, batch,
+                                   cache_blocks, prefill_ms_per_token, decode_ms_per_token, _p(rtt), _p(wv),
+                                   float(scale), _p(route), _p(hit), _p(ttft), _p(e2e), _p(p), _p(score), _p(q),
+                                   _p(size))
+    if rc != 0:
+        raise RuntimeError(f"gorgo_oracle_replay failed with code {rc}")
+    return Replay(route, hit, ttft, e2e, float(p[0]), float(p[1]), score, q, size)
+
+
+def replay_workload(wl, p: int, debug=False, trace=None) -> Replay:
+    """Replay candidate p of a synth.tracegen.Workload."""
+    return replay(trace if trace is not None else wl.trace, R=wl.R, batch=wl.batch, cache_blocks=wl.cache_blocks,
+                  prefill_ms_per_token=wl.prefill_ms_per_token, decode_ms_per_token=wl.decode_ms_per_token,
+                  rtt_ms=wl.rtt_ms, w=wl.params[p], scale=wl.scale[p], block_tokens=wl.block_tokens, debug=debug)

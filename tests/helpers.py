@@ -1,0 +1,115 @@
+"""Test-side helpers: golden-file loading and independent pure-Python models used to pin the oracle.
+
+Nothing here is imported by the oracle or by the GPU library.
+"""
+import json
+import os
+
+import numpy as np
+
+from synth.tracegen import Trace
+
+GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+
+
+def load_golden(name):
+    with open(os.path.join(GOLDEN, name)) as f:
+        g = json.load(f)
+    reqs = g["requests"]
+    nblk = np.array([len(q["hash_ids"]) for q in reqs], dtype=np.int64)
+    tr = Trace(np.array([q["timestamp"] for q in reqs], dtype=np.int64),
+               np.array([q["input_length"] for q in reqs], dtype=np.int32),
+               np.array([q["output_length"] for q in reqs], dtype=np.int32),
+               np.concatenate([[0], np.cumsum(nblk)]).astype(np.int64),
+               np.array([x for q in reqs for x in q["hash_ids"]], dtype=np.int64))
+    return g, tr
+
+
+def model_kwargs(g):
+    m = g["model"]
+    return dict(R=m["R"], batch=m["batch"], cache_blocks=m["cache_blocks"], block_tokens=m["block_tokens"],
+                prefill_ms_per_token=m["prefill_ms_per_token"], decode_ms_per_token=m["decode_ms_per_token"],
+                rtt_ms=g["rtt_ms"], w=g["w"], scale=g["scale"])
+
+
+class ForcedRouteModel:
+    """Independent pure-Python replay in which the ROUTE of every request is dictated from outside.
+
+    For each request it reports the score every replica would have had (Eq. 3) given the state that the
+    dictated predecessors induced; a route sequence is self-consistent when every dictated route is the
+    lowest-index minimum of those scores.  The cache is a recency-ordered Python list (move-to-front,
+    evict from the cold end), the in-flight set a plain list scanned at each request: different data
+    structures from the oracle's on purpose.
+    """
+
+    def __init__(self, trace, R, batch, cache_blocks, block_tokens, a_pf, a_dec, rtt, w, scale):
+        self.tr, self.R, self.B, self.C, self.bt = trace, R, batch, cache_blocks, block_tokens
+        self.a_pf, self.a_dec, self.rtt, self.w, self.scale = a_pf, a_dec, list(rtt), list(w), scale
+
+    def run(self, routes):
+        tr = self.tr
+        lru = [[] for _ in range(self.R)]            # coldest first ... hottest last
+        free = [[0.0] * self.B for _ in range(self.R)]
+        inflight = [[] for _ in range(self.R)]       # (done, tokens)
+        consistent = True
+        out = dict(score=[], hit=[], ttft=[], e2e=[], q=[], done=[])
+        for r in range(tr.N):
+            ids = [int(x) for x in tr.ids_of(r)]
+            L, O = int(tr.in_len[r]), int(tr.out_len[r])
+            t = float(int(tr.ts_ms[r])) * self.scale
+            q = []
+            for i in range(self.R):
+                inflight[i] = [(d, tok) for (d, tok) in inflight[i] if not d <= t]
+                q.append(sum(tok for _, tok in inflight[i]))
+            scores, us, ms = [], [], []
+            for i in range(self.R):
+                m = 0
+                while m < len(ids) and ids[m] in lru[i]:
+                    m += 1
+                u = L - min(L, self.bt * m)
+                pf = self.a_pf * float(u)
+                qd = self.a_pf * float(q[i])
+                scores.append((self.w[0] * self.rtt[i] + self.w[1] * pf) + self.w[2] * qd)
+                us.append(u)
+                ms.append(m)
+            best = min(range(self.R), key=lambda i: (scores[i], i))
+            i = routes[r]
+            if i != best:
+                consistent = False
+            # cache: evict cold entries that are not part of this request, then touch deepest block first
+            # so that the root ends up hottest
+            mine = set(ids)
+            if self.C > 0:
+                n_new = len([x for x in mine if x not in lru[i]])
+                excess = len(lru[i]) + n_new - self.C
+                keep = []
+                for x in lru[i]:
+                    if excess > 0 and x not in mine:
+                        excess -= 1
+                    else:
+                        keep.append(x)
+                lru[i] = keep
+            first_pos = {}
+            for k, x in enumerate(ids):
+                first_pos.setdefault(x, k)
+            for x in sorted(first_pos, key=lambda x: -first_pos[x]):
+                if x in lru[i]:
+                    lru[i].remove(x)
+                lru[i].append(x)
+            half = 0.5 * self.rtt[i]
+            a = t + half
+            ks = min(range(self.B), key=lambda k: (free[i][k], k))
+            s = max(a, free[i][ks])
+            f = s + self.a_pf * float(us[i])
+            e = f + self.a_dec * float(O)
+            free[i][ks] = e
+            done = e + half
+            inflight[i].append((done, L))
+            out["score"].append(scores)
+            out["hit"].append(ms[i])
+            out["ttft"].append((f + half) - t)
+            out["e2e"].append(done - t)
+            out["q"].append(q)
+            out["done"].append(done)
+        out["consistent"] = consistent
+        return out
