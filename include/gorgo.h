@@ -1,0 +1,182 @@
+/* gorgo.h -- C ABI of the batched routing-fitness evaluator (MI355X / gfx950).
+ *
+ * The library replays a Mooncake-style request trace under a whole population of cost-model weight
+ * vectors at once.  For every request, every candidate scores every replica with the three TTFT terms of
+ * the paper's cost model (Eq. 1-3: weighted RTT + prefill cost of the uncached suffix + weighted queueing
+ * term from proxy-recorded load), routes to the replica of minimum score, updates that replica's cache and
+ * queue state, and the replay is reduced to p95 TTFT / p95 E2E -- the objective of the tuner of Sec. 2.3.
+ *
+ * Conventions
+ *   - every function returns an int: GORGO_OK (0) or a negative gorgo_status; nothing throws, aborts or
+ *     prints.  gorgo_last_error() gives a human-readable message for the last failure on this thread.
+ *   - "host" pointers are ordinary CPU memory, "device" pointers are HIP device memory of the current
+ *     device.  All arrays are caller-owned; handles (gorgo_trace*) are library-owned and released with the
+ *     matching free function.
+ *   - all argument validation happens before anything is enqueued: an error return means that no output
+ *     byte was written and no kernel was launched.
+ *   - no routine falls back to the CPU: evaluation entry points fail with GORGO_ERR_DEVICE when no GPU is
+ *     usable.
+ */
+#ifndef GORGO_H
+#define GORGO_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum gorgo_status {
+    GORGO_OK = 0,
+    GORGO_ERR_INVALID_ARG = -1, /* null pointer, size out of range, model limits exceeded                */
+    GORGO_ERR_IO = -2,          /* file cannot be opened / read                                          */
+    GORGO_ERR_PARSE = -3,       /* malformed trace record                                                */
+    GORGO_ERR_UNSORTED = -4,    /* timestamps decrease                                                   */
+    GORGO_ERR_CAPACITY = -5,    /* a request has more distinct blocks than the bounded cache can hold    */
+    GORGO_ERR_NONFINITE = -6,   /* NaN / Inf / out-of-range value among weights, RTTs, scales, constants */
+    GORGO_ERR_WORKSPACE = -7,   /* caller workspace too small or misaligned                              */
+    GORGO_ERR_OOM = -8,         /* host or device allocation failed                                      */
+    GORGO_ERR_DEVICE = -9       /* HIP error or no device                                                */
+} gorgo_status;
+
+/* Message for the most recent failure on the calling thread ("" if none).  Library-owned, valid until the
+ * next library call on this thread. */
+const char* gorgo_last_error(void);
+
+/* ------------------------------------------------------------------------------------------------ trace
+ * A trace is the replay input of Sec. 3 ("Dataset"): per-request timestamps that can be scaled linearly,
+ * request metadata, and one integer hash id per fixed-size prompt block (Mooncake FAST'25 layout).  It is
+ * immutable after load and can be shared by any number of evaluations. */
+typedef struct gorgo_trace gorgo_trace;
+
+/* Parse a JSON-lines file (host path).  One object per line with integer members "timestamp" (ms),
+ * "input_length", "output_length" (tokens) and "hash_ids" (array of integers, one per block of
+ * `block_tokens` tokens); other members are ignored.  Timestamps must be non-decreasing (equal timestamps
+ * keep file order).  On success *out receives a new handle. */
+int gorgo_load_trace(const char* jsonl_path, int32_t block_tokens, gorgo_trace** out);
+
+/* Same, from host arrays (copied; the caller keeps its arrays).  blk_off has N+1 entries, blk_off[0] = 0,
+ * request r owns hash_ids[blk_off[r] .. blk_off[r+1]).  Limits: 0 <= N < 2^31-1, at most 65535 blocks per
+ * request, lengths >= 0. */
+int gorgo_load_trace_arrays(int64_t N, const int64_t* ts_ms, const int32_t* in_len, const int32_t* out_len,
+                            const int64_t* blk_off, const int64_t* hash_ids, int32_t block_tokens,
+                            gorgo_trace** out);
+
+/* Trace statistics (each out pointer may be NULL): request count, total blocks, largest block count of one
+ * request, number of distinct hash ids, and whether the trace is chain-consistent (every id always appears
+ * at one position with one predecessor, never twice in a request -- true for prefix hashes). */
+int gorgo_trace_info(const gorgo_trace* t, int64_t* N, int64_t* total_blocks, int32_t* max_blocks,
+                     int64_t* unique_ids, int32_t* chain_consistent);
+
+/* Releases host and device storage of the handle (NULL is allowed). */
+void gorgo_free_trace(gorgo_trace* t);
+
+/* ------------------------------------------------------------------------------------------------ model
+ * The replica side.  The paper leaves the replica service model open (Sec. 2.1-2.2); this library fixes a
+ * linear one: each replica has `batch` service slots, a request takes the earliest-free slot (lowest index
+ * on ties), prefill costs prefill_ms_per_token per uncached token, decode costs decode_ms_per_token per
+ * output token, and every message between proxy and replica takes half the replica's RTT.  Each replica
+ * caches blocks with least-recently-used eviction at block granularity (cache_blocks = 0: unbounded).
+ * Limits: 1 <= R <= 64, 1 <= batch <= 64, R * batch <= 1024. */
+typedef struct gorgo_model {
+    int32_t R;             /* replicas                                        */
+    int32_t batch;         /* concurrent service slots per replica            */
+    int32_t block_tokens;  /* must equal the trace's                          */
+    int32_t _pad;          /* set to 0                                        */
+    int64_t cache_blocks;  /* per-replica cache capacity in blocks, 0 = unbounded */
+    double prefill_ms_per_token;
+    double decode_ms_per_token;
+} gorgo_model;
+
+/* Per-replay outputs.  Every pointer is a DEVICE pointer owned by the caller, or NULL to skip that output.
+ * P = number of replays, N = requests in the trace; [P][N] arrays are row-major (replay-major). */
+typedef struct gorgo_outputs {
+    uint8_t* route;        /* [P][N] chosen replica                                           */
+    uint16_t* hit_blocks;  /* [P][N] blocks of the request found cached on the chosen replica */
+    double* ttft_ms;       /* [P][N] time to first token                                      */
+    double* e2e_ms;        /* [P][N] end-to-end latency                                       */
+    double* p95_ttft_ms;   /* [P]    nearest-rank 95th percentile of ttft_ms[p][.]            */
+    double* p95_e2e_ms;    /* [P]    nearest-rank 95th percentile of e2e_ms[p][.]             */
+} gorgo_outputs;
+
+/* Device workspace needed by gorgo_eval_population for P replays with this set of outputs (`outputs` may
+ * be NULL: the size then covers any combination).  The workspace holds the per-replay cache tables, the
+ * in-flight request records and stand-ins for per-request outputs that were not requested but are needed
+ * by the percentile reduction. */
+int gorgo_workspace_bytes(const gorgo_trace* t, const gorgo_model* m, int32_t P, const gorgo_outputs* outputs,
+                          size_t* bytes);
+
+/* Evaluate P replays of the trace (Eq. 1-3, Sec. 2.2-2.3; one replay per candidate weight vector and time
+ * scale).  Replay p uses weights params[3p..3p+2] = (w_rtt, w_prefill, w_queue) and scales every timestamp
+ * by scale[p] (Sec. 3: time between requests is scaled linearly to control replica load).
+ *   rtt_ms  host [R]     round-trip time proxy <-> replica, finite, 0 <= rtt <= 1e9
+ *   params  host [P][3]  finite, |w| <= 1e100 (negative weights are legal)
+ *   scale   host [P]     finite, 0 <= scale <= 1e6
+ *   workspace            device, 256-byte aligned, at least gorgo_workspace_bytes(); contents are scratch
+ *   hip_stream           hipStream_t (NULL = default stream)
+ * The call copies the small host arrays, enqueues its kernels on the stream and returns without waiting
+ * for them; outputs are valid once the stream has reached that point.  The first evaluation of a trace on
+ * a device uploads the trace (one allocation and one synchronous copy).  Calls that share a workspace must
+ * be ordered on one stream. */
+int gorgo_eval_population(const gorgo_trace* t, const gorgo_model* m, const double* rtt_ms,
+                          const double* params, const double* scale, int32_t P, const gorgo_outputs* outputs,
+                          void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* ------------------------------------------------------------------------------------------------ tuner
+ * Evolution-strategy state (Sec. 2.3): parent weights theta, step size sigma, per-weight ranges, the
+ * generation counter and the best candidate seen so far.  Plain data, caller-owned; serialise it to
+ * checkpoint a tuning run.  A weight with lo == hi is pinned (the paper pins the prefill weight to 1). */
+typedef struct gorgo_es_state {
+    double theta[3];
+    double sigma;
+    double lo[3];
+    double hi[3];
+    uint64_t seed;
+    int64_t generation;
+    double best_fitness;   /* +inf before the first update */
+    double best_theta[3];
+} gorgo_es_state;
+
+/* Paper defaults: theta = (0.5, 1, 0.1), ranges [0.05, 2] / [1, 1] / [0.05, 0.5], sigma = 0.5 (Sec. 4). */
+int gorgo_es_init(gorgo_es_state* s, uint64_t seed);
+
+/* Standard-normal draws z[P][3] (host) of one generation: a counter-based generator (Philox-4x32-10 keyed
+ * by the seed, counter = (generation, candidate), Box-Muller transform), so that a generation can be
+ * reproduced from (seed, generation) alone. */
+int gorgo_es_sample(uint64_t seed, int64_t generation, int32_t P, double* z);
+
+/* The generator's block function alone (for known-answer tests): out = Philox-4x32-10(counter, key). */
+void gorgo_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]);
+
+/* Candidates of one generation from given draws (host arrays): params[0] = theta (the parent itself),
+ * params[p][k] = clip(exp(ln theta[k] + sigma * z[p][k]), lo[k], hi[k]) for p >= 1 (mutation rule of
+ * Sec. 2.3).  Requires theta, lo, hi > 0. */
+int gorgo_es_propose(const gorgo_es_state* s, const double* z, int32_t P, double* params);
+
+/* Selection and step-size update from evaluated candidates (host arrays; fitness is minimised).  Rank by
+ * (fitness, index); the new parent is the geometric mean of the best max(1, P/4) candidates, clipped (for
+ * P < 8 this is the best candidate itself, so P = 2 is the paper's accept-if-better step); sigma is
+ * multiplied by exp((s - 1/5) / 2) with s the fraction of offspring that strictly beat the parent
+ * (Rechenberg's 1/5 rule); generation is incremented; the best candidate so far is recorded. */
+int gorgo_es_update(const double* params, const double* fitness, int32_t P, gorgo_es_state* inout);
+
+/* One full generation: sample, propose, evaluate all P candidates at one time scale with
+ * gorgo_eval_population (fitness = p95 TTFT in ms), synchronise the stream once, update the state.
+ * params_out [P][3] and fitness_out [P] are optional host arrays.  The workspace must be sized with
+ * gorgo_es_workspace_bytes. */
+int gorgo_es_workspace_bytes(const gorgo_trace* t, const gorgo_model* m, int32_t P, size_t* bytes);
+int gorgo_es_step(const gorgo_trace* t, const gorgo_model* m, const double* rtt_ms, double scale, int32_t P,
+                  gorgo_es_state* inout, double* params_out, double* fitness_out, void* workspace,
+                  size_t workspace_bytes, void* hip_stream);
+
+/* ------------------------------------------------------------------------------------------------ misc
+ * Tuning knob for tests and experiments: the open-addressed cache tables get at least
+ * ceil(factor_percent/100 * (cache_blocks + max blocks of a request)) slots, rounded up to a power of two
+ * (default 200, minimum 110).  Results never depend on it. */
+int gorgo_set_table_factor_percent(int32_t factor_percent);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GORGO_H */

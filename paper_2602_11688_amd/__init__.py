@@ -1,0 +1,5 @@
+"""MI355X-native batched routing-fitness evaluation (replay of a request trace under a population of
+cost-model weight vectors).  The compute lives in libgorgo.so (hand-written HIP for gfx950); this package
+is the thin ctypes binding."""
+from .binding import (GorgoError, Model, Trace, es_init, es_propose, es_sample, es_step, es_update,  # noqa: F401
+                      eval_population, lib, philox4x32_10, set_table_factor_percent, workspace_bytes)

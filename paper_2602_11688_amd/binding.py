@@ -1,0 +1,276 @@
+"""ctypes binding of libgorgo.so: argument marshalling only -- every step of the evaluation runs in the
+library's HIP kernels.  torch is used for device memory and streams, nothing else."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libgorgo.so")
+_lib = None
+
+
+class GorgoError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"gorgo error {code}: {msg}")
+        self.code = code
+
+
+class _Model(C.Structure):
+    _fields_ = [("R", C.c_int32), ("batch", C.c_int32), ("block_tokens", C.c_int32), ("_pad", C.c_int32),
+                ("cache_blocks", C.c_int64), ("prefill_ms_per_token", C.c_double),
+                ("decode_ms_per_token", C.c_double)]
+
+
+class _Outputs(C.Structure):
+    _fields_ = [("route", C.c_void_p), ("hit_blocks", C.c_void_p), ("ttft_ms", C.c_void_p), ("e2e_ms", C.c_void_p),
+                ("p95_ttft_ms", C.c_void_p), ("p95_e2e_ms", C.c_void_p)]
+
+
+class EsState(C.Structure):
+    _fields_ = [("theta", C.c_double * 3), ("sigma", C.c_double), ("lo", C.c_double * 3), ("hi", C.c_double * 3),
+                ("seed", C.c_uint64), ("generation", C.c_int64), ("best_fitness", C.c_double),
+                ("best_theta", C.c_double * 3)]
+
+
+def lib():
+    """Load the HIP library.  There is no fallback: a missing library is an error."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise RuntimeError(f"{_LIB_PATH} is missing: build it with `python -m paper_2602_11688_amd.build`")
+        try:
+            import torch  # noqa: F401  (loads the HIP runtime that the library shares with torch's allocator)
+        except Exception:  # pragma: no cover
+            pass
+        L = C.CDLL(_LIB_PATH)
+        vp, i32, i64, dbl = C.c_void_p, C.c_int32, C.c_int64, C.c_double
+        L.gorgo_last_error.restype = C.c_char_p
+        L.gorgo_last_error.argtypes = []
+        L.gorgo_load_trace.argtypes = [C.c_char_p, i32, C.POINTER(vp)]
+        L.gorgo_load_trace_arrays.argtypes = [i64, vp, vp, vp, vp, vp, i32, C.POINTER(vp)]
+        L.gorgo_trace_info.argtypes = [vp, C.POINTER(i64), C.POINTER(i64), C.POINTER(i32), C.POINTER(i64), C.POINTER(i32)]
+        L.gorgo_free_trace.argtypes = [vp]
+        L.gorgo_free_trace.restype = None
+        L.gorgo_workspace_bytes.argtypes = [vp, C.POINTER(_Model), i32, C.POINTER(_Outputs), C.POINTER(C.c_size_t)]
+        L.gorgo_eval_population.argtypes = [vp, C.POINTER(_Model), vp, vp, vp, i32, C.POINTER(_Outputs), vp,
+                                            C.c_size_t, vp]
+        L.gorgo_es_init.argtypes = [C.POINTER(EsState), C.c_uint64]
+        L.gorgo_es_sample.argtypes = [C.c_uint64, i64, i32, vp]
+        L.gorgo_philox4x32_10.argtypes = [vp, vp, vp]
+        L.gorgo_philox4x32_10.restype = None
+        L.gorgo_es_propose.argtypes = [C.POINTER(EsState), vp, i32, vp]
+        L.gorgo_es_update.argtypes = [vp, vp, i32, C.POINTER(EsState)]
+        L.gorgo_es_workspace_bytes.argtypes = [vp, C.POINTER(_Model), i32, C.POINTER(C.c_size_t)]
+        L.gorgo_es_step.argtypes = [vp, C.POINTER(_Model), vp, dbl, i32, C.POINTER(EsState), vp, vp, vp, C.c_size_t, vp]
+        L.gorgo_set_table_factor_percent.argtypes = [i32]
+        for name in ("gorgo_load_trace", "gorgo_load_trace_arrays", "gorgo_trace_info", "gorgo_workspace_bytes",
+                     "gorgo_eval_population", "gorgo_es_init", "gorgo_es_sample", "gorgo_es_propose",
+                     "gorgo_es_update", "gorgo_es_workspace_bytes", "gorgo_es_step", "gorgo_set_table_factor_percent"):
+            getattr(L, name).restype = C.c_int
+        _lib = L
+    return _lib
+
+
+def _check(rc: int):
+    if rc != 0:
+        raise GorgoError(rc, lib().gorgo_last_error().decode())
+
+
+def _np(a, dtype):
+    return np.ascontiguousarray(a, dtype=dtype)
+
+
+def _ptr(a):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+@dataclass
+class Model:
+    R: int
+    batch: int
+    cache_blocks: int
+    prefill_ms_per_token: float
+    decode_ms_per_token: float
+    block_tokens: int = 512
+
+    def c(self) -> _Model:
+        return _Model(self.R, self.batch, self.block_tokens, 0, self.cache_blocks, self.prefill_ms_per_token,
+                      self.decode_ms_per_token)
+
+
+class Trace:
+    """Handle of a loaded trace (gorgo_load_trace / gorgo_load_trace_arrays)."""
+
+    def __init__(self, handle):
+        self._h = handle
+
+    @classmethod
+    def from_jsonl(cls, path: str, block_tokens: int = 512) -> "Trace":
+        h = C.c_void_p()
+        _check(lib().gorgo_load_trace(os.fsencode(path), block_tokens, C.byref(h)))
+        return cls(h)
+
+    @classmethod
+    def from_arrays(cls, ts_ms, in_len, out_len, blk_off, hash_ids, block_tokens: int = 512) -> "Trace":
+        ts, il, ol = _np(ts_ms, np.int64), _np(in_len, np.int32), _np(out_len, np.int32)
+        bo, hi = _np(blk_off, np.int64), _np(hash_ids, np.int64)
+        if not (ts.shape == il.shape == ol.shape) or bo.shape != (ts.shape[0] + 1,) or (
+                bo.shape[0] and hi.shape[0] < bo[-1]):
+            raise ValueError("inconsistent trace array shapes")
+        h = C.c_void_p()
+        _check(lib().gorgo_load_trace_arrays(ts.shape[0], _ptr(ts), _ptr(il), _ptr(ol), _ptr(bo), _ptr(hi),
+                                             block_tokens, C.byref(h)))
+        return cls(h)
+
+    def info(self) -> dict:
+        n, tb, u = C.c_int64(), C.c_int64(), C.c_int64()
+        mb, cc = C.c_int32(), C.c_int32()
+        _check(lib().gorgo_trace_info(self._h, C.byref(n), C.byref(tb), C.byref(mb), C.byref(u), C.byref(cc)))
+        return dict(N=n.value, total_blocks=tb.value, max_blocks=mb.value, unique_ids=u.value,
+                    chain_consistent=bool(cc.value))
+
+    @property
+    def N(self) -> int:
+        return self.info()["N"]
+
+    def close(self):
+        if self._h:
+            lib().gorgo_free_trace(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def set_table_factor_percent(pct: int):
+    _check(lib().gorgo_set_table_factor_percent(pct))
+
+
+def _outputs_struct(route=None, hit_blocks=None, ttft_ms=None, e2e_ms=None, p95_ttft_ms=None, p95_e2e_ms=None):
+    def dp(x):
+        return None if x is None else C.c_void_p(x.data_ptr())
+    return _Outputs(dp(route), dp(hit_blocks), dp(ttft_ms), dp(e2e_ms), dp(p95_ttft_ms), dp(p95_e2e_ms))
+
+
+def workspace_bytes(trace: Trace, model: Model, P: int, outputs: Optional[_Outputs] = None) -> int:
+    n = C.c_size_t()
+    m = model.c()
+    _check(lib().gorgo_workspace_bytes(trace._h, C.byref(m), P, None if outputs is None else C.byref(outputs),
+                                       C.byref(n)))
+    return n.value
+
+
+@dataclass
+class EvalResult:
+    route: object = None
+    hit_blocks: object = None
+    ttft_ms: object = None
+    e2e_ms: object = None
+    p95_ttft_ms: object = None
+    p95_e2e_ms: object = None
+    workspace: object = None
+
+
+def eval_population(trace: Trace, model: Model, rtt_ms, params, scale, *, per_request: bool = True,
+                    p95: bool = True, workspace=None, stream=None, device="cuda:0") -> EvalResult:
+    """gorgo_eval_population with torch-allocated outputs.  Returns device tensors; asynchronous on `stream`
+    (default: torch's current stream)."""
+    import torch
+    rtt = _np(rtt_ms, np.float64)
+    par = _np(params, np.float64)
+    P = par.shape[0]
+    sc = _np(np.broadcast_to(np.asarray(scale, dtype=np.float64), (P,)), np.float64)
+    if par.shape != (P, 3) or rtt.shape != (model.R,):
+        raise ValueError("params must be [P,3] and rtt_ms [R]")
+    N = trace.N
+    dev = torch.device(device)
+    res = EvalResult()
+    if per_request:
+        res.route = torch.empty((P, N), dtype=torch.uint8, device=dev)
+        res.hit_blocks = torch.empty((P, N), dtype=torch.uint16, device=dev)
+        res.ttft_ms = torch.empty((P, N), dtype=torch.float64, device=dev)
+        res.e2e_ms = torch.empty((P, N), dtype=torch.float64, device=dev)
+    if p95:
+        res.p95_ttft_ms = torch.empty((P,), dtype=torch.float64, device=dev)
+        res.p95_e2e_ms = torch.empty((P,), dtype=torch.float64, device=dev)
+    o = _outputs_struct(res.route, res.hit_blocks, res.ttft_ms, res.e2e_ms, res.p95_ttft_ms, res.p95_e2e_ms)
+    need = workspace_bytes(trace, model, P, o)
+    if workspace is None or workspace.numel() < need:
+        workspace = torch.empty((need,), dtype=torch.uint8, device=dev)
+    res.workspace = workspace
+    s = stream if stream is not None else torch.cuda.current_stream(dev)
+    m = model.c()
+    with torch.cuda.device(dev):
+        _check(lib().gorgo_eval_population(trace._h, C.byref(m), _ptr(rtt), _ptr(par), _ptr(sc), P, C.byref(o),
+                                           C.c_void_p(workspace.data_ptr()), workspace.numel(),
+                                           C.c_void_p(s.cuda_stream)))
+    return res
+
+
+# ------------------------------------------------------------------------------------------------ tuner
+
+def es_init(seed: int) -> EsState:
+    s = EsState()
+    _check(lib().gorgo_es_init(C.byref(s), seed))
+    return s
+
+
+def philox4x32_10(ctr, key) -> np.ndarray:
+    c, k = _np(ctr, np.uint32), _np(key, np.uint32)
+    out = np.zeros(4, np.uint32)
+    lib().gorgo_philox4x32_10(_ptr(c), _ptr(k), _ptr(out))
+    return out
+
+
+def es_sample(seed: int, generation: int, P: int) -> np.ndarray:
+    z = np.zeros((P, 3), np.float64)
+    _check(lib().gorgo_es_sample(seed, generation, P, _ptr(z)))
+    return z
+
+
+def es_propose(state: EsState, z) -> np.ndarray:
+    z = _np(z, np.float64)
+    out = np.zeros_like(z)
+    _check(lib().gorgo_es_propose(C.byref(state), _ptr(z), z.shape[0], _ptr(out)))
+    return out
+
+
+def es_update(state: EsState, params, fitness) -> EsState:
+    par, fit = _np(params, np.float64), _np(fitness, np.float64)
+    _check(lib().gorgo_es_update(_ptr(par), _ptr(fit), par.shape[0], C.byref(state)))
+    return state
+
+
+def es_workspace_bytes(trace: Trace, model: Model, P: int) -> int:
+    n = C.c_size_t()
+    m = model.c()
+    _check(lib().gorgo_es_workspace_bytes(trace._h, C.byref(m), P, C.byref(n)))
+    return n.value
+
+
+def es_step(trace: Trace, model: Model, rtt_ms, scale: float, P: int, state: EsState, *, workspace=None,
+            stream=None, device="cuda:0"):
+    """gorgo_es_step.  Returns (params[P,3], fitness[P], workspace); `state` is updated in place."""
+    import torch
+    rtt = _np(rtt_ms, np.float64)
+    dev = torch.device(device)
+    need = es_workspace_bytes(trace, model, P)
+    if workspace is None or workspace.numel() < need:
+        workspace = torch.empty((need,), dtype=torch.uint8, device=dev)
+    par = np.zeros((P, 3), np.float64)
+    fit = np.zeros(P, np.float64)
+    s = stream if stream is not None else torch.cuda.current_stream(dev)
+    m = model.c()
+    with torch.cuda.device(dev):
+        _check(lib().gorgo_es_step(trace._h, C.byref(m), _ptr(rtt), float(scale), P, C.byref(state), _ptr(par),
+                                   _ptr(fit), C.c_void_p(workspace.data_ptr()), workspace.numel(),
+                                   C.c_void_p(s.cuda_stream)))
+    return par, fit, workspace

@@ -1,0 +1,201 @@
+// Evaluation entry points of the C ABI: argument validation, workspace layout, launches, ES generation.
+#include <atomic>
+#include <cmath>
+#include <cstring>
+#include <limits>
+#include <string>
+#include <vector>
+
+#include "internal.h"
+
+namespace gorgo {
+namespace {
+
+std::atomic<int32_t> g_table_factor_percent{200};
+
+size_t up256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+int check_model(const gorgo_trace* t, const gorgo_model* m) {
+    if (!t) return fail(GORGO_ERR_INVALID_ARG, "trace is NULL");
+    if (!m) return fail(GORGO_ERR_INVALID_ARG, "model is NULL");
+    if (m->R < 1 || m->R > 64) return fail(GORGO_ERR_INVALID_ARG, "R must be in 1..64");
+    if (m->batch < 1 || m->batch > 64) return fail(GORGO_ERR_INVALID_ARG, "batch must be in 1..64");
+    if ((int64_t)m->R * m->batch > 1024) return fail(GORGO_ERR_INVALID_ARG, "R * batch must not exceed 1024");
+    if (m->block_tokens != t->block_tokens)
+        return fail(GORGO_ERR_INVALID_ARG, "model.block_tokens differs from the trace's");
+    if (m->cache_blocks < 0 || m->cache_blocks > ((int64_t)1 << 30))
+        return fail(GORGO_ERR_INVALID_ARG, "cache_blocks must be in 0..2^30");
+    if (!std::isfinite(m->prefill_ms_per_token) || !std::isfinite(m->decode_ms_per_token))
+        return fail(GORGO_ERR_NONFINITE, "service constants must be finite");
+    if (m->prefill_ms_per_token < 0 || m->prefill_ms_per_token > 1e6 || m->decode_ms_per_token < 0 ||
+        m->decode_ms_per_token > 1e6)
+        return fail(GORGO_ERR_NONFINITE, "service constants must be in 0..1e6 ms per token");
+    if (m->cache_blocks > 0 && t->max_distinct > m->cache_blocks)
+        return fail(GORGO_ERR_CAPACITY, "a request has " + std::to_string(t->max_distinct) +
+                                            " distinct blocks but the cache holds " + std::to_string(m->cache_blocks));
+    return GORGO_OK;
+}
+
+// Table geometry and workspace carve-up.
+int make_plan(const gorgo_trace* t, const gorgo_model* m, int32_t P, const gorgo_outputs* o, Plan* pl) {
+    if (P < 1 || P > (1 << 20)) return fail(GORGO_ERR_INVALID_ARG, "P must be in 1..2^20");
+    pl->P = P;
+    pl->R = m->R;
+    pl->B = m->batch;
+    pl->N = t->N;
+    pl->C = m->cache_blocks;
+    pl->block_tokens = m->block_tokens;
+    pl->a_pf = m->prefill_ms_per_token;
+    pl->a_dec = m->decode_ms_per_token;
+    // A table must hold the cached blocks plus the blocks of the request being inserted, with room to
+    // spare: the replay compacts a table once 7/8 of its slots have been used.
+    const int64_t d = t->max_distinct;
+    const int64_t resident = (pl->C > 0 ? pl->C : t->unique_ids) + d;
+    const int64_t factor = g_table_factor_percent.load();
+    int64_t need = (resident * factor + 99) / 100;
+    const int64_t floor_need = ((resident + d) * 8 + 6) / 7 + 64;
+    if (need < floor_need) need = floor_need;
+    int64_t cap = 128;
+    while (cap < need) cap <<= 1;
+    pl->cap = cap;
+    const size_t N = (size_t)t->N;
+    size_t off = 0;
+    pl->off_tables = off;
+    off += up256((size_t)P * pl->R * (size_t)cap * 16);
+    pl->off_spare = off;
+    off += up256((size_t)P * (size_t)cap * 16);
+    pl->off_rec = off;
+    off += up256((size_t)P * N * 16);
+    const bool want_p95_t = !o || o->p95_ttft_ms, want_p95_e = !o || o->p95_e2e_ms;
+    pl->off_route = off;
+    if (!o || !o->route) off += up256((size_t)P * N);
+    pl->off_ttft = off;
+    if (!o || (!o->ttft_ms && want_p95_t)) off += up256((size_t)P * N * 8);
+    pl->off_e2e = off;
+    if (!o || (!o->e2e_ms && want_p95_e)) off += up256((size_t)P * N * 8);
+    pl->off_small = off;
+    off += up256(((size_t)pl->R + 4 * (size_t)P) * 8);
+    pl->total = off;
+    return GORGO_OK;
+}
+
+}  // namespace
+}  // namespace gorgo
+
+using namespace gorgo;
+
+extern "C" {
+
+int gorgo_set_table_factor_percent(int32_t factor_percent) {
+    clear_error();
+    if (factor_percent < 110 || factor_percent > 1600) return fail(GORGO_ERR_INVALID_ARG, "factor must be in 110..1600");
+    g_table_factor_percent.store(factor_percent);
+    return GORGO_OK;
+}
+
+int gorgo_workspace_bytes(const gorgo_trace* t, const gorgo_model* m, int32_t P, const gorgo_outputs* outputs,
+                          size_t* bytes) {
+    clear_error();
+    if (!bytes) return fail(GORGO_ERR_INVALID_ARG, "bytes is NULL");
+    int rc = check_model(t, m);
+    if (rc) return rc;
+    Plan pl;
+    rc = make_plan(t, m, P, outputs, &pl);
+    if (rc) return rc;
+    *bytes = pl.total;
+    return GORGO_OK;
+}
+
+int gorgo_eval_population(const gorgo_trace* t, const gorgo_model* m, const double* rtt_ms, const double* params,
+                          const double* scale, int32_t P, const gorgo_outputs* outputs, void* workspace,
+                          size_t workspace_bytes, void* hip_stream) {
+    clear_error();
+    int rc = check_model(t, m);
+    if (rc) return rc;
+    if (!rtt_ms || !params || !scale || !outputs) return fail(GORGO_ERR_INVALID_ARG, "a required pointer is NULL");
+    Plan pl;
+    rc = make_plan(t, m, P, outputs, &pl);
+    if (rc) return rc;
+    for (int i = 0; i < m->R; ++i)
+        if (!std::isfinite(rtt_ms[i]) || rtt_ms[i] < 0 || rtt_ms[i] > 1e9)
+            return fail(GORGO_ERR_NONFINITE, "rtt_ms[" + std::to_string(i) + "] must be finite and in 0..1e9");
+    for (int64_t j = 0; j < 3 * (int64_t)P; ++j)
+        if (!std::isfinite(params[j]) || std::fabs(params[j]) > 1e100)
+            return fail(GORGO_ERR_NONFINITE, "params[" + std::to_string(j / 3) + "][" + std::to_string(j % 3) +
+                                                 "] must be finite with magnitude <= 1e100");
+    for (int32_t p = 0; p < P; ++p)
+        if (!std::isfinite(scale[p]) || scale[p] < 0 || scale[p] > 1e6)
+            return fail(GORGO_ERR_NONFINITE, "scale[" + std::to_string(p) + "] must be finite and in 0..1e6");
+    if (!workspace) return fail(GORGO_ERR_WORKSPACE, "workspace is NULL");
+    if (reinterpret_cast<uintptr_t>(workspace) & 255) return fail(GORGO_ERR_WORKSPACE, "workspace must be 256-byte aligned");
+    if (workspace_bytes < pl.total)
+        return fail(GORGO_ERR_WORKSPACE, "workspace has " + std::to_string(workspace_bytes) + " bytes, needs " +
+                                             std::to_string(pl.total));
+    rc = upload_trace(t);
+    if (rc) return rc;
+
+    char* ws = static_cast<char*>(workspace);
+    double* d_rtt = reinterpret_cast<double*>(ws + pl.off_small);
+    double* d_params = d_rtt + pl.R;
+    double* d_scale = d_params + 3 * (size_t)P;
+    if ((rc = copy_small_to_device(d_rtt, rtt_ms, sizeof(double) * pl.R, hip_stream))) return rc;
+    if ((rc = copy_small_to_device(d_params, params, sizeof(double) * 3 * (size_t)P, hip_stream))) return rc;
+    if ((rc = copy_small_to_device(d_scale, scale, sizeof(double) * (size_t)P, hip_stream))) return rc;
+
+    uint8_t* route = outputs->route ? outputs->route : reinterpret_cast<uint8_t*>(ws + pl.off_route);
+    double* ttft = outputs->ttft_ms;
+    if (!ttft && outputs->p95_ttft_ms) ttft = reinterpret_cast<double*>(ws + pl.off_ttft);
+    double* e2e = outputs->e2e_ms;
+    if (!e2e && outputs->p95_e2e_ms) e2e = reinterpret_cast<double*>(ws + pl.off_e2e);
+    rc = launch_replay(t, pl, d_rtt, d_params, d_scale, route, outputs->hit_blocks, ttft, e2e, workspace, hip_stream);
+    if (rc) return rc;
+    if (outputs->p95_ttft_ms && (rc = launch_p95(ttft, pl.N, P, outputs->p95_ttft_ms, hip_stream))) return rc;
+    if (outputs->p95_e2e_ms && (rc = launch_p95(e2e, pl.N, P, outputs->p95_e2e_ms, hip_stream))) return rc;
+    return GORGO_OK;
+}
+
+int gorgo_es_workspace_bytes(const gorgo_trace* t, const gorgo_model* m, int32_t P, size_t* bytes) {
+    clear_error();
+    if (!bytes) return fail(GORGO_ERR_INVALID_ARG, "bytes is NULL");
+    int rc = check_model(t, m);
+    if (rc) return rc;
+    gorgo_outputs o;
+    std::memset(&o, 0, sizeof o);
+    o.p95_ttft_ms = reinterpret_cast<double*>(256);   // only which outputs are wanted matters for sizing
+    Plan pl;
+    rc = make_plan(t, m, P, &o, &pl);
+    if (rc) return rc;
+    *bytes = pl.total + up256(sizeof(double) * (size_t)P);
+    return GORGO_OK;
+}
+
+int gorgo_es_step(const gorgo_trace* t, const gorgo_model* m, const double* rtt_ms, double scale, int32_t P,
+                  gorgo_es_state* inout, double* params_out, double* fitness_out, void* workspace,
+                  size_t workspace_bytes, void* hip_stream) {
+    clear_error();
+    if (!inout) return fail(GORGO_ERR_INVALID_ARG, "state is NULL");
+    size_t need = 0;
+    int rc = gorgo_es_workspace_bytes(t, m, P, &need);
+    if (rc) return rc;
+    if (!workspace) return fail(GORGO_ERR_WORKSPACE, "workspace is NULL");
+    if (workspace_bytes < need)
+        return fail(GORGO_ERR_WORKSPACE, "workspace has " + std::to_string(workspace_bytes) + " bytes, needs " +
+                                             std::to_string(need));
+    std::vector<double> z((size_t)P * 3), params((size_t)P * 3), fit((size_t)P), sc((size_t)P, scale);
+    if ((rc = gorgo_es_sample(inout->seed, inout->generation, P, z.data()))) return rc;
+    if ((rc = gorgo_es_propose(inout, z.data(), P, params.data()))) return rc;
+    const size_t fit_bytes = up256(sizeof(double) * (size_t)P);
+    double* d_fit = reinterpret_cast<double*>(static_cast<char*>(workspace) + (need - fit_bytes));
+    gorgo_outputs o;
+    std::memset(&o, 0, sizeof o);
+    o.p95_ttft_ms = d_fit;
+    rc = gorgo_eval_population(t, m, rtt_ms, params.data(), sc.data(), P, &o, workspace, need - fit_bytes, hip_stream);
+    if (rc) return rc;
+    if ((rc = copy_small_to_host_sync(fit.data(), d_fit, sizeof(double) * (size_t)P, hip_stream))) return rc;
+    if ((rc = gorgo_es_update(params.data(), fit.data(), P, inout))) return rc;
+    if (params_out) std::memcpy(params_out, params.data(), sizeof(double) * params.size());
+    if (fitness_out) std::memcpy(fitness_out, fit.data(), sizeof(double) * fit.size());
+    return GORGO_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,71 @@
+// Internal declarations shared by the host-side translation units of libgorgo.
+#pragma once
+#include <cstdint>
+#include <cstddef>
+#include <string>
+#include <vector>
+
+#include "gorgo.h"
+
+namespace gorgo {
+
+// thread-local error text behind gorgo_last_error()
+int fail(int code, const std::string& msg);
+void clear_error();
+
+// Device-resident copy of a trace (filled lazily by the first evaluation).
+struct DeviceTrace {
+    int device = -1;
+    void* base = nullptr;          // one allocation holding every array below
+    const int64_t* ts = nullptr;   // [N]
+    const int32_t* in_len = nullptr;
+    const int32_t* out_len = nullptr;
+    const int64_t* blk_off = nullptr;   // [N+1]
+    const uint32_t* key = nullptr;      // [total] dense block key (1-based)
+    const uint8_t* first = nullptr;     // [total] 1 = first occurrence of its key inside the request
+};
+
+}  // namespace gorgo
+
+// The opaque handle of the C ABI.
+struct gorgo_trace {
+    int64_t N = 0;
+    int32_t block_tokens = 0;
+    std::vector<int64_t> ts;
+    std::vector<int32_t> in_len, out_len;
+    std::vector<int64_t> blk_off;
+    std::vector<uint32_t> key;       // dense remap of hash ids: 1 + order of first appearance in the file
+    std::vector<uint8_t> first;
+    int64_t total_blocks = 0;
+    int32_t max_blocks = 0;          // largest n_r
+    int32_t max_distinct = 0;        // largest number of distinct ids in one request
+    int64_t unique_ids = 0;
+    bool chain_consistent = true;
+    gorgo::DeviceTrace dev;
+};
+
+namespace gorgo {
+
+// Geometry of one evaluation, computed on the host and handed to the launchers.
+struct Plan {
+    int32_t P = 0, R = 0, B = 0;
+    int64_t N = 0, C = 0;
+    int64_t cap = 0;                 // slots per (replay, replica) table, power of two
+    int32_t block_tokens = 0;
+    double a_pf = 0, a_dec = 0;
+    // workspace carve-up (byte offsets from the workspace base)
+    size_t off_tables = 0, off_spare = 0, off_rec = 0, off_route = 0, off_ttft = 0, off_e2e = 0, off_small = 0;
+    size_t total = 0;
+};
+
+// kernels.hip
+int launch_replay(const gorgo_trace* t, const Plan& pl, const double* d_rtt, const double* d_params,
+                  const double* d_scale, uint8_t* route, uint16_t* hit, double* ttft, double* e2e,
+                  void* workspace, void* stream);
+int launch_p95(const double* x, int64_t N, int32_t P, double* out, void* stream);
+int upload_trace(const gorgo_trace* t);
+void release_device_trace(gorgo_trace* t);
+int copy_small_to_device(void* dst, const void* src, size_t bytes, void* stream);
+int copy_small_to_host_sync(void* dst, const void* src, size_t bytes, void* stream);
+
+}  // namespace gorgo

@@ -1,0 +1,609 @@
+// Device side: replay kernel (one wavefront per replay), table fill, exact percentile selection.
+//
+// The replay kernel follows the request loop of the routing policy (Sec. 2.2-2.3): retire completed
+// requests from the load signal (Eq. 2), longest-prefix match of the request's blocks against every
+// replica's cache (the x_r \ c_i of Eq. 1), weighted score (Eq. 3), lowest-index minimum over replicas, cache
+// and queue update on the chosen replica, and the stated linear service model.  Replays are independent,
+// so the grid is one 64-lane workgroup per replay; inside a replay the lanes spread over replicas (first-
+// block probes, scores), over the blocks of the request (prefix match, cache update, eviction walk) and over
+// the service slots (retirement, earliest-free slot).
+//
+// Decision arithmetic is fp64 with every product and sum rounded separately (built with -ffp-contract=off)
+// in the association (w_rtt*rtt + w_prefill*pf) + w_queue*qd, so that routes are reproducible bit for bit.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdint>
+#include <string>
+
+#include "internal.h"
+
+namespace gorgo {
+
+namespace {
+
+constexpr int64_t STAMP_STRIDE = 65536;   // stamp = request * stride + (stride - 1 - position): root newest
+constexpr int WAVE = 64;
+
+// One cache-table slot.  key 0 = never used (then stamp = -1).  An entry is cached iff stamp >= tau of its
+// replica; entries below tau are evicted garbage whose slots can be taken over by inserts.
+struct Slot {
+    uint64_t key;
+    int64_t stamp;
+};
+
+// In-flight request record, linked per (replica, service slot) in dispatch order.
+struct Rec {
+    double done;       // time the completion event reaches the proxy
+    int32_t next;      // next request on the same service slot, -1 = none
+    int32_t tokens;    // input tokens counted in the load signal
+};
+
+struct ReplayArgs {
+    const int64_t* ts;
+    const int32_t* in_len;
+    const int32_t* out_len;
+    const int64_t* blk_off;
+    const uint32_t* key;
+    const uint8_t* first;
+    int64_t N;
+    int32_t R, B;
+    int64_t C;
+    int64_t cap;
+    int32_t cap_log2;
+    int32_t block_tokens;
+    double a_pf, a_dec;
+    const double* rtt;
+    const double* params;
+    const double* scale;
+    Slot* tables;   // [P][R][cap]
+    Slot* spare;    // [P][cap]
+    Rec* rec;       // [P][N]
+    uint8_t* route; // [P][N] never null (workspace stand-in when the caller does not want it)
+    uint16_t* hit;  // nullable
+    double* ttft;   // nullable
+    double* e2e;    // nullable
+};
+
+// All mutable per-replay state in global memory is private to one workgroup; relaxed workgroup-scope
+// atomics plus workgroup barriers between phases are what the memory model asks for.
+template <class T>
+__device__ __forceinline__ T ld(const T* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+}
+template <class T>
+__device__ __forceinline__ void st(T* p, T v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+}
+__device__ __forceinline__ bool cas_stamp(int64_t* p, int64_t expected, int64_t desired) {
+    return __hip_atomic_compare_exchange_strong(p, &expected, desired, __ATOMIC_RELAXED, __ATOMIC_RELAXED,
+                                                __HIP_MEMORY_SCOPE_WORKGROUP);
+}
+
+__device__ __forceinline__ uint64_t home_slot(uint64_t key, int cap_log2) {
+    return (key * 0x9E3779B97F4A7C15ull) >> (64 - cap_log2);
+}
+
+// Physical lookup: slot index of `key`, or -1 when the probe sequence reaches a never-used slot.
+__device__ __forceinline__ int64_t find_slot(const Slot* tab, uint64_t key, uint64_t mask, int cap_log2) {
+    uint64_t h = home_slot(key, cap_log2);
+    for (;;) {
+        uint64_t k = ld(&tab[h].key);
+        if (k == key) return (int64_t)h;
+        if (k == 0) return -1;
+        h = (h + 1) & mask;
+    }
+}
+
+__device__ __forceinline__ bool is_cached(const Slot* tab, uint64_t key, int64_t tau, uint64_t mask, int cap_log2) {
+    int64_t s = find_slot(tab, key, mask, cap_log2);
+    return s >= 0 && ld(&tab[s].stamp) >= tau;
+}
+
+// Takes over the first never-used or evicted slot of the probe sequence.  Returns true when a never-used
+// slot was consumed.  Only called for keys known to be physically absent, by lanes with distinct keys.
+__device__ __forceinline__ bool insert_new(Slot* tab, uint64_t key, int64_t stamp, int64_t tau, uint64_t mask,
+                                           int cap_log2) {
+    uint64_t h = home_slot(key, cap_log2);
+    for (;;) {
+        int64_t s = ld(&tab[h].stamp);
+        if (s < tau && cas_stamp(&tab[h].stamp, s, stamp)) {
+            st(&tab[h].key, key);
+            return s == -1;
+        }
+        h = (h + 1) & mask;
+    }
+}
+
+struct Best {
+    double v;
+    int idx;
+};
+
+// Lowest-index minimum over the wavefront.
+__device__ __forceinline__ Best wave_argmin(double v, int idx) {
+#pragma unroll
+    for (int d = 1; d < WAVE; d <<= 1) {
+        double ov = __shfl_xor(v, d);
+        int oi = __shfl_xor(idx, d);
+        if (ov < v || (ov == v && oi < idx)) {
+            v = ov;
+            idx = oi;
+        }
+    }
+    return Best{v, idx};
+}
+
+__global__ void __launch_bounds__(256) fill_slots(Slot* s, size_t n) {
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (; i < n; i += stride) {
+        s[i].key = 0;
+        s[i].stamp = -1;
+    }
+}
+
+__global__ void __launch_bounds__(WAVE) replay_kernel(ReplayArgs a) {
+    extern __shared__ __align__(16) unsigned char lds_raw[];
+    const int lane = threadIdx.x;
+    const int p = blockIdx.x;
+    const int R = a.R, B = a.B, RB = R * B;
+    const int64_t N = a.N;
+    const uint64_t mask = (uint64_t)a.cap - 1;
+    const int cap_log2 = a.cap_log2;
+
+    // LDS carve-up (8-byte fields first)
+    double* free_at = reinterpret_cast<double*>(lds_raw);         // [RB] time the service slot becomes free
+    double* head_done = free_at + RB;                             // [RB] completion time of the oldest in-flight
+    int64_t* q = reinterpret_cast<int64_t*>(head_done + RB);      // [R] outstanding tokens (Eq. 2)
+    int64_t* tau = q + R;                                         // [R] eviction threshold
+    int32_t* head = reinterpret_cast<int32_t*>(tau + R);          // [RB]
+    int32_t* tail = head + RB;                                    // [RB]
+    int32_t* live = tail + RB;                                    // [R] cached blocks
+    int32_t* used = live + R;                                     // [R] slots ever used since the last rebuild
+    int32_t* cur_r = used + R;                                    // [R] eviction cursor: request ...
+    int32_t* cur_k = cur_r + R;                                   // [R] ... and position (blocks >= cur_k are gone)
+
+    for (int s = lane; s < RB; s += WAVE) {
+        free_at[s] = 0.0;
+        head_done[s] = INFINITY;
+        head[s] = -1;
+        tail[s] = -1;
+    }
+    for (int i = lane; i < R; i += WAVE) {
+        q[i] = 0;
+        tau[i] = 0;
+        live[i] = 0;
+        used[i] = 0;
+        cur_r[i] = -1;
+        cur_k[i] = 0;
+    }
+    __syncthreads();
+
+    const double w_rtt = a.params[3 * (size_t)p + 0];
+    const double w_prefill = a.params[3 * (size_t)p + 1];
+    const double w_queue = a.params[3 * (size_t)p + 2];
+    const double sc = a.scale[p];
+    const double my_rtt = lane < R ? a.rtt[lane] : 0.0;
+
+    Slot* const tables = a.tables + (size_t)p * R * a.cap;
+    Slot* const spare = a.spare + (size_t)p * a.cap;
+    Rec* const rec = a.rec + (size_t)p * N;
+    uint8_t* const route = a.route + (size_t)p * N;
+    const int64_t rebuild_at = a.cap - a.cap / 8;
+
+    for (int64_t r = 0; r < N; ++r) {
+        const int64_t off = a.blk_off[r];
+        const int n = (int)(a.blk_off[r + 1] - off);
+        const int64_t L = a.in_len[r];
+        const int64_t O = a.out_len[r];
+        const double t = (double)a.ts[r] * sc;     // time scale: gaps scale linearly
+
+        // ---- retire: drop requests whose completion event has reached the proxy (done <= t)
+        for (int s = lane; s < RB; s += WAVE) {
+            while (head_done[s] <= t) {
+                const int h = head[s];
+                const int32_t nx = ld(&rec[h].next);
+                const int32_t tok = ld(&rec[h].tokens);
+                atomicAdd(reinterpret_cast<unsigned long long*>(&q[s / B]), (unsigned long long)(-(int64_t)tok));
+                head[s] = nx;
+                if (nx < 0) {
+                    head_done[s] = INFINITY;
+                    tail[s] = -1;
+                } else {
+                    head_done[s] = ld(&rec[nx].done);
+                }
+            }
+        }
+        __syncthreads();
+
+        // ---- prefix match: first block on every replica, then the whole list on replicas that hold it
+        int my_m = 0;
+        {
+            bool has0 = false;
+            if (n > 0 && lane < R)
+                has0 = is_cached(tables + (size_t)lane * a.cap, a.key[off], tau[lane], mask, cap_log2);
+            uint64_t holders = __ballot(has0);
+            while (holders) {
+                const int i = __ffsll((unsigned long long)holders) - 1;
+                holders &= holders - 1;
+                const Slot* tab = tables + (size_t)i * a.cap;
+                const int64_t tau_i = tau[i];
+                int m = 0;
+                for (int base = 0; base < n; base += WAVE) {
+                    const int k = base + lane;
+                    const bool ok = k < n && is_cached(tab, a.key[off + k], tau_i, mask, cap_log2);
+                    const uint64_t got = __ballot(ok);
+                    const int width = n - base < WAVE ? n - base : WAVE;
+                    const uint64_t want = width == WAVE ? ~0ull : ((1ull << width) - 1);
+                    if (got == want) {
+                        m += width;
+                    } else {
+                        m += __ffsll((unsigned long long)(~got)) - 1;
+                        break;
+                    }
+                }
+                if (lane == i) my_m = m;
+            }
+        }
+
+        // ---- score (Eq. 3) and lowest-index minimum
+        int64_t my_u = 0;
+        double my_score = INFINITY;
+        if (lane < R) {
+            int64_t hit_tok = (int64_t)a.block_tokens * my_m;
+            if (hit_tok > L) hit_tok = L;
+            my_u = L - hit_tok;
+            const double pf = a.a_pf * (double)my_u;
+            const double qd = a.a_pf * (double)q[lane];
+            const double s_rtt = w_rtt * my_rtt;
+            const double s_pf = w_prefill * pf;
+            const double s_q = w_queue * qd;
+            my_score = (s_rtt + s_pf) + s_q;
+        }
+        const int best = wave_argmin(my_score, lane < R ? lane : 255).idx;
+        const int64_t u_best = __shfl(my_u, best);
+        const int m_best = __shfl(my_m, best);
+        const double rtt_best = __shfl(my_rtt, best);
+        if (lane == 0) st(&route[r], (uint8_t)best);
+
+        // ---- cache update on the chosen replica
+        Slot* const tab = tables + (size_t)best * a.cap;
+        if ((int64_t)used[best] + n > rebuild_at) {
+            // compact: keep cached entries only, so that never-used slots exist again
+            const int64_t tau_b = tau[best];
+            int64_t kept = 0;
+            for (int64_t base = 0; base < a.cap; base += WAVE) {
+                const uint64_t k = ld(&tab[base + lane].key);
+                const int64_t s = ld(&tab[base + lane].stamp);
+                const bool keep = k != 0 && s >= tau_b;
+                const uint64_t mk = __ballot(keep);
+                if (keep) {
+                    const int64_t pos = kept + __popcll(mk & ((1ull << lane) - 1));
+                    st(&spare[pos].key, k);
+                    st(&spare[pos].stamp, s);
+                }
+                kept += __popcll(mk);
+            }
+            __syncthreads();
+            for (int64_t base = 0; base < a.cap; base += WAVE) {
+                st(&tab[base + lane].key, (uint64_t)0);
+                st(&tab[base + lane].stamp, (int64_t)-1);
+            }
+            __syncthreads();
+            for (int64_t base = 0; base < kept; base += WAVE) {
+                if (base + lane < kept)
+                    insert_new(tab, ld(&spare[base + lane].key), ld(&spare[base + lane].stamp), 0, mask, cap_log2);
+                __syncthreads();
+            }
+            if (lane == 0) used[best] = (int32_t)kept;
+            __syncthreads();
+        }
+        {
+            const int64_t tau_b = tau[best];
+            int add_live = 0, add_used = 0;
+            for (int base = 0; base < n; base += WAVE) {
+                const int k = base + lane;
+                const bool mine = k < n && a.first[off + k] != 0;
+                const uint64_t key = mine ? a.key[off + k] : 0;
+                const int64_t stamp = r * STAMP_STRIDE + (STAMP_STRIDE - 1 - k);
+                int64_t slot = -1;
+                bool was_cached = false;
+                if (mine) {
+                    slot = find_slot(tab, key, mask, cap_log2);
+                    if (slot >= 0) {
+                        was_cached = ld(&tab[slot].stamp) >= tau_b;
+                        st(&tab[slot].stamp, stamp);          // touch, or revive an evicted entry in place
+                    }
+                }
+                __syncthreads();
+                bool took_fresh = false;
+                if (mine && slot < 0) took_fresh = insert_new(tab, key, stamp, tau_b, mask, cap_log2);
+                __syncthreads();
+                add_live += __popcll(__ballot(mine && !was_cached));
+                add_used += __popcll(__ballot(took_fresh));
+            }
+            if (lane == 0) {
+                live[best] += add_live;
+                used[best] += add_used;
+            }
+            __syncthreads();
+        }
+
+        // ---- eviction: advance the threshold past the least recently used blocks until the cache fits.
+        // The log of (request, position) touches on this replica is the route array itself, walked from the
+        // oldest request routed here; a logged touch still counts iff the table holds exactly its stamp.
+        if (a.C > 0 && live[best] > a.C) {
+            int E = (int)(live[best] - a.C);
+            int cr = cur_r[best], ck = cur_k[best];
+            while (E > 0) {
+                if (ck == 0) {
+                    // next request routed to this replica
+                    int64_t x = (int64_t)cr + 1;
+                    for (;;) {
+                        const int64_t y = x + lane;
+                        const bool hitb = y < r && ld(&route[y]) == (uint8_t)best;
+                        const uint64_t mk = __ballot(hitb);
+                        if (mk) {
+                            x += __ffsll((unsigned long long)mk) - 1;
+                            break;
+                        }
+                        x += WAVE;
+                        if (x >= r) break;      // cannot happen while E > 0; bounds the loop regardless
+                    }
+                    if (x >= r) break;
+                    cr = (int)x;
+                    ck = (int)(a.blk_off[x + 1] - a.blk_off[x]);
+                    continue;
+                }
+                const int64_t ooff = a.blk_off[cr];
+                const int k = ck - 1 - lane;               // lane order = eviction order (deepest first)
+                bool alive = false;
+                if (k >= 0 && a.first[ooff + k] != 0) {
+                    const int64_t s = find_slot(tab, a.key[ooff + k], mask, cap_log2);
+                    alive = s >= 0 && ld(&tab[s].stamp) == (int64_t)cr * STAMP_STRIDE + (STAMP_STRIDE - 1 - k);
+                }
+                const uint64_t mk = __ballot(alive);
+                const int cnt = __popcll(mk);
+                if (cnt <= E) {
+                    E -= cnt;
+                    ck = ck > WAVE ? ck - WAVE : 0;
+                } else {
+                    const int rank = __popcll(mk & ((1ull << lane) - 1));
+                    const uint64_t last = __ballot(alive && rank == E - 1);
+                    const int j = __ffsll((unsigned long long)last) - 1;
+                    ck = ck - 1 - j;
+                    E = 0;
+                }
+            }
+            if (lane == 0) {
+                cur_r[best] = cr;
+                cur_k[best] = ck;
+                tau[best] = (int64_t)cr * STAMP_STRIDE + (STAMP_STRIDE - ck);
+                live[best] = (int32_t)a.C + E;
+            }
+        }
+
+        // ---- service on the chosen replica: earliest-free slot, linear prefill + decode (Eq. 1)
+        {
+            const Best slot = wave_argmin(lane < B ? free_at[best * B + lane] : INFINITY, lane < B ? lane : 255);
+            const double half = 0.5 * rtt_best;
+            const double arrive = t + half;
+            const double start = arrive > slot.v ? arrive : slot.v;
+            const double pf = a.a_pf * (double)u_best;
+            const double first_tok = start + pf;
+            const double dec = a.a_dec * (double)O;
+            const double end = first_tok + dec;
+            const double done = end + half;
+            if (lane == 0) {
+                const int s = best * B + slot.idx;
+                free_at[s] = end;
+                st(&rec[r].done, done);
+                st(&rec[r].next, (int32_t)-1);
+                st(&rec[r].tokens, (int32_t)L);
+                const int tl = tail[s];
+                if (tl >= 0) {
+                    st(&rec[tl].next, (int32_t)r);
+                } else {
+                    head[s] = (int32_t)r;
+                    head_done[s] = done;
+                }
+                tail[s] = (int32_t)r;
+                q[best] += L;
+                if (a.hit) a.hit[(size_t)p * N + r] = (uint16_t)m_best;
+                if (a.ttft) a.ttft[(size_t)p * N + r] = (first_tok + half) - t;
+                if (a.e2e) a.e2e[(size_t)p * N + r] = done - t;
+            }
+        }
+        __syncthreads();
+    }
+}
+
+// ---- exact nearest-rank percentile: k-th smallest of x[p][0..N) by most-significant-digit radix selection
+// on the order-preserving integer image of the doubles.  One 256-thread workgroup per row.
+constexpr int SEL_THREADS = 256;
+constexpr int SEL_BITS = 11;
+constexpr int SEL_BINS = 1 << SEL_BITS;
+
+__device__ __forceinline__ uint64_t ordered_bits(double x) {
+    uint64_t b = (uint64_t)__double_as_longlong(x);
+    return (b >> 63) ? ~b : (b | 0x8000000000000000ull);
+}
+
+__global__ void __launch_bounds__(SEL_THREADS) select_kth(const double* x, int64_t N, int64_t kth /*1-based*/,
+                                                          double* out) {
+    __shared__ uint32_t hist[SEL_BINS];
+    __shared__ uint32_t part[SEL_THREADS];
+    __shared__ uint64_t s_prefix;
+    __shared__ int64_t s_k;
+    const int tid = threadIdx.x;
+    const double* row = x + (size_t)blockIdx.x * N;
+    if (N <= 0) {
+        if (tid == 0) out[blockIdx.x] = 0.0;
+        return;
+    }
+    if (tid == 0) {
+        s_prefix = 0;
+        s_k = kth;
+    }
+    int shift = 64;
+    uint64_t prefix_mask = 0;
+    while (shift > 0) {
+        const int bits = shift >= SEL_BITS ? SEL_BITS : shift;
+        shift -= bits;
+        for (int b = tid; b < SEL_BINS; b += SEL_THREADS) hist[b] = 0;
+        __syncthreads();
+        const uint64_t prefix = s_prefix;
+        const int64_t k = s_k;
+        for (int64_t i = tid; i < N; i += SEL_THREADS) {
+            const uint64_t v = ordered_bits(row[i]);
+            if ((v & prefix_mask) == prefix) atomicAdd(&hist[(v >> shift) & ((1u << bits) - 1)], 1u);
+        }
+        __syncthreads();
+        // locate the bin that holds the k-th element: per-thread partial sums, then a short serial scan
+        constexpr int PER = SEL_BINS / SEL_THREADS;
+        uint32_t sum = 0;
+        for (int j = 0; j < PER; ++j) sum += hist[tid * PER + j];
+        part[tid] = sum;
+        __syncthreads();
+        if (tid == 0) {
+            int64_t acc = 0;
+            int g = 0;
+            while (g < SEL_THREADS - 1 && acc + part[g] < k) acc += part[g++];
+            int b = g * PER;
+            while (b < SEL_BINS - 1 && acc + hist[b] < k) acc += hist[b++];
+            s_prefix = prefix | ((uint64_t)b << shift);
+            s_k = k - acc;
+        }
+        prefix_mask |= ((bits == 64 ? ~0ull : ((1ull << bits) - 1)) << shift);
+        __syncthreads();
+    }
+    if (tid == 0) {
+        uint64_t v = s_prefix;
+        uint64_t b = (v >> 63) ? (v & 0x7FFFFFFFFFFFFFFFull) : ~v;
+        out[blockIdx.x] = __longlong_as_double((long long)b);
+    }
+}
+
+int hip_fail(hipError_t e, const char* what) {
+    return fail(GORGO_ERR_DEVICE, std::string(what) + ": " + hipGetErrorString(e));
+}
+
+}  // namespace
+
+int upload_trace(const gorgo_trace* tc) {
+    gorgo_trace* t = const_cast<gorgo_trace*>(tc);
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+    if (t->dev.base && t->dev.device == dev) return GORGO_OK;
+    if (t->dev.base) release_device_trace(t);
+    const size_t N = (size_t)t->N, T = (size_t)t->total_blocks;
+    auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
+    const size_t o_ts = 0;
+    const size_t o_off = o_ts + up(N * 8);
+    const size_t o_il = o_off + up((N + 1) * 8);
+    const size_t o_ol = o_il + up(N * 4);
+    const size_t o_key = o_ol + up(N * 4);
+    const size_t o_first = o_key + up(T * 4);
+    const size_t total = o_first + up(T) + 256;
+    char* base = nullptr;
+    e = hipMalloc(reinterpret_cast<void**>(&base), total);
+    if (e != hipSuccess) return fail(GORGO_ERR_OOM, std::string("hipMalloc(trace): ") + hipGetErrorString(e));
+    auto put = [&](size_t o, const void* src, size_t bytes) {
+        return bytes ? hipMemcpy(base + o, src, bytes, hipMemcpyHostToDevice) : hipSuccess;
+    };
+    if ((e = put(o_ts, t->ts.data(), N * 8)) != hipSuccess || (e = put(o_off, t->blk_off.data(), (N + 1) * 8)) != hipSuccess ||
+        (e = put(o_il, t->in_len.data(), N * 4)) != hipSuccess || (e = put(o_ol, t->out_len.data(), N * 4)) != hipSuccess ||
+        (e = put(o_key, t->key.data(), T * 4)) != hipSuccess || (e = put(o_first, t->first.data(), T)) != hipSuccess) {
+        (void)hipFree(base);
+        return hip_fail(e, "hipMemcpy(trace)");
+    }
+    t->dev.device = dev;
+    t->dev.base = base;
+    t->dev.ts = reinterpret_cast<const int64_t*>(base + o_ts);
+    t->dev.blk_off = reinterpret_cast<const int64_t*>(base + o_off);
+    t->dev.in_len = reinterpret_cast<const int32_t*>(base + o_il);
+    t->dev.out_len = reinterpret_cast<const int32_t*>(base + o_ol);
+    t->dev.key = reinterpret_cast<const uint32_t*>(base + o_key);
+    t->dev.first = reinterpret_cast<const uint8_t*>(base + o_first);
+    return GORGO_OK;
+}
+
+void release_device_trace(gorgo_trace* t) {
+    if (t->dev.base) (void)hipFree(t->dev.base);
+    t->dev = DeviceTrace();
+}
+
+int copy_small_to_device(void* dst, const void* src, size_t bytes, void* stream) {
+    hipError_t e = hipMemcpyAsync(dst, src, bytes, hipMemcpyHostToDevice, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? GORGO_OK : hip_fail(e, "hipMemcpyAsync(H2D)");
+}
+
+int copy_small_to_host_sync(void* dst, const void* src, size_t bytes, void* stream) {
+    hipError_t e = hipMemcpyAsync(dst, src, bytes, hipMemcpyDeviceToHost, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return hip_fail(e, "hipMemcpyAsync(D2H)");
+    e = hipStreamSynchronize(static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? GORGO_OK : hip_fail(e, "hipStreamSynchronize");
+}
+
+size_t replay_lds_bytes(int R, int B) {
+    const size_t RB = (size_t)R * B;
+    return RB * 8 * 2 + (size_t)R * 8 * 2 + RB * 4 * 2 + (size_t)R * 4 * 4;
+}
+
+int launch_replay(const gorgo_trace* t, const Plan& pl, const double* d_rtt, const double* d_params,
+                  const double* d_scale, uint8_t* route, uint16_t* hit, double* ttft, double* e2e,
+                  void* workspace, void* stream) {
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    char* ws = static_cast<char*>(workspace);
+    ReplayArgs a;
+    a.ts = t->dev.ts;
+    a.in_len = t->dev.in_len;
+    a.out_len = t->dev.out_len;
+    a.blk_off = t->dev.blk_off;
+    a.key = t->dev.key;
+    a.first = t->dev.first;
+    a.N = pl.N;
+    a.R = pl.R;
+    a.B = pl.B;
+    a.C = pl.C;
+    a.cap = pl.cap;
+    a.cap_log2 = 0;
+    while ((1ll << a.cap_log2) < pl.cap) ++a.cap_log2;
+    a.block_tokens = pl.block_tokens;
+    a.a_pf = pl.a_pf;
+    a.a_dec = pl.a_dec;
+    a.rtt = d_rtt;
+    a.params = d_params;
+    a.scale = d_scale;
+    a.tables = reinterpret_cast<Slot*>(ws + pl.off_tables);
+    a.spare = reinterpret_cast<Slot*>(ws + pl.off_spare);
+    a.rec = reinterpret_cast<Rec*>(ws + pl.off_rec);
+    a.route = route;
+    a.hit = hit;
+    a.ttft = ttft;
+    a.e2e = e2e;
+    const size_t nslots = (size_t)pl.P * pl.R * pl.cap;
+    size_t blocks = (nslots + 255) / 256;
+    if (blocks > 65536) blocks = 65536;
+    hipLaunchKernelGGL(fill_slots, dim3((unsigned)blocks), dim3(256), 0, s, a.tables, nslots);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(e, "launch fill_slots");
+    if (pl.N > 0) {
+        hipLaunchKernelGGL(replay_kernel, dim3((unsigned)pl.P), dim3(WAVE), replay_lds_bytes(pl.R, pl.B), s, a);
+        e = hipGetLastError();
+        if (e != hipSuccess) return hip_fail(e, "launch replay_kernel");
+    }
+    return GORGO_OK;
+}
+
+int launch_p95(const double* x, int64_t N, int32_t P, double* out, void* stream) {
+    const int64_t kth = (95 * N + 99) / 100;
+    hipLaunchKernelGGL(select_kth, dim3((unsigned)P), dim3(SEL_THREADS), 0, static_cast<hipStream_t>(stream), x, N,
+                       kth, out);
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? GORGO_OK : hip_fail(e, "launch select_kth");
+}
+
+}  // namespace gorgo

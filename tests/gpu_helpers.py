@@ -1,0 +1,52 @@
+"""Shared pieces of the GPU parity tests: run the HIP library and the CPU oracle on the same inputs and
+compare element by element.  Routes and hit counts must be bit-exact; latencies agree to 1e-9 relative."""
+import numpy as np
+
+import paper_2602_11688_amd as g
+from oracle import binding as ob
+
+RTOL = 1e-9      # stated tolerance for TTFT / E2E; both sides use the same fp64 operation order
+
+
+def load(tr):
+    return g.Trace.from_arrays(tr.ts_ms, tr.in_len, tr.out_len, tr.blk_off, tr.hash_ids)
+
+
+def gpu_eval(tr, model: g.Model, rtt, params, scale, handle=None):
+    import torch
+    h = handle if handle is not None else load(tr)
+    res = g.eval_population(h, model, rtt, params, scale)
+    torch.cuda.synchronize()
+    out = dict(route=res.route.cpu().numpy(), hit=res.hit_blocks.cpu().numpy(), ttft=res.ttft_ms.cpu().numpy(),
+               e2e=res.e2e_ms.cpu().numpy(), p95_ttft=res.p95_ttft_ms.cpu().numpy(),
+               p95_e2e=res.p95_e2e_ms.cpu().numpy())
+    return out
+
+
+def oracle_eval(tr, model: g.Model, rtt, w, scale):
+    return ob.replay(tr, R=model.R, batch=model.batch, cache_blocks=model.cache_blocks,
+                     prefill_ms_per_token=model.prefill_ms_per_token, decode_ms_per_token=model.decode_ms_per_token,
+                     rtt_ms=rtt, w=w, scale=scale, block_tokens=model.block_tokens)
+
+
+def assert_replay_equal(got, p, ref, label=""):
+    bad = np.nonzero(got["route"][p] != ref.route)[0]
+    assert bad.size == 0, f"{label} replay {p}: first route mismatch at request {bad[0]} ({bad.size} in all)"
+    bad = np.nonzero(got["hit"][p] != ref.hit_blocks)[0]
+    assert bad.size == 0, f"{label} replay {p}: first hit-count mismatch at request {bad[0]}"
+    np.testing.assert_allclose(got["ttft"][p], ref.ttft_ms, rtol=RTOL, atol=0, err_msg=f"{label} ttft replay {p}")
+    np.testing.assert_allclose(got["e2e"][p], ref.e2e_ms, rtol=RTOL, atol=0, err_msg=f"{label} e2e replay {p}")
+    if ref.ttft_ms.size:
+        assert abs(got["p95_ttft"][p] - ref.p95_ttft_ms) <= RTOL * abs(ref.p95_ttft_ms), f"{label} p95 ttft replay {p}"
+        assert abs(got["p95_e2e"][p] - ref.p95_e2e_ms) <= RTOL * abs(ref.p95_e2e_ms), f"{label} p95 e2e replay {p}"
+
+
+def check_population(tr, model, rtt, params, scale, replays=None, label=""):
+    params = np.asarray(params, np.float64)
+    P = params.shape[0]
+    scale = np.broadcast_to(np.asarray(scale, np.float64), (P,))
+    got = gpu_eval(tr, model, rtt, params, scale)
+    for p in (range(P) if replays is None else replays):
+        ref = oracle_eval(tr, model, rtt, params[p], float(scale[p]))
+        assert_replay_equal(got, p, ref, label)
+    return got

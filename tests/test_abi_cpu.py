@@ -1,0 +1,187 @@
+"""CPU-only tests of the C-ABI library: it loads, exports every declared symbol, and its host-side logic
+(trace loading, validation, tuner arithmetic, random draws) behaves as declared.  No compute call here."""
+import ctypes as C
+import json
+import math
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2602_11688_amd as g
+from paper_2602_11688_amd import binding as gb
+from oracle import es_oracle as eo
+from synth import tracegen as tg
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "gorgo.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    names = set(re.findall(r"\b(gorgo_[a-z0-9_]+)\s*\(", hdr))
+    assert {"gorgo_load_trace", "gorgo_eval_population", "gorgo_es_step"} <= names and len(names) >= 15
+    L = g.lib()
+    for n in sorted(names):
+        assert hasattr(L, n), f"{n} declared in gorgo.h but not exported"
+
+
+def _trace(tr):
+    return g.Trace.from_arrays(tr.ts_ms, tr.in_len, tr.out_len, tr.blk_off, tr.hash_ids)
+
+
+def test_trace_info_and_chain_consistency():
+    w = tg.config(1)
+    t = _trace(w.trace)
+    i = t.info()
+    assert i["N"] == 2000 and i["total_blocks"] == w.trace.blk_off[-1] and i["unique_ids"] == w.notes["unique_ids"]
+    assert i["max_blocks"] == w.notes["max_blocks"] and i["chain_consistent"]
+    bad = tg.random_small(3, 50, 2, consistent=False)
+    assert not _trace(bad).info()["chain_consistent"]
+    assert _trace(tg.random_small(3, 50, 2, consistent=True)).info()["chain_consistent"]
+
+
+def test_jsonl_loader_matches_arrays(tmp_path):
+    w = tg.config(1, 300)
+    p = tmp_path / "t.jsonl"
+    w.trace.write_jsonl(str(p))
+    with open(p, "a") as f:          # unknown members and blank lines are ignored
+        f.write('\n{"extra": {"a": [1, "x"]}, "timestamp": 999999, "hash_ids": [], "input_length": 0, '
+                '"output_length": 1, "note": "end"}\n')
+    t = g.Trace.from_jsonl(str(p))
+    i = t.info()
+    assert i["N"] == 301 and i["total_blocks"] == w.trace.blk_off[-1]
+    assert i == dict(_trace(w.trace).info(), N=301)
+
+
+@pytest.mark.parametrize("text,code", [
+    ('{"timestamp": 1, "input_length": 2, "output_length": 1}\n', -3),                       # hash_ids missing
+    ('{"timestamp": 1, "input_length": 2, "output_length": 1, "hash_ids": [1, }\n', -3),
+    ('{"timestamp": "x", "input_length": 2, "output_length": 1, "hash_ids": []}\n', -3),
+    ('not json\n', -3),
+    ('{"timestamp": 5, "input_length": 2, "output_length": 1, "hash_ids": [1]}\n'
+     '{"timestamp": 4, "input_length": 2, "output_length": 1, "hash_ids": [1]}\n', -4),       # unsorted
+])
+def test_jsonl_loader_errors(tmp_path, text, code):
+    p = tmp_path / "bad.jsonl"
+    p.write_text(text)
+    with pytest.raises(g.GorgoError) as e:
+        g.Trace.from_jsonl(str(p))
+    assert e.value.code == code and len(str(e.value)) > 15
+
+
+def test_loader_io_and_argument_errors(tmp_path):
+    with pytest.raises(g.GorgoError) as e:
+        g.Trace.from_jsonl(str(tmp_path / "missing.jsonl"))
+    assert e.value.code == -2
+    with pytest.raises(g.GorgoError) as e:
+        g.Trace.from_arrays([0, 1], [1, 1], [1, 1], [0, 1, 0], [1])          # blk_off decreases
+    assert e.value.code == -1
+    with pytest.raises(g.GorgoError) as e:
+        g.Trace.from_arrays([0], [-1], [1], [0, 1], [1])
+    assert e.value.code == -1
+    t = g.Trace.from_arrays([], [], [], [0], [])
+    assert t.info()["N"] == 0
+
+
+def test_model_validation_without_gpu():
+    t = _trace(tg.config(1, 100).trace)
+    ok = g.Model(4, 8, 0, 0.05, 20.0)
+    assert g.workspace_bytes(t, ok, 16) > 0
+    for bad, code in [(g.Model(0, 8, 0, 0.05, 20.0), -1), (g.Model(65, 8, 0, 0.05, 20.0), -1),
+                      (g.Model(64, 64, 0, 0.05, 20.0), -1), (g.Model(4, 8, 0, float("nan"), 20.0), -6),
+                      (g.Model(4, 8, 3, 0.05, 20.0), -5), (g.Model(4, 8, 0, 0.05, 20.0, block_tokens=256), -1)]:
+        with pytest.raises(g.GorgoError) as e:
+            g.workspace_bytes(t, bad, 16)
+        assert e.value.code == code
+    with pytest.raises(g.GorgoError):
+        g.workspace_bytes(t, ok, 0)
+
+
+def test_eval_rejects_bad_arguments_before_touching_a_device():
+    t = _trace(tg.config(1, 50).trace)
+    m = g.Model(4, 8, 0, 0.05, 20.0).c()
+    L = g.lib()
+    rtt = np.array([10.0, 40.0, 120.0, 300.0])
+    par = np.ones((2, 3))
+    sc = np.ones(2)
+    o = gb._Outputs()
+
+    def call(rtt=rtt, par=par, sc=sc, ws=C.c_void_p(256), nbytes=1 << 40):
+        return L.gorgo_eval_population(t._h, C.byref(m), gb._ptr(rtt), gb._ptr(par), gb._ptr(sc), 2, C.byref(o), ws,
+                                       nbytes, None)
+    assert call(rtt=np.array([10.0, np.inf, 1, 1])) == -6
+    assert call(par=np.array([[1, 1, np.nan], [1, 1, 1]])) == -6
+    assert call(par=np.array([[1, 1, 1e200], [1, 1, 1]])) == -6
+    assert call(sc=np.array([1.0, -1.0])) == -6
+    assert call(ws=None) == -7
+    assert call(ws=C.c_void_p(264)) == -7
+    assert call(nbytes=1024) == -7
+    assert b"workspace" in L.gorgo_last_error()
+
+
+# ------------------------------------------------------------------------------------------------ tuner
+
+def test_philox_known_answers():
+    """Known-answer vectors of Philox-4x32-10 as published with the generator (Random123 test vectors)."""
+    assert [hex(x) for x in g.philox4x32_10([0, 0, 0, 0], [0, 0])] == ['0x6627e8d5', '0xe169c58d', '0xbc57ac4c', '0x9b00dbd8']
+    assert [hex(x) for x in g.philox4x32_10([0x243f6a88, 0x85a308d3, 0x13198a2e, 0x03707344], [0xa4093822, 0x299f31d0])] == \
+        ['0xd16cfe09', '0x94fdcceb', '0x5001e420', '0x24126ea1']
+
+
+def test_normal_draws_are_reproducible_and_standard():
+    z = g.es_sample(7, 3, 40000)
+    assert (z == g.es_sample(7, 3, 40000)).all()
+    assert (z[:100] == g.es_sample(7, 3, 100)).all()                 # counter-based: prefix-stable
+    assert (z != g.es_sample(7, 4, 40000)).any() and (z != g.es_sample(8, 3, 40000)).any()
+    assert abs(z.mean()) < 0.01 and abs(z.std() - 1) < 0.01
+    assert abs((np.abs(z) < 1.959964).mean() - 0.95) < 0.004
+    assert abs(np.corrcoef(z[:, 0], z[:, 1])[0, 1]) < 0.02
+
+
+def test_propose_matches_oracle_mutation_rule():
+    s = g.es_init(11)
+    assert list(s.theta) == [0.5, 1.0, 0.1] and s.sigma == 0.5 and list(s.lo) == [0.05, 1.0, 0.05] and list(s.hi) == [2.0, 1.0, 0.5]
+    z = g.es_sample(11, 0, 64)
+    z[5] = [50, 0, 50]
+    z[6] = [-50, 0, -50]
+    p = g.es_propose(s, z)
+    ref = eo.offspring(list(s.theta), s.sigma, list(s.lo), list(s.hi), z)
+    np.testing.assert_allclose(p, ref, rtol=1e-15)
+    assert p[0].tolist() == [0.5, 1.0, 0.1] and p[5].tolist() == [2.0, 1.0, 0.5] and p[6].tolist() == [0.05, 1.0, 0.05]
+
+
+@pytest.mark.parametrize("P", [1, 2, 5, 8, 64, 1024])
+def test_update_matches_oracle(P):
+    rng = np.random.default_rng(P)
+    s = g.es_init(3)
+    for gen in range(4):
+        z = g.es_sample(3, s.generation, P)
+        par = g.es_propose(s, z)
+        fit = rng.uniform(100, 200, P).round(0)                      # rounded: ties do occur
+        th, sg, bf, bt = eo.update(list(s.theta), s.sigma, list(s.lo), list(s.hi), par, fit, s.best_fitness,
+                                   np.array(list(s.best_theta)))
+        g.es_update(s, par, fit)
+        np.testing.assert_allclose(list(s.theta), th, rtol=1e-14)
+        assert abs(s.sigma - sg) <= 1e-15 * sg and s.best_fitness == bf and list(s.best_theta) == list(bt)
+        assert s.generation == gen + 1
+
+
+def test_update_one_plus_one_accepts_only_strict_improvement():
+    s = g.es_init(0)
+    par = np.array([[0.5, 1.0, 0.1], [0.9, 1.0, 0.3]])
+    g.es_update(s, par, [10.0, 10.0])
+    assert list(s.theta) == [0.5, 1.0, 0.1] and s.sigma == 0.5 * math.exp(-0.1)
+    g.es_update(s, par, [10.0, 9.0])
+    assert list(s.theta) == [0.9, 1.0, 0.3] and s.best_fitness == 9.0
+
+
+def test_es_rejects_bad_state():
+    s = g.es_init(0)
+    s.theta[0] = -1.0
+    with pytest.raises(g.GorgoError):
+        g.es_propose(s, np.zeros((2, 3)))
+    s = g.es_init(0)
+    with pytest.raises(g.GorgoError):
+        g.es_update(s, np.ones((2, 3)), [float("nan"), 1.0])

@@ -1,0 +1,163 @@
+"""GPU parity: the HIP library against the CPU oracle, element by element, through the C ABI."""
+import numpy as np
+import pytest
+
+import paper_2602_11688_amd as g
+from oracle import binding as ob
+from oracle import es_oracle as eo
+from synth import tracegen as tg
+from tests.gpu_helpers import assert_replay_equal, check_population, gpu_eval, load, oracle_eval
+from tests.helpers import load_golden
+
+pytestmark = pytest.mark.gpu
+
+
+def _model(wl, **over):
+    kw = dict(R=wl.R, batch=wl.batch, cache_blocks=wl.cache_blocks, prefill_ms_per_token=wl.prefill_ms_per_token,
+              decode_ms_per_token=wl.decode_ms_per_token)
+    kw.update(over)
+    return g.Model(**kw)
+
+
+@pytest.mark.parametrize("name", ["hand_trace_A.json", "hand_trace_B.json", "hand_trace_C.json", "hand_trace_D.json"])
+def test_hand_traces(name):
+    gold, tr = load_golden(name)
+    m = gold["model"]
+    model = g.Model(m["R"], m["batch"], m["cache_blocks"], m["prefill_ms_per_token"], m["decode_ms_per_token"])
+    got = gpu_eval(tr, model, gold["rtt_ms"], [gold["w"]], gold["scale"])
+    e = gold["expected"]
+    assert got["route"][0].tolist() == e["route"]
+    assert got["hit"][0].tolist() == e["hit_blocks"]
+    assert got["ttft"][0].tolist() == e["ttft_ms"]
+    assert got["e2e"][0].tolist() == e["e2e_ms"]
+    if "p95_ttft_ms" in e:
+        assert got["p95_ttft"][0] == e["p95_ttft_ms"] and got["p95_e2e"][0] == e["p95_e2e_ms"]
+
+
+def test_config1_all_replays_unbounded_cache():
+    wl = tg.config(1)
+    got = check_population(wl.trace, _model(wl), wl.rtt_ms, wl.params, wl.scale, label="config1")
+    assert len(set(got["route"].ravel().tolist())) == wl.R
+
+
+def test_config2_lru_prefix():
+    # 7,000 requests fill the eight 4,000-block caches several times over
+    wl = tg.config(2, 7000)
+    got = check_population(wl.trace, _model(wl), wl.rtt_ms, wl.params[:6], wl.scale[:6], label="config2")
+    assert got["hit"].max() > 64          # matches span more than one 64-block tile
+
+
+def test_small_cache_heavy_eviction_and_table_compaction():
+    wl = tg.config(2, 2500)
+    g.set_table_factor_percent(110)       # smallest tables: compaction happens often
+    try:
+        model = _model(wl, R=3, cache_blocks=300, batch=4)
+        rng = np.random.default_rng(1)
+        par = rng.uniform(0, 2, (6, 3))
+        par[0] = [0.0, 1.0, 0.0]          # prefix-only: concentrates traffic, evicts the most
+        par[1] = [1.0, 1.0, 0.0]
+        check_population(wl.trace, model, [10.0, 12.0, 15.0], par, 1.0, label="small-cache")
+    finally:
+        g.set_table_factor_percent(200)
+
+
+@pytest.mark.parametrize("seed,C,R,B", [(0, 0, 2, 1), (1, 6, 3, 2), (2, 9, 5, 3), (3, 40, 64, 16), (4, 12, 1, 64)])
+def test_inconsistent_traces_with_repeated_ids(seed, C, R, B):
+    tr = tg.random_small(seed, 700, R, n_ids=40, max_blocks=6, consistent=False, gap_ms=30)
+    rng = np.random.default_rng(seed)
+    model = g.Model(R, B, C, 0.05, 20.0)
+    check_population(tr, model, rng.uniform(5, 80, R), rng.uniform(0, 2, (5, 3)), 1.0, label=f"random{seed}")
+
+
+def test_weight_special_cases_and_negative_weights():
+    wl = tg.config(1, 800)
+    par = np.array([[0, 0, 0], [1, 0, 0], [0, 1, 0], [0, 0, 1], [-1.0, 1.0, 0.5], [1.0, -0.5, 0.25]], np.float64)
+    got = check_population(wl.trace, _model(wl), wl.rtt_ms, par, 1.0, label="special")
+    assert (got["route"][0] == 0).all() and (got["route"][1] == 0).all()
+
+
+def test_time_scales_in_one_launch():
+    wl = tg.config(4, 3000)
+    idx = [0, 127, 128, 400, 640, 1023]
+    check_population(wl.trace, _model(wl, cache_blocks=1500), wl.rtt_ms, wl.params[idx], wl.scale[idx], label="sweep")
+
+
+def test_edge_cases():
+    z = np.zeros(0, np.int64)
+    # empty trace
+    tr = tg.Trace(z, z.astype(np.int32), z.astype(np.int32), np.zeros(1, np.int64), z)
+    got = gpu_eval(tr, g.Model(2, 2, 0, 0.05, 20.0), [1.0, 2.0], [[1, 1, 1]], 1.0)
+    assert got["route"].shape == (1, 0) and got["p95_ttft"][0] == 0.0
+    # requests without blocks, zero-length prompts, identical timestamps, one request
+    tr = tg.Trace(np.array([5, 5, 5, 9]), np.array([0, 100, 700, 0], np.int32), np.array([1, 0, 3, 2], np.int32),
+                  np.array([0, 0, 0, 2, 2]), np.array([4, 5]))
+    check_population(tr, g.Model(2, 1, 0, 0.05, 20.0), [3.0, 3.0], [[1, 1, 1], [0.1, 1, 2]], [1.0, 0.0], label="edge")
+    check_population(tr.head(1), g.Model(1, 1, 2, 0.05, 20.0), [3.0], [[1, 1, 1]], 2.5, label="single")
+
+
+def test_max_blocks_request_and_ragged_tails():
+    # one conversation that grows past several 64-lane tiles with ragged lengths, bounded cache
+    rng = np.random.default_rng(9)
+    lens = [1, 63, 64, 65, 127, 128, 129, 200, 255, 256, 300, 64, 1, 300]
+    ids, off = [], [0]
+    for n in lens:
+        ids += list(range(1, n + 1))
+        off.append(len(ids))
+    N = len(lens)
+    tr = tg.Trace(np.arange(N, dtype=np.int64) * 700, (np.array(lens) * 512 - 7).astype(np.int32),
+                  rng.integers(1, 40, N).astype(np.int32), np.array(off, np.int64), np.array(ids, np.int64))
+    check_population(tr, g.Model(2, 2, 310, 0.05, 20.0), [10.0, 11.0], [[1, 1, 0.0], [1, 1, 1], [0, 0, 1]], 1.0,
+                     label="ragged")
+
+
+def test_same_launch_twice_is_identical():
+    wl = tg.config(2, 3000)
+    h = load(wl.trace)
+    a = gpu_eval(wl.trace, _model(wl, cache_blocks=1000), wl.rtt_ms, wl.params[:4], 1.0, handle=h)
+    b = gpu_eval(wl.trace, _model(wl, cache_blocks=1000), wl.rtt_ms, wl.params[:4], 1.0, handle=h)
+    for k in a:
+        assert a[k].tobytes() == b[k].tobytes()
+
+
+def test_p95_only_outputs_and_percentile_selection():
+    import torch
+    wl = tg.config(1)
+    h = load(wl.trace)
+    res = g.eval_population(h, _model(wl), wl.rtt_ms, wl.params, wl.scale, per_request=False)
+    full = g.eval_population(h, _model(wl), wl.rtt_ms, wl.params, wl.scale)
+    torch.cuda.synchronize()
+    assert res.route is None
+    assert res.p95_ttft_ms.cpu().numpy().tobytes() == full.p95_ttft_ms.cpu().numpy().tobytes()
+    t = full.ttft_ms.cpu().numpy()
+    k = -(-95 * t.shape[1] // 100)
+    assert (np.sort(t, axis=1)[:, k - 1] == full.p95_ttft_ms.cpu().numpy()).all()
+    assert (np.array([ob.p95(row) for row in full.e2e_ms.cpu().numpy()]) == full.p95_e2e_ms.cpu().numpy()).all()
+
+
+def test_es_generations_match_oracle():
+    wl = tg.config(1, 1200)
+    h = load(wl.trace)
+    model = _model(wl)
+    P = 12
+    s = g.es_init(2024)
+    theta, sigma, bf, bt = list(s.theta), s.sigma, float("inf"), None
+    ws = None
+    for gen in range(3):
+        z = g.es_sample(2024, gen, P)
+        par_ref = eo.offspring(theta, sigma, list(s.lo), list(s.hi), z)
+        fit_ref = np.array([oracle_eval(wl.trace, model, wl.rtt_ms, par_ref[p], 1.0).p95_ttft_ms for p in range(P)])
+        theta, sigma, bf, bt = eo.update(theta, sigma, list(s.lo), list(s.hi), par_ref, fit_ref, bf, bt)
+        par, fit, ws = g.es_step(h, model, wl.rtt_ms, 1.0, P, s, workspace=ws)
+        np.testing.assert_allclose(par, par_ref, rtol=1e-15)
+        np.testing.assert_allclose(fit, fit_ref, rtol=1e-9)
+        np.testing.assert_allclose(list(s.theta), theta, rtol=1e-12)
+        assert abs(s.sigma - sigma) <= 1e-12 * sigma and s.generation == gen + 1
+        assert abs(s.best_fitness - bf) <= 1e-9 * bf
+
+
+def test_missing_library_is_an_error(monkeypatch):
+    from paper_2602_11688_amd import binding
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "_LIB_PATH", "/nonexistent/libgorgo.so")
+    with pytest.raises(RuntimeError):
+        binding.lib()
