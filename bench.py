@@ -1,0 +1,150 @@
+#!/usr/bin/env python3
+"""Benchmark of the batched routing-fitness evaluation on one MI355X.
+
+A "step" is one generation of the tuner on the Large workload (R=32 replicas, N=1,000,000 requests,
+16,000-block LRU caches, P=1,024 candidate weight vectors): sample and propose the candidates, replay the
+whole trace under all of them (score, route, cache/queue update per request), reduce every replay to its
+p95 TTFT, update the parent weights and step size.  The trace is resident in HBM before the timed region.
+
+Prints ONE JSON line: candidate-request routings per second (whole job), the replay kernel's HBM roofline
+(algorithmic bytes / HIP-event kernel time against 8 TB/s) and the CPU oracle timed on a bounded sample.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def algorithmic_bytes_per_routing(R, n_mean, hit_mean, outputs_bytes):
+    """Bytes one routing has to move in the hashed-block-set formulation with 16-byte table slots
+    (8-byte key + 8-byte recency stamp), private to one replay:
+      first-block probe on every replica           16 * R
+      prefix match on the replica holding it       16 * (hit + 1)
+      update on the chosen replica                 16 * n probe reads + 8 * hit stamp writes
+                                                   + 16 * (n - hit) inserts
+      eviction walk (every logged touch re-read once before its slot is given up)   16 * n
+      in-flight record push + pop                  16 + 16
+      per-request outputs                          outputs_bytes
+    The trace itself (28 B + 5 B per block per request) is shared by all replays and is not counted."""
+    n, h = n_mean, hit_mean
+    return 16 * R + 16 * (h + 1) + (16 * n + 8 * h + 16 * (n - h)) + 16 * n + 32 + outputs_bytes
+
+
+def cpu_baseline(wl, params, n_req, threads):
+    """The oracle as it stands, one replay per thread, on the first n_req requests of the workload."""
+    from concurrent.futures import ThreadPoolExecutor
+    from oracle import binding as ob
+    tr = wl.trace.head(n_req)
+    ob.lib()
+
+    def one(p):
+        return ob.replay(tr, R=wl.R, batch=wl.batch, cache_blocks=wl.cache_blocks,
+                         prefill_ms_per_token=wl.prefill_ms_per_token, decode_ms_per_token=wl.decode_ms_per_token,
+                         rtt_ms=wl.rtt_ms, w=params[p], scale=1.0).p95_ttft_ms
+    t0 = time.perf_counter()
+    with ThreadPoolExecutor(threads) as ex:
+        list(ex.map(one, range(threads)))
+    dt = time.perf_counter() - t0
+    return threads * tr.N / dt, dt, tr.N
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--config", type=int, default=5, help="workload index (5 = Large, the one the metric is quoted on)")
+    ap.add_argument("--requests", type=int, default=None, help="truncate the trace (experiments only)")
+    ap.add_argument("--population", type=int, default=None, help="override P (experiments only)")
+    ap.add_argument("--cpu-sample-requests", type=int, default=150000)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build evaluates on ONE GPU (replays are independent and would shard by candidate; "
+                 "no multi-GPU path is built) -- run with --gpus 1")
+
+    import torch
+    import paper_2602_11688_amd as g
+    from synth import tracegen as tg
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    t_setup = time.perf_counter()
+    wl = tg.config(args.config, args.requests)
+    es_cfg = wl.es if wl.es else dict(tg.ES_DEFAULTS, P=wl.P, seed=tg.MASTER_SEED + args.config)
+    P = args.population or es_cfg["P"]
+    tr = g.Trace.from_arrays(wl.trace.ts_ms, wl.trace.in_len, wl.trace.out_len, wl.trace.blk_off, wl.trace.hash_ids)
+    N = tr.N
+    model = g.Model(wl.R, wl.batch, wl.cache_blocks, wl.prefill_ms_per_token, wl.decode_ms_per_token)
+    state = g.es_init(es_cfg["seed"])
+    ws = torch.empty((g.es_workspace_bytes(tr, model, P),), dtype=torch.uint8, device="cuda:0")
+    print(f"[bench] workload {wl.name}: R={wl.R} N={N} P={P} C={wl.cache_blocks} mean blocks/request "
+          f"{np.diff(wl.trace.blk_off).mean():.1f}; workspace {ws.numel() / 2**30:.1f} GiB; setup "
+          f"{time.perf_counter() - t_setup:.1f}s", file=sys.stderr, flush=True)
+
+    def generation():
+        par, fit, _ = g.es_step(tr, model, wl.rtt_ms, 1.0, P, state, workspace=ws)
+        return par, fit, g.last_eval_kernel_ms()
+
+    for i in range(args.warmup):
+        t0 = time.perf_counter()
+        generation()
+        print(f"[bench] warmup generation {i}: {time.perf_counter() - t0:.2f}s", file=sys.stderr, flush=True)
+    torch.cuda.synchronize()
+    kernel_ms, fill_ms, select_ms = [], [], []
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        par, fit, km = generation()
+        kernel_ms.append(km["replay_ms"])
+        fill_ms.append(km["fill_ms"])
+        select_ms.append(km["select_ms"])
+        print(f"[bench] generation {i}: replay kernel {km['replay_ms']:.1f} ms, best p95 TTFT {fit.min():.1f} ms, "
+              f"theta=({state.theta[0]:.3f},{state.theta[2]:.3f}) sigma={state.sigma:.3f}", file=sys.stderr, flush=True)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = 1000.0 * wall / args.steps
+    value = P * N * args.steps / wall
+
+    # measured mean hit length on a sample of the last generation's candidates (outside the timed region)
+    sample = min(P, 16)
+    res = g.eval_population(tr, model, wl.rtt_ms, par[:sample], 1.0, p95=False)
+    torch.cuda.synchronize()
+    hit_mean = float(res.hit_blocks.to(torch.float64).mean().item())
+    del res
+    n_mean = float(np.diff(wl.trace.blk_off).mean())
+    bpr = algorithmic_bytes_per_routing(wl.R, n_mean, hit_mean, outputs_bytes=9)   # route u8 + ttft f64
+    k_ms = float(np.mean(kernel_ms))
+    achieved = bpr * P * N / (k_ms * 1e-3) / 1e9
+
+    out = {
+        "metric": "candidate-request routings/sec at P=1024", "value": value, "unit": "routings/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f64", "data": "synthetic",
+        "config": {"workload": f"config-{args.config} {wl.name}: R={wl.R} N={N} P={P} cache={wl.cache_blocks} blocks LRU, "
+                               f"one ES generation per step (eval + p95 TTFT fitness + mean update)",
+                   "es_generation_wall_s": wall / args.steps},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None, "kernel": "replay_kernel",
+                     "kernel_ms": k_ms, "bytes_per_routing": bpr, "mean_blocks": n_mean, "mean_hit_blocks": hit_mean,
+                     "fill_ms": float(np.mean(fill_ms)), "select_ms": float(np.mean(select_ms))},
+    }
+    if not args.no_cpu_baseline:
+        cores = min(len(os.sched_getaffinity(0)), 16)
+        v, dt, n_s = cpu_baseline(wl, par, min(args.cpu_sample_requests, N), cores)
+        out["cpu_baseline"] = {"value": v, "unit": "routings/s", "cores": cores, "kind": "oracle",
+                               "sample": f"{cores} replays (one per thread) x first {n_s} requests of the same trace, "
+                                         f"{dt:.1f}s wall"}
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

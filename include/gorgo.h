@@ -171,7 +171,12 @@ int gorgo_es_step(const gorgo_trace* t, const gorgo_model* m, const double* rtt_
                   size_t workspace_bytes, void* hip_stream);
 
 /* ------------------------------------------------------------------------------------------------ misc
- * Tuning knob for tests and experiments: the open-addressed cache tables get at least
+ * Device time (ms, HIP events recorded on the evaluation's stream) of the three stages of the most recent
+ * gorgo_eval_population / gorgo_es_step issued by the calling thread: state initialisation, the replay
+ * kernel, and the percentile selection.  Waits for that evaluation to finish.  Each pointer may be NULL. */
+int gorgo_last_eval_kernel_ms(double* fill_ms, double* replay_ms, double* select_ms);
+
+/* Tuning knob for tests and experiments: the open-addressed cache tables get at least
  * ceil(factor_percent/100 * (cache_blocks + max blocks of a request)) slots, rounded up to a power of two
  * (default 200, minimum 110).  Results never depend on it. */
 int gorgo_set_table_factor_percent(int32_t factor_percent);

@@ -68,9 +68,11 @@ def lib():
         L.gorgo_es_workspace_bytes.argtypes = [vp, C.POINTER(_Model), i32, C.POINTER(C.c_size_t)]
         L.gorgo_es_step.argtypes = [vp, C.POINTER(_Model), vp, dbl, i32, C.POINTER(EsState), vp, vp, vp, C.c_size_t, vp]
         L.gorgo_set_table_factor_percent.argtypes = [i32]
+        L.gorgo_last_eval_kernel_ms.argtypes = [C.POINTER(dbl)] * 3
         for name in ("gorgo_load_trace", "gorgo_load_trace_arrays", "gorgo_trace_info", "gorgo_workspace_bytes",
                      "gorgo_eval_population", "gorgo_es_init", "gorgo_es_sample", "gorgo_es_propose",
-                     "gorgo_es_update", "gorgo_es_workspace_bytes", "gorgo_es_step", "gorgo_set_table_factor_percent"):
+                     "gorgo_es_update", "gorgo_es_workspace_bytes", "gorgo_es_step", "gorgo_set_table_factor_percent",
+                     "gorgo_last_eval_kernel_ms"):
             getattr(L, name).restype = C.c_int
         _lib = L
     return _lib
@@ -152,6 +154,13 @@ class Trace:
 
 def set_table_factor_percent(pct: int):
     _check(lib().gorgo_set_table_factor_percent(pct))
+
+
+def last_eval_kernel_ms() -> dict:
+    """Device milliseconds of the stages of this thread's most recent evaluation (waits for it)."""
+    a, b, c = C.c_double(), C.c_double(), C.c_double()
+    _check(lib().gorgo_last_eval_kernel_ms(C.byref(a), C.byref(b), C.byref(c)))
+    return dict(fill_ms=a.value, replay_ms=b.value, select_ms=c.value)
 
 
 def _outputs_struct(route=None, hit_blocks=None, ttft_ms=None, e2e_ms=None, p95_ttft_ms=None, p95_e2e_ms=None):

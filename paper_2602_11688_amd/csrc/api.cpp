@@ -154,6 +154,11 @@ int gorgo_eval_population(const gorgo_trace* t, const gorgo_model* m, const doub
     return GORGO_OK;
 }
 
+int gorgo_last_eval_kernel_ms(double* fill_ms, double* replay_ms, double* select_ms) {
+    clear_error();
+    return last_eval_kernel_ms(fill_ms, replay_ms, select_ms);
+}
+
 int gorgo_es_workspace_bytes(const gorgo_trace* t, const gorgo_model* m, int32_t P, size_t* bytes) {
     clear_error();
     if (!bytes) return fail(GORGO_ERR_INVALID_ARG, "bytes is NULL");

@@ -63,6 +63,7 @@ int launch_replay(const gorgo_trace* t, const Plan& pl, const double* d_rtt, con
                   const double* d_scale, uint8_t* route, uint16_t* hit, double* ttft, double* e2e,
                   void* workspace, void* stream);
 int launch_p95(const double* x, int64_t N, int32_t P, double* out, void* stream);
+int last_eval_kernel_ms(double* fill_ms, double* replay_ms, double* select_ms);
 int upload_trace(const gorgo_trace* t);
 void release_device_trace(gorgo_trace* t);
 int copy_small_to_device(void* dst, const void* src, size_t bytes, void* stream);

@@ -489,6 +489,28 @@ int hip_fail(hipError_t e, const char* what) {
     return fail(GORGO_ERR_DEVICE, std::string(what) + ": " + hipGetErrorString(e));
 }
 
+// HIP events bracketing the kernels of the most recent evaluation on this thread (for measurement).
+struct Marks {
+    hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};   // before fill, before replay, after replay, after select
+    int device = -1;
+    bool valid = false;
+};
+thread_local Marks g_marks;
+
+bool marks_ready() {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return false;
+    if (g_marks.device == dev) return true;
+    for (auto& e : g_marks.ev)
+        if (hipEventCreate(&e) != hipSuccess) return false;
+    g_marks.device = dev;
+    return true;
+}
+
+void mark(int i, hipStream_t s) {
+    if (g_marks.device >= 0) (void)hipEventRecord(g_marks.ev[i], s);
+}
+
 }  // namespace
 
 int upload_trace(const gorgo_trace* tc) {
@@ -584,17 +606,39 @@ int launch_replay(const gorgo_trace* t, const Plan& pl, const double* d_rtt, con
     a.hit = hit;
     a.ttft = ttft;
     a.e2e = e2e;
+    g_marks.valid = false;
+    marks_ready();
+    mark(0, s);
     const size_t nslots = (size_t)pl.P * pl.R * pl.cap;
     size_t blocks = (nslots + 255) / 256;
     if (blocks > 65536) blocks = 65536;
     hipLaunchKernelGGL(fill_slots, dim3((unsigned)blocks), dim3(256), 0, s, a.tables, nslots);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(e, "launch fill_slots");
+    mark(1, s);
     if (pl.N > 0) {
         hipLaunchKernelGGL(replay_kernel, dim3((unsigned)pl.P), dim3(WAVE), replay_lds_bytes(pl.R, pl.B), s, a);
         e = hipGetLastError();
         if (e != hipSuccess) return hip_fail(e, "launch replay_kernel");
     }
+    mark(2, s);
+    mark(3, s);
+    g_marks.valid = g_marks.device >= 0;
+    return GORGO_OK;
+}
+
+int last_eval_kernel_ms(double* fill_ms, double* replay_ms, double* select_ms) {
+    if (!g_marks.valid) return fail(GORGO_ERR_INVALID_ARG, "no evaluation has been enqueued on this thread");
+    hipError_t e = hipEventSynchronize(g_marks.ev[3]);
+    if (e != hipSuccess) return hip_fail(e, "hipEventSynchronize");
+    float a = 0, b = 0, c = 0;
+    if ((e = hipEventElapsedTime(&a, g_marks.ev[0], g_marks.ev[1])) != hipSuccess ||
+        (e = hipEventElapsedTime(&b, g_marks.ev[1], g_marks.ev[2])) != hipSuccess ||
+        (e = hipEventElapsedTime(&c, g_marks.ev[2], g_marks.ev[3])) != hipSuccess)
+        return hip_fail(e, "hipEventElapsedTime");
+    if (fill_ms) *fill_ms = a;
+    if (replay_ms) *replay_ms = b;
+    if (select_ms) *select_ms = c;
     return GORGO_OK;
 }
 
@@ -603,6 +647,7 @@ int launch_p95(const double* x, int64_t N, int32_t P, double* out, void* stream)
     hipLaunchKernelGGL(select_kth, dim3((unsigned)P), dim3(SEL_THREADS), 0, static_cast<hipStream_t>(stream), x, N,
                        kth, out);
     hipError_t e = hipGetLastError();
+    mark(3, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? GORGO_OK : hip_fail(e, "launch select_kth");
 }
 
