@@ -65,7 +65,7 @@ def main():
     ap.add_argument("--config", type=int, default=5, help="workload index (5 = Large, the one the metric is quoted on)")
     ap.add_argument("--requests", type=int, default=None, help="truncate the trace (experiments only)")
     ap.add_argument("--population", type=int, default=None, help="override P (experiments only)")
-    ap.add_argument("--cpu-sample-requests", type=int, default=150000)
+    ap.add_argument("--cpu-sample-requests", type=int, default=600000)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
