@@ -176,6 +176,13 @@ int gorgo_es_step(const gorgo_trace* t, const gorgo_model* m, const double* rtt_
  * kernel, and the percentile selection.  Waits for that evaluation to finish.  Each pointer may be NULL. */
 int gorgo_last_eval_kernel_ms(double* fill_ms, double* replay_ms, double* select_ms);
 
+/* Choice of cache-state formulation for subsequent calls: 0 = automatic (default), 1 = hashed block tables
+ * (any trace), 2 = dense segment rows (chain-consistent traces only; evaluation fails with
+ * GORGO_ERR_INVALID_ARG otherwise).  Both compute identical results; they differ in workspace size and
+ * speed.  Automatic picks segment rows when the trace is chain-consistent and its requests average at most
+ * 16 segments.  gorgo_workspace_bytes reflects the choice in force when it is called. */
+int gorgo_set_replay_path(int32_t mode);
+
 /* Tuning knob for tests and experiments: the open-addressed cache tables get at least
  * ceil(factor_percent/100 * (cache_blocks + max blocks of a request)) slots, rounded up to a power of two
  * (default 200, minimum 110).  Results never depend on it. */

@@ -68,11 +68,12 @@ def lib():
         L.gorgo_es_workspace_bytes.argtypes = [vp, C.POINTER(_Model), i32, C.POINTER(C.c_size_t)]
         L.gorgo_es_step.argtypes = [vp, C.POINTER(_Model), vp, dbl, i32, C.POINTER(EsState), vp, vp, vp, C.c_size_t, vp]
         L.gorgo_set_table_factor_percent.argtypes = [i32]
+        L.gorgo_set_replay_path.argtypes = [i32]
         L.gorgo_last_eval_kernel_ms.argtypes = [C.POINTER(dbl)] * 3
         for name in ("gorgo_load_trace", "gorgo_load_trace_arrays", "gorgo_trace_info", "gorgo_workspace_bytes",
                      "gorgo_eval_population", "gorgo_es_init", "gorgo_es_sample", "gorgo_es_propose",
                      "gorgo_es_update", "gorgo_es_workspace_bytes", "gorgo_es_step", "gorgo_set_table_factor_percent",
-                     "gorgo_last_eval_kernel_ms"):
+                     "gorgo_last_eval_kernel_ms", "gorgo_set_replay_path"):
             getattr(L, name).restype = C.c_int
         _lib = L
     return _lib
@@ -154,6 +155,11 @@ class Trace:
 
 def set_table_factor_percent(pct: int):
     _check(lib().gorgo_set_table_factor_percent(pct))
+
+
+def set_replay_path(mode: int):
+    """0 = automatic, 1 = hashed block tables, 2 = dense segment rows."""
+    _check(lib().gorgo_set_replay_path(mode))
 
 
 def last_eval_kernel_ms() -> dict:

@@ -12,6 +12,7 @@ namespace gorgo {
 namespace {
 
 std::atomic<int32_t> g_table_factor_percent{200};
+std::atomic<int32_t> g_path{PATH_AUTO};
 
 size_t up256(size_t x) { return (x + 255) & ~(size_t)255; }
 
@@ -47,6 +48,15 @@ int make_plan(const gorgo_trace* t, const gorgo_model* m, int32_t P, const gorgo
     pl->block_tokens = m->block_tokens;
     pl->a_pf = m->prefill_ms_per_token;
     pl->a_dec = m->decode_ms_per_token;
+    // Formulation: dense segment rows when the trace is chain-consistent and its requests are few segments
+    // long (every request then costs a handful of row reads); hashed block tables otherwise.
+    const int32_t mode = g_path.load();
+    const bool seg_ok = t->chain_consistent;
+    if (mode == PATH_SEGMENTS && !seg_ok)
+        return fail(GORGO_ERR_INVALID_ARG, "the segment formulation needs a chain-consistent trace");
+    const bool few = (int64_t)t->seg.size() <= 16 * (t->N > 0 ? t->N : 1);
+    pl->path = mode == PATH_SEGMENTS || (mode == PATH_AUTO && seg_ok && few) ? PATH_SEGMENTS : PATH_BLOCKS;
+    pl->nseg = t->n_segments;
     // A table must hold the cached blocks plus the blocks of the request being inserted, with room to
     // spare: the replay compacts a table once 7/8 of its slots have been used.
     const int64_t d = t->max_distinct;
@@ -61,9 +71,14 @@ int make_plan(const gorgo_trace* t, const gorgo_model* m, int32_t P, const gorgo
     const size_t N = (size_t)t->N;
     size_t off = 0;
     pl->off_tables = off;
-    off += up256((size_t)P * pl->R * (size_t)cap * 16);
-    pl->off_spare = off;
-    off += up256((size_t)P * (size_t)cap * 16);
+    if (pl->path == PATH_SEGMENTS) {
+        off += up256((size_t)P * (size_t)pl->nseg * pl->R * 4);
+        pl->off_spare = off;
+    } else {
+        off += up256((size_t)P * pl->R * (size_t)cap * 16);
+        pl->off_spare = off;
+        off += up256((size_t)P * (size_t)cap * 16);
+    }
     pl->off_rec = off;
     off += up256((size_t)P * N * 16);
     const bool want_p95_t = !o || o->p95_ttft_ms, want_p95_e = !o || o->p95_e2e_ms;
@@ -90,6 +105,14 @@ int gorgo_set_table_factor_percent(int32_t factor_percent) {
     clear_error();
     if (factor_percent < 110 || factor_percent > 1600) return fail(GORGO_ERR_INVALID_ARG, "factor must be in 110..1600");
     g_table_factor_percent.store(factor_percent);
+    return GORGO_OK;
+}
+
+int gorgo_set_replay_path(int32_t mode) {
+    clear_error();
+    if (mode != PATH_AUTO && mode != PATH_BLOCKS && mode != PATH_SEGMENTS)
+        return fail(GORGO_ERR_INVALID_ARG, "mode must be 0 (auto), 1 (block tables) or 2 (segment rows)");
+    g_path.store(mode);
     return GORGO_OK;
 }
 

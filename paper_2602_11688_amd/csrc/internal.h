@@ -13,6 +13,13 @@ namespace gorgo {
 int fail(int code, const std::string& msg);
 void clear_error();
 
+// One segment of a request's block list: segment id and the number of the request's blocks up to and
+// including this segment.
+struct SegRef {
+    int32_t id;
+    int32_t end;
+};
+
 // Device-resident copy of a trace (filled lazily by the first evaluation).
 struct DeviceTrace {
     int device = -1;
@@ -23,6 +30,8 @@ struct DeviceTrace {
     const int64_t* blk_off = nullptr;   // [N+1]
     const uint32_t* key = nullptr;      // [total] dense block key (1-based)
     const uint8_t* first = nullptr;     // [total] 1 = first occurrence of its key inside the request
+    const int64_t* seg_off = nullptr;   // [N+1] (chain-consistent traces only)
+    const SegRef* seg = nullptr;        // [seg_off[N]]
 };
 
 }  // namespace gorgo
@@ -41,13 +50,20 @@ struct gorgo_trace {
     int32_t max_distinct = 0;        // largest number of distinct ids in one request
     int64_t unique_ids = 0;
     bool chain_consistent = true;
+    std::vector<int64_t> seg_off;    // chain-consistent traces: request -> its segments
+    std::vector<gorgo::SegRef> seg;
+    int64_t n_segments = 0;
     gorgo::DeviceTrace dev;
 };
 
 namespace gorgo {
 
 // Geometry of one evaluation, computed on the host and handed to the launchers.
+enum ReplayPath { PATH_AUTO = 0, PATH_BLOCKS = 1, PATH_SEGMENTS = 2 };
+
 struct Plan {
+    int32_t path = PATH_BLOCKS;      // PATH_BLOCKS: hashed block tables; PATH_SEGMENTS: dense segment rows
+    int64_t nseg = 0;
     int32_t P = 0, R = 0, B = 0;
     int64_t N = 0, C = 0;
     int64_t cap = 0;                 // slots per (replay, replica) table, power of two

@@ -16,27 +16,18 @@
 #include <cstdint>
 #include <string>
 
+#include "device_common.h"
 #include "internal.h"
 
 namespace gorgo {
 
 namespace {
 
-constexpr int64_t STAMP_STRIDE = 65536;   // stamp = request * stride + (stride - 1 - position): root newest
-constexpr int WAVE = 64;
-
 // One cache-table slot.  key 0 = never used (then stamp = -1).  An entry is cached iff stamp >= tau of its
 // replica; entries below tau are evicted garbage whose slots can be taken over by inserts.
 struct Slot {
     uint64_t key;
     int64_t stamp;
-};
-
-// In-flight request record, linked per (replica, service slot) in dispatch order.
-struct Rec {
-    double done;       // time the completion event reaches the proxy
-    int32_t next;      // next request on the same service slot, -1 = none
-    int32_t tokens;    // input tokens counted in the load signal
 };
 
 struct ReplayArgs {
@@ -65,16 +56,6 @@ struct ReplayArgs {
     double* e2e;    // nullable
 };
 
-// All mutable per-replay state in global memory is private to one workgroup; relaxed workgroup-scope
-// atomics plus workgroup barriers between phases are what the memory model asks for.
-template <class T>
-__device__ __forceinline__ T ld(const T* p) {
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-}
-template <class T>
-__device__ __forceinline__ void st(T* p, T v) {
-    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-}
 __device__ __forceinline__ bool cas_stamp(int64_t* p, int64_t expected, int64_t desired) {
     return __hip_atomic_compare_exchange_strong(p, &expected, desired, __ATOMIC_RELAXED, __ATOMIC_RELAXED,
                                                 __HIP_MEMORY_SCOPE_WORKGROUP);
@@ -115,25 +96,6 @@ __device__ __forceinline__ bool insert_new(Slot* tab, uint64_t key, int64_t stam
     }
 }
 
-struct Best {
-    double v;
-    int idx;
-};
-
-// Lowest-index minimum over the wavefront.
-__device__ __forceinline__ Best wave_argmin(double v, int idx) {
-#pragma unroll
-    for (int d = 1; d < WAVE; d <<= 1) {
-        double ov = __shfl_xor(v, d);
-        int oi = __shfl_xor(idx, d);
-        if (ov < v || (ov == v && oi < idx)) {
-            v = ov;
-            idx = oi;
-        }
-    }
-    return Best{v, idx};
-}
-
 __global__ void __launch_bounds__(256) fill_slots(Slot* s, size_t n) {
     size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     const size_t stride = (size_t)gridDim.x * blockDim.x;
@@ -143,35 +105,25 @@ __global__ void __launch_bounds__(256) fill_slots(Slot* s, size_t n) {
     }
 }
 
-__global__ void __launch_bounds__(WAVE) replay_kernel(ReplayArgs a) {
+__global__ void __launch_bounds__(WAVE) replay_blocks_kernel(ReplayArgs a) {
     extern __shared__ __align__(16) unsigned char lds_raw[];
     const int lane = threadIdx.x;
     const int p = blockIdx.x;
-    const int R = a.R, B = a.B, RB = R * B;
+    const int R = a.R, B = a.B;
     const int64_t N = a.N;
     const uint64_t mask = (uint64_t)a.cap - 1;
     const int cap_log2 = a.cap_log2;
 
-    // LDS carve-up (8-byte fields first)
-    double* free_at = reinterpret_cast<double*>(lds_raw);         // [RB] time the service slot becomes free
-    double* head_done = free_at + RB;                             // [RB] completion time of the oldest in-flight
-    int64_t* q = reinterpret_cast<int64_t*>(head_done + RB);      // [R] outstanding tokens (Eq. 2)
-    int64_t* tau = q + R;                                         // [R] eviction threshold
-    int32_t* head = reinterpret_cast<int32_t*>(tau + R);          // [RB]
-    int32_t* tail = head + RB;                                    // [RB]
-    int32_t* live = tail + RB;                                    // [R] cached blocks
+    Queues Q;
+    Q.carve(lds_raw, R, B);
+    int64_t* tau = reinterpret_cast<int64_t*>(lds_raw + Queues::bytes(R, B));   // [R] eviction threshold
+    int32_t* live = reinterpret_cast<int32_t*>(tau + R);          // [R] cached blocks
     int32_t* used = live + R;                                     // [R] slots ever used since the last rebuild
     int32_t* cur_r = used + R;                                    // [R] eviction cursor: request ...
     int32_t* cur_k = cur_r + R;                                   // [R] ... and position (blocks >= cur_k are gone)
 
-    for (int s = lane; s < RB; s += WAVE) {
-        free_at[s] = 0.0;
-        head_done[s] = INFINITY;
-        head[s] = -1;
-        tail[s] = -1;
-    }
+    Q.init(lane);
     for (int i = lane; i < R; i += WAVE) {
-        q[i] = 0;
         tau[i] = 0;
         live[i] = 0;
         used[i] = 0;
@@ -199,23 +151,7 @@ __global__ void __launch_bounds__(WAVE) replay_kernel(ReplayArgs a) {
         const int64_t O = a.out_len[r];
         const double t = (double)a.ts[r] * sc;     // time scale: gaps scale linearly
 
-        // ---- retire: drop requests whose completion event has reached the proxy (done <= t)
-        for (int s = lane; s < RB; s += WAVE) {
-            while (head_done[s] <= t) {
-                const int h = head[s];
-                const int32_t nx = ld(&rec[h].next);
-                const int32_t tok = ld(&rec[h].tokens);
-                atomicAdd(reinterpret_cast<unsigned long long*>(&q[s / B]), (unsigned long long)(-(int64_t)tok));
-                head[s] = nx;
-                if (nx < 0) {
-                    head_done[s] = INFINITY;
-                    tail[s] = -1;
-                } else {
-                    head_done[s] = ld(&rec[nx].done);
-                }
-            }
-        }
-        __syncthreads();
+        Q.retire(t, rec, lane);
 
         // ---- prefix match: first block on every replica, then the whole list on replicas that hold it
         int my_m = 0;
@@ -254,12 +190,7 @@ __global__ void __launch_bounds__(WAVE) replay_kernel(ReplayArgs a) {
             int64_t hit_tok = (int64_t)a.block_tokens * my_m;
             if (hit_tok > L) hit_tok = L;
             my_u = L - hit_tok;
-            const double pf = a.a_pf * (double)my_u;
-            const double qd = a.a_pf * (double)q[lane];
-            const double s_rtt = w_rtt * my_rtt;
-            const double s_pf = w_prefill * pf;
-            const double s_q = w_queue * qd;
-            my_score = (s_rtt + s_pf) + s_q;
+            my_score = eq3_score(w_rtt, w_prefill, w_queue, my_rtt, a.a_pf, my_u, Q.q[lane]);
         }
         const int best = wave_argmin(my_score, lane < R ? lane : 255).idx;
         const int64_t u_best = __shfl(my_u, best);
@@ -338,20 +269,8 @@ __global__ void __launch_bounds__(WAVE) replay_kernel(ReplayArgs a) {
             int cr = cur_r[best], ck = cur_k[best];
             while (E > 0) {
                 if (ck == 0) {
-                    // next request routed to this replica
-                    int64_t x = (int64_t)cr + 1;
-                    for (;;) {
-                        const int64_t y = x + lane;
-                        const bool hitb = y < r && ld(&route[y]) == (uint8_t)best;
-                        const uint64_t mk = __ballot(hitb);
-                        if (mk) {
-                            x += __ffsll((unsigned long long)mk) - 1;
-                            break;
-                        }
-                        x += WAVE;
-                        if (x >= r) break;      // cannot happen while E > 0; bounds the loop regardless
-                    }
-                    if (x >= r) break;
+                    const int64_t x = next_routed(route, cr, r, best, lane);
+                    if (x >= r) break;          // cannot happen while E > 0; bounds the loop regardless
                     cr = (int)x;
                     ck = (int)(a.blk_off[x + 1] - a.blk_off[x]);
                     continue;
@@ -384,36 +303,197 @@ __global__ void __launch_bounds__(WAVE) replay_kernel(ReplayArgs a) {
             }
         }
 
-        // ---- service on the chosen replica: earliest-free slot, linear prefill + decode (Eq. 1)
+        // ---- service on the chosen replica, outputs
+        double ttft, e2e;
+        Q.serve(r, best, t, rtt_best, u_best, L, O, a.a_pf, a.a_dec, rec, lane, &ttft, &e2e);
+        if (lane == 0) {
+            if (a.hit) a.hit[(size_t)p * N + r] = (uint16_t)m_best;
+            if (a.ttft) a.ttft[(size_t)p * N + r] = ttft;
+            if (a.e2e) a.e2e[(size_t)p * N + r] = e2e;
+        }
+        __syncthreads();
+    }
+}
+
+// ---- segment formulation (chain-consistent traces) -------------------------------------------------------
+// On a chain-consistent trace every request is a root-to-node path of the key forest and a whole number of
+// segments.  With the root-newest stamp order a replica's cache is always closed under taking prefixes,
+// every block of a segment carries the same last-touching request, and a block is cached iff its
+// (last request, position) is not below the replica's eviction cursor.  So the cache state of a replay is
+// one 32-bit "last request that touched it" per (segment, replica), stored as dense rows of R entries
+// addressed by segment id: no hashing, no probing, and eviction only moves the cursor, it writes nothing.
+struct SegArgs {
+    const int64_t* ts;
+    const int32_t* in_len;
+    const int32_t* out_len;
+    const int64_t* seg_off;
+    const SegRef* seg;
+    int64_t N;
+    int32_t R, B;
+    int64_t C;
+    int64_t nseg;
+    int32_t block_tokens;
+    double a_pf, a_dec;
+    const double* rtt;
+    const double* params;
+    const double* scale;
+    int32_t* last;   // [P][nseg][R], -1 = never touched
+    Rec* rec;        // [P][N]
+    uint8_t* route;  // [P][N]
+    uint16_t* hit;
+    double* ttft;
+    double* e2e;
+};
+
+__global__ void __launch_bounds__(256) fill_i32(int32_t* x, size_t n, int32_t v) {
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (; i < n; i += stride) x[i] = v;
+}
+
+__global__ void __launch_bounds__(WAVE) replay_segments_kernel(SegArgs a) {
+    extern __shared__ __align__(16) unsigned char lds_raw[];
+    const int lane = threadIdx.x;
+    const int p = blockIdx.x;
+    const int R = a.R, B = a.B;
+    const int64_t N = a.N;
+
+    Queues Q;
+    Q.carve(lds_raw, R, B);
+    int32_t* live = reinterpret_cast<int32_t*>(lds_raw + Queues::bytes(R, B));   // [R] cached blocks
+    Q.init(lane);
+    for (int i = lane; i < R; i += WAVE) live[i] = 0;
+    __syncthreads();
+
+    const double w_rtt = a.params[3 * (size_t)p + 0];
+    const double w_prefill = a.params[3 * (size_t)p + 1];
+    const double w_queue = a.params[3 * (size_t)p + 2];
+    const double sc = a.scale[p];
+    const double my_rtt = lane < R ? a.rtt[lane] : 0.0;
+    // eviction cursor of replica `lane`: blocks touched last by a request before my_cur_r, or by my_cur_r at
+    // positions >= my_cur_k, are evicted
+    int my_cur_r = -1, my_cur_k = 0;
+
+    int32_t* const last = a.last + (size_t)p * a.nseg * R;
+    Rec* const rec = a.rec + (size_t)p * N;
+    uint8_t* const route = a.route + (size_t)p * N;
+
+    for (int64_t r = 0; r < N; ++r) {
+        const int64_t j0 = a.seg_off[r], j1 = a.seg_off[r + 1];
+        const int n = j1 > j0 ? a.seg[j1 - 1].end : 0;
+        const int64_t L = a.in_len[r];
+        const int64_t O = a.out_len[r];
+        const double t = (double)a.ts[r] * sc;     // time scale: gaps scale linearly
+
+        Q.retire(t, rec, lane);
+
+        // ---- prefix match: lane = replica; walk the request's segments while some replica still matches
+        int my_m = 0;
         {
-            const Best slot = wave_argmin(lane < B ? free_at[best * B + lane] : INFINITY, lane < B ? lane : 255);
-            const double half = 0.5 * rtt_best;
-            const double arrive = t + half;
-            const double start = arrive > slot.v ? arrive : slot.v;
-            const double pf = a.a_pf * (double)u_best;
-            const double first_tok = start + pf;
-            const double dec = a.a_dec * (double)O;
-            const double end = first_tok + dec;
-            const double done = end + half;
-            if (lane == 0) {
-                const int s = best * B + slot.idx;
-                free_at[s] = end;
-                st(&rec[r].done, done);
-                st(&rec[r].next, (int32_t)-1);
-                st(&rec[r].tokens, (int32_t)L);
-                const int tl = tail[s];
-                if (tl >= 0) {
-                    st(&rec[tl].next, (int32_t)r);
-                } else {
-                    head[s] = (int32_t)r;
-                    head_done[s] = done;
+            bool open = lane < R;
+            int pos = 0;
+            for (int64_t j = j0; j < j1; ++j) {
+                const SegRef sr = a.seg[j];
+                const int len = sr.end - pos;
+                if (open) {
+                    const int32_t rl = ld(&last[(size_t)sr.id * R + lane]);
+                    int cnt = 0;
+                    if (rl > my_cur_r) {
+                        cnt = len;
+                    } else if (rl == my_cur_r && rl >= 0) {
+                        cnt = my_cur_k - pos;
+                        cnt = cnt < 0 ? 0 : (cnt > len ? len : cnt);
+                    }
+                    my_m += cnt;
+                    open = cnt == len;
                 }
-                tail[s] = (int32_t)r;
-                q[best] += L;
-                if (a.hit) a.hit[(size_t)p * N + r] = (uint16_t)m_best;
-                if (a.ttft) a.ttft[(size_t)p * N + r] = (first_tok + half) - t;
-                if (a.e2e) a.e2e[(size_t)p * N + r] = done - t;
+                pos = sr.end;
+                if (__ballot(open) == 0) break;
             }
+        }
+
+        // ---- score (Eq. 3) and lowest-index minimum
+        int64_t my_u = 0;
+        double my_score = INFINITY;
+        if (lane < R) {
+            int64_t hit_tok = (int64_t)a.block_tokens * my_m;
+            if (hit_tok > L) hit_tok = L;
+            my_u = L - hit_tok;
+            my_score = eq3_score(w_rtt, w_prefill, w_queue, my_rtt, a.a_pf, my_u, Q.q[lane]);
+        }
+        const int best = wave_argmin(my_score, lane < R ? lane : 255).idx;
+        const int64_t u_best = __shfl(my_u, best);
+        const int m_best = __shfl(my_m, best);
+        const double rtt_best = __shfl(my_rtt, best);
+        if (lane == 0) st(&route[r], (uint8_t)best);
+
+        // ---- cache update: every segment of the request is now last touched by r on the chosen replica
+        for (int64_t base = j0; base < j1; base += WAVE) {
+            const int64_t j = base + lane;
+            if (j < j1) st(&last[(size_t)a.seg[j].id * R + best], (int32_t)r);
+        }
+        const int live_now = live[best] + (n - m_best);
+        __syncthreads();
+
+        // ---- eviction: move the cursor of the chosen replica forward until the cache fits.  The touch log
+        // of a replica is the route array; a logged request's segment still counts iff it was not touched
+        // since (its row still holds that request).
+        int E = a.C > 0 && live_now > a.C ? (int)(live_now - a.C) : 0;
+        const bool evicting = E > 0;
+        if (evicting) {
+            int cr = __shfl(my_cur_r, best), ck = __shfl(my_cur_k, best);
+            while (E > 0) {
+                if (ck == 0) {
+                    const int64_t x = next_routed(route, cr, r, best, lane);
+                    if (x >= r) break;          // cannot happen while E > 0; bounds the loop regardless
+                    cr = (int)x;
+                    const int64_t x0 = a.seg_off[x], x1 = a.seg_off[x + 1];
+                    ck = x1 > x0 ? a.seg[x1 - 1].end : 0;
+                    continue;
+                }
+                const int64_t x0 = a.seg_off[cr], x1 = a.seg_off[cr + 1];
+                for (int64_t hi = x1; hi > x0 && E > 0; hi -= WAVE) {
+                    const int64_t j = hi - 1 - lane;          // lane order = eviction order (deepest first)
+                    int pos = 0, top = 0, cnt = 0;
+                    if (j >= x0) {
+                        const SegRef sr = a.seg[j];
+                        pos = j > x0 ? a.seg[j - 1].end : 0;
+                        top = sr.end < ck ? sr.end : ck;
+                        if (top > pos && ld(&last[(size_t)sr.id * R + best]) == cr) cnt = top - pos;
+                    }
+                    int incl = cnt;
+#pragma unroll
+                    for (int d = 1; d < WAVE; d <<= 1) {
+                        const int o = __shfl_up(incl, d);
+                        if (lane >= d) incl += o;
+                    }
+                    const int total = __shfl(incl, WAVE - 1);
+                    if (total < E) {
+                        E -= total;
+                        const int64_t lowest = hi - WAVE > x0 ? hi - WAVE : x0;      // shallowest segment seen
+                        ck = __shfl(pos, (int)(hi - 1 - lowest));
+                    } else {
+                        const uint64_t mk = __ballot(incl >= E);
+                        const int l = __ffsll((unsigned long long)mk) - 1;
+                        ck = __shfl(top - (E - (incl - cnt)), l);
+                        E = 0;
+                    }
+                }
+            }
+            if (lane == best) {
+                my_cur_r = cr;
+                my_cur_k = ck;
+            }
+        }
+        if (lane == 0) live[best] = evicting ? (int32_t)a.C + E : live_now;
+
+        // ---- service on the chosen replica, outputs
+        double ttft, e2e;
+        Q.serve(r, best, t, rtt_best, u_best, L, O, a.a_pf, a.a_dec, rec, lane, &ttft, &e2e);
+        if (lane == 0) {
+            if (a.hit) a.hit[(size_t)p * N + r] = (uint16_t)m_best;
+            if (a.ttft) a.ttft[(size_t)p * N + r] = ttft;
+            if (a.e2e) a.e2e[(size_t)p * N + r] = e2e;
         }
         __syncthreads();
     }
@@ -528,7 +608,10 @@ int upload_trace(const gorgo_trace* tc) {
     const size_t o_ol = o_il + up(N * 4);
     const size_t o_key = o_ol + up(N * 4);
     const size_t o_first = o_key + up(T * 4);
-    const size_t total = o_first + up(T) + 256;
+    const size_t n_sr = t->seg.size();
+    const size_t o_soff = o_first + up(T);
+    const size_t o_seg = o_soff + up(t->seg_off.size() * 8);
+    const size_t total = o_seg + up(n_sr * sizeof(SegRef)) + 256;
     char* base = nullptr;
     e = hipMalloc(reinterpret_cast<void**>(&base), total);
     if (e != hipSuccess) return fail(GORGO_ERR_OOM, std::string("hipMalloc(trace): ") + hipGetErrorString(e));
@@ -537,7 +620,9 @@ int upload_trace(const gorgo_trace* tc) {
     };
     if ((e = put(o_ts, t->ts.data(), N * 8)) != hipSuccess || (e = put(o_off, t->blk_off.data(), (N + 1) * 8)) != hipSuccess ||
         (e = put(o_il, t->in_len.data(), N * 4)) != hipSuccess || (e = put(o_ol, t->out_len.data(), N * 4)) != hipSuccess ||
-        (e = put(o_key, t->key.data(), T * 4)) != hipSuccess || (e = put(o_first, t->first.data(), T)) != hipSuccess) {
+        (e = put(o_key, t->key.data(), T * 4)) != hipSuccess || (e = put(o_first, t->first.data(), T)) != hipSuccess ||
+        (e = put(o_soff, t->seg_off.data(), t->seg_off.size() * 8)) != hipSuccess ||
+        (e = put(o_seg, t->seg.data(), n_sr * sizeof(SegRef))) != hipSuccess) {
         (void)hipFree(base);
         return hip_fail(e, "hipMemcpy(trace)");
     }
@@ -549,6 +634,8 @@ int upload_trace(const gorgo_trace* tc) {
     t->dev.out_len = reinterpret_cast<const int32_t*>(base + o_ol);
     t->dev.key = reinterpret_cast<const uint32_t*>(base + o_key);
     t->dev.first = reinterpret_cast<const uint8_t*>(base + o_first);
+    t->dev.seg_off = reinterpret_cast<const int64_t*>(base + o_soff);
+    t->dev.seg = reinterpret_cast<const SegRef*>(base + o_seg);
     return GORGO_OK;
 }
 
@@ -569,57 +656,91 @@ int copy_small_to_host_sync(void* dst, const void* src, size_t bytes, void* stre
     return e == hipSuccess ? GORGO_OK : hip_fail(e, "hipStreamSynchronize");
 }
 
-size_t replay_lds_bytes(int R, int B) {
-    const size_t RB = (size_t)R * B;
-    return RB * 8 * 2 + (size_t)R * 8 * 2 + RB * 4 * 2 + (size_t)R * 4 * 4;
-}
-
 int launch_replay(const gorgo_trace* t, const Plan& pl, const double* d_rtt, const double* d_params,
                   const double* d_scale, uint8_t* route, uint16_t* hit, double* ttft, double* e2e,
                   void* workspace, void* stream) {
     hipStream_t s = static_cast<hipStream_t>(stream);
     char* ws = static_cast<char*>(workspace);
-    ReplayArgs a;
-    a.ts = t->dev.ts;
-    a.in_len = t->dev.in_len;
-    a.out_len = t->dev.out_len;
-    a.blk_off = t->dev.blk_off;
-    a.key = t->dev.key;
-    a.first = t->dev.first;
-    a.N = pl.N;
-    a.R = pl.R;
-    a.B = pl.B;
-    a.C = pl.C;
-    a.cap = pl.cap;
-    a.cap_log2 = 0;
-    while ((1ll << a.cap_log2) < pl.cap) ++a.cap_log2;
-    a.block_tokens = pl.block_tokens;
-    a.a_pf = pl.a_pf;
-    a.a_dec = pl.a_dec;
-    a.rtt = d_rtt;
-    a.params = d_params;
-    a.scale = d_scale;
-    a.tables = reinterpret_cast<Slot*>(ws + pl.off_tables);
-    a.spare = reinterpret_cast<Slot*>(ws + pl.off_spare);
-    a.rec = reinterpret_cast<Rec*>(ws + pl.off_rec);
-    a.route = route;
-    a.hit = hit;
-    a.ttft = ttft;
-    a.e2e = e2e;
     g_marks.valid = false;
     marks_ready();
     mark(0, s);
-    const size_t nslots = (size_t)pl.P * pl.R * pl.cap;
-    size_t blocks = (nslots + 255) / 256;
-    if (blocks > 65536) blocks = 65536;
-    hipLaunchKernelGGL(fill_slots, dim3((unsigned)blocks), dim3(256), 0, s, a.tables, nslots);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return hip_fail(e, "launch fill_slots");
-    mark(1, s);
-    if (pl.N > 0) {
-        hipLaunchKernelGGL(replay_kernel, dim3((unsigned)pl.P), dim3(WAVE), replay_lds_bytes(pl.R, pl.B), s, a);
-        e = hipGetLastError();
-        if (e != hipSuccess) return hip_fail(e, "launch replay_kernel");
+    hipError_t e;
+    if (pl.path == PATH_SEGMENTS) {
+        SegArgs a;
+        a.ts = t->dev.ts;
+        a.in_len = t->dev.in_len;
+        a.out_len = t->dev.out_len;
+        a.seg_off = t->dev.seg_off;
+        a.seg = t->dev.seg;
+        a.N = pl.N;
+        a.R = pl.R;
+        a.B = pl.B;
+        a.C = pl.C;
+        a.nseg = pl.nseg;
+        a.block_tokens = pl.block_tokens;
+        a.a_pf = pl.a_pf;
+        a.a_dec = pl.a_dec;
+        a.rtt = d_rtt;
+        a.params = d_params;
+        a.scale = d_scale;
+        a.last = reinterpret_cast<int32_t*>(ws + pl.off_tables);
+        a.rec = reinterpret_cast<Rec*>(ws + pl.off_rec);
+        a.route = route;
+        a.hit = hit;
+        a.ttft = ttft;
+        a.e2e = e2e;
+        const size_t cells = (size_t)pl.P * (size_t)pl.nseg * pl.R;
+        if (cells) {
+            size_t blocks = (cells + 255) / 256;
+            if (blocks > 65536) blocks = 65536;
+            hipLaunchKernelGGL(fill_i32, dim3((unsigned)blocks), dim3(256), 0, s, a.last, cells, (int32_t)-1);
+            if ((e = hipGetLastError()) != hipSuccess) return hip_fail(e, "launch fill_i32");
+        }
+        mark(1, s);
+        if (pl.N > 0) {
+            const size_t lds = Queues::bytes(pl.R, pl.B) + (size_t)pl.R * 4;
+            hipLaunchKernelGGL(replay_segments_kernel, dim3((unsigned)pl.P), dim3(WAVE), lds, s, a);
+            if ((e = hipGetLastError()) != hipSuccess) return hip_fail(e, "launch replay_segments_kernel");
+        }
+    } else {
+        ReplayArgs a;
+        a.ts = t->dev.ts;
+        a.in_len = t->dev.in_len;
+        a.out_len = t->dev.out_len;
+        a.blk_off = t->dev.blk_off;
+        a.key = t->dev.key;
+        a.first = t->dev.first;
+        a.N = pl.N;
+        a.R = pl.R;
+        a.B = pl.B;
+        a.C = pl.C;
+        a.cap = pl.cap;
+        a.cap_log2 = 0;
+        while ((1ll << a.cap_log2) < pl.cap) ++a.cap_log2;
+        a.block_tokens = pl.block_tokens;
+        a.a_pf = pl.a_pf;
+        a.a_dec = pl.a_dec;
+        a.rtt = d_rtt;
+        a.params = d_params;
+        a.scale = d_scale;
+        a.tables = reinterpret_cast<Slot*>(ws + pl.off_tables);
+        a.spare = reinterpret_cast<Slot*>(ws + pl.off_spare);
+        a.rec = reinterpret_cast<Rec*>(ws + pl.off_rec);
+        a.route = route;
+        a.hit = hit;
+        a.ttft = ttft;
+        a.e2e = e2e;
+        const size_t nslots = (size_t)pl.P * pl.R * pl.cap;
+        size_t blocks = (nslots + 255) / 256;
+        if (blocks > 65536) blocks = 65536;
+        hipLaunchKernelGGL(fill_slots, dim3((unsigned)blocks), dim3(256), 0, s, a.tables, nslots);
+        if ((e = hipGetLastError()) != hipSuccess) return hip_fail(e, "launch fill_slots");
+        mark(1, s);
+        if (pl.N > 0) {
+            const size_t lds = Queues::bytes(pl.R, pl.B) + (size_t)pl.R * (8 + 4 * 4);
+            hipLaunchKernelGGL(replay_blocks_kernel, dim3((unsigned)pl.P), dim3(WAVE), lds, s, a);
+            if ((e = hipGetLastError()) != hipSuccess) return hip_fail(e, "launch replay_blocks_kernel");
+        }
     }
     mark(2, s);
     mark(3, s);

@@ -89,6 +89,10 @@ int preprocess(gorgo_trace* t, const int64_t* hash_ids) {
     // per-request duplicate detection: last request index in which a key was seen
     std::vector<int64_t> seen_in;
     seen_in.push_back(-1);
+    std::vector<uint32_t> nchild;    // distinct successors of a key
+    std::vector<uint8_t> ends;       // some request ends at this key
+    nchild.push_back(0);
+    ends.push_back(0);
     bool consistent = true;
     int32_t max_blocks = 0, max_distinct = 0;
     for (int64_t r = 0; r < N; ++r) {
@@ -105,6 +109,9 @@ int preprocess(gorgo_trace* t, const int64_t* hash_ids) {
                 parent.push_back(prev);
                 pos.push_back((uint32_t)k);
                 seen_in.push_back(-1);
+                nchild.push_back(0);
+                ends.push_back(0);
+                if (prev) ++nchild[prev];
             } else if (parent[key] != prev || pos[key] != (uint32_t)k) {
                 consistent = false;
             }
@@ -116,12 +123,42 @@ int preprocess(gorgo_trace* t, const int64_t* hash_ids) {
             t->first[(size_t)(b + k)] = dup ? 0 : 1;
             prev = key;
         }
+        if (prev) ends[prev] = 1;
         if (distinct > max_distinct) max_distinct = distinct;
     }
     t->max_blocks = max_blocks;
     t->max_distinct = max_distinct;
     t->unique_ids = (int64_t)map.size();
     t->chain_consistent = consistent;
+    t->seg_off.clear();
+    t->seg.clear();
+    t->n_segments = 0;
+    if (!consistent) return GORGO_OK;
+
+    // Chain-consistent traces: the keys form a forest and every request is a root-to-node path.  Cut the
+    // forest into segments -- maximal runs of keys with a single successor and no request ending inside --
+    // so that every request is a whole number of segments and all blocks of a segment are always touched
+    // together.  Keys are numbered in order of first appearance, so a predecessor precedes its successors.
+    const size_t U = map.size();
+    std::vector<int32_t> seg_of(U + 1, 0);
+    int64_t nseg = 0;
+    for (size_t k = 1; k <= U; ++k) {
+        const uint32_t par = parent[k];
+        if (par == 0 || nchild[par] > 1 || ends[par]) seg_of[k] = (int32_t)(nseg++);
+        else seg_of[k] = seg_of[par];
+        if (nseg >= 0x7FFFFFF0) return fail(GORGO_ERR_INVALID_ARG, "too many segments");
+    }
+    t->n_segments = nseg;
+    t->seg_off.resize((size_t)N + 1);
+    t->seg_off[0] = 0;
+    for (int64_t r = 0; r < N; ++r) {
+        const int64_t b = t->blk_off[r], e = t->blk_off[r + 1];
+        for (int64_t k = b; k < e; ++k) {
+            const int32_t sg = seg_of[t->key[(size_t)k]];
+            if (k + 1 == e || seg_of[t->key[(size_t)k + 1]] != sg) t->seg.push_back(gorgo::SegRef{sg, (int32_t)(k + 1 - b)});
+        }
+        t->seg_off[(size_t)r + 1] = (int64_t)t->seg.size();
+    }
     return GORGO_OK;
 }
 

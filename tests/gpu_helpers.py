@@ -12,11 +12,18 @@ def load(tr):
     return g.Trace.from_arrays(tr.ts_ms, tr.in_len, tr.out_len, tr.blk_off, tr.hash_ids)
 
 
-def gpu_eval(tr, model: g.Model, rtt, params, scale, handle=None):
+PATH_NAMES = {0: "auto", 1: "block-tables", 2: "segment-rows"}
+
+
+def gpu_eval(tr, model: g.Model, rtt, params, scale, handle=None, path=0):
     import torch
     h = handle if handle is not None else load(tr)
-    res = g.eval_population(h, model, rtt, params, scale)
-    torch.cuda.synchronize()
+    g.set_replay_path(path)
+    try:
+        res = g.eval_population(h, model, rtt, params, scale)
+        torch.cuda.synchronize()
+    finally:
+        g.set_replay_path(0)
     out = dict(route=res.route.cpu().numpy(), hit=res.hit_blocks.cpu().numpy(), ttft=res.ttft_ms.cpu().numpy(),
                e2e=res.e2e_ms.cpu().numpy(), p95_ttft=res.p95_ttft_ms.cpu().numpy(),
                p95_e2e=res.p95_e2e_ms.cpu().numpy())
@@ -41,12 +48,20 @@ def assert_replay_equal(got, p, ref, label=""):
         assert abs(got["p95_e2e"][p] - ref.p95_e2e_ms) <= RTOL * abs(ref.p95_e2e_ms), f"{label} p95 e2e replay {p}"
 
 
-def check_population(tr, model, rtt, params, scale, replays=None, label=""):
+def check_population(tr, model, rtt, params, scale, replays=None, label="", paths=None):
+    """Every formulation the trace admits (hashed block tables always, segment rows when the trace is
+    chain-consistent) against the oracle.  Returns the outputs of the last formulation run."""
     params = np.asarray(params, np.float64)
     P = params.shape[0]
     scale = np.broadcast_to(np.asarray(scale, np.float64), (P,))
-    got = gpu_eval(tr, model, rtt, params, scale)
-    for p in (range(P) if replays is None else replays):
-        ref = oracle_eval(tr, model, rtt, params[p], float(scale[p]))
-        assert_replay_equal(got, p, ref, label)
+    h = load(tr)
+    if paths is None:
+        paths = [1, 2] if h.info()["chain_consistent"] else [1]
+    which = list(range(P) if replays is None else replays)
+    refs = {p: oracle_eval(tr, model, rtt, params[p], float(scale[p])) for p in which}
+    got = None
+    for path in paths:
+        got = gpu_eval(tr, model, rtt, params, scale, handle=h, path=path)
+        for p in which:
+            assert_replay_equal(got, p, refs[p], f"{label} [{PATH_NAMES[path]}]")
     return got

@@ -110,13 +110,75 @@ def test_max_blocks_request_and_ragged_tails():
                      label="ragged")
 
 
-def test_same_launch_twice_is_identical():
+@pytest.mark.parametrize("path", [1, 2])
+def test_same_launch_twice_is_identical(path):
     wl = tg.config(2, 3000)
     h = load(wl.trace)
-    a = gpu_eval(wl.trace, _model(wl, cache_blocks=1000), wl.rtt_ms, wl.params[:4], 1.0, handle=h)
-    b = gpu_eval(wl.trace, _model(wl, cache_blocks=1000), wl.rtt_ms, wl.params[:4], 1.0, handle=h)
+    a = gpu_eval(wl.trace, _model(wl, cache_blocks=1000), wl.rtt_ms, wl.params[:4], 1.0, handle=h, path=path)
+    b = gpu_eval(wl.trace, _model(wl, cache_blocks=1000), wl.rtt_ms, wl.params[:4], 1.0, handle=h, path=path)
     for k in a:
         assert a[k].tobytes() == b[k].tobytes()
+
+
+def test_formulations_agree_bit_for_bit():
+    wl = tg.config(3, 4000)
+    h = load(wl.trace)
+    m = _model(wl, cache_blocks=900)
+    a = gpu_eval(wl.trace, m, wl.rtt_ms, wl.params[:8], 1.0, handle=h, path=1)
+    b = gpu_eval(wl.trace, m, wl.rtt_ms, wl.params[:8], 1.0, handle=h, path=2)
+    for k in a:
+        assert a[k].tobytes() == b[k].tobytes(), k
+
+
+def test_segment_rows_rejected_for_inconsistent_trace():
+    tr = tg.random_small(5, 50, 2, consistent=False)
+    with pytest.raises(g.GorgoError) as e:
+        gpu_eval(tr, g.Model(2, 2, 0, 0.05, 20.0), [1.0, 2.0], [[1, 1, 1]], 1.0, path=2)
+    assert e.value.code == -1
+
+
+def test_shared_prefix_forest():
+    """Chain-consistent trace with branching: a common root run shared by every request (a system prompt),
+    a few second-level branches, then per-conversation tails that grow turn by turn; bounded caches."""
+    rng = np.random.default_rng(17)
+    root = list(range(1, 8))
+    branches = [list(range(100 + 10 * b, 100 + 10 * b + int(rng.integers(1, 9)))) for b in range(4)]
+    convs, lists, nxt = [], [], 1000
+    for _ in range(900):
+        if not convs or rng.random() < 0.3:
+            convs.append(root + branches[int(rng.integers(0, 4))])
+        c = int(rng.integers(0, len(convs)))
+        if rng.random() < 0.15:
+            lists.append(list(convs[c][:int(rng.integers(1, len(convs[c]) + 1))]))   # a request that ends mid-way
+            continue
+        add = int(rng.integers(0, 5))
+        convs[c] = convs[c] + list(range(nxt, nxt + add))
+        nxt += add
+        lists.append(list(convs[c]))
+    nblk = np.array([len(x) for x in lists], np.int64)
+    tr = tg.Trace(np.cumsum(rng.integers(0, 50, len(lists))).astype(np.int64), (nblk * 512).astype(np.int32),
+                  rng.integers(1, 30, len(lists)).astype(np.int32), np.concatenate([[0], np.cumsum(nblk)]),
+                  np.array([x for l in lists for x in l], np.int64))
+    assert load(tr).info()["chain_consistent"]
+    par = rng.uniform(0, 2, (6, 3))
+    par[0] = [0.0, 1.0, 0.0]
+    check_population(tr, g.Model(4, 2, 120, 0.05, 20.0), [10.0, 14.0, 30.0, 11.0], par, 1.0, label="forest")
+    check_population(tr, g.Model(3, 2, 0, 0.05, 20.0), [10.0, 14.0, 30.0], par[:3], 1.0, label="forest-unbounded")
+
+
+def test_many_segments_per_request():
+    # one conversation growing by one block per turn: turn t is t single-block segments (> one 64-lane tile)
+    lens = list(range(1, 150)) + [10, 149, 3]
+    ids, off = [], [0]
+    for n in lens:
+        ids += list(range(1, n + 1))
+        off.append(len(ids))
+    N = len(lens)
+    rng = np.random.default_rng(4)
+    tr = tg.Trace(np.arange(N, dtype=np.int64) * 300, (np.array(lens) * 512).astype(np.int32),
+                  rng.integers(1, 20, N).astype(np.int32), np.array(off, np.int64), np.array(ids, np.int64))
+    check_population(tr, g.Model(2, 2, 160, 0.05, 20.0), [10.0, 11.0], [[1, 1, 0.0], [1, 1, 1], [0, 0, 1]], 1.0,
+                     label="many-segments")
 
 
 def test_p95_only_outputs_and_percentile_selection():
