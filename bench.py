@@ -39,6 +39,21 @@ def algorithmic_bytes_per_routing(R, n_mean, hit_mean, outputs_bytes):
     return 16 * R + 16 * (h + 1) + (16 * n + 8 * h + 16 * (n - h)) + 16 * n + 32 + outputs_bytes
 
 
+def algorithmic_bytes_per_routing_segments(R, segs_mean, outputs_bytes):
+    """Bytes one routing has to move in the segment-row formulation (one 4-byte "last request" cell per
+    (segment, replica), rows of R cells addressed by segment id), private to one replay:
+      first segment's row, read by every replica's lane        4 * R
+      deeper segments on the replica(s) that hold the prefix   4 * (s - 1)
+      update of the chosen replica's cells                     4 * s
+      eviction walk: every logged request's cells re-read once 4 * s, plus the scan of the route log to
+      the next request of the same replica                     R
+      in-flight record push + pop                              16 + 16
+      per-request outputs                                      outputs_bytes
+    The trace itself (28 B + 8 B per segment per request) is shared by all replays and is not counted."""
+    s = segs_mean
+    return 4 * R + 4 * (s - 1) + 4 * s + 4 * s + R + 32 + outputs_bytes
+
+
 def cpu_baseline(wl, params, n_req, threads):
     """The oracle as it stands, one replay per thread, on the first n_req requests of the workload."""
     from concurrent.futures import ThreadPoolExecutor
@@ -67,6 +82,7 @@ def main():
     ap.add_argument("--population", type=int, default=None, help="override P (experiments only)")
     ap.add_argument("--cpu-sample-requests", type=int, default=600000)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--path", type=int, default=0, help="0 auto, 1 hashed block tables, 2 segment rows (experiments only)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build evaluates on ONE GPU (replays are independent and would shard by candidate; "
@@ -78,6 +94,7 @@ def main():
 
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
+    g.set_replay_path(args.path)
     t_setup = time.perf_counter()
     wl = tg.config(args.config, args.requests)
     es_cfg = wl.es if wl.es else dict(tg.ES_DEFAULTS, P=wl.P, seed=tg.MASTER_SEED + args.config)
@@ -121,7 +138,14 @@ def main():
     hit_mean = float(res.hit_blocks.to(torch.float64).mean().item())
     del res
     n_mean = float(np.diff(wl.trace.blk_off).mean())
-    bpr = algorithmic_bytes_per_routing(wl.R, n_mean, hit_mean, outputs_bytes=9)   # route u8 + ttft f64
+    rp = tr.replay_path()
+    segs_mean = rp["segment_refs"] / max(N, 1)
+    if rp["path"] == 2:
+        bpr = algorithmic_bytes_per_routing_segments(wl.R, segs_mean, outputs_bytes=9)   # route u8 + ttft f64
+        kernel = "replay_segments_kernel"
+    else:
+        bpr = algorithmic_bytes_per_routing(wl.R, n_mean, hit_mean, outputs_bytes=9)
+        kernel = "replay_blocks_kernel"
     k_ms = float(np.mean(kernel_ms))
     achieved = bpr * P * N / (k_ms * 1e-3) / 1e9
 
@@ -133,7 +157,7 @@ def main():
                                f"one ES generation per step (eval + p95 TTFT fitness + mean update)",
                    "es_generation_wall_s": wall / args.steps},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None, "kernel": "replay_kernel",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None, "kernel": kernel, "mean_segments": segs_mean,
                      "kernel_ms": k_ms, "bytes_per_routing": bpr, "mean_blocks": n_mean, "mean_hit_blocks": hit_mean,
                      "fill_ms": float(np.mean(fill_ms)), "select_ms": float(np.mean(select_ms))},
     }

@@ -183,6 +183,11 @@ int gorgo_last_eval_kernel_ms(double* fill_ms, double* replay_ms, double* select
  * 16 segments.  gorgo_workspace_bytes reflects the choice in force when it is called. */
 int gorgo_set_replay_path(int32_t mode);
 
+/* Formulation that an evaluation of this trace would use now (1 or 2, see gorgo_set_replay_path), the number
+ * of segments of the trace and the total number of (request, segment) references; the last two are 0 for a
+ * trace that is not chain-consistent.  Each out pointer may be NULL. */
+int gorgo_query_replay_path(const gorgo_trace* t, int32_t* path, int64_t* n_segments, int64_t* segment_refs);
+
 /* Tuning knob for tests and experiments: the open-addressed cache tables get at least
  * ceil(factor_percent/100 * (cache_blocks + max blocks of a request)) slots, rounded up to a power of two
  * (default 200, minimum 110).  Results never depend on it. */

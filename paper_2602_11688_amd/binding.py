@@ -69,11 +69,12 @@ def lib():
         L.gorgo_es_step.argtypes = [vp, C.POINTER(_Model), vp, dbl, i32, C.POINTER(EsState), vp, vp, vp, C.c_size_t, vp]
         L.gorgo_set_table_factor_percent.argtypes = [i32]
         L.gorgo_set_replay_path.argtypes = [i32]
+        L.gorgo_query_replay_path.argtypes = [vp, C.POINTER(i32), C.POINTER(i64), C.POINTER(i64)]
         L.gorgo_last_eval_kernel_ms.argtypes = [C.POINTER(dbl)] * 3
         for name in ("gorgo_load_trace", "gorgo_load_trace_arrays", "gorgo_trace_info", "gorgo_workspace_bytes",
                      "gorgo_eval_population", "gorgo_es_init", "gorgo_es_sample", "gorgo_es_propose",
                      "gorgo_es_update", "gorgo_es_workspace_bytes", "gorgo_es_step", "gorgo_set_table_factor_percent",
-                     "gorgo_last_eval_kernel_ms", "gorgo_set_replay_path"):
+                     "gorgo_last_eval_kernel_ms", "gorgo_set_replay_path", "gorgo_query_replay_path"):
             getattr(L, name).restype = C.c_int
         _lib = L
     return _lib
@@ -136,6 +137,12 @@ class Trace:
         _check(lib().gorgo_trace_info(self._h, C.byref(n), C.byref(tb), C.byref(mb), C.byref(u), C.byref(cc)))
         return dict(N=n.value, total_blocks=tb.value, max_blocks=mb.value, unique_ids=u.value,
                     chain_consistent=bool(cc.value))
+
+    def replay_path(self) -> dict:
+        """Formulation an evaluation would use now (1 = block tables, 2 = segment rows) and segment counts."""
+        p, ns, nr = C.c_int32(), C.c_int64(), C.c_int64()
+        _check(lib().gorgo_query_replay_path(self._h, C.byref(p), C.byref(ns), C.byref(nr)))
+        return dict(path=p.value, n_segments=ns.value, segment_refs=nr.value)
 
     @property
     def N(self) -> int:

@@ -116,6 +116,18 @@ int gorgo_set_replay_path(int32_t mode) {
     return GORGO_OK;
 }
 
+int gorgo_query_replay_path(const gorgo_trace* t, int32_t* path, int64_t* n_segments, int64_t* segment_refs) {
+    clear_error();
+    if (!t) return fail(GORGO_ERR_INVALID_ARG, "trace is NULL");
+    const int32_t mode = g_path.load();
+    const bool few = (int64_t)t->seg.size() <= 16 * (t->N > 0 ? t->N : 1);
+    if (path)
+        *path = mode == PATH_SEGMENTS || (mode == PATH_AUTO && t->chain_consistent && few) ? PATH_SEGMENTS : PATH_BLOCKS;
+    if (n_segments) *n_segments = t->n_segments;
+    if (segment_refs) *segment_refs = (int64_t)t->seg.size();
+    return GORGO_OK;
+}
+
 int gorgo_workspace_bytes(const gorgo_trace* t, const gorgo_model* m, int32_t P, const gorgo_outputs* outputs,
                           size_t* bytes) {
     clear_error();
