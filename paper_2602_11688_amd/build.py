@@ -7,7 +7,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libgorgo.so")
 SOURCES = ["trace.cpp", "es.cpp", "api.cpp", "kernels.hip"]
-HEADERS = [os.path.join(CSRC, "internal.h"), os.path.join(CSRC, "device_common.h"), os.path.join(ROOT, "include", "gorgo.h")]
+HEADERS = [os.path.join(CSRC, "internal.h"), os.path.join(CSRC, "device_common.h"), os.path.join(CSRC, "replay_segments.h"), os.path.join(ROOT, "include", "gorgo.h")]
 
 
 def stale() -> bool:

@@ -73,7 +73,8 @@ int make_plan(const gorgo_trace* t, const gorgo_model* m, int32_t P, const gorgo
     pl->off_tables = off;
     if (pl->path == PATH_SEGMENTS) {
         off += up256((size_t)P * (size_t)pl->nseg * pl->R * 4);
-        pl->off_spare = off;
+        pl->off_spare = off;                              // per-request log records of the segment kernel
+        off += up256((size_t)P * (size_t)t->N * 8);
     } else {
         off += up256((size_t)P * pl->R * (size_t)cap * 16);
         pl->off_spare = off;
@@ -83,7 +84,7 @@ int make_plan(const gorgo_trace* t, const gorgo_model* m, int32_t P, const gorgo
     off += up256((size_t)P * N * 16);
     const bool want_p95_t = !o || o->p95_ttft_ms, want_p95_e = !o || o->p95_e2e_ms;
     pl->off_route = off;
-    if (!o || !o->route) off += up256((size_t)P * N);
+    if ((!o || !o->route) && pl->path == PATH_BLOCKS) off += up256((size_t)P * N);   // the block kernel reads it back
     pl->off_ttft = off;
     if (!o || (!o->ttft_ms && want_p95_t)) off += up256((size_t)P * N * 8);
     pl->off_e2e = off;
@@ -177,7 +178,8 @@ int gorgo_eval_population(const gorgo_trace* t, const gorgo_model* m, const doub
     if ((rc = copy_small_to_device(d_params, params, sizeof(double) * 3 * (size_t)P, hip_stream))) return rc;
     if ((rc = copy_small_to_device(d_scale, scale, sizeof(double) * (size_t)P, hip_stream))) return rc;
 
-    uint8_t* route = outputs->route ? outputs->route : reinterpret_cast<uint8_t*>(ws + pl.off_route);
+    uint8_t* route = outputs->route;
+    if (!route && pl.path == PATH_BLOCKS) route = reinterpret_cast<uint8_t*>(ws + pl.off_route);
     double* ttft = outputs->ttft_ms;
     if (!ttft && outputs->p95_ttft_ms) ttft = reinterpret_cast<double*>(ws + pl.off_ttft);
     double* e2e = outputs->e2e_ms;

@@ -18,6 +18,7 @@
 
 #include "device_common.h"
 #include "internal.h"
+#include "replay_segments.h"
 
 namespace gorgo {
 
@@ -137,6 +138,7 @@ __global__ void __launch_bounds__(WAVE) replay_blocks_kernel(ReplayArgs a) {
     const double w_queue = a.params[3 * (size_t)p + 2];
     const double sc = a.scale[p];
     const double my_rtt = lane < R ? a.rtt[lane] : 0.0;
+    double my_min_done = INFINITY;     // earliest completion among the service slots this lane owns
 
     Slot* const tables = a.tables + (size_t)p * R * a.cap;
     Slot* const spare = a.spare + (size_t)p * a.cap;
@@ -151,7 +153,7 @@ __global__ void __launch_bounds__(WAVE) replay_blocks_kernel(ReplayArgs a) {
         const int64_t O = a.out_len[r];
         const double t = (double)a.ts[r] * sc;     // time scale: gaps scale linearly
 
-        Q.retire(t, rec, lane);
+        Q.retire(t, rec, lane, my_min_done);
 
         // ---- prefix match: first block on every replica, then the whole list on replicas that hold it
         int my_m = 0;
@@ -192,10 +194,10 @@ __global__ void __launch_bounds__(WAVE) replay_blocks_kernel(ReplayArgs a) {
             my_u = L - hit_tok;
             my_score = eq3_score(w_rtt, w_prefill, w_queue, my_rtt, a.a_pf, my_u, Q.q[lane]);
         }
-        const int best = wave_argmin(my_score, lane < R ? lane : 255).idx;
-        const int64_t u_best = __shfl(my_u, best);
-        const int m_best = __shfl(my_m, best);
-        const double rtt_best = __shfl(my_rtt, best);
+        const int best = wave_argmin(my_score, lane, R).idx;
+        const int64_t u_best = readlane_i64(my_u, best);
+        const int m_best = __builtin_amdgcn_readlane(my_m, best);
+        const double rtt_best = readlane_f64(my_rtt, best);
         if (lane == 0) st(&route[r], (uint8_t)best);
 
         // ---- cache update on the chosen replica
@@ -305,7 +307,7 @@ __global__ void __launch_bounds__(WAVE) replay_blocks_kernel(ReplayArgs a) {
 
         // ---- service on the chosen replica, outputs
         double ttft, e2e;
-        Q.serve(r, best, t, rtt_best, u_best, L, O, a.a_pf, a.a_dec, rec, lane, &ttft, &e2e);
+        Q.serve(r, best, t, rtt_best, u_best, L, O, a.a_pf, a.a_dec, rec, lane, my_min_done, &ttft, &e2e);
         if (lane == 0) {
             if (a.hit) a.hit[(size_t)p * N + r] = (uint16_t)m_best;
             if (a.ttft) a.ttft[(size_t)p * N + r] = ttft;
@@ -314,189 +316,11 @@ __global__ void __launch_bounds__(WAVE) replay_blocks_kernel(ReplayArgs a) {
         __syncthreads();
     }
 }
-
-// ---- segment formulation (chain-consistent traces) -------------------------------------------------------
-// On a chain-consistent trace every request is a root-to-node path of the key forest and a whole number of
-// segments.  With the root-newest stamp order a replica's cache is always closed under taking prefixes,
-// every block of a segment carries the same last-touching request, and a block is cached iff its
-// (last request, position) is not below the replica's eviction cursor.  So the cache state of a replay is
-// one 32-bit "last request that touched it" per (segment, replica), stored as dense rows of R entries
-// addressed by segment id: no hashing, no probing, and eviction only moves the cursor, it writes nothing.
-struct SegArgs {
-    const int64_t* ts;
-    const int32_t* in_len;
-    const int32_t* out_len;
-    const int64_t* seg_off;
-    const SegRef* seg;
-    int64_t N;
-    int32_t R, B;
-    int64_t C;
-    int64_t nseg;
-    int32_t block_tokens;
-    double a_pf, a_dec;
-    const double* rtt;
-    const double* params;
-    const double* scale;
-    int32_t* last;   // [P][nseg][R], -1 = never touched
-    Rec* rec;        // [P][N]
-    uint8_t* route;  // [P][N]
-    uint16_t* hit;
-    double* ttft;
-    double* e2e;
-};
 
 __global__ void __launch_bounds__(256) fill_i32(int32_t* x, size_t n, int32_t v) {
     size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     const size_t stride = (size_t)gridDim.x * blockDim.x;
     for (; i < n; i += stride) x[i] = v;
-}
-
-__global__ void __launch_bounds__(WAVE) replay_segments_kernel(SegArgs a) {
-    extern __shared__ __align__(16) unsigned char lds_raw[];
-    const int lane = threadIdx.x;
-    const int p = blockIdx.x;
-    const int R = a.R, B = a.B;
-    const int64_t N = a.N;
-
-    Queues Q;
-    Q.carve(lds_raw, R, B);
-    int32_t* live = reinterpret_cast<int32_t*>(lds_raw + Queues::bytes(R, B));   // [R] cached blocks
-    Q.init(lane);
-    for (int i = lane; i < R; i += WAVE) live[i] = 0;
-    __syncthreads();
-
-    const double w_rtt = a.params[3 * (size_t)p + 0];
-    const double w_prefill = a.params[3 * (size_t)p + 1];
-    const double w_queue = a.params[3 * (size_t)p + 2];
-    const double sc = a.scale[p];
-    const double my_rtt = lane < R ? a.rtt[lane] : 0.0;
-    // eviction cursor of replica `lane`: blocks touched last by a request before my_cur_r, or by my_cur_r at
-    // positions >= my_cur_k, are evicted
-    int my_cur_r = -1, my_cur_k = 0;
-
-    int32_t* const last = a.last + (size_t)p * a.nseg * R;
-    Rec* const rec = a.rec + (size_t)p * N;
-    uint8_t* const route = a.route + (size_t)p * N;
-
-    for (int64_t r = 0; r < N; ++r) {
-        const int64_t j0 = a.seg_off[r], j1 = a.seg_off[r + 1];
-        const int n = j1 > j0 ? a.seg[j1 - 1].end : 0;
-        const int64_t L = a.in_len[r];
-        const int64_t O = a.out_len[r];
-        const double t = (double)a.ts[r] * sc;     // time scale: gaps scale linearly
-
-        Q.retire(t, rec, lane);
-
-        // ---- prefix match: lane = replica; walk the request's segments while some replica still matches
-        int my_m = 0;
-        {
-            bool open = lane < R;
-            int pos = 0;
-            for (int64_t j = j0; j < j1; ++j) {
-                const SegRef sr = a.seg[j];
-                const int len = sr.end - pos;
-                if (open) {
-                    const int32_t rl = ld(&last[(size_t)sr.id * R + lane]);
-                    int cnt = 0;
-                    if (rl > my_cur_r) {
-                        cnt = len;
-                    } else if (rl == my_cur_r && rl >= 0) {
-                        cnt = my_cur_k - pos;
-                        cnt = cnt < 0 ? 0 : (cnt > len ? len : cnt);
-                    }
-                    my_m += cnt;
-                    open = cnt == len;
-                }
-                pos = sr.end;
-                if (__ballot(open) == 0) break;
-            }
-        }
-
-        // ---- score (Eq. 3) and lowest-index minimum
-        int64_t my_u = 0;
-        double my_score = INFINITY;
-        if (lane < R) {
-            int64_t hit_tok = (int64_t)a.block_tokens * my_m;
-            if (hit_tok > L) hit_tok = L;
-            my_u = L - hit_tok;
-            my_score = eq3_score(w_rtt, w_prefill, w_queue, my_rtt, a.a_pf, my_u, Q.q[lane]);
-        }
-        const int best = wave_argmin(my_score, lane < R ? lane : 255).idx;
-        const int64_t u_best = __shfl(my_u, best);
-        const int m_best = __shfl(my_m, best);
-        const double rtt_best = __shfl(my_rtt, best);
-        if (lane == 0) st(&route[r], (uint8_t)best);
-
-        // ---- cache update: every segment of the request is now last touched by r on the chosen replica
-        for (int64_t base = j0; base < j1; base += WAVE) {
-            const int64_t j = base + lane;
-            if (j < j1) st(&last[(size_t)a.seg[j].id * R + best], (int32_t)r);
-        }
-        const int live_now = live[best] + (n - m_best);
-        __syncthreads();
-
-        // ---- eviction: move the cursor of the chosen replica forward until the cache fits.  The touch log
-        // of a replica is the route array; a logged request's segment still counts iff it was not touched
-        // since (its row still holds that request).
-        int E = a.C > 0 && live_now > a.C ? (int)(live_now - a.C) : 0;
-        const bool evicting = E > 0;
-        if (evicting) {
-            int cr = __shfl(my_cur_r, best), ck = __shfl(my_cur_k, best);
-            while (E > 0) {
-                if (ck == 0) {
-                    const int64_t x = next_routed(route, cr, r, best, lane);
-                    if (x >= r) break;          // cannot happen while E > 0; bounds the loop regardless
-                    cr = (int)x;
-                    const int64_t x0 = a.seg_off[x], x1 = a.seg_off[x + 1];
-                    ck = x1 > x0 ? a.seg[x1 - 1].end : 0;
-                    continue;
-                }
-                const int64_t x0 = a.seg_off[cr], x1 = a.seg_off[cr + 1];
-                for (int64_t hi = x1; hi > x0 && E > 0; hi -= WAVE) {
-                    const int64_t j = hi - 1 - lane;          // lane order = eviction order (deepest first)
-                    int pos = 0, top = 0, cnt = 0;
-                    if (j >= x0) {
-                        const SegRef sr = a.seg[j];
-                        pos = j > x0 ? a.seg[j - 1].end : 0;
-                        top = sr.end < ck ? sr.end : ck;
-                        if (top > pos && ld(&last[(size_t)sr.id * R + best]) == cr) cnt = top - pos;
-                    }
-                    int incl = cnt;
-#pragma unroll
-                    for (int d = 1; d < WAVE; d <<= 1) {
-                        const int o = __shfl_up(incl, d);
-                        if (lane >= d) incl += o;
-                    }
-                    const int total = __shfl(incl, WAVE - 1);
-                    if (total < E) {
-                        E -= total;
-                        const int64_t lowest = hi - WAVE > x0 ? hi - WAVE : x0;      // shallowest segment seen
-                        ck = __shfl(pos, (int)(hi - 1 - lowest));
-                    } else {
-                        const uint64_t mk = __ballot(incl >= E);
-                        const int l = __ffsll((unsigned long long)mk) - 1;
-                        ck = __shfl(top - (E - (incl - cnt)), l);
-                        E = 0;
-                    }
-                }
-            }
-            if (lane == best) {
-                my_cur_r = cr;
-                my_cur_k = ck;
-            }
-        }
-        if (lane == 0) live[best] = evicting ? (int32_t)a.C + E : live_now;
-
-        // ---- service on the chosen replica, outputs
-        double ttft, e2e;
-        Q.serve(r, best, t, rtt_best, u_best, L, O, a.a_pf, a.a_dec, rec, lane, &ttft, &e2e);
-        if (lane == 0) {
-            if (a.hit) a.hit[(size_t)p * N + r] = (uint16_t)m_best;
-            if (a.ttft) a.ttft[(size_t)p * N + r] = ttft;
-            if (a.e2e) a.e2e[(size_t)p * N + r] = e2e;
-        }
-        __syncthreads();
-    }
 }
 
 // ---- exact nearest-rank percentile: k-th smallest of x[p][0..N) by most-significant-digit radix selection
@@ -684,6 +508,7 @@ int launch_replay(const gorgo_trace* t, const Plan& pl, const double* d_rtt, con
         a.params = d_params;
         a.scale = d_scale;
         a.last = reinterpret_cast<int32_t*>(ws + pl.off_tables);
+        a.log = reinterpret_cast<LogRec*>(ws + pl.off_spare);
         a.rec = reinterpret_cast<Rec*>(ws + pl.off_rec);
         a.route = route;
         a.hit = hit;
@@ -698,7 +523,7 @@ int launch_replay(const gorgo_trace* t, const Plan& pl, const double* d_rtt, con
         }
         mark(1, s);
         if (pl.N > 0) {
-            const size_t lds = Queues::bytes(pl.R, pl.B) + (size_t)pl.R * 4;
+            const size_t lds = replay_segments_lds_bytes(pl.R, pl.B);
             hipLaunchKernelGGL(replay_segments_kernel, dim3((unsigned)pl.P), dim3(WAVE), lds, s, a);
             if ((e = hipGetLastError()) != hipSuccess) return hip_fail(e, "launch replay_segments_kernel");
         }
