@@ -42,16 +42,17 @@ def algorithmic_bytes_per_routing(R, n_mean, hit_mean, outputs_bytes):
 def algorithmic_bytes_per_routing_segments(R, segs_mean, outputs_bytes):
     """Bytes one routing has to move in the segment-row formulation (one 4-byte "last request" cell per
     (segment, replica), rows of R cells addressed by segment id), private to one replay:
-      first segment's row, read by every replica's lane        4 * R
-      deeper segments on the replica(s) that hold the prefix   4 * (s - 1)
-      update of the chosen replica's cells                     4 * s
-      eviction walk: every logged request's cells re-read once 4 * s, plus the scan of the route log to
-      the next request of the same replica                     R
-      in-flight record push + pop                              16 + 16
-      per-request outputs                                      outputs_bytes
-    The trace itself (28 B + 8 B per segment per request) is shared by all replays and is not counted."""
+      rows of the request's segments, read by every replica's lane   4 * R * s
+      update of the chosen replica's cells                            4 * s
+      log record of the request: written (8), linked from its predecessor on the replica (4), its owned
+      suffix moved when a later request takes its segments over (2), read once by the eviction cursor (8)
+      per-request outputs                                             outputs_bytes
+    Queue state (service slots, the two oldest in-flight requests of a slot, load signal) lives in LDS and
+    registers; deeper in-flight records (16 B each way) only exist when a slot is more than two deep and
+    are not counted.  The trace itself (28 B + 8 B per segment per request) is shared by all replays and is
+    not counted."""
     s = segs_mean
-    return 4 * R + 4 * (s - 1) + 4 * s + 4 * s + R + 32 + outputs_bytes
+    return 4 * R * s + 4 * s + 22 + outputs_bytes
 
 
 def cpu_baseline(wl, params, n_req, threads):
@@ -141,7 +142,7 @@ def main():
     rp = tr.replay_path()
     segs_mean = rp["segment_refs"] / max(N, 1)
     if rp["path"] == 2:
-        bpr = algorithmic_bytes_per_routing_segments(wl.R, segs_mean, outputs_bytes=9)   # route u8 + ttft f64
+        bpr = algorithmic_bytes_per_routing_segments(wl.R, segs_mean, outputs_bytes=8)   # ttft f64
         kernel = "replay_segments_kernel"
     else:
         bpr = algorithmic_bytes_per_routing(wl.R, n_mean, hit_mean, outputs_bytes=9)

@@ -79,114 +79,136 @@ __device__ __forceinline__ Best wave_argmin(double v, int lane, int count) {
     return Best{mn, __ffsll(at) - 1};
 }
 
-// Queue side of one replay (LDS): B service slots per replica, the in-flight requests of every slot as a
-// FIFO (completion times increase along a slot), and the load signal q (Eq. 2: tokens of requests without a
-// completion event at the proxy).  The two oldest requests of a slot live in LDS; deeper ones are Rec
-// records in global memory linked in dispatch order, fetched when they become the second oldest.
+// Queue side of one replay.  Lane i owns replica i: its load signal q (Eq. 2: tokens of requests without a
+// completion event at the proxy) and the earliest pending completion live in that lane's registers, its B
+// service slots in LDS (slot b of replica i at index i * Bp + b, Bp = B rounded up to 8).  The in-flight
+// requests of a slot form a FIFO (completion times increase along a slot); the two oldest are in LDS,
+// deeper ones are Rec records in global memory linked in dispatch order, fetched when they become the
+// second oldest.  Only the owning lane ever touches a replica's queue state.
 struct Queues {
-    double* free_at;     // [R*B] time the service slot becomes free
-    double* h_done;      // [R*B] completion time of the oldest in-flight request (+inf: none)
-    double* s_done;      // [R*B] ... of the second oldest
-    int64_t* q;          // [R]
-    int32_t* h_tok;      // [R*B] tokens of the oldest
-    int32_t* s_tok;      // [R*B] tokens of the second oldest
-    int32_t* s_next;     // [R*B] request after the second oldest (-1: none)
-    int32_t* tail;       // [R*B] youngest request of the slot
-    int32_t* depth;      // [R*B] requests in flight on the slot
-    uint8_t* rep_of;     // [R*B] replica of the slot
-    int R, B;
+    double* free_at;     // [R*Bp] time the service slot becomes free (+inf in the padding)
+    double* h_done;      // [R*Bp] completion time of the oldest in-flight request (+inf: none)
+    double* s_done;      // [R*Bp] ... of the second oldest
+    int32_t* h_tok;      // [R*Bp] tokens of the oldest
+    int32_t* s_tok;      // [R*Bp] tokens of the second oldest
+    int32_t* s_next;     // [R*Bp] request after the second oldest (-1: none)
+    int32_t* tail;       // [R*Bp] youngest request of the slot
+    int32_t* depth;      // [R*Bp] requests in flight on the slot
+    int R, B, Bp;
+    double my_min;       // earliest head completion among this lane's slots
+    int64_t my_q;        // outstanding tokens of replica = lane
 
     static __host__ __device__ size_t bytes(int R, int B) {
-        return (size_t)R * B * (8 * 3 + 4 * 5) + (size_t)R * 8 + (((size_t)R * B + 3) & ~(size_t)3);
+        return (size_t)R * ((B + 7) & ~7) * (8 * 3 + 4 * 5);
     }
 
     __device__ void carve(unsigned char* lds, int R_, int B_) {
         R = R_;
         B = B_;
-        const int RB = R * B;
+        Bp = (B + 7) & ~7;
+        const int n = R * Bp;
         free_at = reinterpret_cast<double*>(lds);
-        h_done = free_at + RB;
-        s_done = h_done + RB;
-        q = reinterpret_cast<int64_t*>(s_done + RB);
-        h_tok = reinterpret_cast<int32_t*>(q + R);
-        s_tok = h_tok + RB;
-        s_next = s_tok + RB;
-        tail = s_next + RB;
-        depth = tail + RB;
-        rep_of = reinterpret_cast<uint8_t*>(depth + RB);
+        h_done = free_at + n;
+        s_done = h_done + n;
+        h_tok = reinterpret_cast<int32_t*>(s_done + n);
+        s_tok = h_tok + n;
+        s_next = s_tok + n;
+        tail = s_next + n;
+        depth = tail + n;
     }
 
     __device__ void init(int lane) {
-        for (int s = lane; s < R * B; s += WAVE) {
-            free_at[s] = 0.0;
-            h_done[s] = INFINITY;
-            depth[s] = 0;
-            tail[s] = -1;
-            rep_of[s] = (uint8_t)(s / B);
+        for (int x = lane; x < R * Bp; x += WAVE) {
+            free_at[x] = (x % Bp) < B ? 0.0 : INFINITY;
+            h_done[x] = INFINITY;
+            depth[x] = 0;
+            tail[x] = -1;
         }
-        for (int i = lane; i < R; i += WAVE) q[i] = 0;
+        my_min = INFINITY;
+        my_q = 0;
     }
 
-    // Drop requests whose completion event has reached the proxy (done <= t).  `my_min` is a per-lane
-    // register holding the earliest head completion among the slots this lane owns (slot s belongs to lane
-    // s % 64), so the common case -- nothing to retire -- touches no memory.
-    __device__ void retire(double t, const Rec* rec, int lane, double& my_min) {
+    // Drop requests whose completion event has reached the proxy (done <= t).
+    __device__ void retire(double t, const Rec* rec, int lane) {
         if (__ballot(my_min <= t) == 0) return;
         if (my_min <= t) {
+            const int base = lane * Bp;
             double mn = INFINITY;
-            for (int s = lane; s < R * B; s += WAVE) {
-                double hd = h_done[s];
-                while (hd <= t) {
-                    atomicAdd(reinterpret_cast<unsigned long long*>(&q[rep_of[s]]),
-                              (unsigned long long)(-(int64_t)h_tok[s]));
-                    const int d = depth[s];
-                    if (d == 1) {
-                        hd = INFINITY;
-                    } else {
-                        hd = s_done[s];
-                        h_tok[s] = s_tok[s];
-                        if (d >= 3) {
-                            const int x = s_next[s];
-                            s_done[s] = ld(&rec[x].done);
-                            s_tok[s] = ld(&rec[x].tokens);
-                            s_next[s] = ld(&rec[x].next);
+            for (int b0 = 0; b0 < Bp; b0 += 8) {
+                double hd[8];
+#pragma unroll
+                for (int k = 0; k < 8; ++k) hd[k] = h_done[base + b0 + k];
+#pragma unroll
+                for (int k = 0; k < 8; ++k) {
+                    if (hd[k] <= t) {
+                        const int s = base + b0 + k;
+                        double h = hd[k];
+                        while (h <= t) {
+                            my_q -= h_tok[s];
+                            const int d = depth[s];
+                            if (d == 1) {
+                                h = INFINITY;
+                            } else {
+                                h = s_done[s];
+                                h_tok[s] = s_tok[s];
+                                if (d >= 3) {
+                                    const int x = s_next[s];
+                                    s_done[s] = ld(&rec[x].done);
+                                    s_tok[s] = ld(&rec[x].tokens);
+                                    s_next[s] = ld(&rec[x].next);
+                                }
+                            }
+                            depth[s] = d - 1;
                         }
+                        h_done[s] = h;
+                        hd[k] = h;
                     }
-                    h_done[s] = hd;
-                    depth[s] = d - 1;
+                    mn = hd[k] < mn ? hd[k] : mn;
                 }
-                mn = hd < mn ? hd : mn;
             }
             my_min = mn;
         }
-        __syncthreads();
     }
 
     // Service of request r on replica `best` (the stated linear model; reproduces Eq. 1: ttft = rtt + wait +
-    // prefill): earliest-free slot, lowest index on ties.  Lane 0 updates the state; the caller places a
-    // barrier before the next use.
-    __device__ void serve(int64_t r, int best, double t, double rtt_best, int64_t uncached, int64_t L, int64_t O,
-                          double a_pf, double a_dec, Rec* rec, int lane, double& my_min, double* ttft_out,
-                          double* e2e_out) {
-        const Best slot = wave_argmin(lane < B ? free_at[best * B + lane] : INFINITY, lane, B);
-        const double half = 0.5 * rtt_best;
-        const double arrive = t + half;
-        const double start = arrive > slot.v ? arrive : slot.v;
-        const double pf = a_pf * (double)uncached;
-        const double first_tok = start + pf;
-        const double dec = a_dec * (double)O;
-        const double end = first_tok + dec;
-        const double done = end + half;
-        *ttft_out = (first_tok + half) - t;
-        *e2e_out = done - t;
-        const int s = best * B + slot.idx;
-        const int d = depth[s];
-        if (d == 0 && lane == (s & (WAVE - 1))) my_min = done < my_min ? done : my_min;   // new head of the slot
-        if (lane == 0) {
+    // prefill): earliest-free slot, lowest index on ties.  Runs in the owning lane; the latencies are
+    // broadcast to all lanes.
+    __device__ void serve(int64_t r, int best, double t, double rtt_mine, int64_t uncached_mine, int64_t L, int64_t O,
+                          double a_pf, double a_dec, Rec* rec, int lane, double* ttft_out, double* e2e_out) {
+        double ttft = 0.0, e2e = 0.0;
+        if (lane == best) {
+            const int base = lane * Bp;
+            double fv = INFINITY;
+            int ks = 0;
+            for (int b0 = 0; b0 < Bp; b0 += 8) {
+                double v[8];
+#pragma unroll
+                for (int k = 0; k < 8; ++k) v[k] = free_at[base + b0 + k];
+#pragma unroll
+                for (int k = 0; k < 8; ++k) {
+                    if (v[k] < fv) {
+                        fv = v[k];
+                        ks = b0 + k;
+                    }
+                }
+            }
+            const double half = 0.5 * rtt_mine;
+            const double arrive = t + half;
+            const double start = arrive > fv ? arrive : fv;
+            const double pf = a_pf * (double)uncached_mine;
+            const double first_tok = start + pf;
+            const double dec = a_dec * (double)O;
+            const double end = first_tok + dec;
+            const double done = end + half;
+            ttft = (first_tok + half) - t;
+            e2e = done - t;
+            const int s = base + ks;
             free_at[s] = end;
+            const int d = depth[s];
             if (d == 0) {
                 h_done[s] = done;
                 h_tok[s] = (int32_t)L;
+                my_min = done < my_min ? done : my_min;
             } else if (d == 1) {
                 s_done[s] = done;
                 s_tok[s] = (int32_t)L;
@@ -201,8 +223,10 @@ struct Queues {
             }
             tail[s] = (int32_t)r;
             depth[s] = d + 1;
-            q[best] += L;
+            my_q += L;
         }
+        *ttft_out = readlane_f64(ttft, best);
+        *e2e_out = readlane_f64(e2e, best);
     }
 };
 

@@ -138,7 +138,6 @@ __global__ void __launch_bounds__(WAVE) replay_blocks_kernel(ReplayArgs a) {
     const double w_queue = a.params[3 * (size_t)p + 2];
     const double sc = a.scale[p];
     const double my_rtt = lane < R ? a.rtt[lane] : 0.0;
-    double my_min_done = INFINITY;     // earliest completion among the service slots this lane owns
 
     Slot* const tables = a.tables + (size_t)p * R * a.cap;
     Slot* const spare = a.spare + (size_t)p * a.cap;
@@ -153,7 +152,7 @@ __global__ void __launch_bounds__(WAVE) replay_blocks_kernel(ReplayArgs a) {
         const int64_t O = a.out_len[r];
         const double t = (double)a.ts[r] * sc;     // time scale: gaps scale linearly
 
-        Q.retire(t, rec, lane, my_min_done);
+        Q.retire(t, rec, lane);
 
         // ---- prefix match: first block on every replica, then the whole list on replicas that hold it
         int my_m = 0;
@@ -192,12 +191,10 @@ __global__ void __launch_bounds__(WAVE) replay_blocks_kernel(ReplayArgs a) {
             int64_t hit_tok = (int64_t)a.block_tokens * my_m;
             if (hit_tok > L) hit_tok = L;
             my_u = L - hit_tok;
-            my_score = eq3_score(w_rtt, w_prefill, w_queue, my_rtt, a.a_pf, my_u, Q.q[lane]);
+            my_score = eq3_score(w_rtt, w_prefill, w_queue, my_rtt, a.a_pf, my_u, Q.my_q);
         }
         const int best = wave_argmin(my_score, lane, R).idx;
-        const int64_t u_best = readlane_i64(my_u, best);
         const int m_best = __builtin_amdgcn_readlane(my_m, best);
-        const double rtt_best = readlane_f64(my_rtt, best);
         if (lane == 0) st(&route[r], (uint8_t)best);
 
         // ---- cache update on the chosen replica
@@ -307,7 +304,7 @@ __global__ void __launch_bounds__(WAVE) replay_blocks_kernel(ReplayArgs a) {
 
         // ---- service on the chosen replica, outputs
         double ttft, e2e;
-        Q.serve(r, best, t, rtt_best, u_best, L, O, a.a_pf, a.a_dec, rec, lane, my_min_done, &ttft, &e2e);
+        Q.serve(r, best, t, my_rtt, my_u, L, O, a.a_pf, a.a_dec, rec, lane, &ttft, &e2e);
         if (lane == 0) {
             if (a.hit) a.hit[(size_t)p * N + r] = (uint16_t)m_best;
             if (a.ttft) a.ttft[(size_t)p * N + r] = ttft;

@@ -63,7 +63,7 @@ constexpr int SEG_STAGE = 512;   // segment references of a 64-request batch sta
 constexpr int SEG_CHUNK = 8;     // segments of a request whose rows are loaded together
 
 __host__ __device__ inline size_t replay_segments_lds_bytes(int R, int B) {   // dynamic part
-    return Queues::bytes(R, B) + (size_t)R * 4;
+    return Queues::bytes(R, B);
 }
 
 // Rows of one request's first SEG_CHUNK segments as seen by this lane (= replica), with the segments' end
@@ -75,7 +75,7 @@ struct RowSet {
 
 __global__ void __launch_bounds__(WAVE) replay_segments_kernel(SegArgs a) {
     extern __shared__ __align__(16) unsigned char lds_raw[];
-    __shared__ SegRef stage[SEG_STAGE];
+    __shared__ SegRef stage[SEG_STAGE + SEG_CHUNK];    // padded: whole chunks are read unconditionally
     const int lane = threadIdx.x;
     const int p = blockIdx.x;
     const int R = a.R, B = a.B;
@@ -83,9 +83,8 @@ __global__ void __launch_bounds__(WAVE) replay_segments_kernel(SegArgs a) {
 
     Queues Q;
     Q.carve(lds_raw, R, B);
-    int32_t* const live = reinterpret_cast<int32_t*>(lds_raw + Queues::bytes(R, B));
     Q.init(lane);
-    for (int i = lane; i < R; i += WAVE) live[i] = 0;
+    for (int x = lane; x < SEG_CHUNK; x += WAVE) stage[SEG_STAGE + x] = SegRef{0, 0};
     __syncthreads();
 
     const double w_rtt = a.params[3 * (size_t)p + 0];
@@ -93,17 +92,19 @@ __global__ void __launch_bounds__(WAVE) replay_segments_kernel(SegArgs a) {
     const double w_queue = a.params[3 * (size_t)p + 2];
     const double sc = a.scale[p];
     const double my_rtt = lane < R ? a.rtt[lane] : 0.0;
-    double my_min_done = INFINITY;     // earliest completion among the service slots this lane owns
 
     // Per-replica eviction state, held by lane = replica.  Blocks last touched by a request before cur_r, or
     // by cur_r at positions >= cur_k, are evicted; cur_own is where cur_r's owned suffix starts.  nx_* is
     // the log record after cur_r and n2_* the one after that (kept as the raw 64-bit word so that the load
-    // that fetches it is not waited for until it is needed); tail_r is the youngest request routed here.
+    // that fetches it is not waited for until it is needed; changes made to that record meanwhile are kept
+    // beside it in n2_own / n2_next and override the loaded fields).  tail_r is the youngest request routed
+    // here and my_live the number of blocks cached on the replica.
     int cur_r = -1, cur_k = 0, cur_own = 0;
     int nx_r = -1, nx_n = 0, nx_own = 0;
-    int n2_r = -1;
+    int n2_r = -1, n2_own = -1, n2_next = -1;
     unsigned long long n2_raw = 0;
     int tail_r = -1;
+    int my_live = 0;
 
     int32_t* const last = a.last + (size_t)p * a.nseg * R;
     LogRec* const log = a.log + (size_t)p * N;
@@ -157,15 +158,14 @@ __global__ void __launch_bounds__(WAVE) replay_segments_kernel(SegArgs a) {
         auto request_rows = [&](int i, RowSet& w) {
             const int a0 = __builtin_amdgcn_readlane(m_a0, i);
             const int s = __builtin_amdgcn_readlane(m_s, i);
+            SegRef sr[SEG_CHUNK];
+#pragma unroll
+            for (int k = 0; k < SEG_CHUNK; ++k) sr[k] = stage[a0 + k];
 #pragma unroll
             for (int k = 0; k < SEG_CHUNK; ++k) {
                 w.cell[k] = -1;
-                w.end[k] = 0;
-                if (k < s) {
-                    const SegRef sr = stage[a0 + k];
-                    w.end[k] = sr.end;
-                    if (lane < R) w.cell[k] = ld(&last[(size_t)sr.id * R + lane]);
-                }
+                w.end[k] = sr[k].end;
+                if (k < s && lane < R) w.cell[k] = ld(&last[(size_t)sr[k].id * R + lane]);
             }
         };
 
@@ -181,7 +181,7 @@ __global__ void __launch_bounds__(WAVE) replay_segments_kernel(SegArgs a) {
             const int s = __builtin_amdgcn_readlane(m_s, i);
             const int n = __builtin_amdgcn_readlane(m_n, i);
 
-            Q.retire(t, rec, lane, my_min_done);
+            Q.retire(t, rec, lane);
 
             // ---- prefix match: lane = replica
             int my_m = 0;
@@ -236,12 +236,10 @@ __global__ void __launch_bounds__(WAVE) replay_segments_kernel(SegArgs a) {
                 int64_t hit_tok = (int64_t)a.block_tokens * my_m;
                 if (hit_tok > L) hit_tok = L;
                 my_u = L - hit_tok;
-                my_score = eq3_score(w_rtt, w_prefill, w_queue, my_rtt, a.a_pf, my_u, Q.q[lane]);
+                my_score = eq3_score(w_rtt, w_prefill, w_queue, my_rtt, a.a_pf, my_u, Q.my_q);
             }
             const int best = wave_argmin(my_score, lane, R).idx;
-            const int64_t u_best = readlane_i64(my_u, best);
             const int m_best = __builtin_amdgcn_readlane(my_m, best);
-            const double rtt_best = readlane_f64(my_rtt, best);
 
             // ---- ownership: the segments this request takes over on the chosen replica stop belonging to
             // their previous requests.  Along the path the previous owners form runs; each run moves its
@@ -256,8 +254,7 @@ __global__ void __launch_bounds__(WAVE) replay_segments_kernel(SegArgs a) {
                         if (lane == best) {
                             if (run_owner == cur_r) cur_own = run_end;
                             if (run_owner == nx_r) nx_own = run_end;
-                            if (run_owner == n2_r)
-                                n2_raw = (n2_raw & ~(0xFFFFull << 32)) | ((unsigned long long)run_end << 32);
+                            if (run_owner == n2_r) n2_own = run_end;
                         }
                     }
                 };
@@ -312,18 +309,20 @@ __global__ void __launch_bounds__(WAVE) replay_segments_kernel(SegArgs a) {
                     nx_n = n;
                     nx_own = 0;
                 } else if (nx_r == tail_r) {
-                    n2_r = (int)r;
+                    n2_r = (int)r;               // record known without a load: own 0, next none
                     n2_raw = fresh;
+                    n2_own = -1;
+                    n2_next = -1;
                 } else if (n2_r == tail_r) {
-                    n2_raw = (n2_raw & ~0xFFFFFFFFull) | (unsigned int)r;
+                    n2_next = (int)r;
                 }
                 tail_r = (int)r;
 
                 // ---- eviction: move the cursor forward until the cache fits
                 if (a.C > 0) {
-                    int lv = live[best] + (n - m_best);
-                    if (lv > a.C) {
-                        int E = lv - (int)a.C;
+                    my_live += n - m_best;
+                    if (my_live > a.C) {
+                        int E = my_live - (int)a.C;
                         for (;;) {
                             const int avail = cur_k - cur_own;
                             if (avail >= E) {
@@ -339,20 +338,21 @@ __global__ void __launch_bounds__(WAVE) replay_segments_kernel(SegArgs a) {
                             nx_r = n2_r;
                             if (nx_r >= 0) {
                                 nx_n = (int)(n2_raw >> 48);
-                                nx_own = (int)((n2_raw >> 32) & 0xFFFF);
-                                n2_r = (int)(unsigned int)n2_raw;
+                                nx_own = n2_own >= 0 ? n2_own : (int)((n2_raw >> 32) & 0xFFFF);
+                                n2_r = n2_next >= 0 ? n2_next : (int)(unsigned int)n2_raw;
+                                n2_own = -1;
+                                n2_next = -1;
                                 if (n2_r >= 0) n2_raw = ld(&log64[n2_r]);
                             }
                         }
-                        lv = (int)a.C + E;
+                        my_live = (int)a.C + E;
                     }
-                    live[best] = lv;
                 }
             }
 
             // ---- service on the chosen replica, outputs (kept in registers until the batch ends)
             double ttft, e2e;
-            Q.serve(r, best, t, rtt_best, u_best, L, O, a.a_pf, a.a_dec, rec, lane, my_min_done, &ttft, &e2e);
+            Q.serve(r, best, t, my_rtt, my_u, L, O, a.a_pf, a.a_dec, rec, lane, &ttft, &e2e);
             if (lane == i) {
                 o_route = best;
                 o_hit = m_best;
