@@ -55,6 +55,33 @@ def algorithmic_bytes_per_routing_segments(R, segs_mean, outputs_bytes):
     return 4 * R * s + 4 * s + 22 + outputs_bytes
 
 
+def kernel_source_digest():
+    """Digest of the device sources; HBM counters recorded for another digest are not reported."""
+    import hashlib
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_2602_11688_amd", "csrc")
+    for name in ("device_common.h", "replay_segments.h", "kernels.hip"):
+        with open(os.path.join(csrc, name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
+
+
+def recorded_traffic(kernel, workload_key):
+    """HBM bytes per launch of `kernel` from the rocprofv3 counter runs recorded under profiles/ (FETCH_SIZE
+    and WRITE_SIZE, each scaled by the same counter's reading for a plain 1 GiB copy), or None when the
+    device sources have changed since, or the workload differs."""
+    path = os.path.join(ROOT, "profiles", "hbm_counters.json")
+    try:
+        with open(path) as f:
+            rec = json.load(f)
+    except OSError:
+        return None
+    if rec.get("source_digest") != kernel_source_digest() or rec.get("kernel") != kernel or \
+            rec.get("workload") != workload_key:
+        return None
+    return rec["fetch_bytes_per_launch"] + rec["write_bytes_per_launch"]
+
+
 def cpu_baseline(wl, params, n_req, threads):
     """The oracle as it stands, one replay per thread, on the first n_req requests of the workload."""
     from concurrent.futures import ThreadPoolExecutor
@@ -83,6 +110,8 @@ def main():
     ap.add_argument("--population", type=int, default=None, help="override P (experiments only)")
     ap.add_argument("--cpu-sample-requests", type=int, default=600000)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also launch one plain 1 GiB device copy before the timed region (reference for HBM counters)")
     ap.add_argument("--path", type=int, default=0, help="0 auto, 1 hashed block tables, 2 segment rows (experiments only)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -112,6 +141,14 @@ def main():
     def generation():
         par, fit, _ = g.es_step(tr, model, wl.rtt_ms, 1.0, P, state, workspace=ws)
         return par, fit, g.last_eval_kernel_ms()
+
+    if args.calibrate_copy:
+        src = torch.zeros((1 << 28,), dtype=torch.float32, device="cuda:0")       # 1 GiB read + 1 GiB written
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        torch.add(src, 1.0, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
 
     for i in range(args.warmup):
         t0 = time.perf_counter()
@@ -148,6 +185,7 @@ def main():
         bpr = algorithmic_bytes_per_routing(wl.R, n_mean, hit_mean, outputs_bytes=9)
         kernel = "replay_blocks_kernel"
     k_ms = float(np.mean(kernel_ms))
+    traffic = recorded_traffic(kernel, f"config-{args.config} N={N} P={P}")
     achieved = bpr * P * N / (k_ms * 1e-3) / 1e9
 
     out = {
@@ -158,7 +196,7 @@ def main():
                                f"one ES generation per step (eval + p95 TTFT fitness + mean update)",
                    "es_generation_wall_s": wall / args.steps},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None, "kernel": kernel, "mean_segments": segs_mean,
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "kernel": kernel, "mean_segments": segs_mean,
                      "kernel_ms": k_ms, "bytes_per_routing": bpr, "mean_blocks": n_mean, "mean_hit_blocks": hit_mean,
                      "fill_ms": float(np.mean(fill_ms)), "select_ms": float(np.mean(select_ms))},
     }
