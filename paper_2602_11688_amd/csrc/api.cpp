@@ -72,7 +72,7 @@ int make_plan(const gorgo_trace* t, const gorgo_model* m, int32_t P, const gorgo
     size_t off = 0;
     pl->off_tables = off;
     if (pl->path == PATH_SEGMENTS) {
-        off += up256((size_t)P * (size_t)pl->nseg * pl->R * 4);
+        off += up256((size_t)P * (size_t)(pl->nseg > 0 ? pl->nseg : 1) * pl->R * 4);   // at least one row
         pl->off_spare = off;                              // per-request log records of the segment kernel
         off += up256((size_t)P * (size_t)t->N * 8);
     } else {

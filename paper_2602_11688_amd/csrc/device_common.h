@@ -80,11 +80,12 @@ __device__ __forceinline__ Best wave_argmin(double v, int lane, int count) {
 }
 
 // Queue side of one replay.  Lane i owns replica i: its load signal q (Eq. 2: tokens of requests without a
-// completion event at the proxy) and the earliest pending completion live in that lane's registers, its B
-// service slots in LDS (slot b of replica i at index i * Bp + b, Bp = B rounded up to 8).  The in-flight
-// requests of a slot form a FIFO (completion times increase along a slot); the two oldest are in LDS,
-// deeper ones are Rec records in global memory linked in dispatch order, fetched when they become the
-// second oldest.  Only the owning lane ever touches a replica's queue state.
+// completion event at the proxy), its earliest pending completion and its earliest-free service slot live
+// in that lane's registers, the B service slots themselves in LDS (slot b of replica i at index
+// i * Bp + b, Bp = B rounded up to 8).  The in-flight requests of a slot form a FIFO (completion times
+// increase along a slot); the two oldest are in LDS, deeper ones are Rec records in global memory linked in
+// dispatch order, fetched when they become the second oldest.  Only the owning lane ever touches a
+// replica's queue state, so every lane runs the same code on its own replica and no barrier is needed.
 struct Queues {
     double* free_at;     // [R*Bp] time the service slot becomes free (+inf in the padding)
     double* h_done;      // [R*Bp] completion time of the oldest in-flight request (+inf: none)
@@ -94,18 +95,22 @@ struct Queues {
     int32_t* s_next;     // [R*Bp] request after the second oldest (-1: none)
     int32_t* tail;       // [R*Bp] youngest request of the slot
     int32_t* depth;      // [R*Bp] requests in flight on the slot
-    int R, B, Bp;
-    double my_min;       // earliest head completion among this lane's slots
+    int R, B, Bp, base;
+    double my_min;       // earliest head completion among this lane's slots ...
+    int my_min_k;        // ... and its slot
+    double f_min;        // earliest free time among this lane's slots (lowest slot on ties) ...
+    int f_k;             // ... and its slot
     int64_t my_q;        // outstanding tokens of replica = lane
 
     static __host__ __device__ size_t bytes(int R, int B) {
         return (size_t)R * ((B + 7) & ~7) * (8 * 3 + 4 * 5);
     }
 
-    __device__ void carve(unsigned char* lds, int R_, int B_) {
+    __device__ void carve(unsigned char* lds, int R_, int B_, int lane) {
         R = R_;
         B = B_;
         Bp = (B + 7) & ~7;
+        base = (lane < R ? lane : 0) * Bp;
         const int n = R * Bp;
         free_at = reinterpret_cast<double*>(lds);
         h_done = free_at + n;
@@ -125,90 +130,78 @@ struct Queues {
             tail[x] = -1;
         }
         my_min = INFINITY;
+        my_min_k = 0;
+        f_min = 0.0;
+        f_k = 0;
         my_q = 0;
     }
 
     // Drop requests whose completion event has reached the proxy (done <= t).
-    __device__ void retire(double t, const Rec* rec, int lane) {
-        if (__ballot(my_min <= t) == 0) return;
-        if (my_min <= t) {
-            const int base = lane * Bp;
-            double mn = INFINITY;
-            for (int b0 = 0; b0 < Bp; b0 += 8) {
-                double hd[8];
-#pragma unroll
-                for (int k = 0; k < 8; ++k) hd[k] = h_done[base + b0 + k];
-#pragma unroll
-                for (int k = 0; k < 8; ++k) {
-                    if (hd[k] <= t) {
-                        const int s = base + b0 + k;
-                        double h = hd[k];
-                        while (h <= t) {
-                            my_q -= h_tok[s];
-                            const int d = depth[s];
-                            if (d == 1) {
-                                h = INFINITY;
-                            } else {
-                                h = s_done[s];
-                                h_tok[s] = s_tok[s];
-                                if (d >= 3) {
-                                    const int x = s_next[s];
-                                    s_done[s] = ld(&rec[x].done);
-                                    s_tok[s] = ld(&rec[x].tokens);
-                                    s_next[s] = ld(&rec[x].next);
-                                }
-                            }
-                            depth[s] = d - 1;
-                        }
-                        h_done[s] = h;
-                        hd[k] = h;
+    __device__ void retire(double t, const Rec* rec) {
+        while (__ballot(my_min <= t) != 0) {
+            if (my_min <= t) {
+                const int s = base + my_min_k;
+                my_q -= h_tok[s];
+                const int d = depth[s];
+                if (d > 1) {
+                    h_done[s] = s_done[s];
+                    h_tok[s] = s_tok[s];
+                    if (d >= 3) {
+                        const int x = s_next[s];
+                        s_done[s] = ld(&rec[x].done);
+                        s_tok[s] = ld(&rec[x].tokens);
+                        s_next[s] = ld(&rec[x].next);
                     }
-                    mn = hd[k] < mn ? hd[k] : mn;
+                } else {
+                    h_done[s] = INFINITY;
                 }
+                depth[s] = d - 1;
+                // earliest head of this lane's slots again
+                double mn = INFINITY;
+                int mk = 0;
+                for (int b0 = 0; b0 < Bp; b0 += 8) {
+                    double hd[8];
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) hd[k] = h_done[base + b0 + k];
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) {
+                        const bool lt = hd[k] < mn;
+                        mn = lt ? hd[k] : mn;
+                        mk = lt ? b0 + k : mk;
+                    }
+                }
+                my_min = mn;
+                my_min_k = mk;
             }
-            my_min = mn;
         }
     }
 
     // Service of request r on replica `best` (the stated linear model; reproduces Eq. 1: ttft = rtt + wait +
-    // prefill): earliest-free slot, lowest index on ties.  Runs in the owning lane; the latencies are
-    // broadcast to all lanes.
+    // prefill): earliest-free slot, lowest index on ties.  Every lane evaluates the schedule its own replica
+    // would give; the chosen replica's lane commits it and its latencies are broadcast.
     __device__ void serve(int64_t r, int best, double t, double rtt_mine, int64_t uncached_mine, int64_t L, int64_t O,
                           double a_pf, double a_dec, Rec* rec, int lane, double* ttft_out, double* e2e_out) {
-        double ttft = 0.0, e2e = 0.0;
+        const double half = 0.5 * rtt_mine;
+        const double arrive = t + half;
+        const double start = arrive > f_min ? arrive : f_min;
+        const double pf = a_pf * (double)uncached_mine;
+        const double first_tok = start + pf;
+        const double dec = a_dec * (double)O;
+        const double end = first_tok + dec;
+        const double done = end + half;
+        const double ttft = (first_tok + half) - t;
+        const double e2e = done - t;
         if (lane == best) {
-            const int base = lane * Bp;
-            double fv = INFINITY;
-            int ks = 0;
-            for (int b0 = 0; b0 < Bp; b0 += 8) {
-                double v[8];
-#pragma unroll
-                for (int k = 0; k < 8; ++k) v[k] = free_at[base + b0 + k];
-#pragma unroll
-                for (int k = 0; k < 8; ++k) {
-                    if (v[k] < fv) {
-                        fv = v[k];
-                        ks = b0 + k;
-                    }
-                }
-            }
-            const double half = 0.5 * rtt_mine;
-            const double arrive = t + half;
-            const double start = arrive > fv ? arrive : fv;
-            const double pf = a_pf * (double)uncached_mine;
-            const double first_tok = start + pf;
-            const double dec = a_dec * (double)O;
-            const double end = first_tok + dec;
-            const double done = end + half;
-            ttft = (first_tok + half) - t;
-            e2e = done - t;
-            const int s = base + ks;
+            const int s = base + f_k;
             free_at[s] = end;
             const int d = depth[s];
             if (d == 0) {
                 h_done[s] = done;
                 h_tok[s] = (int32_t)L;
-                my_min = done < my_min ? done : my_min;
+                if (done < my_min) {
+                    my_min = done;
+                    my_min_k = f_k;
+                }
             } else if (d == 1) {
                 s_done[s] = done;
                 s_tok[s] = (int32_t)L;
@@ -224,6 +217,22 @@ struct Queues {
             tail[s] = (int32_t)r;
             depth[s] = d + 1;
             my_q += L;
+            // earliest-free slot of this replica again
+            double fv = INFINITY;
+            int fk = 0;
+            for (int b0 = 0; b0 < Bp; b0 += 8) {
+                double v[8];
+#pragma unroll
+                for (int k = 0; k < 8; ++k) v[k] = free_at[base + b0 + k];
+#pragma unroll
+                for (int k = 0; k < 8; ++k) {
+                    const bool lt = v[k] < fv;
+                    fv = lt ? v[k] : fv;
+                    fk = lt ? b0 + k : fk;
+                }
+            }
+            f_min = fv;
+            f_k = fk;
         }
         *ttft_out = readlane_f64(ttft, best);
         *e2e_out = readlane_f64(e2e, best);

@@ -116,7 +116,7 @@ __global__ void __launch_bounds__(WAVE) replay_blocks_kernel(ReplayArgs a) {
     const int cap_log2 = a.cap_log2;
 
     Queues Q;
-    Q.carve(lds_raw, R, B);
+    Q.carve(lds_raw, R, B, lane);
     int64_t* tau = reinterpret_cast<int64_t*>(lds_raw + Queues::bytes(R, B));   // [R] eviction threshold
     int32_t* live = reinterpret_cast<int32_t*>(tau + R);          // [R] cached blocks
     int32_t* used = live + R;                                     // [R] slots ever used since the last rebuild
@@ -152,7 +152,7 @@ __global__ void __launch_bounds__(WAVE) replay_blocks_kernel(ReplayArgs a) {
         const int64_t O = a.out_len[r];
         const double t = (double)a.ts[r] * sc;     // time scale: gaps scale linearly
 
-        Q.retire(t, rec, lane);
+        Q.retire(t, rec);
 
         // ---- prefix match: first block on every replica, then the whole list on replicas that hold it
         int my_m = 0;
@@ -497,7 +497,7 @@ int launch_replay(const gorgo_trace* t, const Plan& pl, const double* d_rtt, con
         a.R = pl.R;
         a.B = pl.B;
         a.C = pl.C;
-        a.nseg = pl.nseg;
+        a.nseg = pl.nseg > 0 ? pl.nseg : 1;
         a.block_tokens = pl.block_tokens;
         a.a_pf = pl.a_pf;
         a.a_dec = pl.a_dec;
@@ -511,7 +511,7 @@ int launch_replay(const gorgo_trace* t, const Plan& pl, const double* d_rtt, con
         a.hit = hit;
         a.ttft = ttft;
         a.e2e = e2e;
-        const size_t cells = (size_t)pl.P * (size_t)pl.nseg * pl.R;
+        const size_t cells = (size_t)pl.P * (size_t)a.nseg * pl.R;
         if (cells) {
             size_t blocks = (cells + 255) / 256;
             if (blocks > 65536) blocks = 65536;

@@ -12,16 +12,16 @@
 // blocks of its path that no later request on the same replica has touched again; because paths of a forest
 // share prefixes only, that is always a suffix [own, n) of its path.  `own` is kept up to date when a later
 // request takes segments over (the cells just read say whom they belonged to), so the walk needs one small
-// record per logged request (next request on the replica, own, n) and never re-reads cells.
+// record per logged request (next request on the replica, own, n) and never re-reads cells.  Records that
+// own nothing any more are dropped from the walk as soon as they are seen.
 //
-// The request loop is one dependent chain per replay, so the kernel is arranged around memory latency, not
-// bandwidth: a batch of 64 requests is staged at once (scalars in registers, segment references in LDS);
-// the rows of request i+2 are requested while request i is still being processed, and re-requested only if
-// request i+1 wrote into them (same root segment); the log records of the next two eviction victims of every
-// replica are held in registers; all stores are fire-and-forget.
+// The request loop is one dependent chain per replay with one wavefront per SIMD, so the kernel is arranged
+// around latency, not bandwidth: a batch of 64 requests is staged at once (scalars in registers, segment
+// references in LDS); every lane is one replica and keeps that replica's state (cursor, the next log
+// records, load signal, earliest-free slot) in its registers, updated with selects rather than branches;
+// the rows of request i+1 and one log record per replica are requested right after the wait for the rows of
+// request i, so that an iteration has a single point where it waits for memory; stores are fire-and-forget.
 #pragma once
-#include <type_traits>
-
 #include "device_common.h"
 #include "internal.h"
 
@@ -66,12 +66,24 @@ __host__ __device__ inline size_t replay_segments_lds_bytes(int R, int B) {   //
     return Queues::bytes(R, B);
 }
 
-// Rows of one request's first SEG_CHUNK segments as seen by this lane (= replica), with the segments' end
-// positions (the same in every lane).
+// Rows of one request's first SEG_CHUNK segments as seen by this lane (= replica), with the segments' ids
+// and end positions (the same in every lane).  Entries past the request's last segment have end = n (empty
+// segments) and cell = -1.
 struct RowSet {
     int32_t cell[SEG_CHUNK];
     int end[SEG_CHUNK];
+    int id[SEG_CHUNK];
 };
+
+// Cached blocks of one segment [pos, end) whose row cell holds rl, against a cursor (c_r, c_k): all of them
+// if a later request than the cursor's touched it last, those below the cursor position if the cursor's
+// request did, none otherwise.  (A never-touched cell, -1, can only tie with the initial cursor (-1, 0).)
+__device__ __forceinline__ int cached_in(int32_t rl, int pos, int end, int c_r, int c_k) {
+    const int len = end - pos;
+    int part = c_k - pos;
+    part = part < 0 ? 0 : (part > len ? len : part);
+    return rl > c_r ? len : (rl == c_r ? part : 0);
+}
 
 __global__ void __launch_bounds__(WAVE) replay_segments_kernel(SegArgs a) {
     extern __shared__ __align__(16) unsigned char lds_raw[];
@@ -80,9 +92,10 @@ __global__ void __launch_bounds__(WAVE) replay_segments_kernel(SegArgs a) {
     const int p = blockIdx.x;
     const int R = a.R, B = a.B;
     const int64_t N = a.N;
+    const int C = (int)a.C;
 
     Queues Q;
-    Q.carve(lds_raw, R, B);
+    Q.carve(lds_raw, R, B, lane);
     Q.init(lane);
     for (int x = lane; x < SEG_CHUNK; x += WAVE) stage[SEG_STAGE + x] = SegRef{0, 0};
     __syncthreads();
@@ -93,33 +106,57 @@ __global__ void __launch_bounds__(WAVE) replay_segments_kernel(SegArgs a) {
     const double sc = a.scale[p];
     const double my_rtt = lane < R ? a.rtt[lane] : 0.0;
 
-    // Per-replica eviction state, held by lane = replica.  Blocks last touched by a request before cur_r, or
-    // by cur_r at positions >= cur_k, are evicted; cur_own is where cur_r's owned suffix starts.  nx_* is
-    // the log record after cur_r and n2_* the one after that (kept as the raw 64-bit word so that the load
-    // that fetches it is not waited for until it is needed; changes made to that record meanwhile are kept
-    // beside it in n2_own / n2_next and override the loaded fields).  tail_r is the youngest request routed
-    // here and my_live the number of blocks cached on the replica.
+    // Per-replica eviction state, held by lane = replica.
+    //   cursor: blocks last touched by a request before cur_r, or by cur_r at positions >= cur_k, are
+    //   evicted; cur_own is where cur_r's owned suffix starts.
+    //   nx_*, n2_*: the next two records of the replica's log that still own blocks (r < 0: empty).
+    //   fill_r: the record after the last one held here, or -1 when that one is the youngest of the log.
+    //   pend_*: a record being fetched (its load is only waited for one iteration later); changes made to
+    //   it meanwhile are kept in pend_own / pend_next and override the loaded fields.
     int cur_r = -1, cur_k = 0, cur_own = 0;
     int nx_r = -1, nx_n = 0, nx_own = 0;
-    int n2_r = -1, n2_own = -1, n2_next = -1;
-    unsigned long long n2_raw = 0;
-    int tail_r = -1;
-    int my_live = 0;
+    int n2_r = -1, n2_n = 0, n2_own = 0;
+    int fill_r = -1;
+    int pend_r = -1, pend_own = -1, pend_next = -1;
+    unsigned long long pend_raw = 0;
+    int tail_r = -1;          // youngest request routed to this replica
+    int my_live = 0;          // blocks cached on this replica
 
     int32_t* const last = a.last + (size_t)p * a.nseg * R;
     LogRec* const log = a.log + (size_t)p * N;
     unsigned long long* const log64 = reinterpret_cast<unsigned long long*>(log);
     Rec* const rec = a.rec + (size_t)p * N;
 
-    // cached blocks of one segment [pos, end) whose row cell holds rl, against a cursor (c_r, c_k)
-    auto cached_in = [](int32_t rl, int pos, int end, int c_r, int c_k) -> int {
-        const int len = end - pos;
-        if (rl > c_r) return len;
-        if (rl == c_r && rl >= 0) {
-            const int c = c_k - pos;
-            return c < 0 ? 0 : (c > len ? len : c);
+    // the fetched record becomes usable: dropped if it owns nothing, else queued behind nx / n2
+    auto take_pending = [&]() {
+        if (pend_r >= 0) {
+            const int n = (int)(pend_raw >> 48);
+            const int own_mem = (int)((pend_raw >> 32) & 0xFFFF);
+            const int own = pend_own > own_mem ? pend_own : own_mem;
+            const int next = pend_next >= 0 ? pend_next : (int)(unsigned int)pend_raw;
+            if (own < n) {
+                if (nx_r < 0) {
+                    nx_r = pend_r;
+                    nx_n = n;
+                    nx_own = own;
+                } else {
+                    n2_r = pend_r;
+                    n2_n = n;
+                    n2_own = own;
+                }
+            }
+            fill_r = next;
+            pend_r = -1;
         }
-        return 0;
+    };
+    // fetch the next record of the log if there is room for it
+    auto issue_fill = [&]() {
+        if (pend_r < 0 && fill_r >= 0 && n2_r < 0) {
+            pend_r = fill_r;
+            pend_own = -1;
+            pend_next = -1;
+            pend_raw = ld(&log64[fill_r]);
+        }
     };
 
     int64_t r0 = 0;
@@ -140,250 +177,268 @@ __global__ void __launch_bounds__(WAVE) replay_segments_kernel(SegArgs a) {
         const int m_a0 = (int)(my_j0 - J0);
         const int m_s = (int)(my_j1 - my_j0);
         const SegRef* const gref = a.seg + J0;
+        int m_n = 0, m_root = -1;       // blocks of the request; its first segment (the root of its tree)
         if (staged) {
             const int cnt = __builtin_amdgcn_readlane(m_a0 + m_s, nb - 1);
             for (int x = lane; x < cnt; x += WAVE) stage[x] = gref[x];
-        }
-        __syncthreads();
-        int m_n = 0, m_root = -1;       // blocks of the request; its first segment (the root of its tree)
-        if (m_s > 0 && lane < nb) {
-            m_n = staged ? stage[m_a0 + m_s - 1].end : gref[m_a0 + m_s - 1].end;
-            m_root = staged ? stage[m_a0].id : gref[m_a0].id;
+            __syncthreads();
+            if (m_s > 0 && lane < nb) {
+                m_n = stage[m_a0 + m_s - 1].end;
+                m_root = stage[m_a0].id;
+            }
+        } else if (m_s > 0 && lane == 0) {
+            m_n = gref[m_s - 1].end;
+            m_root = gref[0].id;
         }
 
         int o_route = 0, o_hit = 0;
         double o_ttft = 0.0, o_e2e = 0.0;
 
-        // requests the rows of the first segments of request i of the batch (staged batches only)
-        auto request_rows = [&](int i, RowSet& w) {
+        // requests the rows of the first SEG_CHUNK segments of request i of the batch
+        auto request_rows = [&](int i, auto ref, RowSet& w) {
             const int a0 = __builtin_amdgcn_readlane(m_a0, i);
             const int s = __builtin_amdgcn_readlane(m_s, i);
+            const int n = __builtin_amdgcn_readlane(m_n, i);
             SegRef sr[SEG_CHUNK];
 #pragma unroll
-            for (int k = 0; k < SEG_CHUNK; ++k) sr[k] = stage[a0 + k];
+            for (int k = 0; k < SEG_CHUNK; ++k) sr[k] = ref(a0 + k, k < s);
 #pragma unroll
             for (int k = 0; k < SEG_CHUNK; ++k) {
-                w.cell[k] = -1;
-                w.end[k] = sr[k].end;
-                if (k < s && lane < R) w.cell[k] = ld(&last[(size_t)sr[k].id * R + lane]);
+                const bool in = k < s;
+                w.id[k] = in ? sr[k].id : 0;
+                w.end[k] = in ? sr[k].end : n;
             }
+            if (lane < R) {
+#pragma unroll
+                for (int k = 0; k < SEG_CHUNK; ++k) w.cell[k] = ld(&last[(size_t)w.id[k] * R + lane]);
+            }
+#pragma unroll
+            for (int k = 0; k < SEG_CHUNK; ++k) w.cell[k] = (k < s && lane < R) ? w.cell[k] : -1;
         };
 
-        // Processes request i of the batch.  `mine` holds its rows when PRELOADED; `other` holds the rows of
-        // request i+1 and is refreshed if this request writes into them.
-        auto process = [&](int i, auto ref, auto preloaded, RowSet& mine, RowSet& other) {
-            constexpr bool PRELOADED = decltype(preloaded)::value;
+        // Processes request i of the batch.  `mine` holds the rows of its first segments; `other` receives
+        // those of request i+1.
+        auto process = [&](int i, auto ref, RowSet& mine, RowSet& other) {
             const int64_t r = r0 + i;
             const double t = readlane_f64(m_t, i);
-            const int64_t L = __builtin_amdgcn_readlane(m_L, i);
-            const int64_t O = __builtin_amdgcn_readlane(m_O, i);
+            const int L = __builtin_amdgcn_readlane(m_L, i);
+            const int O = __builtin_amdgcn_readlane(m_O, i);
             const int a0 = __builtin_amdgcn_readlane(m_a0, i);
             const int s = __builtin_amdgcn_readlane(m_s, i);
             const int n = __builtin_amdgcn_readlane(m_n, i);
 
-            Q.retire(t, rec, lane);
+            Q.retire(t, rec);
 
-            // ---- prefix match: lane = replica
+            // ---- prefix match: lane = replica.  Also notes, for the ownership update below, how far the
+            // cached prefix reaches on this replica (last cached segment k_last, its end) and whether all
+            // cached segments had the same previous owner.
             int my_m = 0;
-            bool open = lane < R;
+            bool open = true;
             int pos = 0;
-            if (PRELOADED) {
+            int k_end = 0;              // end position of the last segment with cached blocks
+            bool one_owner = true;
 #pragma unroll
-                for (int k = 0; k < SEG_CHUNK; ++k) {
-                    if (k < s) {
-                        if (open) {
-                            const int cnt = cached_in(mine.cell[k], pos, mine.end[k], cur_r, cur_k);
-                            my_m += cnt;
-                            open = cnt == mine.end[k] - pos;
-                        }
-                        pos = mine.end[k];
-                    }
-                }
+            for (int k = 0; k < SEG_CHUNK; ++k) {
+                const int cnt = cached_in(mine.cell[k], pos, mine.end[k], cur_r, cur_k);
+                const bool some = open && cnt > 0;
+                my_m += some ? cnt : 0;
+                k_end = some ? mine.end[k] : k_end;
+                one_owner = one_owner && (!some || mine.cell[k] == mine.cell[0]);
+                open = open && cnt == mine.end[k] - pos;
+                pos = mine.end[k];
             }
-            if ((!PRELOADED || s > SEG_CHUNK) && __ballot(open) != 0) {
-                for (int c0 = PRELOADED ? SEG_CHUNK : 0; c0 < s; c0 += SEG_CHUNK) {
+            bool deep = false;          // the match went past the preloaded segments
+            if (s > SEG_CHUNK && __ballot(open && lane < R) != 0) {
+                deep = true;
+                for (int c0 = SEG_CHUNK; c0 < s; c0 += SEG_CHUNK) {
                     int32_t cell[SEG_CHUNK];
                     int send[SEG_CHUNK];
 #pragma unroll
                     for (int k = 0; k < SEG_CHUNK; ++k) {
                         cell[k] = -1;
-                        send[k] = 0;
+                        send[k] = pos;
                         if (c0 + k < s) {
-                            const SegRef sr = ref(a0 + c0 + k);
+                            const SegRef sr = ref(a0 + c0 + k, true);
                             send[k] = sr.end;
-                            if (open) cell[k] = ld(&last[(size_t)sr.id * R + lane]);
+                            if (open && lane < R) cell[k] = ld(&last[(size_t)sr.id * R + lane]);
                         }
                     }
 #pragma unroll
                     for (int k = 0; k < SEG_CHUNK; ++k) {
                         if (c0 + k < s) {
-                            if (open) {
-                                const int cnt = cached_in(cell[k], pos, send[k], cur_r, cur_k);
-                                my_m += cnt;
-                                open = cnt == send[k] - pos;
-                            }
+                            const int cnt = cached_in(cell[k], pos, send[k], cur_r, cur_k);
+                            my_m += open ? cnt : 0;
+                            open = open && cnt == send[k] - pos;
                             pos = send[k];
                         }
                     }
-                    if (__ballot(open) == 0) break;
+                    if (__ballot(open && lane < R) == 0) break;
                 }
             }
 
+            // ---- the single point of the iteration that waited for memory is behind us: the record fetched
+            // during the previous iteration becomes usable, and the loads for the next iteration go out
+            take_pending();
+            if (i + 1 < nb) request_rows(i + 1, ref, other);
+            issue_fill();
+
             // ---- score (Eq. 3) and lowest-index minimum
-            int64_t my_u = 0;
-            double my_score = INFINITY;
-            if (lane < R) {
-                int64_t hit_tok = (int64_t)a.block_tokens * my_m;
-                if (hit_tok > L) hit_tok = L;
-                my_u = L - hit_tok;
-                my_score = eq3_score(w_rtt, w_prefill, w_queue, my_rtt, a.a_pf, my_u, Q.my_q);
-            }
+            int hit_tok = a.block_tokens * my_m;           // block_tokens * blocks fits: both are below 2^16
+            hit_tok = hit_tok > L ? L : hit_tok;
+            const int my_u = L - hit_tok;
+            const double my_score = eq3_score(w_rtt, w_prefill, w_queue, my_rtt, a.a_pf, my_u, Q.my_q);
             const int best = wave_argmin(my_score, lane, R).idx;
+            const bool is_best = lane == best;
             const int m_best = __builtin_amdgcn_readlane(my_m, best);
 
             // ---- ownership: the segments this request takes over on the chosen replica stop belonging to
             // their previous requests.  Along the path the previous owners form runs; each run moves its
             // owner's `own` to the end of the run.  Only cached segments matter (evicted ones belong to
             // requests the cursor has passed, or to the cursor request beyond its position).
+            auto disown = [&](int owner, int end) {       // lane `best`: owner's owned suffix now starts at end
+                st(&log[owner].own, (uint16_t)end);
+                cur_own = owner == cur_r ? end : cur_own;
+                nx_own = owner == nx_r ? end : nx_own;
+                n2_own = owner == n2_r ? end : n2_own;
+                pend_own = owner == pend_r ? end : pend_own;
+            };
             if (m_best > 0) {
-                const int cb_r = __builtin_amdgcn_readlane(cur_r, best), cb_k = __builtin_amdgcn_readlane(cur_k, best);
-                int run_owner = -1, run_end = 0, vpos = 0;
-                auto flush = [&]() {
-                    if (run_owner >= 0) {
-                        if (lane == 0) st(&log[run_owner].own, (uint16_t)run_end);
-                        if (lane == best) {
-                            if (run_owner == cur_r) cur_own = run_end;
-                            if (run_owner == nx_r) nx_own = run_end;
-                            if (run_owner == n2_r) n2_own = run_end;
-                        }
-                    }
-                };
-                auto visit = [&](int32_t rl, int end) -> bool {      // returns false once the prefix ends
-                    const int cnt = cached_in(rl, vpos, end, cb_r, cb_k);
-                    const bool full = cnt == end - vpos;
-                    if (cnt > 0) {
-                        if (rl != run_owner) {
-                            flush();
-                            run_owner = rl;
-                        }
-                        run_end = end;
-                    }
-                    vpos = end;
-                    return full;
-                };
-                if (PRELOADED && s <= SEG_CHUNK) {
-                    bool go = true;
-#pragma unroll
-                    for (int k = 0; k < SEG_CHUNK; ++k) {
-                        if (go && k < s) {
-                            const int32_t rl = __builtin_amdgcn_readlane(mine.cell[k], best);
-                            const int end = __builtin_amdgcn_readfirstlane(mine.end[k]);
-                            go = visit(rl, end);
-                        }
-                    }
+                const bool simple = !deep && __builtin_amdgcn_readlane((int)one_owner, best) != 0;
+                if (simple) {
+                    if (is_best) disown(mine.cell[0], k_end);
                 } else {
+                    // several previous owners, or a prefix longer than the preloaded rows: walk it
+                    const int cb_r = __builtin_amdgcn_readlane(cur_r, best);
+                    const int cb_k = __builtin_amdgcn_readlane(cur_k, best);
+                    int run_owner = -1, run_end = 0, vpos = 0;
                     for (int j = 0; j < s; ++j) {
-                        const SegRef sr = ref(a0 + j);
-                        if (!visit(ld(&last[(size_t)sr.id * R + best]), sr.end)) break;
+                        const SegRef sr = ref(a0 + j, true);
+                        const int32_t rl = ld(&last[(size_t)sr.id * R + best]);
+                        const int cnt = cached_in(rl, vpos, sr.end, cb_r, cb_k);
+                        if (cnt > 0) {
+                            if (rl != run_owner) {
+                                if (run_owner >= 0 && is_best) disown(run_owner, run_end);
+                                run_owner = rl;
+                            }
+                            run_end = sr.end;
+                        }
+                        if (cnt != sr.end - vpos) break;
+                        vpos = sr.end;
                     }
+                    if (run_owner >= 0 && is_best) disown(run_owner, run_end);
                 }
-                flush();
             }
 
             // ---- cache update: every segment of the request is now last touched by r on the chosen replica
-            for (int base = 0; base < s; base += WAVE) {
-                const int j = base + lane;
-                if (j < s) st(&last[(size_t)ref(a0 + j).id * R + best], (int32_t)r);
+            {
+                int my_id = 0;
+#pragma unroll
+                for (int k = 0; k < SEG_CHUNK; ++k) my_id = lane == k ? mine.id[k] : my_id;
+                if (lane < s && lane < SEG_CHUNK) st(&last[(size_t)my_id * R + best], (int32_t)r);
+                for (int j = SEG_CHUNK + lane; j < s; j += WAVE)
+                    st(&last[(size_t)ref(a0 + j, true).id * R + best], (int32_t)r);
             }
-            // ---- log: append r to the chosen replica's list of routed requests
-            const unsigned long long fresh = 0xFFFFFFFFull | ((unsigned long long)n << 48);   // next -1, own 0, n
-            if (lane == 0) st(&log64[r], fresh);
-            if (lane == best) {
-                if (tail_r >= 0) st(&log[tail_r].next, (int32_t)r);
-                if (tail_r < 0) {
-                    cur_r = (int)r;
-                    cur_k = n;
-                    cur_own = 0;
-                } else if (cur_r == tail_r) {
-                    nx_r = (int)r;
-                    nx_n = n;
-                    nx_own = 0;
-                } else if (nx_r == tail_r) {
-                    n2_r = (int)r;               // record known without a load: own 0, next none
-                    n2_raw = fresh;
-                    n2_own = -1;
-                    n2_next = -1;
-                } else if (n2_r == tail_r) {
-                    n2_next = (int)r;
-                }
-                tail_r = (int)r;
 
-                // ---- eviction: move the cursor forward until the cache fits
-                if (a.C > 0) {
-                    my_live += n - m_best;
-                    if (my_live > a.C) {
-                        int E = my_live - (int)a.C;
-                        for (;;) {
-                            const int avail = cur_k - cur_own;
-                            if (avail >= E) {
-                                cur_k -= E;
-                                E = 0;
-                                break;
-                            }
-                            if (avail > 0) E -= avail;
-                            if (nx_r < 0) break;      // cannot happen while E > 0; bounds the loop regardless
-                            cur_r = nx_r;
-                            cur_k = nx_n;
-                            cur_own = nx_own;
-                            nx_r = n2_r;
-                            if (nx_r >= 0) {
-                                nx_n = (int)(n2_raw >> 48);
-                                nx_own = n2_own >= 0 ? n2_own : (int)((n2_raw >> 32) & 0xFFFF);
-                                n2_r = n2_next >= 0 ? n2_next : (int)(unsigned int)n2_raw;
-                                n2_own = -1;
-                                n2_next = -1;
-                                if (n2_r >= 0) n2_raw = ld(&log64[n2_r]);
-                            }
-                        }
-                        my_live = (int)a.C + E;
+            // ---- log and eviction, in the chosen replica's lane
+            if (is_best) {
+                st(&log64[r], 0xFFFFFFFFull | ((unsigned long long)n << 48));      // next -1, own 0, n
+                if (tail_r >= 0) st(&log[tail_r].next, (int32_t)r);
+            }
+            {
+                // r is now the youngest record of the chosen replica's log
+                const bool first = is_best && tail_r < 0;
+                const bool to_pend = is_best && pend_r >= 0 && pend_r == tail_r;
+                const bool to_fill = is_best && !first && !to_pend && pend_r < 0 && fill_r < 0;
+                cur_r = first ? (int)r : cur_r;
+                cur_k = first ? n : cur_k;
+                cur_own = first ? 0 : cur_own;
+                pend_next = to_pend ? (int)r : pend_next;
+                fill_r = to_fill ? (int)r : fill_r;
+                tail_r = is_best ? (int)r : tail_r;
+
+                // eviction: move the cursor forward until the cache fits.  Up to two steps come from the
+                // records held in registers; more (rare) are fetched on the spot.
+                my_live += (is_best && C > 0) ? n - m_best : 0;
+                int E = (is_best && C > 0) ? my_live - C : 0;
+                E = E > 0 ? E : 0;
+                my_live -= E;
+#pragma unroll
+                for (int step = 0; step < 3; ++step) {
+                    int avail = cur_k - cur_own;
+                    avail = avail > 0 ? avail : 0;
+                    const int take = avail < E ? avail : E;
+                    cur_k -= take;
+                    E -= take;
+                    if (step < 2) {
+                        const bool adv = E > 0 && nx_r >= 0;
+                        cur_r = adv ? nx_r : cur_r;
+                        cur_k = adv ? nx_n : cur_k;
+                        cur_own = adv ? nx_own : cur_own;
+                        nx_r = adv ? n2_r : nx_r;
+                        nx_n = adv ? n2_n : nx_n;
+                        nx_own = adv ? n2_own : nx_own;
+                        n2_r = adv ? -1 : n2_r;
                     }
+                }
+                if (__ballot(E > 0) != 0) {
+                    while (E > 0) {       // only the chosen replica's lane can be here
+                        if (nx_r < 0) {
+                            if (pend_r < 0) {
+                                if (fill_r < 0) break;      // cannot happen while E > 0; bounds the loop
+                                issue_fill();
+                            }
+                            take_pending();
+                            continue;
+                        }
+                        cur_r = nx_r;
+                        cur_k = nx_n;
+                        cur_own = nx_own;
+                        nx_r = n2_r;
+                        nx_n = n2_n;
+                        nx_own = n2_own;
+                        n2_r = -1;
+                        int avail = cur_k - cur_own;
+                        avail = avail > 0 ? avail : 0;
+                        const int take = avail < E ? avail : E;
+                        cur_k -= take;
+                        E -= take;
+                    }
+                    my_live += E;         // nothing left to evict (unreachable, kept consistent)
+                }
+            }
+
+            // ---- the rows of request i+1 were requested before this request's stores: if it continues the
+            // same tree, the cells this request just wrote are patched into them (common prefix of the paths)
+            if (i + 1 < nb && s > 0 && __builtin_amdgcn_readlane(m_root, i + 1) == __builtin_amdgcn_readlane(m_root, i)) {
+                bool common = true;
+#pragma unroll
+                for (int k = 0; k < SEG_CHUNK; ++k) {
+                    common = common && k < s && other.id[k] == mine.id[k] && other.end[k] == mine.end[k];
+                    other.cell[k] = (common && is_best) ? (int32_t)r : other.cell[k];
                 }
             }
 
             // ---- service on the chosen replica, outputs (kept in registers until the batch ends)
             double ttft, e2e;
             Q.serve(r, best, t, my_rtt, my_u, L, O, a.a_pf, a.a_dec, rec, lane, &ttft, &e2e);
-            if (lane == i) {
-                o_route = best;
-                o_hit = m_best;
-                o_ttft = ttft;
-                o_e2e = e2e;
-            }
-
-            // ---- rows for later requests, requested after this request's stores (a wavefront's memory
-            // operations are performed in order): request i+2 into the set just consumed; request i+1 again
-            // if it shares this request's root segment, because its rows were requested before these stores.
-            if (PRELOADED) {
-                if (i + 1 < nb && s > 0 &&
-                    __builtin_amdgcn_readlane(m_root, i + 1) == __builtin_amdgcn_readlane(m_root, i))
-                    request_rows(i + 1, other);
-                if (i + 2 < nb) request_rows(i + 2, mine);
-            }
-            __syncthreads();
+            o_route = lane == i ? best : o_route;
+            o_hit = lane == i ? m_best : o_hit;
+            o_ttft = lane == i ? ttft : o_ttft;
+            o_e2e = lane == i ? e2e : o_e2e;
         };
 
+        RowSet A, Bset;
         if (staged) {
-            RowSet A, Bset;
-            request_rows(0, A);
-            if (nb > 1) request_rows(1, Bset);
-            const auto from_stage = [&](int x) -> SegRef { return stage[x]; };
+            const auto from_stage = [&](int x, bool) -> SegRef { return stage[x]; };
+            request_rows(0, from_stage, A);
             for (int i = 0; i < nb; i += 2) {
-                process(i, from_stage, std::true_type{}, A, Bset);
-                if (i + 1 < nb) process(i + 1, from_stage, std::true_type{}, Bset, A);
+                process(i, from_stage, A, Bset);
+                if (i + 1 < nb) process(i + 1, from_stage, Bset, A);
             }
         } else {
-            RowSet A, Bset;
-            process(0, [&](int x) -> SegRef { return gref[x]; }, std::false_type{}, A, Bset);
+            const auto from_global = [&](int x, bool in) -> SegRef { return in ? gref[x] : SegRef{0, 0}; };
+            request_rows(0, from_global, A);
+            process(0, from_global, A, Bset);
         }
         if (lane < nb) {
             const size_t o = (size_t)p * N + r0 + lane;
