@@ -57,6 +57,8 @@ int make_plan(const gorgo_trace* t, const gorgo_model* m, int32_t P, const gorgo
     const bool few = (int64_t)t->seg.size() <= 16 * (t->N > 0 ? t->N : 1);
     pl->path = mode == PATH_SEGMENTS || (mode == PATH_AUTO && seg_ok && few) ? PATH_SEGMENTS : PATH_BLOCKS;
     pl->nseg = t->n_segments;
+    if (pl->path == PATH_SEGMENTS && (uint64_t)(pl->nseg > 0 ? pl->nseg : 1) * (uint64_t)m->R * 4u >= (1ull << 32))
+        return fail(GORGO_ERR_INVALID_ARG, "segment rows of one replay exceed 4 GiB; use the block-table formulation");
     // A table must hold the cached blocks plus the blocks of the request being inserted, with room to
     // spare: the replay compacts a table once 7/8 of its slots have been used.
     const int64_t d = t->max_distinct;

@@ -123,6 +123,12 @@ __global__ void __launch_bounds__(WAVE) replay_segments_kernel(SegArgs a) {
     int my_live = 0;          // blocks cached on this replica
 
     int32_t* const last = a.last + (size_t)p * a.nseg * R;
+    // this lane's cell of a segment's row; rows of one replay span less than 4 GiB (checked by the host)
+    const unsigned lane_off = (unsigned)(lane < R ? lane : 0) * 4u;
+    const unsigned row_bytes = (unsigned)R * 4u;
+    auto cell_at = [&](int seg_id) -> int32_t* {
+        return reinterpret_cast<int32_t*>(reinterpret_cast<char*>(last) + ((unsigned)seg_id * row_bytes + lane_off));
+    };
     LogRec* const log = a.log + (size_t)p * N;
     unsigned long long* const log64 = reinterpret_cast<unsigned long long*>(log);
     Rec* const rec = a.rec + (size_t)p * N;
@@ -199,21 +205,20 @@ __global__ void __launch_bounds__(WAVE) replay_segments_kernel(SegArgs a) {
             const int a0 = __builtin_amdgcn_readlane(m_a0, i);
             const int s = __builtin_amdgcn_readlane(m_s, i);
             const int n = __builtin_amdgcn_readlane(m_n, i);
-            SegRef sr[SEG_CHUNK];
-#pragma unroll
-            for (int k = 0; k < SEG_CHUNK; ++k) sr[k] = ref(a0 + k, k < s);
 #pragma unroll
             for (int k = 0; k < SEG_CHUNK; ++k) {
-                const bool in = k < s;
-                w.id[k] = in ? sr[k].id : 0;
-                w.end[k] = in ? sr[k].end : n;
-            }
-            if (lane < R) {
-#pragma unroll
-                for (int k = 0; k < SEG_CHUNK; ++k) w.cell[k] = ld(&last[(size_t)w.id[k] * R + lane]);
+                w.cell[k] = -1;
+                w.id[k] = -1;
+                w.end[k] = n;
             }
 #pragma unroll
-            for (int k = 0; k < SEG_CHUNK; ++k) w.cell[k] = (k < s && lane < R) ? w.cell[k] : -1;
+            for (int k = 0; k < SEG_CHUNK; ++k) {
+                if (k >= s) break;
+                const SegRef sr = ref(a0 + k, true);
+                w.id[k] = sr.id;
+                w.end[k] = sr.end;
+                w.cell[k] = ld(cell_at(sr.id));          // lanes beyond R read a neighbouring cell, unused
+            }
         };
 
         // Processes request i of the batch.  `mine` holds the rows of its first segments; `other` receives
@@ -239,6 +244,7 @@ __global__ void __launch_bounds__(WAVE) replay_segments_kernel(SegArgs a) {
             bool one_owner = true;
 #pragma unroll
             for (int k = 0; k < SEG_CHUNK; ++k) {
+                if (k >= s) break;
                 const int cnt = cached_in(mine.cell[k], pos, mine.end[k], cur_r, cur_k);
                 const bool some = open && cnt > 0;
                 my_m += some ? cnt : 0;
@@ -260,7 +266,7 @@ __global__ void __launch_bounds__(WAVE) replay_segments_kernel(SegArgs a) {
                         if (c0 + k < s) {
                             const SegRef sr = ref(a0 + c0 + k, true);
                             send[k] = sr.end;
-                            if (open && lane < R) cell[k] = ld(&last[(size_t)sr.id * R + lane]);
+                            if (open && lane < R) cell[k] = ld(cell_at(sr.id));
                         }
                     }
 #pragma unroll
