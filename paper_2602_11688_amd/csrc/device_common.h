@@ -100,7 +100,7 @@ struct Queues {
     int my_min_k;        // ... and its slot
     double f_min;        // earliest free time among this lane's slots (lowest slot on ties) ...
     int f_k;             // ... and its slot
-    int64_t my_q;        // outstanding tokens of replica = lane
+    double my_q;         // outstanding tokens of replica = lane (an integer below 2^53, exact in fp64)
 
     static __host__ __device__ size_t bytes(int R, int B) {
         return (size_t)R * ((B + 7) & ~7) * (8 * 3 + 4 * 5);
@@ -133,7 +133,7 @@ struct Queues {
         my_min_k = 0;
         f_min = 0.0;
         f_k = 0;
-        my_q = 0;
+        my_q = 0.0;
     }
 
     // Drop requests whose completion event has reached the proxy (done <= t).
@@ -141,7 +141,7 @@ struct Queues {
         while (__ballot(my_min <= t) != 0) {
             if (my_min <= t) {
                 const int s = base + my_min_k;
-                my_q -= h_tok[s];
+                my_q -= (double)h_tok[s];
                 const int d = depth[s];
                 if (d > 1) {
                     h_done[s] = s_done[s];
@@ -216,7 +216,7 @@ struct Queues {
             }
             tail[s] = (int32_t)r;
             depth[s] = d + 1;
-            my_q += L;
+            my_q += (double)L;
             // earliest-free slot of this replica again
             double fv = INFINITY;
             int fk = 0;
@@ -242,9 +242,9 @@ struct Queues {
 // Weighted score of Eq. 3 for one replica, in the fixed association (w_rtt*rtt + w_prefill*pf) + w_queue*qd
 // with every product and sum rounded on its own.
 __device__ __forceinline__ double eq3_score(double w_rtt, double w_prefill, double w_queue, double rtt, double a_pf,
-                                            int64_t uncached, int64_t outstanding) {
+                                            int uncached, double outstanding) {
     const double pf = a_pf * (double)uncached;
-    const double qd = a_pf * (double)outstanding;
+    const double qd = a_pf * outstanding;
     const double s_rtt = w_rtt * rtt;
     const double s_pf = w_prefill * pf;
     const double s_q = w_queue * qd;

@@ -339,7 +339,10 @@ __global__ void __launch_bounds__(WAVE) replay_segments_kernel(SegArgs a) {
             {
                 int my_id = 0;
 #pragma unroll
-                for (int k = 0; k < SEG_CHUNK; ++k) my_id = lane == k ? mine.id[k] : my_id;
+                for (int k = 0; k < SEG_CHUNK; ++k) {
+                    if (k >= s) break;
+                    my_id = lane == k ? mine.id[k] : my_id;
+                }
                 if (lane < s && lane < SEG_CHUNK) st(&last[(size_t)my_id * R + best], (int32_t)r);
                 for (int j = SEG_CHUNK + lane; j < s; j += WAVE)
                     st(&last[(size_t)ref(a0 + j, true).id * R + best], (int32_t)r);
@@ -368,25 +371,14 @@ __global__ void __launch_bounds__(WAVE) replay_segments_kernel(SegArgs a) {
                 int E = (is_best && C > 0) ? my_live - C : 0;
                 E = E > 0 ? E : 0;
                 my_live -= E;
-#pragma unroll
-                for (int step = 0; step < 3; ++step) {
-                    int avail = cur_k - cur_own;
-                    avail = avail > 0 ? avail : 0;
-                    const int take = avail < E ? avail : E;
-                    cur_k -= take;
-                    E -= take;
-                    if (step < 2) {
-                        const bool adv = E > 0 && nx_r >= 0;
-                        cur_r = adv ? nx_r : cur_r;
-                        cur_k = adv ? nx_n : cur_k;
-                        cur_own = adv ? nx_own : cur_own;
-                        nx_r = adv ? n2_r : nx_r;
-                        nx_n = adv ? n2_n : nx_n;
-                        nx_own = adv ? n2_own : nx_own;
-                        n2_r = adv ? -1 : n2_r;
-                    }
-                }
                 if (__ballot(E > 0) != 0) {
+                    {
+                        int avail = cur_k - cur_own;
+                        avail = avail > 0 ? avail : 0;
+                        const int take = avail < E ? avail : E;
+                        cur_k -= take;
+                        E -= take;
+                    }
                     while (E > 0) {       // only the chosen replica's lane can be here
                         if (nx_r < 0) {
                             if (pend_r < 0) {
@@ -427,10 +419,10 @@ __global__ void __launch_bounds__(WAVE) replay_segments_kernel(SegArgs a) {
             // ---- service on the chosen replica, outputs (kept in registers until the batch ends)
             double ttft, e2e;
             Q.serve(r, best, t, my_rtt, my_u, L, O, a.a_pf, a.a_dec, rec, lane, &ttft, &e2e);
-            o_route = lane == i ? best : o_route;
-            o_hit = lane == i ? m_best : o_hit;
-            o_ttft = lane == i ? ttft : o_ttft;
-            o_e2e = lane == i ? e2e : o_e2e;
+            if (a.route) o_route = lane == i ? best : o_route;
+            if (a.hit) o_hit = lane == i ? m_best : o_hit;
+            if (a.ttft) o_ttft = lane == i ? ttft : o_ttft;
+            if (a.e2e) o_e2e = lane == i ? e2e : o_e2e;
         };
 
         RowSet A, Bset;

@@ -178,6 +178,12 @@ int check_and_finish(gorgo_trace* t, const int64_t* hash_ids, int32_t block_toke
         if (n < 0) return fail(GORGO_ERR_INVALID_ARG, "blk_off decreases at request " + std::to_string(r));
         if (n > 65535) return fail(GORGO_ERR_INVALID_ARG, "more than 65535 blocks in request " + std::to_string(r));
     }
+    // the load signal (sum of input tokens in flight) is carried in fp64 and must stay an exact integer
+    int64_t total_tokens = 0;
+    for (int64_t r = 0; r < N; ++r) {
+        total_tokens += t->in_len[r];
+        if (total_tokens > ((int64_t)1 << 53)) return fail(GORGO_ERR_INVALID_ARG, "input tokens sum above 2^53");
+    }
     t->block_tokens = block_tokens;
     return preprocess(t, hash_ids);
 }
