@@ -134,12 +134,12 @@ __global__ void __launch_bounds__(WAVE) replay_segments_kernel(SegArgs a) {
     Rec* const rec = a.rec + (size_t)p * N;
 
     // the fetched record becomes usable: dropped if it owns nothing, else queued behind nx / n2
-    auto take_pending = [&]() {
+    auto take_pending = [&](unsigned long long raw) {
         if (pend_r >= 0) {
-            const int n = (int)(pend_raw >> 48);
-            const int own_mem = (int)((pend_raw >> 32) & 0xFFFF);
+            const int n = (int)(raw >> 48);
+            const int own_mem = (int)((raw >> 32) & 0xFFFF);
             const int own = pend_own > own_mem ? pend_own : own_mem;
-            const int next = pend_next >= 0 ? pend_next : (int)(unsigned int)pend_raw;
+            const int next = pend_next >= 0 ? pend_next : (int)(unsigned int)raw;
             if (own < n) {
                 if (nx_r < 0) {
                     nx_r = pend_r;
@@ -206,8 +206,7 @@ __global__ void __launch_bounds__(WAVE) replay_segments_kernel(SegArgs a) {
             const int s = __builtin_amdgcn_readlane(m_s, i);
             const int n = __builtin_amdgcn_readlane(m_n, i);
 #pragma unroll
-            for (int k = 0; k < SEG_CHUNK; ++k) {
-                w.cell[k] = -1;
+            for (int k = 0; k < SEG_CHUNK; ++k) {       // (cells past the last segment are never read)
                 w.id[k] = -1;
                 w.end[k] = n;
             }
@@ -284,7 +283,7 @@ __global__ void __launch_bounds__(WAVE) replay_segments_kernel(SegArgs a) {
 
             // ---- the single point of the iteration that waited for memory is behind us: the record fetched
             // during the previous iteration becomes usable, and the loads for the next iteration go out
-            take_pending();
+            take_pending(pend_raw);
             if (i + 1 < nb) request_rows(i + 1, ref, other);
             issue_fill();
 
@@ -381,11 +380,17 @@ __global__ void __launch_bounds__(WAVE) replay_segments_kernel(SegArgs a) {
                     }
                     while (E > 0) {       // only the chosen replica's lane can be here
                         if (nx_r < 0) {
+                            // fetch a record on the spot; pend_raw itself is only ever written by the
+                            // look-ahead fetch, so that its load is never waited for in here
+                            unsigned long long raw = pend_raw;
                             if (pend_r < 0) {
                                 if (fill_r < 0) break;      // cannot happen while E > 0; bounds the loop
-                                issue_fill();
+                                pend_r = fill_r;
+                                pend_own = -1;
+                                pend_next = -1;
+                                raw = ld(&log64[fill_r]);
                             }
-                            take_pending();
+                            take_pending(raw);
                             continue;
                         }
                         cur_r = nx_r;
