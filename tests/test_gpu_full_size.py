@@ -1,0 +1,58 @@
+"""GPU parity at the full size of the Large workload (R=32, N=1,000,000, P=1,024), in the launch
+configuration the benchmark times: one launch over all 1,024 candidates of the tuner's first generation.
+
+The oracle replays 34 of the candidates (the parent, the last one and 32 seeded picks) in full, one per host
+thread; every request of those replays is compared (routes and hit counts bit-exact, latencies to 1e-9
+relative), and so are their p95s, both from the launch that writes per-request outputs and from the
+p95-only launch of the benchmark."""
+from concurrent.futures import ThreadPoolExecutor
+
+import numpy as np
+import pytest
+
+import paper_2602_11688_amd as g
+from synth import tracegen as tg
+from tests.gpu_helpers import RTOL, load, oracle_eval
+
+pytestmark = [pytest.mark.gpu, pytest.mark.timeout(900)]
+
+
+def test_large_workload_sampled_replays_match_oracle():
+    import torch
+    wl = tg.config(5)
+    es_cfg = wl.es if wl.es else dict(tg.ES_DEFAULTS, P=wl.P, seed=tg.MASTER_SEED + 5)
+    P = es_cfg["P"]
+    assert (wl.R, wl.trace.N, P) == (32, 1_000_000, 1024)
+    model = g.Model(wl.R, wl.batch, wl.cache_blocks, wl.prefill_ms_per_token, wl.decode_ms_per_token)
+    h = load(wl.trace)
+    assert h.replay_path()["path"] == 2            # the formulation the benchmark runs
+    state = g.es_init(es_cfg["seed"])
+    params = g.es_propose(state, g.es_sample(es_cfg["seed"], 0, P))
+
+    rng = np.random.default_rng(20260211)
+    picks = sorted({0, P - 1} | set(rng.choice(np.arange(1, P - 1), 32, replace=False).tolist()))
+    assert len(picks) == 34
+    with ThreadPoolExecutor(16) as ex:             # ctypes releases the GIL: one oracle replay per thread
+        futs = {p: ex.submit(oracle_eval, wl.trace, model, wl.rtt_ms, params[p], 1.0) for p in picks}
+
+        # the p95-only launch keeps its latencies in the workspace, so its workspace also serves the other
+        lean = g.eval_population(h, model, wl.rtt_ms, params, 1.0, per_request=False)
+        torch.cuda.synchronize()
+        full = g.eval_population(h, model, wl.rtt_ms, params, 1.0, workspace=lean.workspace)
+        torch.cuda.synchronize()
+        assert torch.equal(full.p95_ttft_ms, lean.p95_ttft_ms) and torch.equal(full.p95_e2e_ms, lean.p95_e2e_ms)
+        p95_ttft = full.p95_ttft_ms.cpu().numpy()
+        p95_e2e = full.p95_e2e_ms.cpu().numpy()
+        assert np.isfinite(p95_ttft).all() and (p95_ttft > 0).all() and (p95_e2e >= p95_ttft).all()
+
+        for p in picks:
+            ref = futs[p].result()
+            route = full.route[p].cpu().numpy()
+            bad = np.nonzero(route != ref.route)[0]
+            assert bad.size == 0, f"replay {p}: first route mismatch at request {bad[0]} ({bad.size} in all)"
+            assert np.array_equal(full.hit_blocks[p].cpu().numpy(), ref.hit_blocks), f"replay {p}: hit counts"
+            np.testing.assert_allclose(full.ttft_ms[p].cpu().numpy(), ref.ttft_ms, rtol=RTOL, atol=0)
+            np.testing.assert_allclose(full.e2e_ms[p].cpu().numpy(), ref.e2e_ms, rtol=RTOL, atol=0)
+            assert abs(p95_ttft[p] - ref.p95_ttft_ms) <= RTOL * ref.p95_ttft_ms
+            assert abs(p95_e2e[p] - ref.p95_e2e_ms) <= RTOL * ref.p95_e2e_ms
+            print(f"replay {p}: {ref.route.size} requests equal, p95 TTFT {ref.p95_ttft_ms:.3f} ms", flush=True)
