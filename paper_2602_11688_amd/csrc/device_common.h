@@ -240,15 +240,24 @@ struct Queues {
 };
 
 // Weighted score of Eq. 3 for one replica, in the fixed association (w_rtt*rtt + w_prefill*pf) + w_queue*qd
-// with every product and sum rounded on its own.
-__device__ __forceinline__ double eq3_score(double w_rtt, double w_prefill, double w_queue, double rtt, double a_pf,
-                                            int uncached, double outstanding) {
+// with every product and sum rounded on its own.  The first two terms do not depend on the load signal and
+// can be formed before it is known.
+__device__ __forceinline__ double eq3_without_queue(double w_rtt, double w_prefill, double rtt, double a_pf,
+                                                    int uncached) {
     const double pf = a_pf * (double)uncached;
-    const double qd = a_pf * outstanding;
     const double s_rtt = w_rtt * rtt;
     const double s_pf = w_prefill * pf;
+    return s_rtt + s_pf;
+}
+__device__ __forceinline__ double eq3_with_queue(double rtt_and_prefill, double w_queue, double a_pf,
+                                                 double outstanding) {
+    const double qd = a_pf * outstanding;
     const double s_q = w_queue * qd;
-    return (s_rtt + s_pf) + s_q;
+    return rtt_and_prefill + s_q;
+}
+__device__ __forceinline__ double eq3_score(double w_rtt, double w_prefill, double w_queue, double rtt, double a_pf,
+                                            int uncached, double outstanding) {
+    return eq3_with_queue(eq3_without_queue(w_rtt, w_prefill, rtt, a_pf, uncached), w_queue, a_pf, outstanding);
 }
 
 // Index of the next request after `after` (exclusive) and before `limit` that was routed to `replica`, or

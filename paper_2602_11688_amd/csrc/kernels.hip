@@ -521,7 +521,7 @@ int launch_replay(const gorgo_trace* t, const Plan& pl, const double* d_rtt, con
         mark(1, s);
         if (pl.N > 0) {
             const size_t lds = replay_segments_lds_bytes(pl.R, pl.B);
-            hipLaunchKernelGGL(replay_segments_kernel, dim3((unsigned)pl.P), dim3(WAVE), lds, s, a);
+            hipLaunchKernelGGL(replay_segments_kernel, dim3((unsigned)pl.P), dim3(SEG_THREADS), lds, s, a);
             if ((e = hipGetLastError()) != hipSuccess) return hip_fail(e, "launch replay_segments_kernel");
         }
     } else {

@@ -15,12 +15,19 @@
 // record per logged request (next request on the replica, own, n) and never re-reads cells.  Records that
 // own nothing any more are dropped from the walk as soon as they are seen.
 //
-// The request loop is one dependent chain per replay with one wavefront per SIMD, so the kernel is arranged
-// around latency, not bandwidth: a batch of 64 requests is staged at once (scalars in registers, segment
-// references in LDS); every lane is one replica and keeps that replica's state (cursor, the next log
-// records, load signal, earliest-free slot) in its registers, updated with selects rather than branches;
-// the rows of request i+1 and one log record per replica are requested right after the wait for the rows of
-// request i, so that an iteration has a single point where it waits for memory; stores are fire-and-forget.
+// The request loop is one dependent chain per replay, and a lone wavefront issues about one instruction
+// every four to five cycles whatever its kind, so the kernel is arranged around instruction count and
+// latency, not bandwidth.  A replay is run by two wavefronts of one workgroup.  The cache wavefront keeps the
+// cache side (lane = replica: cursor, the next log records) in its registers, matches, scores, picks the
+// replica and updates rows and log; the queue wavefront keeps the queue side (lane = replica: load signal,
+// earliest completion; service slots in LDS), retires completed requests before every request and serves it
+// once the replica is known.  They meet twice per request through LDS: the queue wavefront publishes the load
+// signals of request r, the cache wavefront answers with the chosen replica and its uncached tokens.  The
+// queue wavefront has the shorter loop, so the cache wavefront normally finds the load signals waiting.
+// In the cache wavefront a batch of 64 requests is staged at once (scalars in registers, segment references
+// in LDS); the rows of request i+1 and one log record per replica are requested right after the wait for the
+// rows of request i, so that an iteration has a single point where it waits for memory; stores are
+// fire-and-forget.
 #pragma once
 #include "device_common.h"
 #include "internal.h"
@@ -61,6 +68,28 @@ struct SegArgs {
 
 constexpr int SEG_STAGE = 512;   // segment references of a 64-request batch staged in LDS
 constexpr int SEG_CHUNK = 8;     // segments of a request whose rows are loaded together
+constexpr int SEG_THREADS = 2 * WAVE;        // cache wavefront + queue wavefront
+constexpr int SEG_SPIN_LIMIT = 1 << 24;      // polls of a hand-over word before the replay is given up (~1 s)
+
+// Hand-over words between the two wavefronts of a replay, in LDS.  Every word carries the number of the
+// request it belongs to (r + 1, so that the initial zero matches nothing).  They are read and written with
+// relaxed workgroup-scope atomics on the LDS variable itself (so that they stay LDS instructions), with
+// LDS-only release / acquire fences between data and word.
+struct SegComm {
+    double q[WAVE];                   // load signal per replica, valid when seq_q == r + 1
+    unsigned seq_q;
+    int abandoned;                    // a wavefront gave up waiting: both leave, latencies are poisoned
+    unsigned long long choice;        // uncached tokens | (((r + 1) mod 2^26) << 6 | replica) << 32
+};
+
+__device__ __forceinline__ void lds_release() { __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local"); }
+__device__ __forceinline__ void lds_acquire() { __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local"); }
+
+// Orders the LDS accesses of one wavefront's lanes (the hardware executes them in program order).
+__device__ __forceinline__ void wave_sync() {
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
 
 __host__ __device__ inline size_t replay_segments_lds_bytes(int R, int B) {   // dynamic part
     return Queues::bytes(R, B);
@@ -85,25 +114,101 @@ __device__ __forceinline__ int cached_in(int32_t rl, int pos, int end, int c_r, 
     return rl > c_r ? len : (rl == c_r ? part : 0);
 }
 
-__global__ void __launch_bounds__(WAVE) replay_segments_kernel(SegArgs a) {
+// Queue wavefront of a replay: for every request, retire what has completed by its arrival, publish the load
+// signals, wait for the cache wavefront's choice, serve the request there.  Writes the latencies.
+__device__ __forceinline__ void queue_wave(const SegArgs& a, int p, int lane, unsigned char* lds_raw, SegComm* comm) {
+    const int R = a.R;
+    const int64_t N = a.N;
+    Queues Q;
+    Q.carve(lds_raw, R, a.B, lane);
+    Q.init(lane);
+    wave_sync();
+    const double sc = a.scale[p];
+    const double my_rtt = lane < R ? a.rtt[lane] : 0.0;
+    Rec* const rec = a.rec + (size_t)p * N;
+    bool dead = false;
+    for (int64_t r0 = 0; r0 < N && !dead; r0 += WAVE) {
+        const int nb = N - r0 < WAVE ? (int)(N - r0) : WAVE;
+        const int64_t rr = r0 + (lane < nb ? lane : nb - 1);
+        const double m_t = (double)a.ts[rr] * sc;          // time scale: gaps scale linearly
+        const int m_L = a.in_len[rr];
+        const int m_O = a.out_len[rr];
+        double o_ttft = 0.0, o_e2e = 0.0;
+        for (int i = 0; i < nb; ++i) {
+            const int64_t r = r0 + i;
+            const double t = readlane_f64(m_t, i);
+            const int L = __builtin_amdgcn_readlane(m_L, i);
+            const int O = __builtin_amdgcn_readlane(m_O, i);
+            Q.retire(t, rec);
+            st(&comm->q[lane], Q.my_q);
+            lds_release();
+            if (lane == 0) st(&comm->seq_q, (unsigned)(r + 1));
+            const unsigned want = (unsigned)(r + 1) & 0x3FFFFFFu;
+            unsigned hi, lo;
+            for (int spins = 0;; ++spins) {
+                const unsigned long long w = ld(&comm->choice);
+                hi = __builtin_amdgcn_readfirstlane((unsigned)(w >> 32));
+                lo = __builtin_amdgcn_readfirstlane((unsigned)w);
+                if ((hi >> 6) == want) break;
+                if (spins > SEG_SPIN_LIMIT || ld(&comm->abandoned) != 0) {
+                    dead = true;
+                    break;
+                }
+                __builtin_amdgcn_s_sleep(1);
+            }
+            if (dead) break;
+            const int best = (int)(hi & 63u);
+            double ttft, e2e;
+            Q.serve(r, best, t, my_rtt, (int64_t)(int)lo, L, O, a.a_pf, a.a_dec, rec, lane, &ttft, &e2e);
+            o_ttft = lane == i ? ttft : o_ttft;
+            o_e2e = lane == i ? e2e : o_e2e;
+        }
+        if (lane < nb && !dead) {
+            const size_t o = (size_t)p * N + r0 + lane;
+            if (a.ttft) a.ttft[o] = o_ttft;
+            if (a.e2e) a.e2e[o] = o_e2e;
+        }
+    }
+    if (dead) {
+        // the partner never answered (cannot happen unless the kernel is wrong): leave, and make sure nobody
+        // mistakes this replay's latencies for results
+        st(&comm->abandoned, 1);
+        for (int64_t x = lane; x < N; x += WAVE) {
+            if (a.ttft) a.ttft[(size_t)p * N + x] = NAN;
+            if (a.e2e) a.e2e[(size_t)p * N + x] = NAN;
+        }
+    }
+}
+
+__global__ void __launch_bounds__(SEG_THREADS) replay_segments_kernel(SegArgs a) {
     extern __shared__ __align__(16) unsigned char lds_raw[];
     __shared__ SegRef stage[SEG_STAGE + SEG_CHUNK];    // padded: whole chunks are read unconditionally
-    const int lane = threadIdx.x;
+    __shared__ SegComm comm;
+    const int lane = threadIdx.x & (WAVE - 1);
     const int p = blockIdx.x;
-    const int R = a.R, B = a.B;
+    const int R = a.R;
     const int64_t N = a.N;
     const int C = (int)a.C;
 
-    Queues Q;
-    Q.carve(lds_raw, R, B, lane);
-    Q.init(lane);
-    for (int x = lane; x < SEG_CHUNK; x += WAVE) stage[SEG_STAGE + x] = SegRef{0, 0};
+    if (threadIdx.x == 0) {
+        comm.seq_q = 0;
+        comm.abandoned = 0;
+        comm.choice = 0;
+    }
     __syncthreads();
+    if (threadIdx.x >= WAVE) {
+        queue_wave(a, p, lane, lds_raw, &comm);
+        return;
+    }
+    __builtin_amdgcn_s_setprio(3);      // the cache wavefront has the longer loop: it goes first at issue
+    bool dead = false;
+
+    for (int x = lane; x < SEG_CHUNK; x += WAVE) stage[SEG_STAGE + x] = SegRef{0, 0};
+    wave_sync();
 
     const double w_rtt = a.params[3 * (size_t)p + 0];
     const double w_prefill = a.params[3 * (size_t)p + 1];
     const double w_queue = a.params[3 * (size_t)p + 2];
-    const double sc = a.scale[p];
     const double my_rtt = lane < R ? a.rtt[lane] : 0.0;
 
     // Per-replica eviction state, held by lane = replica.
@@ -131,7 +236,6 @@ __global__ void __launch_bounds__(WAVE) replay_segments_kernel(SegArgs a) {
     };
     LogRec* const log = a.log + (size_t)p * N;
     unsigned long long* const log64 = reinterpret_cast<unsigned long long*>(log);
-    Rec* const rec = a.rec + (size_t)p * N;
 
     // the fetched record becomes usable: dropped if it owns nothing, else queued behind nx / n2
     auto take_pending = [&](unsigned long long raw) {
@@ -166,15 +270,13 @@ __global__ void __launch_bounds__(WAVE) replay_segments_kernel(SegArgs a) {
     };
 
     int64_t r0 = 0;
-    while (r0 < N) {
+    while (r0 < N && !dead) {
         // ---- stage a batch of up to 64 requests: per-request scalars in registers (lane = request), their
         // segment references in LDS.  The batch is cut where the references stop fitting; a single request
         // with more references than the stage holds is processed alone, reading them from global memory.
         const int nb0 = N - r0 < WAVE ? (int)(N - r0) : WAVE;
         const int64_t rr = r0 + (lane < nb0 ? lane : nb0 - 1);
-        const double m_t = (double)a.ts[rr] * sc;          // time scale: gaps scale linearly
         const int m_L = a.in_len[rr];
-        const int m_O = a.out_len[rr];
         const int64_t my_j0 = a.seg_off[rr], my_j1 = a.seg_off[rr + 1];
         const int64_t J0 = a.seg_off[r0];
         const int fit = __popcll(__ballot(lane < nb0 && my_j1 - J0 <= SEG_STAGE));   // a prefix of the lanes
@@ -187,7 +289,7 @@ __global__ void __launch_bounds__(WAVE) replay_segments_kernel(SegArgs a) {
         if (staged) {
             const int cnt = __builtin_amdgcn_readlane(m_a0 + m_s, nb - 1);
             for (int x = lane; x < cnt; x += WAVE) stage[x] = gref[x];
-            __syncthreads();
+            wave_sync();
             if (m_s > 0 && lane < nb) {
                 m_n = stage[m_a0 + m_s - 1].end;
                 m_root = stage[m_a0].id;
@@ -198,7 +300,6 @@ __global__ void __launch_bounds__(WAVE) replay_segments_kernel(SegArgs a) {
         }
 
         int o_route = 0, o_hit = 0;
-        double o_ttft = 0.0, o_e2e = 0.0;
 
         // requests the rows of the first SEG_CHUNK segments of request i of the batch
         auto request_rows = [&](int i, auto ref, RowSet& w) {
@@ -224,14 +325,10 @@ __global__ void __launch_bounds__(WAVE) replay_segments_kernel(SegArgs a) {
         // those of request i+1.
         auto process = [&](int i, auto ref, RowSet& mine, RowSet& other) {
             const int64_t r = r0 + i;
-            const double t = readlane_f64(m_t, i);
             const int L = __builtin_amdgcn_readlane(m_L, i);
-            const int O = __builtin_amdgcn_readlane(m_O, i);
             const int a0 = __builtin_amdgcn_readlane(m_a0, i);
             const int s = __builtin_amdgcn_readlane(m_s, i);
             const int n = __builtin_amdgcn_readlane(m_n, i);
-
-            Q.retire(t, rec);
 
             // ---- prefix match: lane = replica.  Also notes, for the ownership update below, how far the
             // cached prefix reaches on this replica (last cached segment k_last, its end) and whether all
@@ -290,11 +387,38 @@ __global__ void __launch_bounds__(WAVE) replay_segments_kernel(SegArgs a) {
             // ---- score (Eq. 3) and lowest-index minimum
             int hit_tok = a.block_tokens * my_m;           // block_tokens * blocks fits: both are below 2^16
             hit_tok = hit_tok > L ? L : hit_tok;
-            const int my_u = L - hit_tok;
-            const double my_score = eq3_score(w_rtt, w_prefill, w_queue, my_rtt, a.a_pf, my_u, Q.my_q);
+            int my_u = L - hit_tok;
+            // the load signals of this request come from the queue wavefront (normally already there);
+            // everything that does not need them is finished first, so that little is left between reading
+            // them and announcing the choice
+            const double score_rp = eq3_without_queue(w_rtt, w_prefill, my_rtt, a.a_pf, my_u);
+            asm volatile("" : "+v"(my_u), "+v"(my_m));
+            double score_rp_ready = score_rp;
+            asm volatile("" : "+v"(score_rp_ready));
+            double my_q;
+            for (int spins = 0;; ++spins) {
+                const unsigned seq = __builtin_amdgcn_readfirstlane(ld(&comm.seq_q));
+                lds_acquire();
+                my_q = ld(&comm.q[lane]);
+                if (seq == (unsigned)(r + 1)) break;
+                if (spins > SEG_SPIN_LIMIT || ld(&comm.abandoned) != 0) {
+                    dead = true;
+                    break;
+                }
+            }
+            if (dead) {
+                st(&comm.abandoned, 1);
+                return;
+            }
+            const double my_score = eq3_with_queue(score_rp_ready, w_queue, a.a_pf, my_q);
             const int best = wave_argmin(my_score, lane, R).idx;
             const bool is_best = lane == best;
             const int m_best = __builtin_amdgcn_readlane(my_m, best);
+            if (lane == 0) {
+                const unsigned u_best = (unsigned)__builtin_amdgcn_readlane(my_u, best);
+                const unsigned tag = (((unsigned)(r + 1) & 0x3FFFFFFu) << 6) | (unsigned)best;
+                st(&comm.choice, ((unsigned long long)tag << 32) | u_best);
+            }
 
             // ---- ownership: the segments this request takes over on the chosen replica stop belonging to
             // their previous requests.  Along the path the previous owners form runs; each run moves its
@@ -421,36 +545,30 @@ __global__ void __launch_bounds__(WAVE) replay_segments_kernel(SegArgs a) {
                 }
             }
 
-            // ---- service on the chosen replica, outputs (kept in registers until the batch ends)
-            double ttft, e2e;
-            Q.serve(r, best, t, my_rtt, my_u, L, O, a.a_pf, a.a_dec, rec, lane, &ttft, &e2e);
+            // ---- outputs of the cache side (kept in registers until the batch ends)
             if (a.route) o_route = lane == i ? best : o_route;
             if (a.hit) o_hit = lane == i ? m_best : o_hit;
-            if (a.ttft) o_ttft = lane == i ? ttft : o_ttft;
-            if (a.e2e) o_e2e = lane == i ? e2e : o_e2e;
         };
 
         RowSet A, Bset;
         if (staged) {
             const auto from_stage = [&](int x, bool) -> SegRef { return stage[x]; };
             request_rows(0, from_stage, A);
-            for (int i = 0; i < nb; i += 2) {
+            for (int i = 0; i < nb && !dead; i += 2) {
                 process(i, from_stage, A, Bset);
-                if (i + 1 < nb) process(i + 1, from_stage, Bset, A);
+                if (i + 1 < nb && !dead) process(i + 1, from_stage, Bset, A);
             }
         } else {
             const auto from_global = [&](int x, bool in) -> SegRef { return in ? gref[x] : SegRef{0, 0}; };
             request_rows(0, from_global, A);
             process(0, from_global, A, Bset);
         }
-        if (lane < nb) {
+        if (lane < nb && !dead) {
             const size_t o = (size_t)p * N + r0 + lane;
             if (a.route) a.route[o] = (uint8_t)o_route;
             if (a.hit) a.hit[o] = (uint16_t)o_hit;
-            if (a.ttft) a.ttft[o] = o_ttft;
-            if (a.e2e) a.e2e[o] = o_e2e;
         }
-        __syncthreads();
+        wave_sync();
         r0 += nb;
     }
 }
