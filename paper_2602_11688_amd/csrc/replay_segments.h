@@ -95,13 +95,13 @@ __host__ __device__ inline size_t replay_segments_lds_bytes(int R, int B) {   //
     return Queues::bytes(R, B);
 }
 
-// Rows of one request's first SEG_CHUNK segments as seen by this lane (= replica), with the segments' ids
-// and end positions (the same in every lane).  Entries past the request's last segment have end = n (empty
-// segments) and cell = -1.
+// Rows of one request's first SEG_CHUNK segments as seen by this lane (= replica), with the segments' end
+// positions (the same in every lane; entries past the request's last segment have end = n and no cell), and
+// the reference of segment k in lane k.
 struct RowSet {
     int32_t cell[SEG_CHUNK];
     int end[SEG_CHUNK];
-    int id[SEG_CHUNK];
+    SegRef of_lane;
 };
 
 // Cached blocks of one segment [pos, end) whose row cell holds rl, against a cursor (c_r, c_k): all of them
@@ -301,23 +301,27 @@ __global__ void __launch_bounds__(SEG_THREADS) replay_segments_kernel(SegArgs a)
 
         int o_route = 0, o_hit = 0;
 
-        // requests the rows of the first SEG_CHUNK segments of request i of the batch
+        // requests the rows of the first SEG_CHUNK segments of request i of the batch.  The references are
+        // read four at a time (one LDS round trip), most requests having no more than four segments.
         auto request_rows = [&](int i, auto ref, RowSet& w) {
             const int a0 = __builtin_amdgcn_readlane(m_a0, i);
             const int s = __builtin_amdgcn_readlane(m_s, i);
             const int n = __builtin_amdgcn_readlane(m_n, i);
+            w.of_lane = ref(a0 + (lane < SEG_CHUNK ? lane : 0), lane < s && lane < SEG_CHUNK);
 #pragma unroll
-            for (int k = 0; k < SEG_CHUNK; ++k) {       // (cells past the last segment are never read)
-                w.id[k] = -1;
-                w.end[k] = n;
-            }
+            for (int k = 0; k < SEG_CHUNK; ++k) w.end[k] = n;       // (cells past the last segment are never read)
 #pragma unroll
-            for (int k = 0; k < SEG_CHUNK; ++k) {
-                if (k >= s) break;
-                const SegRef sr = ref(a0 + k, true);
-                w.id[k] = sr.id;
-                w.end[k] = sr.end;
-                w.cell[k] = ld(cell_at(sr.id));          // lanes beyond R read a neighbouring cell, unused
+            for (int h = 0; h < SEG_CHUNK; h += 4) {
+                if (h >= s) break;
+                SegRef sr[4];
+#pragma unroll
+                for (int k = 0; k < 4; ++k) sr[k] = ref(a0 + h + k, h + k < s);
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    if (h + k >= s) break;
+                    w.end[h + k] = sr[k].end;
+                    w.cell[h + k] = ld(cell_at(sr[k].id));           // lanes beyond R read a neighbouring cell, unused
+                }
             }
         };
 
@@ -330,27 +334,34 @@ __global__ void __launch_bounds__(SEG_THREADS) replay_segments_kernel(SegArgs a)
             const int s = __builtin_amdgcn_readlane(m_s, i);
             const int n = __builtin_amdgcn_readlane(m_n, i);
 
-            // ---- prefix match: lane = replica.  Also notes, for the ownership update below, how far the
-            // cached prefix reaches on this replica (last cached segment k_last, its end) and whether all
-            // cached segments had the same previous owner.
-            int my_m = 0;
-            bool open = true;
-            int pos = 0;
-            int k_end = 0;              // end position of the last segment with cached blocks
-            bool one_owner = true;
+            // ---- prefix match: lane = replica.  A request that touches a segment touches all its ancestors,
+            // so along the path the cells never increase: first the segments touched after the cursor's
+            // request (cached), then those it touched last itself (cached below the cursor position), then
+            // older ones (evicted).  The match is max(e_gt, min(cur_k, e_ge)) with e_gt, e_ge the ends of the
+            // last segment whose cell is above, respectively not below, the cursor's request.
+            int e_gt = 0, e_ge = 0;
+            int32_t own_gt = -1;        // previous owner of the last segment counted in e_gt
 #pragma unroll
             for (int k = 0; k < SEG_CHUNK; ++k) {
                 if (k >= s) break;
-                const int cnt = cached_in(mine.cell[k], pos, mine.end[k], cur_r, cur_k);
-                const bool some = open && cnt > 0;
-                my_m += some ? cnt : 0;
-                k_end = some ? mine.end[k] : k_end;
-                one_owner = one_owner && (!some || mine.cell[k] == mine.cell[0]);
-                open = open && cnt == mine.end[k] - pos;
-                pos = mine.end[k];
+                const bool gt = mine.cell[k] > cur_r;
+                const bool ge = mine.cell[k] >= cur_r;
+                e_gt = gt ? mine.end[k] : e_gt;
+                own_gt = gt ? mine.cell[k] : own_gt;
+                e_ge = ge ? mine.end[k] : e_ge;
             }
+            const int below_cursor = cur_k < e_ge ? cur_k : e_ge;
+            const bool some_eq = below_cursor > e_gt;       // blocks of the cursor's own request are matched
+            int my_m = some_eq ? below_cursor : e_gt;
+            // For the ownership update below: where the cached prefix ends on this replica (rounded up to the
+            // end of a segment that the cursor's request owns: what lies beyond the cursor is evicted anyway)
+            // and whether all cached segments had the same previous owner.
+            const int k_end = some_eq ? e_ge : e_gt;
+            const bool one_owner = some_eq ? e_gt == 0 : own_gt == mine.cell[0];
+            int pos = mine.end[SEG_CHUNK - 1];
+            bool open = my_m == pos;
             bool deep = false;          // the match went past the preloaded segments
-            if (s > SEG_CHUNK && __ballot(open && lane < R) != 0) {
+            if (s > SEG_CHUNK && __ballot(open && lane < R) != 0) {      // (pos and open only matter in here)
                 deep = true;
                 for (int c0 = SEG_CHUNK; c0 < s; c0 += SEG_CHUNK) {
                     int32_t cell[SEG_CHUNK];
@@ -459,17 +470,10 @@ __global__ void __launch_bounds__(SEG_THREADS) replay_segments_kernel(SegArgs a)
             }
 
             // ---- cache update: every segment of the request is now last touched by r on the chosen replica
-            {
-                int my_id = 0;
-#pragma unroll
-                for (int k = 0; k < SEG_CHUNK; ++k) {
-                    if (k >= s) break;
-                    my_id = lane == k ? mine.id[k] : my_id;
-                }
-                if (lane < s && lane < SEG_CHUNK) st(&last[(size_t)my_id * R + best], (int32_t)r);
-                for (int j = SEG_CHUNK + lane; j < s; j += WAVE)
-                    st(&last[(size_t)ref(a0 + j, true).id * R + best], (int32_t)r);
-            }
+            // (lane k stores the cell of segment k)
+            if (lane < s && lane < SEG_CHUNK) st(&last[(size_t)mine.of_lane.id * R + best], (int32_t)r);
+            for (int j = SEG_CHUNK + lane; j < s; j += WAVE)
+                st(&last[(size_t)ref(a0 + j, true).id * R + best], (int32_t)r);
 
             // ---- log and eviction, in the chosen replica's lane
             if (is_best) {
@@ -537,12 +541,13 @@ __global__ void __launch_bounds__(SEG_THREADS) replay_segments_kernel(SegArgs a)
             // ---- the rows of request i+1 were requested before this request's stores: if it continues the
             // same tree, the cells this request just wrote are patched into them (common prefix of the paths)
             if (i + 1 < nb && s > 0 && __builtin_amdgcn_readlane(m_root, i + 1) == __builtin_amdgcn_readlane(m_root, i)) {
-                bool common = true;
+                const int s_next = __builtin_amdgcn_readlane(m_s, i + 1);
+                const bool same = lane < s && lane < s_next && other.of_lane.id == mine.of_lane.id &&
+                                  other.of_lane.end == mine.of_lane.end;
+                const unsigned differ = ~(unsigned)__ballot(same && lane < SEG_CHUNK) | (1u << SEG_CHUNK);
+                const int common = __ffs(differ) - 1;              // leading segments the two paths share
 #pragma unroll
-                for (int k = 0; k < SEG_CHUNK; ++k) {
-                    common = common && k < s && other.id[k] == mine.id[k] && other.end[k] == mine.end[k];
-                    other.cell[k] = (common && is_best) ? (int32_t)r : other.cell[k];
-                }
+                for (int k = 0; k < SEG_CHUNK; ++k) other.cell[k] = (k < common && is_best) ? (int32_t)r : other.cell[k];
             }
 
             // ---- outputs of the cache side (kept in registers until the batch ends)
