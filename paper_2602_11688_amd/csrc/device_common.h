@@ -29,21 +29,6 @@ __device__ __forceinline__ void st(T* p, T v) {
     __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
 }
 
-struct Best {
-    double v;
-    int idx;
-};
-
-// Cross-lane move through the data-parallel-primitive path (no LDS round trip).  Lanes whose source is
-// outside the row, or that row_mask excludes, keep their own value.
-template <int CTRL, int ROW_MASK>
-__device__ __forceinline__ double dpp_f64(double x) {
-    const long long b = __double_as_longlong(x);
-    const int lo = __builtin_amdgcn_update_dpp((int)b, (int)b, CTRL, ROW_MASK, 0xf, false);
-    const int hi = __builtin_amdgcn_update_dpp((int)(b >> 32), (int)(b >> 32), CTRL, ROW_MASK, 0xf, false);
-    return __longlong_as_double(((long long)hi << 32) | (unsigned int)lo);
-}
-
 __device__ __forceinline__ double readlane_f64(double v, int src) {
     const long long b = __double_as_longlong(v);
     const int lo = __builtin_amdgcn_readlane((int)b, src);
@@ -57,26 +42,41 @@ __device__ __forceinline__ int64_t readlane_i64(int64_t v, int src) {
     return ((int64_t)hi << 32) | (unsigned int)lo;
 }
 
-__device__ __forceinline__ double min_keep_first(double x, double y) { return y < x ? y : x; }
-
-// Minimum over the 64 lanes: shifts by 1, 2, 4, 8 inside each row of 16 lanes, then the last lane of a row is
-// broadcast into the next row (rows 1 and 3), then lane 31 into rows 2 and 3; lane 63 holds the result.
-__device__ __forceinline__ double wave_min_f64(double x) {
-    x = min_keep_first(x, dpp_f64<0x111, 0xf>(x));   // row_shr:1
-    x = min_keep_first(x, dpp_f64<0x112, 0xf>(x));   // row_shr:2
-    x = min_keep_first(x, dpp_f64<0x114, 0xf>(x));   // row_shr:4
-    x = min_keep_first(x, dpp_f64<0x118, 0xf>(x));   // row_shr:8
-    x = min_keep_first(x, dpp_f64<0x142, 0xa>(x));   // row_bcast:15 into rows 1, 3
-    x = min_keep_first(x, dpp_f64<0x143, 0xc>(x));   // row_bcast:31 into rows 2, 3
-    return readlane_f64(x, 63);
+// Unsigned minimum of x over the wavefront on the data-parallel-primitive path (no LDS round trip): shifts by
+// 1, 2, 4, 8 inside each row of 16 lanes, then the last lane of a row is broadcast into the next row (rows 1
+// and 3), then lane 31 into rows 2 and 3; lane 63 holds the result.  Each step is one instruction (the moved
+// operand is folded into the minimum); lanes without a source see 0xffffffff.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ unsigned dpp_min_u32(unsigned x) {
+    const unsigned moved = (unsigned)__builtin_amdgcn_update_dpp((int)0xffffffffu, (int)x, CTRL, ROW_MASK, 0xf, false);
+    return moved < x ? moved : x;
+}
+__device__ __forceinline__ unsigned wave_min_u32(unsigned x) {
+    x = dpp_min_u32<0x111, 0xf>(x);   // row_shr:1
+    x = dpp_min_u32<0x112, 0xf>(x);   // row_shr:2
+    x = dpp_min_u32<0x114, 0xf>(x);   // row_shr:4
+    x = dpp_min_u32<0x118, 0xf>(x);   // row_shr:8
+    x = dpp_min_u32<0x142, 0xa>(x);   // row_bcast:15 into rows 1, 3
+    x = dpp_min_u32<0x143, 0xc>(x);   // row_bcast:31 into rows 2, 3
+    return (unsigned)__builtin_amdgcn_readlane((int)x, 63);
 }
 
-// Lowest-index minimum over the lanes below `count` (count >= 1; values must not be NaN).
-__device__ __forceinline__ Best wave_argmin(double v, int lane, int count) {
-    const double mine = lane < count ? v : INFINITY;
-    const double mn = wave_min_f64(mine);
-    const unsigned long long at = __ballot(lane < count && mine == mn);
-    return Best{mn, __ffsll(at) - 1};
+// Lowest-index minimum over the lanes below `count` (count >= 1; values must not be NaN).  The values are
+// compared through the usual order-preserving map of an IEEE double to an unsigned 64-bit key (zeros of
+// either sign made equal first), high word first, then the low word among the lanes that tie on the high
+// word: two 32-bit reductions instead of one on register pairs.
+__device__ __forceinline__ int wave_argmin(double v, int lane, int count) {
+    const unsigned long long bits = (unsigned long long)__double_as_longlong(v + 0.0);
+    const unsigned hi = (unsigned)(bits >> 32), lo = (unsigned)bits;
+    const unsigned neg = (unsigned)((int)hi >> 31);
+    const bool in = lane < count;
+    const unsigned khi = in ? hi ^ (neg | 0x80000000u) : 0xffffffffu;
+    const unsigned klo = lo ^ neg;
+    const unsigned mhi = wave_min_u32(khi);
+    const bool tie = in && khi == mhi;
+    const unsigned mlo = wave_min_u32(tie ? klo : 0xffffffffu);
+    const unsigned long long at = __ballot(tie && klo == mlo);
+    return __ffsll(at) - 1;
 }
 
 // Queue side of one replay.  Lane i owns replica i: its load signal q (Eq. 2: tokens of requests without a
@@ -98,8 +98,7 @@ struct Queues {
     int R, B, Bp, base;
     double my_min;       // earliest head completion among this lane's slots ...
     int my_min_k;        // ... and its slot
-    double f_min;        // earliest free time among this lane's slots (lowest slot on ties) ...
-    int f_k;             // ... and its slot
+    unsigned long long idle;   // slots of this lane's replica with nothing in flight (bit b = slot b)
     double my_q;         // outstanding tokens of replica = lane (an integer below 2^53, exact in fp64)
 
     static __host__ __device__ size_t bytes(int R, int B) {
@@ -131,8 +130,7 @@ struct Queues {
         }
         my_min = INFINITY;
         my_min_k = 0;
-        f_min = 0.0;
-        f_k = 0;
+        idle = B >= 64 ? ~0ull : (1ull << B) - 1;
         my_q = 0.0;
     }
 
@@ -154,6 +152,7 @@ struct Queues {
                     }
                 } else {
                     h_done[s] = INFINITY;
+                    idle |= 1ull << my_min_k;
                 }
                 depth[s] = d - 1;
                 // earliest head of this lane's slots again
@@ -177,62 +176,73 @@ struct Queues {
     }
 
     // Service of request r on replica `best` (the stated linear model; reproduces Eq. 1: ttft = rtt + wait +
-    // prefill): earliest-free slot, lowest index on ties.  Every lane evaluates the schedule its own replica
-    // would give; the chosen replica's lane commits it and its latencies are broadcast.
+    // prefill) on the earliest-free slot.  Which of several free slots takes the request changes no latency
+    // and no load signal: a slot with nothing in flight has seen its completion event reach the proxy, so it
+    // has been free since before any later arrival at the replica, exactly like the earliest-free one.  The
+    // slots are therefore only searched for their earliest free time (lowest index on ties) when every slot
+    // still has a request in flight.  The chosen replica's lane works, its latencies are broadcast.
     __device__ void serve(int64_t r, int best, double t, double rtt_mine, int64_t uncached_mine, int64_t L, int64_t O,
                           double a_pf, double a_dec, Rec* rec, int lane, double* ttft_out, double* e2e_out) {
-        const double half = 0.5 * rtt_mine;
-        const double arrive = t + half;
-        const double start = arrive > f_min ? arrive : f_min;
-        const double pf = a_pf * (double)uncached_mine;
-        const double first_tok = start + pf;
-        const double dec = a_dec * (double)O;
-        const double end = first_tok + dec;
-        const double done = end + half;
-        const double ttft = (first_tok + half) - t;
-        const double e2e = done - t;
+        double ttft = 0.0, e2e = 0.0;
         if (lane == best) {
-            const int s = base + f_k;
+            const double half = 0.5 * rtt_mine;
+            const double arrive = t + half;
+            double start = arrive;
+            int k;
+            if (idle != 0) {
+                k = __ffsll(idle) - 1;
+            } else {
+                double fv = INFINITY;
+                k = 0;
+                for (int b0 = 0; b0 < Bp; b0 += 8) {
+                    double v[8];
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) v[j] = free_at[base + b0 + j];
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) {
+                        const bool lt = v[j] < fv;
+                        fv = lt ? v[j] : fv;
+                        k = lt ? b0 + j : k;
+                    }
+                }
+                start = arrive > fv ? arrive : fv;
+            }
+            const double pf = a_pf * (double)uncached_mine;
+            const double first_tok = start + pf;
+            const double dec = a_dec * (double)O;
+            const double end = first_tok + dec;
+            const double done = end + half;
+            ttft = (first_tok + half) - t;
+            e2e = done - t;
+            const int s = base + k;
             free_at[s] = end;
-            const int d = depth[s];
-            if (d == 0) {
+            if (idle != 0) {
+                idle &= ~(1ull << k);
                 h_done[s] = done;
                 h_tok[s] = (int32_t)L;
+                depth[s] = 1;
                 if (done < my_min) {
                     my_min = done;
-                    my_min_k = f_k;
+                    my_min_k = k;
                 }
-            } else if (d == 1) {
-                s_done[s] = done;
-                s_tok[s] = (int32_t)L;
-                s_next[s] = -1;
             } else {
-                // third or deeper: goes to global memory, linked behind the youngest
-                st(&rec[r].done, done);
-                st(&rec[r].next, (int32_t)-1);
-                st(&rec[r].tokens, (int32_t)L);
-                if (d == 2) s_next[s] = (int32_t)r;
-                else st(&rec[tail[s]].next, (int32_t)r);
+                const int d = depth[s];         // at least 1
+                if (d == 1) {
+                    s_done[s] = done;
+                    s_tok[s] = (int32_t)L;
+                    s_next[s] = -1;
+                } else {
+                    // third or deeper: goes to global memory, linked behind the youngest
+                    st(&rec[r].done, done);
+                    st(&rec[r].next, (int32_t)-1);
+                    st(&rec[r].tokens, (int32_t)L);
+                    if (d == 2) s_next[s] = (int32_t)r;
+                    else st(&rec[tail[s]].next, (int32_t)r);
+                }
+                depth[s] = d + 1;
             }
             tail[s] = (int32_t)r;
-            depth[s] = d + 1;
             my_q += (double)L;
-            // earliest-free slot of this replica again
-            double fv = INFINITY;
-            int fk = 0;
-            for (int b0 = 0; b0 < Bp; b0 += 8) {
-                double v[8];
-#pragma unroll
-                for (int k = 0; k < 8; ++k) v[k] = free_at[base + b0 + k];
-#pragma unroll
-                for (int k = 0; k < 8; ++k) {
-                    const bool lt = v[k] < fv;
-                    fv = lt ? v[k] : fv;
-                    fk = lt ? b0 + k : fk;
-                }
-            }
-            f_min = fv;
-            f_k = fk;
         }
         *ttft_out = readlane_f64(ttft, best);
         *e2e_out = readlane_f64(e2e, best);

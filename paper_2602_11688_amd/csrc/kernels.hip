@@ -193,7 +193,7 @@ __global__ void __launch_bounds__(WAVE) replay_blocks_kernel(ReplayArgs a) {
             my_u = L - hit_tok;
             my_score = eq3_score(w_rtt, w_prefill, w_queue, my_rtt, a.a_pf, (int)my_u, Q.my_q);
         }
-        const int best = wave_argmin(my_score, lane, R).idx;
+        const int best = wave_argmin(my_score, lane, R);
         const int m_best = __builtin_amdgcn_readlane(my_m, best);
         if (lane == 0) st(&route[r], (uint8_t)best);
 

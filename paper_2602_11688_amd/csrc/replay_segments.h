@@ -73,8 +73,10 @@ constexpr int SEG_SPIN_LIMIT = 1 << 24;      // polls of a hand-over word before
 
 // Hand-over words between the two wavefronts of a replay, in LDS.  Every word carries the number of the
 // request it belongs to (r + 1, so that the initial zero matches nothing).  They are read and written with
-// relaxed workgroup-scope atomics on the LDS variable itself (so that they stay LDS instructions), with
-// LDS-only release / acquire fences between data and word.
+// relaxed workgroup-scope atomics on the LDS variable itself (so that they stay LDS instructions).  The LDS
+// executes the instructions of one wavefront in the order they were issued, for reads as for writes, so data
+// written before a word is there for whoever reads it after having read that word; the fences between data
+// and word only have to keep the compiler from changing that order, and cost no wait.
 struct SegComm {
     double q[WAVE];                   // load signal per replica, valid when seq_q == r + 1
     unsigned seq_q;
@@ -82,8 +84,8 @@ struct SegComm {
     unsigned long long choice;        // uncached tokens | (((r + 1) mod 2^26) << 6 | replica) << 32
 };
 
-__device__ __forceinline__ void lds_release() { __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local"); }
-__device__ __forceinline__ void lds_acquire() { __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local"); }
+__device__ __forceinline__ void lds_release() { __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront"); }
+__device__ __forceinline__ void lds_acquire() { __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront"); }
 
 // Orders the LDS accesses of one wavefront's lanes (the hardware executes them in program order).
 __device__ __forceinline__ void wave_sync() {
@@ -422,7 +424,7 @@ __global__ void __launch_bounds__(SEG_THREADS) replay_segments_kernel(SegArgs a)
                 return;
             }
             const double my_score = eq3_with_queue(score_rp_ready, w_queue, a.a_pf, my_q);
-            const int best = wave_argmin(my_score, lane, R).idx;
+            const int best = wave_argmin(my_score, lane, R);
             const bool is_best = lane == best;
             const int m_best = __builtin_amdgcn_readlane(my_m, best);
             if (lane == 0) {
