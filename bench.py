@@ -66,10 +66,11 @@ def kernel_source_digest():
     return h.hexdigest()[:16]
 
 
-def recorded_traffic(kernel, workload_key):
-    """HBM bytes per launch of `kernel` from the rocprofv3 counter runs recorded under profiles/ (FETCH_SIZE
-    and WRITE_SIZE, each scaled by the same counter's reading for a plain 1 GiB copy), or None when the
-    device sources have changed since, or the workload differs."""
+def recorded_counters(kernel, workload_key):
+    """Hardware counters of one launch of `kernel` recorded under profiles/ by rocprofv3 runs of this script:
+    HBM bytes (FETCH_SIZE and WRITE_SIZE, each scaled by the same counter's reading for a plain 1 GiB copy) and,
+    when present, the instruction counters.  None when the device sources have changed since, or the workload
+    differs."""
     path = os.path.join(ROOT, "profiles", "hbm_counters.json")
     try:
         with open(path) as f:
@@ -79,7 +80,7 @@ def recorded_traffic(kernel, workload_key):
     if rec.get("source_digest") != kernel_source_digest() or rec.get("kernel") != kernel or \
             rec.get("workload") != workload_key:
         return None
-    return rec["fetch_bytes_per_launch"] + rec["write_bytes_per_launch"]
+    return rec
 
 
 def cpu_baseline(wl, params, n_req, threads):
@@ -185,8 +186,21 @@ def main():
         bpr = algorithmic_bytes_per_routing(wl.R, n_mean, hit_mean, outputs_bytes=9)
         kernel = "replay_blocks_kernel"
     k_ms = float(np.mean(kernel_ms))
-    traffic = recorded_traffic(kernel, f"config-{args.config} N={N} P={P}")
+    counters = recorded_counters(kernel, f"config-{args.config} N={N} P={P}")
+    traffic = counters["fetch_bytes_per_launch"] + counters["write_bytes_per_launch"] if counters else None
     achieved = bpr * P * N / (k_ms * 1e-3) / 1e9
+    # The replay is one dependent chain per candidate: what limits it is the rate at which a SIMD issues the
+    # chain's instructions, not bandwidth.  Recorded instruction counters say how far from that limit it runs:
+    # every wavefront instruction occupies its SIMD's issue port for four cycles.
+    issue = None
+    if counters and "sq_insts_per_routing" in counters:
+        per = counters["sq_insts_per_routing"]
+        n_simd, clock_hz = 256 * 4, 2.4e9
+        total = sum(per.values())
+        rate = total * P * N / (k_ms * 1e-3)
+        issue = {"instructions_per_routing": per, "total_per_routing": total,
+                 "achieved_ginst_s": rate / 1e9, "peak_ginst_s": n_simd * clock_hz / 4 / 1e9,
+                 "frac": rate / (n_simd * clock_hz / 4)}
 
     out = {
         "metric": "candidate-request routings/sec at P=1024", "value": value, "unit": "routings/s",
@@ -198,7 +212,8 @@ def main():
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "kernel": kernel, "mean_segments": segs_mean,
                      "kernel_ms": k_ms, "bytes_per_routing": bpr, "mean_blocks": n_mean, "mean_hit_blocks": hit_mean,
-                     "fill_ms": float(np.mean(fill_ms)), "select_ms": float(np.mean(select_ms))},
+                     "fill_ms": float(np.mean(fill_ms)), "select_ms": float(np.mean(select_ms)),
+                     "issue": issue},
     }
     if not args.no_cpu_baseline:
         cores = min(len(os.sched_getaffinity(0)), 16)
