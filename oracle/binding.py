@@ -22,6 +22,14 @@ def lib():
                                                                           C.c_int64, C.c_double, C.c_double,
                                                                           C.c_void_p, C.c_void_p, C.c_double] + \
                                           [C.c_void_p] * 8
+        L.gorgo_oracle_replay_ex.restype = C.c_int
+        L.gorgo_oracle_replay_ex.argtypes = [C.c_int64] + [C.c_void_p] * 5 + \
+            [C.c_int32, C.c_int32, C.c_int32, C.c_int64, C.c_double, C.c_double, C.c_void_p, C.c_void_p, C.c_double,
+             C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_double] + [C.c_void_p] * 11
+        L.gorgo_oracle_tuner_exp.restype = C.c_double
+        L.gorgo_oracle_tuner_exp.argtypes = [C.c_double]
+        L.gorgo_oracle_online_steps.restype = C.c_int64
+        L.gorgo_oracle_online_steps.argtypes = [C.c_int64, C.c_int32, C.c_int32]
         _lib = L
     return _lib
 
@@ -41,6 +49,13 @@ class Replay:
     score: Optional[np.ndarray] = None   # float64 [N,R]
     q: Optional[np.ndarray] = None       # int64 [N,R]
     size: Optional[np.ndarray] = None    # int64 [N]
+    # online tuner (replay_online only)
+    theta_step: Optional[np.ndarray] = None     # float64 [steps,3] weights in use after each step
+    fitness_step: Optional[np.ndarray] = None   # float64 [steps] window p95 TTFT seen at each step
+    theta_final: Optional[np.ndarray] = None    # float64 [3] parent weights after the last step
+    sigma_final: float = 0.0
+    steps: int = 0
+    accepted: int = 0
 
 
 def p95(x) -> float:
@@ -82,3 +97,62 @@ def replay_workload(wl, p: int, debug=False, trace=None) -> Replay:
     return replay(trace if trace is not None else wl.trace, R=wl.R, batch=wl.batch, cache_blocks=wl.cache_blocks,
                   prefill_ms_per_token=wl.prefill_ms_per_token, decode_ms_per_token=wl.decode_ms_per_token,
                   rtt_ms=wl.rtt_ms, w=wl.params[p], scale=wl.scale[p], block_tokens=wl.block_tokens, debug=debug)
+
+
+def tuner_exp(x: float) -> float:
+    return float(lib().gorgo_oracle_tuner_exp(float(x)))
+
+
+def online_steps(N: int, window: int, hop: int) -> int:
+    return int(lib().gorgo_oracle_online_steps(N, window, hop))
+
+
+def _replay_ex(trace, R, batch, cache_blocks, prefill_ms_per_token, decode_ms_per_token, rtt_ms, w, scale,
+               block_tokens, window, hop, schedule, z, lo, hi, sigma0) -> Replay:
+    N = int(trace.ts_ms.shape[0])
+    ts = np.ascontiguousarray(trace.ts_ms, dtype=np.int64)
+    il = np.ascontiguousarray(trace.in_len, dtype=np.int32)
+    ol = np.ascontiguousarray(trace.out_len, dtype=np.int32)
+    bo = np.ascontiguousarray(trace.blk_off, dtype=np.int64)
+    hs = np.ascontiguousarray(trace.hash_ids, dtype=np.int64)
+    rtt = np.ascontiguousarray(rtt_ms, dtype=np.float64)
+    wv = np.ascontiguousarray(w, dtype=np.float64)
+    steps = online_steps(N, window, hop)
+    sched = None if schedule is None else np.ascontiguousarray(schedule, dtype=np.float64)
+    zz = None if z is None else np.ascontiguousarray(z, dtype=np.float64)
+    lov = None if lo is None else np.ascontiguousarray(lo, dtype=np.float64)
+    hiv = None if hi is None else np.ascontiguousarray(hi, dtype=np.float64)
+    assert rtt.shape == (R,) and wv.shape == (3,) and bo.shape == (N + 1,)
+    assert sched is None or sched.shape == (steps, 3)
+    assert zz is None or zz.shape == (steps, 3)
+    route = np.zeros(N, np.uint8)
+    hit = np.zeros(N, np.uint16)
+    ttft = np.zeros(N, np.float64)
+    e2e = np.zeros(N, np.float64)
+    p = np.zeros(2, np.float64)
+    theta_step = np.zeros((steps, 3), np.float64)
+    fitness_step = np.zeros(steps, np.float64)
+    fin = np.zeros(6, np.float64)
+    rc = lib().gorgo_oracle_replay_ex(N, _p(ts), _p(il), _p(ol), _p(bo), _p(hs), block_tokens, R, batch, cache_blocks,
+                                      prefill_ms_per_token, decode_ms_per_token, _p(rtt), _p(wv), float(scale),
+                                      window, hop, _p(sched), _p(zz), _p(lov), _p(hiv), float(sigma0),
+                                      _p(route), _p(hit), _p(ttft), _p(e2e), _p(p), None, None, None,
+                                      _p(theta_step), _p(fitness_step), _p(fin))
+    if rc != 0:
+        raise RuntimeError(f"gorgo_oracle_replay_ex failed with code {rc}")
+    return Replay(route, hit, ttft, e2e, float(p[0]), float(p[1]), theta_step=theta_step, fitness_step=fitness_step,
+                  theta_final=fin[:3].copy(), sigma_final=float(fin[3]), steps=int(fin[4]), accepted=int(fin[5]))
+
+
+def replay_online(trace, *, R, batch, cache_blocks, prefill_ms_per_token, decode_ms_per_token, rtt_ms, theta0, z, lo,
+                  hi, sigma0, window=128, hop=32, scale=1.0, block_tokens=512) -> Replay:
+    """One replay with the online tuner: z[steps,3] are its standard normal draws."""
+    return _replay_ex(trace, R, batch, cache_blocks, prefill_ms_per_token, decode_ms_per_token, rtt_ms, theta0, scale,
+                      block_tokens, window, hop, None, z, lo, hi, sigma0)
+
+
+def replay_schedule(trace, *, R, batch, cache_blocks, prefill_ms_per_token, decode_ms_per_token, rtt_ms, w, schedule,
+                    window, hop, scale=1.0, block_tokens=512) -> Replay:
+    """One replay whose weights are w, then schedule[h] after requests window + h * hop (no tuner)."""
+    return _replay_ex(trace, R, batch, cache_blocks, prefill_ms_per_token, decode_ms_per_token, rtt_ms, w, scale,
+                      block_tokens, window, hop, schedule, None, None, None, 0.0)

@@ -16,6 +16,11 @@
 // Readings taken where the paper is silent (functional forms of the three terms, the replica service model,
 // LRU order, percentile definition) are stated next to the step that uses them.
 //
+// The online tuner (Sec. 2.3 "GORGO Proxy Design", Sec. 4 "Tuning and evaluation windows") runs inside one
+// replay: after every `hop` requests the p95 TTFT of the last `window` requests is the fitness of the weights
+// in use; a (1+1) evolution strategy keeps them if they beat the parent, adapts its step size by the 1/5
+// rule and proposes the next offspring by the log-space mutation.
+//
 // Pinned by tests (tests/test_oracle_*.py): three hand-worked traces, brute force over every route sequence
 // at R=2 N=10 against an independent forced-route evaluator, weight special cases (all-zero, rtt-only,
 // prefix-only, queue-only, power-of-two rescaling), post-hoc recomputation of the load signal, Lindley /
@@ -25,6 +30,8 @@
 
 #include <cstdint>
 #include <cstddef>
+#include <cstring>
+#include <cmath>
 #include <algorithm>
 #include <map>
 #include <set>
@@ -48,9 +55,41 @@ struct Replica {
     int64_t q = 0;                                // tokens of requests without a completion event (Eq. 2)
 };
 
+// exp(x) from additions and multiplications only, so that every build of it gives the same bits (the weights
+// the tuner proposes decide routes, and the C library's exp is not the same everywhere).  Stated algorithm:
+// k = floor(x / ln 2 + 1/2); r = (x - k * LN2_HI) - k * LN2_LO with ln 2 split so that k * LN2_HI is exact;
+// exp(r) = sum_{j=0}^{13} r^j / j! by Horner's rule from the highest term down; result = that times 2^k.
+// Valid for |x| <= 700 (the tuner's arguments are logarithms of weights in [1e-100, 1e100]).
+double tuner_exp(double x) {
+    const double INV_LN2 = 1.44269504088896338700e+00;
+    const double LN2_HI = 6.93147180369123816490e-01;     // ln 2 with its low 21 bits zero
+    const double LN2_LO = 1.90821492927058770002e-10;     // ln 2 - LN2_HI
+    const double k = std::floor(x * INV_LN2 + 0.5);
+    const double r = (x - k * LN2_HI) - k * LN2_LO;
+    static const double inv_fact[14] = {1.0, 1.0, 1.0 / 2.0, 1.0 / 6.0, 1.0 / 24.0, 1.0 / 120.0, 1.0 / 720.0,
+                                        1.0 / 5040.0, 1.0 / 40320.0, 1.0 / 362880.0, 1.0 / 3628800.0,
+                                        1.0 / 39916800.0, 1.0 / 479001600.0, 1.0 / 6227020800.0};
+    double p = inv_fact[13];
+    for (int j = 12; j >= 0; --j) p = p * r + inv_fact[j];
+    const uint64_t bits = (uint64_t)((int64_t)k + 1023) << 52;      // 2^k
+    double two_k;
+    std::memcpy(&two_k, &bits, sizeof two_k);
+    return p * two_k;
+}
+
+double clip(double x, double lo, double hi) { return std::min(std::max(x, lo), hi); }
+
 }  // namespace
 
 extern "C" {
+
+// Exposed so that tests can pin the tuner's exp against the C library's.
+double gorgo_oracle_tuner_exp(double x) { return tuner_exp(x); }
+
+// Tuner steps a replay of N requests takes: one when the first window is full, then one every hop.
+int64_t gorgo_oracle_online_steps(int64_t N, int32_t window, int32_t hop) {
+    return N >= window ? (N - window) / hop + 1 : 0;
+}
 
 // Nearest-rank percentile: the k-th smallest element with k = ceil(0.95 n) (1-indexed), no interpolation.
 // Objective of the tuner is the p95 of TTFT (Sec. 2.3, Sec. 4).
@@ -68,15 +107,44 @@ double gorgo_oracle_p95(const double* x, int64_t n) {
 // q_dbg[N*R] (load signal after retirement, before dispatch), size_dbg[N] (blocks cached on the chosen
 // replica after the update).  Returns 0, or -1 for bad arguments, -5 if a request has more distinct blocks
 // than a bounded cache can hold.
-int gorgo_oracle_replay(int64_t N, const int64_t* ts_ms, const int32_t* in_len, const int32_t* out_len,
-                        const int64_t* blk_off, const int64_t* hash_ids, int32_t block_tokens,
-                        int32_t R, int32_t B, int64_t C, double a_pf, double a_dec,
-                        const double* rtt_ms, const double* w, double scale,
-                        uint8_t* route, uint16_t* hit_blocks, double* ttft_ms, double* e2e_ms, double* p95,
-                        double* score_dbg, int64_t* q_dbg, int64_t* size_dbg) {
+//
+// Weights: w is what the first request is scored with.  With window > 0 the weights change inside the replay,
+// after requests window, window + hop, window + 2 hop, ... (counting from 1), step h = 0, 1, ...:
+//   * schedule != null: the weights become schedule[h] (nothing else happens);
+//   * otherwise the online tuner runs (z = standard normal draws [steps][3], lo/hi = clip range per weight,
+//     sigma0 = initial step size; tuner outputs, each may be null: theta_step[steps][3] = weights in use after
+//     each step, fitness_step[steps] = window p95 TTFT seen at each step, tuner_final[6] = parent weights (3),
+//     step size, steps taken, offspring accepted).
+int gorgo_oracle_replay_ex(int64_t N, const int64_t* ts_ms, const int32_t* in_len, const int32_t* out_len,
+                           const int64_t* blk_off, const int64_t* hash_ids, int32_t block_tokens,
+                           int32_t R, int32_t B, int64_t C, double a_pf, double a_dec,
+                           const double* rtt_ms, const double* w, double scale,
+                           int32_t window, int32_t hop, const double* schedule, const double* z,
+                           const double* lo, const double* hi, double sigma0,
+                           uint8_t* route, uint16_t* hit_blocks, double* ttft_ms, double* e2e_ms, double* p95,
+                           double* score_dbg, int64_t* q_dbg, int64_t* size_dbg,
+                           double* theta_step, double* fitness_step, double* tuner_final) {
     if (N < 0 || R < 1 || R > 255 || B < 1 || C < 0 || block_tokens < 1) return -1;
     if (N > 0 && (!ts_ms || !in_len || !out_len || !blk_off)) return -1;
-    const double w_rtt = w[0], w_prefill = w[1], w_queue = w[2];
+    if (window < 0 || (window > 0 && hop < 1)) return -1;
+    if (window > 0 && !schedule && (!z || !lo || !hi)) return -1;
+    double w_rtt = w[0], w_prefill = w[1], w_queue = w[2];
+
+    // Tuner state (Sec. 2.3): the parent in log space, its fitness once it has one, the offspring in use (in log
+    // space, after clipping), the step size.  The paper's rule is x' = clip(exp(ln x_t + sigma z), [lo, hi]);
+    // here ln x_t is carried along instead of being taken again from the clipped x_t.
+    double ln_par[3] = {0, 0, 0}, ln_cur[3] = {0, 0, 0}, ln_lo[3] = {0, 0, 0}, ln_hi[3] = {0, 0, 0};
+    double f_par = 0.0, sigma = sigma0;
+    bool have_parent = false;
+    int64_t steps = 0, accepted = 0;
+    // Rechenberg's 1/5 rule in its damped form sigma * exp((s - 1/5) / 2), s = 1 after a success, else 0
+    const double c_up = std::exp(0.4), c_down = std::exp(-0.1);
+    if (window > 0 && !schedule)
+        for (int k = 0; k < 3; ++k) {
+            ln_par[k] = ln_cur[k] = std::log(w[k]);
+            ln_lo[k] = std::log(lo[k]);
+            ln_hi[k] = std::log(hi[k]);
+        }
 
     std::vector<Replica> rep(R);
     for (auto& x : rep) x.free_at.assign(B, 0.0);
@@ -193,12 +261,76 @@ int gorgo_oracle_replay(int64_t N, const int64_t* ts_ms, const int32_t* in_len, 
         if (hit_blocks) hit_blocks[r] = (uint16_t)m[best];
         if (ttft_ms) ttft_ms[r] = ttft[r];
         if (e2e_ms) e2e_ms[r] = e2e[r];
+
+        // online tuning (Sec. 4: "p95 TTFT of a rolling 128-request window with hop size 32"): a step when the
+        // first window is full and then every hop requests; the weights it leaves are used from request r+1 on
+        if (window > 0 && r + 1 >= window && (r + 1 - window) % hop == 0) {
+            const int64_t h = (r + 1 - window) / hop;
+            if (schedule) {
+                w_rtt = schedule[3 * h + 0];
+                w_prefill = schedule[3 * h + 1];
+                w_queue = schedule[3 * h + 2];
+            } else {
+                const double f = gorgo_oracle_p95(ttft.data() + (r + 1 - window), window);
+                if (!have_parent) {
+                    // the first window measures the initial weights: they are the parent
+                    f_par = f;
+                    have_parent = true;
+                } else {
+                    // the offspring replaces the parent iff it beats it on the objective; the step size
+                    // follows the 1/5 success rule
+                    const bool success = f < f_par;
+                    if (success) {
+                        for (int k = 0; k < 3; ++k) ln_par[k] = ln_cur[k];
+                        f_par = f;
+                        ++accepted;
+                    }
+                    sigma = sigma * (success ? c_up : c_down);
+                }
+                // next offspring: multiplicative perturbation in log space, clipped to the range
+                double th[3];
+                for (int k = 0; k < 3; ++k) {
+                    const double y = clip(ln_par[k] + sigma * z[3 * h + k], ln_lo[k], ln_hi[k]);
+                    ln_cur[k] = y;
+                    th[k] = clip(tuner_exp(y), lo[k], hi[k]);
+                }
+                w_rtt = th[0];
+                w_prefill = th[1];
+                w_queue = th[2];
+                if (fitness_step) fitness_step[h] = f;
+                ++steps;
+            }
+            if (theta_step) {
+                theta_step[3 * h + 0] = w_rtt;
+                theta_step[3 * h + 1] = w_prefill;
+                theta_step[3 * h + 2] = w_queue;
+            }
+        }
+    }
+    if (tuner_final && window > 0 && !schedule) {
+        for (int k = 0; k < 3; ++k) tuner_final[k] = clip(tuner_exp(ln_par[k]), lo[k], hi[k]);
+        tuner_final[3] = sigma;
+        tuner_final[4] = (double)steps;
+        tuner_final[5] = (double)accepted;
     }
     if (p95) {
         p95[0] = gorgo_oracle_p95(ttft.data(), N);
         p95[1] = gorgo_oracle_p95(e2e.data(), N);
     }
     return 0;
+}
+
+// One replay under one fixed weight vector.
+int gorgo_oracle_replay(int64_t N, const int64_t* ts_ms, const int32_t* in_len, const int32_t* out_len,
+                        const int64_t* blk_off, const int64_t* hash_ids, int32_t block_tokens,
+                        int32_t R, int32_t B, int64_t C, double a_pf, double a_dec,
+                        const double* rtt_ms, const double* w, double scale,
+                        uint8_t* route, uint16_t* hit_blocks, double* ttft_ms, double* e2e_ms, double* p95,
+                        double* score_dbg, int64_t* q_dbg, int64_t* size_dbg) {
+    return gorgo_oracle_replay_ex(N, ts_ms, in_len, out_len, blk_off, hash_ids, block_tokens, R, B, C, a_pf, a_dec,
+                                  rtt_ms, w, scale, 0, 0, nullptr, nullptr, nullptr, nullptr, 0.0, route,
+                                  hit_blocks, ttft_ms, e2e_ms, p95, score_dbg, q_dbg, size_dbg, nullptr, nullptr,
+                                  nullptr);
 }
 
 }  // extern "C"

@@ -39,7 +39,8 @@ class ForcedRouteModel:
     dictated predecessors induced; a route sequence is self-consistent when every dictated route is the
     lowest-index minimum of those scores.  The cache is a recency-ordered Python list (move-to-front,
     evict from the cold end), the in-flight set a plain list scanned at each request: different data
-    structures from the oracle's on purpose.
+    structures from the oracle's on purpose.  `w` is one weight vector, or one per request (a weight
+    schedule dictated from outside, like the routes).
     """
 
     def __init__(self, trace, R, batch, cache_blocks, block_tokens, a_pf, a_dec, rtt, w, scale):
@@ -69,7 +70,8 @@ class ForcedRouteModel:
                 u = L - min(L, self.bt * m)
                 pf = self.a_pf * float(u)
                 qd = self.a_pf * float(q[i])
-                scores.append((self.w[0] * self.rtt[i] + self.w[1] * pf) + self.w[2] * qd)
+                w = self.w[r] if isinstance(self.w[0], (list, tuple, np.ndarray)) else self.w
+                scores.append((w[0] * self.rtt[i] + w[1] * pf) + w[2] * qd)
                 us.append(u)
                 ms.append(m)
             best = min(range(self.R), key=lambda i: (scores[i], i))
