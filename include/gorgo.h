@@ -170,6 +170,43 @@ int gorgo_es_step(const gorgo_trace* t, const gorgo_model* m, const double* rtt_
                   gorgo_es_state* inout, double* params_out, double* fitness_out, void* workspace,
                   size_t workspace_bytes, void* hip_stream);
 
+/* ------------------------------------------------------------------------------------- online tuner
+ * The tuner as the paper runs it (Sec. 2.3 "GORGO Proxy Design"; Sec. 4 "Tuning and evaluation windows"):
+ * inside ONE replay, the p95 TTFT of a rolling window of `window` requests (paper: 128) is taken every `hop`
+ * requests (paper: 32), first when the first window is full.  It is the fitness of the weights then in use.
+ * The first window measures the initial weights, which become the parent.  Afterwards the weights in use
+ * (the offspring) replace the parent iff their fitness is strictly lower than the parent's, and sigma is
+ * multiplied by exp(0.4) after a success and exp(-0.1) otherwise (the 1/5 rule of gorgo_es_update at P = 2).
+ * Every step ends by proposing the next offspring from the parent by the log-space mutation of Sec. 2.3,
+ *   theta[k] = clip(exp(clip(ln parent[k] + sigma * z[step][k], ln lo[k], ln hi[k])), lo[k], hi[k]),
+ * used from the next request on (ln of the parent is carried along, not retaken from the clipped value; exp
+ * is evaluated by a fixed sequence of additions and multiplications, so that it has the same bits on every
+ * processor).  P replays run P independent tuners (different draws, initial weights or time scales).
+ * Needs a chain-consistent trace (the dense segment-row formulation). */
+typedef struct gorgo_online {
+    int32_t window;        /* 1..1024 requests per fitness window                                     */
+    int32_t hop;           /* >= 1 requests between tuner steps                                        */
+    double lo[3], hi[3];   /* clip range per weight, 0 < lo <= hi, finite; lo == hi pins the weight    */
+    double sigma0;         /* initial step size, finite, >= 0                                          */
+    const double* z;       /* DEVICE [P][steps][3] standard normal draws, steps = gorgo_online_steps() */
+    /* outputs, DEVICE, caller-owned, each may be NULL */
+    double* theta_step;    /* [P][steps][3] weights in use after each step                             */
+    double* fitness_step;  /* [P][steps]    window p95 TTFT (ms) seen at each step                     */
+    double* theta_final;   /* [P][3]        parent weights after the last step                         */
+    double* sigma_final;   /* [P]                                                                      */
+    int32_t* accepted;     /* [P]           offspring that replaced their parent                       */
+} gorgo_online;
+
+/* Tuner steps of a replay of N requests: (N - window) / hop + 1 if N >= window, else 0 (at the paper's 128 /
+ * 32, request 672 ends step 18).  Negative on invalid arguments. */
+int64_t gorgo_online_steps(int64_t N, int32_t window, int32_t hop);
+
+/* Evaluate P replays, each with its own online tuner.  As gorgo_eval_population, except that
+ * theta0 (host [P][3], each within [lo, hi]) are the weights of the first window.  Same workspace size. */
+int gorgo_eval_online(const gorgo_trace* t, const gorgo_model* m, const double* rtt_ms, const double* theta0,
+                      const double* scale, int32_t P, const gorgo_online* online, const gorgo_outputs* outputs,
+                      void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* ------------------------------------------------------------------------------------------------ misc
  * Device time (ms, HIP events recorded on the evaluation's stream) of the three stages of the most recent
  * gorgo_eval_population / gorgo_es_step issued by the calling thread: state initialisation, the replay

@@ -31,6 +31,12 @@ class _Outputs(C.Structure):
                 ("p95_ttft_ms", C.c_void_p), ("p95_e2e_ms", C.c_void_p)]
 
 
+class _Online(C.Structure):
+    _fields_ = [("window", C.c_int32), ("hop", C.c_int32), ("lo", C.c_double * 3), ("hi", C.c_double * 3),
+                ("sigma0", C.c_double), ("z", C.c_void_p), ("theta_step", C.c_void_p), ("fitness_step", C.c_void_p),
+                ("theta_final", C.c_void_p), ("sigma_final", C.c_void_p), ("accepted", C.c_void_p)]
+
+
 class EsState(C.Structure):
     _fields_ = [("theta", C.c_double * 3), ("sigma", C.c_double), ("lo", C.c_double * 3), ("hi", C.c_double * 3),
                 ("seed", C.c_uint64), ("generation", C.c_int64), ("best_fitness", C.c_double),
@@ -59,6 +65,10 @@ def lib():
         L.gorgo_workspace_bytes.argtypes = [vp, C.POINTER(_Model), i32, C.POINTER(_Outputs), C.POINTER(C.c_size_t)]
         L.gorgo_eval_population.argtypes = [vp, C.POINTER(_Model), vp, vp, vp, i32, C.POINTER(_Outputs), vp,
                                             C.c_size_t, vp]
+        L.gorgo_online_steps.argtypes = [i64, i32, i32]
+        L.gorgo_online_steps.restype = i64
+        L.gorgo_eval_online.argtypes = [vp, C.POINTER(_Model), vp, vp, vp, i32, C.POINTER(_Online), C.POINTER(_Outputs),
+                                        vp, C.c_size_t, vp]
         L.gorgo_es_init.argtypes = [C.POINTER(EsState), C.c_uint64]
         L.gorgo_es_sample.argtypes = [C.c_uint64, i64, i32, vp]
         L.gorgo_philox4x32_10.argtypes = [vp, vp, vp]
@@ -72,7 +82,7 @@ def lib():
         L.gorgo_query_replay_path.argtypes = [vp, C.POINTER(i32), C.POINTER(i64), C.POINTER(i64)]
         L.gorgo_last_eval_kernel_ms.argtypes = [C.POINTER(dbl)] * 3
         for name in ("gorgo_load_trace", "gorgo_load_trace_arrays", "gorgo_trace_info", "gorgo_workspace_bytes",
-                     "gorgo_eval_population", "gorgo_es_init", "gorgo_es_sample", "gorgo_es_propose",
+                     "gorgo_eval_population", "gorgo_eval_online", "gorgo_es_init", "gorgo_es_sample", "gorgo_es_propose",
                      "gorgo_es_update", "gorgo_es_workspace_bytes", "gorgo_es_step", "gorgo_set_table_factor_percent",
                      "gorgo_last_eval_kernel_ms", "gorgo_set_replay_path", "gorgo_query_replay_path"):
             getattr(L, name).restype = C.c_int
@@ -199,6 +209,13 @@ class EvalResult:
     p95_ttft_ms: object = None
     p95_e2e_ms: object = None
     workspace: object = None
+    # online tuner (eval_online only)
+    theta_step: object = None       # [P, steps, 3] weights in use after each step
+    fitness_step: object = None     # [P, steps] window p95 TTFT seen at each step
+    theta_final: object = None      # [P, 3]
+    sigma_final: object = None      # [P]
+    accepted: object = None         # [P] int32
+    _z: object = None
 
 
 def eval_population(trace: Trace, model: Model, rtt_ms, params, scale, *, per_request: bool = True,
@@ -234,6 +251,67 @@ def eval_population(trace: Trace, model: Model, rtt_ms, params, scale, *, per_re
         _check(lib().gorgo_eval_population(trace._h, C.byref(m), _ptr(rtt), _ptr(par), _ptr(sc), P, C.byref(o),
                                            C.c_void_p(workspace.data_ptr()), workspace.numel(),
                                            C.c_void_p(s.cuda_stream)))
+    return res
+
+
+def online_steps(N: int, window: int = 128, hop: int = 32) -> int:
+    n = lib().gorgo_online_steps(N, window, hop)
+    if n < 0:
+        raise ValueError("window and hop must be >= 1")
+    return n
+
+
+def eval_online(trace: Trace, model: Model, rtt_ms, theta0, z, scale, *, lo, hi, sigma0, window: int = 128,
+                hop: int = 32, per_request: bool = True, p95: bool = True, trajectory: bool = True, workspace=None,
+                stream=None, device="cuda:0") -> EvalResult:
+    """gorgo_eval_online with torch-allocated outputs: P replays, each tuning its weights online.  theta0 [P,3];
+    z [P, steps, 3] standard normal draws (host array or device tensor)."""
+    import torch
+    rtt = _np(rtt_ms, np.float64)
+    th0 = _np(theta0, np.float64)
+    P = th0.shape[0]
+    sc = _np(np.broadcast_to(np.asarray(scale, dtype=np.float64), (P,)), np.float64)
+    if th0.shape != (P, 3) or rtt.shape != (model.R,):
+        raise ValueError("theta0 must be [P,3] and rtt_ms [R]")
+    N = trace.N
+    steps = online_steps(N, window, hop)
+    dev = torch.device(device)
+    zt = z if isinstance(z, torch.Tensor) else torch.from_numpy(_np(z, np.float64))
+    zt = zt.to(device=dev, dtype=torch.float64).contiguous()
+    if tuple(zt.shape) != (P, steps, 3):
+        raise ValueError(f"z must be [P, {steps}, 3]")
+    res = EvalResult()
+    if per_request:
+        res.route = torch.empty((P, N), dtype=torch.uint8, device=dev)
+        res.hit_blocks = torch.empty((P, N), dtype=torch.uint16, device=dev)
+        res.ttft_ms = torch.empty((P, N), dtype=torch.float64, device=dev)
+        res.e2e_ms = torch.empty((P, N), dtype=torch.float64, device=dev)
+    if p95:
+        res.p95_ttft_ms = torch.empty((P,), dtype=torch.float64, device=dev)
+        res.p95_e2e_ms = torch.empty((P,), dtype=torch.float64, device=dev)
+    if trajectory:
+        res.theta_step = torch.empty((P, steps, 3), dtype=torch.float64, device=dev)
+        res.fitness_step = torch.empty((P, steps), dtype=torch.float64, device=dev)
+    res.theta_final = torch.empty((P, 3), dtype=torch.float64, device=dev)
+    res.sigma_final = torch.empty((P,), dtype=torch.float64, device=dev)
+    res.accepted = torch.empty((P,), dtype=torch.int32, device=dev)
+    o = _outputs_struct(res.route, res.hit_blocks, res.ttft_ms, res.e2e_ms, res.p95_ttft_ms, res.p95_e2e_ms)
+
+    def dp(x):
+        return None if x is None else C.c_void_p(x.data_ptr())
+    on = _Online(window, hop, (C.c_double * 3)(*[float(x) for x in lo]), (C.c_double * 3)(*[float(x) for x in hi]),
+                 float(sigma0), dp(zt), dp(res.theta_step), dp(res.fitness_step), dp(res.theta_final),
+                 dp(res.sigma_final), dp(res.accepted))
+    need = workspace_bytes(trace, model, P, o)
+    if workspace is None or workspace.numel() < need:
+        workspace = torch.empty((need,), dtype=torch.uint8, device=dev)
+    res.workspace = workspace
+    s = stream if stream is not None else torch.cuda.current_stream(dev)
+    m = model.c()
+    with torch.cuda.device(dev):
+        _check(lib().gorgo_eval_online(trace._h, C.byref(m), _ptr(rtt), _ptr(th0), _ptr(sc), P, C.byref(on), C.byref(o),
+                                       C.c_void_p(workspace.data_ptr()), workspace.numel(), C.c_void_p(s.cuda_stream)))
+    res._z = zt          # keep the draws alive until the stream has consumed them
     return res
 
 

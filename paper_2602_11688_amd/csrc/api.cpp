@@ -92,7 +92,7 @@ int make_plan(const gorgo_trace* t, const gorgo_model* m, int32_t P, const gorgo
     pl->off_e2e = off;
     if (!o || (!o->e2e_ms && want_p95_e)) off += up256((size_t)P * N * 8);
     pl->off_small = off;
-    off += up256(((size_t)pl->R + 4 * (size_t)P) * 8);
+    off += up256(((size_t)pl->R + 7 * (size_t)P + TUNER_CONSTS) * 8);     // rtt, params, scale; tuner constants, ln theta0
     pl->total = off;
     return GORGO_OK;
 }
@@ -144,10 +144,14 @@ int gorgo_workspace_bytes(const gorgo_trace* t, const gorgo_model* m, int32_t P,
     return GORGO_OK;
 }
 
-int gorgo_eval_population(const gorgo_trace* t, const gorgo_model* m, const double* rtt_ms, const double* params,
-                          const double* scale, int32_t P, const gorgo_outputs* outputs, void* workspace,
-                          size_t workspace_bytes, void* hip_stream) {
-    clear_error();
+}  // extern "C"
+
+namespace {
+
+// Validation, small copies and launches common to the fixed-weight and the online evaluation.
+int evaluate(const gorgo_trace* t, const gorgo_model* m, const double* rtt_ms, const double* params,
+             const double* scale, int32_t P, const gorgo_online* online, const gorgo_outputs* outputs, void* workspace,
+             size_t workspace_bytes, void* hip_stream) {
     int rc = check_model(t, m);
     if (rc) return rc;
     if (!rtt_ms || !params || !scale || !outputs) return fail(GORGO_ERR_INVALID_ARG, "a required pointer is NULL");
@@ -164,6 +168,37 @@ int gorgo_eval_population(const gorgo_trace* t, const gorgo_model* m, const doub
     for (int32_t p = 0; p < P; ++p)
         if (!std::isfinite(scale[p]) || scale[p] < 0 || scale[p] > 1e6)
             return fail(GORGO_ERR_NONFINITE, "scale[" + std::to_string(p) + "] must be finite and in 0..1e6");
+    std::vector<double> tuner;      // constants, then ln theta0[P][3]
+    int64_t steps = 0;
+    if (online) {
+        if (pl.path != PATH_SEGMENTS)
+            return fail(GORGO_ERR_INVALID_ARG, "the online tuner needs a chain-consistent trace (segment formulation)");
+        steps = gorgo_online_steps(pl.N, online->window, online->hop);
+        if (steps < 0 || online->window > 1024) return fail(GORGO_ERR_INVALID_ARG, "window must be in 1..1024 and hop >= 1");
+        if (steps > 0 && !online->z) return fail(GORGO_ERR_INVALID_ARG, "online->z is NULL");
+        if (!std::isfinite(online->sigma0) || online->sigma0 < 0 || online->sigma0 > 1e3)
+            return fail(GORGO_ERR_NONFINITE, "sigma0 must be finite and in 0..1e3");
+        for (int k = 0; k < 3; ++k) {
+            const double lo = online->lo[k], hi = online->hi[k];
+            if (!std::isfinite(lo) || !std::isfinite(hi) || lo < 1e-100 || hi > 1e100 || lo > hi)
+                return fail(GORGO_ERR_NONFINITE, "lo and hi must satisfy 1e-100 <= lo <= hi <= 1e100");
+            for (int32_t p = 0; p < P; ++p)
+                if (params[3 * (size_t)p + k] < lo || params[3 * (size_t)p + k] > hi)
+                    return fail(GORGO_ERR_INVALID_ARG, "theta0[" + std::to_string(p) + "][" + std::to_string(k) +
+                                                           "] is outside [lo, hi]");
+        }
+        tuner.assign(TUNER_CONSTS + 3 * (size_t)P, 0.0);
+        for (int k = 0; k < 3; ++k) {
+            tuner[k] = online->lo[k];
+            tuner[3 + k] = online->hi[k];
+            tuner[6 + k] = std::log(online->lo[k]);
+            tuner[9 + k] = std::log(online->hi[k]);
+        }
+        tuner[12] = online->sigma0;
+        tuner[13] = std::exp(0.4);       // 1/5 rule: sigma * exp((s - 1/5) / 2) with s = 1 ...
+        tuner[14] = std::exp(-0.1);      // ... and s = 0
+        for (size_t j = 0; j < 3 * (size_t)P; ++j) tuner[TUNER_CONSTS + j] = std::log(params[j]);
+    }
     if (!workspace) return fail(GORGO_ERR_WORKSPACE, "workspace is NULL");
     if (reinterpret_cast<uintptr_t>(workspace) & 255) return fail(GORGO_ERR_WORKSPACE, "workspace must be 256-byte aligned");
     if (workspace_bytes < pl.total)
@@ -176,9 +211,27 @@ int gorgo_eval_population(const gorgo_trace* t, const gorgo_model* m, const doub
     double* d_rtt = reinterpret_cast<double*>(ws + pl.off_small);
     double* d_params = d_rtt + pl.R;
     double* d_scale = d_params + 3 * (size_t)P;
+    double* d_tuner = d_scale + P;
     if ((rc = copy_small_to_device(d_rtt, rtt_ms, sizeof(double) * pl.R, hip_stream))) return rc;
     if ((rc = copy_small_to_device(d_params, params, sizeof(double) * 3 * (size_t)P, hip_stream))) return rc;
     if ((rc = copy_small_to_device(d_scale, scale, sizeof(double) * (size_t)P, hip_stream))) return rc;
+    OnlineLaunch ol;
+    if (online) {
+        // (the host vector may go away when this function returns: the copy must have been taken by then)
+        if ((rc = copy_small_to_device(d_tuner, tuner.data(), sizeof(double) * tuner.size(), hip_stream))) return rc;
+        if ((rc = wait_for_copies(hip_stream))) return rc;
+        ol.window = online->window;
+        ol.hop = online->hop;
+        ol.steps = steps;
+        ol.tuner = d_tuner;
+        ol.ln_theta0 = d_tuner + TUNER_CONSTS;
+        ol.z = online->z;
+        ol.theta_step = online->theta_step;
+        ol.fitness_step = online->fitness_step;
+        ol.theta_final = online->theta_final;
+        ol.sigma_final = online->sigma_final;
+        ol.accepted = online->accepted;
+    }
 
     uint8_t* route = outputs->route;
     if (!route && pl.path == PATH_BLOCKS) route = reinterpret_cast<uint8_t*>(ws + pl.off_route);
@@ -186,11 +239,36 @@ int gorgo_eval_population(const gorgo_trace* t, const gorgo_model* m, const doub
     if (!ttft && outputs->p95_ttft_ms) ttft = reinterpret_cast<double*>(ws + pl.off_ttft);
     double* e2e = outputs->e2e_ms;
     if (!e2e && outputs->p95_e2e_ms) e2e = reinterpret_cast<double*>(ws + pl.off_e2e);
-    rc = launch_replay(t, pl, d_rtt, d_params, d_scale, route, outputs->hit_blocks, ttft, e2e, workspace, hip_stream);
+    rc = launch_replay(t, pl, d_rtt, d_params, d_scale, route, outputs->hit_blocks, ttft, e2e, workspace, hip_stream,
+                       online ? &ol : nullptr);
     if (rc) return rc;
     if (outputs->p95_ttft_ms && (rc = launch_p95(ttft, pl.N, P, outputs->p95_ttft_ms, hip_stream))) return rc;
     if (outputs->p95_e2e_ms && (rc = launch_p95(e2e, pl.N, P, outputs->p95_e2e_ms, hip_stream))) return rc;
     return GORGO_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int gorgo_eval_population(const gorgo_trace* t, const gorgo_model* m, const double* rtt_ms, const double* params,
+                          const double* scale, int32_t P, const gorgo_outputs* outputs, void* workspace,
+                          size_t workspace_bytes, void* hip_stream) {
+    clear_error();
+    return evaluate(t, m, rtt_ms, params, scale, P, nullptr, outputs, workspace, workspace_bytes, hip_stream);
+}
+
+int64_t gorgo_online_steps(int64_t N, int32_t window, int32_t hop) {
+    if (N < 0 || window < 1 || hop < 1) return -1;
+    return N >= window ? (N - window) / hop + 1 : 0;
+}
+
+int gorgo_eval_online(const gorgo_trace* t, const gorgo_model* m, const double* rtt_ms, const double* theta0,
+                      const double* scale, int32_t P, const gorgo_online* online, const gorgo_outputs* outputs,
+                      void* workspace, size_t workspace_bytes, void* hip_stream) {
+    clear_error();
+    if (!online) return fail(GORGO_ERR_INVALID_ARG, "online is NULL");
+    return evaluate(t, m, rtt_ms, theta0, scale, P, online, outputs, workspace, workspace_bytes, hip_stream);
 }
 
 int gorgo_last_eval_kernel_ms(double* fill_ms, double* replay_ms, double* select_ms) {

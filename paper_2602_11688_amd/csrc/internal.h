@@ -74,15 +74,31 @@ struct Plan {
     size_t total = 0;
 };
 
+// Online tuner of one launch (device pointers; see gorgo_online in gorgo.h).
+struct OnlineLaunch {
+    int32_t window = 0, hop = 0;
+    int64_t steps = 0;
+    const double* tuner = nullptr;       // lo[3], hi[3], ln lo[3], ln hi[3], sigma0, exp(0.4), exp(-0.1)
+    const double* ln_theta0 = nullptr;   // [P][3]
+    const double* z = nullptr;
+    double* theta_step = nullptr;
+    double* fitness_step = nullptr;
+    double* theta_final = nullptr;
+    double* sigma_final = nullptr;
+    int32_t* accepted = nullptr;
+};
+constexpr int TUNER_CONSTS = 16;         // doubles reserved for OnlineLaunch::tuner
+
 // kernels.hip
 int launch_replay(const gorgo_trace* t, const Plan& pl, const double* d_rtt, const double* d_params,
                   const double* d_scale, uint8_t* route, uint16_t* hit, double* ttft, double* e2e,
-                  void* workspace, void* stream);
+                  void* workspace, void* stream, const OnlineLaunch* online = nullptr);
 int launch_p95(const double* x, int64_t N, int32_t P, double* out, void* stream);
 int last_eval_kernel_ms(double* fill_ms, double* replay_ms, double* select_ms);
 int upload_trace(const gorgo_trace* t);
 void release_device_trace(gorgo_trace* t);
 int copy_small_to_device(void* dst, const void* src, size_t bytes, void* stream);
+int wait_for_copies(void* stream);
 int copy_small_to_host_sync(void* dst, const void* src, size_t bytes, void* stream);
 
 }  // namespace gorgo

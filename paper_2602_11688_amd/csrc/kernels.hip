@@ -470,6 +470,11 @@ int copy_small_to_device(void* dst, const void* src, size_t bytes, void* stream)
     return e == hipSuccess ? GORGO_OK : hip_fail(e, "hipMemcpyAsync(H2D)");
 }
 
+int wait_for_copies(void* stream) {
+    hipError_t e = hipStreamSynchronize(static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? GORGO_OK : hip_fail(e, "hipStreamSynchronize");
+}
+
 int copy_small_to_host_sync(void* dst, const void* src, size_t bytes, void* stream) {
     hipError_t e = hipMemcpyAsync(dst, src, bytes, hipMemcpyDeviceToHost, static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return hip_fail(e, "hipMemcpyAsync(D2H)");
@@ -479,7 +484,7 @@ int copy_small_to_host_sync(void* dst, const void* src, size_t bytes, void* stre
 
 int launch_replay(const gorgo_trace* t, const Plan& pl, const double* d_rtt, const double* d_params,
                   const double* d_scale, uint8_t* route, uint16_t* hit, double* ttft, double* e2e,
-                  void* workspace, void* stream) {
+                  void* workspace, void* stream, const OnlineLaunch* online) {
     hipStream_t s = static_cast<hipStream_t>(stream);
     char* ws = static_cast<char*>(workspace);
     g_marks.valid = false;
@@ -511,6 +516,11 @@ int launch_replay(const gorgo_trace* t, const Plan& pl, const double* d_rtt, con
         a.hit = hit;
         a.ttft = ttft;
         a.e2e = e2e;
+        a.window = a.hop = 0;
+        a.steps = 0;
+        a.tuner = a.ln_theta0 = a.z = nullptr;
+        a.theta_step = a.fitness_step = a.theta_final = a.sigma_final = nullptr;
+        a.accepted = nullptr;
         const size_t cells = (size_t)pl.P * (size_t)a.nseg * pl.R;
         if (cells) {
             size_t blocks = (cells + 255) / 256;
@@ -519,12 +529,29 @@ int launch_replay(const gorgo_trace* t, const Plan& pl, const double* d_rtt, con
             if ((e = hipGetLastError()) != hipSuccess) return hip_fail(e, "launch fill_i32");
         }
         mark(1, s);
-        if (pl.N > 0) {
-            const size_t lds = replay_segments_lds_bytes(pl.R, pl.B);
-            hipLaunchKernelGGL(replay_segments_kernel, dim3((unsigned)pl.P), dim3(SEG_THREADS), lds, s, a);
+        if (pl.N > 0 || online) {      // (an empty trace still reports the tuner's initial state)
+            if (online) {
+                a.window = online->window;
+                a.hop = online->hop;
+                a.steps = online->steps;
+                a.tuner = online->tuner;
+                a.ln_theta0 = online->ln_theta0;
+                a.z = online->z;
+                a.theta_step = online->theta_step;
+                a.fitness_step = online->fitness_step;
+                a.theta_final = online->theta_final;
+                a.sigma_final = online->sigma_final;
+                a.accepted = online->accepted;
+                const size_t lds = replay_segments_lds_bytes(pl.R, pl.B, online->window);
+                hipLaunchKernelGGL(replay_segments_kernel<true>, dim3((unsigned)pl.P), dim3(SEG_THREADS), lds, s, a);
+            } else {
+                const size_t lds = replay_segments_lds_bytes(pl.R, pl.B, 0);
+                hipLaunchKernelGGL(replay_segments_kernel<false>, dim3((unsigned)pl.P), dim3(SEG_THREADS), lds, s, a);
+            }
             if ((e = hipGetLastError()) != hipSuccess) return hip_fail(e, "launch replay_segments_kernel");
         }
     } else {
+        if (online) return fail(GORGO_ERR_INVALID_ARG, "the online tuner needs the segment formulation");
         ReplayArgs a;
         a.ts = t->dev.ts;
         a.in_len = t->dev.in_len;

@@ -64,6 +64,17 @@ struct SegArgs {
     uint16_t* hit;   // nullable
     double* ttft;    // nullable
     double* e2e;     // nullable
+    // online tuner (only read by the kernel's online variant)
+    int32_t window, hop;
+    int64_t steps;             // tuner steps of one replay
+    const double* tuner;       // lo[3], hi[3], ln lo[3], ln hi[3], sigma0, exp(0.4), exp(-0.1)
+    const double* ln_theta0;   // [P][3]
+    const double* z;           // [P][steps][3]
+    double* theta_step;        // [P][steps][3], nullable
+    double* fitness_step;      // [P][steps], nullable
+    double* theta_final;       // [P][3], nullable
+    double* sigma_final;       // [P], nullable
+    int32_t* accepted;         // [P], nullable
 };
 
 constexpr int SEG_STAGE = 512;   // segment references of a 64-request batch staged in LDS
@@ -82,6 +93,7 @@ struct SegComm {
     unsigned seq_q;
     int abandoned;                    // a wavefront gave up waiting: both leave, latencies are poisoned
     unsigned long long choice;        // uncached tokens | (((r + 1) mod 2^26) << 6 | replica) << 32
+    double w[3];                      // online tuner: weights in use, valid with seq_q like q
 };
 
 __device__ __forceinline__ void lds_release() { __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront"); }
@@ -93,8 +105,78 @@ __device__ __forceinline__ void wave_sync() {
     __builtin_amdgcn_wave_barrier();
 }
 
-__host__ __device__ inline size_t replay_segments_lds_bytes(int R, int B) {   // dynamic part
-    return Queues::bytes(R, B);
+__host__ __device__ inline size_t replay_segments_lds_bytes(int R, int B, int window) {   // dynamic part
+    return Queues::bytes(R, B) + (size_t)((window + 7) & ~7) * sizeof(double);   // queues, then the tuner's TTFT window
+}
+
+// exp(x) for |x| <= 700 from additions and multiplications only, in a fixed order, so that the weights the
+// online tuner proposes (Sec. 2.3) have the same bits wherever they are computed: k = floor(x / ln 2 + 1/2),
+// r = (x - k LN2_HI) - k LN2_LO with ln 2 split so that k LN2_HI is exact, exp(r) as its Taylor polynomial of
+// degree 13 by Horner's rule from the highest term down, times 2^k.
+__device__ __forceinline__ double tuner_exp(double x) {
+    const double INV_LN2 = 1.44269504088896338700e+00;
+    const double LN2_HI = 6.93147180369123816490e-01;
+    const double LN2_LO = 1.90821492927058770002e-10;
+    const double k = __builtin_floor(x * INV_LN2 + 0.5);
+    const double r = (x - k * LN2_HI) - k * LN2_LO;
+    double p = 1.0 / 6227020800.0;
+    p = p * r + 1.0 / 479001600.0;
+    p = p * r + 1.0 / 39916800.0;
+    p = p * r + 1.0 / 3628800.0;
+    p = p * r + 1.0 / 362880.0;
+    p = p * r + 1.0 / 40320.0;
+    p = p * r + 1.0 / 5040.0;
+    p = p * r + 1.0 / 720.0;
+    p = p * r + 1.0 / 120.0;
+    p = p * r + 1.0 / 24.0;
+    p = p * r + 1.0 / 6.0;
+    p = p * r + 1.0 / 2.0;
+    p = p * r + 1.0;
+    p = p * r + 1.0;
+    const unsigned long long bits = (unsigned long long)((long long)k + 1023) << 52;
+    return p * __longlong_as_double((long long)bits);
+}
+__device__ __forceinline__ double clip(double x, double lo, double hi) {
+    const double up = x < lo ? lo : x;
+    return hi < up ? hi : up;
+}
+
+// k-th smallest (1-based) of the W values of `ring` (LDS), by counting: the element with fewer than k values
+// below it and at least k not above it.  Every lane takes the elements lane, lane + 64, ..., two at a time;
+// the values they are counted against are read eight at a time (the ring is padded with +inf up to a multiple
+// of eight, which no count sees).
+__device__ __forceinline__ double window_kth(const double* ring, int W, int kth, int lane) {
+    double found = 0.0;
+    bool have = false;
+    const int W8 = (W + 7) & ~7;
+    for (int e0 = 0; e0 < W; e0 += 2 * WAVE) {
+        const int ea = e0 + lane, eb = e0 + WAVE + lane;
+        const bool va = ea < W, vb = eb < W;
+        const double xa = ring[va ? ea : 0], xb = ring[vb ? eb : 0];
+        int less_a = 0, leq_a = 0, less_b = 0, leq_b = 0;
+        for (int i = 0; i < W8; i += 8) {
+            double v[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) v[j] = ring[i + j];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                less_a += v[j] < xa ? 1 : 0;
+                leq_a += v[j] <= xa ? 1 : 0;
+                less_b += v[j] < xb ? 1 : 0;
+                leq_b += v[j] <= xb ? 1 : 0;
+            }
+        }
+        if (va && less_a < kth && kth <= leq_a) {
+            found = xa;
+            have = true;
+        }
+        if (vb && less_b < kth && kth <= leq_b) {
+            found = xb;
+            have = true;
+        }
+    }
+    const unsigned long long who = __ballot(have);      // every holder has the same value
+    return readlane_f64(found, __ffsll(who) - 1);
 }
 
 // Rows of one request's first SEG_CHUNK segments as seen by this lane (= replica), with the segments' end
@@ -118,6 +200,7 @@ __device__ __forceinline__ int cached_in(int32_t rl, int pos, int end, int c_r, 
 
 // Queue wavefront of a replay: for every request, retire what has completed by its arrival, publish the load
 // signals, wait for the cache wavefront's choice, serve the request there.  Writes the latencies.
+template <bool ONLINE>
 __device__ __forceinline__ void queue_wave(const SegArgs& a, int p, int lane, unsigned char* lds_raw, SegComm* comm) {
     const int R = a.R;
     const int64_t N = a.N;
@@ -125,6 +208,25 @@ __device__ __forceinline__ void queue_wave(const SegArgs& a, int p, int lane, un
     Q.carve(lds_raw, R, a.B, lane);
     Q.init(lane);
     wave_sync();
+    // Online tuner (Sec. 2.3, Sec. 4), run here because this wavefront has the TTFTs: after every hop the p95
+    // TTFT of the last `window` requests is the fitness of the weights in use; they replace the parent iff they
+    // beat it; the step size follows the 1/5 rule; the next offspring is a log-space mutation of the parent.
+    // The state is the same in every lane.
+    double* const ring = reinterpret_cast<double*>(lds_raw + Queues::bytes(R, a.B));
+    const int W = ONLINE ? a.window : 0, H = ONLINE ? a.hop : 0;
+    const int kth = (95 * W + 99) / 100;
+    int ring_pos = 0, until_step = W;
+    int64_t step = 0;
+    int accepted = 0;
+    bool have_parent = false;
+    double ln_par[3] = {0.0, 0.0, 0.0}, ln_cur[3] = {0.0, 0.0, 0.0};
+    double f_par = 0.0, sigma = 0.0;
+    if (ONLINE) {
+        for (int k = 0; k < 3; ++k) ln_par[k] = ln_cur[k] = a.ln_theta0[3 * (size_t)p + k];
+        sigma = a.tuner[12];
+        if (W + lane < ((W + 7) & ~7)) ring[W + lane] = INFINITY;     // padding (entries below W are written before use)
+        wave_sync();
+    }
     const double sc = a.scale[p];
     const double my_rtt = lane < R ? a.rtt[lane] : 0.0;
     Rec* const rec = a.rec + (size_t)p * N;
@@ -164,12 +266,55 @@ __device__ __forceinline__ void queue_wave(const SegArgs& a, int p, int lane, un
             Q.serve(r, best, t, my_rtt, (int64_t)(int)lo, L, O, a.a_pf, a.a_dec, rec, lane, &ttft, &e2e);
             o_ttft = lane == i ? ttft : o_ttft;
             o_e2e = lane == i ? e2e : o_e2e;
+            if (ONLINE) {
+                if (lane == 0) ring[ring_pos] = ttft;
+                ring_pos = ring_pos + 1 == W ? 0 : ring_pos + 1;
+                if (--until_step == 0) {
+                    until_step = H;
+                    wave_sync();
+                    const double f = window_kth(ring, W, kth, lane);
+                    if (!have_parent) {
+                        f_par = f;                 // the first window measures the initial weights: the parent
+                        have_parent = true;
+                    } else {
+                        const bool success = f < f_par;
+                        if (success) {
+                            for (int k = 0; k < 3; ++k) ln_par[k] = ln_cur[k];
+                            f_par = f;
+                            ++accepted;
+                        }
+                        sigma = sigma * (success ? a.tuner[13] : a.tuner[14]);
+                    }
+                    double th[3];
+                    for (int k = 0; k < 3; ++k) {
+                        const double zk = a.z[((size_t)p * a.steps + step) * 3 + k];
+                        const double moved = ln_par[k] + sigma * zk;
+                        ln_cur[k] = clip(moved, a.tuner[6 + k], a.tuner[9 + k]);
+                        th[k] = clip(tuner_exp(ln_cur[k]), a.tuner[k], a.tuner[3 + k]);
+                    }
+                    if (lane == 0) {
+                        for (int k = 0; k < 3; ++k) st(&comm->w[k], th[k]);    // published with the next load signals
+                        if (a.fitness_step) a.fitness_step[(size_t)p * a.steps + step] = f;
+                        if (a.theta_step)
+                            for (int k = 0; k < 3; ++k) a.theta_step[((size_t)p * a.steps + step) * 3 + k] = th[k];
+                    }
+                    ++step;
+                    wave_sync();
+                }
+            }
         }
         if (lane < nb && !dead) {
             const size_t o = (size_t)p * N + r0 + lane;
             if (a.ttft) a.ttft[o] = o_ttft;
             if (a.e2e) a.e2e[o] = o_e2e;
         }
+    }
+    if (ONLINE && lane == 0 && !dead) {
+        if (a.theta_final)
+            for (int k = 0; k < 3; ++k)
+                a.theta_final[3 * (size_t)p + k] = clip(tuner_exp(ln_par[k]), a.tuner[k], a.tuner[3 + k]);
+        if (a.sigma_final) a.sigma_final[p] = sigma;
+        if (a.accepted) a.accepted[p] = accepted;
     }
     if (dead) {
         // the partner never answered (cannot happen unless the kernel is wrong): leave, and make sure nobody
@@ -182,6 +327,7 @@ __device__ __forceinline__ void queue_wave(const SegArgs& a, int p, int lane, un
     }
 }
 
+template <bool ONLINE>
 __global__ void __launch_bounds__(SEG_THREADS) replay_segments_kernel(SegArgs a) {
     extern __shared__ __align__(16) unsigned char lds_raw[];
     __shared__ SegRef stage[SEG_STAGE + SEG_CHUNK];    // padded: whole chunks are read unconditionally
@@ -196,10 +342,11 @@ __global__ void __launch_bounds__(SEG_THREADS) replay_segments_kernel(SegArgs a)
         comm.seq_q = 0;
         comm.abandoned = 0;
         comm.choice = 0;
+        for (int k = 0; k < 3; ++k) comm.w[k] = a.params[3 * (size_t)p + k];
     }
     __syncthreads();
     if (threadIdx.x >= WAVE) {
-        queue_wave(a, p, lane, lds_raw, &comm);
+        queue_wave<ONLINE>(a, p, lane, lds_raw, &comm);
         return;
     }
     __builtin_amdgcn_s_setprio(3);      // the cache wavefront has the longer loop: it goes first at issue
@@ -208,6 +355,7 @@ __global__ void __launch_bounds__(SEG_THREADS) replay_segments_kernel(SegArgs a)
     for (int x = lane; x < SEG_CHUNK; x += WAVE) stage[SEG_STAGE + x] = SegRef{0, 0};
     wave_sync();
 
+    // (with the online tuner the weights come with the load signals instead)
     const double w_rtt = a.params[3 * (size_t)p + 0];
     const double w_prefill = a.params[3 * (size_t)p + 1];
     const double w_queue = a.params[3 * (size_t)p + 2];
@@ -404,15 +552,21 @@ __global__ void __launch_bounds__(SEG_THREADS) replay_segments_kernel(SegArgs a)
             // the load signals of this request come from the queue wavefront (normally already there);
             // everything that does not need them is finished first, so that little is left between reading
             // them and announcing the choice
-            const double score_rp = eq3_without_queue(w_rtt, w_prefill, my_rtt, a.a_pf, my_u);
+            const double score_rp = ONLINE ? 0.0 : eq3_without_queue(w_rtt, w_prefill, my_rtt, a.a_pf, my_u);
             asm volatile("" : "+v"(my_u), "+v"(my_m));
             double score_rp_ready = score_rp;
             asm volatile("" : "+v"(score_rp_ready));
             double my_q;
+            double now_rtt = 0.0, now_prefill = 0.0, now_queue = 0.0;
             for (int spins = 0;; ++spins) {
                 const unsigned seq = __builtin_amdgcn_readfirstlane(ld(&comm.seq_q));
                 lds_acquire();
                 my_q = ld(&comm.q[lane]);
+                if (ONLINE) {
+                    now_rtt = ld(&comm.w[0]);
+                    now_prefill = ld(&comm.w[1]);
+                    now_queue = ld(&comm.w[2]);
+                }
                 if (seq == (unsigned)(r + 1)) break;
                 if (spins > SEG_SPIN_LIMIT || ld(&comm.abandoned) != 0) {
                     dead = true;
@@ -423,7 +577,8 @@ __global__ void __launch_bounds__(SEG_THREADS) replay_segments_kernel(SegArgs a)
                 st(&comm.abandoned, 1);
                 return;
             }
-            const double my_score = eq3_with_queue(score_rp_ready, w_queue, a.a_pf, my_q);
+            const double my_score = ONLINE ? eq3_score(now_rtt, now_prefill, now_queue, my_rtt, a.a_pf, my_u, my_q)
+                                           : eq3_with_queue(score_rp_ready, w_queue, a.a_pf, my_q);
             const int best = wave_argmin(my_score, lane, R);
             const bool is_best = lane == best;
             const int m_best = __builtin_amdgcn_readlane(my_m, best);

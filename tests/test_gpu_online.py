@@ -1,0 +1,140 @@
+"""GPU parity of the online tuner (one (1+1) evolution strategy inside every replay, Sec. 2.3 and Sec. 4) against
+the CPU oracle, through the C ABI: routes, hit counts, window fitness and accept counts bit-exact, weights and
+latencies to 1e-9 relative (they are the same bits in practice)."""
+import json
+import os
+
+import numpy as np
+import pytest
+
+import paper_2602_11688_amd as g
+from oracle import binding as ob
+from synth import tracegen as tg
+from synth.tracegen import Trace
+from tests.gpu_helpers import RTOL, load
+from tests.helpers import GOLDEN
+
+pytestmark = pytest.mark.gpu
+
+LO, HI = [0.05, 1.0, 0.05], [2.0, 1.0, 0.5]
+
+
+def _model(wl, **over):
+    kw = dict(R=wl.R, batch=wl.batch, cache_blocks=wl.cache_blocks, prefill_ms_per_token=wl.prefill_ms_per_token,
+              decode_ms_per_token=wl.decode_ms_per_token)
+    kw.update(over)
+    return g.Model(**kw)
+
+
+def _check(tr, model, rtt, theta0, z, scale, window, hop, lo=LO, hi=HI, sigma0=0.5, replays=None):
+    import torch
+    theta0 = np.asarray(theta0, np.float64)
+    P = theta0.shape[0]
+    scale = np.broadcast_to(np.asarray(scale, np.float64), (P,))
+    res = g.eval_online(load(tr), model, rtt, theta0, z, scale, lo=lo, hi=hi, sigma0=sigma0, window=window, hop=hop)
+    torch.cuda.synchronize()
+    steps = g.online_steps(tr.N, window, hop)
+    for p in (range(P) if replays is None else replays):
+        ref = ob.replay_online(tr, R=model.R, batch=model.batch, cache_blocks=model.cache_blocks,
+                               prefill_ms_per_token=model.prefill_ms_per_token,
+                               decode_ms_per_token=model.decode_ms_per_token, rtt_ms=rtt, theta0=theta0[p], z=z[p], lo=lo,
+                               hi=hi, sigma0=sigma0, window=window, hop=hop, scale=float(scale[p]),
+                               block_tokens=model.block_tokens)
+        bad = np.nonzero(res.route[p].cpu().numpy() != ref.route)[0]
+        assert bad.size == 0, f"replay {p}: first route mismatch at request {bad[0]} ({bad.size} in all)"
+        assert np.array_equal(res.hit_blocks[p].cpu().numpy(), ref.hit_blocks)
+        np.testing.assert_allclose(res.ttft_ms[p].cpu().numpy(), ref.ttft_ms, rtol=RTOL, atol=0)
+        np.testing.assert_allclose(res.e2e_ms[p].cpu().numpy(), ref.e2e_ms, rtol=RTOL, atol=0)
+        assert ref.steps == steps
+        assert np.array_equal(res.fitness_step[p].cpu().numpy(), ref.fitness_step)
+        assert np.array_equal(res.theta_step[p].cpu().numpy(), ref.theta_step), f"replay {p}: weights differ"
+        assert np.array_equal(res.theta_final[p].cpu().numpy(), ref.theta_final)
+        assert float(res.sigma_final[p]) == ref.sigma_final and int(res.accepted[p]) == ref.accepted
+        if tr.N:
+            assert abs(float(res.p95_ttft_ms[p]) - ref.p95_ttft_ms) <= RTOL * abs(ref.p95_ttft_ms)
+    return res
+
+
+def test_hand_worked_tuner_run():
+    import torch
+    with open(os.path.join(GOLDEN, "online_tuner_hand.json")) as f:
+        gold = json.load(f)
+    L = np.array(gold["input_length"], np.int32)
+    n = L.astype(np.int64)
+    tr = Trace(np.arange(len(L), dtype=np.int64) * 1000, L, np.ones(len(L), np.int32),
+               np.concatenate([[0], np.cumsum(n)]).astype(np.int64), np.arange(1, int(n.sum()) + 1, dtype=np.int64))
+    m = gold["model"]
+    model = g.Model(m["R"], m["batch"], m["cache_blocks"], m["prefill_ms_per_token"], m["decode_ms_per_token"],
+                    block_tokens=m["block_tokens"])
+    h = g.Trace.from_arrays(tr.ts_ms, tr.in_len, tr.out_len, tr.blk_off, tr.hash_ids, block_tokens=m["block_tokens"])
+    res = g.eval_online(h, model, gold["rtt_ms"], [gold["theta0"]], np.array([gold["z"]], np.float64), 1.0,
+                        lo=gold["lo"], hi=gold["hi"], sigma0=gold["sigma0"], window=gold["window"], hop=gold["hop"])
+    torch.cuda.synchronize()
+    e = gold["expected"]
+    assert res.ttft_ms[0].cpu().numpy().tolist() == e["ttft_ms"]
+    assert res.fitness_step[0].cpu().numpy().tolist() == e["fitness_step"]
+    np.testing.assert_allclose(res.theta_step[0].cpu().numpy(), e["theta_step"], rtol=4e-16, atol=0)
+    np.testing.assert_allclose(res.theta_final[0].cpu().numpy(), e["theta_final"], rtol=4e-16, atol=0)
+    assert int(res.accepted[0]) == e["accepted"]
+    assert abs(float(res.sigma_final[0]) / gold["sigma0"] - 1.0) < 1e-15
+
+
+def test_config1_paper_window_all_replays():
+    wl = tg.config(1)
+    steps = g.online_steps(wl.trace.N, 128, 32)
+    rng = np.random.default_rng(11)
+    P = 8
+    z = rng.standard_normal((P, steps, 3))
+    theta0 = np.tile([0.5, 1.0, 0.1], (P, 1))
+    scale = np.array([1.0, 1.0, 2.0, 4.0, 4.0, 8.0, 0.5, 3.0])     # saturated to idle: accept rates differ
+    _check(wl.trace, _model(wl), wl.rtt_ms, theta0, z, scale, 128, 32)
+    # a run in which offspring do replace the parent (the same one the oracle's pins use)
+    tr = wl.trace.head(1200)
+    z1 = np.random.default_rng(5).standard_normal((1, g.online_steps(1200, 128, 32), 3))
+    res = _check(tr, _model(wl), wl.rtt_ms, [[0.5, 1.0, 0.1]], z1, 4.0, 128, 32)
+    assert int(res.accepted[0]) > 0
+
+
+def test_config2_bounded_cache_draws_from_the_library():
+    wl = tg.config(2, 6000)
+    steps = g.online_steps(wl.trace.N, 128, 32)
+    P = 6
+    z = g.es_sample(77, 0, P * steps).reshape(P, steps, 3)        # the library's own counter-based generator
+    theta0 = np.tile([0.5, 1.0, 0.1], (P, 1))
+    theta0[1] = [2.0, 1.0, 0.05]
+    theta0[2] = [0.05, 1.0, 0.5]
+    _check(wl.trace, _model(wl), wl.rtt_ms, theta0, z, 1.0, 128, 32)
+
+
+@pytest.mark.parametrize("window,hop,n", [(1, 1, 300), (4, 2, 301), (100, 7, 777), (1024, 64, 2000), (64, 200, 1000),
+                                          (128, 32, 127), (128, 32, 128), (33, 5, 0)])
+def test_window_and_hop_shapes(window, hop, n):
+    wl = tg.config(1, max(n, 1))
+    tr = wl.trace.head(n)
+    steps = g.online_steps(n, window, hop)
+    z = np.random.default_rng(window + hop).standard_normal((3, steps, 3))
+    theta0 = np.array([[0.5, 1.0, 0.1], [1.0, 1.0, 0.3], [0.06, 1.0, 0.06]])
+    _check(tr, _model(wl), wl.rtt_ms, theta0, z, [3.0, 1.0, 5.0], window, hop, sigma0=1.5)
+
+
+def test_all_weights_tuned_and_wide_range():
+    wl = tg.config(3, 3000)
+    steps = g.online_steps(3000, 128, 32)
+    z = 3.0 * np.random.default_rng(2).standard_normal((4, steps, 3))
+    theta0 = np.tile([1.0, 1.0, 1.0], (4, 1))
+    _check(wl.trace, _model(wl), wl.rtt_ms, theta0, z, 1.0, 128, 32, lo=[1e-6, 1e-3, 1e-9], hi=[1e6, 1e3, 1e2], sigma0=2.0)
+
+
+def test_online_needs_a_chain_consistent_trace_and_valid_arguments():
+    bad = tg.random_small(3, 200, 3, consistent=False)
+    model = g.Model(3, 2, 0, 0.05, 20.0)
+    z = np.zeros((1, g.online_steps(200, 16, 4), 3))
+    with pytest.raises(g.GorgoError):
+        g.eval_online(load(bad), model, [10.0, 20.0, 30.0], [[0.5, 1.0, 0.1]], z, 1.0, lo=LO, hi=HI, sigma0=0.5,
+                      window=16, hop=4)
+    ok = tg.random_small(3, 200, 3, consistent=True)
+    with pytest.raises(g.GorgoError):      # theta0 outside the range
+        g.eval_online(load(ok), model, [10.0, 20.0, 30.0], [[5.0, 1.0, 0.1]], z, 1.0, lo=LO, hi=HI, sigma0=0.5,
+                      window=16, hop=4)
+    with pytest.raises(ValueError):
+        g.online_steps(10, 0, 1)
