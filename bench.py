@@ -83,12 +83,27 @@ def recorded_counters(kernel, workload_key):
     return rec
 
 
-def cpu_baseline(wl, params, n_req, threads):
-    """The oracle as it stands, one replay per thread, on the first n_req requests of the workload."""
+def cpu_baseline(wl, params, n_req, threads, online=None):
+    """The oracle as it stands, one replay per thread, on the first n_req requests of the workload (with its online
+    tuner when `online` = (z[P, steps, 3], lo, hi, sigma0) is given)."""
     from concurrent.futures import ThreadPoolExecutor
     from oracle import binding as ob
     tr = wl.trace.head(n_req)
     ob.lib()
+    if online is not None:
+        z, lo, hi, sigma0 = online
+        steps = ob.online_steps(tr.N, 128, 32)
+
+        def one_online(p):
+            return ob.replay_online(tr, R=wl.R, batch=wl.batch, cache_blocks=wl.cache_blocks,
+                                    prefill_ms_per_token=wl.prefill_ms_per_token,
+                                    decode_ms_per_token=wl.decode_ms_per_token, rtt_ms=wl.rtt_ms, theta0=params[p],
+                                    z=z[p, :steps], lo=lo, hi=hi, sigma0=sigma0).p95_ttft_ms
+        t0 = time.perf_counter()
+        with ThreadPoolExecutor(threads) as ex:
+            list(ex.map(one_online, range(threads)))
+        dt = time.perf_counter() - t0
+        return threads * tr.N / dt, dt, tr.N
 
     def one(p):
         return ob.replay(tr, R=wl.R, batch=wl.batch, cache_blocks=wl.cache_blocks,
@@ -114,6 +129,9 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch one plain 1 GiB device copy before the timed region (reference for HBM counters)")
     ap.add_argument("--path", type=int, default=0, help="0 auto, 1 hashed block tables, 2 segment rows (experiments only)")
+    ap.add_argument("--online", action="store_true",
+                    help="instead of one ES generation per step: one pass of P online tuners (window 128, hop 32) "
+                         "over the trace per step -- the tuner as the paper runs it, not the headline metric")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build evaluates on ONE GPU (replays are independent and would shard by candidate; "
@@ -134,12 +152,23 @@ def main():
     N = tr.N
     model = g.Model(wl.R, wl.batch, wl.cache_blocks, wl.prefill_ms_per_token, wl.decode_ms_per_token)
     state = g.es_init(es_cfg["seed"])
-    ws = torch.empty((g.es_workspace_bytes(tr, model, P),), dtype=torch.uint8, device="cuda:0")
+    ws_bytes = g.workspace_bytes(tr, model, P) if args.online else g.es_workspace_bytes(tr, model, P)
+    ws = torch.empty((ws_bytes,), dtype=torch.uint8, device="cuda:0")
     print(f"[bench] workload {wl.name}: R={wl.R} N={N} P={P} C={wl.cache_blocks} mean blocks/request "
           f"{np.diff(wl.trace.blk_off).mean():.1f}; workspace {ws.numel() / 2**30:.1f} GiB; setup "
           f"{time.perf_counter() - t_setup:.1f}s", file=sys.stderr, flush=True)
 
+    if args.online:
+        steps_on = g.online_steps(N, 128, 32)
+        z_on = torch.from_numpy(g.es_sample(es_cfg["seed"], 0, P * steps_on).reshape(P, steps_on, 3)).to("cuda:0")
+        theta0 = np.tile(np.array(state.theta[:]), (P, 1))
+
     def generation():
+        if args.online:
+            res = g.eval_online(tr, model, wl.rtt_ms, theta0, z_on, 1.0, lo=state.lo[:], hi=state.hi[:], sigma0=state.sigma,
+                                per_request=False, trajectory=False, workspace=ws)
+            fit = res.p95_ttft_ms.cpu().numpy()
+            return res.theta_final.cpu().numpy(), fit, g.last_eval_kernel_ms()
         par, fit, _ = g.es_step(tr, model, wl.rtt_ms, 1.0, P, state, workspace=ws)
         return par, fit, g.last_eval_kernel_ms()
 
@@ -186,7 +215,7 @@ def main():
         bpr = algorithmic_bytes_per_routing(wl.R, n_mean, hit_mean, outputs_bytes=9)
         kernel = "replay_blocks_kernel"
     k_ms = float(np.mean(kernel_ms))
-    counters = recorded_counters(kernel, f"config-{args.config} N={N} P={P}")
+    counters = None if args.online else recorded_counters(kernel, f"config-{args.config} N={N} P={P}")
     traffic = counters["fetch_bytes_per_launch"] + counters["write_bytes_per_launch"] if counters else None
     achieved = bpr * P * N / (k_ms * 1e-3) / 1e9
     # The replay is one dependent chain per candidate: what limits it is the rate at which a SIMD issues the
@@ -202,12 +231,15 @@ def main():
                  "achieved_ginst_s": rate / 1e9, "peak_ginst_s": n_simd * clock_hz / 4 / 1e9,
                  "frac": rate / (n_simd * clock_hz / 4)}
 
+    mode = "P online tuners (window 128, hop 32) over the trace per step" if args.online else \
+        "one ES generation per step (eval + p95 TTFT fitness + mean update)"
     out = {
-        "metric": "candidate-request routings/sec at P=1024", "value": value, "unit": "routings/s",
+        "metric": "candidate-request routings/sec at P=1024" + (" (online tuner)" if args.online else ""),
+        "value": value, "unit": "routings/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f64", "data": "synthetic",
         "config": {"workload": f"config-{args.config} {wl.name}: R={wl.R} N={N} P={P} cache={wl.cache_blocks} blocks LRU, "
-                               f"one ES generation per step (eval + p95 TTFT fitness + mean update)",
+                               f"{mode}",
                    "es_generation_wall_s": wall / args.steps},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "kernel": kernel, "mean_segments": segs_mean,
@@ -217,7 +249,8 @@ def main():
     }
     if not args.no_cpu_baseline:
         cores = min(len(os.sched_getaffinity(0)), 16)
-        v, dt, n_s = cpu_baseline(wl, par, min(args.cpu_sample_requests, N), cores)
+        on = (z_on[:cores].cpu().numpy(), list(state.lo[:]), list(state.hi[:]), state.sigma) if args.online else None
+        v, dt, n_s = cpu_baseline(wl, theta0 if args.online else par, min(args.cpu_sample_requests, N), cores, on)
         out["cpu_baseline"] = {"value": v, "unit": "routings/s", "cores": cores, "kind": "oracle",
                                "sample": f"{cores} replays (one per thread) x first {n_s} requests of the same trace, "
                                          f"{dt:.1f}s wall"}
