@@ -25,7 +25,12 @@ def lib():
         L.gorgo_oracle_replay_ex.restype = C.c_int
         L.gorgo_oracle_replay_ex.argtypes = [C.c_int64] + [C.c_void_p] * 5 + \
             [C.c_int32, C.c_int32, C.c_int32, C.c_int64, C.c_double, C.c_double, C.c_void_p, C.c_void_p, C.c_double,
-             C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_double] + [C.c_void_p] * 11
+             C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_double, C.c_int32,
+             C.c_uint64] + [C.c_void_p] * 11
+        L.gorgo_oracle_philox4x32_10.restype = None
+        L.gorgo_oracle_philox4x32_10.argtypes = [C.c_void_p] * 3
+        L.gorgo_oracle_splitmix64_next.restype = C.c_uint64
+        L.gorgo_oracle_splitmix64_next.argtypes = [C.c_uint64]
         L.gorgo_oracle_tuner_exp.restype = C.c_double
         L.gorgo_oracle_tuner_exp.argtypes = [C.c_double]
         L.gorgo_oracle_online_steps.restype = C.c_int64
@@ -107,8 +112,22 @@ def online_steps(N: int, window: int, hop: int) -> int:
     return int(lib().gorgo_oracle_online_steps(N, window, hop))
 
 
+def philox4x32_10(ctr, key) -> np.ndarray:
+    c, k = np.ascontiguousarray(ctr, np.uint32), np.ascontiguousarray(key, np.uint32)
+    out = np.zeros(4, np.uint32)
+    lib().gorgo_oracle_philox4x32_10(_p(c), _p(k), _p(out))
+    return out
+
+
+def splitmix64_next(x: int) -> int:
+    return int(lib().gorgo_oracle_splitmix64_next(x & 0xFFFFFFFFFFFFFFFF))
+
+
+POLICIES = {"cost-model": 0, "least-request": 1, "session-affinity": 2, "random": 3}
+
+
 def _replay_ex(trace, R, batch, cache_blocks, prefill_ms_per_token, decode_ms_per_token, rtt_ms, w, scale,
-               block_tokens, window, hop, schedule, z, lo, hi, sigma0) -> Replay:
+               block_tokens, window, hop, schedule, z, lo, hi, sigma0, policy=0, seed=0) -> Replay:
     N = int(trace.ts_ms.shape[0])
     ts = np.ascontiguousarray(trace.ts_ms, dtype=np.int64)
     il = np.ascontiguousarray(trace.in_len, dtype=np.int32)
@@ -135,8 +154,8 @@ def _replay_ex(trace, R, batch, cache_blocks, prefill_ms_per_token, decode_ms_pe
     fin = np.zeros(6, np.float64)
     rc = lib().gorgo_oracle_replay_ex(N, _p(ts), _p(il), _p(ol), _p(bo), _p(hs), block_tokens, R, batch, cache_blocks,
                                       prefill_ms_per_token, decode_ms_per_token, _p(rtt), _p(wv), float(scale),
-                                      window, hop, _p(sched), _p(zz), _p(lov), _p(hiv), float(sigma0),
-                                      _p(route), _p(hit), _p(ttft), _p(e2e), _p(p), None, None, None,
+                                      window, hop, _p(sched), _p(zz), _p(lov), _p(hiv), float(sigma0), int(policy),
+                                      int(seed), _p(route), _p(hit), _p(ttft), _p(e2e), _p(p), None, None, None,
                                       _p(theta_step), _p(fitness_step), _p(fin))
     if rc != 0:
         raise RuntimeError(f"gorgo_oracle_replay_ex failed with code {rc}")
@@ -156,3 +175,10 @@ def replay_schedule(trace, *, R, batch, cache_blocks, prefill_ms_per_token, deco
     """One replay whose weights are w, then schedule[h] after requests window + h * hop (no tuner)."""
     return _replay_ex(trace, R, batch, cache_blocks, prefill_ms_per_token, decode_ms_per_token, rtt_ms, w, scale,
                       block_tokens, window, hop, schedule, None, None, None, 0.0)
+
+
+def replay_policy(trace, *, R, batch, cache_blocks, prefill_ms_per_token, decode_ms_per_token, rtt_ms, policy, seed=0,
+                  scale=1.0, block_tokens=512) -> Replay:
+    """One replay routed by a baseline policy ("least-request", "session-affinity", "random")."""
+    return _replay_ex(trace, R, batch, cache_blocks, prefill_ms_per_token, decode_ms_per_token, rtt_ms, [0.0, 0.0, 0.0],
+                      scale, block_tokens, 0, 0, None, None, None, None, 0.0, POLICIES[policy], seed)

@@ -79,15 +79,50 @@ double tuner_exp(double x) {
 
 double clip(double x, double lo, double hi) { return std::min(std::max(x, lo), hi); }
 
+// Philox-4x32 with 10 rounds (Salmon, Moraes, Dror, Shaw, "Parallel random numbers: as easy as 1, 2, 3", SC'11),
+// written from the paper's definition: per round, two 32x32 -> 64 bit products of the counter words 0 and 2
+// with the constants M0 and M1; the new counter is (hi(M1 c2) ^ c1 ^ k0, lo(M1 c2), hi(M0 c0) ^ c3 ^ k1,
+// lo(M0 c0)); the key words advance by the Weyl constants between rounds.
+void philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]) {
+    const uint64_t M0 = 0xD2511F53u, M1 = 0xCD9E8D57u;
+    uint32_t c[4] = {ctr[0], ctr[1], ctr[2], ctr[3]};
+    uint32_t k[2] = {key[0], key[1]};
+    for (int round = 0; round < 10; ++round) {
+        const uint64_t a = M0 * c[0], b = M1 * c[2];
+        const uint32_t n[4] = {(uint32_t)(b >> 32) ^ c[1] ^ k[0], (uint32_t)b, (uint32_t)(a >> 32) ^ c[3] ^ k[1],
+                               (uint32_t)a};
+        for (int j = 0; j < 4; ++j) c[j] = n[j];
+        k[0] += 0x9E3779B9u;
+        k[1] += 0xBB67AE85u;
+    }
+    for (int j = 0; j < 4; ++j) out[j] = c[j];
+}
+
+// SplitMix64 output function (Steele, Lea, Flood, "Fast splittable pseudorandom number generators", OOPSLA'14,
+// in the form of Vigna's splitmix64.c): next value of a generator whose state is x.
+uint64_t splitmix64_next(uint64_t x) {
+    uint64_t z = x + 0x9E3779B97F4A7C15ull;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+
+// A 32-bit value spread over R replicas: floor(h * R / 2^32).
+int spread(uint32_t h, int R) { return (int)(((uint64_t)h * (uint64_t)R) >> 32); }
+
 }  // namespace
 
 extern "C" {
 
-// Exposed so that tests can pin the tuner's exp against the C library's.
+// Exposed so that tests can pin the tuner's exp against the C library's, and the two generators against their
+// published answers.
 double gorgo_oracle_tuner_exp(double x) { return tuner_exp(x); }
+void gorgo_oracle_philox4x32_10(const uint32_t* ctr, const uint32_t* key, uint32_t* out) { philox4x32_10(ctr, key, out); }
+uint64_t gorgo_oracle_splitmix64_next(uint64_t x) { return splitmix64_next(x); }
 
 // Tuner steps a replay of N requests takes: one when the first window is full, then one every hop.
 int64_t gorgo_oracle_online_steps(int64_t N, int32_t window, int32_t hop) {
+    if (window < 1 || hop < 1) return 0;      // no tuner
     return N >= window ? (N - window) / hop + 1 : 0;
 }
 
@@ -115,18 +150,29 @@ double gorgo_oracle_p95(const double* x, int64_t n) {
 //     sigma0 = initial step size; tuner outputs, each may be null: theta_step[steps][3] = weights in use after
 //     each step, fitness_step[steps] = window p95 TTFT seen at each step, tuner_final[6] = parent weights (3),
 //     step size, steps taken, offspring accepted).
+//
+// Policy (Sec. 4 "Baseline policies"; the cost model is policy 0, and two of the paper's baselines are
+// special cases of it: prefix-cache = weights (0, 1, 0), proxy-only least-load = weights (0, 0, 1)):
+//   1 least-request: the replica with the fewest in-flight requests (requests without a completion event at
+//     the proxy), lowest index on ties;
+//   2 session affinity: the replica that a hash of the request's first block selects (the paper hashes the
+//     first 256 tokens; traces here carry one id per 512-token block): spread(high 32 bits of
+//     splitmix64_next(first id)); a request without blocks goes to replica 0;
+//   3 random: replica spread(first word of Philox-4x32-10(counter = (r mod 2^32, r div 2^32, 0, 0), key =
+//     (seed mod 2^32, seed div 2^32))).
 int gorgo_oracle_replay_ex(int64_t N, const int64_t* ts_ms, const int32_t* in_len, const int32_t* out_len,
                            const int64_t* blk_off, const int64_t* hash_ids, int32_t block_tokens,
                            int32_t R, int32_t B, int64_t C, double a_pf, double a_dec,
                            const double* rtt_ms, const double* w, double scale,
                            int32_t window, int32_t hop, const double* schedule, const double* z,
-                           const double* lo, const double* hi, double sigma0,
+                           const double* lo, const double* hi, double sigma0, int32_t policy, uint64_t seed,
                            uint8_t* route, uint16_t* hit_blocks, double* ttft_ms, double* e2e_ms, double* p95,
                            double* score_dbg, int64_t* q_dbg, int64_t* size_dbg,
                            double* theta_step, double* fitness_step, double* tuner_final) {
     if (N < 0 || R < 1 || R > 255 || B < 1 || C < 0 || block_tokens < 1) return -1;
     if (N > 0 && (!ts_ms || !in_len || !out_len || !blk_off)) return -1;
     if (window < 0 || (window > 0 && hop < 1)) return -1;
+    if (policy < 0 || policy > 3 || (policy != 0 && window > 0)) return -1;
     if (window > 0 && !schedule && (!z || !lo || !hi)) return -1;
     double w_rtt = w[0], w_prefill = w[1], w_queue = w[2];
 
@@ -199,6 +245,20 @@ int gorgo_oracle_replay_ex(int64_t N, const int64_t* ts_ms, const int32_t* in_le
         int best = 0;
         for (int i = 1; i < R; ++i)
             if (score[i] < score[best]) best = i;
+        // baseline policies route by their own rule instead (Sec. 4)
+        if (policy == 1) {
+            best = 0;
+            for (int i = 1; i < R; ++i)
+                if (rep[i].inflight.size() < rep[best].inflight.size()) best = i;
+        } else if (policy == 2) {
+            best = n > 0 ? spread((uint32_t)(splitmix64_next((uint64_t)ids[0]) >> 32), R) : 0;
+        } else if (policy == 3) {
+            const uint32_t ctr[4] = {(uint32_t)r, (uint32_t)((uint64_t)r >> 32), 0u, 0u};
+            const uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
+            uint32_t x[4];
+            philox4x32_10(ctr, key, x);
+            best = spread(x[0], R);
+        }
         Replica& X = rep[best];
 
         // cache update on the chosen replica: every block of the request becomes (or stays) cached with a
@@ -328,7 +388,7 @@ int gorgo_oracle_replay(int64_t N, const int64_t* ts_ms, const int32_t* in_len, 
                         uint8_t* route, uint16_t* hit_blocks, double* ttft_ms, double* e2e_ms, double* p95,
                         double* score_dbg, int64_t* q_dbg, int64_t* size_dbg) {
     return gorgo_oracle_replay_ex(N, ts_ms, in_len, out_len, blk_off, hash_ids, block_tokens, R, B, C, a_pf, a_dec,
-                                  rtt_ms, w, scale, 0, 0, nullptr, nullptr, nullptr, nullptr, 0.0, route,
+                                  rtt_ms, w, scale, 0, 0, nullptr, nullptr, nullptr, nullptr, 0.0, 0, 0, route,
                                   hit_blocks, ttft_ms, e2e_ms, p95, score_dbg, q_dbg, size_dbg, nullptr, nullptr,
                                   nullptr);
 }

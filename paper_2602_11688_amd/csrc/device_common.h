@@ -80,7 +80,7 @@ __device__ __forceinline__ int wave_argmin(double v, int lane, int count) {
 }
 
 // Queue side of one replay.  Lane i owns replica i: its load signal q (Eq. 2: tokens of requests without a
-// completion event at the proxy), its earliest pending completion and its earliest-free service slot live
+// completion event at the proxy), its earliest pending completion and the set of its idle service slots live
 // in that lane's registers, the B service slots themselves in LDS (slot b of replica i at index
 // i * Bp + b, Bp = B rounded up to 8).  The in-flight requests of a slot form a FIFO (completion times
 // increase along a slot); the two oldest are in LDS, deeper ones are Rec records in global memory linked in

@@ -1,4 +1,5 @@
-// Device side: replay kernel (one wavefront per replay), table fill, exact percentile selection.
+// Device side: the block-table replay kernel (one wavefront per replay), table fill, exact percentile
+// selection, and the launches (the segment-row replay kernel is in replay_segments.h).
 //
 // The replay kernel follows the request loop of the routing policy (Sec. 2.2-2.3): retire completed
 // requests from the load signal (Eq. 2), longest-prefix match of the request's blocks against every

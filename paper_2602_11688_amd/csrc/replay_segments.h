@@ -91,7 +91,7 @@ constexpr int SEG_SPIN_LIMIT = 1 << 24;      // polls of a hand-over word before
 struct SegComm {
     double q[WAVE];                   // load signal per replica, valid when seq_q == r + 1
     unsigned seq_q;
-    int abandoned;                    // a wavefront gave up waiting: both leave, latencies are poisoned
+    int abandoned;                    // a wavefront gave up waiting: both leave, latencies become NaN
     unsigned long long choice;        // uncached tokens | (((r + 1) mod 2^26) << 6 | replica) << 32
     double w[3];                      // online tuner: weights in use, valid with seq_q like q
 };

@@ -53,7 +53,7 @@ class ForcedRouteModel:
         free = [[0.0] * self.B for _ in range(self.R)]
         inflight = [[] for _ in range(self.R)]       # (done, tokens)
         consistent = True
-        out = dict(score=[], hit=[], ttft=[], e2e=[], q=[], done=[])
+        out = dict(score=[], hit=[], ttft=[], e2e=[], q=[], done=[], cnt=[])
         for r in range(tr.N):
             ids = [int(x) for x in tr.ids_of(r)]
             L, O = int(tr.in_len[r]), int(tr.out_len[r])
@@ -112,6 +112,7 @@ class ForcedRouteModel:
             out["ttft"].append((f + half) - t)
             out["e2e"].append(done - t)
             out["q"].append(q)
+            out["cnt"].append([len(inflight[j]) - (1 if j == i else 0) for j in range(self.R)])   # before dispatch
             out["done"].append(done)
         out["consistent"] = consistent
         return out
