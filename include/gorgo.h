@@ -207,6 +207,35 @@ int gorgo_eval_online(const gorgo_trace* t, const gorgo_model* m, const double* 
                       const double* scale, int32_t P, const gorgo_online* online, const gorgo_outputs* outputs,
                       void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* -------------------------------------------------------------------------------- baseline policies
+ * The routing policies that the paper compares the cost model with (Sec. 4 "Baseline policies"), replayed on
+ * the same trace with the same replica model.  Two of them are the cost model itself with special weights and
+ * need no entry point of their own: prefix-cache (highest prefix overlap) is gorgo_eval_population with
+ * weights (0, 1, 0), and least-load restricted to what the proxy itself tracks (tokens of requests without a
+ * completion event) is weights (0, 0, 1).  The others:
+ *   GORGO_POLICY_LEAST_REQUEST     fewest in-flight requests (no completion event at the proxy yet), lowest
+ *                                  replica index on ties
+ *   GORGO_POLICY_SESSION_AFFINITY  the replica selected by a hash of the request's first block (the paper hashes
+ *                                  the first 256 tokens; a trace carries one id per block): replica =
+ *                                  floor(h * R / 2^32) with h the high 32 bits of the value that a SplitMix64
+ *                                  generator in state `id` returns next; a request without blocks goes to replica 0
+ *   GORGO_POLICY_RANDOM            replica = floor(x * R / 2^32) with x the first output word of Philox-4x32-10
+ *                                  for counter (request index, 0, 0) and key seeds[p]
+ * Needs a chain-consistent trace (the dense segment-row formulation). */
+typedef enum gorgo_policy {
+    GORGO_POLICY_COST_MODEL = 0,   /* accepted by gorgo_eval_policy only with weights, i.e. not at all: use gorgo_eval_population */
+    GORGO_POLICY_LEAST_REQUEST = 1,
+    GORGO_POLICY_SESSION_AFFINITY = 2,
+    GORGO_POLICY_RANDOM = 3
+} gorgo_policy;
+
+/* Evaluate P replays routed by `policy`, replay p at time scale scale[p] (and, for the random policy, with
+ * seed seeds[p]; seeds is a host array [P], may be NULL for the other policies).  Everything else as
+ * gorgo_eval_population, same workspace size. */
+int gorgo_eval_policy(const gorgo_trace* t, const gorgo_model* m, const double* rtt_ms, int32_t policy,
+                      const uint64_t* seeds, const double* scale, int32_t P, const gorgo_outputs* outputs,
+                      void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* ------------------------------------------------------------------------------------------------ misc
  * Device time (ms, HIP events recorded on the evaluation's stream) of the three stages of the most recent
  * gorgo_eval_population / gorgo_es_step issued by the calling thread: state initialisation, the replay

@@ -69,6 +69,7 @@ def lib():
         L.gorgo_online_steps.restype = i64
         L.gorgo_eval_online.argtypes = [vp, C.POINTER(_Model), vp, vp, vp, i32, C.POINTER(_Online), C.POINTER(_Outputs),
                                         vp, C.c_size_t, vp]
+        L.gorgo_eval_policy.argtypes = [vp, C.POINTER(_Model), vp, i32, vp, vp, i32, C.POINTER(_Outputs), vp, C.c_size_t, vp]
         L.gorgo_es_init.argtypes = [C.POINTER(EsState), C.c_uint64]
         L.gorgo_es_sample.argtypes = [C.c_uint64, i64, i32, vp]
         L.gorgo_philox4x32_10.argtypes = [vp, vp, vp]
@@ -82,7 +83,7 @@ def lib():
         L.gorgo_query_replay_path.argtypes = [vp, C.POINTER(i32), C.POINTER(i64), C.POINTER(i64)]
         L.gorgo_last_eval_kernel_ms.argtypes = [C.POINTER(dbl)] * 3
         for name in ("gorgo_load_trace", "gorgo_load_trace_arrays", "gorgo_trace_info", "gorgo_workspace_bytes",
-                     "gorgo_eval_population", "gorgo_eval_online", "gorgo_es_init", "gorgo_es_sample", "gorgo_es_propose",
+                     "gorgo_eval_population", "gorgo_eval_online", "gorgo_eval_policy", "gorgo_es_init", "gorgo_es_sample", "gorgo_es_propose",
                      "gorgo_es_update", "gorgo_es_workspace_bytes", "gorgo_es_step", "gorgo_set_table_factor_percent",
                      "gorgo_last_eval_kernel_ms", "gorgo_set_replay_path", "gorgo_query_replay_path"):
             getattr(L, name).restype = C.c_int
@@ -251,6 +252,45 @@ def eval_population(trace: Trace, model: Model, rtt_ms, params, scale, *, per_re
         _check(lib().gorgo_eval_population(trace._h, C.byref(m), _ptr(rtt), _ptr(par), _ptr(sc), P, C.byref(o),
                                            C.c_void_p(workspace.data_ptr()), workspace.numel(),
                                            C.c_void_p(s.cuda_stream)))
+    return res
+
+
+POLICIES = {"least-request": 1, "session-affinity": 2, "random": 3}
+
+
+def eval_policy(trace: Trace, model: Model, rtt_ms, policy: str, scale, *, seeds=None, per_request: bool = True,
+                p95: bool = True, workspace=None, stream=None, device="cuda:0") -> EvalResult:
+    """gorgo_eval_policy with torch-allocated outputs: one replay per entry of `scale`, routed by a baseline policy
+    ("least-request", "session-affinity", "random"; prefix-cache and least-load are eval_population with weights
+    (0,1,0) and (0,0,1)).  seeds [P] for the random policy."""
+    import torch
+    rtt = _np(rtt_ms, np.float64)
+    sc = _np(np.atleast_1d(np.asarray(scale, dtype=np.float64)), np.float64)
+    P = sc.shape[0]
+    sd = None if seeds is None else _np(seeds, np.uint64)
+    if rtt.shape != (model.R,) or (sd is not None and sd.shape != (P,)):
+        raise ValueError("rtt_ms must be [R] and seeds [P]")
+    N = trace.N
+    dev = torch.device(device)
+    res = EvalResult()
+    if per_request:
+        res.route = torch.empty((P, N), dtype=torch.uint8, device=dev)
+        res.hit_blocks = torch.empty((P, N), dtype=torch.uint16, device=dev)
+        res.ttft_ms = torch.empty((P, N), dtype=torch.float64, device=dev)
+        res.e2e_ms = torch.empty((P, N), dtype=torch.float64, device=dev)
+    if p95:
+        res.p95_ttft_ms = torch.empty((P,), dtype=torch.float64, device=dev)
+        res.p95_e2e_ms = torch.empty((P,), dtype=torch.float64, device=dev)
+    o = _outputs_struct(res.route, res.hit_blocks, res.ttft_ms, res.e2e_ms, res.p95_ttft_ms, res.p95_e2e_ms)
+    need = workspace_bytes(trace, model, P, o)
+    if workspace is None or workspace.numel() < need:
+        workspace = torch.empty((need,), dtype=torch.uint8, device=dev)
+    res.workspace = workspace
+    s = stream if stream is not None else torch.cuda.current_stream(dev)
+    m = model.c()
+    with torch.cuda.device(dev):
+        _check(lib().gorgo_eval_policy(trace._h, C.byref(m), _ptr(rtt), POLICIES[policy], _ptr(sd), _ptr(sc), P, C.byref(o),
+                                       C.c_void_p(workspace.data_ptr()), workspace.numel(), C.c_void_p(s.cuda_stream)))
     return res
 
 

@@ -92,7 +92,8 @@ int make_plan(const gorgo_trace* t, const gorgo_model* m, int32_t P, const gorgo
     pl->off_e2e = off;
     if (!o || (!o->e2e_ms && want_p95_e)) off += up256((size_t)P * N * 8);
     pl->off_small = off;
-    off += up256(((size_t)pl->R + 7 * (size_t)P + TUNER_CONSTS) * 8);     // rtt, params, scale; tuner constants, ln theta0
+    // rtt, params, scale; tuner constants, ln theta0; seeds of the random policy
+    off += up256(((size_t)pl->R + 8 * (size_t)P + TUNER_CONSTS) * 8);
     pl->total = off;
     return GORGO_OK;
 }
@@ -150,8 +151,8 @@ namespace {
 
 // Validation, small copies and launches common to the fixed-weight and the online evaluation.
 int evaluate(const gorgo_trace* t, const gorgo_model* m, const double* rtt_ms, const double* params,
-             const double* scale, int32_t P, const gorgo_online* online, const gorgo_outputs* outputs, void* workspace,
-             size_t workspace_bytes, void* hip_stream) {
+             const double* scale, int32_t P, const gorgo_online* online, int32_t policy, const uint64_t* seeds,
+             const gorgo_outputs* outputs, void* workspace, size_t workspace_bytes, void* hip_stream) {
     int rc = check_model(t, m);
     if (rc) return rc;
     if (!rtt_ms || !params || !scale || !outputs) return fail(GORGO_ERR_INVALID_ARG, "a required pointer is NULL");
@@ -168,6 +169,8 @@ int evaluate(const gorgo_trace* t, const gorgo_model* m, const double* rtt_ms, c
     for (int32_t p = 0; p < P; ++p)
         if (!std::isfinite(scale[p]) || scale[p] < 0 || scale[p] > 1e6)
             return fail(GORGO_ERR_NONFINITE, "scale[" + std::to_string(p) + "] must be finite and in 0..1e6");
+    if (policy != 0 && pl.path != PATH_SEGMENTS)
+        return fail(GORGO_ERR_INVALID_ARG, "the baseline policies need a chain-consistent trace (segment formulation)");
     std::vector<double> tuner;      // constants, then ln theta0[P][3]
     int64_t steps = 0;
     if (online) {
@@ -212,6 +215,15 @@ int evaluate(const gorgo_trace* t, const gorgo_model* m, const double* rtt_ms, c
     double* d_params = d_rtt + pl.R;
     double* d_scale = d_params + 3 * (size_t)P;
     double* d_tuner = d_scale + P;
+    uint64_t* d_seeds = reinterpret_cast<uint64_t*>(d_tuner + TUNER_CONSTS + 3 * (size_t)P);
+    PolicyLaunch pol;
+    pol.policy = policy;
+    if (policy == GORGO_POLICY_RANDOM) {
+        if ((rc = copy_small_to_device(d_seeds, seeds, sizeof(uint64_t) * (size_t)P, hip_stream))) return rc;
+        pol.seeds = d_seeds;
+    }
+    // (the caller's stand-in weights may go away when this returns: the copies must have been taken by then)
+    if (policy != 0 && (rc = wait_for_copies(hip_stream))) return rc;
     if ((rc = copy_small_to_device(d_rtt, rtt_ms, sizeof(double) * pl.R, hip_stream))) return rc;
     if ((rc = copy_small_to_device(d_params, params, sizeof(double) * 3 * (size_t)P, hip_stream))) return rc;
     if ((rc = copy_small_to_device(d_scale, scale, sizeof(double) * (size_t)P, hip_stream))) return rc;
@@ -240,7 +252,7 @@ int evaluate(const gorgo_trace* t, const gorgo_model* m, const double* rtt_ms, c
     double* e2e = outputs->e2e_ms;
     if (!e2e && outputs->p95_e2e_ms) e2e = reinterpret_cast<double*>(ws + pl.off_e2e);
     rc = launch_replay(t, pl, d_rtt, d_params, d_scale, route, outputs->hit_blocks, ttft, e2e, workspace, hip_stream,
-                       online ? &ol : nullptr);
+                       online ? &ol : nullptr, policy != 0 ? &pol : nullptr);
     if (rc) return rc;
     if (outputs->p95_ttft_ms && (rc = launch_p95(ttft, pl.N, P, outputs->p95_ttft_ms, hip_stream))) return rc;
     if (outputs->p95_e2e_ms && (rc = launch_p95(e2e, pl.N, P, outputs->p95_e2e_ms, hip_stream))) return rc;
@@ -255,7 +267,7 @@ int gorgo_eval_population(const gorgo_trace* t, const gorgo_model* m, const doub
                           const double* scale, int32_t P, const gorgo_outputs* outputs, void* workspace,
                           size_t workspace_bytes, void* hip_stream) {
     clear_error();
-    return evaluate(t, m, rtt_ms, params, scale, P, nullptr, outputs, workspace, workspace_bytes, hip_stream);
+    return evaluate(t, m, rtt_ms, params, scale, P, nullptr, 0, nullptr, outputs, workspace, workspace_bytes, hip_stream);
 }
 
 int64_t gorgo_online_steps(int64_t N, int32_t window, int32_t hop) {
@@ -268,7 +280,22 @@ int gorgo_eval_online(const gorgo_trace* t, const gorgo_model* m, const double* 
                       void* workspace, size_t workspace_bytes, void* hip_stream) {
     clear_error();
     if (!online) return fail(GORGO_ERR_INVALID_ARG, "online is NULL");
-    return evaluate(t, m, rtt_ms, theta0, scale, P, online, outputs, workspace, workspace_bytes, hip_stream);
+    return evaluate(t, m, rtt_ms, theta0, scale, P, online, 0, nullptr, outputs, workspace, workspace_bytes, hip_stream);
+}
+
+int gorgo_eval_policy(const gorgo_trace* t, const gorgo_model* m, const double* rtt_ms, int32_t policy,
+                      const uint64_t* seeds, const double* scale, int32_t P, const gorgo_outputs* outputs,
+                      void* workspace, size_t workspace_bytes, void* hip_stream) {
+    clear_error();
+    if (policy != GORGO_POLICY_LEAST_REQUEST && policy != GORGO_POLICY_SESSION_AFFINITY && policy != GORGO_POLICY_RANDOM)
+        return fail(GORGO_ERR_INVALID_ARG, "policy must be least-request (1), session-affinity (2) or random (3); "
+                                           "prefix-cache and least-load are gorgo_eval_population with weights "
+                                           "(0,1,0) and (0,0,1)");
+    if (policy == GORGO_POLICY_RANDOM && !seeds) return fail(GORGO_ERR_INVALID_ARG, "seeds is NULL");
+    if (P < 1 || P > (1 << 20)) return fail(GORGO_ERR_INVALID_ARG, "P must be in 1..2^20");
+    const std::vector<double> zero(3 * (size_t)P, 0.0);       // the weights play no part
+    return evaluate(t, m, rtt_ms, zero.data(), scale, P, nullptr, policy, seeds, outputs, workspace, workspace_bytes,
+                    hip_stream);
 }
 
 int gorgo_last_eval_kernel_ms(double* fill_ms, double* replay_ms, double* select_ms) {

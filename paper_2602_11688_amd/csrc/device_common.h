@@ -100,6 +100,7 @@ struct Queues {
     int my_min_k;        // ... and its slot
     unsigned long long idle;   // slots of this lane's replica with nothing in flight (bit b = slot b)
     double my_q;         // outstanding tokens of replica = lane (an integer below 2^53, exact in fp64)
+    double my_cnt;       // requests in flight on replica = lane
 
     static __host__ __device__ size_t bytes(int R, int B) {
         return (size_t)R * ((B + 7) & ~7) * (8 * 3 + 4 * 5);
@@ -132,6 +133,7 @@ struct Queues {
         my_min_k = 0;
         idle = B >= 64 ? ~0ull : (1ull << B) - 1;
         my_q = 0.0;
+        my_cnt = 0.0;
     }
 
     // Drop requests whose completion event has reached the proxy (done <= t).
@@ -140,6 +142,7 @@ struct Queues {
             if (my_min <= t) {
                 const int s = base + my_min_k;
                 my_q -= (double)h_tok[s];
+                my_cnt -= 1.0;
                 const int d = depth[s];
                 if (d > 1) {
                     h_done[s] = s_done[s];
@@ -243,6 +246,7 @@ struct Queues {
             }
             tail[s] = (int32_t)r;
             my_q += (double)L;
+            my_cnt += 1.0;
         }
         *ttft_out = readlane_f64(ttft, best);
         *e2e_out = readlane_f64(e2e, best);

@@ -32,6 +32,7 @@ struct DeviceTrace {
     const uint8_t* first = nullptr;     // [total] 1 = first occurrence of its key inside the request
     const int64_t* seg_off = nullptr;   // [N+1] (chain-consistent traces only)
     const SegRef* seg = nullptr;        // [seg_off[N]]
+    const uint32_t* first_hash = nullptr;   // [N] hash of the request's first block (session-affinity policy)
 };
 
 }  // namespace gorgo
@@ -45,6 +46,7 @@ struct gorgo_trace {
     std::vector<int64_t> blk_off;
     std::vector<uint32_t> key;       // dense remap of hash ids: 1 + order of first appearance in the file
     std::vector<uint8_t> first;
+    std::vector<uint32_t> first_hash;   // per request: high word of SplitMix64's output for its first block id
     int64_t total_blocks = 0;
     int32_t max_blocks = 0;          // largest n_r
     int32_t max_distinct = 0;        // largest number of distinct ids in one request
@@ -89,10 +91,17 @@ struct OnlineLaunch {
 };
 constexpr int TUNER_CONSTS = 16;         // doubles reserved for OnlineLaunch::tuner
 
+// How a replay picks replicas (gorgo_policy in gorgo.h) and, for the random policy, the seeds of the replays.
+struct PolicyLaunch {
+    int32_t policy = 0;
+    const uint64_t* seeds = nullptr;     // device [P]
+};
+
 // kernels.hip
 int launch_replay(const gorgo_trace* t, const Plan& pl, const double* d_rtt, const double* d_params,
                   const double* d_scale, uint8_t* route, uint16_t* hit, double* ttft, double* e2e,
-                  void* workspace, void* stream, const OnlineLaunch* online = nullptr);
+                  void* workspace, void* stream, const OnlineLaunch* online = nullptr,
+                  const PolicyLaunch* policy = nullptr);
 int launch_p95(const double* x, int64_t N, int32_t P, double* out, void* stream);
 int last_eval_kernel_ms(double* fill_ms, double* replay_ms, double* select_ms);
 int upload_trace(const gorgo_trace* t);

@@ -433,7 +433,8 @@ int upload_trace(const gorgo_trace* tc) {
     const size_t n_sr = t->seg.size();
     const size_t o_soff = o_first + up(T);
     const size_t o_seg = o_soff + up(t->seg_off.size() * 8);
-    const size_t total = o_seg + up(n_sr * sizeof(SegRef)) + 256;
+    const size_t o_fh = o_seg + up(n_sr * sizeof(SegRef));
+    const size_t total = o_fh + up(N * 4) + 256;
     char* base = nullptr;
     e = hipMalloc(reinterpret_cast<void**>(&base), total);
     if (e != hipSuccess) return fail(GORGO_ERR_OOM, std::string("hipMalloc(trace): ") + hipGetErrorString(e));
@@ -444,7 +445,8 @@ int upload_trace(const gorgo_trace* tc) {
         (e = put(o_il, t->in_len.data(), N * 4)) != hipSuccess || (e = put(o_ol, t->out_len.data(), N * 4)) != hipSuccess ||
         (e = put(o_key, t->key.data(), T * 4)) != hipSuccess || (e = put(o_first, t->first.data(), T)) != hipSuccess ||
         (e = put(o_soff, t->seg_off.data(), t->seg_off.size() * 8)) != hipSuccess ||
-        (e = put(o_seg, t->seg.data(), n_sr * sizeof(SegRef))) != hipSuccess) {
+        (e = put(o_seg, t->seg.data(), n_sr * sizeof(SegRef))) != hipSuccess ||
+        (e = put(o_fh, t->first_hash.data(), N * 4)) != hipSuccess) {
         (void)hipFree(base);
         return hip_fail(e, "hipMemcpy(trace)");
     }
@@ -458,6 +460,7 @@ int upload_trace(const gorgo_trace* tc) {
     t->dev.first = reinterpret_cast<const uint8_t*>(base + o_first);
     t->dev.seg_off = reinterpret_cast<const int64_t*>(base + o_soff);
     t->dev.seg = reinterpret_cast<const SegRef*>(base + o_seg);
+    t->dev.first_hash = reinterpret_cast<const uint32_t*>(base + o_fh);
     return GORGO_OK;
 }
 
@@ -485,7 +488,7 @@ int copy_small_to_host_sync(void* dst, const void* src, size_t bytes, void* stre
 
 int launch_replay(const gorgo_trace* t, const Plan& pl, const double* d_rtt, const double* d_params,
                   const double* d_scale, uint8_t* route, uint16_t* hit, double* ttft, double* e2e,
-                  void* workspace, void* stream, const OnlineLaunch* online) {
+                  void* workspace, void* stream, const OnlineLaunch* online, const PolicyLaunch* policy) {
     hipStream_t s = static_cast<hipStream_t>(stream);
     char* ws = static_cast<char*>(workspace);
     g_marks.valid = false;
@@ -522,6 +525,8 @@ int launch_replay(const gorgo_trace* t, const Plan& pl, const double* d_rtt, con
         a.tuner = a.ln_theta0 = a.z = nullptr;
         a.theta_step = a.fitness_step = a.theta_final = a.sigma_final = nullptr;
         a.accepted = nullptr;
+        a.first_hash = t->dev.first_hash;
+        a.seeds = policy ? policy->seeds : nullptr;
         const size_t cells = (size_t)pl.P * (size_t)a.nseg * pl.R;
         if (cells) {
             size_t blocks = (cells + 255) / 256;
@@ -544,15 +549,22 @@ int launch_replay(const gorgo_trace* t, const Plan& pl, const double* d_rtt, con
                 a.sigma_final = online->sigma_final;
                 a.accepted = online->accepted;
                 const size_t lds = replay_segments_lds_bytes(pl.R, pl.B, online->window);
-                hipLaunchKernelGGL(replay_segments_kernel<true>, dim3((unsigned)pl.P), dim3(SEG_THREADS), lds, s, a);
+                hipLaunchKernelGGL(replay_segments_kernel<MODE_ONLINE>, dim3((unsigned)pl.P), dim3(SEG_THREADS), lds, s, a);
             } else {
                 const size_t lds = replay_segments_lds_bytes(pl.R, pl.B, 0);
-                hipLaunchKernelGGL(replay_segments_kernel<false>, dim3((unsigned)pl.P), dim3(SEG_THREADS), lds, s, a);
+                const dim3 grid((unsigned)pl.P), block(SEG_THREADS);
+                switch (policy ? policy->policy : 0) {
+                    case 0: hipLaunchKernelGGL(replay_segments_kernel<MODE_COST_MODEL>, grid, block, lds, s, a); break;
+                    case 1: hipLaunchKernelGGL(replay_segments_kernel<MODE_LEAST_REQUEST>, grid, block, lds, s, a); break;
+                    case 2: hipLaunchKernelGGL(replay_segments_kernel<MODE_AFFINITY>, grid, block, lds, s, a); break;
+                    default: hipLaunchKernelGGL(replay_segments_kernel<MODE_RANDOM>, grid, block, lds, s, a); break;
+                }
             }
             if ((e = hipGetLastError()) != hipSuccess) return hip_fail(e, "launch replay_segments_kernel");
         }
     } else {
-        if (online) return fail(GORGO_ERR_INVALID_ARG, "the online tuner needs the segment formulation");
+        if (online || (policy && policy->policy != 0))
+            return fail(GORGO_ERR_INVALID_ARG, "the online tuner and the baseline policies need the segment formulation");
         ReplayArgs a;
         a.ts = t->dev.ts;
         a.in_len = t->dev.in_len;

@@ -75,7 +75,37 @@ struct SegArgs {
     double* theta_final;       // [P][3], nullable
     double* sigma_final;       // [P], nullable
     int32_t* accepted;         // [P], nullable
+    // baseline policies
+    const uint32_t* first_hash;   // [N] hash of the request's first block
+    const uint64_t* seeds;        // [P] seed of the random policy
 };
+
+// What picks the replica: the cost model of Eq. 3 with fixed weights, the same with the online tuner, or one
+// of the baseline policies of Sec. 4 (prefix-cache and proxy-only least-load are the cost model with weights
+// (0, 1, 0) and (0, 0, 1)).
+enum SegMode { MODE_COST_MODEL = 0, MODE_ONLINE = 1, MODE_LEAST_REQUEST = 2, MODE_AFFINITY = 3, MODE_RANDOM = 4 };
+
+// A 32-bit value spread over R replicas: floor(h * R / 2^32).
+__device__ __forceinline__ int spread(uint32_t h, int R) { return (int)(((uint64_t)h * (uint64_t)R) >> 32); }
+
+// First word of Philox-4x32 with 10 rounds (Salmon, Moraes, Dror, Shaw, SC'11) for counter (c0, c1, 0, 0): per
+// round two 32x32 -> 64 bit products of counter words 0 and 2 with the generator's multipliers, xors with the
+// other two words and the key, and a Weyl step of the key.
+__device__ __forceinline__ uint32_t philox4x32_10_first(uint32_t c0, uint32_t c1, uint32_t k0, uint32_t k1) {
+    uint32_t c2 = 0, c3 = 0;
+#pragma unroll
+    for (int round = 0; round < 10; ++round) {
+        const uint64_t a = (uint64_t)0xD2511F53u * c0, b = (uint64_t)0xCD9E8D57u * c2;
+        const uint32_t n0 = (uint32_t)(b >> 32) ^ c1 ^ k0, n2 = (uint32_t)(a >> 32) ^ c3 ^ k1;
+        c1 = (uint32_t)b;
+        c3 = (uint32_t)a;
+        c0 = n0;
+        c2 = n2;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    return c0;
+}
 
 constexpr int SEG_STAGE = 512;   // segment references of a 64-request batch staged in LDS
 constexpr int SEG_CHUNK = 8;     // segments of a request whose rows are loaded together
@@ -200,8 +230,9 @@ __device__ __forceinline__ int cached_in(int32_t rl, int pos, int end, int c_r, 
 
 // Queue wavefront of a replay: for every request, retire what has completed by its arrival, publish the load
 // signals, wait for the cache wavefront's choice, serve the request there.  Writes the latencies.
-template <bool ONLINE>
+template <int MODE>
 __device__ __forceinline__ void queue_wave(const SegArgs& a, int p, int lane, unsigned char* lds_raw, SegComm* comm) {
+    constexpr bool ONLINE = MODE == MODE_ONLINE;
     const int R = a.R;
     const int64_t N = a.N;
     Queues Q;
@@ -244,7 +275,8 @@ __device__ __forceinline__ void queue_wave(const SegArgs& a, int p, int lane, un
             const int L = __builtin_amdgcn_readlane(m_L, i);
             const int O = __builtin_amdgcn_readlane(m_O, i);
             Q.retire(t, rec);
-            st(&comm->q[lane], Q.my_q);
+            // (the least-request policy asks for requests in flight instead of their tokens)
+            st(&comm->q[lane], MODE == MODE_LEAST_REQUEST ? Q.my_cnt : Q.my_q);
             lds_release();
             if (lane == 0) st(&comm->seq_q, (unsigned)(r + 1));
             const unsigned want = (unsigned)(r + 1) & 0x3FFFFFFu;
@@ -327,8 +359,9 @@ __device__ __forceinline__ void queue_wave(const SegArgs& a, int p, int lane, un
     }
 }
 
-template <bool ONLINE>
+template <int MODE>
 __global__ void __launch_bounds__(SEG_THREADS) replay_segments_kernel(SegArgs a) {
+    constexpr bool ONLINE = MODE == MODE_ONLINE;
     extern __shared__ __align__(16) unsigned char lds_raw[];
     __shared__ SegRef stage[SEG_STAGE + SEG_CHUNK];    // padded: whole chunks are read unconditionally
     __shared__ SegComm comm;
@@ -346,7 +379,7 @@ __global__ void __launch_bounds__(SEG_THREADS) replay_segments_kernel(SegArgs a)
     }
     __syncthreads();
     if (threadIdx.x >= WAVE) {
-        queue_wave<ONLINE>(a, p, lane, lds_raw, &comm);
+        queue_wave<MODE>(a, p, lane, lds_raw, &comm);
         return;
     }
     __builtin_amdgcn_s_setprio(3);      // the cache wavefront has the longer loop: it goes first at issue
@@ -355,6 +388,8 @@ __global__ void __launch_bounds__(SEG_THREADS) replay_segments_kernel(SegArgs a)
     for (int x = lane; x < SEG_CHUNK; x += WAVE) stage[SEG_STAGE + x] = SegRef{0, 0};
     wave_sync();
 
+    const uint64_t seed = MODE == MODE_RANDOM ? a.seeds[p] : 0;
+    const uint32_t seed_lo = (uint32_t)seed, seed_hi = (uint32_t)(seed >> 32);
     // (with the online tuner the weights come with the load signals instead)
     const double w_rtt = a.params[3 * (size_t)p + 0];
     const double w_prefill = a.params[3 * (size_t)p + 1];
@@ -427,6 +462,7 @@ __global__ void __launch_bounds__(SEG_THREADS) replay_segments_kernel(SegArgs a)
         const int nb0 = N - r0 < WAVE ? (int)(N - r0) : WAVE;
         const int64_t rr = r0 + (lane < nb0 ? lane : nb0 - 1);
         const int m_L = a.in_len[rr];
+        const uint32_t m_hash = MODE == MODE_AFFINITY ? a.first_hash[rr] : 0u;
         const int64_t my_j0 = a.seg_off[rr], my_j1 = a.seg_off[rr + 1];
         const int64_t J0 = a.seg_off[r0];
         const int fit = __popcll(__ballot(lane < nb0 && my_j1 - J0 <= SEG_STAGE));   // a prefix of the lanes
@@ -577,8 +613,20 @@ __global__ void __launch_bounds__(SEG_THREADS) replay_segments_kernel(SegArgs a)
                 st(&comm.abandoned, 1);
                 return;
             }
-            const double my_score = ONLINE ? eq3_score(now_rtt, now_prefill, now_queue, my_rtt, a.a_pf, my_u, my_q)
-                                           : eq3_with_queue(score_rp_ready, w_queue, a.a_pf, my_q);
+            double my_score;
+            if (MODE == MODE_COST_MODEL) {
+                my_score = eq3_with_queue(score_rp_ready, w_queue, a.a_pf, my_q);
+            } else if (MODE == MODE_ONLINE) {
+                my_score = eq3_score(now_rtt, now_prefill, now_queue, my_rtt, a.a_pf, my_u, my_q);
+            } else if (MODE == MODE_LEAST_REQUEST) {
+                my_score = my_q;                    // requests in flight
+            } else {
+                // the replica is dictated: by the hash of the first block, or by a counter-based draw
+                const int target = MODE == MODE_AFFINITY ? (s > 0 ? spread((uint32_t)__builtin_amdgcn_readlane((int)m_hash, i), R) : 0)
+                                                         : spread(philox4x32_10_first((uint32_t)r, (uint32_t)((uint64_t)r >> 32),
+                                                                                      seed_lo, seed_hi), R);
+                my_score = lane == target ? 0.0 : 1.0;
+            }
             const int best = wave_argmin(my_score, lane, R);
             const bool is_best = lane == best;
             const int m_best = __builtin_amdgcn_readlane(my_m, best);

@@ -185,6 +185,16 @@ int check_and_finish(gorgo_trace* t, const int64_t* hash_ids, int32_t block_toke
         if (total_tokens > ((int64_t)1 << 53)) return fail(GORGO_ERR_INVALID_ARG, "input tokens sum above 2^53");
     }
     t->block_tokens = block_tokens;
+    // session-affinity policy (Sec. 4 "Baseline policies"): hash of the request's first block, here the high word
+    // of the output that a SplitMix64 generator (Steele, Lea, Flood, OOPSLA'14) in state `id` gives next
+    t->first_hash.assign((size_t)N, 0u);
+    for (int64_t r = 0; r < N; ++r)
+        if (t->blk_off[r + 1] > t->blk_off[r]) {
+            uint64_t z = (uint64_t)hash_ids[t->blk_off[r]] + 0x9E3779B97F4A7C15ull;
+            z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+            z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+            t->first_hash[(size_t)r] = (uint32_t)((z ^ (z >> 31)) >> 32);
+        }
     return preprocess(t, hash_ids);
 }
 
