@@ -116,6 +116,36 @@ def cpu_baseline(wl, params, n_req, threads, online=None):
     return threads * tr.N / dt, dt, tr.N
 
 
+def compare_policies(g, torch, tr, model, wl, tuned, N):
+    """The paper's comparison of routing policies in synthetic form: one replay of the trace per policy, same replica
+    model, time scale 1.  TTFT / E2E in ms; block_hit = cached blocks / requested blocks."""
+    nb = torch.from_numpy(np.diff(wl.trace.blk_off).astype(np.float64)).to("cuda:0")
+
+    def stats(res, p):
+        t = res.ttft_ms[p]
+        return {"ttft_p50": t.median().item(), "ttft_p95": res.p95_ttft_ms[p].item(), "ttft_mean": t.mean().item(),
+                "e2e_p95": res.p95_e2e_ms[p].item(),
+                "block_hit": (res.hit_blocks[p].to(torch.float64).sum() / nb.sum()).item()}
+    table = {}
+    weights = {"cost model, initial weights (0.5, 1, 0.1)": [0.5, 1.0, 0.1], "cost model, tuner's best weights": tuned,
+               "prefix-cache = weights (0, 1, 0)": [0.0, 1.0, 0.0], "least-load (proxy tokens) = weights (0, 0, 1)": [0.0, 0.0, 1.0],
+               "nearest replica = weights (1, 0, 0)": [1.0, 0.0, 0.0]}
+    res = g.eval_population(tr, model, wl.rtt_ms, np.array(list(weights.values()), np.float64), 1.0)
+    torch.cuda.synchronize()
+    for i, k in enumerate(weights):
+        table[k] = stats(res, i)
+    del res
+    for pol in ("least-request", "session-affinity", "random"):
+        res = g.eval_policy(tr, model, wl.rtt_ms, pol, [1.0], seeds=np.array([7], np.uint64))
+        torch.cuda.synchronize()
+        table[pol] = stats(res, 0)
+        del res
+    for k, v in table.items():
+        print(f"[bench] {k:46s} ttft p50 {v['ttft_p50']:12.1f} p95 {v['ttft_p95']:12.1f} mean {v['ttft_mean']:12.1f} "
+              f"e2e p95 {v['e2e_p95']:12.1f} block hit {v['block_hit']:.3f}", file=sys.stderr, flush=True)
+    return table
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -129,6 +159,10 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch one plain 1 GiB device copy before the timed region (reference for HBM counters)")
     ap.add_argument("--path", type=int, default=0, help="0 auto, 1 hashed block tables, 2 segment rows (experiments only)")
+    ap.add_argument("--policies", action="store_true",
+                    help="also replay the trace once under each routing policy of the paper's comparison (cost model with "
+                         "the tuner's weights, its special cases, least-request, session affinity, random) and report "
+                         "their latencies under \"policies\" (untimed)")
     ap.add_argument("--online", action="store_true",
                     help="instead of one ES generation per step: one pass of P online tuners (window 128, hop 32) "
                          "over the trace per step -- the tuner as the paper runs it, not the headline metric")
@@ -247,6 +281,8 @@ def main():
                      "fill_ms": float(np.mean(fill_ms)), "select_ms": float(np.mean(select_ms)),
                      "issue": issue},
     }
+    if args.policies:
+        out["policies"] = compare_policies(g, torch, tr, model, wl, [float(x) for x in state.best_theta[:]], N)
     if not args.no_cpu_baseline:
         cores = min(len(os.sched_getaffinity(0)), 16)
         on = (z_on[:cores].cpu().numpy(), list(state.lo[:]), list(state.hi[:]), state.sigma) if args.online else None
