@@ -149,7 +149,7 @@ def compare_policies(g, torch, tr, model, wl, tuned, N):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--config", type=int, default=5, help="workload index (5 = Large, the one the metric is quoted on)")
     ap.add_argument("--requests", type=int, default=None, help="truncate the trace (experiments only)")
@@ -214,9 +214,12 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    warm_wall = []
     for i in range(args.warmup):
         t0 = time.perf_counter()
         generation()
+        torch.cuda.synchronize()
+        warm_wall.append(time.perf_counter() - t0)
         print(f"[bench] warmup generation {i}: {time.perf_counter() - t0:.2f}s", file=sys.stderr, flush=True)
     torch.cuda.synchronize()
     kernel_ms, fill_ms, select_ms = [], [], []
@@ -274,7 +277,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f64", "data": "synthetic",
         "config": {"workload": f"config-{args.config} {wl.name}: R={wl.R} N={N} P={P} cache={wl.cache_blocks} blocks LRU, "
                                f"{mode}",
-                   "es_generation_wall_s": wall / args.steps},
+                   "es_generation_wall_s": wall / args.steps, "warmup_generation_wall_s": warm_wall},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "kernel": kernel, "mean_segments": segs_mean,
                      "kernel_ms": k_ms, "bytes_per_routing": bpr, "mean_blocks": n_mean, "mean_hit_blocks": hit_mean,

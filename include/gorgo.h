@@ -249,6 +249,13 @@ int gorgo_last_eval_kernel_ms(double* fill_ms, double* replay_ms, double* select
  * 16 segments.  gorgo_workspace_bytes reflects the choice in force when it is called. */
 int gorgo_set_replay_path(int32_t mode);
 
+/* How many times a wavefront of the segment-row replay polls for its partner's word before the replay is given
+ * up (default 2^24, about a second; a replay that is given up ends at once, every latency of it becomes NaN, so
+ * does its p95, and gorgo_es_step fails with GORGO_ERR_NONFINITE).  It never happens unless the library is
+ * wrong; the setting exists so that this path can be exercised: with 0 every replay whose partner is not ready
+ * at the first poll is given up. */
+int gorgo_set_handover_poll_limit(int32_t polls);
+
 /* Formulation that an evaluation of this trace would use now (1 or 2, see gorgo_set_replay_path), the number
  * of segments of the trace and the total number of (request, segment) references; the last two are 0 for a
  * trace that is not chain-consistent.  Each out pointer may be NULL. */

@@ -80,12 +80,13 @@ def lib():
         L.gorgo_es_step.argtypes = [vp, C.POINTER(_Model), vp, dbl, i32, C.POINTER(EsState), vp, vp, vp, C.c_size_t, vp]
         L.gorgo_set_table_factor_percent.argtypes = [i32]
         L.gorgo_set_replay_path.argtypes = [i32]
+        L.gorgo_set_handover_poll_limit.argtypes = [i32]
         L.gorgo_query_replay_path.argtypes = [vp, C.POINTER(i32), C.POINTER(i64), C.POINTER(i64)]
         L.gorgo_last_eval_kernel_ms.argtypes = [C.POINTER(dbl)] * 3
         for name in ("gorgo_load_trace", "gorgo_load_trace_arrays", "gorgo_trace_info", "gorgo_workspace_bytes",
                      "gorgo_eval_population", "gorgo_eval_online", "gorgo_eval_policy", "gorgo_es_init", "gorgo_es_sample", "gorgo_es_propose",
                      "gorgo_es_update", "gorgo_es_workspace_bytes", "gorgo_es_step", "gorgo_set_table_factor_percent",
-                     "gorgo_last_eval_kernel_ms", "gorgo_set_replay_path", "gorgo_query_replay_path"):
+                     "gorgo_last_eval_kernel_ms", "gorgo_set_replay_path", "gorgo_set_handover_poll_limit", "gorgo_query_replay_path"):
             getattr(L, name).restype = C.c_int
         _lib = L
     return _lib
@@ -173,6 +174,11 @@ class Trace:
 
 def set_table_factor_percent(pct: int):
     _check(lib().gorgo_set_table_factor_percent(pct))
+
+
+def set_handover_poll_limit(polls: int):
+    """Polls of a hand-over word before a replay is given up (default 2^24); for tests of that path."""
+    _check(lib().gorgo_set_handover_poll_limit(polls))
 
 
 def set_replay_path(mode: int):

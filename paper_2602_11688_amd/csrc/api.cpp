@@ -112,6 +112,13 @@ int gorgo_set_table_factor_percent(int32_t factor_percent) {
     return GORGO_OK;
 }
 
+int gorgo_set_handover_poll_limit(int32_t polls) {
+    clear_error();
+    if (polls < 0) return fail(GORGO_ERR_INVALID_ARG, "polls must be >= 0");
+    set_handover_poll_limit(polls);
+    return GORGO_OK;
+}
+
 int gorgo_set_replay_path(int32_t mode) {
     clear_error();
     if (mode != PATH_AUTO && mode != PATH_BLOCKS && mode != PATH_SEGMENTS)

@@ -11,6 +11,7 @@
 //
 // Decision arithmetic is fp64 with every product and sum rounded separately (built with -ffp-contract=off)
 // in the association (w_rtt*rtt + w_prefill*pf) + w_queue*qd, so that routes are reproducible bit for bit.
+#include <atomic>
 #include <hip/hip_runtime.h>
 
 #include <cmath>
@@ -474,6 +475,9 @@ int copy_small_to_device(void* dst, const void* src, size_t bytes, void* stream)
     return e == hipSuccess ? GORGO_OK : hip_fail(e, "hipMemcpyAsync(H2D)");
 }
 
+std::atomic<int32_t> g_poll_limit{SEG_SPIN_LIMIT};
+void set_handover_poll_limit(int32_t polls) { g_poll_limit.store(polls); }
+
 int wait_for_copies(void* stream) {
     hipError_t e = hipStreamSynchronize(static_cast<hipStream_t>(stream));
     return e == hipSuccess ? GORGO_OK : hip_fail(e, "hipStreamSynchronize");
@@ -527,6 +531,7 @@ int launch_replay(const gorgo_trace* t, const Plan& pl, const double* d_rtt, con
         a.accepted = nullptr;
         a.first_hash = t->dev.first_hash;
         a.seeds = policy ? policy->seeds : nullptr;
+        a.spin_limit = g_poll_limit.load();
         const size_t cells = (size_t)pl.P * (size_t)a.nseg * pl.R;
         if (cells) {
             size_t blocks = (cells + 255) / 256;

@@ -78,6 +78,7 @@ struct SegArgs {
     // baseline policies
     const uint32_t* first_hash;   // [N] hash of the request's first block
     const uint64_t* seeds;        // [P] seed of the random policy
+    int32_t spin_limit;           // polls of a hand-over word before the replay is given up
 };
 
 // What picks the replica: the cost model of Eq. 3 with fixed weights, the same with the online tuner, or one
@@ -110,7 +111,7 @@ __device__ __forceinline__ uint32_t philox4x32_10_first(uint32_t c0, uint32_t c1
 constexpr int SEG_STAGE = 512;   // segment references of a 64-request batch staged in LDS
 constexpr int SEG_CHUNK = 8;     // segments of a request whose rows are loaded together
 constexpr int SEG_THREADS = 2 * WAVE;        // cache wavefront + queue wavefront
-constexpr int SEG_SPIN_LIMIT = 1 << 24;      // polls of a hand-over word before the replay is given up (~1 s)
+constexpr int SEG_SPIN_LIMIT = 1 << 24;      // default: polls of a hand-over word before the replay is given up (~1 s)
 
 // Hand-over words between the two wavefronts of a replay, in LDS.  Every word carries the number of the
 // request it belongs to (r + 1, so that the initial zero matches nothing).  They are read and written with
@@ -286,7 +287,7 @@ __device__ __forceinline__ void queue_wave(const SegArgs& a, int p, int lane, un
                 hi = __builtin_amdgcn_readfirstlane((unsigned)(w >> 32));
                 lo = __builtin_amdgcn_readfirstlane((unsigned)w);
                 if ((hi >> 6) == want) break;
-                if (spins > SEG_SPIN_LIMIT || ld(&comm->abandoned) != 0) {
+                if (spins > a.spin_limit || ld(&comm->abandoned) != 0) {
                     dead = true;
                     break;
                 }
@@ -604,7 +605,7 @@ __global__ void __launch_bounds__(SEG_THREADS) replay_segments_kernel(SegArgs a)
                     now_queue = ld(&comm.w[2]);
                 }
                 if (seq == (unsigned)(r + 1)) break;
-                if (spins > SEG_SPIN_LIMIT || ld(&comm.abandoned) != 0) {
+                if (spins > a.spin_limit || ld(&comm.abandoned) != 0) {
                     dead = true;
                     break;
                 }

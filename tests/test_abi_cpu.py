@@ -121,6 +121,41 @@ def test_eval_rejects_bad_arguments_before_touching_a_device():
     assert b"workspace" in L.gorgo_last_error()
 
 
+def test_online_and_policy_entry_points_reject_bad_arguments_before_touching_a_device():
+    t = _trace(tg.config(1, 300).trace)
+    m = g.Model(4, 8, 0, 0.05, 20.0).c()
+    L = g.lib()
+    rtt = np.array([10.0, 40.0, 120.0, 300.0])
+    th = np.tile([0.5, 1.0, 0.1], (2, 1))
+    sc = np.ones(2)
+    o = gb._Outputs()
+    assert L.gorgo_online_steps(672, 128, 32) == 18 and L.gorgo_online_steps(127, 128, 32) == 0
+    assert L.gorgo_online_steps(10, 0, 1) < 0 and L.gorgo_online_steps(10, 4, 0) < 0
+
+    def online(window=128, hop=32, lo=(0.05, 1.0, 0.05), hi=(2.0, 1.0, 0.5), sigma0=0.5, z=C.c_void_p(256), th=th):
+        on = gb._Online(window, hop, (C.c_double * 3)(*lo), (C.c_double * 3)(*hi), sigma0, z, None, None, None, None, None)
+        return L.gorgo_eval_online(t._h, C.byref(m), gb._ptr(rtt), gb._ptr(th), gb._ptr(sc), 2, C.byref(on), C.byref(o),
+                                   None, 1 << 40, None)
+    assert online(window=0) == -1 and online(window=2048) == -1 and online(hop=0) == -1
+    assert online(z=None) == -1
+    assert online(lo=(0.0, 1.0, 0.05)) == -6 and online(lo=(3.0, 1.0, 0.05)) == -6
+    assert online(sigma0=float("nan")) == -6
+    assert online(th=np.tile([5.0, 1.0, 0.1], (2, 1))) == -1          # theta0 outside [lo, hi]
+    assert online() == -7                                             # everything valid up to the workspace
+    assert L.gorgo_eval_online(t._h, C.byref(m), gb._ptr(rtt), gb._ptr(th), gb._ptr(sc), 2, None, C.byref(o), None, 0,
+                               None) == -1
+
+    def policy(pol, seeds=None):
+        return L.gorgo_eval_policy(t._h, C.byref(m), gb._ptr(rtt), pol, seeds, gb._ptr(sc), 2, C.byref(o), None,
+                                   1 << 40, None)
+    assert policy(0) == -1 and policy(4) == -1 and policy(3) == -1    # random without seeds
+    assert policy(1) == -7 and policy(3, gb._ptr(np.array([1, 2], np.uint64))) == -7
+    bad = _trace(tg.random_small(3, 50, 2, consistent=False))
+    mb = g.Model(2, 2, 0, 0.05, 20.0).c()
+    assert L.gorgo_eval_policy(bad._h, C.byref(mb), gb._ptr(rtt[:2]), 1, None, gb._ptr(sc), 2, C.byref(o), None, 1 << 40,
+                               None) == -1                            # needs a chain-consistent trace
+
+
 # ------------------------------------------------------------------------------------------------ tuner
 
 def test_philox_known_answers():
