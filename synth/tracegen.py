@@ -272,3 +272,34 @@ def random_small(seed: int, N: int, R: int, *, n_ids: int = 12, max_blocks: int 
     in_len = (nblk * block_tokens - rng.integers(0, block_tokens // 2, size=N) * (rng.random(N) < 0.3)).astype(np.int32)
     out_len = rng.integers(1, 6, size=N).astype(np.int32)
     return Trace(ts, in_len, out_len, blk_off, ids)
+
+
+def random_forest(seed: int, N: int, *, roots: int = 3, max_blocks: int = 40, grow: int = 6, gap_ms: int = 40,
+                  block_tokens: int = BLOCK_TOKENS) -> Trace:
+    """Random chain-consistent trace with branching: every request takes a prefix of an earlier request's blocks
+    (cut anywhere) and, more often than not, appends fresh blocks to it, so paths share prefixes, fork in the
+    middle of runs and end inside them.  Ids are fresh integers, so every id has one predecessor and position."""
+    rng = np.random.Generator(np.random.PCG64(np.random.SeedSequence([MASTER_SEED, 98, seed])))
+    ts = np.cumsum(rng.integers(0, gap_ms + 1, size=N)).astype(np.int64)
+    nxt = 1
+    paths, lists = [], []
+    for _ in range(N):
+        if len(paths) < roots or rng.random() < 0.02:
+            base = []
+        else:
+            p = paths[int(rng.integers(0, len(paths)))]
+            base = p[:int(rng.integers(1, len(p) + 1))]
+        add = int(rng.integers(0 if base else 1, grow + 1)) if rng.random() < 0.7 or not base else 0
+        add = min(add, max_blocks - len(base))
+        path = base + list(range(nxt, nxt + add))
+        nxt += add
+        paths.append(path)
+        if len(paths) > 64:
+            paths.pop(int(rng.integers(0, len(paths))))
+        lists.append(path)
+    nblk = np.array([len(x) for x in lists], dtype=np.int64)
+    blk_off = np.concatenate([[0], np.cumsum(nblk)]).astype(np.int64)
+    ids = np.array([x for l in lists for x in l], dtype=np.int64)
+    in_len = (nblk * block_tokens - rng.integers(0, block_tokens // 2, size=N) * (rng.random(N) < 0.3)).astype(np.int32)
+    out_len = rng.integers(1, 40, size=N).astype(np.int32)
+    return Trace(ts, in_len, out_len, blk_off, ids)

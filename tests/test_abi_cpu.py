@@ -40,6 +40,10 @@ def test_trace_info_and_chain_consistency():
     bad = tg.random_small(3, 50, 2, consistent=False)
     assert not _trace(bad).info()["chain_consistent"]
     assert _trace(tg.random_small(3, 50, 2, consistent=True)).info()["chain_consistent"]
+    for seed in range(4):                                 # branching forests: consistent by construction
+        f = tg.random_forest(seed, 300, max_blocks=5 + 10 * seed)
+        i = _trace(f).info()
+        assert i["chain_consistent"] and i["max_blocks"] <= 5 + 10 * seed and np.diff(f.blk_off).min() >= 1
 
 
 def test_jsonl_loader_matches_arrays(tmp_path):
