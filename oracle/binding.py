@@ -27,6 +27,12 @@ def lib():
             [C.c_int32, C.c_int32, C.c_int32, C.c_int64, C.c_double, C.c_double, C.c_void_p, C.c_void_p, C.c_double,
              C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_double, C.c_int32,
              C.c_uint64] + [C.c_void_p] * 11
+        L.gorgo_oracle_replay_engine.restype = C.c_int
+        L.gorgo_oracle_replay_engine.argtypes = [C.c_int64] + [C.c_void_p] * 5 + \
+            [C.c_int32, C.c_int32, C.c_int32, C.c_int64, C.c_double, C.c_void_p, C.c_void_p, C.c_void_p, C.c_double,
+             C.c_void_p, C.c_void_p, C.c_double,
+             C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_double, C.c_int32,
+             C.c_uint64] + [C.c_void_p] * 8
         L.gorgo_oracle_philox4x32_10.restype = None
         L.gorgo_oracle_philox4x32_10.argtypes = [C.c_void_p] * 3
         L.gorgo_oracle_splitmix64_next.restype = C.c_uint64
@@ -127,7 +133,7 @@ POLICIES = {"cost-model": 0, "least-request": 1, "session-affinity": 2, "random"
 
 
 def _replay_ex(trace, R, batch, cache_blocks, prefill_ms_per_token, decode_ms_per_token, rtt_ms, w, scale,
-               block_tokens, window, hop, schedule, z, lo, hi, sigma0, policy=0, seed=0) -> Replay:
+               block_tokens, window, hop, schedule, z, lo, hi, sigma0, policy=0, seed=0, engine=None) -> Replay:
     N = int(trace.ts_ms.shape[0])
     ts = np.ascontiguousarray(trace.ts_ms, dtype=np.int64)
     il = np.ascontiguousarray(trace.in_len, dtype=np.int32)
@@ -152,13 +158,26 @@ def _replay_ex(trace, R, batch, cache_blocks, prefill_ms_per_token, decode_ms_pe
     theta_step = np.zeros((steps, 3), np.float64)
     fitness_step = np.zeros(steps, np.float64)
     fin = np.zeros(6, np.float64)
-    rc = lib().gorgo_oracle_replay_ex(N, _p(ts), _p(il), _p(ol), _p(bo), _p(hs), block_tokens, R, batch, cache_blocks,
-                                      prefill_ms_per_token, decode_ms_per_token, _p(rtt), _p(wv), float(scale),
-                                      window, hop, _p(sched), _p(zz), _p(lov), _p(hiv), float(sigma0), int(policy),
-                                      int(seed), _p(route), _p(hit), _p(ttft), _p(e2e), _p(p), None, None, None,
-                                      _p(theta_step), _p(fitness_step), _p(fin))
+    if engine is None:
+        rc = lib().gorgo_oracle_replay_ex(N, _p(ts), _p(il), _p(ol), _p(bo), _p(hs), block_tokens, R, batch,
+                                          cache_blocks, prefill_ms_per_token, decode_ms_per_token, _p(rtt), _p(wv),
+                                          float(scale), window, hop, _p(sched), _p(zz), _p(lov), _p(hiv),
+                                          float(sigma0), int(policy), int(seed), _p(route), _p(hit), _p(ttft),
+                                          _p(e2e), _p(p), None, None, None, _p(theta_step), _p(fitness_step), _p(fin))
+    else:
+        apf = np.ascontiguousarray(engine["prefill_ms_per_token"], dtype=np.float64)
+        adec = np.ascontiguousarray(engine["decode_ms_per_token"], dtype=np.float64)
+        kv = engine.get("kv_tokens")
+        kv = None if kv is None else np.ascontiguousarray(kv, dtype=np.int64)
+        assert apf.shape == (R,) and adec.shape == (R,) and (kv is None or kv.shape == (R,))
+        rc = lib().gorgo_oracle_replay_engine(N, _p(ts), _p(il), _p(ol), _p(bo), _p(hs), block_tokens, R, batch,
+                                              cache_blocks, prefill_ms_per_token, _p(apf), _p(adec), _p(kv),
+                                              float(engine.get("slowdown", 0.0)), _p(rtt), _p(wv), float(scale),
+                                              window, hop, _p(sched), _p(zz), _p(lov), _p(hiv), float(sigma0),
+                                              int(policy), int(seed), _p(route), _p(hit), _p(ttft), _p(e2e), _p(p),
+                                              _p(theta_step), _p(fitness_step), _p(fin))
     if rc != 0:
-        raise RuntimeError(f"gorgo_oracle_replay_ex failed with code {rc}")
+        raise RuntimeError(f"oracle replay failed with code {rc}")
     return Replay(route, hit, ttft, e2e, float(p[0]), float(p[1]), theta_step=theta_step, fitness_step=fitness_step,
                   theta_final=fin[:3].copy(), sigma_final=float(fin[3]), steps=int(fin[4]), accepted=int(fin[5]))
 
@@ -182,3 +201,14 @@ def replay_policy(trace, *, R, batch, cache_blocks, prefill_ms_per_token, decode
     """One replay routed by a baseline policy ("least-request", "session-affinity", "random")."""
     return _replay_ex(trace, R, batch, cache_blocks, prefill_ms_per_token, decode_ms_per_token, rtt_ms, [0.0, 0.0, 0.0],
                       scale, block_tokens, 0, 0, None, None, None, None, 0.0, POLICIES[policy], seed)
+
+
+def replay_engine(trace, *, R, batch, cache_blocks, prefill_ms_per_token, engine, rtt_ms, w=(0.0, 0.0, 0.0),
+                  policy="cost-model", seed=0, scale=1.0, block_tokens=512, online=None) -> Replay:
+    """One replay with the engine model of a replica.  engine = dict(prefill_ms_per_token=[R],
+    decode_ms_per_token=[R], kv_tokens=[R] or None, slowdown=float); prefill_ms_per_token (the scalar) stays the
+    cost model's rate.  online = dict(z=, lo=, hi=, sigma0=, window=, hop=) runs the tuner from weights w."""
+    o = online or {}
+    return _replay_ex(trace, R, batch, cache_blocks, prefill_ms_per_token, 0.0, rtt_ms, w, scale, block_tokens,
+                      o.get("window", 0), o.get("hop", 0), None, o.get("z"), o.get("lo"), o.get("hi"),
+                      o.get("sigma0", 0.0), POLICIES[policy], seed, engine=engine)

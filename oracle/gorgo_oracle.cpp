@@ -25,8 +25,13 @@
 // at R=2 N=10 against an independent forced-route evaluator, weight special cases (all-zero, rtt-only,
 // prefix-only, queue-only, power-of-two rescaling), post-hoc recomputation of the load signal, Lindley /
 // Kiefer-Wolfowitz recurrences for the service model, a list-based LRU model, sorted-array percentile.
-// Parity unpinned by the paper (fixed by this build's stated readings only): the service-model constants
-// and the root-newest stamp order inside one request.
+// The engine model of a replica (continuous batching with a KV-token budget, decode slow-down under occupancy,
+// per-replica rates; struct Engine below) is pinned by two hand-worked traces, a millisecond-stepped simulation
+// of the admission rule on integer inputs, the serial-server and simultaneous-arrival closed forms, its
+// reduction to the linear model, the independence of replicas under random routing, and its invariants rebuilt
+// from the outputs.
+// Parity unpinned by the paper (fixed by this build's stated readings only): the service-model constants,
+// the functional form of the engine model and the root-newest stamp order inside one request.
 
 #include <cstdint>
 #include <cstddef>
@@ -53,6 +58,31 @@ struct Replica {
     std::vector<double> free_at;                  // per service slot: time the slot becomes free
     std::multiset<std::pair<double, int64_t>> inflight;   // (completion time at the proxy, input tokens)
     int64_t q = 0;                                // tokens of requests without a completion event (Eq. 2)
+    // engine model only: the requests served here that may still be running at a later admission, as (time the
+    // last token is produced, KV tokens held), and the time the latest request was admitted
+    std::vector<std::pair<double, int64_t>> served;
+    double last_start = 0.0;
+};
+
+// The engine model of a replica (Sec. 2.2: continuous batching admits a request into the running batch while
+// the batch is below its maximum number of concurrent requests and the KV-cache budget allows; Sec. 5
+// "Exploiting Continuous Batching": once many requests decode together the replica's memory saturates and
+// inter-token latency grows; Sec. 7: replicas may differ in prefill rate, queueing behaviour and KV capacity).
+// The paper gives no formulas for any of this; the stated model is:
+//   * replica i prefills at a_pf[i] ms per uncached token and decodes at a_dec[i] ms per output token;
+//   * a request holds in_len + out_len KV tokens from its admission until its last token is produced;
+//   * requests are admitted in arrival order (first come first served, no overtaking); a request is admitted at
+//     the first time s, not before its arrival and not before the admission of its predecessor, at which the
+//     requests running at s (admitted earlier, last token produced after s) number fewer than B and either
+//     there are none or their KV tokens plus the request's own fit into kv_tokens[i] (0 = no budget);
+//   * its decode takes (a_dec[i] * out_len) * (1 + slowdown * n), n being the number of requests running at its
+//     admission (the slow-down is fixed at admission and not revised when the batch changes later).
+// With slowdown = 0, no budget and equal rates this is the linear B-slot model.
+struct Engine {
+    const double* a_pf;        // [R]
+    const double* a_dec;       // [R]
+    const int64_t* kv_tokens;  // [R] or null
+    double slowdown;
 };
 
 // exp(x) from additions and multiplications only, so that every build of it gives the same bits (the weights
@@ -110,6 +140,30 @@ uint64_t splitmix64_next(uint64_t x) {
 // A 32-bit value spread over R replicas: floor(h * R / 2^32).
 int spread(uint32_t h, int R) { return (int)(((uint64_t)h * (uint64_t)R) >> 32); }
 
+// Admission time of a request of `kv` KV tokens that arrives at `a` on replica X (see Engine), and the number
+// of requests running then.  Written as the definition: the candidates are the earliest allowed time and every
+// later time at which a running request ends, tried in increasing order.
+double engine_admit(const Replica& X, int B, int64_t budget, double a, int64_t kv, int64_t* running_out) {
+    const double s0 = std::max(a, X.last_start);
+    std::vector<double> cand{s0};
+    for (const auto& x : X.served)
+        if (x.first > s0) cand.push_back(x.first);
+    std::sort(cand.begin(), cand.end());
+    for (double s : cand) {
+        int64_t n = 0, held = 0;
+        for (const auto& x : X.served)
+            if (x.first > s) {
+                ++n;
+                held += x.second;
+            }
+        if (n < B && (n == 0 || budget == 0 || held + kv <= budget)) {
+            *running_out = n;
+            return s;
+        }
+    }
+    return -1.0;   // not reached: after the last end nothing is running
+}
+
 }  // namespace
 
 extern "C" {
@@ -160,15 +214,20 @@ double gorgo_oracle_p95(const double* x, int64_t n) {
 //     splitmix64_next(first id)); a request without blocks goes to replica 0;
 //   3 random: replica spread(first word of Philox-4x32-10(counter = (r mod 2^32, r div 2^32, 0, 0), key =
 //     (seed mod 2^32, seed div 2^32))).
-int gorgo_oracle_replay_ex(int64_t N, const int64_t* ts_ms, const int32_t* in_len, const int32_t* out_len,
-                           const int64_t* blk_off, const int64_t* hash_ids, int32_t block_tokens,
-                           int32_t R, int32_t B, int64_t C, double a_pf, double a_dec,
-                           const double* rtt_ms, const double* w, double scale,
-                           int32_t window, int32_t hop, const double* schedule, const double* z,
-                           const double* lo, const double* hi, double sigma0, int32_t policy, uint64_t seed,
-                           uint8_t* route, uint16_t* hit_blocks, double* ttft_ms, double* e2e_ms, double* p95,
-                           double* score_dbg, int64_t* q_dbg, int64_t* size_dbg,
-                           double* theta_step, double* fitness_step, double* tuner_final) {
+//
+// Replica model: with engine == null the linear B-slot model; otherwise the engine model (see Engine), in which
+// the cost model of Eq. 3 keeps the single prefill rate a_pf: the router does not know that replicas differ
+// (Sec. 7, first limitation).
+static int replay_impl(int64_t N, const int64_t* ts_ms, const int32_t* in_len, const int32_t* out_len,
+                       const int64_t* blk_off, const int64_t* hash_ids, int32_t block_tokens,
+                       int32_t R, int32_t B, int64_t C, double a_pf, double a_dec,
+                       const double* rtt_ms, const double* w, double scale,
+                       int32_t window, int32_t hop, const double* schedule, const double* z,
+                       const double* lo, const double* hi, double sigma0, int32_t policy, uint64_t seed,
+                       const Engine* engine,
+                       uint8_t* route, uint16_t* hit_blocks, double* ttft_ms, double* e2e_ms, double* p95,
+                       double* score_dbg, int64_t* q_dbg, int64_t* size_dbg,
+                       double* theta_step, double* fitness_step, double* tuner_final) {
     if (N < 0 || R < 1 || R > 255 || B < 1 || C < 0 || block_tokens < 1) return -1;
     if (N > 0 && (!ts_ms || !in_len || !out_len || !blk_off)) return -1;
     if (window < 0 || (window > 0 && hop < 1)) return -1;
@@ -298,7 +357,30 @@ int gorgo_oracle_replay_ex(int64_t N, const int64_t* ts_ms, const int32_t* in_le
         // ms per output token.  The request reaches the replica half an RTT after t and its first token /
         // completion event come back half an RTT after they are produced.  This reproduces Eq. 1:
         // ttft = rtt + (start - arrival) + prefill(x_r \ c_i).
-        {
+        if (engine) {
+            const double half = 0.5 * rtt_ms[best];
+            const double a = t + half;
+            const int64_t kv = L + (int64_t)out_len[r];
+            int64_t running = 0;
+            const double s = engine_admit(X, B, engine->kv_tokens ? engine->kv_tokens[best] : 0, a, kv, &running);
+            const double pf = engine->a_pf[best] * (double)u[best];
+            const double f = s + pf;
+            const double dec_alone = engine->a_dec[best] * (double)out_len[r];
+            const double factor = 1.0 + engine->slowdown * (double)running;
+            const double dec = dec_alone * factor;
+            const double e = f + dec;
+            // (requests whose last token is out by s are running at no later admission time: forget them)
+            X.served.erase(std::remove_if(X.served.begin(), X.served.end(),
+                                          [s](const std::pair<double, int64_t>& x) { return x.first <= s; }),
+                           X.served.end());
+            X.served.emplace_back(e, kv);
+            X.last_start = s;
+            const double done = e + half;
+            ttft[r] = (f + half) - t;
+            e2e[r] = done - t;
+            X.inflight.emplace(done, L);
+            X.q += L;
+        } else {
             double half = 0.5 * rtt_ms[best];
             double a = t + half;
             int ks = 0;
@@ -378,6 +460,41 @@ int gorgo_oracle_replay_ex(int64_t N, const int64_t* ts_ms, const int32_t* in_le
         p95[1] = gorgo_oracle_p95(e2e.data(), N);
     }
     return 0;
+}
+
+int gorgo_oracle_replay_ex(int64_t N, const int64_t* ts_ms, const int32_t* in_len, const int32_t* out_len,
+                           const int64_t* blk_off, const int64_t* hash_ids, int32_t block_tokens,
+                           int32_t R, int32_t B, int64_t C, double a_pf, double a_dec,
+                           const double* rtt_ms, const double* w, double scale,
+                           int32_t window, int32_t hop, const double* schedule, const double* z,
+                           const double* lo, const double* hi, double sigma0, int32_t policy, uint64_t seed,
+                           uint8_t* route, uint16_t* hit_blocks, double* ttft_ms, double* e2e_ms, double* p95,
+                           double* score_dbg, int64_t* q_dbg, int64_t* size_dbg,
+                           double* theta_step, double* fitness_step, double* tuner_final) {
+    return replay_impl(N, ts_ms, in_len, out_len, blk_off, hash_ids, block_tokens, R, B, C, a_pf, a_dec, rtt_ms, w,
+                       scale, window, hop, schedule, z, lo, hi, sigma0, policy, seed, nullptr, route, hit_blocks,
+                       ttft_ms, e2e_ms, p95, score_dbg, q_dbg, size_dbg, theta_step, fitness_step, tuner_final);
+}
+
+// The same replay with the engine model of a replica: a_pf_r[R], a_dec_r[R] = per-replica service rates,
+// kv_tokens[R] = KV budgets in tokens (null or 0 = none), slowdown >= 0.  a_pf stays the cost model's rate.
+int gorgo_oracle_replay_engine(int64_t N, const int64_t* ts_ms, const int32_t* in_len, const int32_t* out_len,
+                               const int64_t* blk_off, const int64_t* hash_ids, int32_t block_tokens,
+                               int32_t R, int32_t B, int64_t C, double a_pf,
+                               const double* a_pf_r, const double* a_dec_r, const int64_t* kv_tokens, double slowdown,
+                               const double* rtt_ms, const double* w, double scale,
+                               int32_t window, int32_t hop, const double* schedule, const double* z,
+                               const double* lo, const double* hi, double sigma0, int32_t policy, uint64_t seed,
+                               uint8_t* route, uint16_t* hit_blocks, double* ttft_ms, double* e2e_ms, double* p95,
+                               double* theta_step, double* fitness_step, double* tuner_final) {
+    if (!a_pf_r || !a_dec_r || !(slowdown >= 0.0)) return -1;
+    if (kv_tokens)
+        for (int i = 0; i < R; ++i)
+            if (kv_tokens[i] < 0) return -1;
+    const Engine engine{a_pf_r, a_dec_r, kv_tokens, slowdown};
+    return replay_impl(N, ts_ms, in_len, out_len, blk_off, hash_ids, block_tokens, R, B, C, a_pf, 0.0, rtt_ms, w,
+                       scale, window, hop, schedule, z, lo, hi, sigma0, policy, seed, &engine, route, hit_blocks,
+                       ttft_ms, e2e_ms, p95, nullptr, nullptr, nullptr, theta_step, fitness_step, tuner_final);
 }
 
 // One replay under one fixed weight vector.
