@@ -83,13 +83,24 @@ def recorded_counters(kernel, workload_key):
     return rec
 
 
-def cpu_baseline(wl, params, n_req, threads, online=None):
+def cpu_baseline(wl, params, n_req, threads, online=None, engine=None):
     """The oracle as it stands, one replay per thread, on the first n_req requests of the workload (with its online
-    tuner when `online` = (z[P, steps, 3], lo, hi, sigma0) is given)."""
+    tuner when `online` = (z[P, steps, 3], lo, hi, sigma0) is given; under the engine model of a replica when
+    `engine` = its parameters is given)."""
     from concurrent.futures import ThreadPoolExecutor
     from oracle import binding as ob
     tr = wl.trace.head(n_req)
     ob.lib()
+    if engine is not None:
+        def one_engine(p):
+            return ob.replay_engine(tr, R=wl.R, batch=wl.batch, cache_blocks=wl.cache_blocks,
+                                    prefill_ms_per_token=wl.prefill_ms_per_token, engine=engine, rtt_ms=wl.rtt_ms,
+                                    w=params[p], scale=1.0).p95_ttft_ms
+        t0 = time.perf_counter()
+        with ThreadPoolExecutor(threads) as ex:
+            list(ex.map(one_engine, range(threads)))
+        dt = time.perf_counter() - t0
+        return threads * tr.N / dt, dt, tr.N
     if online is not None:
         z, lo, hi, sigma0 = online
         steps = ob.online_steps(tr.N, 128, 32)
@@ -166,7 +177,13 @@ def main():
     ap.add_argument("--online", action="store_true",
                     help="instead of one ES generation per step: one pass of P online tuners (window 128, hop 32) "
                          "over the trace per step -- the tuner as the paper runs it, not the headline metric")
+    ap.add_argument("--engine", action="store_true",
+                    help="replicas follow the engine model (continuous batching with a KV-token budget, decode slow-down, "
+                         "uneven rates: synth.tracegen.engine_recipe) instead of the linear one; a step is still one ES "
+                         "generation -- not the headline metric")
     args = ap.parse_args()
+    if args.engine and args.online:
+        sys.exit("bench.py: --engine and --online are separate runs")
     if args.gpus != 1:
         sys.exit("bench.py: this build evaluates on ONE GPU (replays are independent and would shard by candidate; "
                  "no multi-GPU path is built) -- run with --gpus 1")
@@ -186,7 +203,7 @@ def main():
     N = tr.N
     model = g.Model(wl.R, wl.batch, wl.cache_blocks, wl.prefill_ms_per_token, wl.decode_ms_per_token)
     state = g.es_init(es_cfg["seed"])
-    ws_bytes = g.workspace_bytes(tr, model, P) if args.online else g.es_workspace_bytes(tr, model, P)
+    ws_bytes = g.workspace_bytes(tr, model, P) if args.online or args.engine else g.es_workspace_bytes(tr, model, P)
     ws = torch.empty((ws_bytes,), dtype=torch.uint8, device="cuda:0")
     print(f"[bench] workload {wl.name}: R={wl.R} N={N} P={P} C={wl.cache_blocks} mean blocks/request "
           f"{np.diff(wl.trace.blk_off).mean():.1f}; workspace {ws.numel() / 2**30:.1f} GiB; setup "
@@ -197,7 +214,19 @@ def main():
         z_on = torch.from_numpy(g.es_sample(es_cfg["seed"], 0, P * steps_on).reshape(P, steps_on, 3)).to("cuda:0")
         theta0 = np.tile(np.array(state.theta[:]), (P, 1))
 
+    if args.engine:
+        recipe = tg.engine_recipe(wl)
+        engine = g.Engine(recipe["prefill_ms_per_token"], recipe["decode_ms_per_token"], recipe["kv_tokens"],
+                          recipe["slowdown"])
+
     def generation():
+        if args.engine:
+            # the generation loop of gorgo_es_step spelled out, with the engine model's evaluation in the middle
+            par = g.es_propose(state, g.es_sample(state.seed, state.generation, P))
+            res = g.eval_engine(tr, model, engine, wl.rtt_ms, 1.0, params=par, per_request=False, workspace=ws)
+            fit = res.p95_ttft_ms.cpu().numpy()
+            g.es_update(state, par, fit)
+            return par, fit, g.last_eval_kernel_ms()
         if args.online:
             res = g.eval_online(tr, model, wl.rtt_ms, theta0, z_on, 1.0, lo=state.lo[:], hi=state.hi[:], sigma0=state.sigma,
                                 per_request=False, trajectory=False, workspace=ws)
@@ -252,7 +281,7 @@ def main():
         bpr = algorithmic_bytes_per_routing(wl.R, n_mean, hit_mean, outputs_bytes=9)
         kernel = "replay_blocks_kernel"
     k_ms = float(np.mean(kernel_ms))
-    counters = None if args.online else recorded_counters(kernel, f"config-{args.config} N={N} P={P}")
+    counters = None if args.online or args.engine else recorded_counters(kernel, f"config-{args.config} N={N} P={P}")
     traffic = counters["fetch_bytes_per_launch"] + counters["write_bytes_per_launch"] if counters else None
     achieved = bpr * P * N / (k_ms * 1e-3) / 1e9
     # The replay is one dependent chain per candidate: what limits it is the rate at which a SIMD issues the
@@ -270,8 +299,11 @@ def main():
 
     mode = "P online tuners (window 128, hop 32) over the trace per step" if args.online else \
         "one ES generation per step (eval + p95 TTFT fitness + mean update)"
+    if args.engine:
+        mode += ", replicas under the engine model (uneven rates, KV-token budget, decode slow-down)"
     out = {
-        "metric": "candidate-request routings/sec at P=1024" + (" (online tuner)" if args.online else ""),
+        "metric": "candidate-request routings/sec at P=1024" + (" (online tuner)" if args.online else "") +
+                  (" (engine model of a replica)" if args.engine else ""),
         "value": value, "unit": "routings/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f64", "data": "synthetic",
@@ -289,7 +321,8 @@ def main():
     if not args.no_cpu_baseline:
         cores = min(len(os.sched_getaffinity(0)), 16)
         on = (z_on[:cores].cpu().numpy(), list(state.lo[:]), list(state.hi[:]), state.sigma) if args.online else None
-        v, dt, n_s = cpu_baseline(wl, theta0 if args.online else par, min(args.cpu_sample_requests, N), cores, on)
+        v, dt, n_s = cpu_baseline(wl, theta0 if args.online else par, min(args.cpu_sample_requests, N), cores, on,
+                                  recipe if args.engine else None)
         out["cpu_baseline"] = {"value": v, "unit": "routings/s", "cores": cores, "kind": "oracle",
                                "sample": f"{cores} replays (one per thread) x first {n_s} requests of the same trace, "
                                          f"{dt:.1f}s wall"}

@@ -236,6 +236,41 @@ int gorgo_eval_policy(const gorgo_trace* t, const gorgo_model* m, const double* 
                       const uint64_t* seeds, const double* scale, int32_t P, const gorgo_outputs* outputs,
                       void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* ------------------------------------------------------------------------- engine model of a replica
+ * A richer replica than the linear B-slot model of gorgo_model, for the effects the paper reports but gives no
+ * formulas for: continuous batching admits a request into the running batch while the batch is below its
+ * maximum number of concurrent requests and the KV-cache budget allows (Sec. 2.2); when many requests decode
+ * together the replica's memory saturates and inter-token latency grows, so a router can buy a low TTFT with a
+ * high E2E latency by concentrating load (Sec. 5 "Exploiting Continuous Batching"); replicas may differ in
+ * prefill rate, queueing behaviour and KV capacity, which the cost model does not know (Sec. 7).  Stated model:
+ *   - replica i prefills at prefill_ms_per_token[i] per uncached token and decodes at decode_ms_per_token[i]
+ *     per output token; the cost model of Eq. 3 keeps the single rate of gorgo_model;
+ *   - a request holds input_length + output_length KV tokens from its admission until its last token;
+ *   - requests are admitted in arrival order: a request is admitted at the first time s, not before its
+ *     arrival at the replica nor the admission of its predecessor there, at which the requests running at s
+ *     (admitted earlier, last token after s) number fewer than gorgo_model.batch and either there are none or
+ *     their KV tokens plus its own do not exceed kv_tokens[i] (0 or a NULL array: no budget);
+ *   - its decode takes (decode_ms_per_token[i] * output_length) * (1 + decode_slowdown * n), n = the number of
+ *     requests running at its admission; the factor is fixed at admission.
+ * With decode_slowdown = 0, no budget and rates equal to gorgo_model's the results equal the linear model's bit
+ * for bit.  gorgo_model.decode_ms_per_token is not used.  Needs a chain-consistent trace. */
+typedef struct gorgo_engine {
+    const double* prefill_ms_per_token;   /* host [R], finite, 0..1e6          */
+    const double* decode_ms_per_token;    /* host [R], finite, 0..1e6          */
+    const int64_t* kv_tokens;             /* host [R], 0..2^52, or NULL        */
+    double decode_slowdown;               /* finite, 0..1e3                    */
+} gorgo_engine;
+
+/* Evaluate P replays under the engine model.  What routes is chosen by `policy`:
+ *   GORGO_POLICY_COST_MODEL with online == NULL: fixed weights params (host [P][3]), as gorgo_eval_population;
+ *   GORGO_POLICY_COST_MODEL with online != NULL: the online tuner from weights params, as gorgo_eval_online;
+ *   the other policies: as gorgo_eval_policy (params may be NULL; seeds as there; online must be NULL).
+ * Everything else (outputs, workspace and its size, stream, errors) as gorgo_eval_population. */
+int gorgo_eval_engine(const gorgo_trace* t, const gorgo_model* m, const gorgo_engine* engine, const double* rtt_ms,
+                      int32_t policy, const double* params, const uint64_t* seeds, const gorgo_online* online,
+                      const double* scale, int32_t P, const gorgo_outputs* outputs, void* workspace,
+                      size_t workspace_bytes, void* hip_stream);
+
 /* ------------------------------------------------------------------------------------------------ misc
  * Device time (ms, HIP events recorded on the evaluation's stream) of the three stages of the most recent
  * gorgo_eval_population / gorgo_es_step issued by the calling thread: state initialisation, the replay

@@ -5,7 +5,7 @@ from __future__ import annotations
 import ctypes as C
 import os
 from dataclasses import dataclass
-from typing import Optional
+from typing import Optional, Sequence
 
 import numpy as np
 
@@ -35,6 +35,11 @@ class _Online(C.Structure):
     _fields_ = [("window", C.c_int32), ("hop", C.c_int32), ("lo", C.c_double * 3), ("hi", C.c_double * 3),
                 ("sigma0", C.c_double), ("z", C.c_void_p), ("theta_step", C.c_void_p), ("fitness_step", C.c_void_p),
                 ("theta_final", C.c_void_p), ("sigma_final", C.c_void_p), ("accepted", C.c_void_p)]
+
+
+class _Engine(C.Structure):
+    _fields_ = [("prefill_ms_per_token", C.c_void_p), ("decode_ms_per_token", C.c_void_p), ("kv_tokens", C.c_void_p),
+                ("decode_slowdown", C.c_double)]
 
 
 class EsState(C.Structure):
@@ -70,6 +75,8 @@ def lib():
         L.gorgo_eval_online.argtypes = [vp, C.POINTER(_Model), vp, vp, vp, i32, C.POINTER(_Online), C.POINTER(_Outputs),
                                         vp, C.c_size_t, vp]
         L.gorgo_eval_policy.argtypes = [vp, C.POINTER(_Model), vp, i32, vp, vp, i32, C.POINTER(_Outputs), vp, C.c_size_t, vp]
+        L.gorgo_eval_engine.argtypes = [vp, C.POINTER(_Model), C.POINTER(_Engine), vp, i32, vp, vp, C.POINTER(_Online), vp,
+                                        i32, C.POINTER(_Outputs), vp, C.c_size_t, vp]
         L.gorgo_es_init.argtypes = [C.POINTER(EsState), C.c_uint64]
         L.gorgo_es_sample.argtypes = [C.c_uint64, i64, i32, vp]
         L.gorgo_philox4x32_10.argtypes = [vp, vp, vp]
@@ -84,7 +91,7 @@ def lib():
         L.gorgo_query_replay_path.argtypes = [vp, C.POINTER(i32), C.POINTER(i64), C.POINTER(i64)]
         L.gorgo_last_eval_kernel_ms.argtypes = [C.POINTER(dbl)] * 3
         for name in ("gorgo_load_trace", "gorgo_load_trace_arrays", "gorgo_trace_info", "gorgo_workspace_bytes",
-                     "gorgo_eval_population", "gorgo_eval_online", "gorgo_eval_policy", "gorgo_es_init", "gorgo_es_sample", "gorgo_es_propose",
+                     "gorgo_eval_population", "gorgo_eval_online", "gorgo_eval_policy", "gorgo_eval_engine", "gorgo_es_init", "gorgo_es_sample", "gorgo_es_propose",
                      "gorgo_es_update", "gorgo_es_workspace_bytes", "gorgo_es_step", "gorgo_set_table_factor_percent",
                      "gorgo_last_eval_kernel_ms", "gorgo_set_replay_path", "gorgo_set_handover_poll_limit", "gorgo_query_replay_path"):
             getattr(L, name).restype = C.c_int
@@ -358,6 +365,89 @@ def eval_online(trace: Trace, model: Model, rtt_ms, theta0, z, scale, *, lo, hi,
         _check(lib().gorgo_eval_online(trace._h, C.byref(m), _ptr(rtt), _ptr(th0), _ptr(sc), P, C.byref(on), C.byref(o),
                                        C.c_void_p(workspace.data_ptr()), workspace.numel(), C.c_void_p(s.cuda_stream)))
     res._z = zt          # keep the draws alive until the stream has consumed them
+    return res
+
+
+@dataclass
+class Engine:
+    """Engine model of a replica (gorgo_engine): per-replica rates, KV budgets in tokens (None = no budget) and
+    the decode slow-down per co-running request."""
+    prefill_ms_per_token: Sequence[float]
+    decode_ms_per_token: Sequence[float]
+    kv_tokens: Optional[Sequence[int]] = None
+    decode_slowdown: float = 0.0
+
+
+def eval_engine(trace: Trace, model: Model, engine: Engine, rtt_ms, scale, *, params=None, policy: str = "cost-model",
+                seeds=None, online: Optional[dict] = None, per_request: bool = True, p95: bool = True,
+                workspace=None, stream=None, device="cuda:0") -> EvalResult:
+    """gorgo_eval_engine with torch-allocated outputs.  policy "cost-model" routes by Eq. 3 with weights params
+    [P,3] (and, with online = dict(z=[P,steps,3], lo=, hi=, sigma0=, window=, hop=), tunes them online); the
+    baseline policies route as in eval_policy, one replay per entry of `scale`."""
+    import torch
+    rtt = _np(rtt_ms, np.float64)
+    cost_model = policy == "cost-model"
+    if cost_model:
+        par = _np(params, np.float64)
+        P = par.shape[0]
+        if par.shape != (P, 3):
+            raise ValueError("params must be [P,3]")
+        sc = _np(np.broadcast_to(np.asarray(scale, dtype=np.float64), (P,)), np.float64)
+    else:
+        par = None
+        sc = _np(np.atleast_1d(np.asarray(scale, dtype=np.float64)), np.float64)
+        P = sc.shape[0]
+    sd = None if seeds is None else _np(seeds, np.uint64)
+    a_pf = _np(engine.prefill_ms_per_token, np.float64)
+    a_dec = _np(engine.decode_ms_per_token, np.float64)
+    kv = None if engine.kv_tokens is None else _np(engine.kv_tokens, np.int64)
+    if rtt.shape != (model.R,) or a_pf.shape != (model.R,) or a_dec.shape != (model.R,) or \
+            (kv is not None and kv.shape != (model.R,)) or (sd is not None and sd.shape != (P,)):
+        raise ValueError("rtt_ms, the engine's rates and budgets must be [R], seeds [P]")
+    eng = _Engine(_ptr(a_pf), _ptr(a_dec), _ptr(kv), float(engine.decode_slowdown))
+    N = trace.N
+    dev = torch.device(device)
+    res = EvalResult()
+    if per_request:
+        res.route = torch.empty((P, N), dtype=torch.uint8, device=dev)
+        res.hit_blocks = torch.empty((P, N), dtype=torch.uint16, device=dev)
+        res.ttft_ms = torch.empty((P, N), dtype=torch.float64, device=dev)
+        res.e2e_ms = torch.empty((P, N), dtype=torch.float64, device=dev)
+    if p95:
+        res.p95_ttft_ms = torch.empty((P,), dtype=torch.float64, device=dev)
+        res.p95_e2e_ms = torch.empty((P,), dtype=torch.float64, device=dev)
+    on = None
+    if online is not None:
+        window, hop = int(online.get("window", 128)), int(online.get("hop", 32))
+        steps = online_steps(N, window, hop)
+        z = online["z"]
+        zt = z if isinstance(z, torch.Tensor) else torch.from_numpy(_np(z, np.float64))
+        zt = zt.to(device=dev, dtype=torch.float64).contiguous()
+        if tuple(zt.shape) != (P, steps, 3):
+            raise ValueError(f"z must be [P, {steps}, 3]")
+        res.theta_step = torch.empty((P, steps, 3), dtype=torch.float64, device=dev)
+        res.fitness_step = torch.empty((P, steps), dtype=torch.float64, device=dev)
+        res.theta_final = torch.empty((P, 3), dtype=torch.float64, device=dev)
+        res.sigma_final = torch.empty((P,), dtype=torch.float64, device=dev)
+        res.accepted = torch.empty((P,), dtype=torch.int32, device=dev)
+        res._z = zt
+        on = _Online(window, hop, (C.c_double * 3)(*[float(x) for x in online["lo"]]),
+                     (C.c_double * 3)(*[float(x) for x in online["hi"]]), float(online["sigma0"]),
+                     C.c_void_p(zt.data_ptr()), C.c_void_p(res.theta_step.data_ptr()),
+                     C.c_void_p(res.fitness_step.data_ptr()), C.c_void_p(res.theta_final.data_ptr()),
+                     C.c_void_p(res.sigma_final.data_ptr()), C.c_void_p(res.accepted.data_ptr()))
+    o = _outputs_struct(res.route, res.hit_blocks, res.ttft_ms, res.e2e_ms, res.p95_ttft_ms, res.p95_e2e_ms)
+    need = workspace_bytes(trace, model, P, o)
+    if workspace is None or workspace.numel() < need:
+        workspace = torch.empty((need,), dtype=torch.uint8, device=dev)
+    res.workspace = workspace
+    s = stream if stream is not None else torch.cuda.current_stream(dev)
+    m = model.c()
+    code = 0 if cost_model else POLICIES[policy]
+    with torch.cuda.device(dev):
+        _check(lib().gorgo_eval_engine(trace._h, C.byref(m), C.byref(eng), _ptr(rtt), code, _ptr(par), _ptr(sd),
+                                       None if on is None else C.byref(on), _ptr(sc), P, C.byref(o),
+                                       C.c_void_p(workspace.data_ptr()), workspace.numel(), C.c_void_p(s.cuda_stream)))
     return res
 
 

@@ -92,8 +92,8 @@ int make_plan(const gorgo_trace* t, const gorgo_model* m, int32_t P, const gorgo
     pl->off_e2e = off;
     if (!o || (!o->e2e_ms && want_p95_e)) off += up256((size_t)P * N * 8);
     pl->off_small = off;
-    // rtt, params, scale; tuner constants, ln theta0; seeds of the random policy
-    off += up256(((size_t)pl->R + 8 * (size_t)P + TUNER_CONSTS) * 8);
+    // rtt, params, scale; tuner constants, ln theta0; seeds of the random policy; rates and budgets of the engine model
+    off += up256((4 * (size_t)pl->R + 8 * (size_t)P + TUNER_CONSTS) * 8);
     pl->total = off;
     return GORGO_OK;
 }
@@ -159,9 +159,30 @@ namespace {
 // Validation, small copies and launches common to the fixed-weight and the online evaluation.
 int evaluate(const gorgo_trace* t, const gorgo_model* m, const double* rtt_ms, const double* params,
              const double* scale, int32_t P, const gorgo_online* online, int32_t policy, const uint64_t* seeds,
-             const gorgo_outputs* outputs, void* workspace, size_t workspace_bytes, void* hip_stream) {
+             const gorgo_outputs* outputs, void* workspace, size_t workspace_bytes, void* hip_stream,
+             const gorgo_engine* engine = nullptr) {
     int rc = check_model(t, m);
     if (rc) return rc;
+    std::vector<double> eng;        // a_pf[R], a_dec[R], budget[R]
+    if (engine) {
+        if (!engine->prefill_ms_per_token || !engine->decode_ms_per_token)
+            return fail(GORGO_ERR_INVALID_ARG, "engine rates are NULL");
+        if (!std::isfinite(engine->decode_slowdown) || engine->decode_slowdown < 0 || engine->decode_slowdown > 1e3)
+            return fail(GORGO_ERR_NONFINITE, "decode_slowdown must be finite and in 0..1e3");
+        eng.assign(3 * (size_t)m->R, 0.0);
+        for (int i = 0; i < m->R; ++i) {
+            const double pf = engine->prefill_ms_per_token[i], dec = engine->decode_ms_per_token[i];
+            if (!std::isfinite(pf) || pf < 0 || pf > 1e6 || !std::isfinite(dec) || dec < 0 || dec > 1e6)
+                return fail(GORGO_ERR_NONFINITE, "engine rates of replica " + std::to_string(i) +
+                                                     " must be finite and in 0..1e6");
+            const int64_t kv = engine->kv_tokens ? engine->kv_tokens[i] : 0;
+            if (kv < 0 || kv > (1ll << 52))
+                return fail(GORGO_ERR_INVALID_ARG, "kv_tokens[" + std::to_string(i) + "] must be in 0..2^52");
+            eng[i] = pf;
+            eng[m->R + i] = dec;
+            eng[2 * (size_t)m->R + i] = (double)kv;
+        }
+    }
     if (!rtt_ms || !params || !scale || !outputs) return fail(GORGO_ERR_INVALID_ARG, "a required pointer is NULL");
     Plan pl;
     rc = make_plan(t, m, P, outputs, &pl);
@@ -178,6 +199,8 @@ int evaluate(const gorgo_trace* t, const gorgo_model* m, const double* rtt_ms, c
             return fail(GORGO_ERR_NONFINITE, "scale[" + std::to_string(p) + "] must be finite and in 0..1e6");
     if (policy != 0 && pl.path != PATH_SEGMENTS)
         return fail(GORGO_ERR_INVALID_ARG, "the baseline policies need a chain-consistent trace (segment formulation)");
+    if (engine && pl.path != PATH_SEGMENTS)
+        return fail(GORGO_ERR_INVALID_ARG, "the engine model needs a chain-consistent trace (segment formulation)");
     std::vector<double> tuner;      // constants, then ln theta0[P][3]
     int64_t steps = 0;
     if (online) {
@@ -223,6 +246,17 @@ int evaluate(const gorgo_trace* t, const gorgo_model* m, const double* rtt_ms, c
     double* d_scale = d_params + 3 * (size_t)P;
     double* d_tuner = d_scale + P;
     uint64_t* d_seeds = reinterpret_cast<uint64_t*>(d_tuner + TUNER_CONSTS + 3 * (size_t)P);
+    double* d_eng = reinterpret_cast<double*>(d_seeds + P);
+    EngineLaunch el;
+    if (engine) {
+        // (the host vector goes away when this function returns: the copy must have been taken by then)
+        if ((rc = copy_small_to_device(d_eng, eng.data(), sizeof(double) * eng.size(), hip_stream))) return rc;
+        if ((rc = wait_for_copies(hip_stream))) return rc;
+        el.a_pf = d_eng;
+        el.a_dec = d_eng + pl.R;
+        el.budget = d_eng + 2 * (size_t)pl.R;
+        el.slowdown = engine->decode_slowdown;
+    }
     PolicyLaunch pol;
     pol.policy = policy;
     if (policy == GORGO_POLICY_RANDOM) {
@@ -259,7 +293,7 @@ int evaluate(const gorgo_trace* t, const gorgo_model* m, const double* rtt_ms, c
     double* e2e = outputs->e2e_ms;
     if (!e2e && outputs->p95_e2e_ms) e2e = reinterpret_cast<double*>(ws + pl.off_e2e);
     rc = launch_replay(t, pl, d_rtt, d_params, d_scale, route, outputs->hit_blocks, ttft, e2e, workspace, hip_stream,
-                       online ? &ol : nullptr, policy != 0 ? &pol : nullptr);
+                       online ? &ol : nullptr, policy != 0 ? &pol : nullptr, engine ? &el : nullptr);
     if (rc) return rc;
     if (outputs->p95_ttft_ms && (rc = launch_p95(ttft, pl.N, P, outputs->p95_ttft_ms, hip_stream))) return rc;
     if (outputs->p95_e2e_ms && (rc = launch_p95(e2e, pl.N, P, outputs->p95_e2e_ms, hip_stream))) return rc;
@@ -303,6 +337,25 @@ int gorgo_eval_policy(const gorgo_trace* t, const gorgo_model* m, const double* 
     const std::vector<double> zero(3 * (size_t)P, 0.0);       // the weights play no part
     return evaluate(t, m, rtt_ms, zero.data(), scale, P, nullptr, policy, seeds, outputs, workspace, workspace_bytes,
                     hip_stream);
+}
+
+int gorgo_eval_engine(const gorgo_trace* t, const gorgo_model* m, const gorgo_engine* engine, const double* rtt_ms,
+                      int32_t policy, const double* params, const uint64_t* seeds, const gorgo_online* online,
+                      const double* scale, int32_t P, const gorgo_outputs* outputs, void* workspace,
+                      size_t workspace_bytes, void* hip_stream) {
+    clear_error();
+    if (!engine) return fail(GORGO_ERR_INVALID_ARG, "engine is NULL");
+    if (policy < GORGO_POLICY_COST_MODEL || policy > GORGO_POLICY_RANDOM)
+        return fail(GORGO_ERR_INVALID_ARG, "policy must be 0 (cost model) .. 3 (random)");
+    if (policy == GORGO_POLICY_COST_MODEL)
+        return evaluate(t, m, rtt_ms, params, scale, P, online, 0, nullptr, outputs, workspace, workspace_bytes,
+                        hip_stream, engine);
+    if (online) return fail(GORGO_ERR_INVALID_ARG, "the online tuner tunes the cost model: policy must be 0");
+    if (policy == GORGO_POLICY_RANDOM && !seeds) return fail(GORGO_ERR_INVALID_ARG, "seeds is NULL");
+    if (P < 1 || P > (1 << 20)) return fail(GORGO_ERR_INVALID_ARG, "P must be in 1..2^20");
+    const std::vector<double> zero(3 * (size_t)P, 0.0);       // the weights play no part
+    return evaluate(t, m, rtt_ms, zero.data(), scale, P, nullptr, policy, seeds, outputs, workspace, workspace_bytes,
+                    hip_stream, engine);
 }
 
 int gorgo_last_eval_kernel_ms(double* fill_ms, double* replay_ms, double* select_ms) {

@@ -95,15 +95,17 @@ struct Queues {
     int32_t* s_next;     // [R*Bp] request after the second oldest (-1: none)
     int32_t* tail;       // [R*Bp] youngest request of the slot
     int32_t* depth;      // [R*Bp] requests in flight on the slot
+    uint32_t* kv;        // [R*Bp] engine model: KV tokens held by the request that frees the slot at free_at
     int R, B, Bp, base;
     double my_min;       // earliest head completion among this lane's slots ...
     int my_min_k;        // ... and its slot
     unsigned long long idle;   // slots of this lane's replica with nothing in flight (bit b = slot b)
     double my_q;         // outstanding tokens of replica = lane (an integer below 2^53, exact in fp64)
     double my_cnt;       // requests in flight on replica = lane
+    double my_last_start;      // engine model: admission time of the latest request of replica = lane
 
     static __host__ __device__ size_t bytes(int R, int B) {
-        return (size_t)R * ((B + 7) & ~7) * (8 * 3 + 4 * 5);
+        return (size_t)R * ((B + 7) & ~7) * (8 * 3 + 4 * 6);
     }
 
     __device__ void carve(unsigned char* lds, int R_, int B_, int lane) {
@@ -120,6 +122,7 @@ struct Queues {
         s_next = s_tok + n;
         tail = s_next + n;
         depth = tail + n;
+        kv = reinterpret_cast<uint32_t*>(depth + n);
     }
 
     __device__ void init(int lane) {
@@ -128,12 +131,14 @@ struct Queues {
             h_done[x] = INFINITY;
             depth[x] = 0;
             tail[x] = -1;
+            kv[x] = 0;
         }
         my_min = INFINITY;
         my_min_k = 0;
         idle = B >= 64 ? ~0ull : (1ull << B) - 1;
         my_q = 0.0;
         my_cnt = 0.0;
+        my_last_start = 0.0;
     }
 
     // Drop requests whose completion event has reached the proxy (done <= t).
@@ -236,6 +241,97 @@ struct Queues {
                     s_next[s] = -1;
                 } else {
                     // third or deeper: goes to global memory, linked behind the youngest
+                    st(&rec[r].done, done);
+                    st(&rec[r].next, (int32_t)-1);
+                    st(&rec[r].tokens, (int32_t)L);
+                    if (d == 2) s_next[s] = (int32_t)r;
+                    else st(&rec[tail[s]].next, (int32_t)r);
+                }
+                depth[s] = d + 1;
+            }
+            tail[s] = (int32_t)r;
+            my_q += (double)L;
+            my_cnt += 1.0;
+        }
+        *ttft_out = readlane_f64(ttft, best);
+        *e2e_out = readlane_f64(e2e, best);
+    }
+
+    // Service of request r on replica `best` under the engine model of a replica (continuous batching, Sec. 2.2;
+    // decode slow-down, Sec. 5 "Exploiting Continuous Batching"; replicas of different speed, Sec. 7).  Requests
+    // are admitted in arrival order; a request holding L + O KV tokens is admitted at the first time s, not
+    // before its arrival nor its predecessor's admission, at which fewer than B requests are running and either
+    // none is or their KV tokens plus its own fit the replica's budget (0 = no budget); its decode takes
+    // (a_dec * O) * (1 + slowdown * n) with n the requests running at s.  All requests admitted earlier have
+    // started by s, so those running at s are the slots with free_at > s: one scan counts them, adds their
+    // tokens up and finds the next time one ends; the scan is repeated from that time until the request fits
+    // (at most B times: each repeat has one request fewer running).  The request takes the lowest slot that is
+    // free at s; its record joins that slot's in-flight list, whose completion times still increase.
+    __device__ void serve_engine(int64_t r, int best, double t, double rtt_mine, int64_t uncached_mine, int64_t L,
+                                 int64_t O, double a_pf_mine, double a_dec_mine, double budget_mine, double slowdown,
+                                 Rec* rec, int lane, double* ttft_out, double* e2e_out) {
+        double ttft = 0.0, e2e = 0.0;
+        if (lane == best) {
+            const double half = 0.5 * rtt_mine;
+            const double arrive = t + half;
+            const double tokens = (double)(L + O);
+            double start = arrive > my_last_start ? arrive : my_last_start;
+            int n, k;
+            for (int scans = 0;; ++scans) {
+                n = B - Bp;                  // the padding slots (free_at = +inf) count as running below
+                k = -1;
+                double held = 0.0, next_end = INFINITY;
+                for (int b0 = 0; b0 < Bp; b0 += 8) {
+                    double f[8];
+                    uint32_t h[8];
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) {
+                        f[j] = free_at[base + b0 + j];
+                        h[j] = kv[base + b0 + j];
+                    }
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) {
+                        const bool running = f[j] > start;
+                        n += running ? 1 : 0;
+                        held += running ? (double)h[j] : 0.0;
+                        next_end = running && f[j] < next_end ? f[j] : next_end;
+                        k = !running && k < 0 ? b0 + j : k;
+                    }
+                }
+                if (n < B && (n == 0 || budget_mine == 0.0 || held + tokens <= budget_mine)) break;
+                if (scans >= Bp) break;      // not reached: every repeat has fewer requests running
+                start = next_end;            // finite: some request is running
+            }
+            k = k < 0 ? 0 : k;               // (a free slot exists whenever fewer than B are running)
+            my_last_start = start;
+            const double pf = a_pf_mine * (double)uncached_mine;
+            const double first_tok = start + pf;
+            const double dec_alone = a_dec_mine * (double)O;
+            const double factor = 1.0 + slowdown * (double)n;
+            const double dec = dec_alone * factor;
+            const double end = first_tok + dec;
+            const double done = end + half;
+            ttft = (first_tok + half) - t;
+            e2e = done - t;
+            const int s = base + k;
+            free_at[s] = end;
+            kv[s] = (uint32_t)(L + O);         // two counts below 2^31 each
+            if ((idle >> k) & 1ull) {
+                idle &= ~(1ull << k);
+                h_done[s] = done;
+                h_tok[s] = (int32_t)L;
+                depth[s] = 1;
+                if (done < my_min) {
+                    my_min = done;
+                    my_min_k = k;
+                }
+            } else {
+                const int d = depth[s];         // at least 1
+                if (d == 1) {
+                    s_done[s] = done;
+                    s_tok[s] = (int32_t)L;
+                    s_next[s] = -1;
+                } else {
                     st(&rec[r].done, done);
                     st(&rec[r].next, (int32_t)-1);
                     st(&rec[r].tokens, (int32_t)L);

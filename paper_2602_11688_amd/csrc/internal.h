@@ -97,12 +97,20 @@ struct PolicyLaunch {
     const uint64_t* seeds = nullptr;     // device [P]
 };
 
+// Engine model of a replica of one launch (device pointers; see gorgo_engine in gorgo.h).
+struct EngineLaunch {
+    const double* a_pf = nullptr;        // [R]
+    const double* a_dec = nullptr;       // [R]
+    const double* budget = nullptr;      // [R] KV tokens as doubles, 0 = none
+    double slowdown = 0.0;
+};
+
 // kernels.hip
 void set_handover_poll_limit(int32_t polls);
 int launch_replay(const gorgo_trace* t, const Plan& pl, const double* d_rtt, const double* d_params,
                   const double* d_scale, uint8_t* route, uint16_t* hit, double* ttft, double* e2e,
                   void* workspace, void* stream, const OnlineLaunch* online = nullptr,
-                  const PolicyLaunch* policy = nullptr);
+                  const PolicyLaunch* policy = nullptr, const EngineLaunch* engine = nullptr);
 int launch_p95(const double* x, int64_t N, int32_t P, double* out, void* stream);
 int last_eval_kernel_ms(double* fill_ms, double* replay_ms, double* select_ms);
 int upload_trace(const gorgo_trace* t);

@@ -492,7 +492,8 @@ int copy_small_to_host_sync(void* dst, const void* src, size_t bytes, void* stre
 
 int launch_replay(const gorgo_trace* t, const Plan& pl, const double* d_rtt, const double* d_params,
                   const double* d_scale, uint8_t* route, uint16_t* hit, double* ttft, double* e2e,
-                  void* workspace, void* stream, const OnlineLaunch* online, const PolicyLaunch* policy) {
+                  void* workspace, void* stream, const OnlineLaunch* online, const PolicyLaunch* policy,
+                  const EngineLaunch* engine) {
     hipStream_t s = static_cast<hipStream_t>(stream);
     char* ws = static_cast<char*>(workspace);
     g_marks.valid = false;
@@ -532,6 +533,10 @@ int launch_replay(const gorgo_trace* t, const Plan& pl, const double* d_rtt, con
         a.first_hash = t->dev.first_hash;
         a.seeds = policy ? policy->seeds : nullptr;
         a.spin_limit = g_poll_limit.load();
+        a.eng_a_pf = engine ? engine->a_pf : nullptr;
+        a.eng_a_dec = engine ? engine->a_dec : nullptr;
+        a.eng_budget = engine ? engine->budget : nullptr;
+        a.eng_slowdown = engine ? engine->slowdown : 0.0;
         const size_t cells = (size_t)pl.P * (size_t)a.nseg * pl.R;
         if (cells) {
             size_t blocks = (cells + 255) / 256;
@@ -554,22 +559,34 @@ int launch_replay(const gorgo_trace* t, const Plan& pl, const double* d_rtt, con
                 a.sigma_final = online->sigma_final;
                 a.accepted = online->accepted;
                 const size_t lds = replay_segments_lds_bytes(pl.R, pl.B, online->window);
-                hipLaunchKernelGGL(replay_segments_kernel<MODE_ONLINE>, dim3((unsigned)pl.P), dim3(SEG_THREADS), lds, s, a);
+                const dim3 grid((unsigned)pl.P), block(SEG_THREADS);
+                if (engine) hipLaunchKernelGGL((replay_segments_kernel<MODE_ONLINE, true>), grid, block, lds, s, a);
+                else hipLaunchKernelGGL((replay_segments_kernel<MODE_ONLINE, false>), grid, block, lds, s, a);
+            } else if (engine) {
+                const size_t lds = replay_segments_lds_bytes(pl.R, pl.B, 0);
+                const dim3 grid((unsigned)pl.P), block(SEG_THREADS);
+                switch (policy ? policy->policy : 0) {
+                    case 0: hipLaunchKernelGGL((replay_segments_kernel<MODE_COST_MODEL, true>), grid, block, lds, s, a); break;
+                    case 1: hipLaunchKernelGGL((replay_segments_kernel<MODE_LEAST_REQUEST, true>), grid, block, lds, s, a); break;
+                    case 2: hipLaunchKernelGGL((replay_segments_kernel<MODE_AFFINITY, true>), grid, block, lds, s, a); break;
+                    default: hipLaunchKernelGGL((replay_segments_kernel<MODE_RANDOM, true>), grid, block, lds, s, a); break;
+                }
             } else {
                 const size_t lds = replay_segments_lds_bytes(pl.R, pl.B, 0);
                 const dim3 grid((unsigned)pl.P), block(SEG_THREADS);
                 switch (policy ? policy->policy : 0) {
-                    case 0: hipLaunchKernelGGL(replay_segments_kernel<MODE_COST_MODEL>, grid, block, lds, s, a); break;
-                    case 1: hipLaunchKernelGGL(replay_segments_kernel<MODE_LEAST_REQUEST>, grid, block, lds, s, a); break;
-                    case 2: hipLaunchKernelGGL(replay_segments_kernel<MODE_AFFINITY>, grid, block, lds, s, a); break;
-                    default: hipLaunchKernelGGL(replay_segments_kernel<MODE_RANDOM>, grid, block, lds, s, a); break;
+                    case 0: hipLaunchKernelGGL((replay_segments_kernel<MODE_COST_MODEL, false>), grid, block, lds, s, a); break;
+                    case 1: hipLaunchKernelGGL((replay_segments_kernel<MODE_LEAST_REQUEST, false>), grid, block, lds, s, a); break;
+                    case 2: hipLaunchKernelGGL((replay_segments_kernel<MODE_AFFINITY, false>), grid, block, lds, s, a); break;
+                    default: hipLaunchKernelGGL((replay_segments_kernel<MODE_RANDOM, false>), grid, block, lds, s, a); break;
                 }
             }
             if ((e = hipGetLastError()) != hipSuccess) return hip_fail(e, "launch replay_segments_kernel");
         }
     } else {
-        if (online || (policy && policy->policy != 0))
-            return fail(GORGO_ERR_INVALID_ARG, "the online tuner and the baseline policies need the segment formulation");
+        if (online || engine || (policy && policy->policy != 0))
+            return fail(GORGO_ERR_INVALID_ARG,
+                        "the online tuner, the baseline policies and the engine model need the segment formulation");
         ReplayArgs a;
         a.ts = t->dev.ts;
         a.in_len = t->dev.in_len;

@@ -79,6 +79,11 @@ struct SegArgs {
     const uint32_t* first_hash;   // [N] hash of the request's first block
     const uint64_t* seeds;        // [P] seed of the random policy
     int32_t spin_limit;           // polls of a hand-over word before the replay is given up
+    // engine model of a replica (only read by the kernel's engine variants)
+    const double* eng_a_pf;       // [R] prefill ms per token
+    const double* eng_a_dec;      // [R] decode ms per token
+    const double* eng_budget;     // [R] KV budget in tokens, 0 = none
+    double eng_slowdown;
 };
 
 // What picks the replica: the cost model of Eq. 3 with fixed weights, the same with the online tuner, or one
@@ -231,7 +236,7 @@ __device__ __forceinline__ int cached_in(int32_t rl, int pos, int end, int c_r, 
 
 // Queue wavefront of a replay: for every request, retire what has completed by its arrival, publish the load
 // signals, wait for the cache wavefront's choice, serve the request there.  Writes the latencies.
-template <int MODE>
+template <int MODE, bool ENGINE>
 __device__ __forceinline__ void queue_wave(const SegArgs& a, int p, int lane, unsigned char* lds_raw, SegComm* comm) {
     constexpr bool ONLINE = MODE == MODE_ONLINE;
     const int R = a.R;
@@ -261,6 +266,10 @@ __device__ __forceinline__ void queue_wave(const SegArgs& a, int p, int lane, un
     }
     const double sc = a.scale[p];
     const double my_rtt = lane < R ? a.rtt[lane] : 0.0;
+    // engine model: this lane's replica has its own rates and KV budget
+    const double my_a_pf = ENGINE && lane < R ? a.eng_a_pf[lane] : 0.0;
+    const double my_a_dec = ENGINE && lane < R ? a.eng_a_dec[lane] : 0.0;
+    const double my_budget = ENGINE && lane < R ? a.eng_budget[lane] : 0.0;
     Rec* const rec = a.rec + (size_t)p * N;
     bool dead = false;
     for (int64_t r0 = 0; r0 < N && !dead; r0 += WAVE) {
@@ -296,7 +305,11 @@ __device__ __forceinline__ void queue_wave(const SegArgs& a, int p, int lane, un
             if (dead) break;
             const int best = (int)(hi & 63u);
             double ttft, e2e;
-            Q.serve(r, best, t, my_rtt, (int64_t)(int)lo, L, O, a.a_pf, a.a_dec, rec, lane, &ttft, &e2e);
+            if (ENGINE)
+                Q.serve_engine(r, best, t, my_rtt, (int64_t)(int)lo, L, O, my_a_pf, my_a_dec, my_budget, a.eng_slowdown,
+                               rec, lane, &ttft, &e2e);
+            else
+                Q.serve(r, best, t, my_rtt, (int64_t)(int)lo, L, O, a.a_pf, a.a_dec, rec, lane, &ttft, &e2e);
             o_ttft = lane == i ? ttft : o_ttft;
             o_e2e = lane == i ? e2e : o_e2e;
             if (ONLINE) {
@@ -360,7 +373,7 @@ __device__ __forceinline__ void queue_wave(const SegArgs& a, int p, int lane, un
     }
 }
 
-template <int MODE>
+template <int MODE, bool ENGINE>
 __global__ void __launch_bounds__(SEG_THREADS) replay_segments_kernel(SegArgs a) {
     constexpr bool ONLINE = MODE == MODE_ONLINE;
     extern __shared__ __align__(16) unsigned char lds_raw[];
@@ -380,7 +393,7 @@ __global__ void __launch_bounds__(SEG_THREADS) replay_segments_kernel(SegArgs a)
     }
     __syncthreads();
     if (threadIdx.x >= WAVE) {
-        queue_wave<MODE>(a, p, lane, lds_raw, &comm);
+        queue_wave<MODE, ENGINE>(a, p, lane, lds_raw, &comm);
         return;
     }
     __builtin_amdgcn_s_setprio(3);      // the cache wavefront has the longer loop: it goes first at issue

@@ -303,3 +303,15 @@ def random_forest(seed: int, N: int, *, roots: int = 3, max_blocks: int = 40, gr
     in_len = (nblk * block_tokens - rng.integers(0, block_tokens // 2, size=N) * (rng.random(N) < 0.3)).astype(np.int32)
     out_len = rng.integers(1, 40, size=N).astype(np.int32)
     return Trace(ts, in_len, out_len, blk_off, ids)
+
+
+def engine_recipe(wl: Workload, seed: int = 0, *, spread: float = 2.0, kv_requests: float = 4.0,
+                  slowdown: float = 0.05) -> dict:
+    """Seeded parameters of an uneven fleet for the engine model of a replica: replica i prefills and decodes at the
+    workload's rates times spread^u, u uniform in (-1, 1), drawn independently for the two rates; every replica's KV
+    budget is kv_requests times the tokens (input + output) of the largest request of the trace."""
+    rng = np.random.Generator(np.random.PCG64(np.random.SeedSequence([MASTER_SEED, 97, wl.config_index, seed])))
+    most = int((wl.trace.in_len.astype(np.int64) + wl.trace.out_len).max()) if wl.trace.N else 1
+    return dict(prefill_ms_per_token=wl.prefill_ms_per_token * spread ** rng.uniform(-1.0, 1.0, wl.R),
+                decode_ms_per_token=wl.decode_ms_per_token * spread ** rng.uniform(-1.0, 1.0, wl.R),
+                kv_tokens=np.full(wl.R, int(kv_requests * most), np.int64), slowdown=float(slowdown))

@@ -160,6 +160,38 @@ def test_online_and_policy_entry_points_reject_bad_arguments_before_touching_a_d
                                None) == -1                            # needs a chain-consistent trace
 
 
+def test_engine_entry_point_rejects_bad_arguments_before_touching_a_device():
+    t = _trace(tg.config(1, 300).trace)
+    m = g.Model(4, 8, 0, 0.05, 20.0).c()
+    L = g.lib()
+    rtt = np.array([10.0, 40.0, 120.0, 300.0])
+    par = np.ones((2, 3))
+    sc = np.ones(2)
+    o = gb._Outputs()
+    ok_pf, ok_dec = np.full(4, 0.05), np.full(4, 20.0)
+
+    def engine(pf=ok_pf, dec=ok_dec, kv=None, slow=0.1, policy=0, par=par, seeds=None, online=None, null=False, tr=t, mm=m):
+        e = gb._Engine(gb._ptr(pf), gb._ptr(dec), gb._ptr(kv), slow)
+        return L.gorgo_eval_engine(tr._h, C.byref(mm), None if null else C.byref(e), gb._ptr(rtt), policy, gb._ptr(par),
+                                   seeds, online, gb._ptr(sc), 2, C.byref(o), None, 1 << 40, None)
+    assert engine(null=True) == -1 and engine(pf=None) == -1 and engine(dec=None) == -1
+    assert engine(pf=np.array([0.05, np.nan, 0.05, 0.05])) == -6 and engine(dec=np.array([20.0, -1.0, 20.0, 20.0])) == -6
+    assert engine(slow=-0.5) == -6 and engine(slow=float("inf")) == -6
+    assert engine(kv=np.array([0, -1, 0, 0], np.int64)) == -1 and engine(kv=np.array([0, 1 << 60, 0, 0], np.int64)) == -1
+    assert engine(policy=-1) == -1 and engine(policy=4) == -1 and engine(policy=3) == -1       # random without seeds
+    assert engine(par=None) == -1                                                                # the cost model needs weights
+    on = gb._Online(128, 32, (C.c_double * 3)(0.05, 0.05, 0.05), (C.c_double * 3)(2.0, 2.0, 2.0), 0.5, C.c_void_p(256),
+                    None, None, None, None, None)
+    assert engine(policy=1, online=C.byref(on)) == -1                                            # the tuner tunes the cost model
+    # everything valid up to the workspace
+    assert engine() == -7 and engine(kv=np.array([0, 5000, 1, 1 << 52], np.int64)) == -7
+    assert engine(policy=1, par=None) == -7 and engine(policy=3, par=None, seeds=gb._ptr(np.array([1, 2], np.uint64))) == -7
+    assert engine(online=C.byref(on)) == -7
+    bad = _trace(tg.random_small(3, 50, 2, consistent=False))
+    mb = g.Model(2, 2, 0, 0.05, 20.0).c()
+    assert engine(tr=bad, mm=mb) == -1                                                           # needs a chain-consistent trace
+
+
 # ------------------------------------------------------------------------------------------------ tuner
 
 def test_philox_known_answers():
