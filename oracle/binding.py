@@ -33,6 +33,11 @@ def lib():
              C.c_void_p, C.c_void_p, C.c_double,
              C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_double, C.c_int32,
              C.c_uint64] + [C.c_void_p] * 8
+        L.gorgo_oracle_replay_proxy.restype = C.c_int
+        L.gorgo_oracle_replay_proxy.argtypes = [C.c_int64] + [C.c_void_p] * 5 + \
+            [C.c_int32, C.c_int32, C.c_int32, C.c_int64, C.c_double, C.c_double, C.c_void_p, C.c_void_p, C.c_void_p,
+             C.c_double, C.c_int32, C.c_int32, C.c_void_p, C.c_double, C.c_int32, C.c_void_p, C.c_double,
+             C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_double] + [C.c_void_p] * 11
         L.gorgo_oracle_philox4x32_10.restype = None
         L.gorgo_oracle_philox4x32_10.argtypes = [C.c_void_p] * 3
         L.gorgo_oracle_splitmix64_next.restype = C.c_uint64
@@ -67,6 +72,9 @@ class Replay:
     sigma_final: float = 0.0
     steps: int = 0
     accepted: int = 0
+    # imperfect proxy knowledge (replay_proxy only)
+    rtt_est: Optional[np.ndarray] = None        # float64 [epochs,R] the proxy's smoothed round trip times
+    believed_hit: Optional[np.ndarray] = None   # uint16 [N] blocks the proxy's index matched on the chosen replica
 
 
 def p95(x) -> float:
@@ -212,3 +220,59 @@ def replay_engine(trace, *, R, batch, cache_blocks, prefill_ms_per_token, engine
     return _replay_ex(trace, R, batch, cache_blocks, prefill_ms_per_token, 0.0, rtt_ms, w, scale, block_tokens,
                       o.get("window", 0), o.get("hop", 0), None, o.get("z"), o.get("lo"), o.get("hi"),
                       o.get("sigma0", 0.0), POLICIES[policy], seed, engine=engine)
+
+
+def replay_proxy(trace, *, R, batch, cache_blocks, prefill_ms_per_token, decode_ms_per_token=0.0, rtt_true, w,
+                 probe_ms=30000, alpha=0.5, stale_index=False, engine=None, scale=1.0, block_tokens=512, online=None,
+                 debug=False) -> Replay:
+    """One replay with imperfect proxy knowledge: rtt_true[epochs,R] are the true round trip times per probe epoch,
+    the cost model scores with their moving average; with stale_index it also takes its cached prefixes from the
+    set of everything ever dispatched to a replica.  engine / online as in replay_engine."""
+    N = int(trace.ts_ms.shape[0])
+    ts = np.ascontiguousarray(trace.ts_ms, dtype=np.int64)
+    il = np.ascontiguousarray(trace.in_len, dtype=np.int32)
+    ol = np.ascontiguousarray(trace.out_len, dtype=np.int32)
+    bo = np.ascontiguousarray(trace.blk_off, dtype=np.int64)
+    hs = np.ascontiguousarray(trace.hash_ids, dtype=np.int64)
+    rt = np.ascontiguousarray(rtt_true, dtype=np.float64)
+    wv = np.ascontiguousarray(w, dtype=np.float64)
+    assert rt.ndim == 2 and rt.shape[1] == R and wv.shape == (3,) and bo.shape == (N + 1,)
+    E = rt.shape[0]
+    o = online or {}
+    window, hop = o.get("window", 0), o.get("hop", 0)
+    steps = online_steps(N, window, hop)
+    zz = None if online is None else np.ascontiguousarray(o["z"], dtype=np.float64)
+    lov = None if online is None else np.ascontiguousarray(o["lo"], dtype=np.float64)
+    hiv = None if online is None else np.ascontiguousarray(o["hi"], dtype=np.float64)
+    assert zz is None or zz.shape == (steps, 3)
+    apf = adec = kv = None
+    slow = 0.0
+    if engine is not None:
+        apf = np.ascontiguousarray(engine["prefill_ms_per_token"], dtype=np.float64)
+        adec = np.ascontiguousarray(engine["decode_ms_per_token"], dtype=np.float64)
+        kv = engine.get("kv_tokens")
+        kv = None if kv is None else np.ascontiguousarray(kv, dtype=np.int64)
+        slow = float(engine.get("slowdown", 0.0))
+        assert apf.shape == (R,) and adec.shape == (R,) and (kv is None or kv.shape == (R,))
+    route = np.zeros(N, np.uint8)
+    hit = np.zeros(N, np.uint16)
+    believed = np.zeros(N, np.uint16)
+    ttft = np.zeros(N, np.float64)
+    e2e = np.zeros(N, np.float64)
+    p = np.zeros(2, np.float64)
+    est = np.zeros((E, R), np.float64)
+    score = np.zeros((N, R), np.float64) if debug else None
+    theta_step = np.zeros((steps, 3), np.float64)
+    fitness_step = np.zeros(steps, np.float64)
+    fin = np.zeros(6, np.float64)
+    rc = lib().gorgo_oracle_replay_proxy(N, _p(ts), _p(il), _p(ol), _p(bo), _p(hs), block_tokens, R, batch, cache_blocks,
+                                         prefill_ms_per_token, decode_ms_per_token, _p(apf), _p(adec), _p(kv), slow,
+                                         E, int(probe_ms), _p(rt), float(alpha), int(bool(stale_index)), _p(wv),
+                                         float(scale), window, hop, _p(zz), _p(lov), _p(hiv), float(o.get("sigma0", 0.0)),
+                                         _p(route), _p(hit), _p(ttft), _p(e2e), _p(p), _p(score), _p(est), _p(believed),
+                                         _p(theta_step), _p(fitness_step), _p(fin))
+    if rc != 0:
+        raise RuntimeError(f"oracle replay failed with code {rc}")
+    return Replay(route, hit, ttft, e2e, float(p[0]), float(p[1]), score=score, theta_step=theta_step,
+                  fitness_step=fitness_step, theta_final=fin[:3].copy(), sigma_final=float(fin[3]), steps=int(fin[4]),
+                  accepted=int(fin[5]), rtt_est=est, believed_hit=believed)

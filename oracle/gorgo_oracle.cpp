@@ -30,8 +30,13 @@
 // of the admission rule on integer inputs, the serial-server and simultaneous-arrival closed forms, its
 // reduction to the linear model, the independence of replicas under random routing, and its invariants rebuilt
 // from the outputs.
+// Imperfect proxy knowledge (round trip times per probe epoch scored through their moving average, a cache index
+// that never forgets; struct Proxy below) is pinned by a hand-worked trace, closed forms of the moving average,
+// probe epochs recovered from latencies at and around the epoch boundaries, reductions to the plain replay, the
+// forced-route model extended with the same knowledge, and the one-sidedness of the index's error.
 // Parity unpinned by the paper (fixed by this build's stated readings only): the service-model constants,
-// the functional form of the engine model and the root-newest stamp order inside one request.
+// the functional form of the engine model, the smoothing constant and the index's forgetting rule, and the
+// root-newest stamp order inside one request.
 
 #include <cstdint>
 #include <cstddef>
@@ -62,6 +67,8 @@ struct Replica {
     // last token is produced, KV tokens held), and the time the latest request was admitted
     std::vector<std::pair<double, int64_t>> served;
     double last_start = 0.0;
+    // imperfect proxy knowledge only: every block ever dispatched to this replica (the proxy's index)
+    std::unordered_set<int64_t> dispatched;
 };
 
 // The engine model of a replica (Sec. 2.2: continuous batching admits a request into the running batch while
@@ -139,6 +146,26 @@ uint64_t splitmix64_next(uint64_t x) {
 
 // A 32-bit value spread over R replicas: floor(h * R / 2^32).
 int spread(uint32_t h, int R) { return (int)(((uint64_t)h * (uint64_t)R) >> 32); }
+
+// What the proxy knows imperfectly (Sec. 2.2: T_network is the exponentially weighted moving average of a ping's
+// round trip time; Sec. 4, RTT figure: measured every 30 s on a separate probe; Sec. 7: the proxy does not observe
+// replica-side eviction, so its cache index may overestimate what is cached).  The paper gives neither the
+// smoothing constant nor the index's own forgetting rule; the stated model is:
+//   * time is cut into epochs of probe_ms: the epoch of time t is the largest e with e * probe_ms <= t, capped
+//     at epochs - 1; during epoch e the true round trip time of replica i is rtt_true[e][i] (both legs of a
+//     request dispatched in epoch e take half of it);
+//   * the proxy probes at the start of every epoch and smooths: est[0] = rtt_true[0], est[e] = alpha *
+//     rtt_true[e] + (1 - alpha) * est[e-1]; the cost model scores with est of the request's epoch;
+//   * stale_index: the proxy's index of replica i is the set of all blocks ever dispatched to i (a prefix trie
+//     of dispatched requests that never forgets); the cost model takes its uncached tokens from the longest
+//     prefix in that index, the replica prefills what its own (LRU, bounded) cache really misses.
+struct Proxy {
+    int32_t epochs;            // >= 1
+    int32_t probe_ms;          // >= 1
+    const double* rtt_true;    // [epochs][R]
+    double alpha;              // in (0, 1]
+    int32_t stale_index;       // 0 = the proxy sees the replicas' caches as they are
+};
 
 // Admission time of a request of `kv` KV tokens that arrives at `a` on replica X (see Engine), and the number
 // of requests running then.  Written as the definition: the candidates are the earliest allowed time and every
@@ -224,7 +251,7 @@ static int replay_impl(int64_t N, const int64_t* ts_ms, const int32_t* in_len, c
                        const double* rtt_ms, const double* w, double scale,
                        int32_t window, int32_t hop, const double* schedule, const double* z,
                        const double* lo, const double* hi, double sigma0, int32_t policy, uint64_t seed,
-                       const Engine* engine,
+                       const Engine* engine, const Proxy* proxy, double* rtt_est_out, uint16_t* believed_hit,
                        uint8_t* route, uint16_t* hit_blocks, double* ttft_ms, double* e2e_ms, double* p95,
                        double* score_dbg, int64_t* q_dbg, int64_t* size_dbg,
                        double* theta_step, double* fitness_step, double* tuner_final) {
@@ -251,10 +278,27 @@ static int replay_impl(int64_t N, const int64_t* ts_ms, const int32_t* in_len, c
             ln_hi[k] = std::log(hi[k]);
         }
 
+    // the proxy's smoothed round trip times, epoch by epoch
+    std::vector<double> rtt_est;
+    if (proxy) {
+        rtt_est.assign((size_t)proxy->epochs * R, 0.0);
+        for (int i = 0; i < R; ++i) rtt_est[i] = proxy->rtt_true[i];
+        for (int64_t e = 1; e < proxy->epochs; ++e)
+            for (int i = 0; i < R; ++i) {
+                const double fresh = proxy->alpha * proxy->rtt_true[e * R + i];
+                const double kept = (1.0 - proxy->alpha) * rtt_est[(e - 1) * R + i];
+                rtt_est[e * R + i] = fresh + kept;
+            }
+        if (rtt_est_out) std::copy(rtt_est.begin(), rtt_est.end(), rtt_est_out);
+    }
+    int64_t epoch = 0;
+    const double* rtt_score = rtt_ms;     // what the cost model believes ...
+    const double* rtt_real = rtt_ms;      // ... and what a request experiences
+
     std::vector<Replica> rep(R);
     for (auto& x : rep) x.free_at.assign(B, 0.0);
     std::vector<double> ttft(N), e2e(N), score(R);
-    std::vector<int64_t> m(R), u(R);
+    std::vector<int64_t> m(R), u(R), m_seen(R), u_seen(R);
 
     for (int64_t r = 0; r < N; ++r) {
         const int64_t* ids = hash_ids + blk_off[r];
@@ -264,6 +308,12 @@ static int replay_impl(int64_t N, const int64_t* ts_ms, const int32_t* in_len, c
 
         // time scale: gaps between requests are scaled linearly (larger scale = lighter load, Table 3)
         const double t = (double)ts_ms[r] * scale;
+        if (proxy) {
+            // (timestamps do not decrease, so the epoch only moves forward)
+            while (epoch + 1 < proxy->epochs && (double)(epoch + 1) * (double)proxy->probe_ms <= t) ++epoch;
+            rtt_score = rtt_est.data() + epoch * R;
+            rtt_real = proxy->rtt_true + epoch * R;
+        }
 
         // retire: a request stops counting toward the load signal once its completion event has reached
         // the proxy (Eq. 2 and the sentence before it).  An event at exactly t counts as completed.
@@ -284,14 +334,24 @@ static int replay_impl(int64_t N, const int64_t* ts_ms, const int32_t* in_len, c
             int64_t hit_tok = std::min<int64_t>(L, (int64_t)block_tokens * k);   // partial last block
             u[i] = L - hit_tok;
         }
+        // with a stale index the cost model sees the longest prefix ever dispatched to the replica instead
+        u_seen = u;
+        m_seen = m;
+        if (proxy && proxy->stale_index)
+            for (int i = 0; i < R; ++i) {
+                int64_t k = 0;
+                while (k < n && rep[i].dispatched.count(ids[k])) ++k;
+                m_seen[i] = k;
+                u_seen[i] = L - std::min<int64_t>(L, (int64_t)block_tokens * k);
+            }
 
         // score (Eq. 3) with all three terms in milliseconds: network = RTT_i; prefill = a_pf * uncached
         // tokens; queue = a_pf * outstanding tokens (time to prefill what is outstanding).  Association
         // is fixed: (w_rtt*rtt + w_prefill*pf) + w_queue*qd.
         for (int i = 0; i < R; ++i) {
-            double pf = a_pf * (double)u[i];
+            double pf = a_pf * (double)u_seen[i];
             double qd = a_pf * (double)rep[i].q;
-            double s_rtt = w_rtt * rtt_ms[i];
+            double s_rtt = w_rtt * rtt_score[i];
             double s_pf = w_prefill * pf;
             double s_q = w_queue * qd;
             double s = s_rtt + s_pf;
@@ -349,6 +409,7 @@ static int replay_impl(int64_t N, const int64_t* ts_ms, const int32_t* in_len, c
                 X.by_stamp.emplace(stamp, ids[k]);
             }
             if (size_dbg) size_dbg[r] = (int64_t)X.cache.size();
+            if (proxy && proxy->stale_index) X.dispatched.insert(ids, ids + n);
         }
 
         // service on the chosen replica (the paper leaves the replica model open; this build states a
@@ -358,7 +419,7 @@ static int replay_impl(int64_t N, const int64_t* ts_ms, const int32_t* in_len, c
         // completion event come back half an RTT after they are produced.  This reproduces Eq. 1:
         // ttft = rtt + (start - arrival) + prefill(x_r \ c_i).
         if (engine) {
-            const double half = 0.5 * rtt_ms[best];
+            const double half = 0.5 * rtt_real[best];
             const double a = t + half;
             const int64_t kv = L + (int64_t)out_len[r];
             int64_t running = 0;
@@ -381,7 +442,7 @@ static int replay_impl(int64_t N, const int64_t* ts_ms, const int32_t* in_len, c
             X.inflight.emplace(done, L);
             X.q += L;
         } else {
-            double half = 0.5 * rtt_ms[best];
+            double half = 0.5 * rtt_real[best];
             double a = t + half;
             int ks = 0;
             for (int k = 1; k < B; ++k)
@@ -401,6 +462,7 @@ static int replay_impl(int64_t N, const int64_t* ts_ms, const int32_t* in_len, c
 
         if (route) route[r] = (uint8_t)best;
         if (hit_blocks) hit_blocks[r] = (uint16_t)m[best];
+        if (believed_hit) believed_hit[r] = (uint16_t)m_seen[best];
         if (ttft_ms) ttft_ms[r] = ttft[r];
         if (e2e_ms) e2e_ms[r] = e2e[r];
 
@@ -472,8 +534,9 @@ int gorgo_oracle_replay_ex(int64_t N, const int64_t* ts_ms, const int32_t* in_le
                            double* score_dbg, int64_t* q_dbg, int64_t* size_dbg,
                            double* theta_step, double* fitness_step, double* tuner_final) {
     return replay_impl(N, ts_ms, in_len, out_len, blk_off, hash_ids, block_tokens, R, B, C, a_pf, a_dec, rtt_ms, w,
-                       scale, window, hop, schedule, z, lo, hi, sigma0, policy, seed, nullptr, route, hit_blocks,
-                       ttft_ms, e2e_ms, p95, score_dbg, q_dbg, size_dbg, theta_step, fitness_step, tuner_final);
+                       scale, window, hop, schedule, z, lo, hi, sigma0, policy, seed, nullptr, nullptr, nullptr, nullptr, route,
+                       hit_blocks, ttft_ms, e2e_ms, p95, score_dbg, q_dbg, size_dbg, theta_step, fitness_step,
+                       tuner_final);
 }
 
 // The same replay with the engine model of a replica: a_pf_r[R], a_dec_r[R] = per-replica service rates,
@@ -493,8 +556,34 @@ int gorgo_oracle_replay_engine(int64_t N, const int64_t* ts_ms, const int32_t* i
             if (kv_tokens[i] < 0) return -1;
     const Engine engine{a_pf_r, a_dec_r, kv_tokens, slowdown};
     return replay_impl(N, ts_ms, in_len, out_len, blk_off, hash_ids, block_tokens, R, B, C, a_pf, 0.0, rtt_ms, w,
-                       scale, window, hop, schedule, z, lo, hi, sigma0, policy, seed, &engine, route, hit_blocks,
-                       ttft_ms, e2e_ms, p95, nullptr, nullptr, nullptr, theta_step, fitness_step, tuner_final);
+                       scale, window, hop, schedule, z, lo, hi, sigma0, policy, seed, &engine, nullptr, nullptr, nullptr, route,
+                       hit_blocks, ttft_ms, e2e_ms, p95, nullptr, nullptr, nullptr, theta_step, fitness_step,
+                       tuner_final);
+}
+
+// The same replay with imperfect proxy knowledge (see Proxy): rtt_true[epochs][R] replaces rtt_ms; the engine
+// model is used when a_pf_r is not null (then a_dec is ignored), else the linear model.  Extra outputs, each may
+// be null: rtt_est[epochs][R] = the proxy's smoothed round trip times, believed_hit[N] = blocks the proxy's
+// index matched on the chosen replica (hit_blocks stays what the replica's cache really held).
+int gorgo_oracle_replay_proxy(int64_t N, const int64_t* ts_ms, const int32_t* in_len, const int32_t* out_len,
+                              const int64_t* blk_off, const int64_t* hash_ids, int32_t block_tokens,
+                              int32_t R, int32_t B, int64_t C, double a_pf, double a_dec,
+                              const double* a_pf_r, const double* a_dec_r, const int64_t* kv_tokens, double slowdown,
+                              int32_t epochs, int32_t probe_ms, const double* rtt_true, double alpha, int32_t stale_index,
+                              const double* w, double scale,
+                              int32_t window, int32_t hop, const double* z,
+                              const double* lo, const double* hi, double sigma0,
+                              uint8_t* route, uint16_t* hit_blocks, double* ttft_ms, double* e2e_ms, double* p95,
+                              double* score_dbg, double* rtt_est, uint16_t* believed_hit,
+                              double* theta_step, double* fitness_step, double* tuner_final) {
+    if (epochs < 1 || probe_ms < 1 || !rtt_true || !(alpha > 0.0) || !(alpha <= 1.0)) return -1;
+    if (a_pf_r && (!a_dec_r || !(slowdown >= 0.0))) return -1;
+    const Engine engine{a_pf_r, a_dec_r, kv_tokens, slowdown};
+    const Proxy proxy{epochs, probe_ms, rtt_true, alpha, stale_index};
+    return replay_impl(N, ts_ms, in_len, out_len, blk_off, hash_ids, block_tokens, R, B, C, a_pf, a_dec, rtt_true, w,
+                       scale, window, hop, nullptr, z, lo, hi, sigma0, 0, 0, a_pf_r ? &engine : nullptr, &proxy, rtt_est,
+                       believed_hit, route, hit_blocks, ttft_ms, e2e_ms, p95, score_dbg, nullptr, nullptr, theta_step,
+                       fitness_step, tuner_final);
 }
 
 // One replay under one fixed weight vector.

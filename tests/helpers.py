@@ -40,12 +40,15 @@ class ForcedRouteModel:
     lowest-index minimum of those scores.  The cache is a recency-ordered Python list (move-to-front,
     evict from the cold end), the in-flight set a plain list scanned at each request: different data
     structures from the oracle's on purpose.  `w` is one weight vector, or one per request (a weight
-    schedule dictated from outside, like the routes).
+    schedule dictated from outside, like the routes).  `proxy` = dict(rtt_true=[epochs][R], probe_ms=, alpha=,
+    stale_index=) switches on imperfect proxy knowledge: round trip times per probe epoch (scored through their
+    moving average), and scores that take their cached prefix from everything ever dispatched to a replica.
     """
 
-    def __init__(self, trace, R, batch, cache_blocks, block_tokens, a_pf, a_dec, rtt, w, scale):
+    def __init__(self, trace, R, batch, cache_blocks, block_tokens, a_pf, a_dec, rtt, w, scale, proxy=None):
         self.tr, self.R, self.B, self.C, self.bt = trace, R, batch, cache_blocks, block_tokens
         self.a_pf, self.a_dec, self.rtt, self.w, self.scale = a_pf, a_dec, list(rtt), list(w), scale
+        self.proxy = proxy
 
     def run(self, routes):
         tr = self.tr
@@ -53,7 +56,14 @@ class ForcedRouteModel:
         free = [[0.0] * self.B for _ in range(self.R)]
         inflight = [[] for _ in range(self.R)]       # (done, tokens)
         consistent = True
-        out = dict(score=[], hit=[], ttft=[], e2e=[], q=[], done=[], cnt=[])
+        out = dict(score=[], hit=[], ttft=[], e2e=[], q=[], done=[], cnt=[], believed=[])
+        px = self.proxy
+        seen = [set() for _ in range(self.R)]        # stale index: everything ever dispatched
+        if px:
+            true = [[float(x) for x in row] for row in px["rtt_true"]]
+            est = [list(true[0])]
+            for e in range(1, len(true)):
+                est.append([px["alpha"] * true[e][i] + (1.0 - px["alpha"]) * est[e - 1][i] for i in range(self.R)])
         for r in range(tr.N):
             ids = [int(x) for x in tr.ids_of(r)]
             L, O = int(tr.in_len[r]), int(tr.out_len[r])
@@ -62,18 +72,30 @@ class ForcedRouteModel:
             for i in range(self.R):
                 inflight[i] = [(d, tok) for (d, tok) in inflight[i] if not d <= t]
                 q.append(sum(tok for _, tok in inflight[i]))
-            scores, us, ms = [], [], []
+            scores, us, ms, seen_ms = [], [], [], []
+            rtt_score, rtt_real = self.rtt, self.rtt
+            if px:
+                e = 0
+                while e + 1 < len(true) and float((e + 1) * px["probe_ms"]) <= t:
+                    e += 1
+                rtt_score, rtt_real = est[e], true[e]
             for i in range(self.R):
                 m = 0
                 while m < len(ids) and ids[m] in lru[i]:
                     m += 1
                 u = L - min(L, self.bt * m)
-                pf = self.a_pf * float(u)
+                ms_seen = m
+                if px and px["stale_index"]:
+                    ms_seen = 0
+                    while ms_seen < len(ids) and ids[ms_seen] in seen[i]:
+                        ms_seen += 1
+                pf = self.a_pf * float(L - min(L, self.bt * ms_seen))
                 qd = self.a_pf * float(q[i])
                 w = self.w[r] if isinstance(self.w[0], (list, tuple, np.ndarray)) else self.w
-                scores.append((w[0] * self.rtt[i] + w[1] * pf) + w[2] * qd)
+                scores.append((w[0] * rtt_score[i] + w[1] * pf) + w[2] * qd)
                 us.append(u)
                 ms.append(m)
+                seen_ms.append(ms_seen)
             best = min(range(self.R), key=lambda i: (scores[i], i))
             i = routes[r]
             if i != best:
@@ -98,7 +120,8 @@ class ForcedRouteModel:
                 if x in lru[i]:
                     lru[i].remove(x)
                 lru[i].append(x)
-            half = 0.5 * self.rtt[i]
+            seen[i].update(ids)
+            half = 0.5 * rtt_real[i]
             a = t + half
             ks = min(range(self.B), key=lambda k: (free[i][k], k))
             s = max(a, free[i][ks])
@@ -109,6 +132,7 @@ class ForcedRouteModel:
             inflight[i].append((done, L))
             out["score"].append(scores)
             out["hit"].append(ms[i])
+            out["believed"].append(seen_ms[i])
             out["ttft"].append((f + half) - t)
             out["e2e"].append(done - t)
             out["q"].append(q)
