@@ -83,7 +83,7 @@ def recorded_counters(kernel, workload_key):
     return rec
 
 
-def cpu_baseline(wl, params, n_req, threads, online=None, engine=None):
+def cpu_baseline(wl, params, n_req, threads, online=None, engine=None, proxy=None):
     """The oracle as it stands, one replay per thread, on the first n_req requests of the workload (with its online
     tuner when `online` = (z[P, steps, 3], lo, hi, sigma0) is given; under the engine model of a replica when
     `engine` = its parameters is given)."""
@@ -91,6 +91,18 @@ def cpu_baseline(wl, params, n_req, threads, online=None, engine=None):
     from oracle import binding as ob
     tr = wl.trace.head(n_req)
     ob.lib()
+    if proxy is not None:
+        def one_proxy(p):
+            return ob.replay_proxy(tr, R=wl.R, batch=wl.batch, cache_blocks=wl.cache_blocks,
+                                   prefill_ms_per_token=wl.prefill_ms_per_token,
+                                   decode_ms_per_token=wl.decode_ms_per_token, rtt_true=proxy.rtt_true_ms,
+                                   probe_ms=proxy.probe_interval_ms, alpha=proxy.ewma_alpha,
+                                   stale_index=proxy.stale_index, w=params[p], scale=1.0).p95_ttft_ms
+        t0 = time.perf_counter()
+        with ThreadPoolExecutor(threads) as ex:
+            list(ex.map(one_proxy, range(threads)))
+        dt = time.perf_counter() - t0
+        return threads * tr.N / dt, dt, tr.N
     if engine is not None:
         def one_engine(p):
             return ob.replay_engine(tr, R=wl.R, batch=wl.batch, cache_blocks=wl.cache_blocks,
@@ -181,9 +193,13 @@ def main():
                     help="replicas follow the engine model (continuous batching with a KV-token budget, decode slow-down, "
                          "uneven rates: synth.tracegen.engine_recipe) instead of the linear one; a step is still one ES "
                          "generation -- not the headline metric")
+    ap.add_argument("--proxy", action="store_true",
+                    help="the proxy knows the replicas imperfectly (true round trip times wander per 30 s probe epoch and are "
+                         "scored through their moving average; its cache index never forgets: synth.tracegen.rtt_walk); "
+                         "a step is still one ES generation -- not the headline metric")
     args = ap.parse_args()
-    if args.engine and args.online:
-        sys.exit("bench.py: --engine and --online are separate runs")
+    if args.engine + args.online + args.proxy > 1:
+        sys.exit("bench.py: --engine, --online and --proxy are separate runs")
     if args.gpus != 1:
         sys.exit("bench.py: this build evaluates on ONE GPU (replays are independent and would shard by candidate; "
                  "no multi-GPU path is built) -- run with --gpus 1")
@@ -203,7 +219,7 @@ def main():
     N = tr.N
     model = g.Model(wl.R, wl.batch, wl.cache_blocks, wl.prefill_ms_per_token, wl.decode_ms_per_token)
     state = g.es_init(es_cfg["seed"])
-    ws_bytes = g.workspace_bytes(tr, model, P) if args.online or args.engine else g.es_workspace_bytes(tr, model, P)
+    ws_bytes = g.workspace_bytes(tr, model, P) if args.online or args.engine or args.proxy else g.es_workspace_bytes(tr, model, P)
     ws = torch.empty((ws_bytes,), dtype=torch.uint8, device="cuda:0")
     print(f"[bench] workload {wl.name}: R={wl.R} N={N} P={P} C={wl.cache_blocks} mean blocks/request "
           f"{np.diff(wl.trace.blk_off).mean():.1f}; workspace {ws.numel() / 2**30:.1f} GiB; setup "
@@ -219,7 +235,17 @@ def main():
         engine = g.Engine(recipe["prefill_ms_per_token"], recipe["decode_ms_per_token"], recipe["kv_tokens"],
                           recipe["slowdown"])
 
+    if args.proxy:
+        epochs = int(float(wl.trace.ts_ms[-1]) // 30000) + 1 if N else 1
+        proxy = g.Proxy(tg.rtt_walk(wl, epochs), 30000, 0.3, True)
+
     def generation():
+        if args.proxy:
+            par = g.es_propose(state, g.es_sample(state.seed, state.generation, P))
+            res = g.eval_proxy(tr, model, proxy, par, 1.0, per_request=False, workspace=ws)
+            fit = res.p95_ttft_ms.cpu().numpy()
+            g.es_update(state, par, fit)
+            return par, fit, g.last_eval_kernel_ms()
         if args.engine:
             # the generation loop of gorgo_es_step spelled out, with the engine model's evaluation in the middle
             par = g.es_propose(state, g.es_sample(state.seed, state.generation, P))
@@ -281,7 +307,7 @@ def main():
         bpr = algorithmic_bytes_per_routing(wl.R, n_mean, hit_mean, outputs_bytes=9)
         kernel = "replay_blocks_kernel"
     k_ms = float(np.mean(kernel_ms))
-    counters = None if args.online or args.engine else recorded_counters(kernel, f"config-{args.config} N={N} P={P}")
+    counters = None if args.online or args.engine or args.proxy else recorded_counters(kernel, f"config-{args.config} N={N} P={P}")
     traffic = counters["fetch_bytes_per_launch"] + counters["write_bytes_per_launch"] if counters else None
     achieved = bpr * P * N / (k_ms * 1e-3) / 1e9
     # The replay is one dependent chain per candidate: what limits it is the rate at which a SIMD issues the
@@ -301,9 +327,12 @@ def main():
         "one ES generation per step (eval + p95 TTFT fitness + mean update)"
     if args.engine:
         mode += ", replicas under the engine model (uneven rates, KV-token budget, decode slow-down)"
+    if args.proxy:
+        mode += ", imperfect proxy knowledge (RTT random walk per 30 s epoch scored through an EWMA with alpha 0.3, stale index)"
     out = {
         "metric": "candidate-request routings/sec at P=1024" + (" (online tuner)" if args.online else "") +
-                  (" (engine model of a replica)" if args.engine else ""),
+                  (" (engine model of a replica)" if args.engine else "") +
+                  (" (imperfect proxy knowledge)" if args.proxy else ""),
         "value": value, "unit": "routings/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f64", "data": "synthetic",
@@ -322,7 +351,7 @@ def main():
         cores = min(len(os.sched_getaffinity(0)), 16)
         on = (z_on[:cores].cpu().numpy(), list(state.lo[:]), list(state.hi[:]), state.sigma) if args.online else None
         v, dt, n_s = cpu_baseline(wl, theta0 if args.online else par, min(args.cpu_sample_requests, N), cores, on,
-                                  recipe if args.engine else None)
+                                  recipe if args.engine else None, proxy if args.proxy else None)
         out["cpu_baseline"] = {"value": v, "unit": "routings/s", "cores": cores, "kind": "oracle",
                                "sample": f"{cores} replays (one per thread) x first {n_s} requests of the same trace, "
                                          f"{dt:.1f}s wall"}

@@ -271,6 +271,42 @@ int gorgo_eval_engine(const gorgo_trace* t, const gorgo_model* m, const gorgo_en
                       const double* scale, int32_t P, const gorgo_outputs* outputs, void* workspace,
                       size_t workspace_bytes, void* hip_stream);
 
+/* ------------------------------------------------------------------------- imperfect proxy knowledge
+ * What the proxy of the paper knows only approximately.  (1) Round trip times: T_network is the exponentially
+ * weighted moving average of a ping's round trip time (Sec. 2.2), measured at fixed intervals on a separate probe
+ * (Sec. 4, RTT figure: every 30 s).  (2) Cached prefixes: the proxy does not observe replica-side eviction, so its
+ * cache index may overestimate what a replica holds (Sec. 7).  The paper gives neither the smoothing constant nor
+ * the index's own forgetting rule.  Stated model:
+ *   - time is cut into epochs of probe_interval_ms: the epoch of time t (= timestamp * scale) is the largest e with
+ *     e * probe_interval_ms <= t, capped at epochs - 1; a request dispatched in epoch e experiences the round trip
+ *     time rtt_true_ms[e][i] on replica i (half of it each way);
+ *   - the proxy probes at the start of every epoch: est[0] = rtt_true_ms[0], est[e] = ewma_alpha * rtt_true_ms[e]
+ *     + (1 - ewma_alpha) * est[e-1]; Eq. 3 scores with est of the request's epoch;
+ *   - stale_index = 1: Eq. 3 takes the uncached tokens of replica i from the longest prefix of the request that
+ *     was ever dispatched to i (a prefix trie of dispatched requests that never forgets), while the replica
+ *     prefills what its own bounded LRU cache really misses; hit_blocks stays the real count.
+ * With one epoch (or equal rows) and stale_index = 0 the results equal gorgo_eval_population's bit for bit.
+ * Needs a chain-consistent trace. */
+typedef struct gorgo_proxy {
+    int32_t epochs;               /* 1..65536 probe epochs given                                              */
+    int32_t probe_interval_ms;    /* >= 1                                                                     */
+    const double* rtt_true_ms;    /* host [epochs][R], finite, 0..1e9                                         */
+    double ewma_alpha;            /* in (0, 1]                                                                */
+    int32_t stale_index;          /* 0 or 1                                                                   */
+    int32_t _pad;
+    double* rtt_tables;           /* DEVICE [2][epochs][R], caller-owned, written: [0] a copy of rtt_true_ms,
+                                     [1] the proxy's estimates; must stay valid until the stream has run      */
+    uint16_t* believed_hit_blocks;/* DEVICE [P][N] or NULL: blocks Eq. 3 took for cached on the chosen replica */
+} gorgo_proxy;
+
+/* Evaluate P replays with imperfect proxy knowledge.  engine may be NULL (linear model) or an engine model as in
+ * gorgo_eval_engine; online may be NULL (fixed weights params, host [P][3]) or an online tuner as in
+ * gorgo_eval_online (params are then the initial weights).  The round trip times come from proxy->rtt_true_ms.
+ * Everything else (outputs, workspace and its size, stream, errors) as gorgo_eval_population. */
+int gorgo_eval_proxy(const gorgo_trace* t, const gorgo_model* m, const gorgo_proxy* proxy, const gorgo_engine* engine,
+                     const double* params, const gorgo_online* online, const double* scale, int32_t P,
+                     const gorgo_outputs* outputs, void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* ------------------------------------------------------------------------------------------------ misc
  * Device time (ms, HIP events recorded on the evaluation's stream) of the three stages of the most recent
  * gorgo_eval_population / gorgo_es_step issued by the calling thread: state initialisation, the replay

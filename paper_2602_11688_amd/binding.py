@@ -42,6 +42,12 @@ class _Engine(C.Structure):
                 ("decode_slowdown", C.c_double)]
 
 
+class _Proxy(C.Structure):
+    _fields_ = [("epochs", C.c_int32), ("probe_interval_ms", C.c_int32), ("rtt_true_ms", C.c_void_p),
+                ("ewma_alpha", C.c_double), ("stale_index", C.c_int32), ("_pad", C.c_int32), ("rtt_tables", C.c_void_p),
+                ("believed_hit_blocks", C.c_void_p)]
+
+
 class EsState(C.Structure):
     _fields_ = [("theta", C.c_double * 3), ("sigma", C.c_double), ("lo", C.c_double * 3), ("hi", C.c_double * 3),
                 ("seed", C.c_uint64), ("generation", C.c_int64), ("best_fitness", C.c_double),
@@ -77,6 +83,8 @@ def lib():
         L.gorgo_eval_policy.argtypes = [vp, C.POINTER(_Model), vp, i32, vp, vp, i32, C.POINTER(_Outputs), vp, C.c_size_t, vp]
         L.gorgo_eval_engine.argtypes = [vp, C.POINTER(_Model), C.POINTER(_Engine), vp, i32, vp, vp, C.POINTER(_Online), vp,
                                         i32, C.POINTER(_Outputs), vp, C.c_size_t, vp]
+        L.gorgo_eval_proxy.argtypes = [vp, C.POINTER(_Model), C.POINTER(_Proxy), C.POINTER(_Engine), vp, C.POINTER(_Online),
+                                       vp, i32, C.POINTER(_Outputs), vp, C.c_size_t, vp]
         L.gorgo_es_init.argtypes = [C.POINTER(EsState), C.c_uint64]
         L.gorgo_es_sample.argtypes = [C.c_uint64, i64, i32, vp]
         L.gorgo_philox4x32_10.argtypes = [vp, vp, vp]
@@ -91,7 +99,7 @@ def lib():
         L.gorgo_query_replay_path.argtypes = [vp, C.POINTER(i32), C.POINTER(i64), C.POINTER(i64)]
         L.gorgo_last_eval_kernel_ms.argtypes = [C.POINTER(dbl)] * 3
         for name in ("gorgo_load_trace", "gorgo_load_trace_arrays", "gorgo_trace_info", "gorgo_workspace_bytes",
-                     "gorgo_eval_population", "gorgo_eval_online", "gorgo_eval_policy", "gorgo_eval_engine", "gorgo_es_init", "gorgo_es_sample", "gorgo_es_propose",
+                     "gorgo_eval_population", "gorgo_eval_online", "gorgo_eval_policy", "gorgo_eval_engine", "gorgo_eval_proxy", "gorgo_es_init", "gorgo_es_sample", "gorgo_es_propose",
                      "gorgo_es_update", "gorgo_es_workspace_bytes", "gorgo_es_step", "gorgo_set_table_factor_percent",
                      "gorgo_last_eval_kernel_ms", "gorgo_set_replay_path", "gorgo_set_handover_poll_limit", "gorgo_query_replay_path"):
             getattr(L, name).restype = C.c_int
@@ -230,6 +238,10 @@ class EvalResult:
     sigma_final: object = None      # [P]
     accepted: object = None         # [P] int32
     _z: object = None
+    # imperfect proxy knowledge (eval_proxy only)
+    rtt_est_ms: object = None           # [epochs, R] the proxy's smoothed round trip times
+    believed_hit_blocks: object = None  # [P, N] uint16 blocks Eq. 3 took for cached on the chosen replica
+    _tables: object = None
 
 
 def eval_population(trace: Trace, model: Model, rtt_ms, params, scale, *, per_request: bool = True,
@@ -448,6 +460,92 @@ def eval_engine(trace: Trace, model: Model, engine: Engine, rtt_ms, scale, *, pa
         _check(lib().gorgo_eval_engine(trace._h, C.byref(m), C.byref(eng), _ptr(rtt), code, _ptr(par), _ptr(sd),
                                        None if on is None else C.byref(on), _ptr(sc), P, C.byref(o),
                                        C.c_void_p(workspace.data_ptr()), workspace.numel(), C.c_void_p(s.cuda_stream)))
+    return res
+
+
+@dataclass
+class Proxy:
+    """Imperfect proxy knowledge (gorgo_proxy): true round trip times per probe epoch [epochs, R], the probe
+    interval, the smoothing constant of the proxy's moving average, and whether its cache index never forgets."""
+    rtt_true_ms: Sequence[Sequence[float]]
+    probe_interval_ms: int = 30000
+    ewma_alpha: float = 0.5
+    stale_index: bool = False
+
+
+def eval_proxy(trace: Trace, model: Model, proxy: Proxy, params, scale, *, engine: Optional[Engine] = None,
+               online: Optional[dict] = None, per_request: bool = True, p95: bool = True, workspace=None, stream=None,
+               device="cuda:0") -> EvalResult:
+    """gorgo_eval_proxy with torch-allocated outputs: P replays under weights params [P,3] (tuned online when
+    online = dict(z=, lo=, hi=, sigma0=, window=, hop=) is given) with imperfect proxy knowledge; replicas follow the
+    engine model when `engine` is given, else the linear one."""
+    import torch
+    par = _np(params, np.float64)
+    P = par.shape[0]
+    if par.shape != (P, 3):
+        raise ValueError("params must be [P,3]")
+    sc = _np(np.broadcast_to(np.asarray(scale, dtype=np.float64), (P,)), np.float64)
+    rt = _np(proxy.rtt_true_ms, np.float64)
+    if rt.ndim != 2 or rt.shape[1] != model.R or rt.shape[0] < 1:
+        raise ValueError("rtt_true_ms must be [epochs, R]")
+    E = rt.shape[0]
+    N = trace.N
+    dev = torch.device(device)
+    res = EvalResult()
+    if per_request:
+        res.route = torch.empty((P, N), dtype=torch.uint8, device=dev)
+        res.hit_blocks = torch.empty((P, N), dtype=torch.uint16, device=dev)
+        res.believed_hit_blocks = torch.empty((P, N), dtype=torch.uint16, device=dev)
+        res.ttft_ms = torch.empty((P, N), dtype=torch.float64, device=dev)
+        res.e2e_ms = torch.empty((P, N), dtype=torch.float64, device=dev)
+    if p95:
+        res.p95_ttft_ms = torch.empty((P,), dtype=torch.float64, device=dev)
+        res.p95_e2e_ms = torch.empty((P,), dtype=torch.float64, device=dev)
+    tables = torch.empty((2, E, model.R), dtype=torch.float64, device=dev)
+    res.rtt_est_ms = tables[1]
+    px = _Proxy(E, int(proxy.probe_interval_ms), _ptr(rt), float(proxy.ewma_alpha), int(bool(proxy.stale_index)), 0,
+                C.c_void_p(tables.data_ptr()),
+                None if res.believed_hit_blocks is None else C.c_void_p(res.believed_hit_blocks.data_ptr()))
+    eng = None
+    if engine is not None:
+        a_pf = _np(engine.prefill_ms_per_token, np.float64)
+        a_dec = _np(engine.decode_ms_per_token, np.float64)
+        kv = None if engine.kv_tokens is None else _np(engine.kv_tokens, np.int64)
+        if a_pf.shape != (model.R,) or a_dec.shape != (model.R,) or (kv is not None and kv.shape != (model.R,)):
+            raise ValueError("the engine's rates and budgets must be [R]")
+        eng = _Engine(_ptr(a_pf), _ptr(a_dec), _ptr(kv), float(engine.decode_slowdown))
+    on = None
+    if online is not None:
+        window, hop = int(online.get("window", 128)), int(online.get("hop", 32))
+        steps = online_steps(N, window, hop)
+        z = online["z"]
+        zt = z if isinstance(z, torch.Tensor) else torch.from_numpy(_np(z, np.float64))
+        zt = zt.to(device=dev, dtype=torch.float64).contiguous()
+        if tuple(zt.shape) != (P, steps, 3):
+            raise ValueError(f"z must be [P, {steps}, 3]")
+        res.theta_step = torch.empty((P, steps, 3), dtype=torch.float64, device=dev)
+        res.fitness_step = torch.empty((P, steps), dtype=torch.float64, device=dev)
+        res.theta_final = torch.empty((P, 3), dtype=torch.float64, device=dev)
+        res.sigma_final = torch.empty((P,), dtype=torch.float64, device=dev)
+        res.accepted = torch.empty((P,), dtype=torch.int32, device=dev)
+        res._z = zt
+        on = _Online(window, hop, (C.c_double * 3)(*[float(x) for x in online["lo"]]),
+                     (C.c_double * 3)(*[float(x) for x in online["hi"]]), float(online["sigma0"]),
+                     C.c_void_p(zt.data_ptr()), C.c_void_p(res.theta_step.data_ptr()),
+                     C.c_void_p(res.fitness_step.data_ptr()), C.c_void_p(res.theta_final.data_ptr()),
+                     C.c_void_p(res.sigma_final.data_ptr()), C.c_void_p(res.accepted.data_ptr()))
+    o = _outputs_struct(res.route, res.hit_blocks, res.ttft_ms, res.e2e_ms, res.p95_ttft_ms, res.p95_e2e_ms)
+    need = workspace_bytes(trace, model, P, o)
+    if workspace is None or workspace.numel() < need:
+        workspace = torch.empty((need,), dtype=torch.uint8, device=dev)
+    res.workspace = workspace
+    s = stream if stream is not None else torch.cuda.current_stream(dev)
+    m = model.c()
+    with torch.cuda.device(dev):
+        _check(lib().gorgo_eval_proxy(trace._h, C.byref(m), C.byref(px), None if eng is None else C.byref(eng), _ptr(par),
+                                      None if on is None else C.byref(on), _ptr(sc), P, C.byref(o),
+                                      C.c_void_p(workspace.data_ptr()), workspace.numel(), C.c_void_p(s.cuda_stream)))
+    res._tables = tables
     return res
 
 

@@ -160,9 +160,22 @@ namespace {
 int evaluate(const gorgo_trace* t, const gorgo_model* m, const double* rtt_ms, const double* params,
              const double* scale, int32_t P, const gorgo_online* online, int32_t policy, const uint64_t* seeds,
              const gorgo_outputs* outputs, void* workspace, size_t workspace_bytes, void* hip_stream,
-             const gorgo_engine* engine = nullptr) {
+             const gorgo_engine* engine = nullptr, const gorgo_proxy* proxy = nullptr) {
     int rc = check_model(t, m);
     if (rc) return rc;
+    if (proxy) {
+        if (proxy->epochs < 1 || proxy->epochs > 65536) return fail(GORGO_ERR_INVALID_ARG, "epochs must be in 1..65536");
+        if (proxy->probe_interval_ms < 1) return fail(GORGO_ERR_INVALID_ARG, "probe_interval_ms must be >= 1");
+        if (!proxy->rtt_true_ms || !proxy->rtt_tables) return fail(GORGO_ERR_INVALID_ARG, "the proxy's round trip time tables are NULL");
+        if (!(proxy->ewma_alpha > 0.0) || !(proxy->ewma_alpha <= 1.0))
+            return fail(GORGO_ERR_NONFINITE, "ewma_alpha must be in (0, 1]");
+        if (proxy->stale_index != 0 && proxy->stale_index != 1) return fail(GORGO_ERR_INVALID_ARG, "stale_index must be 0 or 1");
+        for (int64_t j = 0; j < (int64_t)proxy->epochs * m->R; ++j)
+            if (!std::isfinite(proxy->rtt_true_ms[j]) || proxy->rtt_true_ms[j] < 0 || proxy->rtt_true_ms[j] > 1e9)
+                return fail(GORGO_ERR_NONFINITE, "rtt_true_ms[" + std::to_string(j / m->R) + "][" + std::to_string(j % m->R) +
+                                                     "] must be finite and in 0..1e9");
+        rtt_ms = proxy->rtt_true_ms;      // (its first row stands in where a single row is copied below)
+    }
     std::vector<double> eng;        // a_pf[R], a_dec[R], budget[R]
     if (engine) {
         if (!engine->prefill_ms_per_token || !engine->decode_ms_per_token)
@@ -201,6 +214,8 @@ int evaluate(const gorgo_trace* t, const gorgo_model* m, const double* rtt_ms, c
         return fail(GORGO_ERR_INVALID_ARG, "the baseline policies need a chain-consistent trace (segment formulation)");
     if (engine && pl.path != PATH_SEGMENTS)
         return fail(GORGO_ERR_INVALID_ARG, "the engine model needs a chain-consistent trace (segment formulation)");
+    if (proxy && pl.path != PATH_SEGMENTS)
+        return fail(GORGO_ERR_INVALID_ARG, "imperfect proxy knowledge needs a chain-consistent trace (segment formulation)");
     std::vector<double> tuner;      // constants, then ln theta0[P][3]
     int64_t steps = 0;
     if (online) {
@@ -257,6 +272,19 @@ int evaluate(const gorgo_trace* t, const gorgo_model* m, const double* rtt_ms, c
         el.budget = d_eng + 2 * (size_t)pl.R;
         el.slowdown = engine->decode_slowdown;
     }
+    ProxyLaunch xl;
+    if (proxy) {
+        const size_t cells = (size_t)proxy->epochs * pl.R;
+        if ((rc = copy_small_to_device(proxy->rtt_tables, proxy->rtt_true_ms, sizeof(double) * cells, hip_stream))) return rc;
+        if ((rc = wait_for_copies(hip_stream))) return rc;       // (the caller's host table may go away)
+        xl.epochs = proxy->epochs;
+        xl.probe_ms = proxy->probe_interval_ms;
+        xl.rtt_true = proxy->rtt_tables;
+        xl.rtt_est = proxy->rtt_tables + cells;
+        xl.alpha = proxy->ewma_alpha;
+        xl.stale_index = proxy->stale_index;
+        xl.believed = proxy->believed_hit_blocks;
+    }
     PolicyLaunch pol;
     pol.policy = policy;
     if (policy == GORGO_POLICY_RANDOM) {
@@ -293,7 +321,7 @@ int evaluate(const gorgo_trace* t, const gorgo_model* m, const double* rtt_ms, c
     double* e2e = outputs->e2e_ms;
     if (!e2e && outputs->p95_e2e_ms) e2e = reinterpret_cast<double*>(ws + pl.off_e2e);
     rc = launch_replay(t, pl, d_rtt, d_params, d_scale, route, outputs->hit_blocks, ttft, e2e, workspace, hip_stream,
-                       online ? &ol : nullptr, policy != 0 ? &pol : nullptr, engine ? &el : nullptr);
+                       online ? &ol : nullptr, policy != 0 ? &pol : nullptr, engine ? &el : nullptr, proxy ? &xl : nullptr);
     if (rc) return rc;
     if (outputs->p95_ttft_ms && (rc = launch_p95(ttft, pl.N, P, outputs->p95_ttft_ms, hip_stream))) return rc;
     if (outputs->p95_e2e_ms && (rc = launch_p95(e2e, pl.N, P, outputs->p95_e2e_ms, hip_stream))) return rc;
@@ -356,6 +384,16 @@ int gorgo_eval_engine(const gorgo_trace* t, const gorgo_model* m, const gorgo_en
     const std::vector<double> zero(3 * (size_t)P, 0.0);       // the weights play no part
     return evaluate(t, m, rtt_ms, zero.data(), scale, P, nullptr, policy, seeds, outputs, workspace, workspace_bytes,
                     hip_stream, engine);
+}
+
+int gorgo_eval_proxy(const gorgo_trace* t, const gorgo_model* m, const gorgo_proxy* proxy, const gorgo_engine* engine,
+                     const double* params, const gorgo_online* online, const double* scale, int32_t P,
+                     const gorgo_outputs* outputs, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    clear_error();
+    if (!proxy) return fail(GORGO_ERR_INVALID_ARG, "proxy is NULL");
+    if (!m) return fail(GORGO_ERR_INVALID_ARG, "model is NULL");
+    return evaluate(t, m, proxy->rtt_true_ms, params, scale, P, online, 0, nullptr, outputs, workspace, workspace_bytes,
+                    hip_stream, engine, proxy);
 }
 
 int gorgo_last_eval_kernel_ms(double* fill_ms, double* replay_ms, double* select_ms) {

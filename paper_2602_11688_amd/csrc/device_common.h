@@ -183,12 +183,61 @@ struct Queues {
         }
     }
 
+    // The completion times along a slot's in-flight list increase as long as a replica's round trip time is
+    // constant.  When it changes between dispatches (probe epochs), a request can complete at the proxy before one
+    // dispatched earlier on the same slot; the list is then kept sorted by completion time instead: this inserts
+    // request r (completion `done`, `tok` tokens) into the list of slot s = base + k, which holds d >= 1 requests
+    // the last of which completes after `done`.  An element that has to leave the two LDS positions moves into
+    // the record of request r, which r itself does not need then.  tail[s] stays the record of the last element.
+    __device__ void insert_sorted(int s, int k, int d, int64_t r, double done, int32_t tok, Rec* rec) {
+        if (done < h_done[s] || (d >= 2 && done < s_done[s])) {
+            // r goes into LDS; the element in second position, if any, moves to global memory behind it
+            if (d >= 2) {
+                st(&rec[r].done, s_done[s]);
+                st(&rec[r].tokens, s_tok[s]);
+                st(&rec[r].next, d >= 3 ? s_next[s] : (int32_t)-1);
+                s_next[s] = (int32_t)r;
+                if (d == 2) tail[s] = (int32_t)r;
+            } else {
+                s_next[s] = -1;
+            }
+            if (done < h_done[s]) {
+                s_done[s] = h_done[s];
+                s_tok[s] = h_tok[s];
+                h_done[s] = done;
+                h_tok[s] = tok;
+                if (done < my_min) {
+                    my_min = done;
+                    my_min_k = k;
+                }
+            } else {
+                s_done[s] = done;
+                s_tok[s] = tok;
+            }
+        } else {
+            // r goes between two elements further down (d >= 3): walk to the last one that completes no later
+            int32_t prev = -1;               // -1: the second position
+            int32_t x = s_next[s];
+            for (int steps = 0; steps < d && x >= 0 && !(done < ld(&rec[x].done)); ++steps) {
+                prev = x;
+                x = ld(&rec[x].next);
+            }
+            st(&rec[r].done, done);
+            st(&rec[r].tokens, tok);
+            st(&rec[r].next, x);
+            if (prev < 0) s_next[s] = (int32_t)r;
+            else st(&rec[prev].next, (int32_t)r);
+        }
+        depth[s] = d + 1;
+    }
+
     // Service of request r on replica `best` (the stated linear model; reproduces Eq. 1: ttft = rtt + wait +
     // prefill) on the earliest-free slot.  Which of several free slots takes the request changes no latency
     // and no load signal: a slot with nothing in flight has seen its completion event reach the proxy, so it
     // has been free since before any later arrival at the replica, exactly like the earliest-free one.  The
     // slots are therefore only searched for their earliest free time (lowest index on ties) when every slot
     // still has a request in flight.  The chosen replica's lane works, its latencies are broadcast.
+    template <bool REORDER>
     __device__ void serve(int64_t r, int best, double t, double rtt_mine, int64_t uncached_mine, int64_t L, int64_t O,
                           double a_pf, double a_dec, Rec* rec, int lane, double* ttft_out, double* e2e_out) {
         double ttft = 0.0, e2e = 0.0;
@@ -229,27 +278,32 @@ struct Queues {
                 h_done[s] = done;
                 h_tok[s] = (int32_t)L;
                 depth[s] = 1;
+                tail[s] = (int32_t)r;
                 if (done < my_min) {
                     my_min = done;
                     my_min_k = k;
                 }
             } else {
                 const int d = depth[s];         // at least 1
-                if (d == 1) {
-                    s_done[s] = done;
-                    s_tok[s] = (int32_t)L;
-                    s_next[s] = -1;
+                if (REORDER && done < (d == 1 ? h_done[s] : (d == 2 ? s_done[s] : ld(&rec[tail[s]].done)))) {
+                    insert_sorted(s, k, d, r, done, (int32_t)L, rec);
                 } else {
-                    // third or deeper: goes to global memory, linked behind the youngest
-                    st(&rec[r].done, done);
-                    st(&rec[r].next, (int32_t)-1);
-                    st(&rec[r].tokens, (int32_t)L);
-                    if (d == 2) s_next[s] = (int32_t)r;
-                    else st(&rec[tail[s]].next, (int32_t)r);
+                    if (d == 1) {
+                        s_done[s] = done;
+                        s_tok[s] = (int32_t)L;
+                        s_next[s] = -1;
+                    } else {
+                        // third or deeper: goes to global memory, linked behind the youngest
+                        st(&rec[r].done, done);
+                        st(&rec[r].next, (int32_t)-1);
+                        st(&rec[r].tokens, (int32_t)L);
+                        if (d == 2) s_next[s] = (int32_t)r;
+                        else st(&rec[tail[s]].next, (int32_t)r);
+                    }
+                    depth[s] = d + 1;
+                    tail[s] = (int32_t)r;
                 }
-                depth[s] = d + 1;
             }
-            tail[s] = (int32_t)r;
             my_q += (double)L;
             my_cnt += 1.0;
         }
@@ -267,6 +321,7 @@ struct Queues {
     // tokens up and finds the next time one ends; the scan is repeated from that time until the request fits
     // (at most B times: each repeat has one request fewer running).  The request takes the lowest slot that is
     // free at s; its record joins that slot's in-flight list, whose completion times still increase.
+    template <bool REORDER>
     __device__ void serve_engine(int64_t r, int best, double t, double rtt_mine, int64_t uncached_mine, int64_t L,
                                  int64_t O, double a_pf_mine, double a_dec_mine, double budget_mine, double slowdown,
                                  Rec* rec, int lane, double* ttft_out, double* e2e_out) {
@@ -325,22 +380,27 @@ struct Queues {
                     my_min = done;
                     my_min_k = k;
                 }
+                tail[s] = (int32_t)r;
             } else {
                 const int d = depth[s];         // at least 1
-                if (d == 1) {
-                    s_done[s] = done;
-                    s_tok[s] = (int32_t)L;
-                    s_next[s] = -1;
+                if (REORDER && done < (d == 1 ? h_done[s] : (d == 2 ? s_done[s] : ld(&rec[tail[s]].done)))) {
+                    insert_sorted(s, k, d, r, done, (int32_t)L, rec);
                 } else {
-                    st(&rec[r].done, done);
-                    st(&rec[r].next, (int32_t)-1);
-                    st(&rec[r].tokens, (int32_t)L);
-                    if (d == 2) s_next[s] = (int32_t)r;
-                    else st(&rec[tail[s]].next, (int32_t)r);
+                    if (d == 1) {
+                        s_done[s] = done;
+                        s_tok[s] = (int32_t)L;
+                        s_next[s] = -1;
+                    } else {
+                        st(&rec[r].done, done);
+                        st(&rec[r].next, (int32_t)-1);
+                        st(&rec[r].tokens, (int32_t)L);
+                        if (d == 2) s_next[s] = (int32_t)r;
+                        else st(&rec[tail[s]].next, (int32_t)r);
+                    }
+                    depth[s] = d + 1;
+                    tail[s] = (int32_t)r;
                 }
-                depth[s] = d + 1;
             }
-            tail[s] = (int32_t)r;
             my_q += (double)L;
             my_cnt += 1.0;
         }

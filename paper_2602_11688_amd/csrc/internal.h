@@ -105,12 +105,23 @@ struct EngineLaunch {
     double slowdown = 0.0;
 };
 
+// Imperfect proxy knowledge of one launch (device pointers; see gorgo_proxy in gorgo.h).
+struct ProxyLaunch {
+    int32_t epochs = 0, probe_ms = 0;
+    const double* rtt_true = nullptr;    // [epochs][R]
+    double* rtt_est = nullptr;           // [epochs][R], written by the launch before the replay
+    double alpha = 1.0;
+    int32_t stale_index = 0;
+    uint16_t* believed = nullptr;        // [P][N], nullable
+};
+
 // kernels.hip
 void set_handover_poll_limit(int32_t polls);
 int launch_replay(const gorgo_trace* t, const Plan& pl, const double* d_rtt, const double* d_params,
                   const double* d_scale, uint8_t* route, uint16_t* hit, double* ttft, double* e2e,
                   void* workspace, void* stream, const OnlineLaunch* online = nullptr,
-                  const PolicyLaunch* policy = nullptr, const EngineLaunch* engine = nullptr);
+                  const PolicyLaunch* policy = nullptr, const EngineLaunch* engine = nullptr,
+                  const ProxyLaunch* proxy = nullptr);
 int launch_p95(const double* x, int64_t N, int32_t P, double* out, void* stream);
 int last_eval_kernel_ms(double* fill_ms, double* replay_ms, double* select_ms);
 int upload_trace(const gorgo_trace* t);

@@ -306,7 +306,7 @@ __global__ void __launch_bounds__(WAVE) replay_blocks_kernel(ReplayArgs a) {
 
         // ---- service on the chosen replica, outputs
         double ttft, e2e;
-        Q.serve(r, best, t, my_rtt, my_u, L, O, a.a_pf, a.a_dec, rec, lane, &ttft, &e2e);
+        Q.serve<false>(r, best, t, my_rtt, my_u, L, O, a.a_pf, a.a_dec, rec, lane, &ttft, &e2e);
         if (lane == 0) {
             if (a.hit) a.hit[(size_t)p * N + r] = (uint16_t)m_best;
             if (a.ttft) a.ttft[(size_t)p * N + r] = ttft;
@@ -490,10 +490,30 @@ int copy_small_to_host_sync(void* dst, const void* src, size_t bytes, void* stre
     return e == hipSuccess ? GORGO_OK : hip_fail(e, "hipStreamSynchronize");
 }
 
+namespace {
+
+// The proxy's smoothed round trip times (Sec. 2.2: an exponentially weighted moving average of pings), one
+// thread per replica: est[0] = x[0], est[e] = alpha x[e] + (1 - alpha) est[e-1], each product and sum rounded
+// on its own.
+__global__ void smooth_rtt(const double* x, double* est, int epochs, int R, double alpha) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= R) return;
+    double prev = x[i];
+    est[i] = prev;
+    for (int e = 1; e < epochs; ++e) {
+        const double fresh = alpha * x[(size_t)e * R + i];
+        const double kept = (1.0 - alpha) * prev;
+        prev = fresh + kept;
+        est[(size_t)e * R + i] = prev;
+    }
+}
+
+}  // namespace
+
 int launch_replay(const gorgo_trace* t, const Plan& pl, const double* d_rtt, const double* d_params,
                   const double* d_scale, uint8_t* route, uint16_t* hit, double* ttft, double* e2e,
                   void* workspace, void* stream, const OnlineLaunch* online, const PolicyLaunch* policy,
-                  const EngineLaunch* engine) {
+                  const EngineLaunch* engine, const ProxyLaunch* proxy) {
     hipStream_t s = static_cast<hipStream_t>(stream);
     char* ws = static_cast<char*>(workspace);
     g_marks.valid = false;
@@ -537,6 +557,19 @@ int launch_replay(const gorgo_trace* t, const Plan& pl, const double* d_rtt, con
         a.eng_a_dec = engine ? engine->a_dec : nullptr;
         a.eng_budget = engine ? engine->budget : nullptr;
         a.eng_slowdown = engine ? engine->slowdown : 0.0;
+        a.epochs = proxy ? proxy->epochs : 0;
+        a.probe_ms = proxy ? proxy->probe_ms : 0;
+        a.rtt_true = proxy ? proxy->rtt_true : nullptr;
+        a.rtt_est = proxy ? proxy->rtt_est : nullptr;
+        a.stale_index = proxy ? proxy->stale_index : 0;
+        a.believed = proxy ? proxy->believed : nullptr;
+        if (proxy) {
+            if (policy && policy->policy != 0)
+                return fail(GORGO_ERR_INVALID_ARG, "imperfect proxy knowledge concerns the cost model, not the baseline policies");
+            hipLaunchKernelGGL(smooth_rtt, dim3(1), dim3(WAVE), 0, s, proxy->rtt_true, proxy->rtt_est, proxy->epochs, pl.R,
+                               proxy->alpha);
+            if ((e = hipGetLastError()) != hipSuccess) return hip_fail(e, "launch smooth_rtt");
+        }
         const size_t cells = (size_t)pl.P * (size_t)a.nseg * pl.R;
         if (cells) {
             size_t blocks = (cells + 255) / 256;
@@ -560,33 +593,40 @@ int launch_replay(const gorgo_trace* t, const Plan& pl, const double* d_rtt, con
                 a.accepted = online->accepted;
                 const size_t lds = replay_segments_lds_bytes(pl.R, pl.B, online->window);
                 const dim3 grid((unsigned)pl.P), block(SEG_THREADS);
-                if (engine) hipLaunchKernelGGL((replay_segments_kernel<MODE_ONLINE, true>), grid, block, lds, s, a);
-                else hipLaunchKernelGGL((replay_segments_kernel<MODE_ONLINE, false>), grid, block, lds, s, a);
+                if (proxy && engine) hipLaunchKernelGGL((replay_segments_kernel<MODE_ONLINE, true, true>), grid, block, lds, s, a);
+                else if (proxy) hipLaunchKernelGGL((replay_segments_kernel<MODE_ONLINE, false, true>), grid, block, lds, s, a);
+                else if (engine) hipLaunchKernelGGL((replay_segments_kernel<MODE_ONLINE, true, false>), grid, block, lds, s, a);
+                else hipLaunchKernelGGL((replay_segments_kernel<MODE_ONLINE, false, false>), grid, block, lds, s, a);
+            } else if (proxy) {
+                const size_t lds = replay_segments_lds_bytes(pl.R, pl.B, 0);
+                const dim3 grid((unsigned)pl.P), block(SEG_THREADS);
+                if (engine) hipLaunchKernelGGL((replay_segments_kernel<MODE_COST_MODEL, true, true>), grid, block, lds, s, a);
+                else hipLaunchKernelGGL((replay_segments_kernel<MODE_COST_MODEL, false, true>), grid, block, lds, s, a);
             } else if (engine) {
                 const size_t lds = replay_segments_lds_bytes(pl.R, pl.B, 0);
                 const dim3 grid((unsigned)pl.P), block(SEG_THREADS);
                 switch (policy ? policy->policy : 0) {
-                    case 0: hipLaunchKernelGGL((replay_segments_kernel<MODE_COST_MODEL, true>), grid, block, lds, s, a); break;
-                    case 1: hipLaunchKernelGGL((replay_segments_kernel<MODE_LEAST_REQUEST, true>), grid, block, lds, s, a); break;
-                    case 2: hipLaunchKernelGGL((replay_segments_kernel<MODE_AFFINITY, true>), grid, block, lds, s, a); break;
-                    default: hipLaunchKernelGGL((replay_segments_kernel<MODE_RANDOM, true>), grid, block, lds, s, a); break;
+                    case 0: hipLaunchKernelGGL((replay_segments_kernel<MODE_COST_MODEL, true, false>), grid, block, lds, s, a); break;
+                    case 1: hipLaunchKernelGGL((replay_segments_kernel<MODE_LEAST_REQUEST, true, false>), grid, block, lds, s, a); break;
+                    case 2: hipLaunchKernelGGL((replay_segments_kernel<MODE_AFFINITY, true, false>), grid, block, lds, s, a); break;
+                    default: hipLaunchKernelGGL((replay_segments_kernel<MODE_RANDOM, true, false>), grid, block, lds, s, a); break;
                 }
             } else {
                 const size_t lds = replay_segments_lds_bytes(pl.R, pl.B, 0);
                 const dim3 grid((unsigned)pl.P), block(SEG_THREADS);
                 switch (policy ? policy->policy : 0) {
-                    case 0: hipLaunchKernelGGL((replay_segments_kernel<MODE_COST_MODEL, false>), grid, block, lds, s, a); break;
-                    case 1: hipLaunchKernelGGL((replay_segments_kernel<MODE_LEAST_REQUEST, false>), grid, block, lds, s, a); break;
-                    case 2: hipLaunchKernelGGL((replay_segments_kernel<MODE_AFFINITY, false>), grid, block, lds, s, a); break;
-                    default: hipLaunchKernelGGL((replay_segments_kernel<MODE_RANDOM, false>), grid, block, lds, s, a); break;
+                    case 0: hipLaunchKernelGGL((replay_segments_kernel<MODE_COST_MODEL, false, false>), grid, block, lds, s, a); break;
+                    case 1: hipLaunchKernelGGL((replay_segments_kernel<MODE_LEAST_REQUEST, false, false>), grid, block, lds, s, a); break;
+                    case 2: hipLaunchKernelGGL((replay_segments_kernel<MODE_AFFINITY, false, false>), grid, block, lds, s, a); break;
+                    default: hipLaunchKernelGGL((replay_segments_kernel<MODE_RANDOM, false, false>), grid, block, lds, s, a); break;
                 }
             }
             if ((e = hipGetLastError()) != hipSuccess) return hip_fail(e, "launch replay_segments_kernel");
         }
     } else {
-        if (online || engine || (policy && policy->policy != 0))
-            return fail(GORGO_ERR_INVALID_ARG,
-                        "the online tuner, the baseline policies and the engine model need the segment formulation");
+        if (online || engine || proxy || (policy && policy->policy != 0))
+            return fail(GORGO_ERR_INVALID_ARG, "the online tuner, the baseline policies, the engine model and imperfect "
+                                               "proxy knowledge need the segment formulation");
         ReplayArgs a;
         a.ts = t->dev.ts;
         a.in_len = t->dev.in_len;

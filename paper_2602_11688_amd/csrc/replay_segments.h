@@ -84,6 +84,12 @@ struct SegArgs {
     const double* eng_a_dec;      // [R] decode ms per token
     const double* eng_budget;     // [R] KV budget in tokens, 0 = none
     double eng_slowdown;
+    // imperfect proxy knowledge (only read by the kernel's proxy variants)
+    int32_t epochs, probe_ms;     // probe epochs given, and their length
+    const double* rtt_true;       // [epochs][R] round trip time a request dispatched in the epoch experiences
+    const double* rtt_est;        // [epochs][R] the proxy's moving average of them: what Eq. 3 scores with
+    int32_t stale_index;          // 1: Eq. 3 takes its cached prefix from everything ever dispatched to the replica
+    uint16_t* believed;           // [P][N] blocks the proxy believed cached on the chosen replica, nullable
 };
 
 // What picks the replica: the cost model of Eq. 3 with fixed weights, the same with the online tuner, or one
@@ -130,6 +136,7 @@ struct SegComm {
     int abandoned;                    // a wavefront gave up waiting: both leave, latencies become NaN
     unsigned long long choice;        // uncached tokens | (((r + 1) mod 2^26) << 6 | replica) << 32
     double w[3];                      // online tuner: weights in use, valid with seq_q like q
+    double rtt[WAVE];                 // proxy variants: estimated round trip time per replica, valid like q
 };
 
 __device__ __forceinline__ void lds_release() { __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront"); }
@@ -236,7 +243,7 @@ __device__ __forceinline__ int cached_in(int32_t rl, int pos, int end, int c_r, 
 
 // Queue wavefront of a replay: for every request, retire what has completed by its arrival, publish the load
 // signals, wait for the cache wavefront's choice, serve the request there.  Writes the latencies.
-template <int MODE, bool ENGINE>
+template <int MODE, bool ENGINE, bool PROXY>
 __device__ __forceinline__ void queue_wave(const SegArgs& a, int p, int lane, unsigned char* lds_raw, SegComm* comm) {
     constexpr bool ONLINE = MODE == MODE_ONLINE;
     const int R = a.R;
@@ -265,7 +272,14 @@ __device__ __forceinline__ void queue_wave(const SegArgs& a, int p, int lane, un
         wave_sync();
     }
     const double sc = a.scale[p];
-    const double my_rtt = lane < R ? a.rtt[lane] : 0.0;
+    double my_rtt = lane < R ? (PROXY ? a.rtt_true[lane] : a.rtt[lane]) : 0.0;
+    // imperfect proxy knowledge (Sec. 2.2, Sec. 4 RTT figure): time is cut into probe epochs, the epoch of t being
+    // the largest e with e * probe_ms <= t (capped at the last one given); a request experiences the true round
+    // trip time of its epoch, the cost model scores with the proxy's moving average, handed to the cache wavefront
+    // with the load signals
+    int epoch = 0;
+    double next_probe = PROXY ? (double)a.probe_ms : 0.0;
+    if (PROXY) st(&comm->rtt[lane], lane < R ? a.rtt_est[lane] : 0.0);
     // engine model: this lane's replica has its own rates and KV budget
     const double my_a_pf = ENGINE && lane < R ? a.eng_a_pf[lane] : 0.0;
     const double my_a_dec = ENGINE && lane < R ? a.eng_a_dec[lane] : 0.0;
@@ -284,6 +298,19 @@ __device__ __forceinline__ void queue_wave(const SegArgs& a, int p, int lane, un
             const double t = readlane_f64(m_t, i);
             const int L = __builtin_amdgcn_readlane(m_L, i);
             const int O = __builtin_amdgcn_readlane(m_O, i);
+            if (PROXY) {
+                bool moved = false;
+                while (epoch + 1 < a.epochs && next_probe <= t) {       // (timestamps do not decrease)
+                    ++epoch;
+                    next_probe = (double)(epoch + 1) * (double)a.probe_ms;
+                    moved = true;
+                }
+                if (moved) {
+                    const size_t at = (size_t)epoch * R + (lane < R ? lane : 0);
+                    my_rtt = a.rtt_true[at];
+                    st(&comm->rtt[lane], a.rtt_est[at]);
+                }
+            }
             Q.retire(t, rec);
             // (the least-request policy asks for requests in flight instead of their tokens)
             st(&comm->q[lane], MODE == MODE_LEAST_REQUEST ? Q.my_cnt : Q.my_q);
@@ -306,10 +333,10 @@ __device__ __forceinline__ void queue_wave(const SegArgs& a, int p, int lane, un
             const int best = (int)(hi & 63u);
             double ttft, e2e;
             if (ENGINE)
-                Q.serve_engine(r, best, t, my_rtt, (int64_t)(int)lo, L, O, my_a_pf, my_a_dec, my_budget, a.eng_slowdown,
+                Q.template serve_engine<PROXY>(r, best, t, my_rtt, (int64_t)(int)lo, L, O, my_a_pf, my_a_dec, my_budget, a.eng_slowdown,
                                rec, lane, &ttft, &e2e);
             else
-                Q.serve(r, best, t, my_rtt, (int64_t)(int)lo, L, O, a.a_pf, a.a_dec, rec, lane, &ttft, &e2e);
+                Q.template serve<PROXY>(r, best, t, my_rtt, (int64_t)(int)lo, L, O, a.a_pf, a.a_dec, rec, lane, &ttft, &e2e);
             o_ttft = lane == i ? ttft : o_ttft;
             o_e2e = lane == i ? e2e : o_e2e;
             if (ONLINE) {
@@ -373,7 +400,7 @@ __device__ __forceinline__ void queue_wave(const SegArgs& a, int p, int lane, un
     }
 }
 
-template <int MODE, bool ENGINE>
+template <int MODE, bool ENGINE, bool PROXY>
 __global__ void __launch_bounds__(SEG_THREADS) replay_segments_kernel(SegArgs a) {
     constexpr bool ONLINE = MODE == MODE_ONLINE;
     extern __shared__ __align__(16) unsigned char lds_raw[];
@@ -393,7 +420,7 @@ __global__ void __launch_bounds__(SEG_THREADS) replay_segments_kernel(SegArgs a)
     }
     __syncthreads();
     if (threadIdx.x >= WAVE) {
-        queue_wave<MODE, ENGINE>(a, p, lane, lds_raw, &comm);
+        queue_wave<MODE, ENGINE, PROXY>(a, p, lane, lds_raw, &comm);
         return;
     }
     __builtin_amdgcn_s_setprio(3);      // the cache wavefront has the longer loop: it goes first at issue
@@ -408,7 +435,12 @@ __global__ void __launch_bounds__(SEG_THREADS) replay_segments_kernel(SegArgs a)
     const double w_rtt = a.params[3 * (size_t)p + 0];
     const double w_prefill = a.params[3 * (size_t)p + 1];
     const double w_queue = a.params[3 * (size_t)p + 2];
-    const double my_rtt = lane < R ? a.rtt[lane] : 0.0;
+    const double my_rtt = !PROXY && lane < R ? a.rtt[lane] : 0.0;     // (proxy variants: comes with the load signals)
+    // Proxy variants (Sec. 7: the proxy does not see replica-side eviction): besides the replica's real cached
+    // prefix, the prefix that was ever dispatched to the replica is matched (cells >= 0); with a stale index Eq. 3
+    // scores with the latter.  Ownership is then kept for everything ever dispatched, a superset of what is
+    // cached, which the eviction walk does not mind: records behind the cursor are never looked at again.
+    const bool stale = PROXY && a.stale_index != 0;
 
     // Per-replica eviction state, held by lane = replica.
     //   cursor: blocks last touched by a request before cur_r, or by cur_r at positions >= cur_k, are
@@ -499,7 +531,7 @@ __global__ void __launch_bounds__(SEG_THREADS) replay_segments_kernel(SegArgs a)
             m_root = gref[0].id;
         }
 
-        int o_route = 0, o_hit = 0;
+        int o_route = 0, o_hit = 0, o_believed = 0;
 
         // requests the rows of the first SEG_CHUNK segments of request i of the batch.  The references are
         // read four at a time (one LDS round trip), most requests having no more than four segments.
@@ -541,6 +573,8 @@ __global__ void __launch_bounds__(SEG_THREADS) replay_segments_kernel(SegArgs a)
             // last segment whose cell is above, respectively not below, the cursor's request.
             int e_gt = 0, e_ge = 0;
             int32_t own_gt = -1;        // previous owner of the last segment counted in e_gt
+            int e_any = 0;              // proxy variants: end of the last segment ever dispatched to this replica ...
+            int32_t own_any = -1;       // ... and its previous owner
 #pragma unroll
             for (int k = 0; k < SEG_CHUNK; ++k) {
                 if (k >= s) break;
@@ -549,19 +583,27 @@ __global__ void __launch_bounds__(SEG_THREADS) replay_segments_kernel(SegArgs a)
                 e_gt = gt ? mine.end[k] : e_gt;
                 own_gt = gt ? mine.cell[k] : own_gt;
                 e_ge = ge ? mine.end[k] : e_ge;
+                if (PROXY) {
+                    const bool any = mine.cell[k] >= 0;
+                    e_any = any ? mine.end[k] : e_any;
+                    own_any = any ? mine.cell[k] : own_any;
+                }
             }
             const int below_cursor = cur_k < e_ge ? cur_k : e_ge;
             const bool some_eq = below_cursor > e_gt;       // blocks of the cursor's own request are matched
             int my_m = some_eq ? below_cursor : e_gt;
+            int my_seen = PROXY ? e_any : 0;                // blocks ever dispatched here (>= my_m)
             // For the ownership update below: where the cached prefix ends on this replica (rounded up to the
             // end of a segment that the cursor's request owns: what lies beyond the cursor is evicted anyway)
-            // and whether all cached segments had the same previous owner.
-            const int k_end = some_eq ? e_ge : e_gt;
-            const bool one_owner = some_eq ? e_gt == 0 : own_gt == mine.cell[0];
+            // and whether all cached segments had the same previous owner.  (Proxy variants: the same for the
+            // prefix ever dispatched.)
+            const int k_end = PROXY ? e_any : (some_eq ? e_ge : e_gt);
+            const bool one_owner = PROXY ? own_any == mine.cell[0] : (some_eq ? e_gt == 0 : own_gt == mine.cell[0]);
             int pos = mine.end[SEG_CHUNK - 1];
             bool open = my_m == pos;
+            bool open_seen = PROXY && my_seen == pos;
             bool deep = false;          // the match went past the preloaded segments
-            if (s > SEG_CHUNK && __ballot(open && lane < R) != 0) {      // (pos and open only matter in here)
+            if (s > SEG_CHUNK && __ballot((PROXY ? open_seen : open) && lane < R) != 0) {      // (pos and open only matter in here)
                 deep = true;
                 for (int c0 = SEG_CHUNK; c0 < s; c0 += SEG_CHUNK) {
                     int32_t cell[SEG_CHUNK];
@@ -573,7 +615,7 @@ __global__ void __launch_bounds__(SEG_THREADS) replay_segments_kernel(SegArgs a)
                         if (c0 + k < s) {
                             const SegRef sr = ref(a0 + c0 + k, true);
                             send[k] = sr.end;
-                            if (open && lane < R) cell[k] = ld(cell_at(sr.id));
+                            if ((PROXY ? open_seen : open) && lane < R) cell[k] = ld(cell_at(sr.id));
                         }
                     }
 #pragma unroll
@@ -582,10 +624,15 @@ __global__ void __launch_bounds__(SEG_THREADS) replay_segments_kernel(SegArgs a)
                             const int cnt = cached_in(cell[k], pos, send[k], cur_r, cur_k);
                             my_m += open ? cnt : 0;
                             open = open && cnt == send[k] - pos;
+                            if (PROXY) {
+                                const int cnt_seen = cell[k] >= 0 ? send[k] - pos : 0;
+                                my_seen += open_seen ? cnt_seen : 0;
+                                open_seen = open_seen && cnt_seen == send[k] - pos;
+                            }
                             pos = send[k];
                         }
                     }
-                    if (__ballot(open && lane < R) == 0) break;
+                    if (__ballot((PROXY ? open_seen : open) && lane < R) == 0) break;
                 }
             }
 
@@ -599,19 +646,27 @@ __global__ void __launch_bounds__(SEG_THREADS) replay_segments_kernel(SegArgs a)
             int hit_tok = a.block_tokens * my_m;           // block_tokens * blocks fits: both are below 2^16
             hit_tok = hit_tok > L ? L : hit_tok;
             int my_u = L - hit_tok;
+            int my_u_seen = my_u;       // uncached tokens as Eq. 3 sees them
+            if (PROXY) {
+                int seen_tok = a.block_tokens * (stale ? my_seen : my_m);
+                seen_tok = seen_tok > L ? L : seen_tok;
+                my_u_seen = L - seen_tok;
+            }
             // the load signals of this request come from the queue wavefront (normally already there);
             // everything that does not need them is finished first, so that little is left between reading
             // them and announcing the choice
-            const double score_rp = ONLINE ? 0.0 : eq3_without_queue(w_rtt, w_prefill, my_rtt, a.a_pf, my_u);
+            const double score_rp = ONLINE || PROXY ? 0.0 : eq3_without_queue(w_rtt, w_prefill, my_rtt, a.a_pf, my_u);
             asm volatile("" : "+v"(my_u), "+v"(my_m));
             double score_rp_ready = score_rp;
             asm volatile("" : "+v"(score_rp_ready));
             double my_q;
             double now_rtt = 0.0, now_prefill = 0.0, now_queue = 0.0;
+            double rtt_est = my_rtt;
             for (int spins = 0;; ++spins) {
                 const unsigned seq = __builtin_amdgcn_readfirstlane(ld(&comm.seq_q));
                 lds_acquire();
                 my_q = ld(&comm.q[lane]);
+                if (PROXY) rtt_est = ld(&comm.rtt[lane]);
                 if (ONLINE) {
                     now_rtt = ld(&comm.w[0]);
                     now_prefill = ld(&comm.w[1]);
@@ -629,9 +684,10 @@ __global__ void __launch_bounds__(SEG_THREADS) replay_segments_kernel(SegArgs a)
             }
             double my_score;
             if (MODE == MODE_COST_MODEL) {
-                my_score = eq3_with_queue(score_rp_ready, w_queue, a.a_pf, my_q);
+                my_score = PROXY ? eq3_score(w_rtt, w_prefill, w_queue, rtt_est, a.a_pf, my_u_seen, my_q)
+                                 : eq3_with_queue(score_rp_ready, w_queue, a.a_pf, my_q);
             } else if (MODE == MODE_ONLINE) {
-                my_score = eq3_score(now_rtt, now_prefill, now_queue, my_rtt, a.a_pf, my_u, my_q);
+                my_score = eq3_score(now_rtt, now_prefill, now_queue, rtt_est, a.a_pf, my_u_seen, my_q);
             } else if (MODE == MODE_LEAST_REQUEST) {
                 my_score = my_q;                    // requests in flight
             } else {
@@ -644,6 +700,7 @@ __global__ void __launch_bounds__(SEG_THREADS) replay_segments_kernel(SegArgs a)
             const int best = wave_argmin(my_score, lane, R);
             const bool is_best = lane == best;
             const int m_best = __builtin_amdgcn_readlane(my_m, best);
+            const int seen_best = PROXY ? __builtin_amdgcn_readlane(my_seen, best) : m_best;
             if (lane == 0) {
                 const unsigned u_best = (unsigned)__builtin_amdgcn_readlane(my_u, best);
                 const unsigned tag = (((unsigned)(r + 1) & 0x3FFFFFFu) << 6) | (unsigned)best;
@@ -661,7 +718,7 @@ __global__ void __launch_bounds__(SEG_THREADS) replay_segments_kernel(SegArgs a)
                 n2_own = owner == n2_r ? end : n2_own;
                 pend_own = owner == pend_r ? end : pend_own;
             };
-            if (m_best > 0) {
+            if (seen_best > 0) {
                 const bool simple = !deep && __builtin_amdgcn_readlane((int)one_owner, best) != 0;
                 if (simple) {
                     if (is_best) disown(mine.cell[0], k_end);
@@ -673,7 +730,7 @@ __global__ void __launch_bounds__(SEG_THREADS) replay_segments_kernel(SegArgs a)
                     for (int j = 0; j < s; ++j) {
                         const SegRef sr = ref(a0 + j, true);
                         const int32_t rl = ld(&last[(size_t)sr.id * R + best]);
-                        const int cnt = cached_in(rl, vpos, sr.end, cb_r, cb_k);
+                        const int cnt = PROXY ? (rl >= 0 ? sr.end - vpos : 0) : cached_in(rl, vpos, sr.end, cb_r, cb_k);
                         if (cnt > 0) {
                             if (rl != run_owner) {
                                 if (run_owner >= 0 && is_best) disown(run_owner, run_end);
@@ -772,6 +829,7 @@ __global__ void __launch_bounds__(SEG_THREADS) replay_segments_kernel(SegArgs a)
             // ---- outputs of the cache side (kept in registers until the batch ends)
             if (a.route) o_route = lane == i ? best : o_route;
             if (a.hit) o_hit = lane == i ? m_best : o_hit;
+            if (PROXY && a.believed) o_believed = lane == i ? (stale ? seen_best : m_best) : o_believed;
         };
 
         RowSet A, Bset;
@@ -791,6 +849,7 @@ __global__ void __launch_bounds__(SEG_THREADS) replay_segments_kernel(SegArgs a)
             const size_t o = (size_t)p * N + r0 + lane;
             if (a.route) a.route[o] = (uint8_t)o_route;
             if (a.hit) a.hit[o] = (uint16_t)o_hit;
+            if (PROXY && a.believed) a.believed[o] = (uint16_t)o_believed;
         }
         wave_sync();
         r0 += nb;

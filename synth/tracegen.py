@@ -275,7 +275,7 @@ def random_small(seed: int, N: int, R: int, *, n_ids: int = 12, max_blocks: int 
 
 
 def random_forest(seed: int, N: int, *, roots: int = 3, max_blocks: int = 40, grow: int = 6, gap_ms: int = 40,
-                  block_tokens: int = BLOCK_TOKENS) -> Trace:
+                  block_tokens: int = BLOCK_TOKENS, keep: float = 0.0) -> Trace:
     """Random chain-consistent trace with branching: every request takes a prefix of an earlier request's blocks
     (cut anywhere) and, more often than not, appends fresh blocks to it, so paths share prefixes, fork in the
     middle of runs and end inside them.  Ids are fresh integers, so every id has one predecessor and position."""
@@ -288,7 +288,7 @@ def random_forest(seed: int, N: int, *, roots: int = 3, max_blocks: int = 40, gr
             base = []
         else:
             p = paths[int(rng.integers(0, len(paths)))]
-            base = p[:int(rng.integers(1, len(p) + 1))]
+            base = p if rng.random() < keep else p[:int(rng.integers(1, len(p) + 1))]   # keep: paths grow long
         add = int(rng.integers(0 if base else 1, grow + 1)) if rng.random() < 0.7 or not base else 0
         add = min(add, max_blocks - len(base))
         path = base + list(range(nxt, nxt + add))
@@ -315,3 +315,15 @@ def engine_recipe(wl: Workload, seed: int = 0, *, spread: float = 2.0, kv_reques
     return dict(prefill_ms_per_token=wl.prefill_ms_per_token * spread ** rng.uniform(-1.0, 1.0, wl.R),
                 decode_ms_per_token=wl.decode_ms_per_token * spread ** rng.uniform(-1.0, 1.0, wl.R),
                 kv_tokens=np.full(wl.R, int(kv_requests * most), np.int64), slowdown=float(slowdown))
+
+
+def rtt_walk(wl: Workload, epochs: int, seed: int = 0, *, step: float = 0.15, pull: float = 0.9) -> np.ndarray:
+    """Seeded true round trip times per probe epoch [epochs, R]: each replica's RTT starts at the workload's value and
+    its logarithm wanders around it (x_e = pull * x_(e-1) + step * normal draw: deviations of about a third in the
+    long run), rounded to 0.001 ms."""
+    rng = np.random.Generator(np.random.PCG64(np.random.SeedSequence([MASTER_SEED, 96, wl.config_index, seed])))
+    eps = step * rng.standard_normal((epochs, wl.R))
+    x = np.zeros((epochs, wl.R))
+    for e in range(1, epochs):
+        x[e] = pull * x[e - 1] + eps[e]
+    return np.round(wl.rtt_ms[None, :] * np.exp(x), 3)

@@ -167,7 +167,7 @@ def test_random_cases(seed):
     B = int(rng.choice([1, 2, 3, 8, 16]))
     N = int(rng.integers(60, 700))
     tr = tg.random_forest(100 + seed, N, roots=int(rng.integers(1, 5)), max_blocks=int(rng.integers(4, 40)),
-                          grow=int(rng.integers(1, 9)), gap_ms=int(rng.integers(1, 60)))
+                          grow=int(rng.integers(1, 9)), gap_ms=int(rng.integers(1, 60)), keep=float(rng.choice([0.0, 0.5, 0.85])))
     nmax = int(np.diff(tr.blk_off).max())
     most = int((tr.in_len.astype(np.int64) + tr.out_len).max())
     model = g.Model(R, B, int(rng.choice([0, nmax, 3 * nmax + 1])), float(rng.choice([0.0, 0.01, 0.05])), 0.0)

@@ -98,3 +98,47 @@ def test_large_workload_under_the_engine_model_matches_oracle():
             assert abs(p95_e2e[p] - ref.p95_e2e_ms) <= RTOL * ref.p95_e2e_ms
             print(f"replay {p}: {ref.route.size} requests equal, p95 TTFT {ref.p95_ttft_ms:.3f} ms, p95 E2E "
                   f"{ref.p95_e2e_ms:.3f} ms", flush=True)
+
+
+def test_large_workload_with_imperfect_proxy_knowledge_matches_oracle():
+    """The same launch shape with round trip times that wander per 30 s probe epoch (scored through their moving
+    average) and a proxy cache index that never forgets: 18 replays against the oracle in full."""
+    import torch
+    wl = tg.config(5)
+    es_cfg = wl.es if wl.es else dict(tg.ES_DEFAULTS, P=wl.P, seed=tg.MASTER_SEED + 5)
+    P = es_cfg["P"]
+    model = g.Model(wl.R, wl.batch, wl.cache_blocks, wl.prefill_ms_per_token, wl.decode_ms_per_token)
+    epochs = int(float(wl.trace.ts_ms[-1]) // 30000) + 1
+    px = g.Proxy(tg.rtt_walk(wl, epochs), 30000, 0.3, True)
+    h = load(wl.trace)
+    state = g.es_init(es_cfg["seed"])
+    params = g.es_propose(state, g.es_sample(es_cfg["seed"], 0, P))
+    rng = np.random.default_rng(20260213)
+    picks = sorted({0, P - 1} | set(rng.choice(np.arange(1, P - 1), 16, replace=False).tolist()))
+
+    def oracle(p):
+        return ob.replay_proxy(wl.trace, R=wl.R, batch=wl.batch, cache_blocks=wl.cache_blocks,
+                               prefill_ms_per_token=wl.prefill_ms_per_token, decode_ms_per_token=wl.decode_ms_per_token,
+                               rtt_true=px.rtt_true_ms, probe_ms=30000, alpha=0.3, stale_index=True, w=params[p], scale=1.0)
+    with ThreadPoolExecutor(16) as ex:
+        futs = {p: ex.submit(oracle, p) for p in picks}
+        full = g.eval_proxy(h, model, px, params, 1.0)
+        torch.cuda.synchronize()
+        p95_ttft = full.p95_ttft_ms.cpu().numpy()
+        p95_e2e = full.p95_e2e_ms.cpu().numpy()
+        assert np.isfinite(p95_ttft).all() and (p95_ttft > 0).all() and (p95_e2e >= p95_ttft).all()
+        for p in picks:
+            ref = futs[p].result()
+            route = full.route[p].cpu().numpy()
+            bad = np.nonzero(route != ref.route)[0]
+            assert bad.size == 0, f"replay {p}: first route mismatch at request {bad[0]} ({bad.size} in all)"
+            assert np.array_equal(full.hit_blocks[p].cpu().numpy(), ref.hit_blocks), f"replay {p}: hit counts"
+            assert np.array_equal(full.believed_hit_blocks[p].cpu().numpy(), ref.believed_hit), f"replay {p}: believed hits"
+            np.testing.assert_allclose(full.ttft_ms[p].cpu().numpy(), ref.ttft_ms, rtol=RTOL, atol=0)
+            np.testing.assert_allclose(full.e2e_ms[p].cpu().numpy(), ref.e2e_ms, rtol=RTOL, atol=0)
+            assert abs(p95_ttft[p] - ref.p95_ttft_ms) <= RTOL * ref.p95_ttft_ms
+            assert abs(p95_e2e[p] - ref.p95_e2e_ms) <= RTOL * ref.p95_e2e_ms
+            over = float((ref.believed_hit > ref.hit_blocks).mean())
+            print(f"replay {p}: {ref.route.size} requests equal, p95 TTFT {ref.p95_ttft_ms:.3f} ms, index overestimates on "
+                  f"{100 * over:.1f}% of requests", flush=True)
+        assert np.array_equal(full.rtt_est_ms.cpu().numpy(), futs[picks[0]].result().rtt_est)

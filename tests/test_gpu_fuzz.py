@@ -24,7 +24,7 @@ def _setup(seed):
     kind = seed % 3
     if kind == 0:
         tr = tg.random_forest(seed, N, roots=int(rng.integers(1, 5)), max_blocks=int(rng.integers(4, 60)),
-                              grow=int(rng.integers(1, 9)), gap_ms=int(rng.integers(1, 80)))
+                              grow=int(rng.integers(1, 9)), gap_ms=int(rng.integers(1, 80)), keep=float(rng.choice([0.0, 0.5, 0.85])))
     elif kind == 1:
         tr = tg.random_small(seed, N, R, n_ids=int(rng.integers(10, 200)), max_blocks=int(rng.integers(2, 12)),
                              consistent=True, gap_ms=int(rng.integers(1, 80)))
