@@ -201,7 +201,7 @@ def main():
     if args.engine + args.online + args.proxy > 1:
         sys.exit("bench.py: --engine, --online and --proxy are separate runs")
     if args.gpus != 1:
-        sys.exit("bench.py: this build evaluates on ONE GPU (replays are independent and would shard by candidate; "
+        sys.exit("bench.py: this library evaluates on ONE GPU (replays are independent and would shard by candidate; "
                  "no multi-GPU path is built) -- run with --gpus 1")
 
     import torch

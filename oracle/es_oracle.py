@@ -10,7 +10,7 @@ The normal draws z are INPUTS (the product draws them with its own counter-based
 same numbers to this file in tests), so no random number is generated here.
 
 Parity unpinned by the paper: the 1/5-rule constants (sigma * exp((s - 1/5)/2)) and the parent-selection
-fraction mu = max(1, P // 4) are this build's stated readings.
+fraction mu = max(1, P // 4) are the readings stated here.
 """
 import math
 

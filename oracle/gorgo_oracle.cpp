@@ -34,7 +34,7 @@
 // that never forgets; struct Proxy below) is pinned by a hand-worked trace, closed forms of the moving average,
 // probe epochs recovered from latencies at and around the epoch boundaries, reductions to the plain replay, the
 // forced-route model extended with the same knowledge, and the one-sidedness of the index's error.
-// Parity unpinned by the paper (fixed by this build's stated readings only): the service-model constants,
+// Parity unpinned by the paper (fixed by the readings stated here only): the service-model constants,
 // the functional form of the engine model, the smoothing constant and the index's forgetting rule, and the
 // root-newest stamp order inside one request.
 
@@ -412,8 +412,8 @@ static int replay_impl(int64_t N, const int64_t* ts_ms, const int32_t* in_len, c
             if (proxy && proxy->stale_index) X.dispatched.insert(ids, ids + n);
         }
 
-        // service on the chosen replica (the paper leaves the replica model open; this build states a
-        // linear one): B slots, each serving one request at a time, first come first served on the
+        // service on the chosen replica (the paper leaves the replica model open; the one stated here is
+        // linear): B slots, each serving one request at a time, first come first served on the
         // earliest-free slot (lowest index on ties); prefill a_pf ms per uncached token, then decode a_dec
         // ms per output token.  The request reaches the replica half an RTT after t and its first token /
         // completion event come back half an RTT after they are produced.  This reproduces Eq. 1:
