@@ -61,6 +61,21 @@ __device__ __forceinline__ unsigned wave_min_u32(unsigned x) {
     return (unsigned)__builtin_amdgcn_readlane((int)x, 63);
 }
 
+// Sum of x over the wavefront on the same path (lanes without a source add 0); the sum must fit 32 bits.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ unsigned dpp_add_u32(unsigned x) {
+    return x + (unsigned)__builtin_amdgcn_update_dpp(0, (int)x, CTRL, ROW_MASK, 0xf, false);
+}
+__device__ __forceinline__ unsigned wave_sum_u32(unsigned x) {
+    x = dpp_add_u32<0x111, 0xf>(x);   // row_shr:1
+    x = dpp_add_u32<0x112, 0xf>(x);   // row_shr:2
+    x = dpp_add_u32<0x114, 0xf>(x);   // row_shr:4
+    x = dpp_add_u32<0x118, 0xf>(x);   // row_shr:8: lane 15 of each row holds the row's sum
+    x = dpp_add_u32<0x142, 0xa>(x);   // row_bcast:15 into rows 1, 3
+    x = dpp_add_u32<0x143, 0xc>(x);   // row_bcast:31 into rows 2, 3
+    return (unsigned)__builtin_amdgcn_readlane((int)x, 63);
+}
+
 // Lowest-index minimum over the lanes below `count` (count >= 1; values must not be NaN).  The values are
 // compared through the usual order-preserving map of an IEEE double to an unsigned 64-bit key (zeros of
 // either sign made equal first), high word first, then the low word among the lanes that tie on the high
@@ -317,47 +332,48 @@ struct Queues {
     // before its arrival nor its predecessor's admission, at which fewer than B requests are running and either
     // none is or their KV tokens plus its own fit the replica's budget (0 = no budget); its decode takes
     // (a_dec * O) * (1 + slowdown * n) with n the requests running at s.  All requests admitted earlier have
-    // started by s, so those running at s are the slots with free_at > s: one scan counts them, adds their
-    // tokens up and finds the next time one ends; the scan is repeated from that time until the request fits
-    // (at most B times: each repeat has one request fewer running).  The request takes the lowest slot that is
-    // free at s; its record joins that slot's in-flight list, whose completion times still increase.
+    // started by s, so those running at s are the slots with free_at > s.  The slots of the chosen replica are
+    // spread over the lanes (B <= 64): a ballot counts the running ones and finds a free slot, their tokens are
+    // summed and the next time one ends is found with wavefront reductions; the scan is repeated from that time
+    // until the request fits (at most B times: each repeat has one request fewer running).  The request takes
+    // the lowest slot that is free at s; its record joins that slot's in-flight list.
     template <bool REORDER>
     __device__ void serve_engine(int64_t r, int best, double t, double rtt_mine, int64_t uncached_mine, int64_t L,
                                  int64_t O, double a_pf_mine, double a_dec_mine, double budget_mine, double slowdown,
                                  Rec* rec, int lane, double* ttft_out, double* e2e_out) {
         double ttft = 0.0, e2e = 0.0;
-        if (lane == best) {
-            const double half = 0.5 * rtt_mine;
-            const double arrive = t + half;
-            const double tokens = (double)(L + O);
-            double start = arrive > my_last_start ? arrive : my_last_start;
-            int n, k;
-            for (int scans = 0;; ++scans) {
-                n = B - Bp;                  // the padding slots (free_at = +inf) count as running below
-                k = -1;
-                double held = 0.0, next_end = INFINITY;
-                for (int b0 = 0; b0 < Bp; b0 += 8) {
-                    double f[8];
-                    uint32_t h[8];
-#pragma unroll
-                    for (int j = 0; j < 8; ++j) {
-                        f[j] = free_at[base + b0 + j];
-                        h[j] = kv[base + b0 + j];
-                    }
-#pragma unroll
-                    for (int j = 0; j < 8; ++j) {
-                        const bool running = f[j] > start;
-                        n += running ? 1 : 0;
-                        held += running ? (double)h[j] : 0.0;
-                        next_end = running && f[j] < next_end ? f[j] : next_end;
-                        k = !running && k < 0 ? b0 + j : k;
-                    }
-                }
-                if (n < B && (n == 0 || budget_mine == 0.0 || held + tokens <= budget_mine)) break;
-                if (scans >= Bp) break;      // not reached: every repeat has fewer requests running
-                start = next_end;            // finite: some request is running
+        // The scan runs across the lanes: lane j looks at slot j of the chosen replica (B <= 64).
+        const double half = 0.5 * readlane_f64(rtt_mine, best);
+        const double arrive = t + half;
+        const double tokens = (double)(L + O);
+        const double budget = readlane_f64(budget_mine, best);
+        const double last_start = readlane_f64(my_last_start, best);
+        double start = arrive > last_start ? arrive : last_start;
+        const int slot = best * Bp + (lane < B ? lane : 0);
+        const double f = lane < B ? free_at[slot] : 0.0;
+        const unsigned h = lane < B ? kv[slot] : 0u;
+        int n, k;
+        for (int scans = 0;; ++scans) {
+            const bool running = lane < B && f > start;
+            const unsigned long long run_mask = __ballot(running);
+            n = __popcll(run_mask);
+            k = __ffsll(~run_mask & (B >= 64 ? ~0ull : (1ull << B) - 1)) - 1;
+            if (n == 0) break;
+            bool fits = n < B;
+            if (fits && budget != 0.0) {
+                // tokens held by the running requests: two 16-bit halves summed apart (each sum below 2^22)
+                const unsigned lo = wave_sum_u32(running ? h & 0xffffu : 0u);
+                const unsigned hi = wave_sum_u32(running ? h >> 16 : 0u);
+                const double held = (double)hi * 65536.0 + (double)lo;
+                fits = held + tokens <= budget;
             }
-            k = k < 0 ? 0 : k;               // (a free slot exists whenever fewer than B are running)
+            if (fits || scans >= B) break;       // (the second test is not reached: every repeat has fewer running)
+            // the next time a running request ends (running ones end after `start`: positive, finite)
+            const double ends = running ? f : INFINITY;
+            start = readlane_f64(ends, wave_argmin(ends, lane, WAVE));
+        }
+        k = k < 0 ? 0 : k;                       // (a free slot exists whenever fewer than B are running)
+        if (lane == best) {
             my_last_start = start;
             const double pf = a_pf_mine * (double)uncached_mine;
             const double first_tok = start + pf;
