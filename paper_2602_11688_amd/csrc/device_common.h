@@ -251,18 +251,21 @@ struct Queues {
     // and no load signal: a slot with nothing in flight has seen its completion event reach the proxy, so it
     // has been free since before any later arrival at the replica, exactly like the earliest-free one.  The
     // slots are therefore only searched for their earliest free time (lowest index on ties) when every slot
-    // still has a request in flight.  The chosen replica's lane works, its latencies are broadcast.
+    // still has a request in flight.  `idle_then` is the set of idle slots at the request's time t; the lists
+    // themselves may already have been retired further (to the next request's time), which only makes more
+    // slots idle.  The chosen replica's lane works, its latencies are broadcast.
     template <bool REORDER>
     __device__ void serve(int64_t r, int best, double t, double rtt_mine, int64_t uncached_mine, int64_t L, int64_t O,
-                          double a_pf, double a_dec, Rec* rec, int lane, double* ttft_out, double* e2e_out) {
+                          double a_pf, double a_dec, Rec* rec, int lane, unsigned long long idle_then,
+                          double* ttft_out, double* e2e_out) {
         double ttft = 0.0, e2e = 0.0;
         if (lane == best) {
             const double half = 0.5 * rtt_mine;
             const double arrive = t + half;
             double start = arrive;
             int k;
-            if (idle != 0) {
-                k = __ffsll(idle) - 1;
+            if (idle_then != 0) {
+                k = __ffsll(idle_then) - 1;
             } else {
                 double fv = INFINITY;
                 k = 0;
@@ -288,7 +291,7 @@ struct Queues {
             e2e = done - t;
             const int s = base + k;
             free_at[s] = end;
-            if (idle != 0) {
+            if ((idle >> k) & 1ull) {
                 idle &= ~(1ull << k);
                 h_done[s] = done;
                 h_tok[s] = (int32_t)L;

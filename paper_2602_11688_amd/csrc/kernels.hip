@@ -306,7 +306,7 @@ __global__ void __launch_bounds__(WAVE) replay_blocks_kernel(ReplayArgs a) {
 
         // ---- service on the chosen replica, outputs
         double ttft, e2e;
-        Q.serve<false>(r, best, t, my_rtt, my_u, L, O, a.a_pf, a.a_dec, rec, lane, &ttft, &e2e);
+        Q.serve<false>(r, best, t, my_rtt, my_u, L, O, a.a_pf, a.a_dec, rec, lane, Q.idle, &ttft, &e2e);
         if (lane == 0) {
             if (a.hit) a.hit[(size_t)p * N + r] = (uint16_t)m_best;
             if (a.ttft) a.ttft[(size_t)p * N + r] = ttft;

@@ -316,6 +316,15 @@ __device__ __forceinline__ void queue_wave(const SegArgs& a, int p, int lane, un
             st(&comm->q[lane], MODE == MODE_LEAST_REQUEST ? Q.my_cnt : Q.my_q);
             lds_release();
             if (lane == 0) st(&comm->seq_q, (unsigned)(r + 1));
+            // While the cache wavefront decides, the completions up to the next request's time are retired
+            // already: they do not depend on where this request goes (only this request's own completion is
+            // left for the retire above, next time round).  The service step still has to see the slots that
+            // were idle at this request's time, so their set is kept.
+            const unsigned long long idle_now = Q.idle;
+            if (r + 1 < N) {
+                const double t_next = i + 1 < nb ? readlane_f64(m_t, i + 1) : (double)a.ts[r + 1] * sc;
+                Q.retire(t_next, rec);
+            }
             const unsigned want = (unsigned)(r + 1) & 0x3FFFFFFu;
             unsigned hi, lo;
             for (int spins = 0;; ++spins) {
@@ -336,7 +345,8 @@ __device__ __forceinline__ void queue_wave(const SegArgs& a, int p, int lane, un
                 Q.template serve_engine<PROXY>(r, best, t, my_rtt, (int64_t)(int)lo, L, O, my_a_pf, my_a_dec, my_budget, a.eng_slowdown,
                                rec, lane, &ttft, &e2e);
             else
-                Q.template serve<PROXY>(r, best, t, my_rtt, (int64_t)(int)lo, L, O, a.a_pf, a.a_dec, rec, lane, &ttft, &e2e);
+                Q.template serve<PROXY>(r, best, t, my_rtt, (int64_t)(int)lo, L, O, a.a_pf, a.a_dec, rec, lane, idle_now,
+                                        &ttft, &e2e);
             o_ttft = lane == i ? ttft : o_ttft;
             o_e2e = lane == i ? e2e : o_e2e;
             if (ONLINE) {
