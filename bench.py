@@ -139,9 +139,10 @@ def cpu_baseline(wl, params, n_req, threads, online=None, engine=None, proxy=Non
     return threads * tr.N / dt, dt, tr.N
 
 
-def compare_policies(g, torch, tr, model, wl, tuned, N):
+def compare_policies(g, torch, tr, model, wl, tuned, N, engine=None):
     """The paper's comparison of routing policies in synthetic form: one replay of the trace per policy, same replica
-    model, time scale 1.  TTFT / E2E in ms; block_hit = cached blocks / requested blocks."""
+    model (the engine model when `engine` is given), time scale 1.  TTFT / E2E in ms; block_hit = cached blocks /
+    requested blocks."""
     nb = torch.from_numpy(np.diff(wl.trace.blk_off).astype(np.float64)).to("cuda:0")
 
     def stats(res, p):
@@ -153,13 +154,17 @@ def compare_policies(g, torch, tr, model, wl, tuned, N):
     weights = {"cost model, initial weights (0.5, 1, 0.1)": [0.5, 1.0, 0.1], "cost model, tuner's best weights": tuned,
                "prefix-cache = weights (0, 1, 0)": [0.0, 1.0, 0.0], "least-load (proxy tokens) = weights (0, 0, 1)": [0.0, 0.0, 1.0],
                "nearest replica = weights (1, 0, 0)": [1.0, 0.0, 0.0]}
-    res = g.eval_population(tr, model, wl.rtt_ms, np.array(list(weights.values()), np.float64), 1.0)
+    par = np.array(list(weights.values()), np.float64)
+    res = g.eval_population(tr, model, wl.rtt_ms, par, 1.0) if engine is None else \
+        g.eval_engine(tr, model, engine, wl.rtt_ms, 1.0, params=par)
     torch.cuda.synchronize()
     for i, k in enumerate(weights):
         table[k] = stats(res, i)
     del res
     for pol in ("least-request", "session-affinity", "random"):
-        res = g.eval_policy(tr, model, wl.rtt_ms, pol, [1.0], seeds=np.array([7], np.uint64))
+        seeds = np.array([7], np.uint64)
+        res = g.eval_policy(tr, model, wl.rtt_ms, pol, [1.0], seeds=seeds) if engine is None else \
+            g.eval_engine(tr, model, engine, wl.rtt_ms, [1.0], policy=pol, seeds=seeds)
         torch.cuda.synchronize()
         table[pol] = stats(res, 0)
         del res
@@ -346,7 +351,8 @@ def main():
                      "issue": issue},
     }
     if args.policies:
-        out["policies"] = compare_policies(g, torch, tr, model, wl, [float(x) for x in state.best_theta[:]], N)
+        out["policies"] = compare_policies(g, torch, tr, model, wl, [float(x) for x in state.best_theta[:]], N,
+                                           engine if args.engine else None)
     if not args.no_cpu_baseline:
         cores = min(len(os.sched_getaffinity(0)), 16)
         on = (z_on[:cores].cpu().numpy(), list(state.lo[:]), list(state.hi[:]), state.sigma) if args.online else None
