@@ -36,7 +36,7 @@ def lib():
         L.gorgo_oracle_replay_proxy.restype = C.c_int
         L.gorgo_oracle_replay_proxy.argtypes = [C.c_int64] + [C.c_void_p] * 5 + \
             [C.c_int32, C.c_int32, C.c_int32, C.c_int64, C.c_double, C.c_double, C.c_void_p, C.c_void_p, C.c_void_p,
-             C.c_double, C.c_int32, C.c_int32, C.c_void_p, C.c_double, C.c_int32, C.c_void_p, C.c_double,
+             C.c_double, C.c_int32, C.c_int32, C.c_void_p, C.c_double, C.c_int64, C.c_void_p, C.c_double,
              C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_double] + [C.c_void_p] * 11
         L.gorgo_oracle_philox4x32_10.restype = None
         L.gorgo_oracle_philox4x32_10.argtypes = [C.c_void_p] * 3
@@ -223,11 +223,11 @@ def replay_engine(trace, *, R, batch, cache_blocks, prefill_ms_per_token, engine
 
 
 def replay_proxy(trace, *, R, batch, cache_blocks, prefill_ms_per_token, decode_ms_per_token=0.0, rtt_true, w,
-                 probe_ms=30000, alpha=0.5, stale_index=False, engine=None, scale=1.0, block_tokens=512, online=None,
+                 probe_ms=30000, alpha=0.5, index_blocks=-1, engine=None, scale=1.0, block_tokens=512, online=None,
                  debug=False) -> Replay:
     """One replay with imperfect proxy knowledge: rtt_true[epochs,R] are the true round trip times per probe epoch,
-    the cost model scores with their moving average; with stale_index it also takes its cached prefixes from the
-    set of everything ever dispatched to a replica.  engine / online as in replay_engine."""
+    the cost model scores with their moving average; with index_blocks >= 0 it also takes its cached prefixes from
+    an index of its own (an LRU of that many blocks per replica, 0 = it never forgets) instead of the replicas' caches.  engine / online as in replay_engine."""
     N = int(trace.ts_ms.shape[0])
     ts = np.ascontiguousarray(trace.ts_ms, dtype=np.int64)
     il = np.ascontiguousarray(trace.in_len, dtype=np.int32)
@@ -267,7 +267,7 @@ def replay_proxy(trace, *, R, batch, cache_blocks, prefill_ms_per_token, decode_
     fin = np.zeros(6, np.float64)
     rc = lib().gorgo_oracle_replay_proxy(N, _p(ts), _p(il), _p(ol), _p(bo), _p(hs), block_tokens, R, batch, cache_blocks,
                                          prefill_ms_per_token, decode_ms_per_token, _p(apf), _p(adec), _p(kv), slow,
-                                         E, int(probe_ms), _p(rt), float(alpha), int(bool(stale_index)), _p(wv),
+                                         E, int(probe_ms), _p(rt), float(alpha), int(index_blocks), _p(wv),
                                          float(scale), window, hop, _p(zz), _p(lov), _p(hiv), float(o.get("sigma0", 0.0)),
                                          _p(route), _p(hit), _p(ttft), _p(e2e), _p(p), _p(score), _p(est), _p(believed),
                                          _p(theta_step), _p(fitness_step), _p(fin))

@@ -31,7 +31,7 @@
 // reduction to the linear model, the independence of replicas under random routing, and its invariants rebuilt
 // from the outputs.
 // Imperfect proxy knowledge (round trip times per probe epoch scored through their moving average, a cache index
-// that never forgets; struct Proxy below) is pinned by a hand-worked trace, closed forms of the moving average,
+// of its own capacity; struct Proxy below) is pinned by a hand-worked trace, closed forms of the moving average,
 // probe epochs recovered from latencies at and around the epoch boundaries, reductions to the plain replay, the
 // forced-route model extended with the same knowledge, and the one-sidedness of the index's error.
 // Parity unpinned by the paper (fixed by the readings stated here only): the service-model constants,
@@ -67,8 +67,9 @@ struct Replica {
     // last token is produced, KV tokens held), and the time the latest request was admitted
     std::vector<std::pair<double, int64_t>> served;
     double last_start = 0.0;
-    // imperfect proxy knowledge only: every block ever dispatched to this replica (the proxy's index)
-    std::unordered_set<int64_t> dispatched;
+    // imperfect proxy knowledge only: the proxy's own index of this replica's cache (same rules, own capacity)
+    std::unordered_map<int64_t, int64_t> index_cache;
+    std::map<int64_t, int64_t> index_by_stamp;
 };
 
 // The engine model of a replica (Sec. 2.2: continuous batching admits a request into the running batch while
@@ -156,15 +157,17 @@ int spread(uint32_t h, int R) { return (int)(((uint64_t)h * (uint64_t)R) >> 32);
 //     request dispatched in epoch e take half of it);
 //   * the proxy probes at the start of every epoch and smooths: est[0] = rtt_true[0], est[e] = alpha *
 //     rtt_true[e] + (1 - alpha) * est[e-1]; the cost model scores with est of the request's epoch;
-//   * stale_index: the proxy's index of replica i is the set of all blocks ever dispatched to i (a prefix trie
-//     of dispatched requests that never forgets); the cost model takes its uncached tokens from the longest
-//     prefix in that index, the replica prefills what its own (LRU, bounded) cache really misses.
+//   * index_blocks >= 0: the proxy keeps an index of its own of what it dispatched to replica i (a prefix trie of
+//     dispatched requests), updated like the replica's cache (least recently used block evicted first) but with
+//     its own capacity: index_blocks per replica, 0 = it never forgets; the cost model takes its uncached tokens
+//     from the longest prefix in that index, the replica prefills what its own cache really misses.
+//     index_blocks < 0: the proxy sees the replicas' caches as they are.
 struct Proxy {
     int32_t epochs;            // >= 1
     int32_t probe_ms;          // >= 1
     const double* rtt_true;    // [epochs][R]
     double alpha;              // in (0, 1]
-    int32_t stale_index;       // 0 = the proxy sees the replicas' caches as they are
+    int64_t index_blocks;      // < 0 = the proxy sees the replicas' caches as they are
 };
 
 // Admission time of a request of `kv` KV tokens that arrives at `a` on replica X (see Engine), and the number
@@ -334,13 +337,13 @@ static int replay_impl(int64_t N, const int64_t* ts_ms, const int32_t* in_len, c
             int64_t hit_tok = std::min<int64_t>(L, (int64_t)block_tokens * k);   // partial last block
             u[i] = L - hit_tok;
         }
-        // with a stale index the cost model sees the longest prefix ever dispatched to the replica instead
+        // with an index of its own the cost model sees the longest prefix in that index instead
         u_seen = u;
         m_seen = m;
-        if (proxy && proxy->stale_index)
+        if (proxy && proxy->index_blocks >= 0)
             for (int i = 0; i < R; ++i) {
                 int64_t k = 0;
-                while (k < n && rep[i].dispatched.count(ids[k])) ++k;
+                while (k < n && rep[i].index_cache.count(ids[k])) ++k;
                 m_seen[i] = k;
                 u_seen[i] = L - std::min<int64_t>(L, (int64_t)block_tokens * k);
             }
@@ -383,18 +386,19 @@ static int replay_impl(int64_t N, const int64_t* ts_ms, const int32_t* in_len, c
         // cache update on the chosen replica: every block of the request becomes (or stays) cached with a
         // fresh stamp; if a bounded cache would overflow, the entries with the smallest stamps that do not
         // belong to this request are evicted first (least recently used).
-        {
+        auto touch = [&](std::unordered_map<int64_t, int64_t>& cache, std::map<int64_t, int64_t>& by_stamp,
+                         int64_t capacity) -> int {
             std::unordered_set<int64_t> mine(ids, ids + n);
-            if (C > 0 && (int64_t)mine.size() > C) return -5;
+            if (capacity > 0 && (int64_t)mine.size() > capacity) return -5;
             int64_t n_new = 0;
-            for (int64_t id : mine) if (!X.cache.count(id)) ++n_new;
-            if (C > 0) {
-                int64_t excess = (int64_t)X.cache.size() + n_new - C;
-                auto it = X.by_stamp.begin();
-                while (excess > 0 && it != X.by_stamp.end()) {
+            for (int64_t id : mine) if (!cache.count(id)) ++n_new;
+            if (capacity > 0) {
+                int64_t excess = (int64_t)cache.size() + n_new - capacity;
+                auto it = by_stamp.begin();
+                while (excess > 0 && it != by_stamp.end()) {
                     if (mine.count(it->second)) { ++it; continue; }
-                    X.cache.erase(it->second);
-                    it = X.by_stamp.erase(it);
+                    cache.erase(it->second);
+                    it = by_stamp.erase(it);
                     --excess;
                 }
                 if (excess > 0) return -5;
@@ -403,14 +407,18 @@ static int replay_impl(int64_t N, const int64_t* ts_ms, const int32_t* in_len, c
             for (int64_t k = 0; k < n; ++k) {
                 if (!seen.insert(ids[k]).second) continue;      // stamp comes from the first occurrence
                 int64_t stamp = r * STAMP_STRIDE + (STAMP_STRIDE - 1 - k);
-                auto f = X.cache.find(ids[k]);
-                if (f != X.cache.end()) { X.by_stamp.erase(f->second); f->second = stamp; }
-                else X.cache.emplace(ids[k], stamp);
-                X.by_stamp.emplace(stamp, ids[k]);
+                auto f = cache.find(ids[k]);
+                if (f != cache.end()) { by_stamp.erase(f->second); f->second = stamp; }
+                else cache.emplace(ids[k], stamp);
+                by_stamp.emplace(stamp, ids[k]);
             }
-            if (size_dbg) size_dbg[r] = (int64_t)X.cache.size();
-            if (proxy && proxy->stale_index) X.dispatched.insert(ids, ids + n);
-        }
+            return 0;
+        };
+        if (int rc = touch(X.cache, X.by_stamp, C)) return rc;
+        if (size_dbg) size_dbg[r] = (int64_t)X.cache.size();
+        // the proxy's index records the same dispatch under its own capacity
+        if (proxy && proxy->index_blocks >= 0)
+            if (int rc = touch(X.index_cache, X.index_by_stamp, proxy->index_blocks)) return rc;
 
         // service on the chosen replica (the paper leaves the replica model open; the one stated here is
         // linear): B slots, each serving one request at a time, first come first served on the
@@ -569,7 +577,7 @@ int gorgo_oracle_replay_proxy(int64_t N, const int64_t* ts_ms, const int32_t* in
                               const int64_t* blk_off, const int64_t* hash_ids, int32_t block_tokens,
                               int32_t R, int32_t B, int64_t C, double a_pf, double a_dec,
                               const double* a_pf_r, const double* a_dec_r, const int64_t* kv_tokens, double slowdown,
-                              int32_t epochs, int32_t probe_ms, const double* rtt_true, double alpha, int32_t stale_index,
+                              int32_t epochs, int32_t probe_ms, const double* rtt_true, double alpha, int64_t index_blocks,
                               const double* w, double scale,
                               int32_t window, int32_t hop, const double* z,
                               const double* lo, const double* hi, double sigma0,
@@ -579,7 +587,7 @@ int gorgo_oracle_replay_proxy(int64_t N, const int64_t* ts_ms, const int32_t* in
     if (epochs < 1 || probe_ms < 1 || !rtt_true || !(alpha > 0.0) || !(alpha <= 1.0)) return -1;
     if (a_pf_r && (!a_dec_r || !(slowdown >= 0.0))) return -1;
     const Engine engine{a_pf_r, a_dec_r, kv_tokens, slowdown};
-    const Proxy proxy{epochs, probe_ms, rtt_true, alpha, stale_index};
+    const Proxy proxy{epochs, probe_ms, rtt_true, alpha, index_blocks};
     return replay_impl(N, ts_ms, in_len, out_len, blk_off, hash_ids, block_tokens, R, B, C, a_pf, a_dec, rtt_true, w,
                        scale, window, hop, nullptr, z, lo, hi, sigma0, 0, 0, a_pf_r ? &engine : nullptr, &proxy, rtt_est,
                        believed_hit, route, hit_blocks, ttft_ms, e2e_ms, p95, score_dbg, nullptr, nullptr, theta_step,

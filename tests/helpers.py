@@ -41,8 +41,9 @@ class ForcedRouteModel:
     evict from the cold end), the in-flight set a plain list scanned at each request: different data
     structures from the oracle's on purpose.  `w` is one weight vector, or one per request (a weight
     schedule dictated from outside, like the routes).  `proxy` = dict(rtt_true=[epochs][R], probe_ms=, alpha=,
-    stale_index=) switches on imperfect proxy knowledge: round trip times per probe epoch (scored through their
-    moving average), and scores that take their cached prefix from everything ever dispatched to a replica.
+    index_blocks=) switches on imperfect proxy knowledge: round trip times per probe epoch (scored through their
+    moving average), and, with index_blocks >= 0, scores that take their cached prefix from the proxy's own index
+    of each replica (a recency list like the replica's, with that capacity; 0 = it never forgets).
     """
 
     def __init__(self, trace, R, batch, cache_blocks, block_tokens, a_pf, a_dec, rtt, w, scale, proxy=None):
@@ -58,7 +59,7 @@ class ForcedRouteModel:
         consistent = True
         out = dict(score=[], hit=[], ttft=[], e2e=[], q=[], done=[], cnt=[], believed=[])
         px = self.proxy
-        seen = [set() for _ in range(self.R)]        # stale index: everything ever dispatched
+        seen = [[] for _ in range(self.R)]           # the proxy's own index: coldest first ... hottest last
         if px:
             true = [[float(x) for x in row] for row in px["rtt_true"]]
             est = [list(true[0])]
@@ -85,7 +86,7 @@ class ForcedRouteModel:
                     m += 1
                 u = L - min(L, self.bt * m)
                 ms_seen = m
-                if px and px["stale_index"]:
+                if px and px["index_blocks"] >= 0:
                     ms_seen = 0
                     while ms_seen < len(ids) and ids[ms_seen] in seen[i]:
                         ms_seen += 1
@@ -102,25 +103,28 @@ class ForcedRouteModel:
                 consistent = False
             # cache: evict cold entries that are not part of this request, then touch deepest block first
             # so that the root ends up hottest
-            mine = set(ids)
-            if self.C > 0:
-                n_new = len([x for x in mine if x not in lru[i]])
-                excess = len(lru[i]) + n_new - self.C
-                keep = []
-                for x in lru[i]:
-                    if excess > 0 and x not in mine:
-                        excess -= 1
-                    else:
-                        keep.append(x)
-                lru[i] = keep
-            first_pos = {}
-            for k, x in enumerate(ids):
-                first_pos.setdefault(x, k)
-            for x in sorted(first_pos, key=lambda x: -first_pos[x]):
-                if x in lru[i]:
-                    lru[i].remove(x)
-                lru[i].append(x)
-            seen[i].update(ids)
+            def touch(lst, cap):
+                mine = set(ids)
+                if cap > 0:
+                    n_new = len([x for x in mine if x not in lst])
+                    excess = len(lst) + n_new - cap
+                    keep = []
+                    for x in lst:
+                        if excess > 0 and x not in mine:
+                            excess -= 1
+                        else:
+                            keep.append(x)
+                    lst[:] = keep
+                first_pos = {}
+                for k, x in enumerate(ids):
+                    first_pos.setdefault(x, k)
+                for x in sorted(first_pos, key=lambda x: -first_pos[x]):
+                    if x in lst:
+                        lst.remove(x)
+                    lst.append(x)
+            touch(lru[i], self.C)
+            if px and px["index_blocks"] >= 0:
+                touch(seen[i], px["index_blocks"])
             half = 0.5 * rtt_real[i]
             a = t + half
             ks = min(range(self.B), key=lambda k: (free[i][k], k))

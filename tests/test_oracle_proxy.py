@@ -17,7 +17,7 @@ def test_hand_worked_trace():
     out = ob.replay_proxy(tr, R=m["R"], batch=m["batch"], cache_blocks=m["cache_blocks"], block_tokens=m["block_tokens"],
                           prefill_ms_per_token=m["prefill_ms_per_token"], decode_ms_per_token=m["decode_ms_per_token"],
                           rtt_true=px["rtt_true"], probe_ms=px["probe_ms"], alpha=px["alpha"],
-                          stale_index=px["stale_index"], w=g["w"], scale=g["scale"])
+                          index_blocks=px["index_blocks"], w=g["w"], scale=g["scale"])
     assert out.route.tolist() == e["route"] and out.hit_blocks.tolist() == e["hit_blocks"]
     assert out.believed_hit.tolist() == e["believed_hit"] and out.rtt_est.tolist() == e["rtt_est"]
     assert out.ttft_ms.tolist() == e["ttft_ms"] and out.e2e_ms.tolist() == e["e2e_ms"]
@@ -100,9 +100,15 @@ def test_reductions_to_the_plain_replay():
     # replicas that never evict: an index that never forgets is right
     kw0 = dict(kw, cache_blocks=0)
     a = ob.replay(wl.trace, rtt_ms=wl.rtt_ms, w=wl.params[0], scale=wl.scale[0], **kw0)
-    c = ob.replay_proxy(wl.trace, rtt_true=wl.rtt_ms[None, :], stale_index=True, w=wl.params[0], scale=wl.scale[0], **kw0)
+    c = ob.replay_proxy(wl.trace, rtt_true=wl.rtt_ms[None, :], index_blocks=0, w=wl.params[0], scale=wl.scale[0], **kw0)
     assert np.array_equal(a.route, c.route) and np.array_equal(c.believed_hit, c.hit_blocks)
     assert np.array_equal(a.ttft_ms, c.ttft_ms) and np.array_equal(a.e2e_ms, c.e2e_ms)
+    # an index with the replicas' own capacity evicts exactly what they evict
+    a = ob.replay(wl.trace, rtt_ms=wl.rtt_ms, w=wl.params[0], scale=wl.scale[0], **kw)
+    d = ob.replay_proxy(wl.trace, rtt_true=wl.rtt_ms[None, :], index_blocks=wl.cache_blocks, w=wl.params[0],
+                        scale=wl.scale[0], **kw)
+    assert np.array_equal(a.route, d.route) and np.array_equal(d.believed_hit, d.hit_blocks)
+    assert np.array_equal(a.ttft_ms, d.ttft_ms) and np.array_equal(a.e2e_ms, d.e2e_ms)
 
 
 @pytest.mark.parametrize("seed", range(6))
@@ -114,10 +120,11 @@ def test_forced_route_model_agrees(seed):
     tr = tg.random_small(20 + seed, 150, R, n_ids=25, max_blocks=5, gap_ms=int(rng.integers(5, 60)))
     E = 6
     true = np.round(rng.uniform(2.0, 200.0, (E, R)), 1)
-    px = dict(rtt_true=true.tolist(), probe_ms=700, alpha=float(rng.choice([0.125, 0.3, 1.0])), stale_index=bool(seed % 2 == 0))
+    px = dict(rtt_true=true.tolist(), probe_ms=700, alpha=float(rng.choice([0.125, 0.3, 1.0])),
+              index_blocks=[0, -1, 2 * C, C + 3, 0, 3 * C][seed])
     w = [1.0, 1.0, 0.5]
     out = ob.replay_proxy(tr, R=R, batch=B, cache_blocks=C, prefill_ms_per_token=0.05, decode_ms_per_token=3.0,
-                          rtt_true=true, probe_ms=700, alpha=px["alpha"], stale_index=px["stale_index"], w=w, scale=1.5,
+                          rtt_true=true, probe_ms=700, alpha=px["alpha"], index_blocks=px["index_blocks"], w=w, scale=1.5,
                           debug=True)
     fm = ForcedRouteModel(tr, R, B, C, 512, 0.05, 3.0, true[0], w, 1.5, proxy=px).run(out.route.tolist())
     assert fm["consistent"]
@@ -125,8 +132,8 @@ def test_forced_route_model_agrees(seed):
     np.testing.assert_allclose(fm["score"], out.score, rtol=1e-12)
     np.testing.assert_allclose(fm["ttft"], out.ttft_ms, rtol=1e-12)
     np.testing.assert_allclose(fm["e2e"], out.e2e_ms, rtol=1e-12)
-    if px["stale_index"]:
-        assert (out.believed_hit > out.hit_blocks).any()
+    if px["index_blocks"] >= 0:
+        assert (out.believed_hit >= out.hit_blocks).all() and (out.believed_hit > out.hit_blocks).any()
 
 
 def test_a_stale_index_only_overestimates_and_misleads():
@@ -134,8 +141,12 @@ def test_a_stale_index_only_overestimates_and_misleads():
     kw = dict(R=wl.R, batch=wl.batch, cache_blocks=wl.cache_blocks, prefill_ms_per_token=wl.prefill_ms_per_token,
               decode_ms_per_token=wl.decode_ms_per_token, rtt_true=wl.rtt_ms[None, :], w=[0.5, 1.0, 0.1], scale=4.0)
     good = ob.replay_proxy(wl.trace, **kw)
-    stale = ob.replay_proxy(wl.trace, stale_index=True, **kw)
+    stale = ob.replay_proxy(wl.trace, index_blocks=0, **kw)
     assert (stale.believed_hit >= stale.hit_blocks).all() and (stale.believed_hit > stale.hit_blocks).mean() > 0.1
     assert np.array_equal(good.believed_hit, good.hit_blocks)
     # the misled proxy routes differently and finds fewer blocks really cached
     assert (stale.route != good.route).any() and stale.hit_blocks.sum() < good.hit_blocks.sum()
+    # an index that forgets, but later than the replicas: still one-sided, and wrong less often
+    lag = ob.replay_proxy(wl.trace, index_blocks=2 * wl.cache_blocks, **kw)
+    assert (lag.believed_hit >= lag.hit_blocks).all()
+    assert 0 < (lag.believed_hit > lag.hit_blocks).sum() < (stale.believed_hit > stale.hit_blocks).sum()
