@@ -97,7 +97,7 @@ def cpu_baseline(wl, params, n_req, threads, online=None, engine=None, proxy=Non
                                    prefill_ms_per_token=wl.prefill_ms_per_token,
                                    decode_ms_per_token=wl.decode_ms_per_token, rtt_true=proxy.rtt_true_ms,
                                    probe_ms=proxy.probe_interval_ms, alpha=proxy.ewma_alpha,
-                                   stale_index=proxy.stale_index, w=params[p], scale=1.0).p95_ttft_ms
+                                   index_blocks=proxy.index_blocks, w=params[p], scale=1.0).p95_ttft_ms
         t0 = time.perf_counter()
         with ThreadPoolExecutor(threads) as ex:
             list(ex.map(one_proxy, range(threads)))
@@ -200,7 +200,7 @@ def main():
                          "generation -- not the headline metric")
     ap.add_argument("--proxy", action="store_true",
                     help="the proxy knows the replicas imperfectly (true round trip times wander per 30 s probe epoch and are "
-                         "scored through their moving average; its cache index never forgets: synth.tracegen.rtt_walk); "
+                         "scored through their moving average; its own cache index holds twice what a replica's cache holds: synth.tracegen.rtt_walk); "
                          "a step is still one ES generation -- not the headline metric")
     args = ap.parse_args()
     if args.engine + args.online + args.proxy > 1:
@@ -242,7 +242,7 @@ def main():
 
     if args.proxy:
         epochs = int(float(wl.trace.ts_ms[-1]) // 30000) + 1 if N else 1
-        proxy = g.Proxy(tg.rtt_walk(wl, epochs), 30000, 0.3, True)
+        proxy = g.Proxy(tg.rtt_walk(wl, epochs), 30000, 0.3, 2 * wl.cache_blocks)
 
     def generation():
         if args.proxy:
@@ -333,7 +333,7 @@ def main():
     if args.engine:
         mode += ", replicas under the engine model (uneven rates, KV-token budget, decode slow-down)"
     if args.proxy:
-        mode += ", imperfect proxy knowledge (RTT random walk per 30 s epoch scored through an EWMA with alpha 0.3, stale index)"
+        mode += ", imperfect proxy knowledge (RTT random walk per 30 s epoch scored through an EWMA with alpha 0.3, proxy cache index of twice the replicas' capacity)"
     out = {
         "metric": "candidate-request routings/sec at P=1024" + (" (online tuner)" if args.online else "") +
                   (" (engine model of a replica)" if args.engine else "") +

@@ -282,18 +282,21 @@ int gorgo_eval_engine(const gorgo_trace* t, const gorgo_model* m, const gorgo_en
  *     time rtt_true_ms[e][i] on replica i (half of it each way);
  *   - the proxy probes at the start of every epoch: est[0] = rtt_true_ms[0], est[e] = ewma_alpha * rtt_true_ms[e]
  *     + (1 - ewma_alpha) * est[e-1]; Eq. 3 scores with est of the request's epoch;
- *   - stale_index = 1: Eq. 3 takes the uncached tokens of replica i from the longest prefix of the request that
- *     was ever dispatched to i (a prefix trie of dispatched requests that never forgets), while the replica
- *     prefills what its own bounded LRU cache really misses; hit_blocks stays the real count.
- * With one epoch (or equal rows) and stale_index = 0 the results equal gorgo_eval_population's bit for bit.
+ *   - index_blocks >= 0: the proxy keeps an index of its own of what it dispatched to replica i (a prefix trie of
+ *     dispatched requests), updated like the replica's cache (least recently used block first) but with its own
+ *     capacity: index_blocks per replica (at least gorgo_model.cache_blocks), 0 = it never forgets.  Eq. 3 takes
+ *     the uncached tokens of replica i from the longest prefix of the request in that index, while the replica
+ *     prefills what its own cache really misses; hit_blocks stays the real count.  index_blocks = -1: the proxy
+ *     sees the replicas' caches as they are.
+ * With one epoch (or equal rows) and index_blocks = -1 or = cache_blocks the results equal
+ * gorgo_eval_population's bit for bit.
  * Needs a chain-consistent trace. */
 typedef struct gorgo_proxy {
     int32_t epochs;               /* 1..65536 probe epochs given                                              */
     int32_t probe_interval_ms;    /* >= 1                                                                     */
     const double* rtt_true_ms;    /* host [epochs][R], finite, 0..1e9                                         */
     double ewma_alpha;            /* in (0, 1]                                                                */
-    int32_t stale_index;          /* 0 or 1                                                                   */
-    int32_t _pad;
+    int64_t index_blocks;         /* -1, 0, or cache_blocks..2^30 (only 0 or -1 when cache_blocks is 0)       */
     double* rtt_tables;           /* DEVICE [2][epochs][R], caller-owned, written: [0] a copy of rtt_true_ms,
                                      [1] the proxy's estimates; must stay valid until the stream has run      */
     uint16_t* believed_hit_blocks;/* DEVICE [P][N] or NULL: blocks Eq. 3 took for cached on the chosen replica */

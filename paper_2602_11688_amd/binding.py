@@ -44,7 +44,7 @@ class _Engine(C.Structure):
 
 class _Proxy(C.Structure):
     _fields_ = [("epochs", C.c_int32), ("probe_interval_ms", C.c_int32), ("rtt_true_ms", C.c_void_p),
-                ("ewma_alpha", C.c_double), ("stale_index", C.c_int32), ("_pad", C.c_int32), ("rtt_tables", C.c_void_p),
+                ("ewma_alpha", C.c_double), ("index_blocks", C.c_int64), ("rtt_tables", C.c_void_p),
                 ("believed_hit_blocks", C.c_void_p)]
 
 
@@ -466,11 +466,12 @@ def eval_engine(trace: Trace, model: Model, engine: Engine, rtt_ms, scale, *, pa
 @dataclass
 class Proxy:
     """Imperfect proxy knowledge (gorgo_proxy): true round trip times per probe epoch [epochs, R], the probe
-    interval, the smoothing constant of the proxy's moving average, and whether its cache index never forgets."""
+    interval, the smoothing constant of the proxy's moving average, and the capacity of its own cache index in blocks
+    per replica (0 = it never forgets, -1 = it sees the replicas' caches as they are)."""
     rtt_true_ms: Sequence[Sequence[float]]
     probe_interval_ms: int = 30000
     ewma_alpha: float = 0.5
-    stale_index: bool = False
+    index_blocks: int = -1
 
 
 def eval_proxy(trace: Trace, model: Model, proxy: Proxy, params, scale, *, engine: Optional[Engine] = None,
@@ -503,7 +504,7 @@ def eval_proxy(trace: Trace, model: Model, proxy: Proxy, params, scale, *, engin
         res.p95_e2e_ms = torch.empty((P,), dtype=torch.float64, device=dev)
     tables = torch.empty((2, E, model.R), dtype=torch.float64, device=dev)
     res.rtt_est_ms = tables[1]
-    px = _Proxy(E, int(proxy.probe_interval_ms), _ptr(rt), float(proxy.ewma_alpha), int(bool(proxy.stale_index)), 0,
+    px = _Proxy(E, int(proxy.probe_interval_ms), _ptr(rt), float(proxy.ewma_alpha), int(proxy.index_blocks),
                 C.c_void_p(tables.data_ptr()),
                 None if res.believed_hit_blocks is None else C.c_void_p(res.believed_hit_blocks.data_ptr()))
     eng = None

@@ -169,7 +169,11 @@ int evaluate(const gorgo_trace* t, const gorgo_model* m, const double* rtt_ms, c
         if (!proxy->rtt_true_ms || !proxy->rtt_tables) return fail(GORGO_ERR_INVALID_ARG, "the proxy's round trip time tables are NULL");
         if (!(proxy->ewma_alpha > 0.0) || !(proxy->ewma_alpha <= 1.0))
             return fail(GORGO_ERR_NONFINITE, "ewma_alpha must be in (0, 1]");
-        if (proxy->stale_index != 0 && proxy->stale_index != 1) return fail(GORGO_ERR_INVALID_ARG, "stale_index must be 0 or 1");
+        if (proxy->index_blocks < -1 || proxy->index_blocks > ((int64_t)1 << 30))
+            return fail(GORGO_ERR_INVALID_ARG, "index_blocks must be -1 (none), 0 (never forgets) or a capacity up to 2^30");
+        if (proxy->index_blocks > 0 && (m->cache_blocks == 0 || proxy->index_blocks < m->cache_blocks))
+            return fail(GORGO_ERR_INVALID_ARG, "an index of its own must hold at least cache_blocks (the replicas' caches are " +
+                                                   std::string(m->cache_blocks == 0 ? "unbounded" : "larger") + ")");
         for (int64_t j = 0; j < (int64_t)proxy->epochs * m->R; ++j)
             if (!std::isfinite(proxy->rtt_true_ms[j]) || proxy->rtt_true_ms[j] < 0 || proxy->rtt_true_ms[j] > 1e9)
                 return fail(GORGO_ERR_NONFINITE, "rtt_true_ms[" + std::to_string(j / m->R) + "][" + std::to_string(j % m->R) +
@@ -282,7 +286,7 @@ int evaluate(const gorgo_trace* t, const gorgo_model* m, const double* rtt_ms, c
         xl.rtt_true = proxy->rtt_tables;
         xl.rtt_est = proxy->rtt_tables + cells;
         xl.alpha = proxy->ewma_alpha;
-        xl.stale_index = proxy->stale_index;
+        xl.index_blocks = proxy->index_blocks;
         xl.believed = proxy->believed_hit_blocks;
     }
     PolicyLaunch pol;

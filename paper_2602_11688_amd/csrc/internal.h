@@ -111,7 +111,7 @@ struct ProxyLaunch {
     const double* rtt_true = nullptr;    // [epochs][R]
     double* rtt_est = nullptr;           // [epochs][R], written by the launch before the replay
     double alpha = 1.0;
-    int32_t stale_index = 0;
+    int64_t index_blocks = -1;
     uint16_t* believed = nullptr;        // [P][N], nullable
 };
 

@@ -561,7 +561,7 @@ int launch_replay(const gorgo_trace* t, const Plan& pl, const double* d_rtt, con
         a.probe_ms = proxy ? proxy->probe_ms : 0;
         a.rtt_true = proxy ? proxy->rtt_true : nullptr;
         a.rtt_est = proxy ? proxy->rtt_est : nullptr;
-        a.stale_index = proxy ? proxy->stale_index : 0;
+        a.index_blocks = proxy ? proxy->index_blocks : -1;
         a.believed = proxy ? proxy->believed : nullptr;
         if (proxy) {
             if (policy && policy->policy != 0)

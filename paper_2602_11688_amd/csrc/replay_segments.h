@@ -88,7 +88,8 @@ struct SegArgs {
     int32_t epochs, probe_ms;     // probe epochs given, and their length
     const double* rtt_true;       // [epochs][R] round trip time a request dispatched in the epoch experiences
     const double* rtt_est;        // [epochs][R] the proxy's moving average of them: what Eq. 3 scores with
-    int32_t stale_index;          // 1: Eq. 3 takes its cached prefix from everything ever dispatched to the replica
+    int64_t index_blocks;         // >= 0: Eq. 3 takes its cached prefix from the proxy's own index (an LRU of this
+                                  // many blocks per replica, 0 = it never forgets); < 0: from the replica's cache
     uint16_t* believed;           // [P][N] blocks the proxy believed cached on the chosen replica, nullable
 };
 
@@ -410,6 +411,124 @@ __device__ __forceinline__ void queue_wave(const SegArgs& a, int p, int lane, un
     }
 }
 
+// Eviction cursor of one LRU over a replica's log of routed requests, held by lane = replica.
+//   cursor: blocks last touched by a request before cur_r, or by cur_r at positions >= cur_k, are evicted;
+//   cur_own is where cur_r's owned suffix starts.
+//   nx_*, n2_*: the next two records of the replica's log that still own blocks (r < 0: empty).
+//   fill_r: the record after the last one held here, or -1 when that one is the youngest of the log.
+//   pend_*: a record being fetched (its load is only waited for one iteration later); changes made to it
+//   meanwhile are kept in pend_own / pend_next and override the loaded fields.
+// The kernel keeps the cursor of the replica's cache in plain local variables of the same names (the compiler
+// does measurably better with them); this struct is the same machinery for the proxy's own index of the replica,
+// an LRU of another capacity over the same log.
+struct EvictCursor {
+    int cur_r = -1, cur_k = 0, cur_own = 0;
+    int nx_r = -1, nx_n = 0, nx_own = 0;
+    int n2_r = -1, n2_n = 0, n2_own = 0;
+    int fill_r = -1;
+    int pend_r = -1, pend_own = -1, pend_next = -1;
+    unsigned long long pend_raw = 0;
+    int live = 0;             // blocks this LRU holds
+
+    // the fetched record becomes usable: dropped if it owns nothing, else queued behind nx / n2
+    __device__ __forceinline__ void take_pending(unsigned long long raw) {
+        if (pend_r >= 0) {
+            const int n = (int)(raw >> 48);
+            const int own_mem = (int)((raw >> 32) & 0xFFFF);
+            const int own = pend_own > own_mem ? pend_own : own_mem;
+            const int next = pend_next >= 0 ? pend_next : (int)(unsigned int)raw;
+            if (own < n) {
+                if (nx_r < 0) {
+                    nx_r = pend_r;
+                    nx_n = n;
+                    nx_own = own;
+                } else {
+                    n2_r = pend_r;
+                    n2_n = n;
+                    n2_own = own;
+                }
+            }
+            fill_r = next;
+            pend_r = -1;
+        }
+    }
+    // fetch the next record of the log if there is room for it
+    __device__ __forceinline__ void issue_fill(const unsigned long long* log64) {
+        if (pend_r < 0 && fill_r >= 0 && n2_r < 0) {
+            pend_r = fill_r;
+            pend_own = -1;
+            pend_next = -1;
+            pend_raw = ld(&log64[fill_r]);
+        }
+    }
+    // request `owner`'s owned suffix now starts at `end`
+    __device__ __forceinline__ void disowned(int owner, int end) {
+        cur_own = owner == cur_r ? end : cur_own;
+        nx_own = owner == nx_r ? end : nx_own;
+        n2_own = owner == n2_r ? end : n2_own;
+        pend_own = owner == pend_r ? end : pend_own;
+    }
+    // request r (n blocks) has become the youngest record of the log of the replica whose lane has is_best set;
+    // tail_r is the youngest before it
+    __device__ __forceinline__ void appended(bool is_best, int r, int n, int tail_r) {
+        const bool first = is_best && tail_r < 0;
+        const bool to_pend = is_best && pend_r >= 0 && pend_r == tail_r;
+        const bool to_fill = is_best && !first && !to_pend && pend_r < 0 && fill_r < 0;
+        cur_r = first ? r : cur_r;
+        cur_k = first ? n : cur_k;
+        cur_own = first ? 0 : cur_own;
+        pend_next = to_pend ? r : pend_next;
+        fill_r = to_fill ? r : fill_r;
+    }
+    // `added` blocks have joined the LRU of the lane with `active` set; the cursor moves forward until the LRU
+    // fits `cap` blocks again.  Up to two steps come from the records held in registers; more (rare) are
+    // fetched on the spot.
+    __device__ __forceinline__ void evict(bool active, int added, int cap, const unsigned long long* log64) {
+        live += active ? added : 0;
+        int E = active ? live - cap : 0;
+        E = E > 0 ? E : 0;
+        live -= E;
+        if (__ballot(E > 0) != 0) {
+            {
+                int avail = cur_k - cur_own;
+                avail = avail > 0 ? avail : 0;
+                const int take = avail < E ? avail : E;
+                cur_k -= take;
+                E -= take;
+            }
+            while (E > 0) {       // only the chosen replica's lane can be here
+                if (nx_r < 0) {
+                    // fetch a record on the spot; pend_raw itself is only ever written by the look-ahead
+                    // fetch, so that its load is never waited for in here
+                    unsigned long long raw = pend_raw;
+                    if (pend_r < 0) {
+                        if (fill_r < 0) break;      // cannot happen while E > 0; bounds the loop
+                        pend_r = fill_r;
+                        pend_own = -1;
+                        pend_next = -1;
+                        raw = ld(&log64[fill_r]);
+                    }
+                    take_pending(raw);
+                    continue;
+                }
+                cur_r = nx_r;
+                cur_k = nx_n;
+                cur_own = nx_own;
+                nx_r = n2_r;
+                nx_n = n2_n;
+                nx_own = n2_own;
+                n2_r = -1;
+                int avail = cur_k - cur_own;
+                avail = avail > 0 ? avail : 0;
+                const int take = avail < E ? avail : E;
+                cur_k -= take;
+                E -= take;
+            }
+            live += E;            // nothing left to evict (unreachable, kept consistent)
+        }
+    }
+};
+
 template <int MODE, bool ENGINE, bool PROXY>
 __global__ void __launch_bounds__(SEG_THREADS) replay_segments_kernel(SegArgs a) {
     constexpr bool ONLINE = MODE == MODE_ONLINE;
@@ -446,11 +565,16 @@ __global__ void __launch_bounds__(SEG_THREADS) replay_segments_kernel(SegArgs a)
     const double w_prefill = a.params[3 * (size_t)p + 1];
     const double w_queue = a.params[3 * (size_t)p + 2];
     const double my_rtt = !PROXY && lane < R ? a.rtt[lane] : 0.0;     // (proxy variants: comes with the load signals)
-    // Proxy variants (Sec. 7: the proxy does not see replica-side eviction): besides the replica's real cached
-    // prefix, the prefix that was ever dispatched to the replica is matched (cells >= 0); with a stale index Eq. 3
-    // scores with the latter.  Ownership is then kept for everything ever dispatched, a superset of what is
-    // cached, which the eviction walk does not mind: records behind the cursor are never looked at again.
-    const bool stale = PROXY && a.stale_index != 0;
+    // Proxy variants (Sec. 7: the proxy does not see replica-side eviction): the proxy keeps an index of its own
+    // of what it dispatched to each replica, an LRU like the replica's cache but at least as large (or unbounded).
+    // It sees the same touches, so it is the same rows read against a second eviction cursor (c2), which lags
+    // the replica's; the match loop yields both prefixes, Eq. 3 scores with the index's.  Ownership is kept for
+    // what the index holds, a superset of what is cached, which the replica's eviction walk does not mind:
+    // records behind its cursor are never looked at again.  While the index never forgets (or is not used) its
+    // cursor stays at the replica's first record and "in the index" means "ever dispatched here".
+    const bool own_index = PROXY && a.index_blocks >= 0;
+    const int index_cap = PROXY && a.index_blocks > 0 ? (int)a.index_blocks : 0;
+    EvictCursor c2;                           // the index's cursor, as cur_* etc. below
 
     // Per-replica eviction state, held by lane = replica.
     //   cursor: blocks last touched by a request before cur_r, or by cur_r at positions >= cur_k, are
@@ -583,8 +707,8 @@ __global__ void __launch_bounds__(SEG_THREADS) replay_segments_kernel(SegArgs a)
             // last segment whose cell is above, respectively not below, the cursor's request.
             int e_gt = 0, e_ge = 0;
             int32_t own_gt = -1;        // previous owner of the last segment counted in e_gt
-            int e_any = 0;              // proxy variants: end of the last segment ever dispatched to this replica ...
-            int32_t own_any = -1;       // ... and its previous owner
+            int e_gt2 = 0, e_ge2 = 0;   // proxy variants: the same against the index's cursor
+            int32_t own_gt2 = -1;
 #pragma unroll
             for (int k = 0; k < SEG_CHUNK; ++k) {
                 if (k >= s) break;
@@ -594,21 +718,26 @@ __global__ void __launch_bounds__(SEG_THREADS) replay_segments_kernel(SegArgs a)
                 own_gt = gt ? mine.cell[k] : own_gt;
                 e_ge = ge ? mine.end[k] : e_ge;
                 if (PROXY) {
-                    const bool any = mine.cell[k] >= 0;
-                    e_any = any ? mine.end[k] : e_any;
-                    own_any = any ? mine.cell[k] : own_any;
+                    const bool gt2 = mine.cell[k] > c2.cur_r;
+                    const bool ge2 = mine.cell[k] >= c2.cur_r;
+                    e_gt2 = gt2 ? mine.end[k] : e_gt2;
+                    own_gt2 = gt2 ? mine.cell[k] : own_gt2;
+                    e_ge2 = ge2 ? mine.end[k] : e_ge2;
                 }
             }
             const int below_cursor = cur_k < e_ge ? cur_k : e_ge;
             const bool some_eq = below_cursor > e_gt;       // blocks of the cursor's own request are matched
             int my_m = some_eq ? below_cursor : e_gt;
-            int my_seen = PROXY ? e_any : 0;                // blocks ever dispatched here (>= my_m)
+            const int below_cursor2 = c2.cur_k < e_ge2 ? c2.cur_k : e_ge2;
+            const bool some_eq2 = below_cursor2 > e_gt2;
+            int my_seen = PROXY ? (some_eq2 ? below_cursor2 : e_gt2) : 0;       // blocks in the proxy's index (>= my_m)
             // For the ownership update below: where the cached prefix ends on this replica (rounded up to the
             // end of a segment that the cursor's request owns: what lies beyond the cursor is evicted anyway)
             // and whether all cached segments had the same previous owner.  (Proxy variants: the same for the
-            // prefix ever dispatched.)
-            const int k_end = PROXY ? e_any : (some_eq ? e_ge : e_gt);
-            const bool one_owner = PROXY ? own_any == mine.cell[0] : (some_eq ? e_gt == 0 : own_gt == mine.cell[0]);
+            // prefix in the index.)
+            const int k_end = PROXY ? (some_eq2 ? e_ge2 : e_gt2) : (some_eq ? e_ge : e_gt);
+            const bool one_owner = PROXY ? (some_eq2 ? e_gt2 == 0 : own_gt2 == mine.cell[0])
+                                         : (some_eq ? e_gt == 0 : own_gt == mine.cell[0]);
             int pos = mine.end[SEG_CHUNK - 1];
             bool open = my_m == pos;
             bool open_seen = PROXY && my_seen == pos;
@@ -635,7 +764,7 @@ __global__ void __launch_bounds__(SEG_THREADS) replay_segments_kernel(SegArgs a)
                             my_m += open ? cnt : 0;
                             open = open && cnt == send[k] - pos;
                             if (PROXY) {
-                                const int cnt_seen = cell[k] >= 0 ? send[k] - pos : 0;
+                                const int cnt_seen = cached_in(cell[k], pos, send[k], c2.cur_r, c2.cur_k);
                                 my_seen += open_seen ? cnt_seen : 0;
                                 open_seen = open_seen && cnt_seen == send[k] - pos;
                             }
@@ -649,8 +778,10 @@ __global__ void __launch_bounds__(SEG_THREADS) replay_segments_kernel(SegArgs a)
             // ---- the single point of the iteration that waited for memory is behind us: the record fetched
             // during the previous iteration becomes usable, and the loads for the next iteration go out
             take_pending(pend_raw);
+            if (PROXY && index_cap > 0) c2.take_pending(c2.pend_raw);
             if (i + 1 < nb) request_rows(i + 1, ref, other);
             issue_fill();
+            if (PROXY && index_cap > 0) c2.issue_fill(log64);
 
             // ---- score (Eq. 3) and lowest-index minimum
             int hit_tok = a.block_tokens * my_m;           // block_tokens * blocks fits: both are below 2^16
@@ -658,7 +789,7 @@ __global__ void __launch_bounds__(SEG_THREADS) replay_segments_kernel(SegArgs a)
             int my_u = L - hit_tok;
             int my_u_seen = my_u;       // uncached tokens as Eq. 3 sees them
             if (PROXY) {
-                int seen_tok = a.block_tokens * (stale ? my_seen : my_m);
+                int seen_tok = a.block_tokens * (own_index ? my_seen : my_m);
                 seen_tok = seen_tok > L ? L : seen_tok;
                 my_u_seen = L - seen_tok;
             }
@@ -727,6 +858,7 @@ __global__ void __launch_bounds__(SEG_THREADS) replay_segments_kernel(SegArgs a)
                 nx_own = owner == nx_r ? end : nx_own;
                 n2_own = owner == n2_r ? end : n2_own;
                 pend_own = owner == pend_r ? end : pend_own;
+                if (PROXY) c2.disowned(owner, end);
             };
             if (seen_best > 0) {
                 const bool simple = !deep && __builtin_amdgcn_readlane((int)one_owner, best) != 0;
@@ -734,13 +866,13 @@ __global__ void __launch_bounds__(SEG_THREADS) replay_segments_kernel(SegArgs a)
                     if (is_best) disown(mine.cell[0], k_end);
                 } else {
                     // several previous owners, or a prefix longer than the preloaded rows: walk it
-                    const int cb_r = __builtin_amdgcn_readlane(cur_r, best);
-                    const int cb_k = __builtin_amdgcn_readlane(cur_k, best);
+                    const int cb_r = __builtin_amdgcn_readlane(PROXY ? c2.cur_r : cur_r, best);
+                    const int cb_k = __builtin_amdgcn_readlane(PROXY ? c2.cur_k : cur_k, best);
                     int run_owner = -1, run_end = 0, vpos = 0;
                     for (int j = 0; j < s; ++j) {
                         const SegRef sr = ref(a0 + j, true);
                         const int32_t rl = ld(&last[(size_t)sr.id * R + best]);
-                        const int cnt = PROXY ? (rl >= 0 ? sr.end - vpos : 0) : cached_in(rl, vpos, sr.end, cb_r, cb_k);
+                        const int cnt = cached_in(rl, vpos, sr.end, cb_r, cb_k);
                         if (cnt > 0) {
                             if (rl != run_owner) {
                                 if (run_owner >= 0 && is_best) disown(run_owner, run_end);
@@ -774,6 +906,7 @@ __global__ void __launch_bounds__(SEG_THREADS) replay_segments_kernel(SegArgs a)
                 cur_r = first ? (int)r : cur_r;
                 cur_k = first ? n : cur_k;
                 cur_own = first ? 0 : cur_own;
+                if (PROXY) c2.appended(is_best, (int)r, n, tail_r);
                 pend_next = to_pend ? (int)r : pend_next;
                 fill_r = to_fill ? (int)r : fill_r;
                 tail_r = is_best ? (int)r : tail_r;
@@ -822,6 +955,9 @@ __global__ void __launch_bounds__(SEG_THREADS) replay_segments_kernel(SegArgs a)
                     }
                     my_live += E;         // nothing left to evict (unreachable, kept consistent)
                 }
+                // the proxy's index evicts under its own capacity: its cursor walks the same log (whose memory
+                // is up to date: ownership changes and links are stored as they happen)
+                if (PROXY && index_cap > 0) c2.evict(is_best, n - seen_best, index_cap, log64);
             }
 
             // ---- the rows of request i+1 were requested before this request's stores: if it continues the
@@ -839,7 +975,7 @@ __global__ void __launch_bounds__(SEG_THREADS) replay_segments_kernel(SegArgs a)
             // ---- outputs of the cache side (kept in registers until the batch ends)
             if (a.route) o_route = lane == i ? best : o_route;
             if (a.hit) o_hit = lane == i ? m_best : o_hit;
-            if (PROXY && a.believed) o_believed = lane == i ? (stale ? seen_best : m_best) : o_believed;
+            if (PROXY && a.believed) o_believed = lane == i ? (own_index ? seen_best : m_best) : o_believed;
         };
 
         RowSet A, Bset;

@@ -201,19 +201,22 @@ def test_proxy_entry_point_rejects_bad_arguments_before_touching_a_device():
     o = gb._Outputs()
     ok = np.tile([10.0, 40.0, 120.0, 300.0], (3, 1))
 
-    def proxy(rt=ok, epochs=3, probe=30000, alpha=0.5, stale=1, tables=C.c_void_p(256), null=False, par=par, tr=t, mm=m):
-        x = gb._Proxy(epochs, probe, gb._ptr(rt), alpha, stale, 0, tables, None)
+    def proxy(rt=ok, epochs=3, probe=30000, alpha=0.5, index=0, tables=C.c_void_p(256), null=False, par=par, tr=t, mm=m):
+        x = gb._Proxy(epochs, probe, gb._ptr(rt), alpha, index, tables, None)
         return L.gorgo_eval_proxy(tr._h, C.byref(mm), None if null else C.byref(x), None, gb._ptr(par), None, gb._ptr(sc), 2,
                                   C.byref(o), None, 1 << 40, None)
     assert proxy(null=True) == -1 and proxy(rt=None) == -1 and proxy(tables=None) == -1
-    assert proxy(epochs=0) == -1 and proxy(epochs=1 << 20) == -1 and proxy(probe=0) == -1 and proxy(stale=2) == -1
+    assert proxy(epochs=0) == -1 and proxy(epochs=1 << 20) == -1 and proxy(probe=0) == -1 and proxy(index=-2) == -1
+    assert proxy(index=500) == -1                                     # the replicas' caches are unbounded here
     assert proxy(alpha=0.0) == -6 and proxy(alpha=1.5) == -6 and proxy(alpha=float("nan")) == -6
     bad_rt = ok.copy()
     bad_rt[2, 1] = -1.0
     assert proxy(rt=bad_rt) == -6
     assert b"rtt_true_ms[2][1]" in L.gorgo_last_error()
     assert proxy(par=None) == -1
-    assert proxy() == -7 and proxy(epochs=1, alpha=1.0, stale=0) == -7           # everything valid up to the workspace
+    assert proxy() == -7 and proxy(epochs=1, alpha=1.0, index=-1) == -7           # everything valid up to the workspace
+    mc = g.Model(4, 8, 200, 0.05, 20.0).c()
+    assert proxy(index=199, mm=mc) == -1 and proxy(index=200, mm=mc) == -7 and proxy(index=1000, mm=mc) == -7
     bad = _trace(tg.random_small(3, 50, 2, consistent=False))
     mb = g.Model(2, 2, 0, 0.05, 20.0).c()
     assert proxy(rt=ok[:, :2].copy(), tr=bad, mm=mb) == -1                        # needs a chain-consistent trace

@@ -102,14 +102,14 @@ def test_large_workload_under_the_engine_model_matches_oracle():
 
 def test_large_workload_with_imperfect_proxy_knowledge_matches_oracle():
     """The same launch shape with round trip times that wander per 30 s probe epoch (scored through their moving
-    average) and a proxy cache index that never forgets: 18 replays against the oracle in full."""
+    average) and a proxy cache index of twice the replicas' capacity: 18 replays against the oracle in full."""
     import torch
     wl = tg.config(5)
     es_cfg = wl.es if wl.es else dict(tg.ES_DEFAULTS, P=wl.P, seed=tg.MASTER_SEED + 5)
     P = es_cfg["P"]
     model = g.Model(wl.R, wl.batch, wl.cache_blocks, wl.prefill_ms_per_token, wl.decode_ms_per_token)
     epochs = int(float(wl.trace.ts_ms[-1]) // 30000) + 1
-    px = g.Proxy(tg.rtt_walk(wl, epochs), 30000, 0.3, True)
+    px = g.Proxy(tg.rtt_walk(wl, epochs), 30000, 0.3, 2 * wl.cache_blocks)
     h = load(wl.trace)
     state = g.es_init(es_cfg["seed"])
     params = g.es_propose(state, g.es_sample(es_cfg["seed"], 0, P))
@@ -119,7 +119,7 @@ def test_large_workload_with_imperfect_proxy_knowledge_matches_oracle():
     def oracle(p):
         return ob.replay_proxy(wl.trace, R=wl.R, batch=wl.batch, cache_blocks=wl.cache_blocks,
                                prefill_ms_per_token=wl.prefill_ms_per_token, decode_ms_per_token=wl.decode_ms_per_token,
-                               rtt_true=px.rtt_true_ms, probe_ms=30000, alpha=0.3, stale_index=True, w=params[p], scale=1.0)
+                               rtt_true=px.rtt_true_ms, probe_ms=30000, alpha=0.3, index_blocks=px.index_blocks, w=params[p], scale=1.0)
     with ThreadPoolExecutor(16) as ex:
         futs = {p: ex.submit(oracle, p) for p in picks}
         full = g.eval_proxy(h, model, px, params, 1.0)

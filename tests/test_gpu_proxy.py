@@ -28,7 +28,7 @@ def _oracle(tr, model, px, w, scale, engine=None, online=None):
     return ob.replay_proxy(tr, R=model.R, batch=model.batch, cache_blocks=model.cache_blocks,
                            prefill_ms_per_token=model.prefill_ms_per_token, decode_ms_per_token=model.decode_ms_per_token,
                            block_tokens=model.block_tokens, rtt_true=px.rtt_true_ms, probe_ms=px.probe_interval_ms,
-                           alpha=px.ewma_alpha, stale_index=px.stale_index, engine=e, w=w, scale=scale, online=online)
+                           alpha=px.ewma_alpha, index_blocks=px.index_blocks, engine=e, w=w, scale=scale, online=online)
 
 
 def check_proxy(tr, model, px, params, scale, engine=None, label="proxy", handle=None):
@@ -63,7 +63,7 @@ def test_hand_worked_trace():
     m, x, e = gold["model"], gold["proxy"], gold["expected"]
     model = g.Model(m["R"], m["batch"], m["cache_blocks"], m["prefill_ms_per_token"], m["decode_ms_per_token"],
                     block_tokens=m["block_tokens"])
-    px = g.Proxy(x["rtt_true"], x["probe_ms"], x["alpha"], x["stale_index"])
+    px = g.Proxy(x["rtt_true"], x["probe_ms"], x["alpha"], x["index_blocks"])
     h = g.Trace.from_arrays(tr.ts_ms, tr.in_len, tr.out_len, tr.blk_off, tr.hash_ids, block_tokens=m["block_tokens"])
     got = _numpy(g.eval_proxy(h, model, px, [gold["w"]], [gold["scale"]]))
     assert got["route"][0].tolist() == e["route"] and got["hit"][0].tolist() == e["hit_blocks"]
@@ -72,27 +72,35 @@ def test_hand_worked_trace():
     assert got["p95_ttft"][0] == e["p95_ttft_ms"] and got["p95_e2e"][0] == e["p95_e2e_ms"]
 
 
-def test_equals_the_plain_replay_with_perfect_knowledge():
+@pytest.mark.parametrize("index", [-1, "cache"])
+def test_equals_the_plain_replay_with_perfect_knowledge(index):
+    """Constant round trip times and either no index of its own or one exactly as large as the replicas' caches."""
     import torch
     wl = tg.config(2, 8000)
     model = _model(wl)
+    index = wl.cache_blocks if index == "cache" else index
     h = load(wl.trace)
     plain = g.eval_population(h, model, wl.rtt_ms, wl.params[:6], wl.scale[:6])
-    res = g.eval_proxy(h, model, g.Proxy(np.tile(wl.rtt_ms, (4, 1)), 5000, 0.3, False), wl.params[:6], wl.scale[:6])
+    res = g.eval_proxy(h, model, g.Proxy(np.tile(wl.rtt_ms, (4, 1)), 5000, 0.3, index), wl.params[:6], wl.scale[:6])
     torch.cuda.synchronize()
     for name in ("route", "hit_blocks", "ttft_ms", "e2e_ms", "p95_ttft_ms", "p95_e2e_ms"):
         assert torch.equal(getattr(plain, name), getattr(res, name)), name
     assert torch.equal(res.believed_hit_blocks, res.hit_blocks)
 
 
-@pytest.mark.parametrize("stale", [False, True])
+@pytest.mark.parametrize("index", ["none", "unbounded", "double", "tight"])
 @pytest.mark.parametrize("cfg,head", [(1, None), (2, 8000), (3, 6000)])
-def test_workloads(cfg, head, stale):
+def test_workloads(cfg, head, index):
     wl = tg.config(cfg, head)
+    C = wl.cache_blocks
+    if C == 0 and index in ("double", "tight"):
+        pytest.skip("replicas that never evict leave no room for an index that forgets later")
+    stale = index != "none"
+    index = {"none": -1, "unbounded": 0, "double": 2 * C, "tight": C + 1}[index]
     horizon = float(wl.trace.ts_ms[-1]) * float(max(wl.scale[:4]))
     probe = max(1, int(horizon / 12))
-    px = g.Proxy(_wander(wl.rtt_ms, 10, cfg), probe, 0.3, stale)     # the last epochs repeat the tenth
-    got = check_proxy(wl.trace, _model(wl), px, wl.params[:4], wl.scale[:4], label=f"config {cfg} stale={stale}")
+    px = g.Proxy(_wander(wl.rtt_ms, 10, cfg), probe, 0.3, index)     # the last epochs repeat the tenth
+    got = check_proxy(wl.trace, _model(wl), px, wl.params[:4], wl.scale[:4], label=f"config {cfg} index={index}")
     if stale and wl.cache_blocks > 0:
         assert (got["believed"] > got["hit"]).any()
 
@@ -102,7 +110,7 @@ def test_epoch_boundaries_and_time_scales():
     model = g.Model(3, 2, 14, 0.05, 5.0)
     true = _wander([10.0, 60.0, 25.0], 40, 9, amount=1.0)
     for probe in (1, 50, 333):
-        check_proxy(tr, model, g.Proxy(true, probe, 0.5, True), [[1.0, 1.0, 0.2]] * 4, [1.0, 0.37, 2.5, 0.0], label=f"probe {probe}")
+        check_proxy(tr, model, g.Proxy(true, probe, 0.5, [0, 20, 14][probe % 3]), [[1.0, 1.0, 0.2]] * 4, [1.0, 0.37, 2.5, 0.0], label=f"probe {probe}")
 
 
 def test_with_the_engine_model_and_the_online_tuner():
@@ -111,7 +119,7 @@ def test_with_the_engine_model_and_the_online_tuner():
     model = _model(wl, cache_blocks=600)
     recipe = tg.engine_recipe(wl)
     engine = g.Engine(recipe["prefill_ms_per_token"], recipe["decode_ms_per_token"], recipe["kv_tokens"], 0.2)
-    px = g.Proxy(_wander(wl.rtt_ms, 8, 4), 20000, 0.4, True)
+    px = g.Proxy(_wander(wl.rtt_ms, 8, 4), 20000, 0.4, 900)
     check_proxy(tr, model, px, wl.params[:3], [1.0, 4.0, 16.0], engine=engine, label="engine")
     rng = np.random.default_rng(8)
     P, window, hop = 4, 128, 32
@@ -143,8 +151,10 @@ def test_random_cases(seed):
     model = g.Model(R, B, int(rng.choice([0, nmax, nmax + 1, 2 * nmax + 3, 10 * nmax])), float(rng.choice([0.0, 0.01, 0.05])),
                     float(rng.choice([0.0, 1.0, 20.0])))
     E = int(rng.integers(1, 30))
+    C = model.cache_blocks
+    index = -1 if seed % 3 == 0 else (0 if seed % 3 == 1 or C == 0 else int(rng.choice([C, C + 1, C + nmax, 3 * C])))
     px = g.Proxy(np.round(rng.uniform(0.0, 300.0, (E, R)), 1), int(rng.choice([1, 100, 1000, 30000])),
-                 float(rng.choice([0.05, 0.5, 1.0])), bool(seed % 3 != 0))
+                 float(rng.choice([0.05, 0.5, 1.0])), index)
     par = rng.uniform(0.0, 2.0, (3, 3))
     if seed % 5 == 0:
         par[0] = [0.0, 1.0, 0.0]
@@ -157,16 +167,17 @@ def test_random_cases(seed):
     check_proxy(tr, model, px, par, scale, engine=engine, label=f"fuzz {seed}")
 
 
-def test_long_paths_and_the_stale_index():
-    """Requests with more segments than are preloaded (the deep-match path), tight caches, a stale index."""
+def test_long_paths_and_an_index_of_its_own():
+    """Requests with more segments than are preloaded (the deep-match path), tight caches, an index of its own."""
     tr = tg.random_forest(77, 1200, roots=2, max_blocks=120, grow=3, gap_ms=5, keep=0.8)
     nmax = int(np.diff(tr.blk_off).max())
     segs = load(tr).replay_path()["segment_refs"] / tr.N
     assert segs > 6
     for C in (nmax, 2 * nmax + 1, 6 * nmax):
-        got = check_proxy(tr, g.Model(4, 2, C, 0.05, 3.0), g.Proxy([[5.0, 40.0, 90.0, 20.0]], 30000, 0.5, True),
-                          [[0.5, 1.0, 0.1], [0.0, 1.0, 0.0], [1.0, 1.0, 1.0]], [1.0, 1.0, 3.0], label=f"deep C={C}")
-        assert (got["believed"] > got["hit"]).any()
+        for index in (0, C + nmax // 2, 3 * C):
+            got = check_proxy(tr, g.Model(4, 2, C, 0.05, 3.0), g.Proxy([[5.0, 40.0, 90.0, 20.0]], 30000, 0.5, index),
+                              [[0.5, 1.0, 0.1], [0.0, 1.0, 0.0], [1.0, 1.0, 1.0]], [1.0, 1.0, 3.0], label=f"deep C={C} index={index}")
+            assert (got["believed"] >= got["hit"]).all() and (got["believed"] > got["hit"]).any()
 
 
 @pytest.mark.parametrize("B", [1, 3])
@@ -177,7 +188,7 @@ def test_completion_events_that_overtake_each_other(B):
     tr = tg.random_forest(31, 2500, roots=3, max_blocks=8, grow=3, gap_ms=6)
     R = 2
     cycle = np.array([[8000.0, 6000.0], [0.0, 3000.0], [4000.0, 100.0], [6000.0, 7000.0], [1000.0, 0.0], [5000.0, 2500.0]])
-    px = g.Proxy(np.tile(cycle, (8, 1)), 150, 0.5, False)
+    px = g.Proxy(np.tile(cycle, (8, 1)), 150, 0.5, -1)
     got = check_proxy(tr, g.Model(R, B, 0, 0.001, 0.01), px, [[0.0, 0.0, 1.0], [0.1, 1.0, 1.0], [0.0, 0.0, 1.0]], [1.0, 1.0, 0.3],
                       label=f"overtaking B={B}")
     assert len(set(got["route"][0].tolist())) == R
