@@ -23,6 +23,9 @@ def build(verbose: bool = False) -> str:
            # every fp64 product and sum on the decision path is rounded on its own: no fused multiply-add
            "-ffp-contract=off", "-fno-fast-math",
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           # the replay kernels are long dependent chains: scheduling for instruction-level parallelism measures
+           # about 2 % faster than the default (occupancy-first) strategy
+           "-mllvm", "-amdgpu-sched-strategy=max-ilp",
            "-Wall", "-Wno-unused-command-line-argument",
            "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-x", "hip"]
     cmd += [os.path.join(CSRC, s) for s in SOURCES]
