@@ -79,7 +79,8 @@ __device__ __forceinline__ unsigned wave_sum_u32(unsigned x) {
 // Lowest-index minimum over the lanes below `count` (count >= 1; values must not be NaN).  The values are
 // compared through the usual order-preserving map of an IEEE double to an unsigned 64-bit key (zeros of
 // either sign made equal first), high word first, then the low word among the lanes that tie on the high
-// word: two 32-bit reductions instead of one on register pairs.
+// word: two 32-bit reductions instead of one on register pairs, and only one when the high words already decide
+// (scores that differ by more than a part in a million).
 __device__ __forceinline__ int wave_argmin(double v, int lane, int count) {
     const unsigned long long bits = (unsigned long long)__double_as_longlong(v + 0.0);
     const unsigned hi = (unsigned)(bits >> 32), lo = (unsigned)bits;
@@ -89,6 +90,8 @@ __device__ __forceinline__ int wave_argmin(double v, int lane, int count) {
     const unsigned klo = lo ^ neg;
     const unsigned mhi = wave_min_u32(khi);
     const bool tie = in && khi == mhi;
+    const unsigned long long ties = __ballot(tie);
+    if ((ties & (ties - 1)) == 0) return __ffsll(ties) - 1;      // one lane holds the smallest high word: done
     const unsigned mlo = wave_min_u32(tie ? klo : 0xffffffffu);
     const unsigned long long at = __ballot(tie && klo == mlo);
     return __ffsll(at) - 1;
