@@ -192,3 +192,28 @@ def test_completion_events_that_overtake_each_other(B):
     got = check_proxy(tr, g.Model(R, B, 0, 0.001, 0.01), px, [[0.0, 0.0, 1.0], [0.1, 1.0, 1.0], [0.0, 0.0, 1.0]], [1.0, 1.0, 0.3],
                       label=f"overtaking B={B}")
     assert len(set(got["route"][0].tolist())) == R
+
+
+def test_largest_launch_shape():
+    """64 replicas x 16 slots, a 1,024-request tuner window, engine model and imperfect proxy knowledge together: the
+    variant with the most per-replay state in LDS and registers still launches and matches the oracle."""
+    R, B = 64, 16
+    tr = tg.random_forest(55, 2600, roots=4, max_blocks=30, grow=5, gap_ms=4, keep=0.5)
+    nmax = int(np.diff(tr.blk_off).max())
+    most = int((tr.in_len.astype(np.int64) + tr.out_len).max())
+    rng = np.random.default_rng(55)
+    model = g.Model(R, B, 3 * nmax, 0.05, 0.0)
+    engine = g.Engine(rng.uniform(0.02, 0.1, R), rng.uniform(1.0, 20.0, R), [6 * most] * R, 0.1)
+    px = g.Proxy(np.round(rng.uniform(1.0, 200.0, (12, R)), 1), 900, 0.3, 5 * nmax)
+    P, window, hop = 3, 1024, 64
+    steps = g.online_steps(tr.N, window, hop)
+    z = rng.standard_normal((P, steps, 3))
+    theta0 = np.tile([1.0, 0.5, 0.1], (P, 1))
+    on = dict(lo=[0.05] * 3, hi=[2.0] * 3, sigma0=0.5, window=window, hop=hop)
+    res = g.eval_proxy(load(tr), model, px, theta0, [1.0, 2.0, 0.5], engine=engine, online=dict(on, z=z))
+    got = _numpy(res)
+    for p, sc in enumerate([1.0, 2.0, 0.5]):
+        ref = _oracle(tr, model, px, theta0[p], sc, engine, online=dict(on, z=z[p]))
+        assert_replay_equal(got, p, ref, "largest shape")
+        assert np.array_equal(got["believed"][p], ref.believed_hit)
+        assert np.array_equal(res.theta_step[p].cpu().numpy(), ref.theta_step)
