@@ -60,7 +60,7 @@ def kernel_source_digest():
     import hashlib
     h = hashlib.sha256()
     csrc = os.path.join(ROOT, "paper_2602_11688_amd", "csrc")
-    for name in ("device_common.h", "replay_segments.h", "kernels.hip"):
+    for name in ("device_common.h", "replay_segments.h", "replay_segments_packed.h", "kernels.hip"):
         with open(os.path.join(csrc, name), "rb") as f:
             h.update(f.read())
     return h.hexdigest()[:16]

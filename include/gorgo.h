@@ -330,6 +330,13 @@ int gorgo_set_replay_path(int32_t mode);
  * at the first poll is given up. */
 int gorgo_set_handover_poll_limit(int32_t polls);
 
+/* With at most 32 replicas, at most 16 slots per replica and an even number of replays, gorgo_eval_population and
+ * gorgo_es_step can run two replays per pair of wavefronts of the segment-row kernel (a replay keeps one lane per
+ * replica, so half of a 64-lane wavefront idles otherwise).  A replay is a serial chain, so this only pays when
+ * the replays would not all be resident on the GPU at once (more than about 1,024 of them): mode 2 (default) packs
+ * exactly then, mode 1 whenever the shape allows, mode 0 never.  Results are the same bit for bit. */
+int gorgo_set_replay_packing(int32_t mode);
+
 /* Formulation that an evaluation of this trace would use now (1 or 2, see gorgo_set_replay_path), the number
  * of segments of the trace and the total number of (request, segment) references; the last two are 0 for a
  * trace that is not chain-consistent.  Each out pointer may be NULL. */

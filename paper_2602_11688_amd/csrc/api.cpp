@@ -119,6 +119,13 @@ int gorgo_set_handover_poll_limit(int32_t polls) {
     return GORGO_OK;
 }
 
+int gorgo_set_replay_packing(int32_t mode) {
+    clear_error();
+    if (mode < 0 || mode > 2) return fail(GORGO_ERR_INVALID_ARG, "mode must be 0 (never), 1 (whenever possible) or 2 (automatic)");
+    set_replay_packing(mode);
+    return GORGO_OK;
+}
+
 int gorgo_set_replay_path(int32_t mode) {
     clear_error();
     if (mode != PATH_AUTO && mode != PATH_BLOCKS && mode != PATH_SEGMENTS)

@@ -256,8 +256,9 @@ struct Queues {
     // slots are therefore only searched for their earliest free time (lowest index on ties) when every slot
     // still has a request in flight.  `idle_then` is the set of idle slots at the request's time t; the lists
     // themselves may already have been retired further (to the next request's time), which only makes more
-    // slots idle.  The chosen replica's lane works, its latencies are broadcast.
-    template <bool REORDER>
+    // slots idle.  The chosen replica's lane works, its latencies are broadcast (LOCAL: left in that lane; `best`,
+    // `t` and `uncached_mine` may then differ between lanes, for wavefronts that serve two replays at once).
+    template <bool REORDER, bool LOCAL = false>
     __device__ void serve(int64_t r, int best, double t, double rtt_mine, int64_t uncached_mine, int64_t L, int64_t O,
                           double a_pf, double a_dec, Rec* rec, int lane, unsigned long long idle_then,
                           double* ttft_out, double* e2e_out) {
@@ -328,8 +329,8 @@ struct Queues {
             my_q += (double)L;
             my_cnt += 1.0;
         }
-        *ttft_out = readlane_f64(ttft, best);
-        *e2e_out = readlane_f64(e2e, best);
+        *ttft_out = LOCAL ? ttft : readlane_f64(ttft, best);
+        *e2e_out = LOCAL ? e2e : readlane_f64(e2e, best);
     }
 
     // Service of request r on replica `best` under the engine model of a replica (continuous batching, Sec. 2.2;

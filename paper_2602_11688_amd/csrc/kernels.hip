@@ -21,6 +21,7 @@
 #include "device_common.h"
 #include "internal.h"
 #include "replay_segments.h"
+#include "replay_segments_packed.h"
 
 namespace gorgo {
 
@@ -475,7 +476,32 @@ int copy_small_to_device(void* dst, const void* src, size_t bytes, void* stream)
     return e == hipSuccess ? GORGO_OK : hip_fail(e, "hipMemcpyAsync(H2D)");
 }
 
+std::atomic<int32_t> g_packing{2};      // 0 never, 1 whenever the shape allows, 2 when the replays would not all be resident
 std::atomic<int32_t> g_poll_limit{SEG_SPIN_LIMIT};
+void set_replay_packing(int32_t mode) { g_packing.store(mode); }
+
+namespace {
+
+// Whether a launch of fixed-weight replays runs two replays per wavefront pair.  A replay is a serial chain whose
+// duration does not depend on how many others run beside it, and a packed pair takes a few percent longer per
+// request than a lone replay: packing pays exactly when the replays would not all be resident at once otherwise.
+bool pack_replays(const Plan& pl, int64_t nseg) {
+    const int32_t mode = g_packing.load();
+    if (mode == 0 || pl.R > HALF || pl.B > 16 || pl.P % 2 != 0 ||
+        2ull * (uint64_t)nseg * (uint64_t)pl.R * 4u >= (1ull << 32))
+        return false;
+    if (mode == 1) return true;
+    int device = 0, cus = 0, per_cu = 0;
+    if (hipGetDevice(&device) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess ||
+        hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, replay_segments_kernel<MODE_COST_MODEL, false, false>,
+                                                     SEG_THREADS, replay_segments_lds_bytes(pl.R, pl.B, 0)) != hipSuccess)
+        return false;
+    return (int64_t)pl.P > (int64_t)cus * per_cu;
+}
+
+}  // namespace
+
 void set_handover_poll_limit(int32_t polls) { g_poll_limit.store(polls); }
 
 int wait_for_copies(void* stream) {
@@ -611,6 +637,10 @@ int launch_replay(const gorgo_trace* t, const Plan& pl, const double* d_rtt, con
                     case 2: hipLaunchKernelGGL((replay_segments_kernel<MODE_AFFINITY, true, false>), grid, block, lds, s, a); break;
                     default: hipLaunchKernelGGL((replay_segments_kernel<MODE_RANDOM, true, false>), grid, block, lds, s, a); break;
                 }
+            } else if (!(policy && policy->policy != 0) && pack_replays(pl, a.nseg)) {
+                // fixed weights, at most 32 replicas: two replays per wavefront pair
+                hipLaunchKernelGGL(replay_segments_packed_kernel, dim3((unsigned)(pl.P / 2)), dim3(SEG_THREADS),
+                                   replay_segments_packed_lds_bytes(pl.B), s, a);
             } else {
                 const size_t lds = replay_segments_lds_bytes(pl.R, pl.B, 0);
                 const dim3 grid((unsigned)pl.P), block(SEG_THREADS);

@@ -15,15 +15,17 @@ def load(tr):
 PATH_NAMES = {0: "auto", 1: "block-tables", 2: "segment-rows"}
 
 
-def gpu_eval(tr, model: g.Model, rtt, params, scale, handle=None, path=0):
+def gpu_eval(tr, model: g.Model, rtt, params, scale, handle=None, path=0, packing=True):
     import torch
     h = handle if handle is not None else load(tr)
     g.set_replay_path(path)
+    g.set_replay_packing(1 if packing else 0)
     try:
         res = g.eval_population(h, model, rtt, params, scale)
         torch.cuda.synchronize()
     finally:
         g.set_replay_path(0)
+        g.set_replay_packing(2)
     out = dict(route=res.route.cpu().numpy(), hit=res.hit_blocks.cpu().numpy(), ttft=res.ttft_ms.cpu().numpy(),
                e2e=res.e2e_ms.cpu().numpy(), p95_ttft=res.p95_ttft_ms.cpu().numpy(),
                p95_e2e=res.p95_e2e_ms.cpu().numpy())
@@ -61,7 +63,9 @@ def check_population(tr, model, rtt, params, scale, replays=None, label="", path
     refs = {p: oracle_eval(tr, model, rtt, params[p], float(scale[p])) for p in which}
     got = None
     for path in paths:
-        got = gpu_eval(tr, model, rtt, params, scale, handle=h, path=path)
-        for p in which:
-            assert_replay_equal(got, p, refs[p], f"{label} [{PATH_NAMES[path]}]")
+        # segment rows: with two replays per wavefront pair where the shape allows it, and without
+        for packing in ((False, True) if path == 2 else (True,)):
+            got = gpu_eval(tr, model, rtt, params, scale, handle=h, path=path, packing=packing)
+            for p in which:
+                assert_replay_equal(got, p, refs[p], f"{label} [{PATH_NAMES[path]}{'' if packing else ', unpacked'}]")
     return got

@@ -125,6 +125,14 @@ def test_eval_rejects_bad_arguments_before_touching_a_device():
     assert b"workspace" in L.gorgo_last_error()
 
 
+def test_settings_validate_their_arguments():
+    L = g.lib()
+    assert L.gorgo_set_replay_packing(3) == -1 and L.gorgo_set_replay_packing(-1) == -1
+    assert L.gorgo_set_replay_packing(0) == 0 and L.gorgo_set_replay_packing(1) == 0 and L.gorgo_set_replay_packing(2) == 0
+    assert L.gorgo_set_handover_poll_limit(-1) == -1 and L.gorgo_set_handover_poll_limit(1 << 24) == 0
+    assert L.gorgo_set_replay_path(3) == -1 and L.gorgo_set_replay_path(0) == 0
+
+
 def test_online_and_policy_entry_points_reject_bad_arguments_before_touching_a_device():
     t = _trace(tg.config(1, 300).trace)
     m = g.Model(4, 8, 0, 0.05, 20.0).c()

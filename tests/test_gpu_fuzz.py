@@ -35,12 +35,12 @@ def _setup(seed):
     C = int(rng.choice([0, nmax, nmax + 1, 2 * nmax + 3, 10 * nmax]))
     model = g.Model(R, B, C, float(rng.choice([0.0, 0.01, 0.05, 0.5])), float(rng.choice([0.0, 1.0, 20.0])))
     rtt = np.round(rng.uniform(0.0, 300.0, R), 1)
-    par = rng.uniform(0.0, 2.0, (3, 3))
+    par = rng.uniform(0.0, 2.0, (4, 3))
     if seed % 5 == 0:
         par[0] = [0.0, 0.0, 0.0]
     if seed % 7 == 0:
         par[1] = [-1.0, 1.0, 0.5]
-    scale = rng.choice([0.25, 1.0, 3.0, 10.0], 3)
+    scale = rng.choice([0.25, 1.0, 3.0, 10.0], 4)
     return rng, tr, model, rtt, par, scale
 
 
@@ -53,7 +53,7 @@ def test_random_cases(seed):
     window, hop = int(rng.integers(1, 200)), int(rng.integers(1, 70))
     steps = g.online_steps(tr.N, window, hop)
     theta0 = np.clip(par, 0.05, 2.0)
-    check_online(tr, model, rtt, theta0, 2.0 * rng.standard_normal((3, steps, 3)), scale, window, hop, lo=[0.05] * 3,
+    check_online(tr, model, rtt, theta0, 2.0 * rng.standard_normal((4, steps, 3)), scale, window, hop, lo=[0.05] * 3,
                  hi=[2.0] * 3, sigma0=float(rng.choice([0.0, 0.5, 3.0])))
     for policy in ("least-request", "session-affinity", "random"):
         check_policy(tr, model, rtt, policy, list(scale[:2]), np.array([seed, seed + 1], np.uint64))

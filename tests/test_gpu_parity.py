@@ -6,7 +6,7 @@ import paper_2602_11688_amd as g
 from oracle import binding as ob
 from oracle import es_oracle as eo
 from synth import tracegen as tg
-from tests.gpu_helpers import assert_replay_equal, check_population, gpu_eval, load, oracle_eval
+from tests.gpu_helpers import RTOL, assert_replay_equal, check_population, gpu_eval, load, oracle_eval
 from tests.helpers import load_golden
 
 pytestmark = pytest.mark.gpu
@@ -250,3 +250,35 @@ def test_given_up_replays_end_and_poison_their_latencies():
     got = gpu_eval(wl.trace, model, wl.rtt_ms, wl.params[:2], 1.0, handle=h, path=2)
     for p in range(2):
         assert_replay_equal(got, p, oracle_eval(wl.trace, model, wl.rtt_ms, wl.params[p], 1.0), "after give-up")
+
+
+def test_two_replays_per_wavefront_pair_give_the_same_results():
+    """Packed and unpacked launches of the segment-row kernel on the same inputs, bit for bit, at a shape where the
+    automatic choice packs as well (more replays than fit on the GPU at once), with per-request outputs and without."""
+    import torch
+    wl = tg.config(3, 1500)
+    model = g.Model(wl.R, wl.batch, 300, wl.prefill_ms_per_token, wl.decode_ms_per_token)
+    h = load(wl.trace)
+    rng = np.random.default_rng(12)
+    P = 2600
+    params = rng.uniform(0.05, 2.0, (P, 3))
+    scale = rng.choice([0.5, 1.0, 2.0], P)
+    out = {}
+    for mode in (0, 1, 2):
+        g.set_replay_packing(mode)
+        try:
+            res = g.eval_population(h, model, wl.rtt_ms, params, scale)
+            lean = g.eval_population(h, model, wl.rtt_ms, params, scale, per_request=False)
+            torch.cuda.synchronize()
+        finally:
+            g.set_replay_packing(2)
+        assert torch.equal(res.p95_ttft_ms, lean.p95_ttft_ms) and torch.equal(res.p95_e2e_ms, lean.p95_e2e_ms)
+        out[mode] = res
+    for mode in (1, 2):
+        for name in ("route", "hit_blocks", "ttft_ms", "e2e_ms", "p95_ttft_ms", "p95_e2e_ms"):
+            assert torch.equal(getattr(out[0], name), getattr(out[mode], name)), (mode, name)
+    # and the unpacked launch is the oracle's
+    for p in (0, 1, 1299, 2598, 2599):
+        ref = oracle_eval(wl.trace, model, wl.rtt_ms, params[p], float(scale[p]))
+        assert np.array_equal(out[0].route[p].cpu().numpy(), ref.route)
+        np.testing.assert_allclose(out[0].ttft_ms[p].cpu().numpy(), ref.ttft_ms, rtol=RTOL, atol=0)
