@@ -181,6 +181,23 @@ def test_many_segments_per_request():
                      label="many-segments")
 
 
+def test_requests_with_more_segments_than_a_staged_batch_holds():
+    # the same growth continued past 512 segments per request: such a request is processed on its own, its
+    # segment references read from global memory
+    lens = list(range(1, 540, 3)) + list(range(520, 560)) + [7, 559, 2, 530]
+    ids, off = [], [0]
+    for n in lens:
+        ids += list(range(1, n + 1))
+        off.append(len(ids))
+    N = len(lens)
+    rng = np.random.default_rng(5)
+    tr = tg.Trace(np.arange(N, dtype=np.int64) * 300, (np.array(lens) * 512).astype(np.int32),
+                  rng.integers(1, 20, N).astype(np.int32), np.array(off, np.int64), np.array(ids, np.int64))
+    assert load(tr).replay_path()["segment_refs"] > 40 * N
+    check_population(tr, g.Model(3, 2, 600, 0.05, 20.0), [10.0, 11.0, 30.0], [[1, 1, 0.0], [1, 1, 1], [0, 0, 1], [0.5, 1, 0.1]],
+                     [1.0, 1.0, 2.0, 0.5], label="beyond-stage", paths=[2])
+
+
 def test_p95_only_outputs_and_percentile_selection():
     import torch
     wl = tg.config(1)
