@@ -307,7 +307,8 @@ def main():
     segs_mean = rp["segment_refs"] / max(N, 1)
     if rp["path"] == 2:
         bpr = algorithmic_bytes_per_routing_segments(wl.R, segs_mean, outputs_bytes=8)   # ttft f64
-        kernel = "replay_segments_kernel"
+        plain = args.online or args.engine or args.proxy
+        kernel = "replay_segments_kernel" if plain or not g.replay_packing(tr, model, P) else "replay_segments_packed_kernel"
     else:
         bpr = algorithmic_bytes_per_routing(wl.R, n_mean, hit_mean, outputs_bytes=9)
         kernel = "replay_blocks_kernel"

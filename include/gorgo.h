@@ -337,6 +337,10 @@ int gorgo_set_handover_poll_limit(int32_t polls);
  * exactly then, mode 1 whenever the shape allows, mode 0 never.  Results are the same bit for bit. */
 int gorgo_set_replay_packing(int32_t mode);
 
+/* Whether gorgo_eval_population with P replays of this trace and model would pack them now (*packed = 1) or not
+ * (0).  Asks the current device how many workgroups it holds at once. */
+int gorgo_query_replay_packing(const gorgo_trace* t, const gorgo_model* m, int32_t P, int32_t* packed);
+
 /* Formulation that an evaluation of this trace would use now (1 or 2, see gorgo_set_replay_path), the number
  * of segments of the trace and the total number of (request, segment) references; the last two are 0 for a
  * trace that is not chain-consistent.  Each out pointer may be NULL. */

@@ -97,12 +97,13 @@ def lib():
         L.gorgo_set_replay_path.argtypes = [i32]
         L.gorgo_set_handover_poll_limit.argtypes = [i32]
         L.gorgo_set_replay_packing.argtypes = [i32]
+        L.gorgo_query_replay_packing.argtypes = [vp, C.POINTER(_Model), i32, C.POINTER(i32)]
         L.gorgo_query_replay_path.argtypes = [vp, C.POINTER(i32), C.POINTER(i64), C.POINTER(i64)]
         L.gorgo_last_eval_kernel_ms.argtypes = [C.POINTER(dbl)] * 3
         for name in ("gorgo_load_trace", "gorgo_load_trace_arrays", "gorgo_trace_info", "gorgo_workspace_bytes",
                      "gorgo_eval_population", "gorgo_eval_online", "gorgo_eval_policy", "gorgo_eval_engine", "gorgo_eval_proxy", "gorgo_es_init", "gorgo_es_sample", "gorgo_es_propose",
                      "gorgo_es_update", "gorgo_es_workspace_bytes", "gorgo_es_step", "gorgo_set_table_factor_percent",
-                     "gorgo_last_eval_kernel_ms", "gorgo_set_replay_path", "gorgo_set_handover_poll_limit", "gorgo_set_replay_packing", "gorgo_query_replay_path"):
+                     "gorgo_last_eval_kernel_ms", "gorgo_set_replay_path", "gorgo_set_handover_poll_limit", "gorgo_set_replay_packing", "gorgo_query_replay_packing", "gorgo_query_replay_path"):
             getattr(L, name).restype = C.c_int
         _lib = L
     return _lib
@@ -196,6 +197,14 @@ def set_replay_packing(mode: int) -> None:
     """Two replays per wavefront pair: 0 never, 1 whenever the shape allows it, 2 (default) when the replays would not
     all be resident at once otherwise; results do not depend on it."""
     _check(lib().gorgo_set_replay_packing(int(mode)))
+
+
+def replay_packing(trace: "Trace", model: "Model", P: int) -> bool:
+    """Whether eval_population with P replays would run two replays per wavefront pair now."""
+    out = C.c_int32()
+    m = model.c()
+    _check(lib().gorgo_query_replay_packing(trace._h, C.byref(m), P, C.byref(out)))
+    return bool(out.value)
 
 
 def set_handover_poll_limit(polls: int):

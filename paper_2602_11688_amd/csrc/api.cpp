@@ -126,6 +126,18 @@ int gorgo_set_replay_packing(int32_t mode) {
     return GORGO_OK;
 }
 
+int gorgo_query_replay_packing(const gorgo_trace* t, const gorgo_model* m, int32_t P, int32_t* packed) {
+    clear_error();
+    if (!packed) return fail(GORGO_ERR_INVALID_ARG, "packed is NULL");
+    int rc = check_model(t, m);
+    if (rc) return rc;
+    Plan pl;
+    rc = make_plan(t, m, P, nullptr, &pl);
+    if (rc) return rc;
+    *packed = pl.path == PATH_SEGMENTS && pack_replays(pl, pl.nseg > 0 ? pl.nseg : 1) ? 1 : 0;
+    return GORGO_OK;
+}
+
 int gorgo_set_replay_path(int32_t mode) {
     clear_error();
     if (mode != PATH_AUTO && mode != PATH_BLOCKS && mode != PATH_SEGMENTS)

@@ -118,6 +118,7 @@ struct ProxyLaunch {
 // kernels.hip
 void set_handover_poll_limit(int32_t polls);
 void set_replay_packing(int32_t mode);
+bool pack_replays(const Plan& pl, int64_t nseg);
 int launch_replay(const gorgo_trace* t, const Plan& pl, const double* d_rtt, const double* d_params,
                   const double* d_scale, uint8_t* route, uint16_t* hit, double* ttft, double* e2e,
                   void* workspace, void* stream, const OnlineLaunch* online = nullptr,

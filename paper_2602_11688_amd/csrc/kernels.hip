@@ -480,8 +480,6 @@ std::atomic<int32_t> g_packing{2};      // 0 never, 1 whenever the shape allows,
 std::atomic<int32_t> g_poll_limit{SEG_SPIN_LIMIT};
 void set_replay_packing(int32_t mode) { g_packing.store(mode); }
 
-namespace {
-
 // Whether a launch of fixed-weight replays runs two replays per wavefront pair.  A replay is a serial chain whose
 // duration does not depend on how many others run beside it, and a packed pair takes a few percent longer per
 // request than a lone replay: packing pays exactly when the replays would not all be resident at once otherwise.
@@ -499,8 +497,6 @@ bool pack_replays(const Plan& pl, int64_t nseg) {
         return false;
     return (int64_t)pl.P > (int64_t)cus * per_cu;
 }
-
-}  // namespace
 
 void set_handover_poll_limit(int32_t polls) { g_poll_limit.store(polls); }
 
