@@ -1,7 +1,6 @@
 """CPU-only tests of the C-ABI library: it loads, exports every declared symbol, and its host-side logic
 (trace loading, validation, tuner arithmetic, random draws) behaves as declared.  No compute call here."""
 import ctypes as C
-import json
 import math
 import os
 import re

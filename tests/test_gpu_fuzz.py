@@ -5,9 +5,8 @@ import numpy as np
 import pytest
 
 import paper_2602_11688_amd as g
-from oracle import binding as ob
 from synth import tracegen as tg
-from tests.gpu_helpers import assert_replay_equal, check_population, load
+from tests.gpu_helpers import check_population, load
 from tests.test_gpu_online import _check as check_online
 from tests.test_gpu_policies import _check as check_policy
 

@@ -5,7 +5,7 @@ import pytest
 import paper_2602_11688_amd as g
 from oracle import binding as ob
 from synth import tracegen as tg
-from tests.gpu_helpers import RTOL, assert_replay_equal, gpu_eval, load
+from tests.gpu_helpers import assert_replay_equal, gpu_eval, load
 
 pytestmark = pytest.mark.gpu
 
