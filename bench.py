@@ -359,9 +359,17 @@ def main():
         on = (z_on[:cores].cpu().numpy(), list(state.lo[:]), list(state.hi[:]), state.sigma) if args.online else None
         v, dt, n_s = cpu_baseline(wl, theta0 if args.online else par, min(args.cpu_sample_requests, N), cores, on,
                                   recipe if args.engine else None, proxy if args.proxy else None)
+        cpu_model = "unknown"
+        try:
+            with open("/proc/cpuinfo") as f:
+                cpu_model = next((l.split(":", 1)[1].strip() for l in f if l.startswith("model name")), cpu_model)
+        except OSError:
+            pass
         out["cpu_baseline"] = {"value": v, "unit": "routings/s", "cores": cores, "kind": "oracle",
                                "sample": f"{cores} replays (one per thread) x first {n_s} requests of the same trace, "
-                                         f"{dt:.1f}s wall"}
+                                         f"{dt:.1f}s wall",
+                               "per_core": v / cores, "cpu_model": cpu_model, "host_cpus": os.cpu_count(),
+                               "gpu_over_oracle": value / v}
     print(json.dumps(out), flush=True)
 
 

@@ -142,3 +142,46 @@ def test_large_workload_with_imperfect_proxy_knowledge_matches_oracle():
             print(f"replay {p}: {ref.route.size} requests equal, p95 TTFT {ref.p95_ttft_ms:.3f} ms, index overestimates on "
                   f"{100 * over:.1f}% of requests", flush=True)
         assert np.array_equal(full.rtt_est_ms.cpu().numpy(), futs[picks[0]].result().rtt_est)
+
+
+def _against_oracle(wl, params, scale, picks, label):
+    """One launch over all replays with per-request outputs; the picked replays against the oracle in full, one
+    oracle replay per host thread."""
+    import torch
+    model = g.Model(wl.R, wl.batch, wl.cache_blocks, wl.prefill_ms_per_token, wl.decode_ms_per_token)
+    h = load(wl.trace)
+    with ThreadPoolExecutor(16) as ex:
+        futs = {p: ex.submit(oracle_eval, wl.trace, model, wl.rtt_ms, params[p], float(scale[p])) for p in picks}
+        full = g.eval_population(h, model, wl.rtt_ms, params, scale)
+        torch.cuda.synchronize()
+        p95_ttft = full.p95_ttft_ms.cpu().numpy()
+        p95_e2e = full.p95_e2e_ms.cpu().numpy()
+        assert np.isfinite(p95_ttft).all() and (p95_ttft > 0).all() and (p95_e2e >= p95_ttft).all()
+        for p in picks:
+            ref = futs[p].result()
+            bad = np.nonzero(full.route[p].cpu().numpy() != ref.route)[0]
+            assert bad.size == 0, f"{label} replay {p}: first route mismatch at request {bad[0]} ({bad.size} in all)"
+            assert np.array_equal(full.hit_blocks[p].cpu().numpy(), ref.hit_blocks), f"{label} replay {p}: hit counts"
+            np.testing.assert_allclose(full.ttft_ms[p].cpu().numpy(), ref.ttft_ms, rtol=RTOL, atol=0)
+            np.testing.assert_allclose(full.e2e_ms[p].cpu().numpy(), ref.e2e_ms, rtol=RTOL, atol=0)
+            assert abs(p95_ttft[p] - ref.p95_ttft_ms) <= RTOL * ref.p95_ttft_ms
+            assert abs(p95_e2e[p] - ref.p95_e2e_ms) <= RTOL * ref.p95_e2e_ms
+    print(f"{label}: {len(picks)} replays x {wl.trace.N} requests equal", flush=True)
+
+
+@pytest.mark.parametrize("cfg", [2, 3])
+def test_smaller_workloads_at_full_size_every_replay(cfg):
+    """Configs 2 (R=8, N=50,000, P=64) and 3 (R=16, N=200,000, P=256) whole: every replay against the oracle."""
+    wl = tg.config(cfg)
+    _against_oracle(wl, wl.params, wl.scale, list(range(wl.params.shape[0])), f"config {cfg}")
+
+
+def test_saturation_sweep_at_full_size_sampled_replays():
+    """Config 4 (R=16, N=200,000, 1,024 (time scale, candidate) pairs in one launch): replay 0, the last one and 32
+    seeded picks against the oracle in full."""
+    wl = tg.config(4)
+    P = wl.params.shape[0]
+    assert P == 1024 and len(set(np.asarray(wl.scale).tolist())) > 1
+    rng = np.random.default_rng(20260214)
+    picks = sorted({0, P - 1} | set(rng.choice(np.arange(1, P - 1), 32, replace=False).tolist()))
+    _against_oracle(wl, wl.params, wl.scale, picks, "config 4")
