@@ -123,6 +123,25 @@ int gorgo_eval_population(const gorgo_trace* t, const gorgo_model* m, const doub
                           const double* params, const double* scale, int32_t P, const gorgo_outputs* outputs,
                           void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* Uploads the trace to the current device now (one allocation, one synchronous copy) instead of at its first
+ * evaluation there.  Does nothing if it is already resident on this device. */
+int gorgo_trace_to_device(const gorgo_trace* t);
+
+/* gorgo_eval_population for callers that cannot allocate device memory: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid it.  Same arguments, results and errors, except that there is no workspace
+ * argument: the cache rows, logs, in-flight records and the copies of the small host arrays live in an array of
+ * GORGO_STATIC_SCRATCH_BYTES that is part of the library's device code (each GPU the library runs on holds it
+ * until the process ends).  The call allocates nothing on the device and creates no event or stream
+ * (gorgo_last_eval_kernel_ms does not cover it); the trace must already be resident on the current device
+ * (gorgo_trace_to_device, or any earlier evaluation there), else GORGO_ERR_INVALID_ARG.  An evaluation whose
+ * gorgo_workspace_bytes exceeds GORGO_STATIC_SCRATCH_BYTES is refused with GORGO_ERR_WORKSPACE before anything
+ * is enqueued.  Every call on a GPU uses that GPU's one array: what must start clean is cleared by the call's
+ * own kernels, and two such calls that overlap in time on one GPU (different streams or threads) race. */
+#define GORGO_STATIC_SCRATCH_BYTES ((size_t)64 << 20)
+int gorgo_eval_population_static(const gorgo_trace* t, const gorgo_model* m, const double* rtt_ms,
+                                 const double* params, const double* scale, int32_t P,
+                                 const gorgo_outputs* outputs, void* hip_stream);
+
 /* ------------------------------------------------------------------------------------------------ tuner
  * Evolution-strategy state (Sec. 2.3): parent weights theta, step size sigma, per-weight ranges, the
  * generation counter and the best candidate seen so far.  Plain data, caller-owned; serialise it to

@@ -76,6 +76,8 @@ def lib():
         L.gorgo_workspace_bytes.argtypes = [vp, C.POINTER(_Model), i32, C.POINTER(_Outputs), C.POINTER(C.c_size_t)]
         L.gorgo_eval_population.argtypes = [vp, C.POINTER(_Model), vp, vp, vp, i32, C.POINTER(_Outputs), vp,
                                             C.c_size_t, vp]
+        L.gorgo_trace_to_device.argtypes = [vp]
+        L.gorgo_eval_population_static.argtypes = [vp, C.POINTER(_Model), vp, vp, vp, i32, C.POINTER(_Outputs), vp]
         L.gorgo_online_steps.argtypes = [i64, i32, i32]
         L.gorgo_online_steps.restype = i64
         L.gorgo_eval_online.argtypes = [vp, C.POINTER(_Model), vp, vp, vp, i32, C.POINTER(_Online), C.POINTER(_Outputs),
@@ -101,7 +103,7 @@ def lib():
         L.gorgo_query_replay_path.argtypes = [vp, C.POINTER(i32), C.POINTER(i64), C.POINTER(i64)]
         L.gorgo_last_eval_kernel_ms.argtypes = [C.POINTER(dbl)] * 3
         for name in ("gorgo_load_trace", "gorgo_load_trace_arrays", "gorgo_trace_info", "gorgo_workspace_bytes",
-                     "gorgo_eval_population", "gorgo_eval_online", "gorgo_eval_policy", "gorgo_eval_engine", "gorgo_eval_proxy", "gorgo_es_init", "gorgo_es_sample", "gorgo_es_propose",
+                     "gorgo_eval_population", "gorgo_trace_to_device", "gorgo_eval_population_static", "gorgo_eval_online", "gorgo_eval_policy", "gorgo_eval_engine", "gorgo_eval_proxy", "gorgo_es_init", "gorgo_es_sample", "gorgo_es_propose",
                      "gorgo_es_update", "gorgo_es_workspace_bytes", "gorgo_es_step", "gorgo_set_table_factor_percent",
                      "gorgo_last_eval_kernel_ms", "gorgo_set_replay_path", "gorgo_set_handover_poll_limit", "gorgo_set_replay_packing", "gorgo_query_replay_packing", "gorgo_query_replay_path"):
             getattr(L, name).restype = C.c_int
@@ -293,6 +295,41 @@ def eval_population(trace: Trace, model: Model, rtt_ms, params, scale, *, per_re
         _check(lib().gorgo_eval_population(trace._h, C.byref(m), _ptr(rtt), _ptr(par), _ptr(sc), P, C.byref(o),
                                            C.c_void_p(workspace.data_ptr()), workspace.numel(),
                                            C.c_void_p(s.cuda_stream)))
+    return res
+
+
+STATIC_SCRATCH_BYTES = 64 << 20
+
+
+def eval_population_static(trace: Trace, model: Model, rtt_ms, params, scale, *, per_request: bool = True,
+                           p95: bool = True, stream=None, device="cuda:0") -> EvalResult:
+    """gorgo_eval_population_static: as eval_population, with the library's static scratch array as the workspace
+    (nothing is allocated by the library; the outputs are still torch tensors allocated here)."""
+    import torch
+    rtt = _np(rtt_ms, np.float64)
+    par = _np(params, np.float64)
+    P = par.shape[0]
+    sc = _np(np.broadcast_to(np.asarray(scale, dtype=np.float64), (P,)), np.float64)
+    if par.shape != (P, 3) or rtt.shape != (model.R,):
+        raise ValueError("params must be [P,3] and rtt_ms [R]")
+    N = trace.N
+    dev = torch.device(device)
+    res = EvalResult()
+    if per_request:
+        res.route = torch.empty((P, N), dtype=torch.uint8, device=dev)
+        res.hit_blocks = torch.empty((P, N), dtype=torch.uint16, device=dev)
+        res.ttft_ms = torch.empty((P, N), dtype=torch.float64, device=dev)
+        res.e2e_ms = torch.empty((P, N), dtype=torch.float64, device=dev)
+    if p95:
+        res.p95_ttft_ms = torch.empty((P,), dtype=torch.float64, device=dev)
+        res.p95_e2e_ms = torch.empty((P,), dtype=torch.float64, device=dev)
+    o = _outputs_struct(res.route, res.hit_blocks, res.ttft_ms, res.e2e_ms, res.p95_ttft_ms, res.p95_e2e_ms)
+    s = stream if stream is not None else torch.cuda.current_stream(dev)
+    m = model.c()
+    with torch.cuda.device(dev):
+        _check(lib().gorgo_trace_to_device(trace._h))
+        _check(lib().gorgo_eval_population_static(trace._h, C.byref(m), _ptr(rtt), _ptr(par), _ptr(sc), P, C.byref(o),
+                                                  C.c_void_p(s.cuda_stream)))
     return res
 
 

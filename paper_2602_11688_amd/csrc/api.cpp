@@ -362,6 +362,35 @@ int gorgo_eval_population(const gorgo_trace* t, const gorgo_model* m, const doub
     return evaluate(t, m, rtt_ms, params, scale, P, nullptr, 0, nullptr, outputs, workspace, workspace_bytes, hip_stream);
 }
 
+int gorgo_trace_to_device(const gorgo_trace* t) {
+    clear_error();
+    if (!t) return fail(GORGO_ERR_INVALID_ARG, "trace is NULL");
+    return upload_trace(t);
+}
+
+int gorgo_eval_population_static(const gorgo_trace* t, const gorgo_model* m, const double* rtt_ms, const double* params,
+                                 const double* scale, int32_t P, const gorgo_outputs* outputs, void* hip_stream) {
+    clear_error();
+    int rc = check_model(t, m);
+    if (rc) return rc;
+    if (!trace_is_resident(t))
+        return fail(GORGO_ERR_INVALID_ARG, "the trace is not resident on the current device: call gorgo_trace_to_device "
+                                           "(which allocates) once beforehand");
+    Plan pl;
+    if ((rc = make_plan(t, m, P, outputs, &pl))) return rc;
+    void* scratch = nullptr;
+    size_t have = 0;
+    if ((rc = static_scratch(&scratch, &have))) return rc;
+    if (pl.total > have)
+        return fail(GORGO_ERR_WORKSPACE, "this evaluation needs " + std::to_string(pl.total) + " bytes of workspace, the "
+                                         "library's static scratch holds " + std::to_string(have) +
+                                         " (GORGO_STATIC_SCRATCH_BYTES): use gorgo_eval_population with a caller workspace");
+    set_event_marks(false);       // no event is created or recorded on this path
+    rc = evaluate(t, m, rtt_ms, params, scale, P, nullptr, 0, nullptr, outputs, scratch, have, hip_stream);
+    set_event_marks(true);
+    return rc;
+}
+
 int64_t gorgo_online_steps(int64_t N, int32_t window, int32_t hop) {
     if (N < 0 || window < 1 || hop < 1) return -1;
     return N >= window ? (N - window) / hop + 1 : 0;

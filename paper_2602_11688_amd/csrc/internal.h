@@ -127,6 +127,9 @@ int launch_replay(const gorgo_trace* t, const Plan& pl, const double* d_rtt, con
 int launch_p95(const double* x, int64_t N, int32_t P, double* out, void* stream);
 int last_eval_kernel_ms(double* fill_ms, double* replay_ms, double* select_ms);
 int upload_trace(const gorgo_trace* t);
+bool trace_is_resident(const gorgo_trace* t);          // on the current device
+int static_scratch(void** ptr, size_t* bytes);         // device address and size of the library's static scratch array
+void set_event_marks(bool on);                         // whether this thread's evaluations record timing events
 void release_device_trace(gorgo_trace* t);
 int copy_small_to_device(void* dst, const void* src, size_t bytes, void* stream);
 int wait_for_copies(void* stream);

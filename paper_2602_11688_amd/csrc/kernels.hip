@@ -13,6 +13,7 @@
 // in the association (w_rtt*rtt + w_prefill*pf) + w_queue*qd, so that routes are reproducible bit for bit.
 #include <atomic>
 #include <hip/hip_runtime.h>
+#include <mutex>
 
 #include <cmath>
 #include <cstdint>
@@ -411,9 +412,15 @@ bool marks_ready() {
     return true;
 }
 
+thread_local bool g_marks_on = true;      // off for the evaluation that must not create or record events
+
 void mark(int i, hipStream_t s) {
-    if (g_marks.device >= 0) (void)hipEventRecord(g_marks.ev[i], s);
+    if (g_marks_on && g_marks.device >= 0) (void)hipEventRecord(g_marks.ev[i], s);
 }
+
+// Device memory for the entry point that allocates nothing: one array per GPU, there from the moment the library
+// is loaded until the process ends.  Host code only ever uses its device address, looked up once per device.
+static __device__ __align__(256) unsigned char scratch[GORGO_STATIC_SCRATCH_BYTES];
 
 }  // namespace
 
@@ -532,6 +539,32 @@ __global__ void smooth_rtt(const double* x, double* est, int epochs, int R, doub
 
 }  // namespace
 
+int static_scratch(void** ptr, size_t* bytes) {
+    static std::mutex mu;
+    static void* address[64] = {};        // per device: each GPU holds its own copy of the array at its own address
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+    if (dev < 0 || dev >= 64) return fail(GORGO_ERR_DEVICE, "device index out of range");
+    std::lock_guard<std::mutex> lock(mu);
+    if (!address[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) return hip_fail(e, "hipGetSymbolAddress(scratch)");
+        address[dev] = p;
+    }
+    *ptr = address[dev];
+    *bytes = sizeof(scratch);
+    return GORGO_OK;
+}
+
+bool trace_is_resident(const gorgo_trace* t) {
+    int dev = 0;
+    return hipGetDevice(&dev) == hipSuccess && t->dev.base && t->dev.device == dev;
+}
+
+void set_event_marks(bool on) { g_marks_on = on; }
+
 int launch_replay(const gorgo_trace* t, const Plan& pl, const double* d_rtt, const double* d_params,
                   const double* d_scale, uint8_t* route, uint16_t* hit, double* ttft, double* e2e,
                   void* workspace, void* stream, const OnlineLaunch* online, const PolicyLaunch* policy,
@@ -539,7 +572,7 @@ int launch_replay(const gorgo_trace* t, const Plan& pl, const double* d_rtt, con
     hipStream_t s = static_cast<hipStream_t>(stream);
     char* ws = static_cast<char*>(workspace);
     g_marks.valid = false;
-    marks_ready();
+    if (g_marks_on) marks_ready();
     mark(0, s);
     hipError_t e;
     if (pl.path == PATH_SEGMENTS) {
@@ -694,7 +727,7 @@ int launch_replay(const gorgo_trace* t, const Plan& pl, const double* d_rtt, con
     }
     mark(2, s);
     mark(3, s);
-    g_marks.valid = g_marks.device >= 0;
+    g_marks.valid = g_marks_on && g_marks.device >= 0;
     return GORGO_OK;
 }
 
