@@ -335,6 +335,22 @@ int gorgo_eval_proxy(const gorgo_trace* t, const gorgo_model* m, const gorgo_pro
  * kernel, and the percentile selection.  Waits for that evaluation to finish.  Each pointer may be NULL. */
 int gorgo_last_eval_kernel_ms(double* fill_ms, double* replay_ms, double* select_ms);
 
+/* Measurement aid: gorgo_eval_population run by an instantiation of the segment-row kernel that reads the GPU's
+ * cycle counter between the sections of its request loop and adds up, per replay and wavefront, the cycles each
+ * section took (same results; slower by the clock reads, each of which also waits for the wavefront's
+ * outstanding LDS accesses).  sections: DEVICE [P][2][GORGO_SECTIONS] uint64, [p][0] the cache wavefront
+ * (0 waiting for the queue terms, 1 match incl. the wait for its rows, 2 log records and the next rows, 3 score,
+ * minimum and announcement, 4 waiting at the second meeting point, 5 ownership, 6 stores, log and eviction,
+ * 7 patch and loop; then counts, not cycles: 8 log records fetched on the spot by the eviction walk, 9 cursor
+ * advances, 10 log records dropped because they own nothing, 11 ownership walks), [p][1] the queue wavefront (0 retire and publish, 1 waiting at the first meeting point,
+ * 2 retiring ahead, 3 front end, 4 waiting for the choice, 5 service and outputs, 6 batch turnover).  Needs the
+ * segment formulation without packing; everything else as gorgo_eval_population. */
+#define GORGO_SECTIONS 12
+int gorgo_eval_population_sections(const gorgo_trace* t, const gorgo_model* m, const double* rtt_ms,
+                                   const double* params, const double* scale, int32_t P,
+                                   const gorgo_outputs* outputs, void* workspace, size_t workspace_bytes,
+                                   void* hip_stream, uint64_t* sections);
+
 /* Choice of cache-state formulation for subsequent calls: 0 = automatic (default), 1 = hashed block tables
  * (any trace), 2 = dense segment rows (chain-consistent traces only; evaluation fails with
  * GORGO_ERR_INVALID_ARG otherwise).  Both compute identical results; they differ in workspace size and

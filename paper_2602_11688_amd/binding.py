@@ -76,6 +76,8 @@ def lib():
         L.gorgo_workspace_bytes.argtypes = [vp, C.POINTER(_Model), i32, C.POINTER(_Outputs), C.POINTER(C.c_size_t)]
         L.gorgo_eval_population.argtypes = [vp, C.POINTER(_Model), vp, vp, vp, i32, C.POINTER(_Outputs), vp,
                                             C.c_size_t, vp]
+        L.gorgo_eval_population_sections.argtypes = [vp, C.POINTER(_Model), vp, vp, vp, i32, C.POINTER(_Outputs), vp,
+                                                     C.c_size_t, vp, vp]
         L.gorgo_trace_to_device.argtypes = [vp]
         L.gorgo_eval_population_static.argtypes = [vp, C.POINTER(_Model), vp, vp, vp, i32, C.POINTER(_Outputs), vp]
         L.gorgo_online_steps.argtypes = [i64, i32, i32]
@@ -103,7 +105,7 @@ def lib():
         L.gorgo_query_replay_path.argtypes = [vp, C.POINTER(i32), C.POINTER(i64), C.POINTER(i64)]
         L.gorgo_last_eval_kernel_ms.argtypes = [C.POINTER(dbl)] * 3
         for name in ("gorgo_load_trace", "gorgo_load_trace_arrays", "gorgo_trace_info", "gorgo_workspace_bytes",
-                     "gorgo_eval_population", "gorgo_trace_to_device", "gorgo_eval_population_static", "gorgo_eval_online", "gorgo_eval_policy", "gorgo_eval_engine", "gorgo_eval_proxy", "gorgo_es_init", "gorgo_es_sample", "gorgo_es_propose",
+                     "gorgo_eval_population", "gorgo_eval_population_sections", "gorgo_trace_to_device", "gorgo_eval_population_static", "gorgo_eval_online", "gorgo_eval_policy", "gorgo_eval_engine", "gorgo_eval_proxy", "gorgo_es_init", "gorgo_es_sample", "gorgo_es_propose",
                      "gorgo_es_update", "gorgo_es_workspace_bytes", "gorgo_es_step", "gorgo_set_table_factor_percent",
                      "gorgo_last_eval_kernel_ms", "gorgo_set_replay_path", "gorgo_set_handover_poll_limit", "gorgo_set_replay_packing", "gorgo_query_replay_packing", "gorgo_query_replay_path"):
             getattr(L, name).restype = C.c_int
@@ -249,6 +251,7 @@ class EvalResult:
     p95_ttft_ms: object = None
     p95_e2e_ms: object = None
     workspace: object = None
+    sections: object = None         # [P, 2, 12] int64 cycles per section (eval_population(sections=True) only)
     # online tuner (eval_online only)
     theta_step: object = None       # [P, steps, 3] weights in use after each step
     fitness_step: object = None     # [P, steps] window p95 TTFT seen at each step
@@ -263,9 +266,10 @@ class EvalResult:
 
 
 def eval_population(trace: Trace, model: Model, rtt_ms, params, scale, *, per_request: bool = True,
-                    p95: bool = True, workspace=None, stream=None, device="cuda:0") -> EvalResult:
+                    p95: bool = True, workspace=None, stream=None, device="cuda:0", sections: bool = False) -> EvalResult:
     """gorgo_eval_population with torch-allocated outputs.  Returns device tensors; asynchronous on `stream`
-    (default: torch's current stream)."""
+    (default: torch's current stream).  sections=True runs gorgo_eval_population_sections instead and adds
+    `sections` [P, 2, 12] (cycles per section of the request loop, cache and queue wavefront) to the result."""
     import torch
     rtt = _np(rtt_ms, np.float64)
     par = _np(params, np.float64)
@@ -292,9 +296,15 @@ def eval_population(trace: Trace, model: Model, rtt_ms, params, scale, *, per_re
     s = stream if stream is not None else torch.cuda.current_stream(dev)
     m = model.c()
     with torch.cuda.device(dev):
-        _check(lib().gorgo_eval_population(trace._h, C.byref(m), _ptr(rtt), _ptr(par), _ptr(sc), P, C.byref(o),
-                                           C.c_void_p(workspace.data_ptr()), workspace.numel(),
-                                           C.c_void_p(s.cuda_stream)))
+        if sections:
+            res.sections = torch.zeros((P, 2, 12), dtype=torch.int64, device=dev)
+            _check(lib().gorgo_eval_population_sections(trace._h, C.byref(m), _ptr(rtt), _ptr(par), _ptr(sc), P, C.byref(o),
+                                                        C.c_void_p(workspace.data_ptr()), workspace.numel(),
+                                                        C.c_void_p(s.cuda_stream), C.c_void_p(res.sections.data_ptr())))
+        else:
+            _check(lib().gorgo_eval_population(trace._h, C.byref(m), _ptr(rtt), _ptr(par), _ptr(sc), P, C.byref(o),
+                                               C.c_void_p(workspace.data_ptr()), workspace.numel(),
+                                               C.c_void_p(s.cuda_stream)))
     return res
 
 

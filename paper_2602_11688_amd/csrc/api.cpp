@@ -22,6 +22,8 @@ int check_model(const gorgo_trace* t, const gorgo_model* m) {
     if (m->R < 1 || m->R > 64) return fail(GORGO_ERR_INVALID_ARG, "R must be in 1..64");
     if (m->batch < 1 || m->batch > 64) return fail(GORGO_ERR_INVALID_ARG, "batch must be in 1..64");
     if ((int64_t)m->R * m->batch > 1024) return fail(GORGO_ERR_INVALID_ARG, "R * batch must not exceed 1024");
+    if (m->block_tokens < 1 || m->block_tokens > 32767)      // (tokens of a cached prefix are counted in 32 bits)
+        return fail(GORGO_ERR_INVALID_ARG, "block_tokens must be in 1..32767");
     if (m->block_tokens != t->block_tokens)
         return fail(GORGO_ERR_INVALID_ARG, "model.block_tokens differs from the trace's");
     if (m->cache_blocks < 0 || m->cache_blocks > ((int64_t)1 << 30))
@@ -57,7 +59,7 @@ int make_plan(const gorgo_trace* t, const gorgo_model* m, int32_t P, const gorgo
     const bool few = (int64_t)t->seg.size() <= 16 * (t->N > 0 ? t->N : 1);
     pl->path = mode == PATH_SEGMENTS || (mode == PATH_AUTO && seg_ok && few) ? PATH_SEGMENTS : PATH_BLOCKS;
     pl->nseg = t->n_segments;
-    if (pl->path == PATH_SEGMENTS && (uint64_t)(pl->nseg > 0 ? pl->nseg : 1) * (uint64_t)m->R * 4u >= (1ull << 32))
+    if (pl->path == PATH_SEGMENTS && (uint64_t)(pl->nseg + 2) * (uint64_t)m->R * 4u >= (1ull << 32))
         return fail(GORGO_ERR_INVALID_ARG, "segment rows of one replay exceed 4 GiB; use the block-table formulation");
     // A table must hold the cached blocks plus the blocks of the request being inserted, with room to
     // spare: the replay compacts a table once 7/8 of its slots have been used.
@@ -74,9 +76,9 @@ int make_plan(const gorgo_trace* t, const gorgo_model* m, int32_t P, const gorgo
     size_t off = 0;
     pl->off_tables = off;
     if (pl->path == PATH_SEGMENTS) {
-        off += up256((size_t)P * (size_t)(pl->nseg > 0 ? pl->nseg : 1) * pl->R * 4);   // at least one row
+        off += up256((size_t)P * (size_t)(pl->nseg + 2) * pl->R * 4);   // a row per segment, one that no request touches, a spare
         pl->off_spare = off;                              // per-request log records of the segment kernel
-        off += up256((size_t)P * (size_t)t->N * 8);
+        off += up256((size_t)P * ((size_t)t->N + 1) * 8);            // (and a spare record per replay)
     } else {
         off += up256((size_t)P * pl->R * (size_t)cap * 16);
         pl->off_spare = off;
@@ -134,7 +136,7 @@ int gorgo_query_replay_packing(const gorgo_trace* t, const gorgo_model* m, int32
     Plan pl;
     rc = make_plan(t, m, P, nullptr, &pl);
     if (rc) return rc;
-    *packed = pl.path == PATH_SEGMENTS && pack_replays(pl, pl.nseg > 0 ? pl.nseg : 1) ? 1 : 0;
+    *packed = pl.path == PATH_SEGMENTS && pack_replays(pl, pl.nseg + 2) ? 1 : 0;
     return GORGO_OK;
 }
 
@@ -179,7 +181,8 @@ namespace {
 int evaluate(const gorgo_trace* t, const gorgo_model* m, const double* rtt_ms, const double* params,
              const double* scale, int32_t P, const gorgo_online* online, int32_t policy, const uint64_t* seeds,
              const gorgo_outputs* outputs, void* workspace, size_t workspace_bytes, void* hip_stream,
-             const gorgo_engine* engine = nullptr, const gorgo_proxy* proxy = nullptr) {
+             const gorgo_engine* engine = nullptr, const gorgo_proxy* proxy = nullptr,
+             unsigned long long* sections = nullptr) {
     int rc = check_model(t, m);
     if (rc) return rc;
     if (proxy) {
@@ -344,7 +347,8 @@ int evaluate(const gorgo_trace* t, const gorgo_model* m, const double* rtt_ms, c
     double* e2e = outputs->e2e_ms;
     if (!e2e && outputs->p95_e2e_ms) e2e = reinterpret_cast<double*>(ws + pl.off_e2e);
     rc = launch_replay(t, pl, d_rtt, d_params, d_scale, route, outputs->hit_blocks, ttft, e2e, workspace, hip_stream,
-                       online ? &ol : nullptr, policy != 0 ? &pol : nullptr, engine ? &el : nullptr, proxy ? &xl : nullptr);
+                       online ? &ol : nullptr, policy != 0 ? &pol : nullptr, engine ? &el : nullptr, proxy ? &xl : nullptr,
+                       sections);
     if (rc) return rc;
     if (outputs->p95_ttft_ms && (rc = launch_p95(ttft, pl.N, P, outputs->p95_ttft_ms, hip_stream))) return rc;
     if (outputs->p95_e2e_ms && (rc = launch_p95(e2e, pl.N, P, outputs->p95_e2e_ms, hip_stream))) return rc;
@@ -360,6 +364,15 @@ int gorgo_eval_population(const gorgo_trace* t, const gorgo_model* m, const doub
                           size_t workspace_bytes, void* hip_stream) {
     clear_error();
     return evaluate(t, m, rtt_ms, params, scale, P, nullptr, 0, nullptr, outputs, workspace, workspace_bytes, hip_stream);
+}
+
+int gorgo_eval_population_sections(const gorgo_trace* t, const gorgo_model* m, const double* rtt_ms, const double* params,
+                                   const double* scale, int32_t P, const gorgo_outputs* outputs, void* workspace,
+                                   size_t workspace_bytes, void* hip_stream, uint64_t* sections) {
+    clear_error();
+    if (!sections) return fail(GORGO_ERR_INVALID_ARG, "sections is NULL");
+    return evaluate(t, m, rtt_ms, params, scale, P, nullptr, 0, nullptr, outputs, workspace, workspace_bytes, hip_stream,
+                    nullptr, nullptr, reinterpret_cast<unsigned long long*>(sections));
 }
 
 int gorgo_trace_to_device(const gorgo_trace* t) {

@@ -118,12 +118,12 @@ struct ProxyLaunch {
 // kernels.hip
 void set_handover_poll_limit(int32_t polls);
 void set_replay_packing(int32_t mode);
-bool pack_replays(const Plan& pl, int64_t nseg);
+bool pack_replays(const Plan& pl, int64_t rows);     // rows of one replay: its segments + 2
 int launch_replay(const gorgo_trace* t, const Plan& pl, const double* d_rtt, const double* d_params,
                   const double* d_scale, uint8_t* route, uint16_t* hit, double* ttft, double* e2e,
                   void* workspace, void* stream, const OnlineLaunch* online = nullptr,
                   const PolicyLaunch* policy = nullptr, const EngineLaunch* engine = nullptr,
-                  const ProxyLaunch* proxy = nullptr);
+                  const ProxyLaunch* proxy = nullptr, unsigned long long* sections = nullptr);
 int launch_p95(const double* x, int64_t N, int32_t P, double* out, void* stream);
 int last_eval_kernel_ms(double* fill_ms, double* replay_ms, double* select_ms);
 int upload_trace(const gorgo_trace* t);

@@ -324,6 +324,13 @@ __global__ void __launch_bounds__(256) fill_i32(int32_t* x, size_t n, int32_t v)
     for (; i < n; i += stride) x[i] = v;
 }
 
+// The last row but one of every replay's rows (the one no request touches) gets the cell value that is below any
+// cursor.
+__global__ void __launch_bounds__(256) fill_last_rows(int32_t* x, int32_t P, int64_t rows, int32_t R, int32_t v) {
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < (size_t)P * R) x[((i / R) * (size_t)rows + (size_t)(rows - 2)) * R + i % R] = v;
+}
+
 // ---- exact nearest-rank percentile: k-th smallest of x[p][0..N) by most-significant-digit radix selection
 // on the order-preserving integer image of the doubles.  One 256-thread workgroup per row.
 constexpr int SEL_THREADS = 256;
@@ -490,17 +497,17 @@ void set_replay_packing(int32_t mode) { g_packing.store(mode); }
 // Whether a launch of fixed-weight replays runs two replays per wavefront pair.  A replay is a serial chain whose
 // duration does not depend on how many others run beside it, and a packed pair takes a few percent longer per
 // request than a lone replay: packing pays exactly when the replays would not all be resident at once otherwise.
-bool pack_replays(const Plan& pl, int64_t nseg) {
+bool pack_replays(const Plan& pl, int64_t rows) {
     const int32_t mode = g_packing.load();
     if (mode == 0 || pl.R > HALF || pl.B > 16 || pl.P % 2 != 0 ||
-        2ull * (uint64_t)nseg * (uint64_t)pl.R * 4u >= (1ull << 32))
+        2ull * (uint64_t)rows * (uint64_t)pl.R * 4u >= (1ull << 32))
         return false;
     if (mode == 1) return true;
     int device = 0, cus = 0, per_cu = 0;
     if (hipGetDevice(&device) != hipSuccess ||
         hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess ||
         hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, replay_segments_kernel<MODE_COST_MODEL, false, false>,
-                                                     SEG_THREADS, replay_segments_lds_bytes(pl.R, pl.B, 0)) != hipSuccess)
+                                                     SEG3_THREADS, replay_segments_lds_bytes(pl.R, pl.B, 0)) != hipSuccess)
         return false;
     return (int64_t)pl.P > (int64_t)cus * per_cu;
 }
@@ -568,7 +575,7 @@ void set_event_marks(bool on) { g_marks_on = on; }
 int launch_replay(const gorgo_trace* t, const Plan& pl, const double* d_rtt, const double* d_params,
                   const double* d_scale, uint8_t* route, uint16_t* hit, double* ttft, double* e2e,
                   void* workspace, void* stream, const OnlineLaunch* online, const PolicyLaunch* policy,
-                  const EngineLaunch* engine, const ProxyLaunch* proxy) {
+                  const EngineLaunch* engine, const ProxyLaunch* proxy, unsigned long long* sections) {
     hipStream_t s = static_cast<hipStream_t>(stream);
     char* ws = static_cast<char*>(workspace);
     g_marks.valid = false;
@@ -586,7 +593,7 @@ int launch_replay(const gorgo_trace* t, const Plan& pl, const double* d_rtt, con
         a.R = pl.R;
         a.B = pl.B;
         a.C = pl.C;
-        a.nseg = pl.nseg > 0 ? pl.nseg : 1;
+        a.nseg = pl.nseg + 2;             // rows of one replay: one per segment, one that no request touches, a spare
         a.block_tokens = pl.block_tokens;
         a.a_pf = pl.a_pf;
         a.a_dec = pl.a_dec;
@@ -607,7 +614,7 @@ int launch_replay(const gorgo_trace* t, const Plan& pl, const double* d_rtt, con
         a.accepted = nullptr;
         a.first_hash = t->dev.first_hash;
         a.seeds = policy ? policy->seeds : nullptr;
-        a.spin_limit = g_poll_limit.load();
+        a.spin_limit = g_poll_limit.load();     // (only the packed kernel still polls)
         a.eng_a_pf = engine ? engine->a_pf : nullptr;
         a.eng_a_dec = engine ? engine->a_dec : nullptr;
         a.eng_budget = engine ? engine->budget : nullptr;
@@ -618,6 +625,9 @@ int launch_replay(const gorgo_trace* t, const Plan& pl, const double* d_rtt, con
         a.rtt_est = proxy ? proxy->rtt_est : nullptr;
         a.index_blocks = proxy ? proxy->index_blocks : -1;
         a.believed = proxy ? proxy->believed : nullptr;
+        a.sections = sections;
+        if (sections && (online || engine || proxy || (policy && policy->policy != 0)))
+            return fail(GORGO_ERR_INVALID_ARG, "section timing exists for the fixed-weight cost model with the linear replica model");
         if (proxy) {
             if (policy && policy->policy != 0)
                 return fail(GORGO_ERR_INVALID_ARG, "imperfect proxy knowledge concerns the cost model, not the baseline policies");
@@ -631,6 +641,9 @@ int launch_replay(const gorgo_trace* t, const Plan& pl, const double* d_rtt, con
             if (blocks > 65536) blocks = 65536;
             hipLaunchKernelGGL(fill_i32, dim3((unsigned)blocks), dim3(256), 0, s, a.last, cells, (int32_t)-1);
             if ((e = hipGetLastError()) != hipSuccess) return hip_fail(e, "launch fill_i32");
+            hipLaunchKernelGGL(fill_last_rows, dim3((unsigned)(((size_t)pl.P * pl.R + 255) / 256)), dim3(256), 0, s, a.last,
+                               pl.P, a.nseg, pl.R, NEVER_CACHED);
+            if ((e = hipGetLastError()) != hipSuccess) return hip_fail(e, "launch fill_last_rows");
         }
         mark(1, s);
         if (pl.N > 0 || online) {      // (an empty trace still reports the tuner's initial state)
@@ -647,32 +660,35 @@ int launch_replay(const gorgo_trace* t, const Plan& pl, const double* d_rtt, con
                 a.sigma_final = online->sigma_final;
                 a.accepted = online->accepted;
                 const size_t lds = replay_segments_lds_bytes(pl.R, pl.B, online->window);
-                const dim3 grid((unsigned)pl.P), block(SEG_THREADS);
+                const dim3 grid((unsigned)pl.P), block(SEG3_THREADS);
                 if (proxy && engine) hipLaunchKernelGGL((replay_segments_kernel<MODE_ONLINE, true, true>), grid, block, lds, s, a);
                 else if (proxy) hipLaunchKernelGGL((replay_segments_kernel<MODE_ONLINE, false, true>), grid, block, lds, s, a);
                 else if (engine) hipLaunchKernelGGL((replay_segments_kernel<MODE_ONLINE, true, false>), grid, block, lds, s, a);
                 else hipLaunchKernelGGL((replay_segments_kernel<MODE_ONLINE, false, false>), grid, block, lds, s, a);
             } else if (proxy) {
                 const size_t lds = replay_segments_lds_bytes(pl.R, pl.B, 0);
-                const dim3 grid((unsigned)pl.P), block(SEG_THREADS);
+                const dim3 grid((unsigned)pl.P), block(SEG3_THREADS);
                 if (engine) hipLaunchKernelGGL((replay_segments_kernel<MODE_COST_MODEL, true, true>), grid, block, lds, s, a);
                 else hipLaunchKernelGGL((replay_segments_kernel<MODE_COST_MODEL, false, true>), grid, block, lds, s, a);
             } else if (engine) {
                 const size_t lds = replay_segments_lds_bytes(pl.R, pl.B, 0);
-                const dim3 grid((unsigned)pl.P), block(SEG_THREADS);
+                const dim3 grid((unsigned)pl.P), block(SEG3_THREADS);
                 switch (policy ? policy->policy : 0) {
                     case 0: hipLaunchKernelGGL((replay_segments_kernel<MODE_COST_MODEL, true, false>), grid, block, lds, s, a); break;
                     case 1: hipLaunchKernelGGL((replay_segments_kernel<MODE_LEAST_REQUEST, true, false>), grid, block, lds, s, a); break;
                     case 2: hipLaunchKernelGGL((replay_segments_kernel<MODE_AFFINITY, true, false>), grid, block, lds, s, a); break;
                     default: hipLaunchKernelGGL((replay_segments_kernel<MODE_RANDOM, true, false>), grid, block, lds, s, a); break;
                 }
+            } else if (sections) {
+                hipLaunchKernelGGL((replay_segments_kernel<MODE_COST_MODEL, false, false, true>), dim3((unsigned)pl.P),
+                                   dim3(SEG3_THREADS), replay_segments_lds_bytes(pl.R, pl.B, 0), s, a);
             } else if (!(policy && policy->policy != 0) && pack_replays(pl, a.nseg)) {
                 // fixed weights, at most 32 replicas: two replays per wavefront pair
                 hipLaunchKernelGGL(replay_segments_packed_kernel, dim3((unsigned)(pl.P / 2)), dim3(SEG_THREADS),
                                    replay_segments_packed_lds_bytes(pl.B), s, a);
             } else {
                 const size_t lds = replay_segments_lds_bytes(pl.R, pl.B, 0);
-                const dim3 grid((unsigned)pl.P), block(SEG_THREADS);
+                const dim3 grid((unsigned)pl.P), block(SEG3_THREADS);
                 switch (policy ? policy->policy : 0) {
                     case 0: hipLaunchKernelGGL((replay_segments_kernel<MODE_COST_MODEL, false, false>), grid, block, lds, s, a); break;
                     case 1: hipLaunchKernelGGL((replay_segments_kernel<MODE_LEAST_REQUEST, false, false>), grid, block, lds, s, a); break;
@@ -683,6 +699,7 @@ int launch_replay(const gorgo_trace* t, const Plan& pl, const double* d_rtt, con
             if ((e = hipGetLastError()) != hipSuccess) return hip_fail(e, "launch replay_segments_kernel");
         }
     } else {
+        if (sections) return fail(GORGO_ERR_INVALID_ARG, "section timing needs the segment formulation");
         if (online || engine || proxy || (policy && policy->policy != 0))
             return fail(GORGO_ERR_INVALID_ARG, "the online tuner, the baseline policies, the engine model and imperfect "
                                                "proxy knowledge need the segment formulation");

@@ -16,18 +16,21 @@
 // own nothing any more are dropped from the walk as soon as they are seen.
 //
 // The request loop is one dependent chain per replay, and a lone wavefront issues about one instruction
-// every four to five cycles whatever its kind, so the kernel is arranged around instruction count and
-// latency, not bandwidth.  A replay is run by two wavefronts of one workgroup.  The cache wavefront keeps the
-// cache side (lane = replica: cursor, the next log records) in its registers, matches, scores, picks the
-// replica and updates rows and log; the queue wavefront keeps the queue side (lane = replica: load signal,
-// earliest completion; service slots in LDS), retires completed requests before every request and serves it
-// once the replica is known.  They meet twice per request through LDS: the queue wavefront publishes the load
-// signals of request r, the cache wavefront answers with the chosen replica and its uncached tokens.  The
-// queue wavefront has the shorter loop, so the cache wavefront normally finds the load signals waiting.
-// In the cache wavefront a batch of 64 requests is staged at once (scalars in registers, segment references
-// in LDS); the rows of request i+1 and one log record per replica are requested right after the wait for the
-// rows of request i, so that an iteration has a single point where it waits for memory; stores are
-// fire-and-forget.
+// every four to five cycles whatever its kind (a branch costs three to four times that), so the kernel is
+// arranged around the instruction count of that chain, not around bandwidth.  A replay is run by two
+// wavefronts of one workgroup that meet at two workgroup barriers per request.
+//   The cache wavefront (lane = replica) holds the cache side in registers: eviction cursor, the next log
+// records, the row cells of the current and the next request.  Per request it matches, scores, takes the
+// minimum, announces the choice, then updates rows, log and cursor.  It does nothing else.
+//   The queue wavefront (lane = replica) owns the service slots (LDS) and the load signal: before request r it
+// retires what has completed by t_r and publishes every replica's queue term of Eq. 3; after the choice it
+// serves the request and keeps the latencies and the per-request outputs.  It has the shorter chain, so it
+// also is the trace's front end: three requests ahead it reads the request's segment references and leaves a
+// descriptor in a small LDS ring -- row offsets, end positions, flags -- from which the cache wavefront
+// issues its row loads without any address arithmetic or staging of its own.
+//   Barrier A(r): the queue terms of r are published (and the descriptor of r + 1 is complete).  Barrier
+// B(r): the choice of r is published.  Every wavefront executes exactly two barriers per request, whatever
+// the data, so neither can wait for ever.
 #pragma once
 #include "device_common.h"
 #include "internal.h"
@@ -91,6 +94,7 @@ struct SegArgs {
     int64_t index_blocks;         // >= 0: Eq. 3 takes its cached prefix from the proxy's own index (an LRU of this
                                   // many blocks per replica, 0 = it never forgets); < 0: from the replica's cache
     uint16_t* believed;           // [P][N] blocks the proxy believed cached on the chosen replica, nullable
+    unsigned long long* sections; // timed instantiation only: [P][2][SECTIONS] cycles per section (cache, queue wavefront)
 };
 
 // What picks the replica: the cost model of Eq. 3 with fixed weights, the same with the online tuner, or one
@@ -122,24 +126,13 @@ __device__ __forceinline__ uint32_t philox4x32_10_first(uint32_t c0, uint32_t c1
 
 constexpr int SEG_STAGE = 512;   // segment references of a 64-request batch staged in LDS
 constexpr int SEG_CHUNK = 8;     // segments of a request whose rows are loaded together
-constexpr int SEG_THREADS = 2 * WAVE;        // cache wavefront + queue wavefront
+constexpr int SEG_THREADS = 2 * WAVE;        // two replays per wavefront pair: cache wavefront + queue wavefront
+constexpr int SEG3_THREADS = 3 * WAVE;       // cache, queue and front-end wavefront
 constexpr int SEG_SPIN_LIMIT = 1 << 24;      // default: polls of a hand-over word before the replay is given up (~1 s)
 
-// Hand-over words between the two wavefronts of a replay, in LDS.  Every word carries the number of the
-// request it belongs to (r + 1, so that the initial zero matches nothing).  They are read and written with
-// relaxed workgroup-scope atomics on the LDS variable itself (so that they stay LDS instructions).  The LDS
-// executes the instructions of one wavefront in the order they were issued, for reads as for writes, so data
-// written before a word is there for whoever reads it after having read that word; the fences between data
-// and word only have to keep the compiler from changing that order, and cost no wait.
-struct SegComm {
-    double q[WAVE];                   // load signal per replica, valid when seq_q == r + 1
-    unsigned seq_q;
-    int abandoned;                    // a wavefront gave up waiting: both leave, latencies become NaN
-    unsigned long long choice;        // uncached tokens | (((r + 1) mod 2^26) << 6 | replica) << 32
-    double w[3];                      // online tuner: weights in use, valid with seq_q like q
-    double rtt[WAVE];                 // proxy variants: estimated round trip time per replica, valid like q
-};
-
+// Fences between LDS data and the word that announces it (two replays per wavefront pair still hand over
+// through polled words): the LDS executes the instructions of one wavefront in the order they were issued, so
+// the fences only have to keep the compiler from changing that order, and cost no wait.
 __device__ __forceinline__ void lds_release() { __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront"); }
 __device__ __forceinline__ void lds_acquire() { __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront"); }
 
@@ -242,17 +235,203 @@ __device__ __forceinline__ int cached_in(int32_t rl, int pos, int end, int c_r, 
     return rl > c_r ? len : (rl == c_r ? part : 0);
 }
 
-// Queue wavefront of a replay: for every request, retire what has completed by its arrival, publish the load
-// signals, wait for the cache wavefront's choice, serve the request there.  Writes the latencies.
-template <int MODE, bool ENGINE, bool PROXY>
-__device__ __forceinline__ void queue_wave(const SegArgs& a, int p, int lane, unsigned char* lds_raw, SegComm* comm) {
+
+// ---------------------------------------------------------------------------------------------- hand-over
+// Descriptor of one request, written by the queue wavefront's front end, read by the cache wavefront.
+struct SegEnt {
+    uint32_t rowoff;     // byte offset of the segment's row within the replay's rows
+    int32_t end;         // blocks of the request up to and including this segment
+};
+struct SegDesc {
+    SegEnt e[8];         // first eight segments; past the last one: the never-cached row, n
+    int32_t L, n, s;     // input tokens, blocks, segments
+    int32_t flags;       // DESC_MORE4 | DESC_DEEP | leading segments shared with the previous request << 8
+    int64_t j0;          // index of the request's first segment reference (for requests of more than 8 segments)
+    int32_t target;      // replica dictated by the session-affinity / random policy
+    int32_t pad;
+};
+static_assert(sizeof(SegDesc) == 96, "descriptor layout");
+constexpr int DESC_RING = 8;         // descriptors in flight (power of two)
+constexpr int DESC_AHEAD = 3;        // the front end reads references this many requests ahead
+constexpr int DESC_MORE4 = 1;        // more than four segments
+constexpr int DESC_DEEP = 2;         // more than eight segments
+constexpr int32_t NEVER_CACHED = INT32_MIN;      // cell value of the extra row: below any cursor
+
+struct Handover {
+    double sq[WAVE];                  // per replica: queue term of Eq. 3, w_queue * (a_pf * outstanding tokens)
+                                      // (least-request policy: requests in flight)
+    double rtt[WAVE];                 // proxy variants: estimated round trip time per replica
+    double w[2];                      // online tuner: w_rtt, w_prefill in use
+    unsigned long long choice;        // uncached tokens | (replica | cached blocks << 8) << 32
+    unsigned long long unused[WAVE];  // where the lanes other than lane 0 write when the choice is announced
+    int seen;                         // proxy variants: blocks the proxy believed cached on the chosen replica
+    SegDesc ring[DESC_RING];
+};
+
+// Workgroup barrier that both wavefronts of a replay meet at; `after_lds`: this wavefront's LDS accesses have
+// been performed before it arrives (what it wrote is there for the partner, what it read has been read).
+// Global memory is not waited for: every global location is only ever touched by one of the two wavefronts.
+__device__ __forceinline__ void meet(bool after_lds) {
+    if (after_lds) asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    else asm volatile("s_barrier" ::: "memory");
+}
+
+// Section clock of the timed instantiation: cycles since the previous call are added to section k.  (Reading the
+// clock waits for this wavefront's outstanding LDS and scalar-memory accesses, which the plain kernel does not.)
+constexpr int SECTIONS = 12;
+template <bool TIMED>
+struct SectionClock {
+    unsigned long long acc[SECTIONS] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+    unsigned long long last = 0;
+    __device__ __forceinline__ void start() {
+        if (TIMED) last = __builtin_readcyclecounter();
+    }
+    __device__ __forceinline__ void tick(int k) {
+        if (TIMED) {
+            const unsigned long long now = __builtin_readcyclecounter();
+            acc[k] += now - last;
+            last = now;
+        }
+    }
+    __device__ __forceinline__ void write(unsigned long long* out, int lane) {
+        if (TIMED && out && lane == 0)
+            for (int k = 0; k < SECTIONS; ++k) out[k] = acc[k];
+    }
+};
+
+__device__ __forceinline__ unsigned long long ballot(bool c) { return __builtin_amdgcn_ballot_w64(c); }
+
+// Lowest-index minimum as wave_argmin, with the lane mask given.
+__device__ __forceinline__ int argmin_lanes(double v, bool in) {
+    const unsigned long long bits = (unsigned long long)__double_as_longlong(v + 0.0);
+    const unsigned hi = (unsigned)(bits >> 32), lo = (unsigned)bits;
+    const unsigned neg = (unsigned)((int)hi >> 31);
+    const unsigned khi = in ? hi ^ (neg | 0x80000000u) : 0xffffffffu;
+    const unsigned mhi = wave_min_u32(khi);
+    const bool tie = khi == mhi;             // (lanes outside hold the all-ones key, which no score maps to)
+    const unsigned long long ties = ballot(tie);
+    if ((ties & (ties - 1)) == 0) return __builtin_ctzll(ties);      // one lane holds the smallest high word: done
+    const unsigned klo = lo ^ neg;
+    const unsigned mlo = wave_min_u32(tie ? klo : 0xffffffffu);
+    return __builtin_ctzll(ballot(tie && klo == mlo));
+}
+
+// ---------------------------------------------------------------------------------------------- front end
+// Front-end wavefront of a replay: walks the trace DESC_AHEAD requests ahead of the other two and leaves every
+// request's descriptor in the ring.  Lane k < 8 holds segment reference k of the request in hand, lane 8 the last
+// one (whose end position is the request's number of blocks).  It takes part in both meetings of every request
+// (a workgroup barrier counts every wavefront) and is always early.
+template <int MODE>
+__device__ __forceinline__ void front_wave(const SegArgs& a, int p, int lane, Handover* comm) {
+    const int R = a.R;
+    const int64_t N = a.N;
+    const uint64_t seed = MODE == MODE_RANDOM ? a.seeds[p] : 0;
+    const uint32_t seed_lo = (uint32_t)seed, seed_hi = (uint32_t)(seed >> 32);
+    // the trace, 64 requests per lane-held batch (lane = request), two batches deep
+    struct Batch {
+        int L, s;        // input tokens, segment references
+        int64_t j0;      // first segment reference
+        uint32_t hash;   // session-affinity policy: hash of the first block
+    };
+    auto load_batch = [&](int64_t b0, Batch& b) {
+        const int64_t x = b0 + lane;
+        const bool in = x < N;
+        const int64_t xx = in ? x : N - 1;
+        b.L = in ? a.in_len[xx] : 0;
+        const int64_t j0 = a.seg_off[xx], j1 = a.seg_off[xx + 1];
+        b.j0 = j0;
+        b.s = in ? (int)(j1 - j0) : 0;               // (requests past the end look empty)
+        b.hash = MODE == MODE_AFFINITY ? a.first_hash[xx] : 0u;
+    };
+    Batch cur, nxt;
+    int64_t b0 = 0;
+    load_batch(0, cur);
+    load_batch(WAVE, nxt);
+    const uint32_t row_bytes = (uint32_t)R * 4u;
+    const uint32_t never_off = (uint32_t)(a.nseg - 2) * row_bytes;      // the extra row that no request touches
+    int pend_id = 0, pend_end = 0, pend_s = 0, pend_L = 0, pend_target = 0;
+    int64_t pend_j0 = 0;
+    int prev_id = 0, prev_end = 0, prev_s = 0;
+    // request j's references are requested ... (j in this batch or the next)
+    auto fe_issue = [&](int64_t j) {
+        const int jj = (int)(j - b0);
+        const bool here = jj < WAVE;
+        const int jl = here ? jj : jj - WAVE;
+        const int s = here ? __builtin_amdgcn_readlane(cur.s, jl) : __builtin_amdgcn_readlane(nxt.s, jl);
+        pend_L = here ? __builtin_amdgcn_readlane(cur.L, jl) : __builtin_amdgcn_readlane(nxt.L, jl);
+        pend_j0 = here ? readlane_i64(cur.j0, jl) : readlane_i64(nxt.j0, jl);
+        pend_s = s;
+        if (MODE == MODE_AFFINITY) {
+            const uint32_t h = (uint32_t)(here ? __builtin_amdgcn_readlane((int)cur.hash, jl) : __builtin_amdgcn_readlane((int)nxt.hash, jl));
+            pend_target = s > 0 ? spread(h, R) : 0;
+        } else if (MODE == MODE_RANDOM) {
+            pend_target = spread(philox4x32_10_first((uint32_t)j, (uint32_t)((uint64_t)j >> 32), seed_lo, seed_hi), R);
+        }
+        const int k = lane < 8 ? lane : s - 1;
+        const bool on = lane < 8 ? lane < s : (lane == 8 && s > 0);
+        SegRef ref{0, 0};
+        if (on) ref = a.seg[pend_j0 + k];
+        pend_id = ref.id;
+        pend_end = ref.end;
+    };
+    // ... and one request later its descriptor is written
+    auto fe_commit = [&](int64_t j) {
+        const int s = pend_s;
+        const int n = s > 0 ? __builtin_amdgcn_readlane(pend_end, 8) : 0;
+        SegDesc* const d = &comm->ring[j & (DESC_RING - 1)];
+        const bool real = lane < s;
+        const uint32_t off = real ? (uint32_t)pend_id * row_bytes : never_off;
+        const int end = real ? pend_end : n;
+        if (lane < 8) d->e[lane] = SegEnt{off, end};
+        // leading segments shared with the previous request (same tree, same path so far): the cache wavefront
+        // has requested this request's rows before the previous request's stores, and patches exactly these
+        const bool same = lane < 8 && lane < s && lane < prev_s && pend_id == prev_id && pend_end == prev_end;
+        const unsigned differ = ~(unsigned)ballot(same) | 0x100u;
+        const int common = __builtin_ctz(differ);
+        if (lane == 0) {
+            d->L = pend_L;
+            d->n = n;
+            d->s = s;
+            d->flags = (s > 4 ? DESC_MORE4 : 0) | (s > 8 ? DESC_DEEP : 0) | (common << 8);
+            d->j0 = pend_j0;
+            d->target = pend_target;
+        }
+        prev_id = pend_id;
+        prev_end = pend_end;
+        prev_s = s;
+    };
+    fe_issue(0);
+    fe_commit(0);
+    fe_issue(1);
+    fe_commit(1);
+    fe_issue(2);
+    meet(true);         // the first descriptors are there: the cache wavefront may start
+    for (int64_t r = 0; r < N; ++r) {
+        // in the long stretch between B(r - 1) and A(r), where the cache wavefront reads the descriptor of r + 1
+        fe_commit(r + 2);           // (first read by the cache wavefront after B(r))
+        fe_issue(r + 3);
+        if (r + 1 - b0 == WAVE) {
+            cur = nxt;
+            b0 += WAVE;
+            load_batch(b0 + WAVE, nxt);
+        }
+        meet(true);                                                  // A(r)
+        meet(false);                                                 // B(r)
+    }
+}
+
+// ---------------------------------------------------------------------------------------------- queue side
+// Queue wavefront of a replay.  Per request: retire what has completed by its arrival, publish the queue
+// terms, meet (A); retire ahead to the next arrival and run the front end; meet (B); serve the request on
+// the chosen replica.  Keeps and writes the latencies and the per-request outputs.
+template <int MODE, bool ENGINE, bool PROXY, bool TIMED>
+__device__ __forceinline__ void queue_wave(const SegArgs& a, int p, int lane, unsigned char* lds_raw, Handover* comm) {
     constexpr bool ONLINE = MODE == MODE_ONLINE;
     const int R = a.R;
     const int64_t N = a.N;
     Queues Q;
     Q.carve(lds_raw, R, a.B, lane);
     Q.init(lane);
-    wave_sync();
     // Online tuner (Sec. 2.3, Sec. 4), run here because this wavefront has the TTFTs: after every hop the p95
     // TTFT of the last `window` requests is the fitness of the weights in use; they replace the parent iff they
     // beat it; the step size follows the 1/5 rule; the next offspring is a log-space mutation of the parent.
@@ -270,147 +449,173 @@ __device__ __forceinline__ void queue_wave(const SegArgs& a, int p, int lane, un
         for (int k = 0; k < 3; ++k) ln_par[k] = ln_cur[k] = a.ln_theta0[3 * (size_t)p + k];
         sigma = a.tuner[12];
         if (W + lane < ((W + 7) & ~7)) ring[W + lane] = INFINITY;     // padding (entries below W are written before use)
-        wave_sync();
     }
+    auto tuner_results = [&]() {
+        if (ONLINE && lane == 0) {
+            if (a.theta_final)
+                for (int k = 0; k < 3; ++k)
+                    a.theta_final[3 * (size_t)p + k] = clip(tuner_exp(ln_par[k]), a.tuner[k], a.tuner[3 + k]);
+            if (a.sigma_final) a.sigma_final[p] = sigma;
+            if (a.accepted) a.accepted[p] = accepted;
+        }
+    };
+    if (N == 0) {           // (an empty trace still reports the tuner's initial state)
+        tuner_results();
+        return;
+    }
+    double w_queue = a.params[3 * (size_t)p + 2];      // (the online tuner replaces it at every step)
     const double sc = a.scale[p];
     double my_rtt = lane < R ? (PROXY ? a.rtt_true[lane] : a.rtt[lane]) : 0.0;
     // imperfect proxy knowledge (Sec. 2.2, Sec. 4 RTT figure): time is cut into probe epochs, the epoch of t being
     // the largest e with e * probe_ms <= t (capped at the last one given); a request experiences the true round
     // trip time of its epoch, the cost model scores with the proxy's moving average, handed to the cache wavefront
-    // with the load signals
+    // with the queue terms
     int epoch = 0;
     double next_probe = PROXY ? (double)a.probe_ms : 0.0;
-    if (PROXY) st(&comm->rtt[lane], lane < R ? a.rtt_est[lane] : 0.0);
+    if (PROXY) comm->rtt[lane] = lane < R ? a.rtt_est[lane] : 0.0;
     // engine model: this lane's replica has its own rates and KV budget
     const double my_a_pf = ENGINE && lane < R ? a.eng_a_pf[lane] : 0.0;
     const double my_a_dec = ENGINE && lane < R ? a.eng_a_dec[lane] : 0.0;
     const double my_budget = ENGINE && lane < R ? a.eng_budget[lane] : 0.0;
     Rec* const rec = a.rec + (size_t)p * N;
-    bool dead = false;
-    for (int64_t r0 = 0; r0 < N && !dead; r0 += WAVE) {
-        const int nb = N - r0 < WAVE ? (int)(N - r0) : WAVE;
-        const int64_t rr = r0 + (lane < nb ? lane : nb - 1);
-        const double m_t = (double)a.ts[rr] * sc;          // time scale: gaps scale linearly
-        const int m_L = a.in_len[rr];
-        const int m_O = a.out_len[rr];
-        double o_ttft = 0.0, o_e2e = 0.0;
-        for (int i = 0; i < nb; ++i) {
-            const int64_t r = r0 + i;
-            const double t = readlane_f64(m_t, i);
-            const int L = __builtin_amdgcn_readlane(m_L, i);
-            const int O = __builtin_amdgcn_readlane(m_O, i);
-            if (PROXY) {
-                bool moved = false;
-                while (epoch + 1 < a.epochs && next_probe <= t) {       // (timestamps do not decrease)
-                    ++epoch;
-                    next_probe = (double)(epoch + 1) * (double)a.probe_ms;
-                    moved = true;
-                }
-                if (moved) {
-                    const size_t at = (size_t)epoch * R + (lane < R ? lane : 0);
-                    my_rtt = a.rtt_true[at];
-                    st(&comm->rtt[lane], a.rtt_est[at]);
-                }
+
+    // ---- the trace, 64 requests per lane-held batch (lane = request), two batches deep so that a batch's loads
+    // have a whole batch of time to arrive
+    struct Batch {
+        double t;        // arrival time, scaled
+        int L, O;        // input tokens, output tokens
+    };
+    auto load_batch = [&](int64_t b0, Batch& b) {
+        const int64_t x = b0 + lane;
+        const int64_t xx = x < N ? x : N - 1;
+        b.t = (double)a.ts[xx] * sc;                 // time scale: gaps scale linearly
+        b.L = a.in_len[xx];
+        b.O = a.out_len[xx];
+    };
+    Batch cur, nxt;
+    int64_t b0 = 0;
+    load_batch(0, cur);
+    load_batch(WAVE, nxt);
+    meet(false);        // (the front end's first descriptors are there: the cache wavefront may start)
+
+    double o_ttft = 0.0, o_e2e = 0.0;
+    int o_route = 0, o_hit = 0, o_believed = 0;
+    SectionClock<TIMED> clk;
+    clk.start();
+    for (int64_t r = 0; r < N; ++r) {
+        const int i = (int)(r - b0);
+        const double t = readlane_f64(cur.t, i);
+        const int L = __builtin_amdgcn_readlane(cur.L, i);
+        const int O = __builtin_amdgcn_readlane(cur.O, i);
+        if (PROXY) {
+            bool moved = false;
+            while (epoch + 1 < a.epochs && next_probe <= t) {       // (timestamps do not decrease)
+                ++epoch;
+                next_probe = (double)(epoch + 1) * (double)a.probe_ms;
+                moved = true;
             }
-            Q.retire(t, rec);
-            // (the least-request policy asks for requests in flight instead of their tokens)
-            st(&comm->q[lane], MODE == MODE_LEAST_REQUEST ? Q.my_cnt : Q.my_q);
-            lds_release();
-            if (lane == 0) st(&comm->seq_q, (unsigned)(r + 1));
-            // While the cache wavefront decides, the completions up to the next request's time are retired
-            // already: they do not depend on where this request goes (only this request's own completion is
-            // left for the retire above, next time round).  The service step still has to see the slots that
-            // were idle at this request's time, so their set is kept.
-            const unsigned long long idle_now = Q.idle;
-            if (r + 1 < N) {
-                const double t_next = i + 1 < nb ? readlane_f64(m_t, i + 1) : (double)a.ts[r + 1] * sc;
-                Q.retire(t_next, rec);
-            }
-            const unsigned want = (unsigned)(r + 1) & 0x3FFFFFFu;
-            unsigned hi, lo;
-            for (int spins = 0;; ++spins) {
-                const unsigned long long w = ld(&comm->choice);
-                hi = __builtin_amdgcn_readfirstlane((unsigned)(w >> 32));
-                lo = __builtin_amdgcn_readfirstlane((unsigned)w);
-                if ((hi >> 6) == want) break;
-                if (spins > a.spin_limit || ld(&comm->abandoned) != 0) {
-                    dead = true;
-                    break;
-                }
-                __builtin_amdgcn_s_sleep(1);
-            }
-            if (dead) break;
-            const int best = (int)(hi & 63u);
-            double ttft, e2e;
-            if (ENGINE)
-                Q.template serve_engine<PROXY>(r, best, t, my_rtt, (int64_t)(int)lo, L, O, my_a_pf, my_a_dec, my_budget, a.eng_slowdown,
-                               rec, lane, &ttft, &e2e);
-            else
-                Q.template serve<PROXY>(r, best, t, my_rtt, (int64_t)(int)lo, L, O, a.a_pf, a.a_dec, rec, lane, idle_now,
-                                        &ttft, &e2e);
-            o_ttft = lane == i ? ttft : o_ttft;
-            o_e2e = lane == i ? e2e : o_e2e;
-            if (ONLINE) {
-                if (lane == 0) ring[ring_pos] = ttft;
-                ring_pos = ring_pos + 1 == W ? 0 : ring_pos + 1;
-                if (--until_step == 0) {
-                    until_step = H;
-                    wave_sync();
-                    const double f = window_kth(ring, W, kth, lane);
-                    if (!have_parent) {
-                        f_par = f;                 // the first window measures the initial weights: the parent
-                        have_parent = true;
-                    } else {
-                        const bool success = f < f_par;
-                        if (success) {
-                            for (int k = 0; k < 3; ++k) ln_par[k] = ln_cur[k];
-                            f_par = f;
-                            ++accepted;
-                        }
-                        sigma = sigma * (success ? a.tuner[13] : a.tuner[14]);
-                    }
-                    double th[3];
-                    for (int k = 0; k < 3; ++k) {
-                        const double zk = a.z[((size_t)p * a.steps + step) * 3 + k];
-                        const double moved = ln_par[k] + sigma * zk;
-                        ln_cur[k] = clip(moved, a.tuner[6 + k], a.tuner[9 + k]);
-                        th[k] = clip(tuner_exp(ln_cur[k]), a.tuner[k], a.tuner[3 + k]);
-                    }
-                    if (lane == 0) {
-                        for (int k = 0; k < 3; ++k) st(&comm->w[k], th[k]);    // published with the next load signals
-                        if (a.fitness_step) a.fitness_step[(size_t)p * a.steps + step] = f;
-                        if (a.theta_step)
-                            for (int k = 0; k < 3; ++k) a.theta_step[((size_t)p * a.steps + step) * 3 + k] = th[k];
-                    }
-                    ++step;
-                    wave_sync();
-                }
+            if (moved) {
+                const size_t at = (size_t)epoch * R + (lane < R ? lane : 0);
+                my_rtt = a.rtt_true[at];
+                comm->rtt[lane] = a.rtt_est[at];
             }
         }
-        if (lane < nb && !dead) {
-            const size_t o = (size_t)p * N + r0 + lane;
-            if (a.ttft) a.ttft[o] = o_ttft;
-            if (a.e2e) a.e2e[o] = o_e2e;
+        Q.retire(t, rec);
+        // the queue term of Eq. 3, products rounded one by one (the least-request policy asks for the requests in
+        // flight instead; the dictated policies ignore it)
+        if (MODE == MODE_LEAST_REQUEST) comm->sq[lane] = Q.my_cnt;
+        else if (MODE == MODE_COST_MODEL || MODE == MODE_ONLINE) {
+            const double qd = a.a_pf * Q.my_q;
+            comm->sq[lane] = w_queue * qd;
+        }
+        clk.tick(0);                                                 // retire, publish
+        // While the cache wavefront is still busy with its own side of the previous request, the completions up
+        // to the next request's time are retired already: they do not depend on where this request goes (only
+        // this request's own completion is left for the retire above, next time round).  The service step still
+        // has to see the slots that were idle at this request's time, so their set is kept.
+        const unsigned long long idle_now = Q.idle;
+        if (r + 1 < N) Q.retire(i + 1 < WAVE ? readlane_f64(cur.t, i + 1) : readlane_f64(nxt.t, 0), rec);
+        clk.tick(2);                                                 // retire ahead
+        meet(true);                                                  // A(r)
+        clk.tick(1);                                                 // waiting at A
+        meet(false);                                                 // B(r)
+        clk.tick(4);                                                 // waiting at B
+        const unsigned long long w = comm->choice;
+        const unsigned hi = __builtin_amdgcn_readfirstlane((unsigned)(w >> 32));
+        const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)w);
+        const int best = (int)(hi & 63u);
+        double ttft, e2e;
+        if (ENGINE)
+            Q.template serve_engine<PROXY>(r, best, t, my_rtt, (int64_t)(int)lo, L, O, my_a_pf, my_a_dec, my_budget, a.eng_slowdown,
+                           rec, lane, &ttft, &e2e);
+        else
+            Q.template serve<PROXY>(r, best, t, my_rtt, (int64_t)(int)lo, L, O, a.a_pf, a.a_dec, rec, lane, idle_now,
+                                    &ttft, &e2e);
+        o_ttft = lane == i ? ttft : o_ttft;
+        o_e2e = lane == i ? e2e : o_e2e;
+        o_route = lane == i ? best : o_route;
+        o_hit = lane == i ? (int)(hi >> 8) : o_hit;
+        if (PROXY && a.believed) o_believed = lane == i ? __builtin_amdgcn_readfirstlane(comm->seen) : o_believed;
+        if (ONLINE) {
+            if (lane == 0) ring[ring_pos] = ttft;
+            ring_pos = ring_pos + 1 == W ? 0 : ring_pos + 1;
+            if (--until_step == 0) {
+                until_step = H;
+                wave_sync();
+                const double f = window_kth(ring, W, kth, lane);
+                if (!have_parent) {
+                    f_par = f;                 // the first window measures the initial weights: the parent
+                    have_parent = true;
+                } else {
+                    const bool success = f < f_par;
+                    if (success) {
+                        for (int k = 0; k < 3; ++k) ln_par[k] = ln_cur[k];
+                        f_par = f;
+                        ++accepted;
+                    }
+                    sigma = sigma * (success ? a.tuner[13] : a.tuner[14]);
+                }
+                double th[3];
+                for (int k = 0; k < 3; ++k) {
+                    const double zk = a.z[((size_t)p * a.steps + step) * 3 + k];
+                    const double moved = ln_par[k] + sigma * zk;
+                    ln_cur[k] = clip(moved, a.tuner[6 + k], a.tuner[9 + k]);
+                    th[k] = clip(tuner_exp(ln_cur[k]), a.tuner[k], a.tuner[3 + k]);
+                }
+                w_queue = th[2];                                     // in use from the next request on
+                if (lane == 0) {
+                    comm->w[0] = th[0];
+                    comm->w[1] = th[1];
+                    if (a.fitness_step) a.fitness_step[(size_t)p * a.steps + step] = f;
+                    if (a.theta_step)
+                        for (int k = 0; k < 3; ++k) a.theta_step[((size_t)p * a.steps + step) * 3 + k] = th[k];
+                }
+                ++step;
+                wave_sync();
+            }
+        }
+        clk.tick(5);                                                 // serve, outputs, tuner
+        if (i == WAVE - 1 || r == N - 1) {
+            // the batch is done: its outputs go out, the next batch moves up and the one after it is requested
+            if (lane <= i) {
+                const size_t o = (size_t)p * N + b0 + lane;
+                if (a.ttft) a.ttft[o] = o_ttft;
+                if (a.e2e) a.e2e[o] = o_e2e;
+                if (a.route) a.route[o] = (uint8_t)o_route;
+                if (a.hit) a.hit[o] = (uint16_t)o_hit;
+                if (PROXY && a.believed) a.believed[o] = (uint16_t)o_believed;
+            }
+            cur = nxt;
+            b0 += WAVE;
+            load_batch(b0 + WAVE, nxt);
+            clk.tick(6);                                             // batch turnover
         }
     }
-    if (ONLINE && lane == 0 && !dead) {
-        if (a.theta_final)
-            for (int k = 0; k < 3; ++k)
-                a.theta_final[3 * (size_t)p + k] = clip(tuner_exp(ln_par[k]), a.tuner[k], a.tuner[3 + k]);
-        if (a.sigma_final) a.sigma_final[p] = sigma;
-        if (a.accepted) a.accepted[p] = accepted;
-    }
-    if (dead) {
-        // the partner never answered (cannot happen unless the kernel is wrong): leave, and make sure nobody
-        // mistakes this replay's latencies for results
-        st(&comm->abandoned, 1);
-        for (int64_t x = lane; x < N; x += WAVE) {
-            if (a.ttft) a.ttft[(size_t)p * N + x] = NAN;
-            if (a.e2e) a.e2e[(size_t)p * N + x] = NAN;
-        }
-    }
+    clk.write(a.sections ? a.sections + ((size_t)p * 2 + 1) * SECTIONS : nullptr, lane);
+    tuner_results();
 }
 
+// ---------------------------------------------------------------------------------------------- cache side
 // Eviction cursor of one LRU over a replica's log of routed requests, held by lane = replica.
 //   cursor: blocks last touched by a request before cur_r, or by cur_r at positions >= cur_k, are evicted;
 //   cur_own is where cur_r's owned suffix starts.
@@ -429,39 +634,41 @@ struct EvictCursor {
     int pend_r = -1, pend_own = -1, pend_next = -1;
     unsigned long long pend_raw = 0;
     int live = 0;             // blocks this LRU holds
+    int n_spot = 0, n_adv = 0, n_dead = 0;       // statistics (only the timed instantiation reads them): records fetched
+                                                 // on the spot, cursor advances, records dropped because they own nothing
 
-    // the fetched record becomes usable: dropped if it owns nothing, else queued behind nx / n2
+    // The record requested by the previous issue_fill becomes usable: dropped if it owns nothing, else queued behind
+    // nx / n2.  Straight-line code: lanes with nothing pending go through it unchanged.
     __device__ __forceinline__ void take_pending(unsigned long long raw) {
-        if (pend_r >= 0) {
-            const int n = (int)(raw >> 48);
-            const int own_mem = (int)((raw >> 32) & 0xFFFF);
-            const int own = pend_own > own_mem ? pend_own : own_mem;
-            const int next = pend_next >= 0 ? pend_next : (int)(unsigned int)raw;
-            if (own < n) {
-                if (nx_r < 0) {
-                    nx_r = pend_r;
-                    nx_n = n;
-                    nx_own = own;
-                } else {
-                    n2_r = pend_r;
-                    n2_n = n;
-                    n2_own = own;
-                }
-            }
-            fill_r = next;
-            pend_r = -1;
-        }
+        const bool have = pend_r >= 0;
+        const int n = (int)(raw >> 48);
+        const int own_mem = (int)((raw >> 32) & 0xFFFF);
+        const int own = pend_own > own_mem ? pend_own : own_mem;
+        const int next = pend_next >= 0 ? pend_next : (int)(unsigned int)raw;
+        const bool alive = have && own < n;
+        const bool to_nx = alive && nx_r < 0;
+        const bool to_n2 = alive && !(nx_r < 0);
+        n_dead += have && !alive ? 1 : 0;
+        nx_r = to_nx ? pend_r : nx_r;
+        nx_n = to_nx ? n : nx_n;
+        nx_own = to_nx ? own : nx_own;
+        n2_r = to_n2 ? pend_r : n2_r;
+        n2_n = to_n2 ? n : n2_n;
+        n2_own = to_n2 ? own : n2_own;
+        fill_r = have ? next : fill_r;
+        pend_r = -1;
     }
-    // fetch the next record of the log if there is room for it
-    __device__ __forceinline__ void issue_fill(const unsigned long long* log64) {
-        if (pend_r < 0 && fill_r >= 0 && n2_r < 0) {
-            pend_r = fill_r;
-            pend_own = -1;
-            pend_next = -1;
-            pend_raw = ld(&log64[fill_r]);
-        }
+    // Request the next record of the log where there is room for it.  Every lane loads (those with nothing to
+    // fetch read the spare record behind the log, `spare`, and ignore it), so that the load is a plain instruction
+    // of the request loop and not a branch around one.  Called right after take_pending: nothing is pending.
+    __device__ __forceinline__ void issue_fill(const unsigned long long* log64, int spare) {
+        const bool want = fill_r >= 0 && n2_r < 0;
+        pend_r = want ? fill_r : -1;
+        pend_own = -1;
+        pend_next = -1;
+        pend_raw = ld(&log64[want ? fill_r : spare]);
     }
-    // request `owner`'s owned suffix now starts at `end`
+    // request `owner`'s owned suffix now starts at `end` (owner = -2: nobody's)
     __device__ __forceinline__ void disowned(int owner, int end) {
         cur_own = owner == cur_r ? end : cur_own;
         nx_own = owner == nx_r ? end : nx_own;
@@ -480,26 +687,27 @@ struct EvictCursor {
         pend_next = to_pend ? r : pend_next;
         fill_r = to_fill ? r : fill_r;
     }
+    // takes up to E blocks from the owned suffix of the cursor's record
+    __device__ __forceinline__ void take_from_cursor(int& E) {
+        int avail = cur_k - cur_own;
+        avail = avail > 0 ? avail : 0;
+        const int take = avail < E ? avail : E;
+        cur_k -= take;
+        E -= take;
+    }
     // `added` blocks have joined the LRU of the lane with `active` set; the cursor moves forward until the LRU
-    // fits `cap` blocks again.  Up to two steps come from the records held in registers; more (rare) are
-    // fetched on the spot.
+    // fits `cap` blocks again.  The cursor's own record and one step to the next record held in registers are
+    // straight-line code; more steps (rarer) loop, and fetch on the spot when the registers run out.
     __device__ __forceinline__ void evict(bool active, int added, int cap, const unsigned long long* log64) {
         live += active ? added : 0;
         int E = active ? live - cap : 0;
         E = E > 0 ? E : 0;
         live -= E;
-        if (__ballot(E > 0) != 0) {
-            {
-                int avail = cur_k - cur_own;
-                avail = avail > 0 ? avail : 0;
-                const int take = avail < E ? avail : E;
-                cur_k -= take;
-                E -= take;
-            }
+        take_from_cursor(E);
+        if (ballot(E > 0) != 0) {
             while (E > 0) {       // only the chosen replica's lane can be here
                 if (nx_r < 0) {
-                    // fetch a record on the spot; pend_raw itself is only ever written by the look-ahead
-                    // fetch, so that its load is never waited for in here
+                    // fetch a record on the spot (the one being fetched, if any, is waited for instead)
                     unsigned long long raw = pend_raw;
                     if (pend_r < 0) {
                         if (fill_r < 0) break;      // cannot happen while E > 0; bounds the loop
@@ -507,10 +715,12 @@ struct EvictCursor {
                         pend_own = -1;
                         pend_next = -1;
                         raw = ld(&log64[fill_r]);
+                        ++n_spot;
                     }
                     take_pending(raw);
                     continue;
                 }
+                ++n_adv;
                 cur_r = nx_r;
                 cur_k = nx_n;
                 cur_own = nx_own;
@@ -518,249 +728,181 @@ struct EvictCursor {
                 nx_n = n2_n;
                 nx_own = n2_own;
                 n2_r = -1;
-                int avail = cur_k - cur_own;
-                avail = avail > 0 ? avail : 0;
-                const int take = avail < E ? avail : E;
-                cur_k -= take;
-                E -= take;
+                take_from_cursor(E);
             }
             live += E;            // nothing left to evict (unreachable, kept consistent)
         }
     }
 };
 
-template <int MODE, bool ENGINE, bool PROXY>
-__global__ void __launch_bounds__(SEG_THREADS) replay_segments_kernel(SegArgs a) {
+// Row cells of one request's first eight segments as seen by this lane (= replica), with the request's scalars
+// (the same in every lane) and the row of segment (lane mod 8), whose cell that lane stores.
+struct RowsOf {
+    int32_t cell[8];
+    int32_t end[8];
+    int L, n, s, flags;
+    uint32_t my_off;
+};
+
+// Cache wavefront of a replay.  Per request: meet (A); match the rows requested one request earlier, request the
+// next request's rows, score, take the minimum, announce the choice; meet (B); update ownership, rows, log and
+// eviction cursor on the chosen replica.
+template <int MODE, bool ENGINE, bool PROXY, bool TIMED>
+__device__ __forceinline__ void cache_wave(const SegArgs& a, int p, int lane, Handover* comm) {
     constexpr bool ONLINE = MODE == MODE_ONLINE;
-    extern __shared__ __align__(16) unsigned char lds_raw[];
-    __shared__ SegRef stage[SEG_STAGE + SEG_CHUNK];    // padded: whole chunks are read unconditionally
-    __shared__ SegComm comm;
-    const int lane = threadIdx.x & (WAVE - 1);
-    const int p = blockIdx.x;
+    constexpr bool SCORED = MODE == MODE_COST_MODEL || MODE == MODE_ONLINE;
+    constexpr bool DICTATED = MODE == MODE_AFFINITY || MODE == MODE_RANDOM;
     const int R = a.R;
     const int64_t N = a.N;
-    const int C = (int)a.C;
-
-    if (threadIdx.x == 0) {
-        comm.seq_q = 0;
-        comm.abandoned = 0;
-        comm.choice = 0;
-        for (int k = 0; k < 3; ++k) comm.w[k] = a.params[3 * (size_t)p + k];
-    }
-    __syncthreads();
-    if (threadIdx.x >= WAVE) {
-        queue_wave<MODE, ENGINE, PROXY>(a, p, lane, lds_raw, &comm);
-        return;
-    }
-    __builtin_amdgcn_s_setprio(3);      // the cache wavefront has the longer loop: it goes first at issue
-    bool dead = false;
-
-    for (int x = lane; x < SEG_CHUNK; x += WAVE) stage[SEG_STAGE + x] = SegRef{0, 0};
-    wave_sync();
-
-    const uint64_t seed = MODE == MODE_RANDOM ? a.seeds[p] : 0;
-    const uint32_t seed_lo = (uint32_t)seed, seed_hi = (uint32_t)(seed >> 32);
-    // (with the online tuner the weights come with the load signals instead)
+    const bool bounded = a.C > 0;
+    const int cap = (int)a.C;
+    const bool in = lane < R;
+    // (with the online tuner the weights come with the queue terms instead)
     const double w_rtt = a.params[3 * (size_t)p + 0];
     const double w_prefill = a.params[3 * (size_t)p + 1];
-    const double w_queue = a.params[3 * (size_t)p + 2];
-    const double my_rtt = !PROXY && lane < R ? a.rtt[lane] : 0.0;     // (proxy variants: comes with the load signals)
+    const double my_rtt = !PROXY && in ? a.rtt[lane] : 0.0;     // (proxy variants: comes with the queue terms)
+    const double rtt_term = w_rtt * my_rtt;                      // first product of Eq. 3, the same for every request
     // Proxy variants (Sec. 7: the proxy does not see replica-side eviction): the proxy keeps an index of its own
     // of what it dispatched to each replica, an LRU like the replica's cache but at least as large (or unbounded).
     // It sees the same touches, so it is the same rows read against a second eviction cursor (c2), which lags
-    // the replica's; the match loop yields both prefixes, Eq. 3 scores with the index's.  Ownership is kept for
+    // the replica's; the match yields both prefixes, Eq. 3 scores with the index's.  Ownership is kept for
     // what the index holds, a superset of what is cached, which the replica's eviction walk does not mind:
     // records behind its cursor are never looked at again.  While the index never forgets (or is not used) its
     // cursor stays at the replica's first record and "in the index" means "ever dispatched here".
     const bool own_index = PROXY && a.index_blocks >= 0;
     const int index_cap = PROXY && a.index_blocks > 0 ? (int)a.index_blocks : 0;
-    EvictCursor c2;                           // the index's cursor, as cur_* etc. below
+    EvictCursor c1, c2;                       // the cache's cursor, the index's cursor
+    int tail_r = -1;                          // youngest request routed to this replica
 
-    // Per-replica eviction state, held by lane = replica.
-    //   cursor: blocks last touched by a request before cur_r, or by cur_r at positions >= cur_k, are
-    //   evicted; cur_own is where cur_r's owned suffix starts.
-    //   nx_*, n2_*: the next two records of the replica's log that still own blocks (r < 0: empty).
-    //   fill_r: the record after the last one held here, or -1 when that one is the youngest of the log.
-    //   pend_*: a record being fetched (its load is only waited for one iteration later); changes made to
-    //   it meanwhile are kept in pend_own / pend_next and override the loaded fields.
-    int cur_r = -1, cur_k = 0, cur_own = 0;
-    int nx_r = -1, nx_n = 0, nx_own = 0;
-    int n2_r = -1, n2_n = 0, n2_own = 0;
-    int fill_r = -1;
-    int pend_r = -1, pend_own = -1, pend_next = -1;
-    unsigned long long pend_raw = 0;
-    int tail_r = -1;          // youngest request routed to this replica
-    int my_live = 0;          // blocks cached on this replica
-
-    int32_t* const last = a.last + (size_t)p * a.nseg * R;
-    // this lane's cell of a segment's row; rows of one replay span less than 4 GiB (checked by the host)
-    const unsigned lane_off = (unsigned)(lane < R ? lane : 0) * 4u;
+    char* const rows = reinterpret_cast<char*>(a.last + (size_t)p * a.nseg * R);
+    // this lane's cell of a row; the rows of one replay span less than 4 GiB (checked by the host)
+    const unsigned lane_off = (unsigned)(in ? lane : 0) * 4u;
     const unsigned row_bytes = (unsigned)R * 4u;
-    auto cell_at = [&](int seg_id) -> int32_t* {
-        return reinterpret_cast<int32_t*>(reinterpret_cast<char*>(last) + ((unsigned)seg_id * row_bytes + lane_off));
+    auto cell_at = [&](uint32_t rowoff) -> int32_t* { return reinterpret_cast<int32_t*>(rows + (rowoff + lane_off)); };
+    auto cell_of = [&](uint32_t rowoff, int replica) -> int32_t* {
+        return reinterpret_cast<int32_t*>(rows + (rowoff + (unsigned)replica * 4u));
     };
-    LogRec* const log = a.log + (size_t)p * N;
+    // Stores and loads that only some lanes have use for are issued by every lane all the same, the others aimed
+    // at a spare location (a row and a log record that nothing reads): a plain instruction of the request loop is
+    // cheaper than a branch around it, and the number of memory operations in flight stays the same on every path.
+    const unsigned spare_row = (unsigned)(a.nseg - 1) * row_bytes;
+    const int spare = (int)N;                                   // the log record behind the last request's
+    LogRec* const log = a.log + (size_t)p * (N + 1);
     unsigned long long* const log64 = reinterpret_cast<unsigned long long*>(log);
+    unsigned long long* const choice_slot = lane == 0 ? &comm->choice : &comm->unused[lane];
 
-    // the fetched record becomes usable: dropped if it owns nothing, else queued behind nx / n2
-    auto take_pending = [&](unsigned long long raw) {
-        if (pend_r >= 0) {
-            const int n = (int)(raw >> 48);
-            const int own_mem = (int)((raw >> 32) & 0xFFFF);
-            const int own = pend_own > own_mem ? pend_own : own_mem;
-            const int next = pend_next >= 0 ? pend_next : (int)(unsigned int)raw;
-            if (own < n) {
-                if (nx_r < 0) {
-                    nx_r = pend_r;
-                    nx_n = n;
-                    nx_own = own;
-                } else {
-                    n2_r = pend_r;
-                    n2_n = n;
-                    n2_own = own;
-                }
-            }
-            fill_r = next;
-            pend_r = -1;
+    // the row loads of one request, from its descriptor
+    auto request_rows = [&](const SegDesc* d, RowsOf& w) {
+        const int4 h = *reinterpret_cast<const int4*>(&d->L);
+        const int4 e01 = reinterpret_cast<const int4*>(d->e)[0], e23 = reinterpret_cast<const int4*>(d->e)[1];
+        w.my_off = d->e[lane & 7].rowoff;
+        w.L = h.x;
+        w.n = h.y;
+        w.s = h.z;
+        w.flags = h.w;
+        w.cell[0] = ld(cell_at((uint32_t)e01.x));
+        w.cell[1] = ld(cell_at((uint32_t)e01.z));
+        w.cell[2] = ld(cell_at((uint32_t)e23.x));
+        w.cell[3] = ld(cell_at((uint32_t)e23.z));
+        w.end[0] = e01.y;
+        w.end[1] = e01.w;
+        w.end[2] = e23.y;
+        w.end[3] = e23.w;
+        if (h.w & DESC_MORE4) {
+            const int4 e45 = reinterpret_cast<const int4*>(d->e)[2], e67 = reinterpret_cast<const int4*>(d->e)[3];
+            w.cell[4] = ld(cell_at((uint32_t)e45.x));
+            w.cell[5] = ld(cell_at((uint32_t)e45.z));
+            w.cell[6] = ld(cell_at((uint32_t)e67.x));
+            w.cell[7] = ld(cell_at((uint32_t)e67.z));
+            w.end[4] = e45.y;
+            w.end[5] = e45.w;
+            w.end[6] = e67.y;
+            w.end[7] = e67.w;
         }
     };
-    // fetch the next record of the log if there is room for it
-    auto issue_fill = [&]() {
-        if (pend_r < 0 && fill_r >= 0 && n2_r < 0) {
-            pend_r = fill_r;
-            pend_own = -1;
-            pend_next = -1;
-            pend_raw = ld(&log64[fill_r]);
-        }
-    };
 
-    int64_t r0 = 0;
-    while (r0 < N && !dead) {
-        // ---- stage a batch of up to 64 requests: per-request scalars in registers (lane = request), their
-        // segment references in LDS.  The batch is cut where the references stop fitting; a single request
-        // with more references than the stage holds is processed alone, reading them from global memory.
-        const int nb0 = N - r0 < WAVE ? (int)(N - r0) : WAVE;
-        const int64_t rr = r0 + (lane < nb0 ? lane : nb0 - 1);
-        const int m_L = a.in_len[rr];
-        const uint32_t m_hash = MODE == MODE_AFFINITY ? a.first_hash[rr] : 0u;
-        const int64_t my_j0 = a.seg_off[rr], my_j1 = a.seg_off[rr + 1];
-        const int64_t J0 = a.seg_off[r0];
-        const int fit = __popcll(__ballot(lane < nb0 && my_j1 - J0 <= SEG_STAGE));   // a prefix of the lanes
-        const bool staged = fit > 0;
-        const int nb = staged ? fit : 1;
-        const int m_a0 = (int)(my_j0 - J0);
-        const int m_s = (int)(my_j1 - my_j0);
-        const SegRef* const gref = a.seg + J0;
-        int m_n = 0, m_root = -1;       // blocks of the request; its first segment (the root of its tree)
-        if (staged) {
-            const int cnt = __builtin_amdgcn_readlane(m_a0 + m_s, nb - 1);
-            for (int x = lane; x < cnt; x += WAVE) stage[x] = gref[x];
-            wave_sync();
-            if (m_s > 0 && lane < nb) {
-                m_n = stage[m_a0 + m_s - 1].end;
-                m_root = stage[m_a0].id;
-            }
-        } else if (m_s > 0 && lane == 0) {
-            m_n = gref[m_s - 1].end;
-            m_root = gref[0].id;
-        }
+    // Request r: `mine` holds its rows, `other` receives those of request r + 1.
+    SectionClock<TIMED> clk;
+    int n_walks = 0;          // statistics: ownership walks
+    auto step = [&](int64_t r, RowsOf& mine, RowsOf& other) {
+        const SegDesc* const dr = &comm->ring[r & (DESC_RING - 1)];
+        const int target = DICTATED ? dr->target : 0;
+        const int L = mine.L, n = mine.n, s = mine.s;
 
-        int o_route = 0, o_hit = 0, o_believed = 0;
-
-        // requests the rows of the first SEG_CHUNK segments of request i of the batch.  The references are
-        // read four at a time (one LDS round trip), most requests having no more than four segments.
-        auto request_rows = [&](int i, auto ref, RowSet& w) {
-            const int a0 = __builtin_amdgcn_readlane(m_a0, i);
-            const int s = __builtin_amdgcn_readlane(m_s, i);
-            const int n = __builtin_amdgcn_readlane(m_n, i);
-            w.of_lane = ref(a0 + (lane < SEG_CHUNK ? lane : 0), lane < s && lane < SEG_CHUNK);
-#pragma unroll
-            for (int k = 0; k < SEG_CHUNK; ++k) w.end[k] = n;       // (cells past the last segment are never read)
-#pragma unroll
-            for (int h = 0; h < SEG_CHUNK; h += 4) {
-                if (h >= s) break;
-                SegRef sr[4];
-#pragma unroll
-                for (int k = 0; k < 4; ++k) sr[k] = ref(a0 + h + k, h + k < s);
-#pragma unroll
-                for (int k = 0; k < 4; ++k) {
-                    if (h + k >= s) break;
-                    w.end[h + k] = sr[k].end;
-                    w.cell[h + k] = ld(cell_at(sr[k].id));           // lanes beyond R read a neighbouring cell, unused
-                }
+        // ---- prefix match: lane = replica.  A request that touches a segment touches all its ancestors,
+        // so along the path the cells never increase: first the segments touched after the cursor's
+        // request (cached), then those it touched last itself (cached below the cursor position), then
+        // older ones (evicted).  The match is max(e_gt, min(cur_k, e_ge)) with e_gt, e_ge the ends of the
+        // last segment whose cell is above, respectively not below, the cursor's request.  (Entries past the
+        // request's last segment hold the never-cached cell: they change nothing.)
+        int e_gt = 0, e_ge = 0;
+        int32_t own_gt = -1;        // previous owner of the last segment counted in e_gt
+        int e_gt2 = 0, e_ge2 = 0;   // proxy variants: the same against the index's cursor
+        int32_t own_gt2 = -1;
+        auto compare = [&](int k) {
+            const bool gt = mine.cell[k] > c1.cur_r;
+            const bool ge = mine.cell[k] >= c1.cur_r;
+            e_gt = gt ? mine.end[k] : e_gt;
+            own_gt = gt ? mine.cell[k] : own_gt;
+            e_ge = ge ? mine.end[k] : e_ge;
+            if (PROXY) {
+                const bool gt2 = mine.cell[k] > c2.cur_r;
+                const bool ge2 = mine.cell[k] >= c2.cur_r;
+                e_gt2 = gt2 ? mine.end[k] : e_gt2;
+                own_gt2 = gt2 ? mine.cell[k] : own_gt2;
+                e_ge2 = ge2 ? mine.end[k] : e_ge2;
             }
         };
-
-        // Processes request i of the batch.  `mine` holds the rows of its first segments; `other` receives
-        // those of request i+1.
-        auto process = [&](int i, auto ref, RowSet& mine, RowSet& other) {
-            const int64_t r = r0 + i;
-            const int L = __builtin_amdgcn_readlane(m_L, i);
-            const int a0 = __builtin_amdgcn_readlane(m_a0, i);
-            const int s = __builtin_amdgcn_readlane(m_s, i);
-            const int n = __builtin_amdgcn_readlane(m_n, i);
-
-            // ---- prefix match: lane = replica.  A request that touches a segment touches all its ancestors,
-            // so along the path the cells never increase: first the segments touched after the cursor's
-            // request (cached), then those it touched last itself (cached below the cursor position), then
-            // older ones (evicted).  The match is max(e_gt, min(cur_k, e_ge)) with e_gt, e_ge the ends of the
-            // last segment whose cell is above, respectively not below, the cursor's request.
-            int e_gt = 0, e_ge = 0;
-            int32_t own_gt = -1;        // previous owner of the last segment counted in e_gt
-            int e_gt2 = 0, e_ge2 = 0;   // proxy variants: the same against the index's cursor
-            int32_t own_gt2 = -1;
-#pragma unroll
-            for (int k = 0; k < SEG_CHUNK; ++k) {
-                if (k >= s) break;
-                const bool gt = mine.cell[k] > cur_r;
-                const bool ge = mine.cell[k] >= cur_r;
-                e_gt = gt ? mine.end[k] : e_gt;
-                own_gt = gt ? mine.cell[k] : own_gt;
-                e_ge = ge ? mine.end[k] : e_ge;
-                if (PROXY) {
-                    const bool gt2 = mine.cell[k] > c2.cur_r;
-                    const bool ge2 = mine.cell[k] >= c2.cur_r;
-                    e_gt2 = gt2 ? mine.end[k] : e_gt2;
-                    own_gt2 = gt2 ? mine.cell[k] : own_gt2;
-                    e_ge2 = ge2 ? mine.end[k] : e_ge2;
-                }
-            }
-            const int below_cursor = cur_k < e_ge ? cur_k : e_ge;
-            const bool some_eq = below_cursor > e_gt;       // blocks of the cursor's own request are matched
-            int my_m = some_eq ? below_cursor : e_gt;
-            const int below_cursor2 = c2.cur_k < e_ge2 ? c2.cur_k : e_ge2;
-            const bool some_eq2 = below_cursor2 > e_gt2;
-            int my_seen = PROXY ? (some_eq2 ? below_cursor2 : e_gt2) : 0;       // blocks in the proxy's index (>= my_m)
-            // For the ownership update below: where the cached prefix ends on this replica (rounded up to the
-            // end of a segment that the cursor's request owns: what lies beyond the cursor is evicted anyway)
-            // and whether all cached segments had the same previous owner.  (Proxy variants: the same for the
-            // prefix in the index.)
-            const int k_end = PROXY ? (some_eq2 ? e_ge2 : e_gt2) : (some_eq ? e_ge : e_gt);
-            const bool one_owner = PROXY ? (some_eq2 ? e_gt2 == 0 : own_gt2 == mine.cell[0])
-                                         : (some_eq ? e_gt == 0 : own_gt == mine.cell[0]);
-            int pos = mine.end[SEG_CHUNK - 1];
+        compare(0);
+        compare(1);
+        compare(2);
+        compare(3);
+        if (mine.flags & DESC_MORE4) {
+            compare(4);
+            compare(5);
+            compare(6);
+            compare(7);
+        }
+        const int below_cursor = c1.cur_k < e_ge ? c1.cur_k : e_ge;
+        const bool some_eq = below_cursor > e_gt;       // blocks of the cursor's own request are matched
+        int my_m = some_eq ? below_cursor : e_gt;
+        const int below_cursor2 = c2.cur_k < e_ge2 ? c2.cur_k : e_ge2;
+        const bool some_eq2 = below_cursor2 > e_gt2;
+        int my_seen = PROXY ? (some_eq2 ? below_cursor2 : e_gt2) : 0;       // blocks in the proxy's index (>= my_m)
+        // For the ownership update below: where the cached prefix ends on this replica (rounded up to the
+        // end of a segment that the cursor's request owns: what lies beyond the cursor is evicted anyway)
+        // and whether all cached segments had the same previous owner.  (Proxy variants: the same for the
+        // prefix in the index.)
+        const int k_end = PROXY ? (some_eq2 ? e_ge2 : e_gt2) : (some_eq ? e_ge : e_gt);
+        const bool one_owner = PROXY ? (some_eq2 ? e_gt2 == 0 : own_gt2 == mine.cell[0])
+                                     : (some_eq ? e_gt == 0 : own_gt == mine.cell[0]);
+        bool deep = false;          // the match went past the preloaded segments
+        if (mine.flags & DESC_DEEP) {
+            // more than eight segments (rare): the rest of the path is read from the trace, eight references at a
+            // time, as long as some replica's prefix is still open
+            const int64_t j0 = dr->j0;
+            int pos = mine.end[7];
             bool open = my_m == pos;
             bool open_seen = PROXY && my_seen == pos;
-            bool deep = false;          // the match went past the preloaded segments
-            if (s > SEG_CHUNK && __ballot((PROXY ? open_seen : open) && lane < R) != 0) {      // (pos and open only matter in here)
+            if (ballot((PROXY ? open_seen : open) && in) != 0) {
                 deep = true;
-                for (int c0 = SEG_CHUNK; c0 < s; c0 += SEG_CHUNK) {
-                    int32_t cell[SEG_CHUNK];
-                    int send[SEG_CHUNK];
+                for (int c0 = 8; c0 < s; c0 += 8) {
+                    int32_t cell[8];
+                    int send[8];
 #pragma unroll
-                    for (int k = 0; k < SEG_CHUNK; ++k) {
+                    for (int k = 0; k < 8; ++k) {
                         cell[k] = -1;
                         send[k] = pos;
                         if (c0 + k < s) {
-                            const SegRef sr = ref(a0 + c0 + k, true);
+                            const SegRef sr = a.seg[j0 + c0 + k];
                             send[k] = sr.end;
-                            if ((PROXY ? open_seen : open) && lane < R) cell[k] = ld(cell_at(sr.id));
+                            if ((PROXY ? open_seen : open) && in) cell[k] = ld(cell_at((uint32_t)sr.id * row_bytes));
                         }
                     }
 #pragma unroll
-                    for (int k = 0; k < SEG_CHUNK; ++k) {
+                    for (int k = 0; k < 8; ++k) {
                         if (c0 + k < s) {
-                            const int cnt = cached_in(cell[k], pos, send[k], cur_r, cur_k);
+                            const int cnt = cached_in(cell[k], pos, send[k], c1.cur_r, c1.cur_k);
                             my_m += open ? cnt : 0;
                             open = open && cnt == send[k] - pos;
                             if (PROXY) {
@@ -771,234 +913,177 @@ __global__ void __launch_bounds__(SEG_THREADS) replay_segments_kernel(SegArgs a)
                             pos = send[k];
                         }
                     }
-                    if (__ballot((PROXY ? open_seen : open) && lane < R) == 0) break;
+                    if (ballot((PROXY ? open_seen : open) && in) == 0) break;
                 }
             }
+        }
 
-            // ---- the single point of the iteration that waited for memory is behind us: the record fetched
-            // during the previous iteration becomes usable, and the loads for the next iteration go out
-            take_pending(pend_raw);
-            if (PROXY && index_cap > 0) c2.take_pending(c2.pend_raw);
-            if (i + 1 < nb) request_rows(i + 1, ref, other);
-            issue_fill();
-            if (PROXY && index_cap > 0) c2.issue_fill(log64);
+        clk.tick(1);                                                 // match (and the wait for the rows)
+        // ---- the rows of this request have arrived, so has the log record requested during the previous
+        // request; the loads for the next request go out
+        c1.take_pending(c1.pend_raw);
+        if (PROXY && index_cap > 0) c2.take_pending(c2.pend_raw);
+        request_rows(&comm->ring[(r + 1) & (DESC_RING - 1)], other);
+        c1.issue_fill(log64, spare);
+        if (PROXY && index_cap > 0) c2.issue_fill(log64, spare);
 
-            // ---- score (Eq. 3) and lowest-index minimum
-            int hit_tok = a.block_tokens * my_m;           // block_tokens * blocks fits: both are below 2^16
-            hit_tok = hit_tok > L ? L : hit_tok;
-            int my_u = L - hit_tok;
-            int my_u_seen = my_u;       // uncached tokens as Eq. 3 sees them
-            if (PROXY) {
-                int seen_tok = a.block_tokens * (own_index ? my_seen : my_m);
-                seen_tok = seen_tok > L ? L : seen_tok;
-                my_u_seen = L - seen_tok;
-            }
-            // the load signals of this request come from the queue wavefront (normally already there);
-            // everything that does not need them is finished first, so that little is left between reading
-            // them and announcing the choice
-            const double score_rp = ONLINE || PROXY ? 0.0 : eq3_without_queue(w_rtt, w_prefill, my_rtt, a.a_pf, my_u);
-            asm volatile("" : "+v"(my_u), "+v"(my_m));
-            double score_rp_ready = score_rp;
-            asm volatile("" : "+v"(score_rp_ready));
-            double my_q;
-            double now_rtt = 0.0, now_prefill = 0.0, now_queue = 0.0;
-            double rtt_est = my_rtt;
-            for (int spins = 0;; ++spins) {
-                const unsigned seq = __builtin_amdgcn_readfirstlane(ld(&comm.seq_q));
-                lds_acquire();
-                my_q = ld(&comm.q[lane]);
-                if (PROXY) rtt_est = ld(&comm.rtt[lane]);
-                if (ONLINE) {
-                    now_rtt = ld(&comm.w[0]);
-                    now_prefill = ld(&comm.w[1]);
-                    now_queue = ld(&comm.w[2]);
-                }
-                if (seq == (unsigned)(r + 1)) break;
-                if (spins > a.spin_limit || ld(&comm.abandoned) != 0) {
-                    dead = true;
-                    break;
-                }
-            }
-            if (dead) {
-                st(&comm.abandoned, 1);
-                return;
-            }
-            double my_score;
-            if (MODE == MODE_COST_MODEL) {
-                my_score = PROXY ? eq3_score(w_rtt, w_prefill, w_queue, rtt_est, a.a_pf, my_u_seen, my_q)
-                                 : eq3_with_queue(score_rp_ready, w_queue, a.a_pf, my_q);
-            } else if (MODE == MODE_ONLINE) {
-                my_score = eq3_score(now_rtt, now_prefill, now_queue, rtt_est, a.a_pf, my_u_seen, my_q);
-            } else if (MODE == MODE_LEAST_REQUEST) {
-                my_score = my_q;                    // requests in flight
-            } else {
-                // the replica is dictated: by the hash of the first block, or by a counter-based draw
-                const int target = MODE == MODE_AFFINITY ? (s > 0 ? spread((uint32_t)__builtin_amdgcn_readlane((int)m_hash, i), R) : 0)
-                                                         : spread(philox4x32_10_first((uint32_t)r, (uint32_t)((uint64_t)r >> 32),
-                                                                                      seed_lo, seed_hi), R);
-                my_score = lane == target ? 0.0 : 1.0;
-            }
-            const int best = wave_argmin(my_score, lane, R);
-            const bool is_best = lane == best;
-            const int m_best = __builtin_amdgcn_readlane(my_m, best);
-            const int seen_best = PROXY ? __builtin_amdgcn_readlane(my_seen, best) : m_best;
-            if (lane == 0) {
-                const unsigned u_best = (unsigned)__builtin_amdgcn_readlane(my_u, best);
-                const unsigned tag = (((unsigned)(r + 1) & 0x3FFFFFFu) << 6) | (unsigned)best;
-                st(&comm.choice, ((unsigned long long)tag << 32) | u_best);
-            }
+        // ---- score (Eq. 3: rtt and prefill terms here, the queue term from the queue wavefront) and lowest-index
+        // minimum.  block_tokens * blocks fits: below 2^15 and 2^16.
+        int hit_tok = __mul24(a.block_tokens, my_m);
+        hit_tok = hit_tok > L ? L : hit_tok;
+        const int my_u = L - hit_tok;
+        int my_u_seen = my_u;       // uncached tokens as Eq. 3 sees them
+        if (PROXY) {
+            int seen_tok = __mul24(a.block_tokens, own_index ? my_seen : my_m);
+            seen_tok = seen_tok > L ? L : seen_tok;
+            my_u_seen = L - seen_tok;
+        }
+        clk.tick(2);                                                 // log records, next rows, uncached tokens
+        meet(false);                                                 // A(r): the queue terms of r are there
+        clk.tick(0);                                                 // waiting at A
+        const double sq = SCORED || MODE == MODE_LEAST_REQUEST ? comm->sq[lane] : 0.0;
+        double rtt_now = my_rtt, now_rtt = w_rtt, now_prefill = w_prefill;
+        if (PROXY) rtt_now = comm->rtt[lane];
+        if (ONLINE) {
+            now_rtt = comm->w[0];
+            now_prefill = comm->w[1];
+        }
+        double my_score;
+        if (SCORED) {
+            const double pf = a.a_pf * (double)my_u_seen;
+            const double s_rtt = ONLINE || PROXY ? now_rtt * rtt_now : rtt_term;
+            const double s_pf = now_prefill * pf;
+            const double rtt_and_prefill = s_rtt + s_pf;
+            my_score = rtt_and_prefill + sq;
+        } else if (MODE == MODE_LEAST_REQUEST) {
+            my_score = sq;                      // requests in flight
+        } else {
+            my_score = lane == target ? 0.0 : 1.0;      // the replica is dictated
+        }
+        const int best = argmin_lanes(my_score, in);
+        const bool is_best = lane == best;
+        const int m_best = __builtin_amdgcn_readlane(my_m, best);
+        const int seen_best = PROXY ? __builtin_amdgcn_readlane(my_seen, best) : m_best;
+        const unsigned u_best = (unsigned)__builtin_amdgcn_readlane(my_u, best);
+        // (every lane writes: lane 0 the word that is read, the others a word of their own that is not)
+        *choice_slot = ((unsigned long long)((unsigned)best | ((unsigned)m_best << 8)) << 32) | u_best;
+        if (PROXY && lane == 0) comm->seen = own_index ? seen_best : m_best;
+        clk.tick(3);                                                 // score, minimum, announcement
+        meet(true);                                                  // B(r): the choice is there
+        clk.tick(4);                                                 // waiting at B
 
-            // ---- ownership: the segments this request takes over on the chosen replica stop belonging to
-            // their previous requests.  Along the path the previous owners form runs; each run moves its
-            // owner's `own` to the end of the run.  Only cached segments matter (evicted ones belong to
-            // requests the cursor has passed, or to the cursor request beyond its position).
+        // ---- ownership: the segments this request takes over on the chosen replica stop belonging to
+        // their previous requests.  Along the path the previous owners form runs; each run moves its
+        // owner's `own` to the end of the run.  Only cached segments matter (evicted ones belong to
+        // requests the cursor has passed, or to the cursor request beyond its position).  One previous owner
+        // (the usual case) is straight-line code: the chosen replica's lane names it, the others name nobody.
+        const bool cached_some = seen_best > 0;
+        const bool simple = cached_some && !deep && ((ballot(one_owner) >> best) & 1ull) != 0;
+        const int dis_owner = is_best && simple ? mine.cell[0] : -2;
+        if (cached_some && !simple) {
+            // several previous owners, or a prefix longer than the preloaded rows: walk it
+            ++n_walks;
             auto disown = [&](int owner, int end) {       // lane `best`: owner's owned suffix now starts at end
                 st(&log[owner].own, (uint16_t)end);
-                cur_own = owner == cur_r ? end : cur_own;
-                nx_own = owner == nx_r ? end : nx_own;
-                n2_own = owner == n2_r ? end : n2_own;
-                pend_own = owner == pend_r ? end : pend_own;
+                c1.disowned(owner, end);
                 if (PROXY) c2.disowned(owner, end);
             };
-            if (seen_best > 0) {
-                const bool simple = !deep && __builtin_amdgcn_readlane((int)one_owner, best) != 0;
-                if (simple) {
-                    if (is_best) disown(mine.cell[0], k_end);
-                } else {
-                    // several previous owners, or a prefix longer than the preloaded rows: walk it
-                    const int cb_r = __builtin_amdgcn_readlane(PROXY ? c2.cur_r : cur_r, best);
-                    const int cb_k = __builtin_amdgcn_readlane(PROXY ? c2.cur_k : cur_k, best);
-                    int run_owner = -1, run_end = 0, vpos = 0;
-                    for (int j = 0; j < s; ++j) {
-                        const SegRef sr = ref(a0 + j, true);
-                        const int32_t rl = ld(&last[(size_t)sr.id * R + best]);
-                        const int cnt = cached_in(rl, vpos, sr.end, cb_r, cb_k);
-                        if (cnt > 0) {
-                            if (rl != run_owner) {
-                                if (run_owner >= 0 && is_best) disown(run_owner, run_end);
-                                run_owner = rl;
-                            }
-                            run_end = sr.end;
-                        }
-                        if (cnt != sr.end - vpos) break;
-                        vpos = sr.end;
+            const int64_t j0 = dr->j0;
+            const int cb_r = __builtin_amdgcn_readlane(PROXY ? c2.cur_r : c1.cur_r, best);
+            const int cb_k = __builtin_amdgcn_readlane(PROXY ? c2.cur_k : c1.cur_k, best);
+            int run_owner = -1, run_end = 0, vpos = 0;
+            for (int j = 0; j < s; ++j) {
+                const SegRef sr = a.seg[j0 + j];
+                const int32_t rl = ld(cell_of((uint32_t)sr.id * row_bytes, best));
+                const int cnt = cached_in(rl, vpos, sr.end, cb_r, cb_k);
+                if (cnt > 0) {
+                    if (rl != run_owner) {
+                        if (run_owner >= 0 && is_best) disown(run_owner, run_end);
+                        run_owner = rl;
                     }
-                    if (run_owner >= 0 && is_best) disown(run_owner, run_end);
+                    run_end = sr.end;
                 }
+                if (cnt != sr.end - vpos) break;
+                vpos = sr.end;
             }
+            if (run_owner >= 0 && is_best) disown(run_owner, run_end);
+        }
+        c1.disowned(dis_owner, k_end);
+        if (PROXY) c2.disowned(dis_owner, k_end);
+        st(&log[dis_owner >= 0 ? dis_owner : spare].own, (uint16_t)k_end);
 
-            // ---- cache update: every segment of the request is now last touched by r on the chosen replica
-            // (lane k stores the cell of segment k)
-            if (lane < s && lane < SEG_CHUNK) st(&last[(size_t)mine.of_lane.id * R + best], (int32_t)r);
-            for (int j = SEG_CHUNK + lane; j < s; j += WAVE)
-                st(&last[(size_t)ref(a0 + j, true).id * R + best], (int32_t)r);
+        clk.tick(5);                                                 // ownership
+        // ---- cache update: every segment of the request is now last touched by r on the chosen replica
+        // (lane k, and k + 8, ..., store the cell of segment k)
+        st(cell_of((lane & 7) < s ? mine.my_off : spare_row, best), (int32_t)r);
+        if (mine.flags & DESC_DEEP) {
+            const int64_t j0 = dr->j0;
+            for (int j = 8 + lane; j < s; j += WAVE) st(cell_of((uint32_t)a.seg[j0 + j].id * row_bytes, best), (int32_t)r);
+        }
 
-            // ---- log and eviction, in the chosen replica's lane
-            if (is_best) {
-                st(&log64[r], 0xFFFFFFFFull | ((unsigned long long)n << 48));      // next -1, own 0, n
-                if (tail_r >= 0) st(&log[tail_r].next, (int32_t)r);
-            }
-            {
-                // r is now the youngest record of the chosen replica's log
-                const bool first = is_best && tail_r < 0;
-                const bool to_pend = is_best && pend_r >= 0 && pend_r == tail_r;
-                const bool to_fill = is_best && !first && !to_pend && pend_r < 0 && fill_r < 0;
-                cur_r = first ? (int)r : cur_r;
-                cur_k = first ? n : cur_k;
-                cur_own = first ? 0 : cur_own;
-                if (PROXY) c2.appended(is_best, (int)r, n, tail_r);
-                pend_next = to_pend ? (int)r : pend_next;
-                fill_r = to_fill ? (int)r : fill_r;
-                tail_r = is_best ? (int)r : tail_r;
+        // ---- log (every lane writes the same record; the chosen replica's lane links it) and eviction
+        st(&log64[r], 0xFFFFFFFFull | ((unsigned long long)n << 48));      // next -1, own 0, n
+        st(&log[is_best && tail_r >= 0 ? tail_r : spare].next, (int32_t)r);
+        c1.appended(is_best, (int)r, n, tail_r);
+        if (PROXY) c2.appended(is_best, (int)r, n, tail_r);
+        tail_r = is_best ? (int)r : tail_r;
+        c1.evict(is_best && bounded, n - m_best, cap, log64);
+        // the proxy's index evicts under its own capacity: its cursor walks the same log (whose memory is up to
+        // date: ownership changes and links are stored as they happen)
+        if (PROXY && index_cap > 0) c2.evict(is_best, n - seen_best, index_cap, log64);
 
-                // eviction: move the cursor forward until the cache fits.  Up to two steps come from the
-                // records held in registers; more (rare) are fetched on the spot.
-                my_live += (is_best && C > 0) ? n - m_best : 0;
-                int E = (is_best && C > 0) ? my_live - C : 0;
-                E = E > 0 ? E : 0;
-                my_live -= E;
-                if (__ballot(E > 0) != 0) {
-                    {
-                        int avail = cur_k - cur_own;
-                        avail = avail > 0 ? avail : 0;
-                        const int take = avail < E ? avail : E;
-                        cur_k -= take;
-                        E -= take;
-                    }
-                    while (E > 0) {       // only the chosen replica's lane can be here
-                        if (nx_r < 0) {
-                            // fetch a record on the spot; pend_raw itself is only ever written by the
-                            // look-ahead fetch, so that its load is never waited for in here
-                            unsigned long long raw = pend_raw;
-                            if (pend_r < 0) {
-                                if (fill_r < 0) break;      // cannot happen while E > 0; bounds the loop
-                                pend_r = fill_r;
-                                pend_own = -1;
-                                pend_next = -1;
-                                raw = ld(&log64[fill_r]);
-                            }
-                            take_pending(raw);
-                            continue;
-                        }
-                        cur_r = nx_r;
-                        cur_k = nx_n;
-                        cur_own = nx_own;
-                        nx_r = n2_r;
-                        nx_n = n2_n;
-                        nx_own = n2_own;
-                        n2_r = -1;
-                        int avail = cur_k - cur_own;
-                        avail = avail > 0 ? avail : 0;
-                        const int take = avail < E ? avail : E;
-                        cur_k -= take;
-                        E -= take;
-                    }
-                    my_live += E;         // nothing left to evict (unreachable, kept consistent)
-                }
-                // the proxy's index evicts under its own capacity: its cursor walks the same log (whose memory
-                // is up to date: ownership changes and links are stored as they happen)
-                if (PROXY && index_cap > 0) c2.evict(is_best, n - seen_best, index_cap, log64);
-            }
-
-            // ---- the rows of request i+1 were requested before this request's stores: if it continues the
-            // same tree, the cells this request just wrote are patched into them (common prefix of the paths)
-            if (i + 1 < nb && s > 0 && __builtin_amdgcn_readlane(m_root, i + 1) == __builtin_amdgcn_readlane(m_root, i)) {
-                const int s_next = __builtin_amdgcn_readlane(m_s, i + 1);
-                const bool same = lane < s && lane < s_next && other.of_lane.id == mine.of_lane.id &&
-                                  other.of_lane.end == mine.of_lane.end;
-                const unsigned differ = ~(unsigned)__ballot(same && lane < SEG_CHUNK) | (1u << SEG_CHUNK);
-                const int common = __ffs(differ) - 1;              // leading segments the two paths share
+        clk.tick(6);                                                 // stores, log, eviction
+        // ---- the rows of request r + 1 were requested before this request's stores: the leading segments the two
+        // paths share (none unless r + 1 continues the same tree) get the cells this request just wrote
+        const int common = other.flags >> 8;
+        if (common > 0) {
 #pragma unroll
-                for (int k = 0; k < SEG_CHUNK; ++k) other.cell[k] = (k < common && is_best) ? (int32_t)r : other.cell[k];
+            for (int k = 0; k < 4; ++k) other.cell[k] = (k < common && is_best) ? (int32_t)r : other.cell[k];
+            if (other.flags & DESC_MORE4) {
+#pragma unroll
+                for (int k = 4; k < 8; ++k) other.cell[k] = (k < common && is_best) ? (int32_t)r : other.cell[k];
             }
-
-            // ---- outputs of the cache side (kept in registers until the batch ends)
-            if (a.route) o_route = lane == i ? best : o_route;
-            if (a.hit) o_hit = lane == i ? m_best : o_hit;
-            if (PROXY && a.believed) o_believed = lane == i ? (own_index ? seen_best : m_best) : o_believed;
-        };
-
-        RowSet A, Bset;
-        if (staged) {
-            const auto from_stage = [&](int x, bool) -> SegRef { return stage[x]; };
-            request_rows(0, from_stage, A);
-            for (int i = 0; i < nb && !dead; i += 2) {
-                process(i, from_stage, A, Bset);
-                if (i + 1 < nb && !dead) process(i + 1, from_stage, Bset, A);
-            }
-        } else {
-            const auto from_global = [&](int x, bool in) -> SegRef { return in ? gref[x] : SegRef{0, 0}; };
-            request_rows(0, from_global, A);
-            process(0, from_global, A, Bset);
         }
-        if (lane < nb && !dead) {
-            const size_t o = (size_t)p * N + r0 + lane;
-            if (a.route) a.route[o] = (uint8_t)o_route;
-            if (a.hit) a.hit[o] = (uint16_t)o_hit;
-            if (PROXY && a.believed) a.believed[o] = (uint16_t)o_believed;
-        }
-        wave_sync();
-        r0 += nb;
+        clk.tick(7);                                                 // patch, loop
+    };
+
+    RowsOf A, B;
+    meet(false);                              // the first descriptors are there
+    request_rows(&comm->ring[0], A);
+    clk.start();
+    for (int64_t r = 0; r < N; r += 2) {
+        step(r, A, B);
+        if (r + 1 < N) step(r + 1, B, A);
+    }
+    if (TIMED) {
+        // statistics of the eviction walk, summed over the replicas
+        clk.acc[8] = wave_sum_u32((unsigned)c1.n_spot);
+        clk.acc[9] = wave_sum_u32((unsigned)c1.n_adv);
+        clk.acc[10] = wave_sum_u32((unsigned)c1.n_dead);
+        clk.acc[11] = (unsigned)__builtin_amdgcn_readfirstlane(n_walks);
+    }
+    clk.write(a.sections ? a.sections + (size_t)p * 2 * SECTIONS : nullptr, lane);
+}
+
+template <int MODE, bool ENGINE, bool PROXY, bool TIMED = false>
+__global__ void __launch_bounds__(SEG3_THREADS) replay_segments_kernel(SegArgs a) {
+    extern __shared__ __align__(16) unsigned char lds_raw[];
+    __shared__ __align__(16) Handover comm;
+    const int lane = threadIdx.x & (WAVE - 1);
+    const int p = blockIdx.x;
+    if (threadIdx.x == 0) {
+        comm.w[0] = a.params[3 * (size_t)p + 0];
+        comm.w[1] = a.params[3 * (size_t)p + 1];
+    }
+    __syncthreads();
+    if (threadIdx.x >= 2 * WAVE) {
+        if (a.N > 0) front_wave<MODE>(a, p, lane, &comm);
+    } else if (threadIdx.x >= WAVE) {
+        __builtin_amdgcn_s_setprio(2);
+        queue_wave<MODE, ENGINE, PROXY, TIMED>(a, p, lane, lds_raw, &comm);
+    } else if (a.N > 0) {
+        __builtin_amdgcn_s_setprio(3);      // the two wavefronts on the chain go first at issue
+        cache_wave<MODE, ENGINE, PROXY, TIMED>(a, p, lane, &comm);
     }
 }
 
