@@ -432,6 +432,228 @@ struct Queues {
     }
 };
 
+__device__ __forceinline__ unsigned long long ballot(bool c) { return __builtin_amdgcn_ballot_w64(c); }
+
+// Queue side of one replay with one lane per service slot instead of one per replica, for shapes whose slots fit
+// four passes of the wavefront (replicas x slots rounded up to a power of two <= 256): slot b of replica i is slot
+// g = i * Bp + b, handled by lane g mod 64 in pass g / 64, so the slots of a replica are Bp neighbouring lanes of one
+// pass.  Every slot keeps its list of in-flight requests as Queues does, but nothing has to be searched: "which
+// slots' oldest request has completed by t" is one comparison per pass for all slots at once, and an idle slot of
+// the chosen replica is one ballot.  The oldest request of every slot and the number in flight are in registers
+// (one set per pass), so that the usual request -- nothing or one request retired, an idle slot taken -- needs no
+// LDS round trip; the second oldest, the free times and the list ends are in LDS at index g (every lane only ever
+// addresses its own slots: no conflicts), deeper requests are Rec records in global memory.  The load signal and
+// the request count stay per replica (lane = replica), as the cache side reads them.  Same arithmetic as Queues,
+// operation for operation.
+struct SlotHead {
+    double done;         // completion time of the slot's oldest in-flight request (+inf: none)
+    int tok;             // its tokens
+    int depth;           // requests in flight on the slot
+    int rep;             // replica of the slot (-1 where there is no slot)
+};
+
+struct SlotQueues {
+    static constexpr int PASSES = 4;
+    static constexpr int SLOTS = PASSES * WAVE;
+    SlotHead H0, H1, H2, H3;
+    double* s_done;      // [SLOTS] completion time of the second oldest
+    double* free_at;     // [SLOTS] time the slot becomes free (+inf where there is no slot)
+    int32_t* s_tok;      // [SLOTS] tokens of the second oldest
+    int32_t* s_next;     // [SLOTS] request after the second oldest (-1: none)
+    int32_t* tail;       // [SLOTS] youngest request of the slot
+    double* spare8;      // [WAVE] where the lanes that have nothing to store write
+    int32_t* spare4;     // [WAVE]
+    double my_q;         // outstanding tokens of replica = lane (an integer below 2^53, exact in fp64)
+    double my_cnt;       // requests in flight on replica = lane
+    int log2bp;
+
+    // whether a model's slots fit: Bp = B rounded up to a power of two, R * Bp <= SLOTS
+    static __host__ __device__ bool fits(int R, int B) {
+        int bp = 1;
+        while (bp < B) bp <<= 1;
+        return R * bp <= SLOTS;
+    }
+    static __host__ __device__ size_t bytes() { return (size_t)SLOTS * (2 * 8 + 3 * 4) + WAVE * (8 + 4); }
+
+    __device__ __forceinline__ void init_head(SlotHead& h, int pass, int R, int B, int lane) {
+        const int g = pass * WAVE + lane;
+        const int i = g >> log2bp, b = g & ((1 << log2bp) - 1);
+        h.rep = i < R && b < B ? i : -1;
+        h.done = INFINITY;
+        h.tok = 0;
+        h.depth = 0;
+        free_at[g] = h.rep >= 0 ? 0.0 : INFINITY;
+        s_done[g] = INFINITY;
+        s_tok[g] = 0;
+        s_next[g] = tail[g] = -1;
+    }
+    __device__ __forceinline__ void init(unsigned char* lds, int R, int B, int lane) {
+        s_done = reinterpret_cast<double*>(lds);
+        free_at = s_done + SLOTS;
+        s_tok = reinterpret_cast<int32_t*>(free_at + SLOTS);
+        s_next = s_tok + SLOTS;
+        tail = s_next + SLOTS;
+        spare8 = reinterpret_cast<double*>(tail + SLOTS);
+        spare4 = reinterpret_cast<int32_t*>(spare8 + WAVE);
+        log2bp = 0;
+        while ((1 << log2bp) < B) ++log2bp;
+        init_head(H0, 0, R, B, lane);
+        init_head(H1, 1, R, B, lane);
+        init_head(H2, 2, R, B, lane);
+        init_head(H3, 3, R, B, lane);
+        my_q = 0.0;
+        my_cnt = 0.0;
+    }
+
+    // The slots of one pass whose oldest request has completed by t drop it (and whatever else of theirs has
+    // completed by t).  A slot with a single request in flight -- the usual case -- only changes its registers.
+    __device__ __forceinline__ void pop(SlotHead& h, int g, bool due, double t, const Rec* rec, int lane) {
+        const unsigned long long mask = ballot(due);
+        if (mask == 0) return;
+        // load signal and request count of the replicas concerned: one scalar step per completed request
+        for (unsigned long long rest = mask; rest != 0; rest &= rest - 1) {
+            const int l = __builtin_ctzll(rest);
+            const int tok = __builtin_amdgcn_readlane(h.tok, l);
+            const int i = __builtin_amdgcn_readlane(h.rep, l);
+            my_q -= lane == i ? (double)tok : 0.0;
+            my_cnt -= lane == i ? 1.0 : 0.0;
+        }
+        const int d = h.depth;
+        double n_done = INFINITY;
+        int n_tok = 0, n_depth = 0;
+        if (ballot(due && d > 1) != 0) {
+            // slots with more in flight: the list moves up, as long as its head has completed as well
+            double dq = 0.0, dc = 0.0;          // what further leaves the load signal of this lane's slot
+            if (due && d > 1) {
+                n_done = s_done[g];
+                n_tok = s_tok[g];
+                n_depth = d - 1;
+                int x = n_depth >= 2 ? s_next[g] : -1;      // the request that moves into second position
+                for (;;) {
+                    const bool again = n_depth > 0 && n_done <= t;     // the new head has completed too
+                    if (again) {
+                        dq += (double)n_tok;
+                        dc += 1.0;
+                        --n_depth;
+                    }
+                    double x_done = INFINITY;
+                    int x_tok = 0, x_next = -1;
+                    if (x >= 0) {
+                        x_done = ld(&rec[x].done);
+                        x_tok = ld(&rec[x].tokens);
+                        x_next = ld(&rec[x].next);
+                    }
+                    if (!again) {
+                        // settled: x (if any) is the second oldest
+                        s_done[g] = x_done;
+                        s_tok[g] = x_tok;
+                        s_next[g] = x_next;
+                        break;
+                    }
+                    n_done = x_done;            // x moves up to the head (+inf when the list is empty)
+                    n_tok = x_tok;
+                    x = x_next;
+                }
+            }
+            // (further completions are rare: their tokens reach the replicas' lanes one slot at a time)
+            for (unsigned long long rest = ballot(dc != 0.0); rest != 0; rest &= rest - 1) {
+                const int l = __builtin_ctzll(rest);
+                const double q1 = readlane_f64(dq, l), c1 = readlane_f64(dc, l);
+                const int i = __builtin_amdgcn_readlane(h.rep, l);
+                my_q -= lane == i ? q1 : 0.0;
+                my_cnt -= lane == i ? c1 : 0.0;
+            }
+        }
+        h.done = due ? n_done : h.done;
+        h.tok = due ? n_tok : h.tok;
+        h.depth = due ? n_depth : d;
+    }
+
+    // Drop requests whose completion event has reached the proxy (done <= t).
+    __device__ __forceinline__ void retire(double t, const Rec* rec, int lane) {
+        const bool due0 = H0.done <= t, due1 = H1.done <= t, due2 = H2.done <= t, due3 = H3.done <= t;
+        if (ballot(due0 || due1 || due2 || due3) == 0) return;
+        pop(H0, lane, due0, t, rec, lane);
+        pop(H1, WAVE + lane, due1, t, rec, lane);
+        pop(H2, 2 * WAVE + lane, due2, t, rec, lane);
+        pop(H3, 3 * WAVE + lane, due3, t, rec, lane);
+    }
+
+    // Service of request r on replica `best` (the stated linear model; reproduces Eq. 1: ttft = rtt + wait +
+    // prefill).  A slot of the replica with nothing in flight has been free since before any later arrival at the
+    // replica (its completion event has already reached the proxy), and which of several such slots takes the
+    // request changes no latency and no load signal; only when every slot has a request in flight are they
+    // searched for the earliest free time (lowest index on ties).  rtt_best: the chosen replica's round trip time.
+    // The latencies come back the same in every lane.
+    __device__ __forceinline__ void serve_in(SlotHead& h, int g, int64_t r, int best, double t, double rtt_best, int uncached,
+                                            int L, int O, double a_pf, double a_dec, Rec* rec, int lane, double* ttft_out,
+                                            double* e2e_out) {
+        const bool mine = h.rep == best;
+        const int d = h.depth;
+        const double half = 0.5 * rtt_best;
+        const double arrive = t + half;
+        double start = arrive;
+        int k;
+        const unsigned long long idle = ballot(mine && d == 0);
+        if (idle != 0) {
+            k = __builtin_ctzll(idle);
+        } else {
+            // every slot is busy: the earliest free one (times are >= 0: the order of the bits is the order of the values)
+            const double f = mine ? free_at[g] : INFINITY;
+            const unsigned long long bits = (unsigned long long)__double_as_longlong(f);
+            const unsigned hi = (unsigned)(bits >> 32), lo = (unsigned)bits;
+            const unsigned mhi = wave_min_u32(hi);
+            const bool tie = hi == mhi;
+            const unsigned mlo = wave_min_u32(tie ? lo : 0xffffffffu);
+            k = __builtin_ctzll(ballot(tie && lo == mlo));
+            const double fv = readlane_f64(f, k);
+            start = arrive > fv ? arrive : fv;
+        }
+        const double pf = a_pf * (double)uncached;
+        const double first_tok = start + pf;
+        const double dec = a_dec * (double)O;
+        const double end = first_tok + dec;
+        const double done = end + half;
+        *ttft_out = (first_tok + half) - t;
+        *e2e_out = done - t;
+        const bool on = lane == k;
+        if (ballot(on && d > 0) != 0) {
+            // the slot still has requests in flight: the new one queues behind them
+            if (on) {
+                if (d == 1) {
+                    s_done[g] = done;
+                    s_tok[g] = L;
+                    s_next[g] = -1;
+                } else {
+                    // third or deeper: goes to global memory, linked behind the youngest
+                    st(&rec[r].done, done);
+                    st(&rec[r].next, (int32_t)-1);
+                    st(&rec[r].tokens, (int32_t)L);
+                    if (d == 2) s_next[g] = (int32_t)r;
+                    else st(&rec[tail[g]].next, (int32_t)r);
+                }
+            }
+        }
+        // (every lane stores: the chosen slot's lane into the slot, the others into a spare word of their own)
+        *(on ? &free_at[g] : &spare8[lane]) = end;
+        *(on ? &tail[g] : &spare4[lane]) = (int32_t)r;
+        h.done = on && d == 0 ? done : h.done;
+        h.tok = on && d == 0 ? L : h.tok;
+        h.depth = on ? d + 1 : d;
+        my_q += lane == best ? (double)L : 0.0;
+        my_cnt += lane == best ? 1.0 : 0.0;
+    }
+    __device__ __forceinline__ void serve(int64_t r, int best, double t, double rtt_best, int uncached, int L, int O,
+                                          double a_pf, double a_dec, Rec* rec, int lane, double* ttft_out, double* e2e_out) {
+        switch ((best << log2bp) >> 6) {       // the pass that holds the replica's slots
+            case 0: serve_in(H0, lane, r, best, t, rtt_best, uncached, L, O, a_pf, a_dec, rec, lane, ttft_out, e2e_out); break;
+            case 1: serve_in(H1, WAVE + lane, r, best, t, rtt_best, uncached, L, O, a_pf, a_dec, rec, lane, ttft_out, e2e_out); break;
+            case 2: serve_in(H2, 2 * WAVE + lane, r, best, t, rtt_best, uncached, L, O, a_pf, a_dec, rec, lane, ttft_out, e2e_out); break;
+            default: serve_in(H3, 3 * WAVE + lane, r, best, t, rtt_best, uncached, L, O, a_pf, a_dec, rec, lane, ttft_out, e2e_out); break;
+        }
+    }
+};
+
 // Weighted score of Eq. 3 for one replica, in the fixed association (w_rtt*rtt + w_prefill*pf) + w_queue*qd
 // with every product and sum rounded on its own.  The first two terms do not depend on the load signal and
 // can be formed before it is known.

@@ -664,6 +664,7 @@ int launch_replay(const gorgo_trace* t, const Plan& pl, const double* d_rtt, con
                 if (proxy && engine) hipLaunchKernelGGL((replay_segments_kernel<MODE_ONLINE, true, true>), grid, block, lds, s, a);
                 else if (proxy) hipLaunchKernelGGL((replay_segments_kernel<MODE_ONLINE, false, true>), grid, block, lds, s, a);
                 else if (engine) hipLaunchKernelGGL((replay_segments_kernel<MODE_ONLINE, true, false>), grid, block, lds, s, a);
+                else if (SlotQueues::fits(pl.R, pl.B)) hipLaunchKernelGGL((replay_segments_kernel<MODE_ONLINE, false, false, true>), grid, block, lds, s, a);
                 else hipLaunchKernelGGL((replay_segments_kernel<MODE_ONLINE, false, false>), grid, block, lds, s, a);
             } else if (proxy) {
                 const size_t lds = replay_segments_lds_bytes(pl.R, pl.B, 0);
@@ -680,8 +681,12 @@ int launch_replay(const gorgo_trace* t, const Plan& pl, const double* d_rtt, con
                     default: hipLaunchKernelGGL((replay_segments_kernel<MODE_RANDOM, true, false>), grid, block, lds, s, a); break;
                 }
             } else if (sections) {
-                hipLaunchKernelGGL((replay_segments_kernel<MODE_COST_MODEL, false, false, true>), dim3((unsigned)pl.P),
-                                   dim3(SEG3_THREADS), replay_segments_lds_bytes(pl.R, pl.B, 0), s, a);
+                const dim3 grid((unsigned)pl.P), block(SEG3_THREADS);
+                const size_t lds = replay_segments_lds_bytes(pl.R, pl.B, 0);
+                if (SlotQueues::fits(pl.R, pl.B))
+                    hipLaunchKernelGGL((replay_segments_kernel<MODE_COST_MODEL, false, false, true, true>), grid, block, lds, s, a);
+                else
+                    hipLaunchKernelGGL((replay_segments_kernel<MODE_COST_MODEL, false, false, false, true>), grid, block, lds, s, a);
             } else if (!(policy && policy->policy != 0) && pack_replays(pl, a.nseg)) {
                 // fixed weights, at most 32 replicas: two replays per wavefront pair
                 hipLaunchKernelGGL(replay_segments_packed_kernel, dim3((unsigned)(pl.P / 2)), dim3(SEG_THREADS),
@@ -689,11 +694,20 @@ int launch_replay(const gorgo_trace* t, const Plan& pl, const double* d_rtt, con
             } else {
                 const size_t lds = replay_segments_lds_bytes(pl.R, pl.B, 0);
                 const dim3 grid((unsigned)pl.P), block(SEG3_THREADS);
-                switch (policy ? policy->policy : 0) {
-                    case 0: hipLaunchKernelGGL((replay_segments_kernel<MODE_COST_MODEL, false, false>), grid, block, lds, s, a); break;
-                    case 1: hipLaunchKernelGGL((replay_segments_kernel<MODE_LEAST_REQUEST, false, false>), grid, block, lds, s, a); break;
-                    case 2: hipLaunchKernelGGL((replay_segments_kernel<MODE_AFFINITY, false, false>), grid, block, lds, s, a); break;
-                    default: hipLaunchKernelGGL((replay_segments_kernel<MODE_RANDOM, false, false>), grid, block, lds, s, a); break;
+                if (SlotQueues::fits(pl.R, pl.B)) {
+                    switch (policy ? policy->policy : 0) {
+                        case 0: hipLaunchKernelGGL((replay_segments_kernel<MODE_COST_MODEL, false, false, true>), grid, block, lds, s, a); break;
+                        case 1: hipLaunchKernelGGL((replay_segments_kernel<MODE_LEAST_REQUEST, false, false, true>), grid, block, lds, s, a); break;
+                        case 2: hipLaunchKernelGGL((replay_segments_kernel<MODE_AFFINITY, false, false, true>), grid, block, lds, s, a); break;
+                        default: hipLaunchKernelGGL((replay_segments_kernel<MODE_RANDOM, false, false, true>), grid, block, lds, s, a); break;
+                    }
+                } else {
+                    switch (policy ? policy->policy : 0) {
+                        case 0: hipLaunchKernelGGL((replay_segments_kernel<MODE_COST_MODEL, false, false>), grid, block, lds, s, a); break;
+                        case 1: hipLaunchKernelGGL((replay_segments_kernel<MODE_LEAST_REQUEST, false, false>), grid, block, lds, s, a); break;
+                        case 2: hipLaunchKernelGGL((replay_segments_kernel<MODE_AFFINITY, false, false>), grid, block, lds, s, a); break;
+                        default: hipLaunchKernelGGL((replay_segments_kernel<MODE_RANDOM, false, false>), grid, block, lds, s, a); break;
+                    }
                 }
             }
             if ((e = hipGetLastError()) != hipSuccess) return hip_fail(e, "launch replay_segments_kernel");

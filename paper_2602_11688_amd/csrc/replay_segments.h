@@ -32,6 +32,8 @@
 // B(r): the choice of r is published.  Every wavefront executes exactly two barriers per request, whatever
 // the data, so neither can wait for ever.
 #pragma once
+#include <type_traits>
+
 #include "device_common.h"
 #include "internal.h"
 
@@ -143,7 +145,9 @@ __device__ __forceinline__ void wave_sync() {
 }
 
 __host__ __device__ inline size_t replay_segments_lds_bytes(int R, int B, int window) {   // dynamic part
-    return Queues::bytes(R, B) + (size_t)((window + 7) & ~7) * sizeof(double);   // queues, then the tuner's TTFT window
+    // queues (in whichever layout is the larger: the launch picks one), then the tuner's TTFT window
+    const size_t q = Queues::bytes(R, B) > SlotQueues::bytes() ? Queues::bytes(R, B) : SlotQueues::bytes();
+    return q + (size_t)((window + 7) & ~7) * sizeof(double);
 }
 
 // exp(x) for |x| <= 700 from additions and multiplications only, in a fixed order, so that the weights the
@@ -299,7 +303,6 @@ struct SectionClock {
     }
 };
 
-__device__ __forceinline__ unsigned long long ballot(bool c) { return __builtin_amdgcn_ballot_w64(c); }
 
 // Lowest-index minimum as wave_argmin, with the lane mask given.
 __device__ __forceinline__ int argmin_lanes(double v, bool in) {
@@ -424,19 +427,26 @@ __device__ __forceinline__ void front_wave(const SegArgs& a, int p, int lane, Ha
 // Queue wavefront of a replay.  Per request: retire what has completed by its arrival, publish the queue
 // terms, meet (A); retire ahead to the next arrival and run the front end; meet (B); serve the request on
 // the chosen replica.  Keeps and writes the latencies and the per-request outputs.
-template <int MODE, bool ENGINE, bool PROXY, bool TIMED>
+template <int MODE, bool ENGINE, bool PROXY, bool SLOTS, bool TIMED>
 __device__ __forceinline__ void queue_wave(const SegArgs& a, int p, int lane, unsigned char* lds_raw, Handover* comm) {
     constexpr bool ONLINE = MODE == MODE_ONLINE;
+    static_assert(!SLOTS || (!ENGINE && !PROXY), "one lane per slot exists for the linear replica model with fixed round trip times");
     const int R = a.R;
     const int64_t N = a.N;
-    Queues Q;
-    Q.carve(lds_raw, R, a.B, lane);
-    Q.init(lane);
+    // the queue state: one lane per service slot where the model's shape allows it, else one lane per replica
+    // with the slots in LDS
+    typename std::conditional<SLOTS, SlotQueues, Queues>::type Q;
+    if constexpr (SLOTS) {
+        Q.init(lds_raw, R, a.B, lane);
+    } else {
+        Q.carve(lds_raw, R, a.B, lane);
+        Q.init(lane);
+    }
     // Online tuner (Sec. 2.3, Sec. 4), run here because this wavefront has the TTFTs: after every hop the p95
     // TTFT of the last `window` requests is the fitness of the weights in use; they replace the parent iff they
     // beat it; the step size follows the 1/5 rule; the next offspring is a log-space mutation of the parent.
     // The state is the same in every lane.
-    double* const ring = reinterpret_cast<double*>(lds_raw + Queues::bytes(R, a.B));
+    double* const ring = reinterpret_cast<double*>(lds_raw + (SLOTS ? SlotQueues::bytes() : Queues::bytes(R, a.B)));
     const int W = ONLINE ? a.window : 0, H = ONLINE ? a.hop : 0;
     const int kth = (95 * W + 99) / 100;
     int ring_pos = 0, until_step = W;
@@ -520,7 +530,8 @@ __device__ __forceinline__ void queue_wave(const SegArgs& a, int p, int lane, un
                 comm->rtt[lane] = a.rtt_est[at];
             }
         }
-        Q.retire(t, rec);
+        if constexpr (SLOTS) Q.retire(t, rec, lane);
+        else Q.retire(t, rec);
         // the queue term of Eq. 3, products rounded one by one (the least-request policy asks for the requests in
         // flight instead; the dictated policies ignore it)
         if (MODE == MODE_LEAST_REQUEST) comm->sq[lane] = Q.my_cnt;
@@ -532,9 +543,13 @@ __device__ __forceinline__ void queue_wave(const SegArgs& a, int p, int lane, un
         // While the cache wavefront is still busy with its own side of the previous request, the completions up
         // to the next request's time are retired already: they do not depend on where this request goes (only
         // this request's own completion is left for the retire above, next time round).  The service step still
-        // has to see the slots that were idle at this request's time, so their set is kept.
-        const unsigned long long idle_now = Q.idle;
-        if (r + 1 < N) Q.retire(i + 1 < WAVE ? readlane_f64(cur.t, i + 1) : readlane_f64(nxt.t, 0), rec);
+        // has to see the slots that were idle at this request's time, so their set is kept.  (With a lane per
+        // slot retiring costs next to nothing when nothing has completed, and is not done ahead.)
+        unsigned long long idle_now = 0;
+        if constexpr (!SLOTS) {
+            idle_now = Q.idle;
+            if (r + 1 < N) Q.retire(i + 1 < WAVE ? readlane_f64(cur.t, i + 1) : readlane_f64(nxt.t, 0), rec);
+        }
         clk.tick(2);                                                 // retire ahead
         meet(true);                                                  // A(r)
         clk.tick(1);                                                 // waiting at A
@@ -545,7 +560,9 @@ __device__ __forceinline__ void queue_wave(const SegArgs& a, int p, int lane, un
         const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)w);
         const int best = (int)(hi & 63u);
         double ttft, e2e;
-        if (ENGINE)
+        if constexpr (SLOTS)
+            Q.serve(r, best, t, readlane_f64(my_rtt, best), (int)lo, L, O, a.a_pf, a.a_dec, rec, lane, &ttft, &e2e);
+        else if constexpr (ENGINE)
             Q.template serve_engine<PROXY>(r, best, t, my_rtt, (int64_t)(int)lo, L, O, my_a_pf, my_a_dec, my_budget, a.eng_slowdown,
                            rec, lane, &ttft, &e2e);
         else
@@ -791,33 +808,44 @@ __device__ __forceinline__ void cache_wave(const SegArgs& a, int p, int lane, Ha
     unsigned long long* const log64 = reinterpret_cast<unsigned long long*>(log);
     unsigned long long* const choice_slot = lane == 0 ? &comm->choice : &comm->unused[lane];
 
-    // the row loads of one request, from its descriptor
-    auto request_rows = [&](const SegDesc* d, RowsOf& w) {
-        const int4 h = *reinterpret_cast<const int4*>(&d->L);
-        const int4 e01 = reinterpret_cast<const int4*>(d->e)[0], e23 = reinterpret_cast<const int4*>(d->e)[1];
-        w.my_off = d->e[lane & 7].rowoff;
-        w.L = h.x;
-        w.n = h.y;
-        w.s = h.z;
-        w.flags = h.w;
-        w.cell[0] = ld(cell_at((uint32_t)e01.x));
-        w.cell[1] = ld(cell_at((uint32_t)e01.z));
-        w.cell[2] = ld(cell_at((uint32_t)e23.x));
-        w.cell[3] = ld(cell_at((uint32_t)e23.z));
-        w.end[0] = e01.y;
-        w.end[1] = e01.w;
-        w.end[2] = e23.y;
-        w.end[3] = e23.w;
-        if (h.w & DESC_MORE4) {
-            const int4 e45 = reinterpret_cast<const int4*>(d->e)[2], e67 = reinterpret_cast<const int4*>(d->e)[3];
-            w.cell[4] = ld(cell_at((uint32_t)e45.x));
-            w.cell[5] = ld(cell_at((uint32_t)e45.z));
-            w.cell[6] = ld(cell_at((uint32_t)e67.x));
-            w.cell[7] = ld(cell_at((uint32_t)e67.z));
-            w.end[4] = e45.y;
-            w.end[5] = e45.w;
-            w.end[6] = e67.y;
-            w.end[7] = e67.w;
+    // the row loads of one request, from its descriptor: the descriptor is read (LDS) well before the loads go out
+    struct DescCopy {
+        int4 h, e01, e23, e45, e67;
+        uint32_t my_off;
+    };
+    auto read_desc = [&](const SegDesc* d) {
+        DescCopy c;
+        c.h = *reinterpret_cast<const int4*>(&d->L);
+        c.e01 = reinterpret_cast<const int4*>(d->e)[0];
+        c.e23 = reinterpret_cast<const int4*>(d->e)[1];
+        c.e45 = reinterpret_cast<const int4*>(d->e)[2];
+        c.e67 = reinterpret_cast<const int4*>(d->e)[3];
+        c.my_off = d->e[lane & 7].rowoff;
+        return c;
+    };
+    auto request_rows = [&](const DescCopy& c, RowsOf& w) {
+        w.my_off = c.my_off;
+        w.L = c.h.x;
+        w.n = c.h.y;
+        w.s = c.h.z;
+        w.flags = c.h.w;
+        w.cell[0] = ld(cell_at((uint32_t)c.e01.x));
+        w.cell[1] = ld(cell_at((uint32_t)c.e01.z));
+        w.cell[2] = ld(cell_at((uint32_t)c.e23.x));
+        w.cell[3] = ld(cell_at((uint32_t)c.e23.z));
+        w.end[0] = c.e01.y;
+        w.end[1] = c.e01.w;
+        w.end[2] = c.e23.y;
+        w.end[3] = c.e23.w;
+        if (c.h.w & DESC_MORE4) {
+            w.cell[4] = ld(cell_at((uint32_t)c.e45.x));
+            w.cell[5] = ld(cell_at((uint32_t)c.e45.z));
+            w.cell[6] = ld(cell_at((uint32_t)c.e67.x));
+            w.cell[7] = ld(cell_at((uint32_t)c.e67.z));
+            w.end[4] = c.e45.y;
+            w.end[5] = c.e45.w;
+            w.end[6] = c.e67.y;
+            w.end[7] = c.e67.w;
         }
     };
 
@@ -827,6 +855,7 @@ __device__ __forceinline__ void cache_wave(const SegArgs& a, int p, int lane, Ha
     auto step = [&](int64_t r, RowsOf& mine, RowsOf& other) {
         const SegDesc* const dr = &comm->ring[r & (DESC_RING - 1)];
         const int target = DICTATED ? dr->target : 0;
+        const DescCopy next = read_desc(&comm->ring[(r + 1) & (DESC_RING - 1)]);
         const int L = mine.L, n = mine.n, s = mine.s;
 
         // ---- prefix match: lane = replica.  A request that touches a segment touches all its ancestors,
@@ -923,7 +952,7 @@ __device__ __forceinline__ void cache_wave(const SegArgs& a, int p, int lane, Ha
         // request; the loads for the next request go out
         c1.take_pending(c1.pend_raw);
         if (PROXY && index_cap > 0) c2.take_pending(c2.pend_raw);
-        request_rows(&comm->ring[(r + 1) & (DESC_RING - 1)], other);
+        request_rows(next, other);
         c1.issue_fill(log64, spare);
         if (PROXY && index_cap > 0) c2.issue_fill(log64, spare);
 
@@ -1049,7 +1078,7 @@ __device__ __forceinline__ void cache_wave(const SegArgs& a, int p, int lane, Ha
 
     RowsOf A, B;
     meet(false);                              // the first descriptors are there
-    request_rows(&comm->ring[0], A);
+    request_rows(read_desc(&comm->ring[0]), A);
     clk.start();
     for (int64_t r = 0; r < N; r += 2) {
         step(r, A, B);
@@ -1065,7 +1094,7 @@ __device__ __forceinline__ void cache_wave(const SegArgs& a, int p, int lane, Ha
     clk.write(a.sections ? a.sections + (size_t)p * 2 * SECTIONS : nullptr, lane);
 }
 
-template <int MODE, bool ENGINE, bool PROXY, bool TIMED = false>
+template <int MODE, bool ENGINE, bool PROXY, bool SLOTS = false, bool TIMED = false>
 __global__ void __launch_bounds__(SEG3_THREADS) replay_segments_kernel(SegArgs a) {
     extern __shared__ __align__(16) unsigned char lds_raw[];
     __shared__ __align__(16) Handover comm;
@@ -1080,7 +1109,7 @@ __global__ void __launch_bounds__(SEG3_THREADS) replay_segments_kernel(SegArgs a
         if (a.N > 0) front_wave<MODE>(a, p, lane, &comm);
     } else if (threadIdx.x >= WAVE) {
         __builtin_amdgcn_s_setprio(2);
-        queue_wave<MODE, ENGINE, PROXY, TIMED>(a, p, lane, lds_raw, &comm);
+        queue_wave<MODE, ENGINE, PROXY, SLOTS, TIMED>(a, p, lane, lds_raw, &comm);
     } else if (a.N > 0) {
         __builtin_amdgcn_s_setprio(3);      // the two wavefronts on the chain go first at issue
         cache_wave<MODE, ENGINE, PROXY, TIMED>(a, p, lane, &comm);
