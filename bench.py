@@ -5,6 +5,8 @@ A "step" is one generation of the tuner on the Large workload (R=32 replicas, N=
 16,000-block LRU caches, P=1,024 candidate weight vectors): sample and propose the candidates, replay the
 whole trace under all of them (score, route, cache/queue update per request), reduce every replay to its
 p95 TTFT, update the parent weights and step size.  The trace is resident in HBM before the timed region.
+With --config 4 a step is the saturation sweep instead: one launch of 8 time scales x 128 candidates = 1,024
+replays of the 200,000-request trace, reduced to their p95s (there is no tuner step in that workload).
 
 Prints ONE JSON line: candidate-request routings per second (whole job), the replay kernel's HBM roofline
 (algorithmic bytes / HIP-event kernel time against 8 TB/s) and the CPU oracle timed on a bounded sample.
@@ -83,7 +85,19 @@ def recorded_counters(kernel, workload_key):
     return rec
 
 
-def cpu_baseline(wl, params, n_req, threads, online=None, engine=None, proxy=None):
+def cpu_single_thread(wl, params, n_req):
+    """The oracle on one thread: one replay of the first n_req requests (routings/s of one core that has the
+    machine to itself, which a run on every core at once does not show)."""
+    from oracle import binding as ob
+    tr = wl.trace.head(n_req)
+    t0 = time.perf_counter()
+    ob.replay(tr, R=wl.R, batch=wl.batch, cache_blocks=wl.cache_blocks, prefill_ms_per_token=wl.prefill_ms_per_token,
+              decode_ms_per_token=wl.decode_ms_per_token, rtt_ms=wl.rtt_ms, w=params[0], scale=1.0)
+    dt = time.perf_counter() - t0
+    return tr.N / dt, dt, tr.N
+
+
+def cpu_baseline(wl, params, n_req, threads, online=None, engine=None, proxy=None, scales=None):
     """The oracle as it stands, one replay per thread, on the first n_req requests of the workload (with its online
     tuner when `online` = (z[P, steps, 3], lo, hi, sigma0) is given; under the engine model of a replica when
     `engine` = its parameters is given)."""
@@ -131,7 +145,7 @@ def cpu_baseline(wl, params, n_req, threads, online=None, engine=None, proxy=Non
     def one(p):
         return ob.replay(tr, R=wl.R, batch=wl.batch, cache_blocks=wl.cache_blocks,
                          prefill_ms_per_token=wl.prefill_ms_per_token, decode_ms_per_token=wl.decode_ms_per_token,
-                         rtt_ms=wl.rtt_ms, w=params[p], scale=1.0).p95_ttft_ms
+                         rtt_ms=wl.rtt_ms, w=params[p], scale=1.0 if scales is None else float(scales[p])).p95_ttft_ms
     t0 = time.perf_counter()
     with ThreadPoolExecutor(threads) as ex:
         list(ex.map(one, range(threads)))
@@ -205,6 +219,9 @@ def main():
     args = ap.parse_args()
     if args.engine + args.online + args.proxy > 1:
         sys.exit("bench.py: --engine, --online and --proxy are separate runs")
+    sweep = args.config == 4          # the saturation sweep: a population evaluation over (scale, candidate) pairs, no tuner
+    if sweep and (args.engine or args.online or args.proxy):
+        sys.exit("bench.py: the saturation sweep (--config 4) is timed with the linear replica model and fixed weights")
     if args.gpus != 1:
         sys.exit("bench.py: this library evaluates on ONE GPU (replays are independent and would shard by candidate; "
                  "no multi-GPU path is built) -- run with --gpus 1")
@@ -224,7 +241,7 @@ def main():
     N = tr.N
     model = g.Model(wl.R, wl.batch, wl.cache_blocks, wl.prefill_ms_per_token, wl.decode_ms_per_token)
     state = g.es_init(es_cfg["seed"])
-    ws_bytes = g.workspace_bytes(tr, model, P) if args.online or args.engine or args.proxy else g.es_workspace_bytes(tr, model, P)
+    ws_bytes = g.workspace_bytes(tr, model, P) if args.online or args.engine or args.proxy or sweep else g.es_workspace_bytes(tr, model, P)
     ws = torch.empty((ws_bytes,), dtype=torch.uint8, device="cuda:0")
     print(f"[bench] workload {wl.name}: R={wl.R} N={N} P={P} C={wl.cache_blocks} mean blocks/request "
           f"{np.diff(wl.trace.blk_off).mean():.1f}; workspace {ws.numel() / 2**30:.1f} GiB; setup "
@@ -244,7 +261,14 @@ def main():
         epochs = int(float(wl.trace.ts_ms[-1]) // 30000) + 1 if N else 1
         proxy = g.Proxy(tg.rtt_walk(wl, epochs), 30000, 0.3, 2 * wl.cache_blocks)
 
+    sweep_par = np.ascontiguousarray(wl.params[:P]) if sweep else None
+    sweep_scale = np.ascontiguousarray(wl.scale[:P]) if sweep else None
+
     def generation():
+        if sweep:
+            res = g.eval_population(tr, model, wl.rtt_ms, sweep_par, sweep_scale, per_request=False, workspace=ws)
+            fit = res.p95_ttft_ms.cpu().numpy()
+            return sweep_par, fit, g.last_eval_kernel_ms()
         if args.proxy:
             par = g.es_propose(state, g.es_sample(state.seed, state.generation, P))
             res = g.eval_proxy(tr, model, proxy, par, 1.0, per_request=False, workspace=ws)
@@ -298,7 +322,7 @@ def main():
 
     # measured mean hit length on a sample of the last generation's candidates (outside the timed region)
     sample = min(P, 16)
-    res = g.eval_population(tr, model, wl.rtt_ms, par[:sample], 1.0, p95=False)
+    res = g.eval_population(tr, model, wl.rtt_ms, par[:sample], sweep_scale[:sample] if sweep else 1.0, p95=False)
     torch.cuda.synchronize()
     hit_mean = float(res.hit_blocks.to(torch.float64).mean().item())
     del res
@@ -316,20 +340,31 @@ def main():
     counters = None if args.online or args.engine or args.proxy else recorded_counters(kernel, f"config-{args.config} N={N} P={P}")
     traffic = counters["fetch_bytes_per_launch"] + counters["write_bytes_per_launch"] if counters else None
     achieved = bpr * P * N / (k_ms * 1e-3) / 1e9
-    # The replay is one dependent chain per candidate: what limits it is the rate at which a SIMD issues the
-    # chain's instructions, not bandwidth.  Recorded instruction counters say how far from that limit it runs:
-    # every wavefront instruction occupies its SIMD's issue port for four cycles.
-    issue = None
+    # The replay is one dependent chain per candidate, so what limits it is how long one wavefront takes per request,
+    # not a throughput ceiling: the recorded counters are reported per routing -- instructions by class, the share of
+    # its cycles that the SIMD's vector ALU is busy, and the share of their cycles that the wavefronts spend waiting
+    # (for memory, LDS, barriers or issue).  No fraction of an issue "peak" is given: a CU issues vector, scalar,
+    # LDS, memory and branch instructions of different wavefronts side by side, so there is no single such limit.
+    chain = None
     if counters and "sq_insts_per_routing" in counters:
         per = counters["sq_insts_per_routing"]
-        n_simd, clock_hz = 256 * 4, 2.4e9
-        total = sum(per.values())
-        rate = total * P * N / (k_ms * 1e-3)
-        issue = {"instructions_per_routing": per, "total_per_routing": total,
-                 "achieved_ginst_s": rate / 1e9, "peak_ginst_s": n_simd * clock_hz / 4 / 1e9,
-                 "frac": rate / (n_simd * clock_hz / 4)}
+        chain = {"instructions_per_routing": per, "total_per_routing": sum(per.values()),
+                 "us_per_request_step": k_ms * 1e3 / max(N, 1) * (1 if P <= 1024 else 1024 / P),
+                 "valu_busy_frac": counters.get("valu_busy_frac"), "wave_wait_frac": counters.get("wave_wait_frac")}
+    per_scale = None
+    if sweep:
+        # untimed breakdown: one launch per time scale (its 128 candidates)
+        per_scale = {}
+        for sc in sorted(set(float(x) for x in sweep_scale)):
+            idx = np.nonzero(sweep_scale == sc)[0]
+            g.eval_population(tr, model, wl.rtt_ms, sweep_par[idx], sweep_scale[idx], per_request=False, workspace=ws)
+            torch.cuda.synchronize()
+            per_scale[f"{sc:g}"] = g.last_eval_kernel_ms()["replay_ms"] * 1e3 / max(N, 1)
+        print("[bench] us per request step by time scale: " + ", ".join(f"{k}: {v:.3f}" for k, v in per_scale.items()),
+              file=sys.stderr, flush=True)
 
     mode = "P online tuners (window 128, hop 32) over the trace per step" if args.online else \
+        "one launch of 8 time scales x 128 candidates per step (eval + p95 TTFT / E2E)" if sweep else \
         "one ES generation per step (eval + p95 TTFT fitness + mean update)"
     if args.engine:
         mode += ", replicas under the engine model (uneven rates, KV-token budget, decode slow-down)"
@@ -344,12 +379,13 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f64", "data": "synthetic",
         "config": {"workload": f"config-{args.config} {wl.name}: R={wl.R} N={N} P={P} cache={wl.cache_blocks} blocks LRU, "
                                f"{mode}",
-                   "es_generation_wall_s": wall / args.steps, "warmup_generation_wall_s": warm_wall},
+                   "es_generation_wall_s": None if sweep else wall / args.steps, "warmup_generation_wall_s": warm_wall,
+                   "us_per_request_step_by_time_scale": per_scale},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "kernel": kernel, "mean_segments": segs_mean,
                      "kernel_ms": k_ms, "bytes_per_routing": bpr, "mean_blocks": n_mean, "mean_hit_blocks": hit_mean,
                      "fill_ms": float(np.mean(fill_ms)), "select_ms": float(np.mean(select_ms)),
-                     "issue": issue},
+                     "chain": chain},
     }
     if args.policies:
         out["policies"] = compare_policies(g, torch, tr, model, wl, [float(x) for x in state.best_theta[:]], N,
@@ -357,8 +393,12 @@ def main():
     if not args.no_cpu_baseline:
         cores = min(len(os.sched_getaffinity(0)), 16)
         on = (z_on[:cores].cpu().numpy(), list(state.lo[:]), list(state.hi[:]), state.sigma) if args.online else None
-        v, dt, n_s = cpu_baseline(wl, theta0 if args.online else par, min(args.cpu_sample_requests, N), cores, on,
-                                  recipe if args.engine else None, proxy if args.proxy else None)
+        sel = np.arange(cores) * max(1, P // cores) if sweep else np.arange(cores)      # (the sweep: replays of every time scale)
+        v, dt, n_s = cpu_baseline(wl, theta0 if args.online else par[sel % len(par)], min(args.cpu_sample_requests, N), cores, on,
+                                  recipe if args.engine else None, proxy if args.proxy else None,
+                                  sweep_scale[sel] if sweep else None)
+        plain = not (args.online or args.engine or args.proxy)
+        v1, dt1, n1 = cpu_single_thread(wl, par, min(150000, N)) if plain else (None, None, None)
         cpu_model = "unknown"
         try:
             with open("/proc/cpuinfo") as f:
@@ -369,7 +409,9 @@ def main():
                                "sample": f"{cores} replays (one per thread) x first {n_s} requests of the same trace, "
                                          f"{dt:.1f}s wall",
                                "per_core": v / cores, "cpu_model": cpu_model, "host_cpus": os.cpu_count(),
-                               "gpu_over_oracle": value / v}
+                               "gpu_over_oracle": value / v,
+                               "single_thread": None if v1 is None else
+                               {"value": v1, "unit": "routings/s", "sample": f"1 replay x first {n1} requests, {dt1:.1f}s wall"}}
     print(json.dumps(out), flush=True)
 
 

@@ -200,7 +200,10 @@ int gorgo_es_step(const gorgo_trace* t, const gorgo_model* m, const double* rtt_
  *   theta[k] = clip(exp(clip(ln parent[k] + sigma * z[step][k], ln lo[k], ln hi[k])), lo[k], hi[k]),
  * used from the next request on (ln of the parent is carried along, not retaken from the clipped value; exp
  * is evaluated by a fixed sequence of additions and multiplications, so that it has the same bits on every
- * processor).  P replays run P independent tuners (different draws, initial weights or time scales).
+ * processor).  A request's TTFT enters the window when the request is dispatched: the stated service model gives
+ * it at once, whereas the paper's proxy only sees a TTFT when the first token has come back, so the tuner here is
+ * fed a little earlier than a live one would be (a reading of this library, see the design notes).
+ * P replays run P independent tuners (different draws, initial weights or time scales).
  * Needs a chain-consistent trace (the dense segment-row formulation). */
 typedef struct gorgo_online {
     int32_t window;        /* 1..1024 requests per fitness window                                     */
@@ -338,12 +341,13 @@ int gorgo_last_eval_kernel_ms(double* fill_ms, double* replay_ms, double* select
 /* Measurement aid: gorgo_eval_population run by an instantiation of the segment-row kernel that reads the GPU's
  * cycle counter between the sections of its request loop and adds up, per replay and wavefront, the cycles each
  * section took (same results; slower by the clock reads, each of which also waits for the wavefront's
- * outstanding LDS accesses).  sections: DEVICE [P][2][GORGO_SECTIONS] uint64, [p][0] the cache wavefront
+ * outstanding LDS accesses).  sections: DEVICE [P][3][GORGO_SECTIONS] uint64, [p][0] the cache wavefront
  * (0 waiting for the queue terms, 1 match incl. the wait for its rows, 2 log records and the next rows, 3 score,
  * minimum and announcement, 4 waiting at the second meeting point, 5 ownership, 6 stores, log and eviction,
  * 7 patch and loop; then counts, not cycles: 8 log records fetched on the spot by the eviction walk, 9 cursor
  * advances, 10 log records dropped because they own nothing, 11 ownership walks), [p][1] the queue wavefront (0 retire and publish, 1 waiting at the first meeting point,
- * 2 retiring ahead, 3 front end, 4 waiting for the choice, 5 service and outputs, 6 batch turnover).  Needs the
+ * 2 retiring ahead, 3 nothing, 4 waiting for the choice, 5 service and outputs, 6 batch turnover), [p][2] the
+ * front-end wavefront (0 descriptors, 1 and 2 waiting at the two meeting points).  Needs the
  * segment formulation without packing; everything else as gorgo_eval_population. */
 #define GORGO_SECTIONS 12
 int gorgo_eval_population_sections(const gorgo_trace* t, const gorgo_model* m, const double* rtt_ms,

@@ -474,8 +474,10 @@ static int replay_impl(int64_t N, const int64_t* ts_ms, const int32_t* in_len, c
         if (ttft_ms) ttft_ms[r] = ttft[r];
         if (e2e_ms) e2e_ms[r] = e2e[r];
 
-        // online tuning (Sec. 4: "p95 TTFT of a rolling 128-request window with hop size 32"): a step when the
-        // first window is full and then every hop requests; the weights it leaves are used from request r+1 on
+        // online tuning (Sec. 4, tuning window: p95 TTFT over a rolling window, taken every hop requests): a step
+        // when the first window is full and then every hop requests; a request's TTFT enters the window when the
+        // request is dispatched (the stated service model gives it at once), and the weights a step leaves are
+        // used from request r+1 on
         if (window > 0 && r + 1 >= window && (r + 1 - window) % hop == 0) {
             const int64_t h = (r + 1 - window) / hop;
             if (schedule) {

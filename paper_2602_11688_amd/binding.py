@@ -251,7 +251,7 @@ class EvalResult:
     p95_ttft_ms: object = None
     p95_e2e_ms: object = None
     workspace: object = None
-    sections: object = None         # [P, 2, 12] int64 cycles per section (eval_population(sections=True) only)
+    sections: object = None         # [P, 3, 12] int64 cycles per section (eval_population(sections=True) only)
     # online tuner (eval_online only)
     theta_step: object = None       # [P, steps, 3] weights in use after each step
     fitness_step: object = None     # [P, steps] window p95 TTFT seen at each step
@@ -269,7 +269,7 @@ def eval_population(trace: Trace, model: Model, rtt_ms, params, scale, *, per_re
                     p95: bool = True, workspace=None, stream=None, device="cuda:0", sections: bool = False) -> EvalResult:
     """gorgo_eval_population with torch-allocated outputs.  Returns device tensors; asynchronous on `stream`
     (default: torch's current stream).  sections=True runs gorgo_eval_population_sections instead and adds
-    `sections` [P, 2, 12] (cycles per section of the request loop, cache and queue wavefront) to the result."""
+    `sections` [P, 3, 12] (cycles per section of the request loop: cache, queue and front-end wavefront) to the result."""
     import torch
     rtt = _np(rtt_ms, np.float64)
     par = _np(params, np.float64)
@@ -297,7 +297,7 @@ def eval_population(trace: Trace, model: Model, rtt_ms, params, scale, *, per_re
     m = model.c()
     with torch.cuda.device(dev):
         if sections:
-            res.sections = torch.zeros((P, 2, 12), dtype=torch.int64, device=dev)
+            res.sections = torch.zeros((P, 3, 12), dtype=torch.int64, device=dev)
             _check(lib().gorgo_eval_population_sections(trace._h, C.byref(m), _ptr(rtt), _ptr(par), _ptr(sc), P, C.byref(o),
                                                         C.c_void_p(workspace.data_ptr()), workspace.numel(),
                                                         C.c_void_p(s.cuda_stream), C.c_void_p(res.sections.data_ptr())))

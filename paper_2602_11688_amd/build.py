@@ -1,4 +1,5 @@
-"""Build libgorgo.so (HIP, gfx950 only) in-tree with hipcc."""
+"""Build libgorgo.so (HIP, gfx950 only) in-tree with hipcc.  Every call compiles: the sources include every header
+under csrc/, and nothing here guesses whether an existing library is still current."""
 import os
 import subprocess
 
@@ -7,15 +8,6 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libgorgo.so")
 SOURCES = ["trace.cpp", "es.cpp", "api.cpp", "kernels.hip"]
-HEADERS = [os.path.join(CSRC, "internal.h"), os.path.join(CSRC, "device_common.h"), os.path.join(CSRC, "replay_segments.h"), os.path.join(ROOT, "include", "gorgo.h")]
-
-
-def stale() -> bool:
-    if not os.path.exists(LIB):
-        return True
-    t = os.path.getmtime(LIB)
-    return any(os.path.getmtime(p) > t for p in [os.path.join(CSRC, s) for s in SOURCES] + HEADERS)
-
 
 def build(verbose: bool = False) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")

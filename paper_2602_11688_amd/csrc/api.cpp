@@ -317,11 +317,11 @@ int evaluate(const gorgo_trace* t, const gorgo_model* m, const double* rtt_ms, c
         if ((rc = copy_small_to_device(d_seeds, seeds, sizeof(uint64_t) * (size_t)P, hip_stream))) return rc;
         pol.seeds = d_seeds;
     }
-    // (the caller's stand-in weights may go away when this returns: the copies must have been taken by then)
-    if (policy != 0 && (rc = wait_for_copies(hip_stream))) return rc;
     if ((rc = copy_small_to_device(d_rtt, rtt_ms, sizeof(double) * pl.R, hip_stream))) return rc;
     if ((rc = copy_small_to_device(d_params, params, sizeof(double) * 3 * (size_t)P, hip_stream))) return rc;
     if ((rc = copy_small_to_device(d_scale, scale, sizeof(double) * (size_t)P, hip_stream))) return rc;
+    // (the library's own stand-in weights go away when its entry point returns: every copy must have been taken by then)
+    if (policy != 0 && (rc = wait_for_copies(hip_stream))) return rc;
     OnlineLaunch ol;
     if (online) {
         // (the host vector may go away when this function returns: the copy must have been taken by then)

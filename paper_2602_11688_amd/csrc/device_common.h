@@ -584,17 +584,19 @@ struct SlotQueues {
     // replica (its completion event has already reached the proxy), and which of several such slots takes the
     // request changes no latency and no load signal; only when every slot has a request in flight are they
     // searched for the earliest free time (lowest index on ties).  rtt_best: the chosen replica's round trip time.
-    // The latencies come back the same in every lane.
-    __device__ __forceinline__ void serve_in(SlotHead& h, int g, int64_t r, int best, double t, double rtt_best, int uncached,
-                                            int L, int O, double a_pf, double a_dec, Rec* rec, int lane, double* ttft_out,
-                                            double* e2e_out) {
+    // idle_then: the slots of this pass that had nothing in flight at the request's time t (the lists may have been
+    // retired further since, to the next request's time, which only makes more slots idle).  The latencies come
+    // back the same in every lane.
+    __device__ __forceinline__ void serve_in(SlotHead& h, int g, unsigned long long idle_then, int64_t r, int best, double t,
+                                            double rtt_best, int uncached, int L, int O, double a_pf, double a_dec, Rec* rec,
+                                            int lane, double* ttft_out, double* e2e_out) {
         const bool mine = h.rep == best;
         const int d = h.depth;
         const double half = 0.5 * rtt_best;
         const double arrive = t + half;
         double start = arrive;
         int k;
-        const unsigned long long idle = ballot(mine && d == 0);
+        const unsigned long long idle = ballot(mine) & idle_then;
         if (idle != 0) {
             k = __builtin_ctzll(idle);
         } else {
@@ -643,13 +645,21 @@ struct SlotQueues {
         my_q += lane == best ? (double)L : 0.0;
         my_cnt += lane == best ? 1.0 : 0.0;
     }
+    // the slots with nothing in flight, per pass (to be handed to serve after the lists have been retired further)
+    struct Idle {
+        unsigned long long m0, m1, m2, m3;
+    };
+    __device__ __forceinline__ Idle idle_slots() const {
+        return Idle{ballot(H0.depth == 0), ballot(H1.depth == 0), ballot(H2.depth == 0), ballot(H3.depth == 0)};
+    }
     __device__ __forceinline__ void serve(int64_t r, int best, double t, double rtt_best, int uncached, int L, int O,
-                                          double a_pf, double a_dec, Rec* rec, int lane, double* ttft_out, double* e2e_out) {
+                                          double a_pf, double a_dec, Rec* rec, int lane, const Idle& idle_then,
+                                          double* ttft_out, double* e2e_out) {
         switch ((best << log2bp) >> 6) {       // the pass that holds the replica's slots
-            case 0: serve_in(H0, lane, r, best, t, rtt_best, uncached, L, O, a_pf, a_dec, rec, lane, ttft_out, e2e_out); break;
-            case 1: serve_in(H1, WAVE + lane, r, best, t, rtt_best, uncached, L, O, a_pf, a_dec, rec, lane, ttft_out, e2e_out); break;
-            case 2: serve_in(H2, 2 * WAVE + lane, r, best, t, rtt_best, uncached, L, O, a_pf, a_dec, rec, lane, ttft_out, e2e_out); break;
-            default: serve_in(H3, 3 * WAVE + lane, r, best, t, rtt_best, uncached, L, O, a_pf, a_dec, rec, lane, ttft_out, e2e_out); break;
+            case 0: serve_in(H0, lane, idle_then.m0, r, best, t, rtt_best, uncached, L, O, a_pf, a_dec, rec, lane, ttft_out, e2e_out); break;
+            case 1: serve_in(H1, WAVE + lane, idle_then.m1, r, best, t, rtt_best, uncached, L, O, a_pf, a_dec, rec, lane, ttft_out, e2e_out); break;
+            case 2: serve_in(H2, 2 * WAVE + lane, idle_then.m2, r, best, t, rtt_best, uncached, L, O, a_pf, a_dec, rec, lane, ttft_out, e2e_out); break;
+            default: serve_in(H3, 3 * WAVE + lane, idle_then.m3, r, best, t, rtt_best, uncached, L, O, a_pf, a_dec, rec, lane, ttft_out, e2e_out); break;
         }
     }
 };

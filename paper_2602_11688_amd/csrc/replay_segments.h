@@ -96,7 +96,7 @@ struct SegArgs {
     int64_t index_blocks;         // >= 0: Eq. 3 takes its cached prefix from the proxy's own index (an LRU of this
                                   // many blocks per replica, 0 = it never forgets); < 0: from the replica's cache
     uint16_t* believed;           // [P][N] blocks the proxy believed cached on the chosen replica, nullable
-    unsigned long long* sections; // timed instantiation only: [P][2][SECTIONS] cycles per section (cache, queue wavefront)
+    unsigned long long* sections; // timed instantiation only: [P][3][SECTIONS] cycles per section (cache, queue, front-end wavefront)
 };
 
 // What picks the replica: the cost model of Eq. 3 with fixed weights, the same with the online tuner, or one
@@ -313,7 +313,7 @@ __device__ __forceinline__ int argmin_lanes(double v, bool in) {
     const unsigned mhi = wave_min_u32(khi);
     const bool tie = khi == mhi;             // (lanes outside hold the all-ones key, which no score maps to)
     const unsigned long long ties = ballot(tie);
-    if ((ties & (ties - 1)) == 0) return __builtin_ctzll(ties);      // one lane holds the smallest high word: done
+    if (__builtin_popcountll(ties) <= 1) return __builtin_ctzll(ties);      // one lane holds the smallest high word: done
     const unsigned klo = lo ^ neg;
     const unsigned mlo = wave_min_u32(tie ? klo : 0xffffffffu);
     return __builtin_ctzll(ballot(tie && klo == mlo));
@@ -324,7 +324,7 @@ __device__ __forceinline__ int argmin_lanes(double v, bool in) {
 // request's descriptor in the ring.  Lane k < 8 holds segment reference k of the request in hand, lane 8 the last
 // one (whose end position is the request's number of blocks).  It takes part in both meetings of every request
 // (a workgroup barrier counts every wavefront) and is always early.
-template <int MODE>
+template <int MODE, bool TIMED>
 __device__ __forceinline__ void front_wave(const SegArgs& a, int p, int lane, Handover* comm) {
     const int R = a.R;
     const int64_t N = a.N;
@@ -409,6 +409,8 @@ __device__ __forceinline__ void front_wave(const SegArgs& a, int p, int lane, Ha
     fe_commit(1);
     fe_issue(2);
     meet(true);         // the first descriptors are there: the cache wavefront may start
+    SectionClock<TIMED> clk;
+    clk.start();
     for (int64_t r = 0; r < N; ++r) {
         // in the long stretch between B(r - 1) and A(r), where the cache wavefront reads the descriptor of r + 1
         fe_commit(r + 2);           // (first read by the cache wavefront after B(r))
@@ -418,9 +420,13 @@ __device__ __forceinline__ void front_wave(const SegArgs& a, int p, int lane, Ha
             b0 += WAVE;
             load_batch(b0 + WAVE, nxt);
         }
+        clk.tick(0);                                                 // descriptors
         meet(true);                                                  // A(r)
+        clk.tick(1);                                                 // waiting at A
         meet(false);                                                 // B(r)
+        clk.tick(2);                                                 // waiting at B
     }
+    clk.write(a.sections ? a.sections + ((size_t)p * 3 + 2) * SECTIONS : nullptr, lane);
 }
 
 // ---------------------------------------------------------------------------------------------- queue side
@@ -532,6 +538,7 @@ __device__ __forceinline__ void queue_wave(const SegArgs& a, int p, int lane, un
         }
         if constexpr (SLOTS) Q.retire(t, rec, lane);
         else Q.retire(t, rec);
+        clk.tick(10);                                                // (finer: readlanes and retiring)
         // the queue term of Eq. 3, products rounded one by one (the least-request policy asks for the requests in
         // flight instead; the dictated policies ignore it)
         if (MODE == MODE_LEAST_REQUEST) comm->sq[lane] = Q.my_cnt;
@@ -540,34 +547,45 @@ __device__ __forceinline__ void queue_wave(const SegArgs& a, int p, int lane, un
             comm->sq[lane] = w_queue * qd;
         }
         clk.tick(0);                                                 // retire, publish
-        // While the cache wavefront is still busy with its own side of the previous request, the completions up
-        // to the next request's time are retired already: they do not depend on where this request goes (only
-        // this request's own completion is left for the retire above, next time round).  The service step still
-        // has to see the slots that were idle at this request's time, so their set is kept.  (With a lane per
-        // slot retiring costs next to nothing when nothing has completed, and is not done ahead.)
+        // The completions up to the next request's time do not depend on where this request goes (only this
+        // request's own completion does, which is left for the retire above, next time round): they are retired
+        // ahead, where this wavefront would otherwise wait -- with the slots in LDS (a retirement there is a search)
+        // before the meeting, while the cache wavefront is still busy with the previous request; with a lane per
+        // slot after it, while the cache wavefront decides.  The service step still has to see the slots that were
+        // idle at this request's time, so their set is kept.
         unsigned long long idle_now = 0;
-        if constexpr (!SLOTS) {
+        SlotQueues::Idle idle_then{0, 0, 0, 0};
+        const double t_ahead = i + 1 < WAVE ? readlane_f64(cur.t, i + 1) : readlane_f64(nxt.t, 0);
+        if constexpr (SLOTS) {
+            idle_then = Q.idle_slots();
+        } else {
             idle_now = Q.idle;
-            if (r + 1 < N) Q.retire(i + 1 < WAVE ? readlane_f64(cur.t, i + 1) : readlane_f64(nxt.t, 0), rec);
+            if (r + 1 < N) Q.retire(t_ahead, rec);
         }
         clk.tick(2);                                                 // retire ahead
+        clk.tick(3);                                                 // (nothing: what reading the clock costs)
         meet(true);                                                  // A(r)
         clk.tick(1);                                                 // waiting at A
+        if constexpr (SLOTS) {
+            if (r + 1 < N) Q.retire(t_ahead, rec, lane);
+        }
         meet(false);                                                 // B(r)
         clk.tick(4);                                                 // waiting at B
         const unsigned long long w = comm->choice;
         const unsigned hi = __builtin_amdgcn_readfirstlane((unsigned)(w >> 32));
         const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)w);
         const int best = (int)(hi & 63u);
+        clk.tick(8);                                                 // (finer: the choice read)
         double ttft, e2e;
         if constexpr (SLOTS)
-            Q.serve(r, best, t, readlane_f64(my_rtt, best), (int)lo, L, O, a.a_pf, a.a_dec, rec, lane, &ttft, &e2e);
+            Q.serve(r, best, t, readlane_f64(my_rtt, best), (int)lo, L, O, a.a_pf, a.a_dec, rec, lane, idle_then, &ttft, &e2e);
         else if constexpr (ENGINE)
             Q.template serve_engine<PROXY>(r, best, t, my_rtt, (int64_t)(int)lo, L, O, my_a_pf, my_a_dec, my_budget, a.eng_slowdown,
                            rec, lane, &ttft, &e2e);
         else
             Q.template serve<PROXY>(r, best, t, my_rtt, (int64_t)(int)lo, L, O, a.a_pf, a.a_dec, rec, lane, idle_now,
                                     &ttft, &e2e);
+        clk.tick(9);                                                 // (finer: service)
         o_ttft = lane == i ? ttft : o_ttft;
         o_e2e = lane == i ? e2e : o_e2e;
         o_route = lane == i ? best : o_route;
@@ -628,7 +646,7 @@ __device__ __forceinline__ void queue_wave(const SegArgs& a, int p, int lane, un
             clk.tick(6);                                             // batch turnover
         }
     }
-    clk.write(a.sections ? a.sections + ((size_t)p * 2 + 1) * SECTIONS : nullptr, lane);
+    clk.write(a.sections ? a.sections + ((size_t)p * 3 + 1) * SECTIONS : nullptr, lane);
     tuner_results();
 }
 
@@ -948,13 +966,8 @@ __device__ __forceinline__ void cache_wave(const SegArgs& a, int p, int lane, Ha
         }
 
         clk.tick(1);                                                 // match (and the wait for the rows)
-        // ---- the rows of this request have arrived, so has the log record requested during the previous
-        // request; the loads for the next request go out
-        c1.take_pending(c1.pend_raw);
-        if (PROXY && index_cap > 0) c2.take_pending(c2.pend_raw);
+        // ---- the rows of this request have arrived: the loads for the next request go out
         request_rows(next, other);
-        c1.issue_fill(log64, spare);
-        if (PROXY && index_cap > 0) c2.issue_fill(log64, spare);
 
         // ---- score (Eq. 3: rtt and prefill terms here, the queue term from the queue wavefront) and lowest-index
         // minimum.  block_tokens * blocks fits: below 2^15 and 2^16.
@@ -977,6 +990,12 @@ __device__ __forceinline__ void cache_wave(const SegArgs& a, int p, int lane, Ha
             now_rtt = comm->w[0];
             now_prefill = comm->w[1];
         }
+        // (while those words come from LDS: the log record requested during the previous request has arrived and
+        // becomes usable, and the next one is requested)
+        c1.take_pending(c1.pend_raw);
+        if (PROXY && index_cap > 0) c2.take_pending(c2.pend_raw);
+        c1.issue_fill(log64, spare);
+        if (PROXY && index_cap > 0) c2.issue_fill(log64, spare);
         double my_score;
         if (SCORED) {
             const double pf = a.a_pf * (double)my_u_seen;
@@ -998,8 +1017,8 @@ __device__ __forceinline__ void cache_wave(const SegArgs& a, int p, int lane, Ha
         *choice_slot = ((unsigned long long)((unsigned)best | ((unsigned)m_best << 8)) << 32) | u_best;
         if (PROXY && lane == 0) comm->seen = own_index ? seen_best : m_best;
         clk.tick(3);                                                 // score, minimum, announcement
-        meet(true);                                                  // B(r): the choice is there
-        clk.tick(4);                                                 // waiting at B
+        // (the announcement is on its way through LDS; the second meeting comes after the stores below, which do
+        // not depend on the queue side and give it the time to arrive)
 
         // ---- ownership: the segments this request takes over on the chosen replica stop belonging to
         // their previous requests.  Along the path the previous owners form runs; each run moves its
@@ -1053,6 +1072,9 @@ __device__ __forceinline__ void cache_wave(const SegArgs& a, int p, int lane, Ha
         // ---- log (every lane writes the same record; the chosen replica's lane links it) and eviction
         st(&log64[r], 0xFFFFFFFFull | ((unsigned long long)n << 48));      // next -1, own 0, n
         st(&log[is_best && tail_r >= 0 ? tail_r : spare].next, (int32_t)r);
+        clk.tick(6);                                                 // stores, log
+        meet(true);                                                  // B(r): the choice is there
+        clk.tick(4);                                                 // waiting at B
         c1.appended(is_best, (int)r, n, tail_r);
         if (PROXY) c2.appended(is_best, (int)r, n, tail_r);
         tail_r = is_best ? (int)r : tail_r;
@@ -1061,7 +1083,6 @@ __device__ __forceinline__ void cache_wave(const SegArgs& a, int p, int lane, Ha
         // date: ownership changes and links are stored as they happen)
         if (PROXY && index_cap > 0) c2.evict(is_best, n - seen_best, index_cap, log64);
 
-        clk.tick(6);                                                 // stores, log, eviction
         // ---- the rows of request r + 1 were requested before this request's stores: the leading segments the two
         // paths share (none unless r + 1 continues the same tree) get the cells this request just wrote
         const int common = other.flags >> 8;
@@ -1073,12 +1094,17 @@ __device__ __forceinline__ void cache_wave(const SegArgs& a, int p, int lane, Ha
                 for (int k = 4; k < 8; ++k) other.cell[k] = (k < common && is_best) ? (int32_t)r : other.cell[k];
             }
         }
-        clk.tick(7);                                                 // patch, loop
+        clk.tick(7);                                                 // eviction, patch, loop
     };
 
     RowsOf A, B;
     meet(false);                              // the first descriptors are there
     request_rows(read_desc(&comm->ring[0]), A);
+    // (Where the loop is entered, as many memory operations are in flight behind the first request's row loads as a
+    // pass through the loop leaves behind the next request's -- a log record load and four stores -- so that the
+    // wait for the rows at the top of the loop is the same wait on both ways in, and not one for everything.)
+    c1.issue_fill(log64, spare);
+    for (int k = 0; k < 4; ++k) st(&log64[spare], 0ull);
     clk.start();
     for (int64_t r = 0; r < N; r += 2) {
         step(r, A, B);
@@ -1091,7 +1117,7 @@ __device__ __forceinline__ void cache_wave(const SegArgs& a, int p, int lane, Ha
         clk.acc[10] = wave_sum_u32((unsigned)c1.n_dead);
         clk.acc[11] = (unsigned)__builtin_amdgcn_readfirstlane(n_walks);
     }
-    clk.write(a.sections ? a.sections + (size_t)p * 2 * SECTIONS : nullptr, lane);
+    clk.write(a.sections ? a.sections + (size_t)p * 3 * SECTIONS : nullptr, lane);
 }
 
 template <int MODE, bool ENGINE, bool PROXY, bool SLOTS = false, bool TIMED = false>
@@ -1106,9 +1132,12 @@ __global__ void __launch_bounds__(SEG3_THREADS) replay_segments_kernel(SegArgs a
     }
     __syncthreads();
     if (threadIdx.x >= 2 * WAVE) {
-        if (a.N > 0) front_wave<MODE>(a, p, lane, &comm);
+        if (a.N > 0) {
+            __builtin_amdgcn_s_setprio(1);
+            front_wave<MODE, TIMED>(a, p, lane, &comm);
+        }
     } else if (threadIdx.x >= WAVE) {
-        __builtin_amdgcn_s_setprio(2);
+        __builtin_amdgcn_s_setprio(3);
         queue_wave<MODE, ENGINE, PROXY, SLOTS, TIMED>(a, p, lane, lds_raw, &comm);
     } else if (a.N > 0) {
         __builtin_amdgcn_s_setprio(3);      // the two wavefronts on the chain go first at issue
