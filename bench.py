@@ -153,6 +153,38 @@ def cpu_baseline(wl, params, n_req, threads, online=None, engine=None, proxy=Non
     return threads * tr.N / dt, dt, tr.N
 
 
+def section_table(sec, N, P):
+    """The timed instantiation's per-wavefront section budget as text: shader-clock cycles per request of each
+    of the three wavefronts of a replay (mean over replays), between the marks the kernel sets, and the cache side's
+    event counts.  sec = the [P, 3, 12] array of gorgo_eval_population_sections."""
+    m = (sec.astype(np.float64) / max(N, 1)).mean(axis=0)
+    lines = []
+    cache = ["waiting at barrier A (queue terms)", "prefix match (waits for the rows)", "log records, next rows, uncached tokens",
+             "score, minimum, announcement", "waiting at barrier B (stores seen)", "ownership", "cell, log and link stores",
+             "eviction, patching the next rows, loop"]
+    queue = {10: "lane broadcasts, retiring what is due", 0: "publishing the queue terms", 1: "waiting at barrier A",
+             2: "retiring ahead for the next request", 3: "(reading the clock once)", 4: "waiting at barrier B", 8: "reading the choice",
+             9: "service: slot, completion time", 5: "outputs, tuner, loop", 6: "batch turnover"}
+    front = ["descriptors of request r+2, loads of r+3", "waiting at barrier A", "waiting at barrier B"]
+    lines.append(f"shader-clock cycles per request (s_memtime), mean over {P} replays")
+    k = 1.0
+    lines.append("cache wavefront (lane = replica):")
+    for i, name in enumerate(cache):
+        lines.append(f"  {name:44s} {m[0, i] * k:8.1f}")
+    lines.append(f"  {'total':44s} {m[0, :8].sum() * k:8.1f}")
+    lines.append(f"  events per request: on-the-spot record fetches {m[0, 8]:.3f}, cursor advances {m[0, 9]:.3f}, "
+                 f"dead records dropped {m[0, 10]:.3f}, ownership walks {m[0, 11]:.3f}")
+    lines.append("queue wavefront (lane = service slot):")
+    for i, name in queue.items():
+        lines.append(f"  {name:44s} {m[1, i] * k:8.1f}")
+    lines.append(f"  {'total':44s} {sum(m[1, i] for i in queue) * k:8.1f}")
+    lines.append("front-end wavefront (lane = segment reference):")
+    for i, name in enumerate(front):
+        lines.append(f"  {name:44s} {m[2, i] * k:8.1f}")
+    lines.append(f"  {'total':44s} {m[2, :3].sum() * k:8.1f}")
+    return "\n".join(lines)
+
+
 def compare_policies(g, torch, tr, model, wl, tuned, N, engine=None):
     """The paper's comparison of routing policies in synthetic form: one replay of the trace per policy, same replica
     model (the engine model when `engine` is given), time scale 1.  TTFT / E2E in ms; block_hit = cached blocks /
@@ -201,6 +233,9 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch one plain 1 GiB device copy before the timed region (reference for HBM counters)")
     ap.add_argument("--path", type=int, default=0, help="0 auto, 1 hashed block tables, 2 segment rows (experiments only)")
+    ap.add_argument("--sections", action="store_true",
+                    help="after the timed region, launch the kernel's timed instantiation once (it reads the clock at marks "
+                         "in each of its three wavefronts) and print the per-section cycle budget to stderr")
     ap.add_argument("--policies", action="store_true",
                     help="also replay the trace once under each routing policy of the paper's comparison (cost model with "
                          "the tuner's weights, its special cases, least-request, session affinity, random) and report "
@@ -362,6 +397,17 @@ def main():
             per_scale[f"{sc:g}"] = g.last_eval_kernel_ms()["replay_ms"] * 1e3 / max(N, 1)
         print("[bench] us per request step by time scale: " + ", ".join(f"{k}: {v:.3f}" for k, v in per_scale.items()),
               file=sys.stderr, flush=True)
+
+    if args.sections and rp["path"] == 2 and not (args.online or args.engine or args.proxy):
+        del ws                                     # (the section array needs a workspace of its own size)
+        torch.cuda.empty_cache()
+        res = g.eval_population(tr, model, wl.rtt_ms, par, sweep_scale if sweep else 1.0, per_request=False, sections=True)
+        torch.cuda.synchronize()
+        t_ms = g.last_eval_kernel_ms()["replay_ms"]
+        print(f"[bench] timed instantiation: replay kernel {t_ms:.1f} ms = {t_ms * 1e3 / max(N, 1):.3f} us per request step "
+              f"(plain kernel: {k_ms * 1e3 / max(N, 1):.3f})", file=sys.stderr)
+        print(section_table(res.sections.cpu().numpy(), N, P), file=sys.stderr, flush=True)
+        del res
 
     mode = "P online tuners (window 128, hop 32) over the trace per step" if args.online else \
         "one launch of 8 time scales x 128 candidates per step (eval + p95 TTFT / E2E)" if sweep else \

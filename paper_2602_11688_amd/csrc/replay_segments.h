@@ -261,6 +261,7 @@ constexpr int DESC_MORE4 = 1;        // more than four segments
 constexpr int DESC_DEEP = 2;         // more than eight segments
 constexpr int32_t NEVER_CACHED = INT32_MIN;      // cell value of the extra row: below any cursor
 
+constexpr int LOOK_RING = 8;          // log records of look-ahead kept in LDS per replica, behind the two in registers
 struct Handover {
     double sq[WAVE];                  // per replica: queue term of Eq. 3, w_queue * (a_pf * outstanding tokens)
                                       // (least-request policy: requests in flight)
@@ -270,6 +271,9 @@ struct Handover {
     unsigned long long unused[WAVE];  // where the lanes other than lane 0 write when the choice is announced
     int seen;                         // proxy variants: blocks the proxy believed cached on the chosen replica
     SegDesc ring[DESC_RING];
+    // look-ahead of the eviction cursors (the cache's; the proxy's index's): per replica, log records fetched ahead
+    // of the cursor, slot k of replica i at [k * WAVE + i]; the last slot is a spare that nothing reads
+    unsigned long long look[2][(LOOK_RING + 1) * WAVE];
 };
 
 // Workgroup barrier that both wavefronts of a replay meet at; `after_lds`: this wavefront's LDS accesses have
@@ -654,61 +658,73 @@ __device__ __forceinline__ void queue_wave(const SegArgs& a, int p, int lane, un
 // Eviction cursor of one LRU over a replica's log of routed requests, held by lane = replica.
 //   cursor: blocks last touched by a request before cur_r, or by cur_r at positions >= cur_k, are evicted;
 //   cur_own is where cur_r's owned suffix starts.
-//   nx_*, n2_*: the next two records of the replica's log that still own blocks (r < 0: empty).
 //   fill_r: the record after the last one held here, or -1 when that one is the youngest of the log.
 //   pend_*: a record being fetched (its load is only waited for one iteration later); changes made to it
 //   meanwhile are kept in pend_own / pend_next and override the loaded fields.
-// The kernel keeps the cursor of the replica's cache in plain local variables of the same names (the compiler
-// does measurably better with them); this struct is the same machinery for the proxy's own index of the replica,
-// an LRU of another capacity over the same log.
+//   Records that have arrived wait in a ring in LDS until the cursor reaches them: the log is
+//   read as far ahead of the cursor as the ring is long, so that a request which evicts several records' blocks at
+//   once rarely has to wait for a record to come from memory.
+// The same machinery serves the proxy's own index of the replica, an LRU of another capacity over the same log.
 struct EvictCursor {
     int cur_r = -1, cur_k = 0, cur_own = 0;
-    int nx_r = -1, nx_n = 0, nx_own = 0;
-    int n2_r = -1, n2_n = 0, n2_own = 0;
     int fill_r = -1;
     int pend_r = -1, pend_own = -1, pend_next = -1;
     unsigned long long pend_raw = 0;
+    // The look-ahead: a ring of records in LDS (slot k of this lane at ring[k * WAVE], packed r | own << 32 | n << 48),
+    // ring_cnt of them from slot ring_head on, the youngest being request ring_hi.
+    unsigned long long* ring = nullptr;
+    int ring_head = 0, ring_cnt = 0, ring_hi = -1;
     int live = 0;             // blocks this LRU holds
     int n_spot = 0, n_adv = 0, n_dead = 0;       // statistics (only the timed instantiation reads them): records fetched
                                                  // on the spot, cursor advances, records dropped because they own nothing
 
-    // The record requested by the previous issue_fill becomes usable: dropped if it owns nothing, else queued behind
-    // nx / n2.  Straight-line code: lanes with nothing pending go through it unchanged.
-    __device__ __forceinline__ void take_pending(unsigned long long raw) {
-        const bool have = pend_r >= 0;
-        const int n = (int)(raw >> 48);
-        const int own_mem = (int)((raw >> 32) & 0xFFFF);
+    // In the lanes with `who` set, the record requested by the previous issue_fill becomes usable: dropped if it owns
+    // nothing, else it joins the ring.  Straight-line code: lanes with nothing pending go through it unchanged
+    // (every lane stores to LDS: those with nothing for the ring into its spare slot).
+    __device__ __forceinline__ void take_pending(unsigned long long raw, bool who = true) {
+        const bool have = who && pend_r >= 0;
+        const unsigned hi = (unsigned)(raw >> 32);
+        const int n = (int)(hi >> 16);
+        const int own_mem = (int)(hi & 0xFFFFu);
         const int own = pend_own > own_mem ? pend_own : own_mem;
-        const int next = pend_next >= 0 ? pend_next : (int)(unsigned int)raw;
+        const int next = pend_next >= 0 ? pend_next : (int)(unsigned)raw;
         const bool alive = have && own < n;
-        const bool to_nx = alive && nx_r < 0;
-        const bool to_n2 = alive && !(nx_r < 0);
+        const int slot = alive ? (ring_head + ring_cnt) & (LOOK_RING - 1) : LOOK_RING;
+        ring[slot * WAVE] = (unsigned long long)(unsigned)pend_r | ((unsigned long long)((hi & 0xFFFF0000u) | (unsigned)own) << 32);
+        ring_cnt += alive ? 1 : 0;
+        ring_hi = alive ? pend_r : ring_hi;
         n_dead += have && !alive ? 1 : 0;
-        nx_r = to_nx ? pend_r : nx_r;
-        nx_n = to_nx ? n : nx_n;
-        nx_own = to_nx ? own : nx_own;
-        n2_r = to_n2 ? pend_r : n2_r;
-        n2_n = to_n2 ? n : n2_n;
-        n2_own = to_n2 ? own : n2_own;
         fill_r = have ? next : fill_r;
-        pend_r = -1;
+        pend_r = have ? -1 : pend_r;
     }
-    // Request the next record of the log where there is room for it.  Every lane loads (those with nothing to
+    // Request the next record of the log where the ring has room for it.  Every lane loads (those with nothing to
     // fetch read the spare record behind the log, `spare`, and ignore it), so that the load is a plain instruction
     // of the request loop and not a branch around one.  Called right after take_pending: nothing is pending.
     __device__ __forceinline__ void issue_fill(const unsigned long long* log64, int spare) {
-        const bool want = fill_r >= 0 && n2_r < 0;
+        const bool want = fill_r >= 0 && ring_cnt < LOOK_RING;
         pend_r = want ? fill_r : -1;
         pend_own = -1;
         pend_next = -1;
         pend_raw = ld(&log64[want ? fill_r : spare]);
     }
-    // request `owner`'s owned suffix now starts at `end` (owner = -2: nobody's)
+    // whether request `owner` may be one of the records in the ring (then disowned_anywhere is the call to make)
+    __device__ __forceinline__ bool maybe_in_ring(int owner) const { return ring_cnt > 0 && owner <= ring_hi; }
+    // request `owner`'s owned suffix now starts at `end` (owner = -2: nobody's); the owner is not in the ring
     __device__ __forceinline__ void disowned(int owner, int end) {
         cur_own = owner == cur_r ? end : cur_own;
-        nx_own = owner == nx_r ? end : nx_own;
-        n2_own = owner == n2_r ? end : n2_own;
         pend_own = owner == pend_r ? end : pend_own;
+    }
+    // the same where the owner may be a record in the ring (only called by the lanes it concerns)
+    __device__ __forceinline__ void disowned_anywhere(int owner, int end) {
+        disowned(owner, end);
+        if (maybe_in_ring(owner)) {
+#pragma nounroll
+            for (int k = 0; k < LOOK_RING; ++k) {
+                const unsigned long long e = ring[k * WAVE];
+                if ((int)(unsigned)e == owner)
+                    ring[k * WAVE] = (e & ~(0xFFFFull << 32)) | ((unsigned long long)(unsigned)end << 32);
+            }
+        }
     }
     // request r (n blocks) has become the youngest record of the log of the replica whose lane has is_best set;
     // tail_r is the youngest before it
@@ -731,41 +747,41 @@ struct EvictCursor {
         E -= take;
     }
     // `added` blocks have joined the LRU of the lane with `active` set; the cursor moves forward until the LRU
-    // fits `cap` blocks again.  The cursor's own record and one step to the next record held in registers are
-    // straight-line code; more steps (rarer) loop, and fetch on the spot when the registers run out.
-    __device__ __forceinline__ void evict(bool active, int added, int cap, const unsigned long long* log64) {
+    // fits `cap` blocks again.  The cursor's own record is straight-line code; steps to further records loop (all
+    // lanes together, those with nothing to evict unchanged), taking records from the ring, and from memory on the
+    // spot when the ring has run out.
+    __device__ __forceinline__ void evict(bool active, int added, int cap, const unsigned long long* log64, int spare) {
         live += active ? added : 0;
         int E = active ? live - cap : 0;
         E = E > 0 ? E : 0;
         live -= E;
         take_from_cursor(E);
-        if (ballot(E > 0) != 0) {
-            while (E > 0) {       // only the chosen replica's lane can be here
-                if (nx_r < 0) {
-                    // fetch a record on the spot (the one being fetched, if any, is waited for instead)
-                    unsigned long long raw = pend_raw;
-                    if (pend_r < 0) {
-                        if (fill_r < 0) break;      // cannot happen while E > 0; bounds the loop
-                        pend_r = fill_r;
-                        pend_own = -1;
-                        pend_next = -1;
-                        raw = ld(&log64[fill_r]);
-                        ++n_spot;
-                    }
-                    take_pending(raw);
-                    continue;
-                }
-                ++n_adv;
-                cur_r = nx_r;
-                cur_k = nx_n;
-                cur_own = nx_own;
-                nx_r = n2_r;
-                nx_n = n2_n;
-                nx_own = n2_own;
-                n2_r = -1;
-                take_from_cursor(E);
+        while (ballot(E > 0) != 0) {
+            const bool empty = E > 0 && ring_cnt == 0;
+            if (ballot(empty) != 0) {
+                // fetch a record on the spot (the one being fetched, if any, is waited for instead)
+                const bool fetch = empty && pend_r < 0 && fill_r >= 0;
+                const bool stuck = empty && pend_r < 0 && fill_r < 0;      // cannot happen; bounds the loop
+                live += stuck ? E : 0;
+                E = stuck ? 0 : E;
+                const unsigned long long got = ld(&log64[fetch ? fill_r : spare]);
+                pend_r = fetch ? fill_r : pend_r;
+                pend_own = fetch ? -1 : pend_own;
+                pend_next = fetch ? -1 : pend_next;
+                n_spot += fetch ? 1 : 0;
+                take_pending(fetch ? got : pend_raw, empty && !stuck);
+                continue;
             }
-            live += E;            // nothing left to evict (unreachable, kept consistent)
+            const bool go = E > 0;
+            const unsigned long long e = ring[(ring_head & (LOOK_RING - 1)) * WAVE];
+            const unsigned hi = (unsigned)(e >> 32);
+            n_adv += go ? 1 : 0;
+            cur_r = go ? (int)(unsigned)e : cur_r;
+            cur_k = go ? (int)(hi >> 16) : cur_k;
+            cur_own = go ? (int)(hi & 0xFFFFu) : cur_own;
+            ring_head += go ? 1 : 0;
+            ring_cnt -= go ? 1 : 0;
+            take_from_cursor(E);         // (lanes with E = 0 take nothing)
         }
     }
 };
@@ -807,6 +823,12 @@ __device__ __forceinline__ void cache_wave(const SegArgs& a, int p, int lane, Ha
     const bool own_index = PROXY && a.index_blocks >= 0;
     const int index_cap = PROXY && a.index_blocks > 0 ? (int)a.index_blocks : 0;
     EvictCursor c1, c2;                       // the cache's cursor, the index's cursor
+    c1.ring = &comm->look[0][lane];
+    c2.ring = &comm->look[1][lane];
+    for (int k = 0; k <= LOOK_RING; ++k) {
+        c1.ring[k * WAVE] = ~0ull;
+        c2.ring[k * WAVE] = ~0ull;
+    }
     int tail_r = -1;                          // youngest request routed to this replica
 
     char* const rows = reinterpret_cast<char*>(a.last + (size_t)p * a.nseg * R);
@@ -1026,15 +1048,18 @@ __device__ __forceinline__ void cache_wave(const SegArgs& a, int p, int lane, Ha
         // requests the cursor has passed, or to the cursor request beyond its position).  One previous owner
         // (the usual case) is straight-line code: the chosen replica's lane names it, the others name nobody.
         const bool cached_some = seen_best > 0;
-        const bool simple = cached_some && !deep && ((ballot(one_owner) >> best) & 1ull) != 0;
+        // (a previous owner whose record waits in a cursor's look-ahead ring goes the long way too: rare, the ring
+        // holds the oldest records of the replica and previous owners are mostly young)
+        const bool plain_owner = one_owner && !c1.maybe_in_ring(mine.cell[0]) && !(PROXY && c2.maybe_in_ring(mine.cell[0]));
+        const bool simple = cached_some && !deep && ((ballot(plain_owner) >> best) & 1ull) != 0;
         const int dis_owner = is_best && simple ? mine.cell[0] : -2;
         if (cached_some && !simple) {
             // several previous owners, or a prefix longer than the preloaded rows: walk it
             ++n_walks;
             auto disown = [&](int owner, int end) {       // lane `best`: owner's owned suffix now starts at end
                 st(&log[owner].own, (uint16_t)end);
-                c1.disowned(owner, end);
-                if (PROXY) c2.disowned(owner, end);
+                c1.disowned_anywhere(owner, end);
+                if (PROXY) c2.disowned_anywhere(owner, end);
             };
             const int64_t j0 = dr->j0;
             const int cb_r = __builtin_amdgcn_readlane(PROXY ? c2.cur_r : c1.cur_r, best);
@@ -1078,10 +1103,10 @@ __device__ __forceinline__ void cache_wave(const SegArgs& a, int p, int lane, Ha
         c1.appended(is_best, (int)r, n, tail_r);
         if (PROXY) c2.appended(is_best, (int)r, n, tail_r);
         tail_r = is_best ? (int)r : tail_r;
-        c1.evict(is_best && bounded, n - m_best, cap, log64);
+        c1.evict(is_best && bounded, n - m_best, cap, log64, spare);
         // the proxy's index evicts under its own capacity: its cursor walks the same log (whose memory is up to
         // date: ownership changes and links are stored as they happen)
-        if (PROXY && index_cap > 0) c2.evict(is_best, n - seen_best, index_cap, log64);
+        if (PROXY && index_cap > 0) c2.evict(is_best, n - seen_best, index_cap, log64, spare);
 
         // ---- the rows of request r + 1 were requested before this request's stores: the leading segments the two
         // paths share (none unless r + 1 continues the same tree) get the cells this request just wrote
