@@ -89,6 +89,37 @@ typedef struct gorgo_model {
     double decode_ms_per_token;
 } gorgo_model;
 
+/* How an evaluation is carried out.  None of it changes a result; all of it is per call: every entry point that
+ * evaluates, sizes a workspace or answers a question about an evaluation takes a `const gorgo_options*`, and NULL
+ * stands for the defaults (the library keeps no settings between calls).  gorgo_options_default fills in the
+ * defaults; out-of-range values make the call fail with GORGO_ERR_INVALID_ARG.
+ *   replay_path: formulation of the cache state.  0 = automatic (default), 1 = hashed block tables (any trace),
+ *     2 = dense segment rows (chain-consistent traces only; the call fails otherwise).  Both compute identical
+ *     results; they differ in workspace size and speed.  Automatic picks segment rows when the trace is
+ *     chain-consistent and its requests average at most 16 segments.  Size the workspace with the same options
+ *     as the evaluation.
+ *   replay_packing: with at most 32 replicas, at most 16 slots per replica and an even number of replays,
+ *     gorgo_eval_population and gorgo_es_step can run two replays per pair of wavefronts of the segment-row kernel
+ *     (a replay keeps one lane per replica, so half of a 64-lane wavefront idles otherwise).  A replay is a serial
+ *     chain, so this only pays when the replays would not all be resident on the GPU at once (more than about
+ *     1,024 of them): 2 (default) packs exactly then, 1 whenever the shape allows, 0 never.
+ *   handover_poll_limit: how many times a wavefront of the packed segment-row replay polls for its partner's
+ *     word before the replay is given up (default 2^24, about a second; a replay that is given up ends at once,
+ *     every latency of it becomes NaN, so does its p95, and gorgo_es_step fails with GORGO_ERR_NONFINITE).  It
+ *     never happens unless the library is wrong; the setting exists so that this path can be exercised: with 0
+ *     every replay whose partner is not ready at the first poll is given up.  (The unpacked kernel's wavefronts
+ *     meet at workgroup barriers and do not poll.)
+ *   table_factor_percent: the open-addressed cache tables of the block-table formulation get at least
+ *     ceil(factor/100 * (cache_blocks + max blocks of a request)) slots, rounded up to a power of two
+ *     (default 200, 110..1600). */
+typedef struct gorgo_options {
+    int32_t replay_path;
+    int32_t replay_packing;
+    int32_t handover_poll_limit;
+    int32_t table_factor_percent;
+} gorgo_options;
+void gorgo_options_default(gorgo_options* options);
+
 /* Per-replay outputs.  Every pointer is a DEVICE pointer owned by the caller, or NULL to skip that output.
  * P = number of replays, N = requests in the trace; [P][N] arrays are row-major (replay-major). */
 typedef struct gorgo_outputs {
@@ -104,7 +135,7 @@ typedef struct gorgo_outputs {
  * be NULL: the size then covers any combination).  The workspace holds the per-replay cache tables, the
  * in-flight request records and stand-ins for per-request outputs that were not requested but are needed
  * by the percentile reduction. */
-int gorgo_workspace_bytes(const gorgo_trace* t, const gorgo_model* m, int32_t P, const gorgo_outputs* outputs,
+int gorgo_workspace_bytes(const gorgo_trace* t, const gorgo_model* m, const gorgo_options* options, int32_t P, const gorgo_outputs* outputs,
                           size_t* bytes);
 
 /* Evaluate P replays of the trace (Eq. 1-3, Sec. 2.2-2.3; one replay per candidate weight vector and time
@@ -119,7 +150,7 @@ int gorgo_workspace_bytes(const gorgo_trace* t, const gorgo_model* m, int32_t P,
  * for them; outputs are valid once the stream has reached that point.  The first evaluation of a trace on
  * a device uploads the trace (one allocation and one synchronous copy).  Calls that share a workspace must
  * be ordered on one stream. */
-int gorgo_eval_population(const gorgo_trace* t, const gorgo_model* m, const double* rtt_ms,
+int gorgo_eval_population(const gorgo_trace* t, const gorgo_model* m, const gorgo_options* options, const double* rtt_ms,
                           const double* params, const double* scale, int32_t P, const gorgo_outputs* outputs,
                           void* workspace, size_t workspace_bytes, void* hip_stream);
 
@@ -138,7 +169,7 @@ int gorgo_trace_to_device(const gorgo_trace* t);
  * is enqueued.  Every call on a GPU uses that GPU's one array: what must start clean is cleared by the call's
  * own kernels, and two such calls that overlap in time on one GPU (different streams or threads) race. */
 #define GORGO_STATIC_SCRATCH_BYTES ((size_t)64 << 20)
-int gorgo_eval_population_static(const gorgo_trace* t, const gorgo_model* m, const double* rtt_ms,
+int gorgo_eval_population_static(const gorgo_trace* t, const gorgo_model* m, const gorgo_options* options, const double* rtt_ms,
                                  const double* params, const double* scale, int32_t P,
                                  const gorgo_outputs* outputs, void* hip_stream);
 
@@ -184,8 +215,8 @@ int gorgo_es_update(const double* params, const double* fitness, int32_t P, gorg
  * gorgo_eval_population (fitness = p95 TTFT in ms), synchronise the stream once, update the state.
  * params_out [P][3] and fitness_out [P] are optional host arrays.  The workspace must be sized with
  * gorgo_es_workspace_bytes. */
-int gorgo_es_workspace_bytes(const gorgo_trace* t, const gorgo_model* m, int32_t P, size_t* bytes);
-int gorgo_es_step(const gorgo_trace* t, const gorgo_model* m, const double* rtt_ms, double scale, int32_t P,
+int gorgo_es_workspace_bytes(const gorgo_trace* t, const gorgo_model* m, const gorgo_options* options, int32_t P, size_t* bytes);
+int gorgo_es_step(const gorgo_trace* t, const gorgo_model* m, const gorgo_options* options, const double* rtt_ms, double scale, int32_t P,
                   gorgo_es_state* inout, double* params_out, double* fitness_out, void* workspace,
                   size_t workspace_bytes, void* hip_stream);
 
@@ -225,7 +256,7 @@ int64_t gorgo_online_steps(int64_t N, int32_t window, int32_t hop);
 
 /* Evaluate P replays, each with its own online tuner.  As gorgo_eval_population, except that
  * theta0 (host [P][3], each within [lo, hi]) are the weights of the first window.  Same workspace size. */
-int gorgo_eval_online(const gorgo_trace* t, const gorgo_model* m, const double* rtt_ms, const double* theta0,
+int gorgo_eval_online(const gorgo_trace* t, const gorgo_model* m, const gorgo_options* options, const double* rtt_ms, const double* theta0,
                       const double* scale, int32_t P, const gorgo_online* online, const gorgo_outputs* outputs,
                       void* workspace, size_t workspace_bytes, void* hip_stream);
 
@@ -254,7 +285,7 @@ typedef enum gorgo_policy {
 /* Evaluate P replays routed by `policy`, replay p at time scale scale[p] (and, for the random policy, with
  * seed seeds[p]; seeds is a host array [P], may be NULL for the other policies).  Everything else as
  * gorgo_eval_population, same workspace size. */
-int gorgo_eval_policy(const gorgo_trace* t, const gorgo_model* m, const double* rtt_ms, int32_t policy,
+int gorgo_eval_policy(const gorgo_trace* t, const gorgo_model* m, const gorgo_options* options, const double* rtt_ms, int32_t policy,
                       const uint64_t* seeds, const double* scale, int32_t P, const gorgo_outputs* outputs,
                       void* workspace, size_t workspace_bytes, void* hip_stream);
 
@@ -288,7 +319,7 @@ typedef struct gorgo_engine {
  *   GORGO_POLICY_COST_MODEL with online != NULL: the online tuner from weights params, as gorgo_eval_online;
  *   the other policies: as gorgo_eval_policy (params may be NULL; seeds as there; online must be NULL).
  * Everything else (outputs, workspace and its size, stream, errors) as gorgo_eval_population. */
-int gorgo_eval_engine(const gorgo_trace* t, const gorgo_model* m, const gorgo_engine* engine, const double* rtt_ms,
+int gorgo_eval_engine(const gorgo_trace* t, const gorgo_model* m, const gorgo_options* options, const gorgo_engine* engine, const double* rtt_ms,
                       int32_t policy, const double* params, const uint64_t* seeds, const gorgo_online* online,
                       const double* scale, int32_t P, const gorgo_outputs* outputs, void* workspace,
                       size_t workspace_bytes, void* hip_stream);
@@ -328,7 +359,7 @@ typedef struct gorgo_proxy {
  * gorgo_eval_engine; online may be NULL (fixed weights params, host [P][3]) or an online tuner as in
  * gorgo_eval_online (params are then the initial weights).  The round trip times come from proxy->rtt_true_ms.
  * Everything else (outputs, workspace and its size, stream, errors) as gorgo_eval_population. */
-int gorgo_eval_proxy(const gorgo_trace* t, const gorgo_model* m, const gorgo_proxy* proxy, const gorgo_engine* engine,
+int gorgo_eval_proxy(const gorgo_trace* t, const gorgo_model* m, const gorgo_options* options, const gorgo_proxy* proxy, const gorgo_engine* engine,
                      const double* params, const gorgo_online* online, const double* scale, int32_t P,
                      const gorgo_outputs* outputs, void* workspace, size_t workspace_bytes, void* hip_stream);
 
@@ -350,45 +381,21 @@ int gorgo_last_eval_kernel_ms(double* fill_ms, double* replay_ms, double* select
  * front-end wavefront (0 descriptors, 1 and 2 waiting at the two meeting points).  Needs the
  * segment formulation without packing; everything else as gorgo_eval_population. */
 #define GORGO_SECTIONS 12
-int gorgo_eval_population_sections(const gorgo_trace* t, const gorgo_model* m, const double* rtt_ms,
+int gorgo_eval_population_sections(const gorgo_trace* t, const gorgo_model* m, const gorgo_options* options, const double* rtt_ms,
                                    const double* params, const double* scale, int32_t P,
                                    const gorgo_outputs* outputs, void* workspace, size_t workspace_bytes,
                                    void* hip_stream, uint64_t* sections);
 
-/* Choice of cache-state formulation for subsequent calls: 0 = automatic (default), 1 = hashed block tables
- * (any trace), 2 = dense segment rows (chain-consistent traces only; evaluation fails with
- * GORGO_ERR_INVALID_ARG otherwise).  Both compute identical results; they differ in workspace size and
- * speed.  Automatic picks segment rows when the trace is chain-consistent and its requests average at most
- * 16 segments.  gorgo_workspace_bytes reflects the choice in force when it is called. */
-int gorgo_set_replay_path(int32_t mode);
+/* Whether gorgo_eval_population with P replays of this trace and model would pack them under these options
+ * (*packed = 1) or not (0).  Asks the current device how many workgroups it holds at once. */
+int gorgo_query_replay_packing(const gorgo_trace* t, const gorgo_model* m, const gorgo_options* options, int32_t P,
+                               int32_t* packed);
 
-/* How many times a wavefront of the segment-row replay polls for its partner's word before the replay is given
- * up (default 2^24, about a second; a replay that is given up ends at once, every latency of it becomes NaN, so
- * does its p95, and gorgo_es_step fails with GORGO_ERR_NONFINITE).  It never happens unless the library is
- * wrong; the setting exists so that this path can be exercised: with 0 every replay whose partner is not ready
- * at the first poll is given up. */
-int gorgo_set_handover_poll_limit(int32_t polls);
-
-/* With at most 32 replicas, at most 16 slots per replica and an even number of replays, gorgo_eval_population and
- * gorgo_es_step can run two replays per pair of wavefronts of the segment-row kernel (a replay keeps one lane per
- * replica, so half of a 64-lane wavefront idles otherwise).  A replay is a serial chain, so this only pays when
- * the replays would not all be resident on the GPU at once (more than about 1,024 of them): mode 2 (default) packs
- * exactly then, mode 1 whenever the shape allows, mode 0 never.  Results are the same bit for bit. */
-int gorgo_set_replay_packing(int32_t mode);
-
-/* Whether gorgo_eval_population with P replays of this trace and model would pack them now (*packed = 1) or not
- * (0).  Asks the current device how many workgroups it holds at once. */
-int gorgo_query_replay_packing(const gorgo_trace* t, const gorgo_model* m, int32_t P, int32_t* packed);
-
-/* Formulation that an evaluation of this trace would use now (1 or 2, see gorgo_set_replay_path), the number
+/* Formulation that an evaluation of this trace would use under these options (1 or 2, see gorgo_options), the number
  * of segments of the trace and the total number of (request, segment) references; the last two are 0 for a
  * trace that is not chain-consistent.  Each out pointer may be NULL. */
-int gorgo_query_replay_path(const gorgo_trace* t, int32_t* path, int64_t* n_segments, int64_t* segment_refs);
-
-/* Tuning knob for tests and experiments: the open-addressed cache tables get at least
- * ceil(factor_percent/100 * (cache_blocks + max blocks of a request)) slots, rounded up to a power of two
- * (default 200, minimum 110).  Results never depend on it. */
-int gorgo_set_table_factor_percent(int32_t factor_percent);
+int gorgo_query_replay_path(const gorgo_trace* t, const gorgo_options* options, int32_t* path, int64_t* n_segments,
+                            int64_t* segment_refs);
 
 #ifdef __cplusplus
 }

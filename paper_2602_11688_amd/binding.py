@@ -48,6 +48,15 @@ class _Proxy(C.Structure):
                 ("believed_hit_blocks", C.c_void_p)]
 
 
+class Options(C.Structure):
+    """gorgo_options: how an evaluation is carried out (no result depends on it), passed to the library with every
+    call.  replay_path 0 automatic / 1 hashed block tables / 2 dense segment rows; replay_packing 0 never / 1 whenever
+    the shape allows / 2 automatic; handover_poll_limit polls before a packed replay is given up;
+    table_factor_percent 110..1600."""
+    _fields_ = [("replay_path", C.c_int32), ("replay_packing", C.c_int32), ("handover_poll_limit", C.c_int32),
+                ("table_factor_percent", C.c_int32)]
+
+
 class EsState(C.Structure):
     _fields_ = [("theta", C.c_double * 3), ("sigma", C.c_double), ("lo", C.c_double * 3), ("hi", C.c_double * 3),
                 ("seed", C.c_uint64), ("generation", C.c_int64), ("best_fitness", C.c_double),
@@ -73,21 +82,21 @@ def lib():
         L.gorgo_trace_info.argtypes = [vp, C.POINTER(i64), C.POINTER(i64), C.POINTER(i32), C.POINTER(i64), C.POINTER(i32)]
         L.gorgo_free_trace.argtypes = [vp]
         L.gorgo_free_trace.restype = None
-        L.gorgo_workspace_bytes.argtypes = [vp, C.POINTER(_Model), i32, C.POINTER(_Outputs), C.POINTER(C.c_size_t)]
-        L.gorgo_eval_population.argtypes = [vp, C.POINTER(_Model), vp, vp, vp, i32, C.POINTER(_Outputs), vp,
+        L.gorgo_workspace_bytes.argtypes = [vp, C.POINTER(_Model), C.POINTER(Options), i32, C.POINTER(_Outputs), C.POINTER(C.c_size_t)]
+        L.gorgo_eval_population.argtypes = [vp, C.POINTER(_Model), C.POINTER(Options), vp, vp, vp, i32, C.POINTER(_Outputs), vp,
                                             C.c_size_t, vp]
-        L.gorgo_eval_population_sections.argtypes = [vp, C.POINTER(_Model), vp, vp, vp, i32, C.POINTER(_Outputs), vp,
+        L.gorgo_eval_population_sections.argtypes = [vp, C.POINTER(_Model), C.POINTER(Options), vp, vp, vp, i32, C.POINTER(_Outputs), vp,
                                                      C.c_size_t, vp, vp]
         L.gorgo_trace_to_device.argtypes = [vp]
-        L.gorgo_eval_population_static.argtypes = [vp, C.POINTER(_Model), vp, vp, vp, i32, C.POINTER(_Outputs), vp]
+        L.gorgo_eval_population_static.argtypes = [vp, C.POINTER(_Model), C.POINTER(Options), vp, vp, vp, i32, C.POINTER(_Outputs), vp]
         L.gorgo_online_steps.argtypes = [i64, i32, i32]
         L.gorgo_online_steps.restype = i64
-        L.gorgo_eval_online.argtypes = [vp, C.POINTER(_Model), vp, vp, vp, i32, C.POINTER(_Online), C.POINTER(_Outputs),
+        L.gorgo_eval_online.argtypes = [vp, C.POINTER(_Model), C.POINTER(Options), vp, vp, vp, i32, C.POINTER(_Online), C.POINTER(_Outputs),
                                         vp, C.c_size_t, vp]
-        L.gorgo_eval_policy.argtypes = [vp, C.POINTER(_Model), vp, i32, vp, vp, i32, C.POINTER(_Outputs), vp, C.c_size_t, vp]
-        L.gorgo_eval_engine.argtypes = [vp, C.POINTER(_Model), C.POINTER(_Engine), vp, i32, vp, vp, C.POINTER(_Online), vp,
+        L.gorgo_eval_policy.argtypes = [vp, C.POINTER(_Model), C.POINTER(Options), vp, i32, vp, vp, i32, C.POINTER(_Outputs), vp, C.c_size_t, vp]
+        L.gorgo_eval_engine.argtypes = [vp, C.POINTER(_Model), C.POINTER(Options), C.POINTER(_Engine), vp, i32, vp, vp, C.POINTER(_Online), vp,
                                         i32, C.POINTER(_Outputs), vp, C.c_size_t, vp]
-        L.gorgo_eval_proxy.argtypes = [vp, C.POINTER(_Model), C.POINTER(_Proxy), C.POINTER(_Engine), vp, C.POINTER(_Online),
+        L.gorgo_eval_proxy.argtypes = [vp, C.POINTER(_Model), C.POINTER(Options), C.POINTER(_Proxy), C.POINTER(_Engine), vp, C.POINTER(_Online),
                                        vp, i32, C.POINTER(_Outputs), vp, C.c_size_t, vp]
         L.gorgo_es_init.argtypes = [C.POINTER(EsState), C.c_uint64]
         L.gorgo_es_sample.argtypes = [C.c_uint64, i64, i32, vp]
@@ -95,19 +104,17 @@ def lib():
         L.gorgo_philox4x32_10.restype = None
         L.gorgo_es_propose.argtypes = [C.POINTER(EsState), vp, i32, vp]
         L.gorgo_es_update.argtypes = [vp, vp, i32, C.POINTER(EsState)]
-        L.gorgo_es_workspace_bytes.argtypes = [vp, C.POINTER(_Model), i32, C.POINTER(C.c_size_t)]
-        L.gorgo_es_step.argtypes = [vp, C.POINTER(_Model), vp, dbl, i32, C.POINTER(EsState), vp, vp, vp, C.c_size_t, vp]
-        L.gorgo_set_table_factor_percent.argtypes = [i32]
-        L.gorgo_set_replay_path.argtypes = [i32]
-        L.gorgo_set_handover_poll_limit.argtypes = [i32]
-        L.gorgo_set_replay_packing.argtypes = [i32]
-        L.gorgo_query_replay_packing.argtypes = [vp, C.POINTER(_Model), i32, C.POINTER(i32)]
-        L.gorgo_query_replay_path.argtypes = [vp, C.POINTER(i32), C.POINTER(i64), C.POINTER(i64)]
+        L.gorgo_es_workspace_bytes.argtypes = [vp, C.POINTER(_Model), C.POINTER(Options), i32, C.POINTER(C.c_size_t)]
+        L.gorgo_es_step.argtypes = [vp, C.POINTER(_Model), C.POINTER(Options), vp, dbl, i32, C.POINTER(EsState), vp, vp, vp, C.c_size_t, vp]
+        L.gorgo_query_replay_packing.argtypes = [vp, C.POINTER(_Model), C.POINTER(Options), i32, C.POINTER(i32)]
+        L.gorgo_query_replay_path.argtypes = [vp, C.POINTER(Options), C.POINTER(i32), C.POINTER(i64), C.POINTER(i64)]
+        L.gorgo_options_default.argtypes = [C.POINTER(Options)]
+        L.gorgo_options_default.restype = None
         L.gorgo_last_eval_kernel_ms.argtypes = [C.POINTER(dbl)] * 3
         for name in ("gorgo_load_trace", "gorgo_load_trace_arrays", "gorgo_trace_info", "gorgo_workspace_bytes",
                      "gorgo_eval_population", "gorgo_eval_population_sections", "gorgo_trace_to_device", "gorgo_eval_population_static", "gorgo_eval_online", "gorgo_eval_policy", "gorgo_eval_engine", "gorgo_eval_proxy", "gorgo_es_init", "gorgo_es_sample", "gorgo_es_propose",
-                     "gorgo_es_update", "gorgo_es_workspace_bytes", "gorgo_es_step", "gorgo_set_table_factor_percent",
-                     "gorgo_last_eval_kernel_ms", "gorgo_set_replay_path", "gorgo_set_handover_poll_limit", "gorgo_set_replay_packing", "gorgo_query_replay_packing", "gorgo_query_replay_path"):
+                     "gorgo_es_update", "gorgo_es_workspace_bytes", "gorgo_es_step",
+                     "gorgo_last_eval_kernel_ms", "gorgo_query_replay_packing", "gorgo_query_replay_path"):
             getattr(L, name).restype = C.c_int
         _lib = L
     return _lib
@@ -171,10 +178,10 @@ class Trace:
         return dict(N=n.value, total_blocks=tb.value, max_blocks=mb.value, unique_ids=u.value,
                     chain_consistent=bool(cc.value))
 
-    def replay_path(self) -> dict:
-        """Formulation an evaluation would use now (1 = block tables, 2 = segment rows) and segment counts."""
+    def replay_path(self, options: Optional["Options"] = None) -> dict:
+        """Formulation an evaluation would use under the options (1 = block tables, 2 = segment rows) and segment counts."""
         p, ns, nr = C.c_int32(), C.c_int64(), C.c_int64()
-        _check(lib().gorgo_query_replay_path(self._h, C.byref(p), C.byref(ns), C.byref(nr)))
+        _check(lib().gorgo_query_replay_path(self._h, _opt(options), C.byref(p), C.byref(ns), C.byref(nr)))
         return dict(path=p.value, n_segments=ns.value, segment_refs=nr.value)
 
     @property
@@ -193,32 +200,58 @@ class Trace:
             pass
 
 
+# The library keeps no settings: every call carries its options.  For callers that want one choice for a whole
+# script (tests, the benchmark), this module keeps a default Options object of its own, passed wherever a call
+# gives none; the set_* functions below change it.
+_default_options = None
+
+
+def default_options() -> Options:
+    """The Options passed when a call gives none (initially the library's defaults)."""
+    global _default_options
+    if _default_options is None:
+        o = Options()
+        lib().gorgo_options_default(C.byref(o))
+        _default_options = o
+    return _default_options
+
+
+def _opt(options: Optional[Options]):
+    return C.byref(options if options is not None else default_options())
+
+
+def _set_default(field: str, value: int, lo: int, hi: int, what: str):
+    if not lo <= int(value) <= hi:
+        raise GorgoError(-1, f"{what} must be in {lo}..{hi}")
+    setattr(default_options(), field, int(value))
+
+
 def set_table_factor_percent(pct: int):
-    _check(lib().gorgo_set_table_factor_percent(pct))
+    _set_default("table_factor_percent", pct, 110, 1600, "table_factor_percent")
 
 
 def set_replay_packing(mode: int) -> None:
     """Two replays per wavefront pair: 0 never, 1 whenever the shape allows it, 2 (default) when the replays would not
     all be resident at once otherwise; results do not depend on it."""
-    _check(lib().gorgo_set_replay_packing(int(mode)))
+    _set_default("replay_packing", mode, 0, 2, "replay_packing")
 
 
-def replay_packing(trace: "Trace", model: "Model", P: int) -> bool:
-    """Whether eval_population with P replays would run two replays per wavefront pair now."""
+def replay_packing(trace: "Trace", model: "Model", P: int, options: Optional[Options] = None) -> bool:
+    """Whether eval_population with P replays would run two replays per wavefront pair under the options."""
     out = C.c_int32()
     m = model.c()
-    _check(lib().gorgo_query_replay_packing(trace._h, C.byref(m), P, C.byref(out)))
+    _check(lib().gorgo_query_replay_packing(trace._h, C.byref(m), _opt(options), P, C.byref(out)))
     return bool(out.value)
 
 
 def set_handover_poll_limit(polls: int):
-    """Polls of a hand-over word before a replay is given up (default 2^24); for tests of that path."""
-    _check(lib().gorgo_set_handover_poll_limit(polls))
+    """Polls of a hand-over word before a packed replay is given up (default 2^24); for tests of that path."""
+    _set_default("handover_poll_limit", polls, 0, 2**31 - 1, "handover_poll_limit")
 
 
 def set_replay_path(mode: int):
     """0 = automatic, 1 = hashed block tables, 2 = dense segment rows."""
-    _check(lib().gorgo_set_replay_path(mode))
+    _set_default("replay_path", mode, 0, 2, "replay_path")
 
 
 def last_eval_kernel_ms() -> dict:
@@ -234,10 +267,10 @@ def _outputs_struct(route=None, hit_blocks=None, ttft_ms=None, e2e_ms=None, p95_
     return _Outputs(dp(route), dp(hit_blocks), dp(ttft_ms), dp(e2e_ms), dp(p95_ttft_ms), dp(p95_e2e_ms))
 
 
-def workspace_bytes(trace: Trace, model: Model, P: int, outputs: Optional[_Outputs] = None) -> int:
+def workspace_bytes(trace: Trace, model: Model, P: int, outputs: Optional[_Outputs] = None, options: Optional[Options] = None) -> int:
     n = C.c_size_t()
     m = model.c()
-    _check(lib().gorgo_workspace_bytes(trace._h, C.byref(m), P, None if outputs is None else C.byref(outputs),
+    _check(lib().gorgo_workspace_bytes(trace._h, C.byref(m), _opt(options), P, None if outputs is None else C.byref(outputs),
                                        C.byref(n)))
     return n.value
 
@@ -266,7 +299,7 @@ class EvalResult:
 
 
 def eval_population(trace: Trace, model: Model, rtt_ms, params, scale, *, per_request: bool = True,
-                    p95: bool = True, workspace=None, stream=None, device="cuda:0", sections: bool = False) -> EvalResult:
+                    p95: bool = True, workspace=None, stream=None, device="cuda:0", sections: bool = False, options: Optional[Options] = None) -> EvalResult:
     """gorgo_eval_population with torch-allocated outputs.  Returns device tensors; asynchronous on `stream`
     (default: torch's current stream).  sections=True runs gorgo_eval_population_sections instead and adds
     `sections` [P, 3, 12] (cycles per section of the request loop: cache, queue and front-end wavefront) to the result."""
@@ -289,7 +322,7 @@ def eval_population(trace: Trace, model: Model, rtt_ms, params, scale, *, per_re
         res.p95_ttft_ms = torch.empty((P,), dtype=torch.float64, device=dev)
         res.p95_e2e_ms = torch.empty((P,), dtype=torch.float64, device=dev)
     o = _outputs_struct(res.route, res.hit_blocks, res.ttft_ms, res.e2e_ms, res.p95_ttft_ms, res.p95_e2e_ms)
-    need = workspace_bytes(trace, model, P, o)
+    need = workspace_bytes(trace, model, P, o, options)
     if workspace is None or workspace.numel() < need:
         workspace = torch.empty((need,), dtype=torch.uint8, device=dev)
     res.workspace = workspace
@@ -298,11 +331,11 @@ def eval_population(trace: Trace, model: Model, rtt_ms, params, scale, *, per_re
     with torch.cuda.device(dev):
         if sections:
             res.sections = torch.zeros((P, 3, 12), dtype=torch.int64, device=dev)
-            _check(lib().gorgo_eval_population_sections(trace._h, C.byref(m), _ptr(rtt), _ptr(par), _ptr(sc), P, C.byref(o),
+            _check(lib().gorgo_eval_population_sections(trace._h, C.byref(m), _opt(options), _ptr(rtt), _ptr(par), _ptr(sc), P, C.byref(o),
                                                         C.c_void_p(workspace.data_ptr()), workspace.numel(),
                                                         C.c_void_p(s.cuda_stream), C.c_void_p(res.sections.data_ptr())))
         else:
-            _check(lib().gorgo_eval_population(trace._h, C.byref(m), _ptr(rtt), _ptr(par), _ptr(sc), P, C.byref(o),
+            _check(lib().gorgo_eval_population(trace._h, C.byref(m), _opt(options), _ptr(rtt), _ptr(par), _ptr(sc), P, C.byref(o),
                                                C.c_void_p(workspace.data_ptr()), workspace.numel(),
                                                C.c_void_p(s.cuda_stream)))
     return res
@@ -312,7 +345,7 @@ STATIC_SCRATCH_BYTES = 64 << 20
 
 
 def eval_population_static(trace: Trace, model: Model, rtt_ms, params, scale, *, per_request: bool = True,
-                           p95: bool = True, stream=None, device="cuda:0") -> EvalResult:
+                           p95: bool = True, stream=None, device="cuda:0", options: Optional[Options] = None) -> EvalResult:
     """gorgo_eval_population_static: as eval_population, with the library's static scratch array as the workspace
     (nothing is allocated by the library; the outputs are still torch tensors allocated here)."""
     import torch
@@ -338,7 +371,7 @@ def eval_population_static(trace: Trace, model: Model, rtt_ms, params, scale, *,
     m = model.c()
     with torch.cuda.device(dev):
         _check(lib().gorgo_trace_to_device(trace._h))
-        _check(lib().gorgo_eval_population_static(trace._h, C.byref(m), _ptr(rtt), _ptr(par), _ptr(sc), P, C.byref(o),
+        _check(lib().gorgo_eval_population_static(trace._h, C.byref(m), _opt(options), _ptr(rtt), _ptr(par), _ptr(sc), P, C.byref(o),
                                                   C.c_void_p(s.cuda_stream)))
     return res
 
@@ -347,7 +380,7 @@ POLICIES = {"least-request": 1, "session-affinity": 2, "random": 3}
 
 
 def eval_policy(trace: Trace, model: Model, rtt_ms, policy: str, scale, *, seeds=None, per_request: bool = True,
-                p95: bool = True, workspace=None, stream=None, device="cuda:0") -> EvalResult:
+                p95: bool = True, workspace=None, stream=None, device="cuda:0", options: Optional[Options] = None) -> EvalResult:
     """gorgo_eval_policy with torch-allocated outputs: one replay per entry of `scale`, routed by a baseline policy
     ("least-request", "session-affinity", "random"; prefix-cache and least-load are eval_population with weights
     (0,1,0) and (0,0,1)).  seeds [P] for the random policy."""
@@ -370,14 +403,14 @@ def eval_policy(trace: Trace, model: Model, rtt_ms, policy: str, scale, *, seeds
         res.p95_ttft_ms = torch.empty((P,), dtype=torch.float64, device=dev)
         res.p95_e2e_ms = torch.empty((P,), dtype=torch.float64, device=dev)
     o = _outputs_struct(res.route, res.hit_blocks, res.ttft_ms, res.e2e_ms, res.p95_ttft_ms, res.p95_e2e_ms)
-    need = workspace_bytes(trace, model, P, o)
+    need = workspace_bytes(trace, model, P, o, options)
     if workspace is None or workspace.numel() < need:
         workspace = torch.empty((need,), dtype=torch.uint8, device=dev)
     res.workspace = workspace
     s = stream if stream is not None else torch.cuda.current_stream(dev)
     m = model.c()
     with torch.cuda.device(dev):
-        _check(lib().gorgo_eval_policy(trace._h, C.byref(m), _ptr(rtt), POLICIES[policy], _ptr(sd), _ptr(sc), P, C.byref(o),
+        _check(lib().gorgo_eval_policy(trace._h, C.byref(m), _opt(options), _ptr(rtt), POLICIES[policy], _ptr(sd), _ptr(sc), P, C.byref(o),
                                        C.c_void_p(workspace.data_ptr()), workspace.numel(), C.c_void_p(s.cuda_stream)))
     return res
 
@@ -391,7 +424,7 @@ def online_steps(N: int, window: int = 128, hop: int = 32) -> int:
 
 def eval_online(trace: Trace, model: Model, rtt_ms, theta0, z, scale, *, lo, hi, sigma0, window: int = 128,
                 hop: int = 32, per_request: bool = True, p95: bool = True, trajectory: bool = True, workspace=None,
-                stream=None, device="cuda:0") -> EvalResult:
+                stream=None, device="cuda:0", options: Optional[Options] = None) -> EvalResult:
     """gorgo_eval_online with torch-allocated outputs: P replays, each tuning its weights online.  theta0 [P,3];
     z [P, steps, 3] standard normal draws (host array or device tensor)."""
     import torch
@@ -430,14 +463,14 @@ def eval_online(trace: Trace, model: Model, rtt_ms, theta0, z, scale, *, lo, hi,
     on = _Online(window, hop, (C.c_double * 3)(*[float(x) for x in lo]), (C.c_double * 3)(*[float(x) for x in hi]),
                  float(sigma0), dp(zt), dp(res.theta_step), dp(res.fitness_step), dp(res.theta_final),
                  dp(res.sigma_final), dp(res.accepted))
-    need = workspace_bytes(trace, model, P, o)
+    need = workspace_bytes(trace, model, P, o, options)
     if workspace is None or workspace.numel() < need:
         workspace = torch.empty((need,), dtype=torch.uint8, device=dev)
     res.workspace = workspace
     s = stream if stream is not None else torch.cuda.current_stream(dev)
     m = model.c()
     with torch.cuda.device(dev):
-        _check(lib().gorgo_eval_online(trace._h, C.byref(m), _ptr(rtt), _ptr(th0), _ptr(sc), P, C.byref(on), C.byref(o),
+        _check(lib().gorgo_eval_online(trace._h, C.byref(m), _opt(options), _ptr(rtt), _ptr(th0), _ptr(sc), P, C.byref(on), C.byref(o),
                                        C.c_void_p(workspace.data_ptr()), workspace.numel(), C.c_void_p(s.cuda_stream)))
     res._z = zt          # keep the draws alive until the stream has consumed them
     return res
@@ -455,7 +488,7 @@ class Engine:
 
 def eval_engine(trace: Trace, model: Model, engine: Engine, rtt_ms, scale, *, params=None, policy: str = "cost-model",
                 seeds=None, online: Optional[dict] = None, per_request: bool = True, p95: bool = True,
-                workspace=None, stream=None, device="cuda:0") -> EvalResult:
+                workspace=None, stream=None, device="cuda:0", options: Optional[Options] = None) -> EvalResult:
     """gorgo_eval_engine with torch-allocated outputs.  policy "cost-model" routes by Eq. 3 with weights params
     [P,3] (and, with online = dict(z=[P,steps,3], lo=, hi=, sigma0=, window=, hop=), tunes them online); the
     baseline policies route as in eval_policy, one replay per entry of `scale`."""
@@ -512,7 +545,7 @@ def eval_engine(trace: Trace, model: Model, engine: Engine, rtt_ms, scale, *, pa
                      C.c_void_p(res.fitness_step.data_ptr()), C.c_void_p(res.theta_final.data_ptr()),
                      C.c_void_p(res.sigma_final.data_ptr()), C.c_void_p(res.accepted.data_ptr()))
     o = _outputs_struct(res.route, res.hit_blocks, res.ttft_ms, res.e2e_ms, res.p95_ttft_ms, res.p95_e2e_ms)
-    need = workspace_bytes(trace, model, P, o)
+    need = workspace_bytes(trace, model, P, o, options)
     if workspace is None or workspace.numel() < need:
         workspace = torch.empty((need,), dtype=torch.uint8, device=dev)
     res.workspace = workspace
@@ -520,7 +553,7 @@ def eval_engine(trace: Trace, model: Model, engine: Engine, rtt_ms, scale, *, pa
     m = model.c()
     code = 0 if cost_model else POLICIES[policy]
     with torch.cuda.device(dev):
-        _check(lib().gorgo_eval_engine(trace._h, C.byref(m), C.byref(eng), _ptr(rtt), code, _ptr(par), _ptr(sd),
+        _check(lib().gorgo_eval_engine(trace._h, C.byref(m), _opt(options), C.byref(eng), _ptr(rtt), code, _ptr(par), _ptr(sd),
                                        None if on is None else C.byref(on), _ptr(sc), P, C.byref(o),
                                        C.c_void_p(workspace.data_ptr()), workspace.numel(), C.c_void_p(s.cuda_stream)))
     return res
@@ -539,7 +572,7 @@ class Proxy:
 
 def eval_proxy(trace: Trace, model: Model, proxy: Proxy, params, scale, *, engine: Optional[Engine] = None,
                online: Optional[dict] = None, per_request: bool = True, p95: bool = True, workspace=None, stream=None,
-               device="cuda:0") -> EvalResult:
+               device="cuda:0", options: Optional[Options] = None) -> EvalResult:
     """gorgo_eval_proxy with torch-allocated outputs: P replays under weights params [P,3] (tuned online when
     online = dict(z=, lo=, hi=, sigma0=, window=, hop=) is given) with imperfect proxy knowledge; replicas follow the
     engine model when `engine` is given, else the linear one."""
@@ -599,14 +632,14 @@ def eval_proxy(trace: Trace, model: Model, proxy: Proxy, params, scale, *, engin
                      C.c_void_p(res.fitness_step.data_ptr()), C.c_void_p(res.theta_final.data_ptr()),
                      C.c_void_p(res.sigma_final.data_ptr()), C.c_void_p(res.accepted.data_ptr()))
     o = _outputs_struct(res.route, res.hit_blocks, res.ttft_ms, res.e2e_ms, res.p95_ttft_ms, res.p95_e2e_ms)
-    need = workspace_bytes(trace, model, P, o)
+    need = workspace_bytes(trace, model, P, o, options)
     if workspace is None or workspace.numel() < need:
         workspace = torch.empty((need,), dtype=torch.uint8, device=dev)
     res.workspace = workspace
     s = stream if stream is not None else torch.cuda.current_stream(dev)
     m = model.c()
     with torch.cuda.device(dev):
-        _check(lib().gorgo_eval_proxy(trace._h, C.byref(m), C.byref(px), None if eng is None else C.byref(eng), _ptr(par),
+        _check(lib().gorgo_eval_proxy(trace._h, C.byref(m), _opt(options), C.byref(px), None if eng is None else C.byref(eng), _ptr(par),
                                       None if on is None else C.byref(on), _ptr(sc), P, C.byref(o),
                                       C.c_void_p(workspace.data_ptr()), workspace.numel(), C.c_void_p(s.cuda_stream)))
     res._tables = tables
@@ -647,20 +680,20 @@ def es_update(state: EsState, params, fitness) -> EsState:
     return state
 
 
-def es_workspace_bytes(trace: Trace, model: Model, P: int) -> int:
+def es_workspace_bytes(trace: Trace, model: Model, P: int, options: Optional[Options] = None) -> int:
     n = C.c_size_t()
     m = model.c()
-    _check(lib().gorgo_es_workspace_bytes(trace._h, C.byref(m), P, C.byref(n)))
+    _check(lib().gorgo_es_workspace_bytes(trace._h, C.byref(m), _opt(options), P, C.byref(n)))
     return n.value
 
 
 def es_step(trace: Trace, model: Model, rtt_ms, scale: float, P: int, state: EsState, *, workspace=None,
-            stream=None, device="cuda:0"):
+            stream=None, device="cuda:0", options: Optional[Options] = None):
     """gorgo_es_step.  Returns (params[P,3], fitness[P], workspace); `state` is updated in place."""
     import torch
     rtt = _np(rtt_ms, np.float64)
     dev = torch.device(device)
-    need = es_workspace_bytes(trace, model, P)
+    need = es_workspace_bytes(trace, model, P, options)
     if workspace is None or workspace.numel() < need:
         workspace = torch.empty((need,), dtype=torch.uint8, device=dev)
     par = np.zeros((P, 3), np.float64)
@@ -668,7 +701,7 @@ def es_step(trace: Trace, model: Model, rtt_ms, scale: float, P: int, state: EsS
     s = stream if stream is not None else torch.cuda.current_stream(dev)
     m = model.c()
     with torch.cuda.device(dev):
-        _check(lib().gorgo_es_step(trace._h, C.byref(m), _ptr(rtt), float(scale), P, C.byref(state), _ptr(par),
+        _check(lib().gorgo_es_step(trace._h, C.byref(m), _opt(options), _ptr(rtt), float(scale), P, C.byref(state), _ptr(par),
                                    _ptr(fit), C.c_void_p(workspace.data_ptr()), workspace.numel(),
                                    C.c_void_p(s.cuda_stream)))
     return par, fit, workspace

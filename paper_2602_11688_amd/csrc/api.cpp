@@ -11,10 +11,29 @@
 namespace gorgo {
 namespace {
 
-std::atomic<int32_t> g_table_factor_percent{200};
-std::atomic<int32_t> g_path{PATH_AUTO};
 
 size_t up256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+constexpr gorgo_options DEFAULT_OPTIONS = {PATH_AUTO, 2, 1 << 24, 200};
+
+// The caller's options (NULL: the defaults), checked.
+int take_options(const gorgo_options* given, gorgo_options* out) {
+    *out = given ? *given : DEFAULT_OPTIONS;
+    if (out->replay_path != PATH_AUTO && out->replay_path != PATH_BLOCKS && out->replay_path != PATH_SEGMENTS)
+        return fail(GORGO_ERR_INVALID_ARG, "options.replay_path must be 0 (auto), 1 (block tables) or 2 (segment rows)");
+    if (out->replay_packing < 0 || out->replay_packing > 2)
+        return fail(GORGO_ERR_INVALID_ARG, "options.replay_packing must be 0 (never), 1 (whenever possible) or 2 (automatic)");
+    if (out->handover_poll_limit < 0) return fail(GORGO_ERR_INVALID_ARG, "options.handover_poll_limit must be >= 0");
+    if (out->table_factor_percent < 110 || out->table_factor_percent > 1600)
+        return fail(GORGO_ERR_INVALID_ARG, "options.table_factor_percent must be in 110..1600");
+    return GORGO_OK;
+}
+
+// which formulation a trace gets under a replay_path setting
+int32_t path_for(const gorgo_trace* t, int32_t mode) {
+    const bool few = (int64_t)t->seg.size() <= 16 * (t->N > 0 ? t->N : 1);
+    return mode == PATH_SEGMENTS || (mode == PATH_AUTO && t->chain_consistent && few) ? PATH_SEGMENTS : PATH_BLOCKS;
+}
 
 int check_model(const gorgo_trace* t, const gorgo_model* m) {
     if (!t) return fail(GORGO_ERR_INVALID_ARG, "trace is NULL");
@@ -40,8 +59,14 @@ int check_model(const gorgo_trace* t, const gorgo_model* m) {
 }
 
 // Table geometry and workspace carve-up.
-int make_plan(const gorgo_trace* t, const gorgo_model* m, int32_t P, const gorgo_outputs* o, Plan* pl) {
+int make_plan(const gorgo_trace* t, const gorgo_model* m, const gorgo_options* options, int32_t P, const gorgo_outputs* o,
+              Plan* pl) {
     if (P < 1 || P > (1 << 20)) return fail(GORGO_ERR_INVALID_ARG, "P must be in 1..2^20");
+    gorgo_options opt;
+    int orc = take_options(options, &opt);
+    if (orc) return orc;
+    pl->packing = opt.replay_packing;
+    pl->poll_limit = opt.handover_poll_limit;
     pl->P = P;
     pl->R = m->R;
     pl->B = m->batch;
@@ -52,12 +77,9 @@ int make_plan(const gorgo_trace* t, const gorgo_model* m, int32_t P, const gorgo
     pl->a_dec = m->decode_ms_per_token;
     // Formulation: dense segment rows when the trace is chain-consistent and its requests are few segments
     // long (every request then costs a handful of row reads); hashed block tables otherwise.
-    const int32_t mode = g_path.load();
-    const bool seg_ok = t->chain_consistent;
-    if (mode == PATH_SEGMENTS && !seg_ok)
+    if (opt.replay_path == PATH_SEGMENTS && !t->chain_consistent)
         return fail(GORGO_ERR_INVALID_ARG, "the segment formulation needs a chain-consistent trace");
-    const bool few = (int64_t)t->seg.size() <= 16 * (t->N > 0 ? t->N : 1);
-    pl->path = mode == PATH_SEGMENTS || (mode == PATH_AUTO && seg_ok && few) ? PATH_SEGMENTS : PATH_BLOCKS;
+    pl->path = path_for(t, opt.replay_path);
     pl->nseg = t->n_segments;
     if (pl->path == PATH_SEGMENTS && (uint64_t)(pl->nseg + 2) * (uint64_t)m->R * 4u >= (1ull << 32))
         return fail(GORGO_ERR_INVALID_ARG, "segment rows of one replay exceed 4 GiB; use the block-table formulation");
@@ -65,7 +87,7 @@ int make_plan(const gorgo_trace* t, const gorgo_model* m, int32_t P, const gorgo
     // spare: the replay compacts a table once 7/8 of its slots have been used.
     const int64_t d = t->max_distinct;
     const int64_t resident = (pl->C > 0 ? pl->C : t->unique_ids) + d;
-    const int64_t factor = g_table_factor_percent.load();
+    const int64_t factor = opt.table_factor_percent;
     int64_t need = (resident * factor + 99) / 100;
     const int64_t floor_need = ((resident + d) * 8 + 6) / 7 + 64;
     if (need < floor_need) need = floor_need;
@@ -107,67 +129,45 @@ using namespace gorgo;
 
 extern "C" {
 
-int gorgo_set_table_factor_percent(int32_t factor_percent) {
-    clear_error();
-    if (factor_percent < 110 || factor_percent > 1600) return fail(GORGO_ERR_INVALID_ARG, "factor must be in 110..1600");
-    g_table_factor_percent.store(factor_percent);
-    return GORGO_OK;
+void gorgo_options_default(gorgo_options* options) {
+    if (options) *options = DEFAULT_OPTIONS;
 }
 
-int gorgo_set_handover_poll_limit(int32_t polls) {
-    clear_error();
-    if (polls < 0) return fail(GORGO_ERR_INVALID_ARG, "polls must be >= 0");
-    set_handover_poll_limit(polls);
-    return GORGO_OK;
-}
-
-int gorgo_set_replay_packing(int32_t mode) {
-    clear_error();
-    if (mode < 0 || mode > 2) return fail(GORGO_ERR_INVALID_ARG, "mode must be 0 (never), 1 (whenever possible) or 2 (automatic)");
-    set_replay_packing(mode);
-    return GORGO_OK;
-}
-
-int gorgo_query_replay_packing(const gorgo_trace* t, const gorgo_model* m, int32_t P, int32_t* packed) {
+int gorgo_query_replay_packing(const gorgo_trace* t, const gorgo_model* m, const gorgo_options* options, int32_t P,
+                               int32_t* packed) {
     clear_error();
     if (!packed) return fail(GORGO_ERR_INVALID_ARG, "packed is NULL");
     int rc = check_model(t, m);
     if (rc) return rc;
     Plan pl;
-    rc = make_plan(t, m, P, nullptr, &pl);
+    rc = make_plan(t, m, options, P, nullptr, &pl);
     if (rc) return rc;
     *packed = pl.path == PATH_SEGMENTS && pack_replays(pl, pl.nseg + 2) ? 1 : 0;
     return GORGO_OK;
 }
 
-int gorgo_set_replay_path(int32_t mode) {
-    clear_error();
-    if (mode != PATH_AUTO && mode != PATH_BLOCKS && mode != PATH_SEGMENTS)
-        return fail(GORGO_ERR_INVALID_ARG, "mode must be 0 (auto), 1 (block tables) or 2 (segment rows)");
-    g_path.store(mode);
-    return GORGO_OK;
-}
-
-int gorgo_query_replay_path(const gorgo_trace* t, int32_t* path, int64_t* n_segments, int64_t* segment_refs) {
+int gorgo_query_replay_path(const gorgo_trace* t, const gorgo_options* options, int32_t* path, int64_t* n_segments,
+                            int64_t* segment_refs) {
     clear_error();
     if (!t) return fail(GORGO_ERR_INVALID_ARG, "trace is NULL");
-    const int32_t mode = g_path.load();
-    const bool few = (int64_t)t->seg.size() <= 16 * (t->N > 0 ? t->N : 1);
-    if (path)
-        *path = mode == PATH_SEGMENTS || (mode == PATH_AUTO && t->chain_consistent && few) ? PATH_SEGMENTS : PATH_BLOCKS;
+    gorgo_options opt;
+    const int orc = take_options(options, &opt);
+    if (orc) return orc;
+    if (path) *path = path_for(t, opt.replay_path);
     if (n_segments) *n_segments = t->n_segments;
     if (segment_refs) *segment_refs = (int64_t)t->seg.size();
     return GORGO_OK;
 }
 
-int gorgo_workspace_bytes(const gorgo_trace* t, const gorgo_model* m, int32_t P, const gorgo_outputs* outputs,
+int gorgo_workspace_bytes(const gorgo_trace* t, const gorgo_model* m, const gorgo_options* options, int32_t P,
+                          const gorgo_outputs* outputs,
                           size_t* bytes) {
     clear_error();
     if (!bytes) return fail(GORGO_ERR_INVALID_ARG, "bytes is NULL");
     int rc = check_model(t, m);
     if (rc) return rc;
     Plan pl;
-    rc = make_plan(t, m, P, outputs, &pl);
+    rc = make_plan(t, m, options, P, outputs, &pl);
     if (rc) return rc;
     *bytes = pl.total;
     return GORGO_OK;
@@ -178,7 +178,8 @@ int gorgo_workspace_bytes(const gorgo_trace* t, const gorgo_model* m, int32_t P,
 namespace {
 
 // Validation, small copies and launches common to the fixed-weight and the online evaluation.
-int evaluate(const gorgo_trace* t, const gorgo_model* m, const double* rtt_ms, const double* params,
+int evaluate(const gorgo_trace* t, const gorgo_model* m, const gorgo_options* options, const double* rtt_ms,
+             const double* params,
              const double* scale, int32_t P, const gorgo_online* online, int32_t policy, const uint64_t* seeds,
              const gorgo_outputs* outputs, void* workspace, size_t workspace_bytes, void* hip_stream,
              const gorgo_engine* engine = nullptr, const gorgo_proxy* proxy = nullptr,
@@ -224,7 +225,7 @@ int evaluate(const gorgo_trace* t, const gorgo_model* m, const double* rtt_ms, c
     }
     if (!rtt_ms || !params || !scale || !outputs) return fail(GORGO_ERR_INVALID_ARG, "a required pointer is NULL");
     Plan pl;
-    rc = make_plan(t, m, P, outputs, &pl);
+    rc = make_plan(t, m, options, P, outputs, &pl);
     if (rc) return rc;
     for (int i = 0; i < m->R; ++i)
         if (!std::isfinite(rtt_ms[i]) || rtt_ms[i] < 0 || rtt_ms[i] > 1e9)
@@ -359,19 +360,21 @@ int evaluate(const gorgo_trace* t, const gorgo_model* m, const double* rtt_ms, c
 
 extern "C" {
 
-int gorgo_eval_population(const gorgo_trace* t, const gorgo_model* m, const double* rtt_ms, const double* params,
+int gorgo_eval_population(const gorgo_trace* t, const gorgo_model* m, const gorgo_options* options,
+        const double* rtt_ms, const double* params,
                           const double* scale, int32_t P, const gorgo_outputs* outputs, void* workspace,
                           size_t workspace_bytes, void* hip_stream) {
     clear_error();
-    return evaluate(t, m, rtt_ms, params, scale, P, nullptr, 0, nullptr, outputs, workspace, workspace_bytes, hip_stream);
+    return evaluate(t, m, options, rtt_ms, params, scale, P, nullptr, 0, nullptr, outputs, workspace, workspace_bytes, hip_stream);
 }
 
-int gorgo_eval_population_sections(const gorgo_trace* t, const gorgo_model* m, const double* rtt_ms, const double* params,
+int gorgo_eval_population_sections(const gorgo_trace* t, const gorgo_model* m, const gorgo_options* options,
+        const double* rtt_ms, const double* params,
                                    const double* scale, int32_t P, const gorgo_outputs* outputs, void* workspace,
                                    size_t workspace_bytes, void* hip_stream, uint64_t* sections) {
     clear_error();
     if (!sections) return fail(GORGO_ERR_INVALID_ARG, "sections is NULL");
-    return evaluate(t, m, rtt_ms, params, scale, P, nullptr, 0, nullptr, outputs, workspace, workspace_bytes, hip_stream,
+    return evaluate(t, m, options, rtt_ms, params, scale, P, nullptr, 0, nullptr, outputs, workspace, workspace_bytes, hip_stream,
                     nullptr, nullptr, reinterpret_cast<unsigned long long*>(sections));
 }
 
@@ -381,7 +384,8 @@ int gorgo_trace_to_device(const gorgo_trace* t) {
     return upload_trace(t);
 }
 
-int gorgo_eval_population_static(const gorgo_trace* t, const gorgo_model* m, const double* rtt_ms, const double* params,
+int gorgo_eval_population_static(const gorgo_trace* t, const gorgo_model* m, const gorgo_options* options,
+        const double* rtt_ms, const double* params,
                                  const double* scale, int32_t P, const gorgo_outputs* outputs, void* hip_stream) {
     clear_error();
     int rc = check_model(t, m);
@@ -390,7 +394,7 @@ int gorgo_eval_population_static(const gorgo_trace* t, const gorgo_model* m, con
         return fail(GORGO_ERR_INVALID_ARG, "the trace is not resident on the current device: call gorgo_trace_to_device "
                                            "(which allocates) once beforehand");
     Plan pl;
-    if ((rc = make_plan(t, m, P, outputs, &pl))) return rc;
+    if ((rc = make_plan(t, m, options, P, outputs, &pl))) return rc;
     void* scratch = nullptr;
     size_t have = 0;
     if ((rc = static_scratch(&scratch, &have))) return rc;
@@ -399,7 +403,7 @@ int gorgo_eval_population_static(const gorgo_trace* t, const gorgo_model* m, con
                                          "library's static scratch holds " + std::to_string(have) +
                                          " (GORGO_STATIC_SCRATCH_BYTES): use gorgo_eval_population with a caller workspace");
     set_event_marks(false);       // no event is created or recorded on this path
-    rc = evaluate(t, m, rtt_ms, params, scale, P, nullptr, 0, nullptr, outputs, scratch, have, hip_stream);
+    rc = evaluate(t, m, options, rtt_ms, params, scale, P, nullptr, 0, nullptr, outputs, scratch, have, hip_stream);
     set_event_marks(true);
     return rc;
 }
@@ -409,15 +413,17 @@ int64_t gorgo_online_steps(int64_t N, int32_t window, int32_t hop) {
     return N >= window ? (N - window) / hop + 1 : 0;
 }
 
-int gorgo_eval_online(const gorgo_trace* t, const gorgo_model* m, const double* rtt_ms, const double* theta0,
+int gorgo_eval_online(const gorgo_trace* t, const gorgo_model* m, const gorgo_options* options,
+        const double* rtt_ms, const double* theta0,
                       const double* scale, int32_t P, const gorgo_online* online, const gorgo_outputs* outputs,
                       void* workspace, size_t workspace_bytes, void* hip_stream) {
     clear_error();
     if (!online) return fail(GORGO_ERR_INVALID_ARG, "online is NULL");
-    return evaluate(t, m, rtt_ms, theta0, scale, P, online, 0, nullptr, outputs, workspace, workspace_bytes, hip_stream);
+    return evaluate(t, m, options, rtt_ms, theta0, scale, P, online, 0, nullptr, outputs, workspace, workspace_bytes, hip_stream);
 }
 
-int gorgo_eval_policy(const gorgo_trace* t, const gorgo_model* m, const double* rtt_ms, int32_t policy,
+int gorgo_eval_policy(const gorgo_trace* t, const gorgo_model* m, const gorgo_options* options,
+        const double* rtt_ms, int32_t policy,
                       const uint64_t* seeds, const double* scale, int32_t P, const gorgo_outputs* outputs,
                       void* workspace, size_t workspace_bytes, void* hip_stream) {
     clear_error();
@@ -428,11 +434,12 @@ int gorgo_eval_policy(const gorgo_trace* t, const gorgo_model* m, const double* 
     if (policy == GORGO_POLICY_RANDOM && !seeds) return fail(GORGO_ERR_INVALID_ARG, "seeds is NULL");
     if (P < 1 || P > (1 << 20)) return fail(GORGO_ERR_INVALID_ARG, "P must be in 1..2^20");
     const std::vector<double> zero(3 * (size_t)P, 0.0);       // the weights play no part
-    return evaluate(t, m, rtt_ms, zero.data(), scale, P, nullptr, policy, seeds, outputs, workspace, workspace_bytes,
+    return evaluate(t, m, options, rtt_ms, zero.data(), scale, P, nullptr, policy, seeds, outputs, workspace, workspace_bytes,
                     hip_stream);
 }
 
-int gorgo_eval_engine(const gorgo_trace* t, const gorgo_model* m, const gorgo_engine* engine, const double* rtt_ms,
+int gorgo_eval_engine(const gorgo_trace* t, const gorgo_model* m, const gorgo_options* options,
+        const gorgo_engine* engine, const double* rtt_ms,
                       int32_t policy, const double* params, const uint64_t* seeds, const gorgo_online* online,
                       const double* scale, int32_t P, const gorgo_outputs* outputs, void* workspace,
                       size_t workspace_bytes, void* hip_stream) {
@@ -441,23 +448,24 @@ int gorgo_eval_engine(const gorgo_trace* t, const gorgo_model* m, const gorgo_en
     if (policy < GORGO_POLICY_COST_MODEL || policy > GORGO_POLICY_RANDOM)
         return fail(GORGO_ERR_INVALID_ARG, "policy must be 0 (cost model) .. 3 (random)");
     if (policy == GORGO_POLICY_COST_MODEL)
-        return evaluate(t, m, rtt_ms, params, scale, P, online, 0, nullptr, outputs, workspace, workspace_bytes,
+        return evaluate(t, m, options, rtt_ms, params, scale, P, online, 0, nullptr, outputs, workspace, workspace_bytes,
                         hip_stream, engine);
     if (online) return fail(GORGO_ERR_INVALID_ARG, "the online tuner tunes the cost model: policy must be 0");
     if (policy == GORGO_POLICY_RANDOM && !seeds) return fail(GORGO_ERR_INVALID_ARG, "seeds is NULL");
     if (P < 1 || P > (1 << 20)) return fail(GORGO_ERR_INVALID_ARG, "P must be in 1..2^20");
     const std::vector<double> zero(3 * (size_t)P, 0.0);       // the weights play no part
-    return evaluate(t, m, rtt_ms, zero.data(), scale, P, nullptr, policy, seeds, outputs, workspace, workspace_bytes,
+    return evaluate(t, m, options, rtt_ms, zero.data(), scale, P, nullptr, policy, seeds, outputs, workspace, workspace_bytes,
                     hip_stream, engine);
 }
 
-int gorgo_eval_proxy(const gorgo_trace* t, const gorgo_model* m, const gorgo_proxy* proxy, const gorgo_engine* engine,
+int gorgo_eval_proxy(const gorgo_trace* t, const gorgo_model* m, const gorgo_options* options,
+        const gorgo_proxy* proxy, const gorgo_engine* engine,
                      const double* params, const gorgo_online* online, const double* scale, int32_t P,
                      const gorgo_outputs* outputs, void* workspace, size_t workspace_bytes, void* hip_stream) {
     clear_error();
     if (!proxy) return fail(GORGO_ERR_INVALID_ARG, "proxy is NULL");
     if (!m) return fail(GORGO_ERR_INVALID_ARG, "model is NULL");
-    return evaluate(t, m, proxy->rtt_true_ms, params, scale, P, online, 0, nullptr, outputs, workspace, workspace_bytes,
+    return evaluate(t, m, options, proxy->rtt_true_ms, params, scale, P, online, 0, nullptr, outputs, workspace, workspace_bytes,
                     hip_stream, engine, proxy);
 }
 
@@ -466,7 +474,8 @@ int gorgo_last_eval_kernel_ms(double* fill_ms, double* replay_ms, double* select
     return last_eval_kernel_ms(fill_ms, replay_ms, select_ms);
 }
 
-int gorgo_es_workspace_bytes(const gorgo_trace* t, const gorgo_model* m, int32_t P, size_t* bytes) {
+int gorgo_es_workspace_bytes(const gorgo_trace* t, const gorgo_model* m, const gorgo_options* options, int32_t P,
+                             size_t* bytes) {
     clear_error();
     if (!bytes) return fail(GORGO_ERR_INVALID_ARG, "bytes is NULL");
     int rc = check_model(t, m);
@@ -475,19 +484,20 @@ int gorgo_es_workspace_bytes(const gorgo_trace* t, const gorgo_model* m, int32_t
     std::memset(&o, 0, sizeof o);
     o.p95_ttft_ms = reinterpret_cast<double*>(256);   // only which outputs are wanted matters for sizing
     Plan pl;
-    rc = make_plan(t, m, P, &o, &pl);
+    rc = make_plan(t, m, options, P, &o, &pl);
     if (rc) return rc;
     *bytes = pl.total + up256(sizeof(double) * (size_t)P);
     return GORGO_OK;
 }
 
-int gorgo_es_step(const gorgo_trace* t, const gorgo_model* m, const double* rtt_ms, double scale, int32_t P,
+int gorgo_es_step(const gorgo_trace* t, const gorgo_model* m, const gorgo_options* options,
+        const double* rtt_ms, double scale, int32_t P,
                   gorgo_es_state* inout, double* params_out, double* fitness_out, void* workspace,
                   size_t workspace_bytes, void* hip_stream) {
     clear_error();
     if (!inout) return fail(GORGO_ERR_INVALID_ARG, "state is NULL");
     size_t need = 0;
-    int rc = gorgo_es_workspace_bytes(t, m, P, &need);
+    int rc = gorgo_es_workspace_bytes(t, m, options, P, &need);
     if (rc) return rc;
     if (!workspace) return fail(GORGO_ERR_WORKSPACE, "workspace is NULL");
     if (workspace_bytes < need)
@@ -501,7 +511,7 @@ int gorgo_es_step(const gorgo_trace* t, const gorgo_model* m, const double* rtt_
     gorgo_outputs o;
     std::memset(&o, 0, sizeof o);
     o.p95_ttft_ms = d_fit;
-    rc = gorgo_eval_population(t, m, rtt_ms, params.data(), sc.data(), P, &o, workspace, need - fit_bytes, hip_stream);
+    rc = gorgo_eval_population(t, m, options, rtt_ms, params.data(), sc.data(), P, &o, workspace, need - fit_bytes, hip_stream);
     if (rc) return rc;
     if ((rc = copy_small_to_host_sync(fit.data(), d_fit, sizeof(double) * (size_t)P, hip_stream))) return rc;
     if ((rc = gorgo_es_update(params.data(), fit.data(), P, inout))) return rc;

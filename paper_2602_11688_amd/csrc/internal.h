@@ -71,6 +71,8 @@ struct Plan {
     int64_t cap = 0;                 // slots per (replay, replica) table, power of two
     int32_t block_tokens = 0;
     double a_pf = 0, a_dec = 0;
+    int32_t packing = 2;             // gorgo_options::replay_packing of the call
+    int32_t poll_limit = 1 << 24;    // gorgo_options::handover_poll_limit of the call
     // workspace carve-up (byte offsets from the workspace base)
     size_t off_tables = 0, off_spare = 0, off_rec = 0, off_route = 0, off_ttft = 0, off_e2e = 0, off_small = 0;
     size_t total = 0;
@@ -116,8 +118,6 @@ struct ProxyLaunch {
 };
 
 // kernels.hip
-void set_handover_poll_limit(int32_t polls);
-void set_replay_packing(int32_t mode);
 bool pack_replays(const Plan& pl, int64_t rows);     // rows of one replay: its segments + 2
 int launch_replay(const gorgo_trace* t, const Plan& pl, const double* d_rtt, const double* d_params,
                   const double* d_scale, uint8_t* route, uint16_t* hit, double* ttft, double* e2e,

@@ -490,15 +490,11 @@ int copy_small_to_device(void* dst, const void* src, size_t bytes, void* stream)
     return e == hipSuccess ? GORGO_OK : hip_fail(e, "hipMemcpyAsync(H2D)");
 }
 
-std::atomic<int32_t> g_packing{2};      // 0 never, 1 whenever the shape allows, 2 when the replays would not all be resident
-std::atomic<int32_t> g_poll_limit{SEG_SPIN_LIMIT};
-void set_replay_packing(int32_t mode) { g_packing.store(mode); }
-
 // Whether a launch of fixed-weight replays runs two replays per wavefront pair.  A replay is a serial chain whose
 // duration does not depend on how many others run beside it, and a packed pair takes a few percent longer per
 // request than a lone replay: packing pays exactly when the replays would not all be resident at once otherwise.
 bool pack_replays(const Plan& pl, int64_t rows) {
-    const int32_t mode = g_packing.load();
+    const int32_t mode = pl.packing;       // 0 never, 1 whenever the shape allows, 2 when the replays would not all be resident
     if (mode == 0 || pl.R > HALF || pl.B > 16 || pl.P % 2 != 0 ||
         2ull * (uint64_t)rows * (uint64_t)pl.R * 4u >= (1ull << 32))
         return false;
@@ -511,8 +507,6 @@ bool pack_replays(const Plan& pl, int64_t rows) {
         return false;
     return (int64_t)pl.P > (int64_t)cus * per_cu;
 }
-
-void set_handover_poll_limit(int32_t polls) { g_poll_limit.store(polls); }
 
 int wait_for_copies(void* stream) {
     hipError_t e = hipStreamSynchronize(static_cast<hipStream_t>(stream));
@@ -614,7 +608,7 @@ int launch_replay(const gorgo_trace* t, const Plan& pl, const double* d_rtt, con
         a.accepted = nullptr;
         a.first_hash = t->dev.first_hash;
         a.seeds = policy ? policy->seeds : nullptr;
-        a.spin_limit = g_poll_limit.load();     // (only the packed kernel still polls)
+        a.spin_limit = pl.poll_limit;           // (only the packed kernel polls)
         a.eng_a_pf = engine ? engine->a_pf : nullptr;
         a.eng_a_dec = engine ? engine->a_dec : nullptr;
         a.eng_budget = engine ? engine->budget : nullptr;

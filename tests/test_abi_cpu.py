@@ -100,6 +100,15 @@ def test_model_validation_without_gpu():
         assert e.value.code == code
     with pytest.raises(g.GorgoError):
         g.workspace_bytes(t, ok, 0)
+    # tokens of a cached prefix (block_tokens * blocks, blocks < 2^16) are counted in 32 bits: block sizes beyond
+    # 32767 tokens are refused, the largest allowed one is accepted
+    tr = tg.config(1, 100).trace
+    big = g.Trace.from_arrays(tr.ts_ms, tr.in_len, tr.out_len, tr.blk_off, tr.hash_ids, block_tokens=32767)
+    assert g.workspace_bytes(big, g.Model(4, 8, 0, 0.05, 20.0, block_tokens=32767), 16) > 0
+    too_big = g.Trace.from_arrays(tr.ts_ms, tr.in_len, tr.out_len, tr.blk_off, tr.hash_ids, block_tokens=32768)
+    with pytest.raises(g.GorgoError) as e:
+        g.workspace_bytes(too_big, g.Model(4, 8, 0, 0.05, 20.0, block_tokens=32768), 16)
+    assert e.value.code == -1 and "32767" in str(e.value)
 
 
 def test_eval_rejects_bad_arguments_before_touching_a_device():
@@ -112,7 +121,7 @@ def test_eval_rejects_bad_arguments_before_touching_a_device():
     o = gb._Outputs()
 
     def call(rtt=rtt, par=par, sc=sc, ws=C.c_void_p(256), nbytes=1 << 40):
-        return L.gorgo_eval_population(t._h, C.byref(m), gb._ptr(rtt), gb._ptr(par), gb._ptr(sc), 2, C.byref(o), ws,
+        return L.gorgo_eval_population(t._h, C.byref(m), None, gb._ptr(rtt), gb._ptr(par), gb._ptr(sc), 2, C.byref(o), ws,
                                        nbytes, None)
     assert call(rtt=np.array([10.0, np.inf, 1, 1])) == -6
     assert call(par=np.array([[1, 1, np.nan], [1, 1, 1]])) == -6
@@ -124,12 +133,51 @@ def test_eval_rejects_bad_arguments_before_touching_a_device():
     assert b"workspace" in L.gorgo_last_error()
 
 
-def test_settings_validate_their_arguments():
+def test_options_are_per_call_and_validated():
+    """The library keeps no settings: options travel with each call (NULL = defaults) and are checked there."""
     L = g.lib()
-    assert L.gorgo_set_replay_packing(3) == -1 and L.gorgo_set_replay_packing(-1) == -1
-    assert L.gorgo_set_replay_packing(0) == 0 and L.gorgo_set_replay_packing(1) == 0 and L.gorgo_set_replay_packing(2) == 0
-    assert L.gorgo_set_handover_poll_limit(-1) == -1 and L.gorgo_set_handover_poll_limit(1 << 24) == 0
-    assert L.gorgo_set_replay_path(3) == -1 and L.gorgo_set_replay_path(0) == 0
+    for name in ("gorgo_set_replay_path", "gorgo_set_replay_packing", "gorgo_set_handover_poll_limit",
+                 "gorgo_set_table_factor_percent"):
+        assert not hasattr(L, name)
+    d = g.Options()
+    L.gorgo_options_default(C.byref(d))
+    assert (d.replay_path, d.replay_packing, d.handover_poll_limit, d.table_factor_percent) == (0, 2, 1 << 24, 200)
+    wl = tg.config(1)
+    t = g.Trace.from_arrays(wl.trace.ts_ms, wl.trace.in_len, wl.trace.out_len, wl.trace.blk_off, wl.trace.hash_ids)
+    m = g.Model(wl.R, wl.batch, wl.cache_blocks, wl.prefill_ms_per_token, wl.decode_ms_per_token).c()
+    path, n = C.c_int32(), C.c_size_t()
+
+    def query(**kw):
+        o = g.Options(0, 2, 1 << 24, 200)
+        for k, v in kw.items():
+            setattr(o, k, v)
+        return L.gorgo_query_replay_path(t._h, C.byref(o), C.byref(path), None, None)
+    assert query() == 0 and path.value == 2
+    assert query(replay_path=1) == 0 and path.value == 1
+    for bad in (dict(replay_path=3), dict(replay_path=-1), dict(replay_packing=3), dict(replay_packing=-1),
+                dict(handover_poll_limit=-1), dict(table_factor_percent=109), dict(table_factor_percent=1601)):
+        assert query(**bad) == -1 and b"options." in L.gorgo_last_error()
+        o = g.Options(0, 2, 1 << 24, 200)
+        for k, v in bad.items():
+            setattr(o, k, v)
+        assert L.gorgo_workspace_bytes(t._h, C.byref(m), C.byref(o), 4, None, C.byref(n)) == -1
+    # two calls with different options do not influence each other: the workspace follows the call's own options
+    sizes = {}
+    for rp in (1, 2, 1):
+        o = g.Options(rp, 2, 1 << 24, 200)
+        assert L.gorgo_workspace_bytes(t._h, C.byref(m), C.byref(o), 4, None, C.byref(n)) == 0
+        sizes.setdefault(rp, set()).add(n.value)
+    assert len(sizes[1]) == 1 and sizes[1] != sizes[2]
+    assert L.gorgo_workspace_bytes(t._h, C.byref(m), None, 4, None, C.byref(n)) == 0 and {n.value} == sizes[2]
+    # the binding's own defaults object is what its set_* helpers change
+    g.set_replay_path(1)
+    try:
+        assert g.default_options().replay_path == 1 and t.replay_path()["path"] == 1
+        with pytest.raises(g.GorgoError):
+            g.set_replay_path(3)
+    finally:
+        g.set_replay_path(0)
+    assert t.replay_path()["path"] == 2
 
 
 def test_online_and_policy_entry_points_reject_bad_arguments_before_touching_a_device():
@@ -145,7 +193,7 @@ def test_online_and_policy_entry_points_reject_bad_arguments_before_touching_a_d
 
     def online(window=128, hop=32, lo=(0.05, 1.0, 0.05), hi=(2.0, 1.0, 0.5), sigma0=0.5, z=C.c_void_p(256), th=th):
         on = gb._Online(window, hop, (C.c_double * 3)(*lo), (C.c_double * 3)(*hi), sigma0, z, None, None, None, None, None)
-        return L.gorgo_eval_online(t._h, C.byref(m), gb._ptr(rtt), gb._ptr(th), gb._ptr(sc), 2, C.byref(on), C.byref(o),
+        return L.gorgo_eval_online(t._h, C.byref(m), None, gb._ptr(rtt), gb._ptr(th), gb._ptr(sc), 2, C.byref(on), C.byref(o),
                                    None, 1 << 40, None)
     assert online(window=0) == -1 and online(window=2048) == -1 and online(hop=0) == -1
     assert online(z=None) == -1
@@ -153,17 +201,17 @@ def test_online_and_policy_entry_points_reject_bad_arguments_before_touching_a_d
     assert online(sigma0=float("nan")) == -6
     assert online(th=np.tile([5.0, 1.0, 0.1], (2, 1))) == -1          # theta0 outside [lo, hi]
     assert online() == -7                                             # everything valid up to the workspace
-    assert L.gorgo_eval_online(t._h, C.byref(m), gb._ptr(rtt), gb._ptr(th), gb._ptr(sc), 2, None, C.byref(o), None, 0,
+    assert L.gorgo_eval_online(t._h, C.byref(m), None, gb._ptr(rtt), gb._ptr(th), gb._ptr(sc), 2, None, C.byref(o), None, 0,
                                None) == -1
 
     def policy(pol, seeds=None):
-        return L.gorgo_eval_policy(t._h, C.byref(m), gb._ptr(rtt), pol, seeds, gb._ptr(sc), 2, C.byref(o), None,
+        return L.gorgo_eval_policy(t._h, C.byref(m), None, gb._ptr(rtt), pol, seeds, gb._ptr(sc), 2, C.byref(o), None,
                                    1 << 40, None)
     assert policy(0) == -1 and policy(4) == -1 and policy(3) == -1    # random without seeds
     assert policy(1) == -7 and policy(3, gb._ptr(np.array([1, 2], np.uint64))) == -7
     bad = _trace(tg.random_small(3, 50, 2, consistent=False))
     mb = g.Model(2, 2, 0, 0.05, 20.0).c()
-    assert L.gorgo_eval_policy(bad._h, C.byref(mb), gb._ptr(rtt[:2]), 1, None, gb._ptr(sc), 2, C.byref(o), None, 1 << 40,
+    assert L.gorgo_eval_policy(bad._h, C.byref(mb), None, gb._ptr(rtt[:2]), 1, None, gb._ptr(sc), 2, C.byref(o), None, 1 << 40,
                                None) == -1                            # needs a chain-consistent trace
 
 
@@ -179,7 +227,7 @@ def test_engine_entry_point_rejects_bad_arguments_before_touching_a_device():
 
     def engine(pf=ok_pf, dec=ok_dec, kv=None, slow=0.1, policy=0, par=par, seeds=None, online=None, null=False, tr=t, mm=m):
         e = gb._Engine(gb._ptr(pf), gb._ptr(dec), gb._ptr(kv), slow)
-        return L.gorgo_eval_engine(tr._h, C.byref(mm), None if null else C.byref(e), gb._ptr(rtt), policy, gb._ptr(par),
+        return L.gorgo_eval_engine(tr._h, C.byref(mm), None, None if null else C.byref(e), gb._ptr(rtt), policy, gb._ptr(par),
                                    seeds, online, gb._ptr(sc), 2, C.byref(o), None, 1 << 40, None)
     assert engine(null=True) == -1 and engine(pf=None) == -1 and engine(dec=None) == -1
     assert engine(pf=np.array([0.05, np.nan, 0.05, 0.05])) == -6 and engine(dec=np.array([20.0, -1.0, 20.0, 20.0])) == -6
@@ -210,7 +258,7 @@ def test_proxy_entry_point_rejects_bad_arguments_before_touching_a_device():
 
     def proxy(rt=ok, epochs=3, probe=30000, alpha=0.5, index=0, tables=C.c_void_p(256), null=False, par=par, tr=t, mm=m):
         x = gb._Proxy(epochs, probe, gb._ptr(rt), alpha, index, tables, None)
-        return L.gorgo_eval_proxy(tr._h, C.byref(mm), None if null else C.byref(x), None, gb._ptr(par), None, gb._ptr(sc), 2,
+        return L.gorgo_eval_proxy(tr._h, C.byref(mm), None, None if null else C.byref(x), None, gb._ptr(par), None, gb._ptr(sc), 2,
                                   C.byref(o), None, 1 << 40, None)
     assert proxy(null=True) == -1 and proxy(rt=None) == -1 and proxy(tables=None) == -1
     assert proxy(epochs=0) == -1 and proxy(epochs=1 << 20) == -1 and proxy(probe=0) == -1 and proxy(index=-2) == -1

@@ -50,7 +50,7 @@ def test_static_scratch_entry_point_refuses_what_does_not_fit_and_a_trace_that_i
     p95 = torch.empty((P,), dtype=torch.float64, device="cuda:0")
     o = binding._outputs_struct(p95_ttft_ms=p95)
     # not resident yet: no evaluation and no gorgo_trace_to_device has run on this handle
-    rc = L.gorgo_eval_population_static(tr._h, C.byref(m), binding._ptr(rtt), binding._ptr(par), binding._ptr(sc), P,
+    rc = L.gorgo_eval_population_static(tr._h, C.byref(m), None, binding._ptr(rtt), binding._ptr(par), binding._ptr(sc), P,
                                         C.byref(o), None)
     assert rc == -1 and b"resident" in L.gorgo_last_error()
     assert L.gorgo_trace_to_device(tr._h) == 0
@@ -60,6 +60,6 @@ def test_static_scratch_entry_point_refuses_what_does_not_fit_and_a_trace_that_i
     p95b = torch.empty((big,), dtype=torch.float64, device="cuda:0")
     ob = binding._outputs_struct(p95_ttft_ms=p95b)
     assert g.workspace_bytes(tr, model, big) > binding.STATIC_SCRATCH_BYTES
-    rc = L.gorgo_eval_population_static(tr._h, C.byref(m), binding._ptr(rtt), binding._ptr(parb), binding._ptr(scb), big,
+    rc = L.gorgo_eval_population_static(tr._h, C.byref(m), None, binding._ptr(rtt), binding._ptr(parb), binding._ptr(scb), big,
                                         C.byref(ob), None)
     assert rc == -7 and b"static scratch" in L.gorgo_last_error()
