@@ -391,6 +391,13 @@ int gorgo_eval_population_sections(const gorgo_trace* t, const gorgo_model* m, c
 int gorgo_query_replay_packing(const gorgo_trace* t, const gorgo_model* m, const gorgo_options* options, int32_t P,
                                int32_t* packed);
 
+/* Rows of cells that a replay of this trace keeps in the segment formulation (0 for a trace that is not
+ * chain-consistent).  A segment only needs a row from the first to the last request that references it, which the
+ * trace fixes for every candidate alike, so the loader lets segments share rows: a segment takes a row slot at its
+ * first reference and hands it on after its last.  The number is the most segments in use at one time (plus none of
+ * the two rows the kernel adds for its own use); it replaces the number of segments in the workspace size. */
+int gorgo_query_row_slots(const gorgo_trace* t, int64_t* slots);
+
 /* Formulation that an evaluation of this trace would use under these options (1 or 2, see gorgo_options), the number
  * of segments of the trace and the total number of (request, segment) references; the last two are 0 for a
  * trace that is not chain-consistent.  Each out pointer may be NULL. */

@@ -108,6 +108,8 @@ def lib():
         L.gorgo_es_step.argtypes = [vp, C.POINTER(_Model), C.POINTER(Options), vp, dbl, i32, C.POINTER(EsState), vp, vp, vp, C.c_size_t, vp]
         L.gorgo_query_replay_packing.argtypes = [vp, C.POINTER(_Model), C.POINTER(Options), i32, C.POINTER(i32)]
         L.gorgo_query_replay_path.argtypes = [vp, C.POINTER(Options), C.POINTER(i32), C.POINTER(i64), C.POINTER(i64)]
+        L.gorgo_query_row_slots.argtypes = [vp, C.POINTER(i64)]
+        L.gorgo_query_row_slots.restype = C.c_int
         L.gorgo_options_default.argtypes = [C.POINTER(Options)]
         L.gorgo_options_default.restype = None
         L.gorgo_last_eval_kernel_ms.argtypes = [C.POINTER(dbl)] * 3
@@ -183,6 +185,12 @@ class Trace:
         p, ns, nr = C.c_int32(), C.c_int64(), C.c_int64()
         _check(lib().gorgo_query_replay_path(self._h, _opt(options), C.byref(p), C.byref(ns), C.byref(nr)))
         return dict(path=p.value, n_segments=ns.value, segment_refs=nr.value)
+
+    def row_slots(self) -> int:
+        """Rows of cells a replay keeps in the segment formulation: the most segments in use at one time."""
+        n = C.c_int64()
+        _check(lib().gorgo_query_row_slots(self._h, C.byref(n)))
+        return n.value
 
     @property
     def N(self) -> int:

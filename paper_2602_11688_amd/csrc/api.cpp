@@ -80,7 +80,7 @@ int make_plan(const gorgo_trace* t, const gorgo_model* m, const gorgo_options* o
     if (opt.replay_path == PATH_SEGMENTS && !t->chain_consistent)
         return fail(GORGO_ERR_INVALID_ARG, "the segment formulation needs a chain-consistent trace");
     pl->path = path_for(t, opt.replay_path);
-    pl->nseg = t->n_segments;
+    pl->nseg = t->n_slots;           // rows: segments share them, see the loader
     if (pl->path == PATH_SEGMENTS && (uint64_t)(pl->nseg + 2) * (uint64_t)m->R * 4u >= (1ull << 32))
         return fail(GORGO_ERR_INVALID_ARG, "segment rows of one replay exceed 4 GiB; use the block-table formulation");
     // A table must hold the cached blocks plus the blocks of the request being inserted, with room to
@@ -143,6 +143,14 @@ int gorgo_query_replay_packing(const gorgo_trace* t, const gorgo_model* m, const
     rc = make_plan(t, m, options, P, nullptr, &pl);
     if (rc) return rc;
     *packed = pl.path == PATH_SEGMENTS && pack_replays(pl, pl.nseg + 2) ? 1 : 0;
+    return GORGO_OK;
+}
+
+int gorgo_query_row_slots(const gorgo_trace* t, int64_t* slots) {
+    clear_error();
+    if (!t) return fail(GORGO_ERR_INVALID_ARG, "trace is NULL");
+    if (!slots) return fail(GORGO_ERR_INVALID_ARG, "slots is NULL");
+    *slots = t->n_slots;
     return GORGO_OK;
 }
 

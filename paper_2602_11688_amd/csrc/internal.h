@@ -16,9 +16,11 @@ void clear_error();
 // One segment of a request's block list: segment id and the number of the request's blocks up to and
 // including this segment.
 struct SegRef {
-    int32_t id;
-    int32_t end;
+    int32_t id;       // in the loaded trace: the row slot the segment occupies while it is referenced
+    int32_t end;      // | SEG_FRESH where this is the segment's first reference (its row slot starts over there)
 };
+constexpr int32_t SEG_FRESH = 1 << 30;
+constexpr int32_t SEG_END_MASK = 0xFFFF;     // (a request has fewer than 2^16 blocks)
 
 // Device-resident copy of a trace (filled lazily by the first evaluation).
 struct DeviceTrace {
@@ -55,6 +57,7 @@ struct gorgo_trace {
     std::vector<int64_t> seg_off;    // chain-consistent traces: request -> its segments
     std::vector<gorgo::SegRef> seg;
     int64_t n_segments = 0;
+    int64_t n_slots = 0;             // rows a replay needs: the most segments in use at one time
     gorgo::DeviceTrace dev;
 };
 

@@ -629,12 +629,9 @@ int launch_replay(const gorgo_trace* t, const Plan& pl, const double* d_rtt, con
                                proxy->alpha);
             if ((e = hipGetLastError()) != hipSuccess) return hip_fail(e, "launch smooth_rtt");
         }
-        const size_t cells = (size_t)pl.P * (size_t)a.nseg * pl.R;
-        if (cells) {
-            size_t blocks = (cells + 255) / 256;
-            if (blocks > 65536) blocks = 65536;
-            hipLaunchKernelGGL(fill_i32, dim3((unsigned)blocks), dim3(256), 0, s, a.last, cells, (int32_t)-1);
-            if ((e = hipGetLastError()) != hipSuccess) return hip_fail(e, "launch fill_i32");
+        // (a row is written through before it is first read -- the request that brings a segment into a row slot
+        // resets the row -- so only the never-cached row needs a value beforehand)
+        if (pl.P > 0) {
             hipLaunchKernelGGL(fill_last_rows, dim3((unsigned)(((size_t)pl.P * pl.R + 255) / 256)), dim3(256), 0, s, a.last,
                                pl.P, a.nseg, pl.R, NEVER_CACHED);
             if ((e = hipGetLastError()) != hipSuccess) return hip_fail(e, "launch fill_last_rows");

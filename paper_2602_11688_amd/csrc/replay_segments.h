@@ -227,6 +227,7 @@ struct RowSet {
     int32_t cell[SEG_CHUNK];
     int end[SEG_CHUNK];
     SegRef of_lane;
+    int fresh;           // bit k: segment k's row slot starts over with this request (SEG_FRESH)
 };
 
 // Cached blocks of one segment [pos, end) whose row cell holds rl, against a cursor (c_r, c_k): all of them
@@ -247,14 +248,27 @@ struct SegEnt {
     int32_t end;         // blocks of the request up to and including this segment
 };
 struct SegDesc {
-    SegEnt e[8];         // first eight segments; past the last one: the never-cached row, n
+    SegEnt e[8];         // first eight segments, as the match reads them: where to load the row from and where the
+                         // segment ends.  Past the last segment: the never-cached row, n.  Also the never-cached row for
+                         // a segment whose row slot starts over with this request (SEG_FRESH: what the slot still holds
+                         // belongs to a segment of the past), and for one whose slot started over with the previous
+                         // request (this request's rows are loaded before that request's stores)
     int32_t L, n, s;     // input tokens, blocks, segments
-    int32_t flags;       // DESC_MORE4 | DESC_DEEP | leading segments shared with the previous request << 8
+    int32_t flags;       // DESC_MORE4 | DESC_DEEP | leading segments shared with the previous request << 8 |
+                         // index of the first fresh segment among the first eight (8: none) << 16
     int64_t j0;          // index of the request's first segment reference (for requests of more than 8 segments)
     int32_t target;      // replica dictated by the session-affinity / random policy
     int32_t pad;
+    uint32_t slot[8];    // where the rows of the first eight segments really are (past the last one: the spare row)
+    uint32_t store[WAVE];   // per lane of the cache wavefront: the row its store after the decision goes to.  Lanes
+                         // 0..31: the row of segment (lane mod 8), where this request's number is written into the
+                         // chosen replica's cell.  Lanes 32..63, with at most 32 replicas: the row of the request's
+                         // last segment if that one is fresh (replica lane - 32 of that row starts over), else, like
+                         // every lane with nothing to store, the spare row
 };
-static_assert(sizeof(SegDesc) == 96, "descriptor layout");
+static_assert(sizeof(SegDesc) == 128 + 4 * WAVE, "descriptor layout");
+constexpr int DESC_FRESH_TAIL = 4;   // the request's last segment is fresh and among the first eight (lanes 32..63 reset its row)
+constexpr int DESC_FRESH_MORE = 8;   // further fresh segments among the first eight
 constexpr int DESC_RING = 8;         // descriptors in flight (power of two)
 constexpr int DESC_AHEAD = 3;        // the front end reads references this many requests ahead
 constexpr int DESC_MORE4 = 1;        // more than four segments
@@ -356,9 +370,11 @@ __device__ __forceinline__ void front_wave(const SegArgs& a, int p, int lane, Ha
     load_batch(WAVE, nxt);
     const uint32_t row_bytes = (uint32_t)R * 4u;
     const uint32_t never_off = (uint32_t)(a.nseg - 2) * row_bytes;      // the extra row that no request touches
+    const uint32_t spare_off = (uint32_t)(a.nseg - 1) * row_bytes;      // the row that nothing reads
     int pend_id = 0, pend_end = 0, pend_s = 0, pend_L = 0, pend_target = 0;
     int64_t pend_j0 = 0;
     int prev_id = 0, prev_end = 0, prev_s = 0;
+    bool prev_fresh = false;
     // request j's references are requested ... (j in this batch or the next)
     auto fe_issue = [&](int64_t j) {
         const int jj = (int)(j - b0);
@@ -379,33 +395,52 @@ __device__ __forceinline__ void front_wave(const SegArgs& a, int p, int lane, Ha
         SegRef ref{0, 0};
         if (on) ref = a.seg[pend_j0 + k];
         pend_id = ref.id;
-        pend_end = ref.end;
+        pend_end = ref.end;       // (with the SEG_FRESH mark)
     };
     // ... and one request later its descriptor is written
     auto fe_commit = [&](int64_t j) {
         const int s = pend_s;
-        const int n = s > 0 ? __builtin_amdgcn_readlane(pend_end, 8) : 0;
+        const bool fresh = (pend_end & SEG_FRESH) != 0;
+        const int my_end = pend_end & SEG_END_MASK;
+        const int n = s > 0 ? __builtin_amdgcn_readlane(my_end, 8) : 0;
         SegDesc* const d = &comm->ring[j & (DESC_RING - 1)];
         const bool real = lane < s;
-        const uint32_t off = real ? (uint32_t)pend_id * row_bytes : never_off;
-        const int end = real ? pend_end : n;
-        if (lane < 8) d->e[lane] = SegEnt{off, end};
         // leading segments shared with the previous request (same tree, same path so far): the cache wavefront
         // has requested this request's rows before the previous request's stores, and patches exactly these
-        const bool same = lane < 8 && lane < s && lane < prev_s && pend_id == prev_id && pend_end == prev_end;
+        // (a fresh segment may sit in the slot that the previous request's segment at this place just gave up)
+        const bool same = lane < 8 && lane < s && lane < prev_s && !fresh && pend_id == prev_id && my_end == prev_end;
         const unsigned differ = ~(unsigned)ballot(same) | 0x100u;
         const int common = __builtin_ctz(differ);
+        // what the match loads: the segment's row, unless the row starts over now or did with the previous request
+        const bool from_slot = real && !fresh && !(same && prev_fresh);
+        const uint32_t slot_off = (uint32_t)pend_id * row_bytes;
+        const int end = real ? my_end : n;
+        if (lane < 8) {
+            d->e[lane] = SegEnt{from_slot ? slot_off : never_off, end};
+            d->slot[lane] = real ? slot_off : spare_off;
+        }
+        const unsigned fresh8 = (unsigned)ballot(lane < 8 && real && fresh);
+        const int first_fresh = __builtin_ctz(fresh8 | 0x100u);
+        // the store targets of the cache wavefront's lanes: lane 8 here holds the request's last segment
+        const bool tail_fresh = s > 0 && s <= 8 && ((fresh8 >> (s - 1)) & 1u) != 0;
+        const bool narrow = R <= 32;
+        const uint32_t of_seg = (uint32_t)__builtin_amdgcn_ds_bpermute((lane & 7) << 2, (int)(real ? slot_off : spare_off));
+        const uint32_t of_tail = (uint32_t)__builtin_amdgcn_readlane((int)slot_off, 8);
+        d->store[lane] = lane < 32 || !narrow ? of_seg : (tail_fresh && lane - 32 < R ? of_tail : spare_off);
+        const bool fresh_more = narrow ? (fresh8 & ~(tail_fresh ? 1u << (s - 1) : 0u)) != 0 : fresh8 != 0;
         if (lane == 0) {
             d->L = pend_L;
             d->n = n;
             d->s = s;
-            d->flags = (s > 4 ? DESC_MORE4 : 0) | (s > 8 ? DESC_DEEP : 0) | (common << 8);
+            d->flags = (s > 4 ? DESC_MORE4 : 0) | (s > 8 ? DESC_DEEP : 0) | (tail_fresh && narrow ? DESC_FRESH_TAIL : 0) |
+                       (fresh_more ? DESC_FRESH_MORE : 0) | (common << 8) | (first_fresh << 16);
             d->j0 = pend_j0;
             d->target = pend_target;
         }
         prev_id = pend_id;
-        prev_end = pend_end;
+        prev_end = my_end;
         prev_s = s;
+        prev_fresh = fresh;
     };
     fe_issue(0);
     fe_commit(0);
@@ -416,17 +451,20 @@ __device__ __forceinline__ void front_wave(const SegArgs& a, int p, int lane, Ha
     SectionClock<TIMED> clk;
     clk.start();
     for (int64_t r = 0; r < N; ++r) {
-        // in the long stretch between B(r - 1) and A(r), where the cache wavefront reads the descriptor of r + 1
-        fe_commit(r + 2);           // (first read by the cache wavefront after B(r))
+        // in the long stretch between B(r - 1) and A(r), where the cache wavefront reads the descriptor of r + 1:
+        // the descriptor after that (first read by the cache wavefront after B(r))
+        fe_commit(r + 2);
+        clk.tick(0);                                                 // descriptors
+        meet(true);                                                  // A(r)
+        clk.tick(1);                                                 // waiting at A
+        // in the short stretch where the cache wavefront decides: the references of the request after that
         fe_issue(r + 3);
         if (r + 1 - b0 == WAVE) {
             cur = nxt;
             b0 += WAVE;
             load_batch(b0 + WAVE, nxt);
         }
-        clk.tick(0);                                                 // descriptors
-        meet(true);                                                  // A(r)
-        clk.tick(1);                                                 // waiting at A
+        clk.tick(3);                                                 // references
         meet(false);                                                 // B(r)
         clk.tick(2);                                                 // waiting at B
     }
@@ -847,6 +885,9 @@ __device__ __forceinline__ void cache_wave(const SegArgs& a, int p, int lane, Ha
     LogRec* const log = a.log + (size_t)p * (N + 1);
     unsigned long long* const log64 = reinterpret_cast<unsigned long long*>(log);
     unsigned long long* const choice_slot = lane == 0 ? &comm->choice : &comm->unused[lane];
+    // the lanes that reset the row of a fresh last segment (see the store after the decision), and the replica of each
+    const bool reset_lane = R <= 32 && lane >= 32;
+    const int reset_rep = lane - 32 < R ? lane - 32 : R - 1;
 
     // the row loads of one request, from its descriptor: the descriptor is read (LDS) well before the loads go out
     struct DescCopy {
@@ -860,7 +901,7 @@ __device__ __forceinline__ void cache_wave(const SegArgs& a, int p, int lane, Ha
         c.e23 = reinterpret_cast<const int4*>(d->e)[1];
         c.e45 = reinterpret_cast<const int4*>(d->e)[2];
         c.e67 = reinterpret_cast<const int4*>(d->e)[3];
-        c.my_off = d->e[lane & 7].rowoff;
+        c.my_off = d->store[lane];
         return c;
     };
     auto request_rows = [&](const DescCopy& c, RowsOf& w) {
@@ -960,12 +1001,14 @@ __device__ __forceinline__ void cache_wave(const SegArgs& a, int p, int lane, Ha
                     int send[8];
 #pragma unroll
                     for (int k = 0; k < 8; ++k) {
-                        cell[k] = -1;
+                        cell[k] = NEVER_CACHED;
                         send[k] = pos;
                         if (c0 + k < s) {
                             const SegRef sr = a.seg[j0 + c0 + k];
-                            send[k] = sr.end;
-                            if ((PROXY ? open_seen : open) && in) cell[k] = ld(cell_at((uint32_t)sr.id * row_bytes));
+                            send[k] = sr.end & SEG_END_MASK;
+                            // (a fresh segment's row still holds what a segment of the past left there)
+                            if ((PROXY ? open_seen : open) && in && !(sr.end & SEG_FRESH))
+                                cell[k] = ld(cell_at((uint32_t)sr.id * row_bytes));
                         }
                     }
 #pragma unroll
@@ -1066,8 +1109,9 @@ __device__ __forceinline__ void cache_wave(const SegArgs& a, int p, int lane, Ha
             const int cb_k = __builtin_amdgcn_readlane(PROXY ? c2.cur_k : c1.cur_k, best);
             int run_owner = -1, run_end = 0, vpos = 0;
             for (int j = 0; j < s; ++j) {
-                const SegRef sr = a.seg[j0 + j];
-                const int32_t rl = ld(cell_of((uint32_t)sr.id * row_bytes, best));
+                SegRef sr = a.seg[j0 + j];
+                const int32_t rl = sr.end & SEG_FRESH ? NEVER_CACHED : ld(cell_of((uint32_t)sr.id * row_bytes, best));
+                sr.end &= SEG_END_MASK;
                 const int cnt = cached_in(rl, vpos, sr.end, cb_r, cb_k);
                 if (cnt > 0) {
                     if (rl != run_owner) {
@@ -1088,10 +1132,34 @@ __device__ __forceinline__ void cache_wave(const SegArgs& a, int p, int lane, Ha
         clk.tick(5);                                                 // ownership
         // ---- cache update: every segment of the request is now last touched by r on the chosen replica
         // (lane k, and k + 8, ..., store the cell of segment k)
-        st(cell_of((lane & 7) < s ? mine.my_off : spare_row, best), (int32_t)r);
+        // A segment that this request is the first to reference has taken over a row slot from a segment of the
+        // past (the loader hands slots on): the row starts over, every replica's cell, never cached except on the
+        // chosen one.  Fresh segments are the last ones of the path; mostly there is one, or none.  With at most 32
+        // replicas the upper lanes do that in the same store: lane 32 + i writes replica i's cell of the row that the
+        // front end names (the last segment's if it is fresh).  Further fresh segments, and any with more replicas,
+        // take a loop of their own.
+        {
+            const int rep = reset_lane ? reset_rep : best;
+            const int32_t val = reset_lane && rep != best ? NEVER_CACHED : (int32_t)r;
+            st(cell_of(mine.my_off, rep), val);
+        }
+        if (mine.flags & DESC_FRESH_MORE) {
+            const int first_fresh = (mine.flags >> 16) & 15;
+            const int stop = (s < 8 ? s : 8) - ((mine.flags & DESC_FRESH_TAIL) ? 1 : 0);
+            const int32_t fresh_cell = is_best ? (int32_t)r : NEVER_CACHED;
+            for (int k = first_fresh; k < stop; ++k) {
+                const uint32_t off = ld(&dr->slot[k]);
+                st(cell_at(in ? off : spare_row), fresh_cell);
+            }
+        }
         if (mine.flags & DESC_DEEP) {
             const int64_t j0 = dr->j0;
-            for (int j = 8 + lane; j < s; j += WAVE) st(cell_of((uint32_t)a.seg[j0 + j].id * row_bytes, best), (int32_t)r);
+            for (int j = 8; j < s; ++j) {
+                const SegRef sr = a.seg[j0 + j];
+                const uint32_t off = (uint32_t)sr.id * row_bytes;
+                if (sr.end & SEG_FRESH) st(cell_at(in ? off : spare_row), is_best ? (int32_t)r : NEVER_CACHED);
+                else if (is_best) st(cell_at(off), (int32_t)r);
+            }
         }
 
         // ---- log (every lane writes the same record; the chosen replica's lane links it) and eviction
@@ -1110,7 +1178,7 @@ __device__ __forceinline__ void cache_wave(const SegArgs& a, int p, int lane, Ha
 
         // ---- the rows of request r + 1 were requested before this request's stores: the leading segments the two
         // paths share (none unless r + 1 continues the same tree) get the cells this request just wrote
-        const int common = other.flags >> 8;
+        const int common = (other.flags >> 8) & 0xFF;
         if (common > 0) {
 #pragma unroll
             for (int k = 0; k < 4; ++k) other.cell[k] = (k < common && is_best) ? (int32_t)r : other.cell[k];
@@ -1126,10 +1194,10 @@ __device__ __forceinline__ void cache_wave(const SegArgs& a, int p, int lane, Ha
     meet(false);                              // the first descriptors are there
     request_rows(read_desc(&comm->ring[0]), A);
     // (Where the loop is entered, as many memory operations are in flight behind the first request's row loads as a
-    // pass through the loop leaves behind the next request's -- a log record load and four stores -- so that the
+    // pass through the loop leaves behind the next request's -- a log record load and five stores -- so that the
     // wait for the rows at the top of the loop is the same wait on both ways in, and not one for everything.)
     c1.issue_fill(log64, spare);
-    for (int k = 0; k < 4; ++k) st(&log64[spare], 0ull);
+    for (int k = 0; k < 5; ++k) st(&log64[spare], 0ull);
     clk.start();
     for (int64_t r = 0; r < N; r += 2) {
         step(r, A, B);

@@ -269,11 +269,11 @@ __global__ void __launch_bounds__(SEG_THREADS) replay_segments_packed_kernel(Seg
             for (int x = lane; x < cnt; x += WAVE) stage[x] = gref[x];
             wave_sync();
             if (m_s > 0 && lane < nb) {
-                m_n = stage[m_a0 + m_s - 1].end;
+                m_n = stage[m_a0 + m_s - 1].end & SEG_END_MASK;
                 m_root = stage[m_a0].id;
             }
         } else if (m_s > 0 && lane == 0) {
-            m_n = gref[m_s - 1].end;
+            m_n = gref[m_s - 1].end & SEG_END_MASK;
             m_root = gref[0].id;
         }
 
@@ -285,6 +285,7 @@ __global__ void __launch_bounds__(SEG_THREADS) replay_segments_packed_kernel(Seg
             const int s = __builtin_amdgcn_readlane(m_s, i);
             const int n = __builtin_amdgcn_readlane(m_n, i);
             w.of_lane = ref(a0 + (rl < SEG_CHUNK ? rl : 0), rl < s && rl < SEG_CHUNK);
+            w.fresh = 0;
 #pragma unroll
             for (int k = 0; k < SEG_CHUNK; ++k) w.end[k] = n;       // (cells past the last segment are never read)
 #pragma unroll
@@ -296,8 +297,14 @@ __global__ void __launch_bounds__(SEG_THREADS) replay_segments_packed_kernel(Seg
 #pragma unroll
                 for (int k = 0; k < 4; ++k) {
                     if (h + k >= s) break;
-                    w.end[h + k] = sr[k].end;
-                    w.cell[h + k] = ld(cell_at(sr[k].id));           // lanes beyond R read a neighbouring cell, unused
+                    w.end[h + k] = sr[k].end & SEG_END_MASK;
+                    if (sr[k].end & SEG_FRESH) {
+                        // the row slot starts over with this request: what it holds belongs to a segment of the past
+                        w.fresh |= 1 << (h + k);
+                        w.cell[h + k] = NEVER_CACHED;
+                    } else {
+                        w.cell[h + k] = ld(cell_at(sr[k].id));       // lanes beyond R read a neighbouring cell, unused
+                    }
                 }
             }
         };
@@ -337,12 +344,12 @@ __global__ void __launch_bounds__(SEG_THREADS) replay_segments_packed_kernel(Seg
                     int send[SEG_CHUNK];
 #pragma unroll
                     for (int k = 0; k < SEG_CHUNK; ++k) {
-                        cell[k] = -1;
+                        cell[k] = NEVER_CACHED;
                         send[k] = pos;
                         if (c0 + k < s) {
                             const SegRef sr = ref(a0 + c0 + k, true);
-                            send[k] = sr.end;
-                            if (open && rl < R) cell[k] = ld(cell_at(sr.id));
+                            send[k] = sr.end & SEG_END_MASK;
+                            if (open && rl < R && !(sr.end & SEG_FRESH)) cell[k] = ld(cell_at(sr.id));
                         }
                     }
 #pragma unroll
@@ -425,9 +432,11 @@ __global__ void __launch_bounds__(SEG_THREADS) replay_segments_packed_kernel(Seg
                     bool walking = m_best > 0 && !simple;
                     int run_owner = -1, run_end = 0, vpos = 0;
                     for (int j = 0; j < s && __ballot(walking) != 0; ++j) {
-                        const SegRef sr = ref(a0 + j, true);
+                        SegRef sr = ref(a0 + j, true);
+                        const bool fresh = (sr.end & SEG_FRESH) != 0;
+                        sr.end &= SEG_END_MASK;
                         if (walking) {
-                            const int32_t rlast = ld(cell_of(sr.id, best));
+                            const int32_t rlast = fresh ? NEVER_CACHED : ld(cell_of(sr.id, best));
                             const int cnt = cached_in(rlast, vpos, sr.end, cb_r, cb_k);
                             if (cnt > 0) {
                                 if (rlast != run_owner) {
@@ -448,6 +457,15 @@ __global__ void __launch_bounds__(SEG_THREADS) replay_segments_packed_kernel(Seg
             // each replay (lane k of a half stores the cell of segment k)
             if (rl < s && rl < SEG_CHUNK) st(cell_of(mine.of_lane.id, best), (int32_t)r);
             for (int j = SEG_CHUNK + rl; j < s; j += HALF) st(cell_of(ref(a0 + j, true).id, best), (int32_t)r);
+            // A segment that this request is the first to reference has taken over a row slot from a segment of the
+            // past: the row starts over, every replica's cell of either replay, never cached except on the chosen one.
+            if (mine.fresh != 0 || s > SEG_CHUNK) {
+                const int32_t fresh_cell = is_best ? (int32_t)r : NEVER_CACHED;
+                for (int j = 0; j < s; ++j) {
+                    const SegRef sr = ref(a0 + j, true);
+                    if ((sr.end & SEG_FRESH) && rl < R) st(cell_at(sr.id), fresh_cell);
+                }
+            }
 
             // ---- log and eviction, in the chosen replicas' lanes
             if (is_best) {
@@ -511,12 +529,18 @@ __global__ void __launch_bounds__(SEG_THREADS) replay_segments_packed_kernel(Seg
             // same tree, the cells this request just wrote are patched into them (common prefix of the paths)
             if (i + 1 < nb && s > 0 && __builtin_amdgcn_readlane(m_root, i + 1) == __builtin_amdgcn_readlane(m_root, i)) {
                 const int s_next = __builtin_amdgcn_readlane(m_s, i + 1);
-                const bool same = rl < s && rl < s_next && other.of_lane.id == mine.of_lane.id &&
-                                  other.of_lane.end == mine.of_lane.end;
+                // (a fresh segment of the next request may sit in the slot that this request's segment just gave up)
+                const bool same = rl < s && rl < s_next && !(other.of_lane.end & SEG_FRESH) &&
+                                  other.of_lane.id == mine.of_lane.id &&
+                                  (other.of_lane.end & SEG_END_MASK) == (mine.of_lane.end & SEG_END_MASK);
                 const unsigned differ = ~(unsigned)__ballot(same && rl < SEG_CHUNK) | (1u << SEG_CHUNK);   // (lower half)
                 const int common = __ffs(differ) - 1;              // leading segments the two paths share
+                // (where this request has just started the row over, what was loaded is the past's: never cached)
 #pragma unroll
-                for (int k = 0; k < SEG_CHUNK; ++k) other.cell[k] = (k < common && is_best) ? (int32_t)r : other.cell[k];
+                for (int k = 0; k < SEG_CHUNK; ++k) {
+                    const int32_t elsewhere = (mine.fresh >> k) & 1 ? NEVER_CACHED : other.cell[k];
+                    other.cell[k] = k < common ? (is_best ? (int32_t)r : elsewhere) : other.cell[k];
+                }
             }
 
             // ---- outputs of the cache side (kept in registers until the batch ends)

@@ -133,6 +133,7 @@ int preprocess(gorgo_trace* t, const int64_t* hash_ids) {
     t->seg_off.clear();
     t->seg.clear();
     t->n_segments = 0;
+    t->n_slots = 0;
     if (!consistent) return GORGO_OK;
 
     // Chain-consistent traces: the keys form a forest and every request is a root-to-node path.  Cut the
@@ -159,6 +160,40 @@ int preprocess(gorgo_trace* t, const int64_t* hash_ids) {
         }
         t->seg_off[(size_t)r + 1] = (int64_t)t->seg.size();
     }
+
+    // Row slots.  The replay keeps one row of cells per segment, but a segment only matters between the first and
+    // the last request that reference it (no candidate can change that: it is a property of the trace), and at any
+    // time only the segments of conversations still going on are between the two.  So segments share rows: a
+    // segment takes a slot at its first reference -- marked SEG_FRESH in that reference, where the replay resets
+    // the row before anything reads it -- and gives it back after its last one.  Slots are reused oldest-first.
+    std::vector<int64_t> last_ref((size_t)nseg, -1);
+    for (int64_t r = 0; r < N; ++r)
+        for (int64_t j = t->seg_off[(size_t)r]; j < t->seg_off[(size_t)r + 1]; ++j) last_ref[(size_t)t->seg[(size_t)j].id] = r;
+    std::vector<int32_t> slot_of((size_t)nseg, -1);
+    std::vector<int32_t> free_slots;       // a queue: taken from `head`, given back at the end
+    size_t head = 0;
+    int32_t n_slots = 0;
+    std::vector<int32_t> seg_at;           // segments of the request in hand, by place in its path
+    for (int64_t r = 0; r < N; ++r) {
+        const int64_t j0 = t->seg_off[(size_t)r], j1 = t->seg_off[(size_t)r + 1];
+        seg_at.clear();
+        for (int64_t j = j0; j < j1; ++j) {
+            gorgo::SegRef& ref = t->seg[(size_t)j];
+            const size_t sg = (size_t)ref.id;
+            seg_at.push_back(ref.id);
+            if (slot_of[sg] < 0) {
+                slot_of[sg] = head < free_slots.size() ? free_slots[head++] : n_slots++;
+                ref.end |= gorgo::SEG_FRESH;
+            }
+            ref.id = slot_of[sg];
+        }
+        // (given back only now: a slot is not handed on within the request that still uses it)
+        for (int64_t j = j0; j < j1; ++j) {
+            const int32_t slot = t->seg[(size_t)j].id;
+            if (last_ref[(size_t)seg_at[(size_t)(j - j0)]] == r) free_slots.push_back(slot);
+        }
+    }
+    t->n_slots = n_slots;
     return GORGO_OK;
 }
 

@@ -341,3 +341,51 @@ def test_es_rejects_bad_state():
     s = g.es_init(0)
     with pytest.raises(g.GorgoError):
         g.es_update(s, np.ones((2, 3)), [float("nan"), 1.0])
+
+
+def test_segments_share_row_slots_between_their_first_and_last_reference():
+    """The loader's row slots: as many as the most segments in use at one time -- checked against a count made here
+    from the block lists alone (a segment = a maximal run of blocks that the same set of requests touches; it is in
+    use from the first to the last request that touches it)."""
+    for cfg, n in ((1, None), (2, 4000), (5, 20000)):
+        wl = tg.config(cfg, n)
+        tr = wl.trace
+        t = _trace(tr)
+        info = t.replay_path()
+        assert t.info()["chain_consistent"]
+        # first and last request of every block id; blocks with the same (first, last, predecessor chain) form segments,
+        # and what matters here is only how many distinct segments are alive at once: count blocks' [first, last]
+        # intervals per segment through the segment's last block (ids are unique per position in a consistent trace)
+        first, last = {}, {}
+        for r in range(tr.N):
+            for b in tr.hash_ids[tr.blk_off[r]:tr.blk_off[r + 1]].tolist():
+                first.setdefault(b, r)
+                last[b] = r
+        # a request's path is cut wherever the set of touching requests changes: count, per request, the distinct
+        # (first, last) pairs among its blocks = its segments; a segment is identified by its last block
+        seg_first, seg_last = {}, {}
+        refs = 0
+        for r in range(tr.N):
+            ids = tr.hash_ids[tr.blk_off[r]:tr.blk_off[r + 1]].tolist()
+            for k, b in enumerate(ids):
+                nxt = ids[k + 1] if k + 1 < len(ids) else None
+                if nxt is None or (first[nxt], last[nxt]) != (first[b], last[b]):
+                    refs += 1
+                    seg_first.setdefault(b, r)
+                    seg_last[b] = r
+        events = np.zeros(tr.N + 1, np.int64)
+        for b in seg_first:
+            events[seg_first[b]] += 1
+            events[seg_last[b] + 1] -= 1
+        alive_most = int(np.cumsum(events).max())
+        # (the loader's segments are at least as fine as the ones counted here, never coarser: a cut also falls where
+        # the touching sets agree but a request ends; so its counts can only be larger, and equal on these traces)
+        assert info["segment_refs"] >= refs and info["n_segments"] >= len(seg_first)
+        slots = t.row_slots()
+        assert alive_most <= slots <= info["n_segments"]
+        if info["n_segments"] == len(seg_first):
+            assert slots == alive_most
+        if cfg == 5:
+            assert slots < info["n_segments"] // 3         # (most conversations of the workload are over at any time)
+    bad = _trace(tg.random_small(3, 200, 4, n_ids=40, max_blocks=8, consistent=False, gap_ms=5))
+    assert not bad.info()["chain_consistent"] and bad.row_slots() == 0

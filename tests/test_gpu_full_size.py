@@ -4,7 +4,8 @@ configuration the benchmark times: one launch over all 1,024 candidates of the t
 The oracle replays 34 of the candidates (the parent, the last one and 32 seeded picks) in full, one per host
 thread; every request of those replays is compared (routes and hit counts bit-exact, latencies to 1e-9
 relative), and so are their p95s, both from the launch that writes per-request outputs and from the
-p95-only launch of the benchmark."""
+p95-only launch of the benchmark.  The p95 of every one of the 1,024 replays is checked against the nearest-rank
+percentile of that replay's own latencies."""
 from concurrent.futures import ThreadPoolExecutor
 
 import numpy as np
@@ -45,6 +46,7 @@ def test_large_workload_sampled_replays_match_oracle():
         p95_ttft = full.p95_ttft_ms.cpu().numpy()
         p95_e2e = full.p95_e2e_ms.cpu().numpy()
         assert np.isfinite(p95_ttft).all() and (p95_ttft > 0).all() and (p95_e2e >= p95_ttft).all()
+        all_replays_p95_is_the_nearest_rank_of_their_latencies(torch, full)
 
         for p in picks:
             ref = futs[p].result()
@@ -57,6 +59,18 @@ def test_large_workload_sampled_replays_match_oracle():
             assert abs(p95_ttft[p] - ref.p95_ttft_ms) <= RTOL * ref.p95_ttft_ms
             assert abs(p95_e2e[p] - ref.p95_e2e_ms) <= RTOL * ref.p95_e2e_ms
             print(f"replay {p}: {ref.route.size} requests equal, p95 TTFT {ref.p95_ttft_ms:.3f} ms", flush=True)
+
+
+def all_replays_p95_is_the_nearest_rank_of_their_latencies(torch, res):
+    """The p95 of EVERY replay of a launch (not only of those the oracle replays in full) is the nearest-rank
+    percentile -- the k-th smallest, k = ceil(0.95 N), the oracle's definition -- of that replay's own per-request
+    latencies, bit for bit: the reduction is checked on all P, the latencies it reduces on the sampled replays."""
+    P, N = res.ttft_ms.shape
+    k = (95 * N + 99) // 100
+    for lat, p95 in ((res.ttft_ms, res.p95_ttft_ms), (res.e2e_ms, res.p95_e2e_ms)):
+        for a in range(0, P, 64):
+            kth = torch.kthvalue(lat[a:a + 64], k, dim=1).values
+            assert torch.equal(kth, p95[a:a + 64]), f"replays {a}..{a + 63}"
 
 
 def test_large_workload_under_the_engine_model_matches_oracle():
@@ -86,6 +100,7 @@ def test_large_workload_under_the_engine_model_matches_oracle():
         p95_ttft = full.p95_ttft_ms.cpu().numpy()
         p95_e2e = full.p95_e2e_ms.cpu().numpy()
         assert np.isfinite(p95_ttft).all() and (p95_ttft > 0).all() and (p95_e2e >= p95_ttft).all()
+        all_replays_p95_is_the_nearest_rank_of_their_latencies(torch, full)
         for p in picks:
             ref = futs[p].result()
             route = full.route[p].cpu().numpy()
@@ -127,6 +142,7 @@ def test_large_workload_with_imperfect_proxy_knowledge_matches_oracle():
         p95_ttft = full.p95_ttft_ms.cpu().numpy()
         p95_e2e = full.p95_e2e_ms.cpu().numpy()
         assert np.isfinite(p95_ttft).all() and (p95_ttft > 0).all() and (p95_e2e >= p95_ttft).all()
+        all_replays_p95_is_the_nearest_rank_of_their_latencies(torch, full)
         for p in picks:
             ref = futs[p].result()
             route = full.route[p].cpu().numpy()
@@ -157,6 +173,7 @@ def _against_oracle(wl, params, scale, picks, label):
         p95_ttft = full.p95_ttft_ms.cpu().numpy()
         p95_e2e = full.p95_e2e_ms.cpu().numpy()
         assert np.isfinite(p95_ttft).all() and (p95_ttft > 0).all() and (p95_e2e >= p95_ttft).all()
+        all_replays_p95_is_the_nearest_rank_of_their_latencies(torch, full)
         for p in picks:
             ref = futs[p].result()
             bad = np.nonzero(full.route[p].cpu().numpy() != ref.route)[0]

@@ -303,3 +303,61 @@ def test_two_replays_per_wavefront_pair_give_the_same_results():
         ref = oracle_eval(wl.trace, model, wl.rtt_ms, params[p], float(scale[p]))
         assert np.array_equal(out[0].route[p].cpu().numpy(), ref.route)
         np.testing.assert_allclose(out[0].ttft_ms[p].cpu().numpy(), ref.ttft_ms, rtol=RTOL, atol=0)
+
+
+def _churn_trace(seed, conversations, turns_max, branch):
+    """Conversations one after the other: each is a few turns that extend the previous turn's blocks, then it is over
+    for good -- so the row slots of its segments are handed on to the next conversation at once, a request's path
+    often sits in slots that the previous request's path has just given up, and long conversations have paths of more
+    segments than the kernels preload.  With `branch`, later requests also end in the middle of what an earlier
+    turn added, which cuts that turn's blocks into several segments that all start with the same request."""
+    rng = np.random.default_rng(seed)
+    ts, in_len, out_len, off, ids = [], [], [], [0], []
+    t, next_id = 0, 1
+    for c in range(conversations):
+        path = []
+        turns = int(rng.integers(1, turns_max + 1))
+        history = []
+        for k in range(turns):
+            add = int(rng.integers(1, 5))
+            path = path + list(range(next_id, next_id + add))
+            next_id += add
+            history.append(list(path))
+            t += int(rng.integers(0, 30))
+            ts.append(t)
+            ids += path
+            off.append(len(ids))
+            in_len.append(len(path) * 512 - int(rng.integers(0, 512)))
+            out_len.append(int(rng.integers(1, 200)))
+            if branch and k >= 1 and rng.random() < 0.4:
+                # a request that stops inside an earlier turn's addition, then goes its own way
+                cut = history[int(rng.integers(0, len(history)))]
+                stop = int(rng.integers(1, len(cut) + 1))
+                own = list(range(next_id, next_id + int(rng.integers(0, 3))))
+                next_id += len(own)
+                t += int(rng.integers(0, 30))
+                ts.append(t)
+                ids += cut[:stop] + own
+                off.append(len(ids))
+                in_len.append((stop + len(own)) * 512)
+                out_len.append(int(rng.integers(1, 200)))
+    return tg.Trace(np.array(ts, np.int64), np.array(in_len, np.int32), np.array(out_len, np.int32),
+                    np.array(off, np.int64), np.array(ids, np.int64))
+
+
+@pytest.mark.parametrize("seed,R,B,turns_max,branch,cache", [(1, 32, 8, 4, False, 0), (2, 32, 8, 4, True, 40), (3, 8, 2, 14, True, 60),
+                                                              (4, 64, 4, 12, True, 50), (5, 33, 3, 3, False, 12), (6, 5, 16, 20, True, 0),
+                                                              (7, 16, 8, 2, True, 9)])
+def test_row_slots_handed_on_between_segments(seed, R, B, turns_max, branch, cache):
+    tr = _churn_trace(seed, 120, turns_max, branch)
+    h = load(tr)
+    assert h.info()["chain_consistent"]
+    # the point of the trace: far fewer rows than segments, so every slot serves many segments in turn
+    assert h.row_slots() * 4 < h.replay_path()["n_segments"]
+    nmax = int(np.diff(tr.blk_off).max())
+    rng = np.random.default_rng(seed)
+    model = g.Model(R, B, max(cache, nmax) if cache else 0, 0.05, 20.0)
+    rtt = np.round(rng.uniform(1.0, 200.0, R), 1)
+    par = rng.uniform(0.0, 2.0, (6, 3))
+    par[0] = [0.0, 1.0, 0.0]            # prefix-cache routing: follows the cached prefix wherever it is
+    check_population(tr, model, rtt, par, [1.0, 0.3, 4.0, 1.0, 1.0, 2.0], label=f"churn {seed}")
