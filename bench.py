@@ -165,7 +165,7 @@ def section_table(sec, N, P):
     queue = {10: "lane broadcasts, retiring what is due", 0: "publishing the queue terms", 1: "waiting at barrier A",
              2: "retiring ahead for the next request", 3: "(reading the clock once)", 4: "waiting at barrier B", 8: "reading the choice",
              9: "service: slot, completion time", 5: "outputs, tuner, loop", 6: "batch turnover"}
-    front = ["descriptors of request r+2, loads of r+3", "waiting at barrier A", "waiting at barrier B"]
+    front = {0: "descriptor of request r+2", 1: "waiting at barrier A", 3: "references of request r+3 (loads)", 2: "waiting at barrier B"}
     lines.append(f"shader-clock cycles per request (s_memtime), mean over {P} replays")
     k = 1.0
     lines.append("cache wavefront (lane = replica):")
@@ -179,9 +179,9 @@ def section_table(sec, N, P):
         lines.append(f"  {name:44s} {m[1, i] * k:8.1f}")
     lines.append(f"  {'total':44s} {sum(m[1, i] for i in queue) * k:8.1f}")
     lines.append("front-end wavefront (lane = segment reference):")
-    for i, name in enumerate(front):
+    for i, name in front.items():
         lines.append(f"  {name:44s} {m[2, i] * k:8.1f}")
-    lines.append(f"  {'total':44s} {m[2, :3].sum() * k:8.1f}")
+    lines.append(f"  {'total':44s} {sum(m[2, i] for i in front) * k:8.1f}")
     return "\n".join(lines)
 
 

@@ -378,7 +378,8 @@ int gorgo_last_eval_kernel_ms(double* fill_ms, double* replay_ms, double* select
  * 7 patch and loop; then counts, not cycles: 8 log records fetched on the spot by the eviction walk, 9 cursor
  * advances, 10 log records dropped because they own nothing, 11 ownership walks), [p][1] the queue wavefront (0 retire and publish, 1 waiting at the first meeting point,
  * 2 retiring ahead, 3 nothing, 4 waiting for the choice, 5 service and outputs, 6 batch turnover), [p][2] the
- * front-end wavefront (0 descriptors, 1 and 2 waiting at the two meeting points).  Needs the
+ * front-end wavefront (0 the descriptor of the request after next, 1 and 2 waiting at the two meeting points, 3 the
+ * references of the request after that, loaded between the meeting points).  Needs the
  * segment formulation without packing; everything else as gorgo_eval_population. */
 #define GORGO_SECTIONS 12
 int gorgo_eval_population_sections(const gorgo_trace* t, const gorgo_model* m, const gorgo_options* options, const double* rtt_ms,
