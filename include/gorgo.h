@@ -102,7 +102,7 @@ typedef struct gorgo_model {
  *     gorgo_eval_population and gorgo_es_step can run two replays per pair of wavefronts of the segment-row kernel
  *     (a replay keeps one lane per replica, so half of a 64-lane wavefront idles otherwise).  A replay is a serial
  *     chain, so this only pays when the replays would not all be resident on the GPU at once (more than about
- *     1,024 of them): 2 (default) packs exactly then, 1 whenever the shape allows, 0 never.
+ *     1,024 of them) but the pairs would: 2 (default) packs exactly then, 1 whenever the shape allows, 0 never.
  *   handover_poll_limit: how many times a wavefront of the packed segment-row replay polls for its partner's
  *     word before the replay is given up (default 2^24, about a second; a replay that is given up ends at once,
  *     every latency of it becomes NaN, so does its p95, and gorgo_es_step fails with GORGO_ERR_NONFINITE).  It

@@ -491,8 +491,9 @@ int copy_small_to_device(void* dst, const void* src, size_t bytes, void* stream)
 }
 
 // Whether a launch of fixed-weight replays runs two replays per wavefront pair.  A replay is a serial chain whose
-// duration does not depend on how many others run beside it, and a packed pair takes a few percent longer per
-// request than a lone replay: packing pays exactly when the replays would not all be resident at once otherwise.
+// duration does not depend on how many others run beside it, and a packed pair takes about half as long again per
+// request as a lone replay: packing pays when the replays would not all be resident at once otherwise, but the
+// pairs are.
 bool pack_replays(const Plan& pl, int64_t rows) {
     const int32_t mode = pl.packing;       // 0 never, 1 whenever the shape allows, 2 when the replays would not all be resident
     if (mode == 0 || pl.R > HALF || pl.B > 16 || pl.P % 2 != 0 ||
@@ -505,7 +506,10 @@ bool pack_replays(const Plan& pl, int64_t rows) {
         hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, replay_segments_kernel<MODE_COST_MODEL, false, false>,
                                                      SEG3_THREADS, replay_segments_lds_bytes(pl.R, pl.B, 0)) != hipSuccess)
         return false;
-    return (int64_t)pl.P > (int64_t)cus * per_cu;
+    // (measured: packed pairs win when they make one round of what would be two; with more rounds on either side
+    // the unpacked kernel's shorter request step wins again)
+    const int64_t resident = (int64_t)cus * per_cu;
+    return (int64_t)pl.P > resident && (int64_t)pl.P <= 2 * resident;
 }
 
 int wait_for_copies(void* stream) {

@@ -461,7 +461,11 @@ __global__ void __launch_bounds__(SEG_THREADS) replay_segments_packed_kernel(Seg
             // past: the row starts over, every replica's cell of either replay, never cached except on the chosen one.
             if (mine.fresh != 0 || s > SEG_CHUNK) {
                 const int32_t fresh_cell = is_best ? (int32_t)r : NEVER_CACHED;
-                for (int j = 0; j < s; ++j) {
+                for (unsigned rest = (unsigned)mine.fresh; rest != 0; rest &= rest - 1) {      // (mostly one)
+                    const SegRef sr = ref(a0 + __builtin_ctz(rest), true);
+                    if (rl < R) st(cell_at(sr.id), fresh_cell);
+                }
+                for (int j = SEG_CHUNK; j < s; ++j) {
                     const SegRef sr = ref(a0 + j, true);
                     if ((sr.end & SEG_FRESH) && rl < R) st(cell_at(sr.id), fresh_cell);
                 }
