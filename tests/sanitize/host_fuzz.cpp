@@ -67,8 +67,9 @@ static std::string valid_trace(Written* w) {
 static void damage(std::string& s) {
     static const char* const fragments[] = {"{", "}", "[", "]", "\"", ",", ":", "-", "e308", "1e999", "99999999999999999999999",
                                             "-1", "null", "\"timestamp\"", "\"hash_ids\": [", "\\u0000", "\n", "\n\n", " ", "0x10",
-                                            "\"input_length\": -5", "\"output_length\": 4294967296", "\t", "\r\n", "nan", "1.5"};
-    const int kind = (int)below(8);
+                                            "\"input_length\": -5", "\"output_length\": 4294967296", "\t", "\r\n", "nan", "1.5",
+                                            "\xEF\xBB\xBF", "[[1, 2], [3]]", "[1, [2, [3, [4]]]]", "1e", "-", "1.", "00012", "+7"};
+    const int kind = (int)below(9);
     if (s.empty()) return;
     const size_t at = (size_t)below(s.size());
     switch (kind) {
@@ -78,7 +79,18 @@ static void damage(std::string& s) {
         case 3: s.insert(at, s.substr((size_t)below(s.size()), (size_t)below(64))); break;      // duplicate a piece
         case 4: s.resize(at); break;                                                 // truncate
         case 5: for (int k = 0; k < 8; ++k) s[(size_t)below(s.size())] = (char)below(256); break;
-        case 6: s.insert(at, std::string((size_t)below(5000), "0123456789[,"[below(12)])); break;     // a long run
+        case 6:
+            if (below(4) == 0) {
+                // a request with more ids than a request may have (65,535), as one well-formed line
+                std::string line = "{\"timestamp\": 999999999, \"input_length\": 1, \"output_length\": 1, \"hash_ids\": [";
+                const int n = 65530 + (int)below(5000);
+                for (int k = 0; k < n; ++k) line += k ? ",1" : "1";
+                s += line + "]}\n";
+            } else {
+                s.insert(at, std::string((size_t)below(5000), "0123456789[,"[below(12)]));     // a long run
+            }
+            break;
+        case 7: s.insert(0, "\xEF\xBB\xBF"); break;                                   // a byte-order mark in front
         default: {                                                                   // swap two lines (timestamps may decrease)
             const size_t a = s.find('\n', at);
             if (a != std::string::npos && a + 1 < s.size()) {
