@@ -22,6 +22,7 @@ struct PackComm {
     unsigned seq_q;
     int abandoned;
     unsigned long long choice[2];     // per replay: uncached tokens | (((r + 1) mod 2^26) << 6 | replica) << 32
+    unsigned long long look[(LOOK_RING + 1) * WAVE];      // look-ahead of the eviction cursors, see EvictCursor
 };
 
 __host__ __device__ inline size_t replay_segments_packed_lds_bytes(int B) { return Queues::bytes(WAVE, B); }
@@ -191,15 +192,11 @@ __global__ void __launch_bounds__(SEG_THREADS) replay_segments_packed_kernel(Seg
     const double w_queue = a.params[3 * p + 2];
     const double my_rtt = rl < R ? a.rtt[rl] : 0.0;
 
-    // Per-(replay, replica) eviction state, held by the lane: see replay_segments_kernel.
-    int cur_r = -1, cur_k = 0, cur_own = 0;
-    int nx_r = -1, nx_n = 0, nx_own = 0;
-    int n2_r = -1, n2_n = 0, n2_own = 0;
-    int fill_r = -1;
-    int pend_r = -1, pend_own = -1, pend_next = -1;
-    unsigned long long pend_raw = 0;
+    // Per-(replay, replica) eviction state, held by the lane: the same cursor as in replay_segments_kernel.
+    EvictCursor c1;
+    c1.ring = &comm.look[lane];
+    for (int k = 0; k <= LOOK_RING; ++k) c1.ring[k * WAVE] = ~0ull;
     int tail_r = -1;          // youngest request routed to this replica
-    int my_live = 0;          // blocks cached on this replica
 
     // rows of the two replays follow each other; a cell is addressed by a 32-bit byte offset from the first
     int32_t* const last = a.last + p0 * (size_t)a.nseg * R;
@@ -213,40 +210,9 @@ __global__ void __launch_bounds__(SEG_THREADS) replay_segments_packed_kernel(Seg
         return reinterpret_cast<int32_t*>(reinterpret_cast<char*>(last) +
                                           ((unsigned)seg_id * row_bytes + replay_off + (unsigned)replica * 4u));
     };
-    LogRec* const log = a.log + p * N;
+    LogRec* const log = a.log + p * (N + 1);
     unsigned long long* const log64 = reinterpret_cast<unsigned long long*>(log);
-
-    // the fetched record becomes usable: dropped if it owns nothing, else queued behind nx / n2
-    auto take_pending = [&](unsigned long long raw) {
-        if (pend_r >= 0) {
-            const int n = (int)(raw >> 48);
-            const int own_mem = (int)((raw >> 32) & 0xFFFF);
-            const int own = pend_own > own_mem ? pend_own : own_mem;
-            const int next = pend_next >= 0 ? pend_next : (int)(unsigned int)raw;
-            if (own < n) {
-                if (nx_r < 0) {
-                    nx_r = pend_r;
-                    nx_n = n;
-                    nx_own = own;
-                } else {
-                    n2_r = pend_r;
-                    n2_n = n;
-                    n2_own = own;
-                }
-            }
-            fill_r = next;
-            pend_r = -1;
-        }
-    };
-    // fetch the next record of the log if there is room for it
-    auto issue_fill = [&]() {
-        if (pend_r < 0 && fill_r >= 0 && n2_r < 0) {
-            pend_r = fill_r;
-            pend_own = -1;
-            pend_next = -1;
-            pend_raw = ld(&log64[fill_r]);
-        }
-    };
+    const int spare = (int)N;           // the log record behind the last request's: where loads with nothing to fetch go
 
     int64_t r0 = 0;
     while (r0 < N && !dead) {
@@ -323,13 +289,13 @@ __global__ void __launch_bounds__(SEG_THREADS) replay_segments_packed_kernel(Seg
 #pragma unroll
             for (int k = 0; k < SEG_CHUNK; ++k) {
                 if (k >= s) break;
-                const bool gt = mine.cell[k] > cur_r;
-                const bool ge = mine.cell[k] >= cur_r;
+                const bool gt = mine.cell[k] > c1.cur_r;
+                const bool ge = mine.cell[k] >= c1.cur_r;
                 e_gt = gt ? mine.end[k] : e_gt;
                 own_gt = gt ? mine.cell[k] : own_gt;
                 e_ge = ge ? mine.end[k] : e_ge;
             }
-            const int below_cursor = cur_k < e_ge ? cur_k : e_ge;
+            const int below_cursor = c1.cur_k < e_ge ? c1.cur_k : e_ge;
             const bool some_eq = below_cursor > e_gt;
             int my_m = some_eq ? below_cursor : e_gt;
             const int k_end = some_eq ? e_ge : e_gt;
@@ -355,7 +321,7 @@ __global__ void __launch_bounds__(SEG_THREADS) replay_segments_packed_kernel(Seg
 #pragma unroll
                     for (int k = 0; k < SEG_CHUNK; ++k) {
                         if (c0 + k < s) {
-                            const int cnt = cached_in(cell[k], pos, send[k], cur_r, cur_k);
+                            const int cnt = cached_in(cell[k], pos, send[k], c1.cur_r, c1.cur_k);
                             my_m += open ? cnt : 0;
                             open = open && cnt == send[k] - pos;
                             pos = send[k];
@@ -366,9 +332,9 @@ __global__ void __launch_bounds__(SEG_THREADS) replay_segments_packed_kernel(Seg
             }
 
             // ---- the single point of the iteration that waited for memory is behind us
-            take_pending(pend_raw);
+            c1.take_pending(c1.pend_raw);
             if (i + 1 < nb) request_rows(i + 1, ref, other);
-            issue_fill();
+            c1.issue_fill(log64, spare);
 
             // ---- score (Eq. 3) and lowest-index minimum, per replay
             int hit_tok = a.block_tokens * my_m;
@@ -413,10 +379,7 @@ __global__ void __launch_bounds__(SEG_THREADS) replay_segments_packed_kernel(Seg
             // ---- ownership, per replay: see replay_segments_kernel
             auto disown = [&](int owner, int end) {       // chosen lane: owner's owned suffix now starts at end
                 st(&log[owner].own, (uint16_t)end);
-                cur_own = owner == cur_r ? end : cur_own;
-                nx_own = owner == nx_r ? end : nx_own;
-                n2_own = owner == n2_r ? end : n2_own;
-                pend_own = owner == pend_r ? end : pend_own;
+                c1.disowned_anywhere(owner, end);
             };
             if ((m_best0 | m_best1) > 0) {
                 const bool simple0 = !deep && __builtin_amdgcn_readlane((int)one_owner, best0) != 0;
@@ -426,8 +389,8 @@ __global__ void __launch_bounds__(SEG_THREADS) replay_segments_packed_kernel(Seg
                 if ((m_best0 > 0 && !simple0) || (m_best1 > 0 && !simple1)) {
                     // several previous owners, or a prefix longer than the preloaded rows: walk it (all lanes of a
                     // half follow their replay's chosen replica; halves that need no walk stay out)
-                    const int cb_r0 = __builtin_amdgcn_readlane(cur_r, best0), cb_r1 = __builtin_amdgcn_readlane(cur_r, HALF + best1);
-                    const int cb_k0 = __builtin_amdgcn_readlane(cur_k, best0), cb_k1 = __builtin_amdgcn_readlane(cur_k, HALF + best1);
+                    const int cb_r0 = __builtin_amdgcn_readlane(c1.cur_r, best0), cb_r1 = __builtin_amdgcn_readlane(c1.cur_r, HALF + best1);
+                    const int cb_k0 = __builtin_amdgcn_readlane(c1.cur_k, best0), cb_k1 = __builtin_amdgcn_readlane(c1.cur_k, HALF + best1);
                     const int cb_r = upper ? cb_r1 : cb_r0, cb_k = upper ? cb_k1 : cb_k0;
                     bool walking = m_best > 0 && !simple;
                     int run_owner = -1, run_end = 0, vpos = 0;
@@ -476,58 +439,9 @@ __global__ void __launch_bounds__(SEG_THREADS) replay_segments_packed_kernel(Seg
                 st(&log64[r], 0xFFFFFFFFull | ((unsigned long long)n << 48));      // next -1, own 0, n
                 if (tail_r >= 0) st(&log[tail_r].next, (int32_t)r);
             }
-            {
-                const bool first = is_best && tail_r < 0;
-                const bool to_pend = is_best && pend_r >= 0 && pend_r == tail_r;
-                const bool to_fill = is_best && !first && !to_pend && pend_r < 0 && fill_r < 0;
-                cur_r = first ? (int)r : cur_r;
-                cur_k = first ? n : cur_k;
-                cur_own = first ? 0 : cur_own;
-                pend_next = to_pend ? (int)r : pend_next;
-                fill_r = to_fill ? (int)r : fill_r;
-                tail_r = is_best ? (int)r : tail_r;
-
-                my_live += (is_best && C > 0) ? n - m_best : 0;
-                int E = (is_best && C > 0) ? my_live - C : 0;
-                E = E > 0 ? E : 0;
-                my_live -= E;
-                if (__ballot(E > 0) != 0) {
-                    {
-                        int avail = cur_k - cur_own;
-                        avail = avail > 0 ? avail : 0;
-                        const int take = avail < E ? avail : E;
-                        cur_k -= take;
-                        E -= take;
-                    }
-                    while (E > 0) {       // only the chosen replicas' lanes can be here
-                        if (nx_r < 0) {
-                            unsigned long long raw = pend_raw;
-                            if (pend_r < 0) {
-                                if (fill_r < 0) break;      // cannot happen while E > 0; bounds the loop
-                                pend_r = fill_r;
-                                pend_own = -1;
-                                pend_next = -1;
-                                raw = ld(&log64[fill_r]);
-                            }
-                            take_pending(raw);
-                            continue;
-                        }
-                        cur_r = nx_r;
-                        cur_k = nx_n;
-                        cur_own = nx_own;
-                        nx_r = n2_r;
-                        nx_n = n2_n;
-                        nx_own = n2_own;
-                        n2_r = -1;
-                        int avail = cur_k - cur_own;
-                        avail = avail > 0 ? avail : 0;
-                        const int take = avail < E ? avail : E;
-                        cur_k -= take;
-                        E -= take;
-                    }
-                    my_live += E;         // nothing left to evict (unreachable, kept consistent)
-                }
-            }
+            c1.appended(is_best, (int)r, n, tail_r);
+            tail_r = is_best ? (int)r : tail_r;
+            c1.evict(is_best && C > 0, n - m_best, C, log64, spare);
 
             // ---- the rows of request i+1 were requested before this request's stores: if it continues the
             // same tree, the cells this request just wrote are patched into them (common prefix of the paths)
