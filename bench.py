@@ -159,9 +159,9 @@ def section_table(sec, N, P):
     event counts.  sec = the [P, 3, 12] array of gorgo_eval_population_sections."""
     m = (sec.astype(np.float64) / max(N, 1)).mean(axis=0)
     lines = []
-    cache = ["waiting at barrier A (queue terms)", "prefix match (waits for the rows)", "log records, next rows, uncached tokens",
-             "score, minimum, announcement", "waiting at barrier B (stores seen)", "ownership", "cell, log and link stores",
-             "eviction, patching the next rows, loop"]
+    cache = {0: "waiting at barrier A (queue terms)", 1: "prefix match (waits for the rows)", 2: "log records, next rows, uncached tokens",
+             3: "score, minimum, announcement", 5: "ownership", 4: "waiting at barrier B", 6: "cell, log and link stores",
+             7: "eviction, patching the next rows, loop"}
     queue = {10: "lane broadcasts, retiring what is due", 0: "publishing the queue terms", 1: "waiting at barrier A",
              2: "retiring ahead for the next request", 3: "(reading the clock once)", 4: "waiting at barrier B", 8: "reading the choice",
              9: "service: slot, completion time", 5: "outputs, tuner, loop", 6: "batch turnover"}
@@ -169,7 +169,7 @@ def section_table(sec, N, P):
     lines.append(f"shader-clock cycles per request (s_memtime), mean over {P} replays")
     k = 1.0
     lines.append("cache wavefront (lane = replica):")
-    for i, name in enumerate(cache):
+    for i, name in cache.items():
         lines.append(f"  {name:44s} {m[0, i] * k:8.1f}")
     lines.append(f"  {'total':44s} {m[0, :8].sum() * k:8.1f}")
     lines.append(f"  events per request: on-the-spot record fetches {m[0, 8]:.3f}, cursor advances {m[0, 9]:.3f}, "

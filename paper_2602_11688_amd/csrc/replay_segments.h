@@ -1082,8 +1082,8 @@ __device__ __forceinline__ void cache_wave(const SegArgs& a, int p, int lane, Ha
         *choice_slot = ((unsigned long long)((unsigned)best | ((unsigned)m_best << 8)) << 32) | u_best;
         if (PROXY && lane == 0) comm->seen = own_index ? seen_best : m_best;
         clk.tick(3);                                                 // score, minimum, announcement
-        // (the announcement is on its way through LDS; the second meeting comes after the stores below, which do
-        // not depend on the queue side and give it the time to arrive)
+        // (the announcement is on its way through LDS; the second meeting comes after the ownership update below,
+        // which does not depend on the queue side and gives it the time to arrive)
 
         // ---- ownership: the segments this request takes over on the chosen replica stop belonging to
         // their previous requests.  Along the path the previous owners form runs; each run moves its
@@ -1130,6 +1130,9 @@ __device__ __forceinline__ void cache_wave(const SegArgs& a, int p, int lane, Ha
         st(&log[dis_owner >= 0 ? dis_owner : spare].own, (uint16_t)k_end);
 
         clk.tick(5);                                                 // ownership
+        meet(true);                                                  // B(r): the choice is there (the stores below follow it:
+                                                                     // the queue wavefront need not wait for them)
+        clk.tick(4);                                                 // waiting at B
         // ---- cache update: every segment of the request is now last touched by r on the chosen replica
         // (lane k, and k + 8, ..., store the cell of segment k)
         // A segment that this request is the first to reference has taken over a row slot from a segment of the
@@ -1166,8 +1169,6 @@ __device__ __forceinline__ void cache_wave(const SegArgs& a, int p, int lane, Ha
         st(&log64[r], 0xFFFFFFFFull | ((unsigned long long)n << 48));      // next -1, own 0, n
         st(&log[is_best && tail_r >= 0 ? tail_r : spare].next, (int32_t)r);
         clk.tick(6);                                                 // stores, log
-        meet(true);                                                  // B(r): the choice is there
-        clk.tick(4);                                                 // waiting at B
         c1.appended(is_best, (int)r, n, tail_r);
         if (PROXY) c2.appended(is_best, (int)r, n, tail_r);
         tail_r = is_best ? (int)r : tail_r;
