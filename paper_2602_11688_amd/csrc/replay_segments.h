@@ -933,7 +933,7 @@ __device__ __forceinline__ void cache_wave(const SegArgs& a, int p, int lane, Ha
     // Request r: `mine` holds its rows, `other` receives those of request r + 1.
     SectionClock<TIMED> clk;
     int n_walks = 0;          // statistics: ownership walks
-    auto step = [&](int64_t r, RowsOf& mine, RowsOf& other) {
+    auto step = [&](int64_t r, RowsOf& mine, RowsOf& other, auto feeds) {
         const SegDesc* const dr = &comm->ring[r & (DESC_RING - 1)];
         const int target = DICTATED ? dr->target : 0;
         const DescCopy next = read_desc(&comm->ring[(r + 1) & (DESC_RING - 1)]);
@@ -1055,12 +1055,16 @@ __device__ __forceinline__ void cache_wave(const SegArgs& a, int p, int lane, Ha
             now_rtt = comm->w[0];
             now_prefill = comm->w[1];
         }
-        // (while those words come from LDS: the log record requested during the previous request has arrived and
-        // becomes usable, and the next one is requested)
-        c1.take_pending(c1.pend_raw);
-        if (PROXY && index_cap > 0) c2.take_pending(c2.pend_raw);
-        c1.issue_fill(log64, spare);
-        if (PROXY && index_cap > 0) c2.issue_fill(log64, spare);
+        // (while those words come from LDS, every fourth request: the log record requested four requests ago has
+        // arrived and becomes usable, and the next one is requested.  A replica's look-ahead needs a record every
+        // thirty requests or so, and holds eight; feeding it in every fourth request costs a quarter.  Only the
+        // second copy of the step has the code at all, so the other requests do not even branch around it.)
+        if (decltype(feeds)::value && (r & 2)) {
+            c1.take_pending(c1.pend_raw);
+            if (PROXY && index_cap > 0) c2.take_pending(c2.pend_raw);
+            c1.issue_fill(log64, spare);
+            if (PROXY && index_cap > 0) c2.issue_fill(log64, spare);
+        }
         double my_score;
         if (SCORED) {
             const double pf = a.a_pf * (double)my_u_seen;
@@ -1201,8 +1205,8 @@ __device__ __forceinline__ void cache_wave(const SegArgs& a, int p, int lane, Ha
     for (int k = 0; k < 5; ++k) st(&log64[spare], 0ull);
     clk.start();
     for (int64_t r = 0; r < N; r += 2) {
-        step(r, A, B);
-        if (r + 1 < N) step(r + 1, B, A);
+        step(r, A, B, std::false_type{});
+        if (r + 1 < N) step(r + 1, B, A, std::true_type{});
     }
     if (TIMED) {
         // statistics of the eviction walk, summed over the replicas
