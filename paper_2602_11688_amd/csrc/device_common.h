@@ -586,10 +586,10 @@ struct SlotQueues {
     // searched for the earliest free time (lowest index on ties).  rtt_best: the chosen replica's round trip time.
     // idle_then: the slots of this pass that had nothing in flight at the request's time t (the lists may have been
     // retired further since, to the next request's time, which only makes more slots idle).  The latencies come
-    // back the same in every lane.
+    // back the same in every lane, and so does the time the request's completion reaches the proxy.
     __device__ __forceinline__ void serve_in(SlotHead& h, int g, unsigned long long idle_then, int64_t r, int best, double t,
                                             double rtt_best, int uncached, int L, int O, double a_pf, double a_dec, Rec* rec,
-                                            int lane, double* ttft_out, double* e2e_out) {
+                                            int lane, double* ttft_out, double* e2e_out, double* done_out) {
         const bool mine = h.rep == best;
         const int d = h.depth;
         const double half = 0.5 * rtt_best;
@@ -618,6 +618,7 @@ struct SlotQueues {
         const double done = end + half;
         *ttft_out = (first_tok + half) - t;
         *e2e_out = done - t;
+        *done_out = done;
         const bool on = lane == k;
         if (ballot(on && d > 0) != 0) {
             // the slot still has requests in flight: the new one queues behind them
@@ -654,12 +655,12 @@ struct SlotQueues {
     }
     __device__ __forceinline__ void serve(int64_t r, int best, double t, double rtt_best, int uncached, int L, int O,
                                           double a_pf, double a_dec, Rec* rec, int lane, const Idle& idle_then,
-                                          double* ttft_out, double* e2e_out) {
+                                          double* ttft_out, double* e2e_out, double* done_out) {
         switch ((best << log2bp) >> 6) {       // the pass that holds the replica's slots
-            case 0: serve_in(H0, lane, idle_then.m0, r, best, t, rtt_best, uncached, L, O, a_pf, a_dec, rec, lane, ttft_out, e2e_out); break;
-            case 1: serve_in(H1, WAVE + lane, idle_then.m1, r, best, t, rtt_best, uncached, L, O, a_pf, a_dec, rec, lane, ttft_out, e2e_out); break;
-            case 2: serve_in(H2, 2 * WAVE + lane, idle_then.m2, r, best, t, rtt_best, uncached, L, O, a_pf, a_dec, rec, lane, ttft_out, e2e_out); break;
-            default: serve_in(H3, 3 * WAVE + lane, idle_then.m3, r, best, t, rtt_best, uncached, L, O, a_pf, a_dec, rec, lane, ttft_out, e2e_out); break;
+            case 0: serve_in(H0, lane, idle_then.m0, r, best, t, rtt_best, uncached, L, O, a_pf, a_dec, rec, lane, ttft_out, e2e_out, done_out); break;
+            case 1: serve_in(H1, WAVE + lane, idle_then.m1, r, best, t, rtt_best, uncached, L, O, a_pf, a_dec, rec, lane, ttft_out, e2e_out, done_out); break;
+            case 2: serve_in(H2, 2 * WAVE + lane, idle_then.m2, r, best, t, rtt_best, uncached, L, O, a_pf, a_dec, rec, lane, ttft_out, e2e_out, done_out); break;
+            default: serve_in(H3, 3 * WAVE + lane, idle_then.m3, r, best, t, rtt_best, uncached, L, O, a_pf, a_dec, rec, lane, ttft_out, e2e_out, done_out); break;
         }
     }
 };

@@ -318,12 +318,6 @@ __global__ void __launch_bounds__(WAVE) replay_blocks_kernel(ReplayArgs a) {
     }
 }
 
-__global__ void __launch_bounds__(256) fill_i32(int32_t* x, size_t n, int32_t v) {
-    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const size_t stride = (size_t)gridDim.x * blockDim.x;
-    for (; i < n; i += stride) x[i] = v;
-}
-
 // The last row but one of every replay's rows (the one no request touches) gets the cell value that is below any
 // cursor.
 __global__ void __launch_bounds__(256) fill_last_rows(int32_t* x, int32_t P, int64_t rows, int32_t R, int32_t v) {

@@ -558,6 +558,7 @@ __device__ __forceinline__ void queue_wave(const SegArgs& a, int p, int lane, un
 
     double o_ttft = 0.0, o_e2e = 0.0;
     int o_route = 0, o_hit = 0, o_believed = 0;
+    double own_done = INFINITY;               // (one lane per slot) when the previous request's completion reaches the proxy
     SectionClock<TIMED> clk;
     clk.start();
     for (int64_t r = 0; r < N; ++r) {
@@ -578,8 +579,13 @@ __device__ __forceinline__ void queue_wave(const SegArgs& a, int p, int lane, un
                 comm->rtt[lane] = a.rtt_est[at];
             }
         }
-        if constexpr (SLOTS) Q.retire(t, rec, lane);
-        else Q.retire(t, rec);
+        // (one lane per slot: everything that completes by t was retired ahead, while the cache wavefront decided the
+        // previous request -- except that request itself, whose completion time is known since it was served)
+        if constexpr (SLOTS) {
+            if (own_done <= t) Q.retire(t, rec, lane);
+        } else {
+            Q.retire(t, rec);
+        }
         clk.tick(10);                                                // (finer: readlanes and retiring)
         // the queue term of Eq. 3, products rounded one by one (the least-request policy asks for the requests in
         // flight instead; the dictated policies ignore it)
@@ -597,11 +603,11 @@ __device__ __forceinline__ void queue_wave(const SegArgs& a, int p, int lane, un
         // idle at this request's time, so their set is kept.
         unsigned long long idle_now = 0;
         SlotQueues::Idle idle_then{0, 0, 0, 0};
-        const double t_ahead = i + 1 < WAVE ? readlane_f64(cur.t, i + 1) : readlane_f64(nxt.t, 0);
         if constexpr (SLOTS) {
             idle_then = Q.idle_slots();
         } else {
             idle_now = Q.idle;
+            const double t_ahead = i + 1 < WAVE ? readlane_f64(cur.t, i + 1) : readlane_f64(nxt.t, 0);
             if (r + 1 < N) Q.retire(t_ahead, rec);
         }
         clk.tick(2);                                                 // retire ahead
@@ -609,6 +615,7 @@ __device__ __forceinline__ void queue_wave(const SegArgs& a, int p, int lane, un
         meet(true);                                                  // A(r)
         clk.tick(1);                                                 // waiting at A
         if constexpr (SLOTS) {
+            const double t_ahead = i + 1 < WAVE ? readlane_f64(cur.t, i + 1) : readlane_f64(nxt.t, 0);
             if (r + 1 < N) Q.retire(t_ahead, rec, lane);
         }
         meet(false);                                                 // B(r)
@@ -620,7 +627,7 @@ __device__ __forceinline__ void queue_wave(const SegArgs& a, int p, int lane, un
         clk.tick(8);                                                 // (finer: the choice read)
         double ttft, e2e;
         if constexpr (SLOTS)
-            Q.serve(r, best, t, readlane_f64(my_rtt, best), (int)lo, L, O, a.a_pf, a.a_dec, rec, lane, idle_then, &ttft, &e2e);
+            Q.serve(r, best, t, readlane_f64(my_rtt, best), (int)lo, L, O, a.a_pf, a.a_dec, rec, lane, idle_then, &ttft, &e2e, &own_done);
         else if constexpr (ENGINE)
             Q.template serve_engine<PROXY>(r, best, t, my_rtt, (int64_t)(int)lo, L, O, my_a_pf, my_a_dec, my_budget, a.eng_slowdown,
                            rec, lane, &ttft, &e2e);
@@ -766,13 +773,12 @@ struct EvictCursor {
     }
     // request r (n blocks) has become the youngest record of the log of the replica whose lane has is_best set;
     // tail_r is the youngest before it
+    // (The replica's first record is not made the cursor's at once: it is the next one to fetch, like any record
+    // appended after the look-ahead has caught up with the log, and the cursor, which starts before every request,
+    // moves to it when something has to be evicted.)
     __device__ __forceinline__ void appended(bool is_best, int r, int n, int tail_r) {
-        const bool first = is_best && tail_r < 0;
         const bool to_pend = is_best && pend_r >= 0 && pend_r == tail_r;
-        const bool to_fill = is_best && !first && !to_pend && pend_r < 0 && fill_r < 0;
-        cur_r = first ? r : cur_r;
-        cur_k = first ? n : cur_k;
-        cur_own = first ? 0 : cur_own;
+        const bool to_fill = is_best && !to_pend && pend_r < 0 && fill_r < 0;
         pend_next = to_pend ? r : pend_next;
         fill_r = to_fill ? r : fill_r;
     }
