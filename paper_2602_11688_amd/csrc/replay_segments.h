@@ -790,17 +790,18 @@ struct EvictCursor {
         cur_k -= take;
         E -= take;
     }
-    // `added` blocks have joined the LRU of the lane with `active` set; the cursor moves forward until the LRU
-    // fits `cap` blocks again.  The cursor's own record is straight-line code; steps to further records loop (all
-    // lanes together, those with nothing to evict unchanged), taking records from the ring, and from memory on the
-    // spot when the ring has run out.
-    __device__ __forceinline__ void evict(bool active, int added, int cap, const unsigned long long* log64, int spare) {
-        live += active ? added : 0;
-        int E = active ? live - cap : 0;
-        E = E > 0 ? E : 0;
-        live -= E;
-        take_from_cursor(E);
-        while (ballot(E > 0) != 0) {
+    // The cursor moves on to further records until E blocks have been given up (all lanes together, those with
+    // nothing to evict unchanged): records come from the ring, and from memory on the spot when the ring has run
+    // out.  Works on a copy of the state, written back at the end: the request loop's common path, which does not
+    // come here, then carries no register copies for this loop's sake.
+    __device__ __forceinline__ void advance(int E_in, const unsigned long long* log64, int spare) {
+        EvictCursor w = *this;
+        int E = E_in;
+        w.advance_loop(E, log64, spare);
+        *this = w;
+    }
+    __device__ __forceinline__ void advance_loop(int& E, const unsigned long long* log64, int spare) {
+        do {
             const bool empty = E > 0 && ring_cnt == 0;
             if (ballot(empty) != 0) {
                 // fetch a record on the spot (the one being fetched, if any, is waited for instead)
@@ -826,7 +827,19 @@ struct EvictCursor {
             ring_head += go ? 1 : 0;
             ring_cnt -= go ? 1 : 0;
             take_from_cursor(E);         // (lanes with E = 0 take nothing)
-        }
+        } while (ballot(E > 0) != 0);
+    }
+    // `added` blocks have joined the LRU of the lane with `active` set; the cursor moves forward until the LRU
+    // fits `cap` blocks again.  The cursor's own record is straight-line code; steps to further records loop (all
+    // lanes together, those with nothing to evict unchanged), taking records from the ring, and from memory on the
+    // spot when the ring has run out.
+    __device__ __forceinline__ void evict(bool active, int added, int cap, const unsigned long long* log64, int spare) {
+        live += active ? added : 0;
+        int E = active ? live - cap : 0;
+        E = E > 0 ? E : 0;
+        live -= E;
+        take_from_cursor(E);
+        if (ballot(E > 0) != 0) advance(E, log64, spare);
     }
 };
 
@@ -850,7 +863,10 @@ __device__ __forceinline__ void cache_wave(const SegArgs& a, int p, int lane, Ha
     const int R = a.R;
     const int64_t N = a.N;
     const bool bounded = a.C > 0;
-    const int cap = (int)a.C;
+    // (kept in a vector register: under scalar-register pressure the compiler would otherwise re-read it from the
+    // kernel arguments inside the request loop, a scalar-memory wait on the chain)
+    int cap = (int)a.C;
+    asm volatile("" : "+v"(cap));
     const bool in = lane < R;
     // (with the online tuner the weights come with the queue terms instead)
     const double w_rtt = a.params[3 * (size_t)p + 0];
@@ -944,6 +960,8 @@ __device__ __forceinline__ void cache_wave(const SegArgs& a, int p, int lane, Ha
         const int target = DICTATED ? dr->target : 0;
         const DescCopy next = read_desc(&comm->ring[(r + 1) & (DESC_RING - 1)]);
         const int L = mine.L, n = mine.n, s = mine.s;
+        int32_t rv = (int32_t)r;            // the request's number, once in a vector register for the stores below
+        asm volatile("" : "+v"(rv));
 
         // ---- prefix match: lane = replica.  A request that touches a segment touches all its ancestors,
         // so along the path the cells never increase: first the segments touched after the cursor's
@@ -1153,7 +1171,7 @@ __device__ __forceinline__ void cache_wave(const SegArgs& a, int p, int lane, Ha
         // take a loop of their own.
         {
             const int rep = reset_lane ? reset_rep : best;
-            const int32_t val = reset_lane && rep != best ? NEVER_CACHED : (int32_t)r;
+            const int32_t val = reset_lane && rep != best ? NEVER_CACHED : rv;
             st(cell_of(mine.my_off, rep), val);
         }
         if (mine.flags & DESC_FRESH_MORE) {
@@ -1177,11 +1195,11 @@ __device__ __forceinline__ void cache_wave(const SegArgs& a, int p, int lane, Ha
 
         // ---- log (every lane writes the same record; the chosen replica's lane links it) and eviction
         st(&log64[r], 0xFFFFFFFFull | ((unsigned long long)n << 48));      // next -1, own 0, n
-        st(&log[is_best && tail_r >= 0 ? tail_r : spare].next, (int32_t)r);
+        st(&log[is_best && tail_r >= 0 ? tail_r : spare].next, rv);
         clk.tick(6);                                                 // stores, log
-        c1.appended(is_best, (int)r, n, tail_r);
+        c1.appended(is_best, rv, n, tail_r);
         if (PROXY) c2.appended(is_best, (int)r, n, tail_r);
-        tail_r = is_best ? (int)r : tail_r;
+        tail_r = is_best ? rv : tail_r;
         c1.evict(is_best && bounded, n - m_best, cap, log64, spare);
         // the proxy's index evicts under its own capacity: its cursor walks the same log (whose memory is up to
         // date: ownership changes and links are stored as they happen)
@@ -1192,10 +1210,10 @@ __device__ __forceinline__ void cache_wave(const SegArgs& a, int p, int lane, Ha
         const int common = (other.flags >> 8) & 0xFF;
         if (common > 0) {
 #pragma unroll
-            for (int k = 0; k < 4; ++k) other.cell[k] = (k < common && is_best) ? (int32_t)r : other.cell[k];
+            for (int k = 0; k < 4; ++k) other.cell[k] = (k < common && is_best) ? rv : other.cell[k];
             if (other.flags & DESC_MORE4) {
 #pragma unroll
-                for (int k = 4; k < 8; ++k) other.cell[k] = (k < common && is_best) ? (int32_t)r : other.cell[k];
+                for (int k = 4; k < 8; ++k) other.cell[k] = (k < common && is_best) ? rv : other.cell[k];
             }
         }
         clk.tick(7);                                                 // eviction, patch, loop
