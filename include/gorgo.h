@@ -235,7 +235,7 @@ int gorgo_es_step(const gorgo_trace* t, const gorgo_model* m, const gorgo_option
  * it at once, whereas the paper's proxy only sees a TTFT when the first token has come back, so the tuner here is
  * fed a little earlier than a live one would be (a reading of this library, see the design notes).
  * P replays run P independent tuners (different draws, initial weights or time scales).
- * Needs a chain-consistent trace (the dense segment-row formulation). */
+ * Runs in either formulation of the cache state (gorgo_options.replay_path), like everything below. */
 typedef struct gorgo_online {
     int32_t window;        /* 1..1024 requests per fitness window                                     */
     int32_t hop;           /* >= 1 requests between tuner steps                                        */
@@ -273,8 +273,7 @@ int gorgo_eval_online(const gorgo_trace* t, const gorgo_model* m, const gorgo_op
  *                                  floor(h * R / 2^32) with h the high 32 bits of the value that a SplitMix64
  *                                  generator in state `id` returns next; a request without blocks goes to replica 0
  *   GORGO_POLICY_RANDOM            replica = floor(x * R / 2^32) with x the first output word of Philox-4x32-10
- *                                  for counter (request index, 0, 0) and key seeds[p]
- * Needs a chain-consistent trace (the dense segment-row formulation). */
+ *                                  for counter (request index, 0, 0) and key seeds[p] */
 typedef enum gorgo_policy {
     GORGO_POLICY_COST_MODEL = 0,   /* accepted by gorgo_eval_policy only with weights, i.e. not at all: use gorgo_eval_population */
     GORGO_POLICY_LEAST_REQUEST = 1,
@@ -306,7 +305,7 @@ int gorgo_eval_policy(const gorgo_trace* t, const gorgo_model* m, const gorgo_op
  *   - its decode takes (decode_ms_per_token[i] * output_length) * (1 + decode_slowdown * n), n = the number of
  *     requests running at its admission; the factor is fixed at admission.
  * With decode_slowdown = 0, no budget and rates equal to gorgo_model's the results equal the linear model's bit
- * for bit.  gorgo_model.decode_ms_per_token is not used.  Needs a chain-consistent trace. */
+ * for bit.  gorgo_model.decode_ms_per_token is not used. */
 typedef struct gorgo_engine {
     const double* prefill_ms_per_token;   /* host [R], finite, 0..1e6          */
     const double* decode_ms_per_token;    /* host [R], finite, 0..1e6          */
@@ -343,7 +342,10 @@ int gorgo_eval_engine(const gorgo_trace* t, const gorgo_model* m, const gorgo_op
  *     sees the replicas' caches as they are.
  * With one epoch (or equal rows) and index_blocks = -1 or = cache_blocks the results equal
  * gorgo_eval_population's bit for bit.
- * Needs a chain-consistent trace. */
+ * In the block-table formulation the index lives in the replica's table (the same entries read against a second
+ * eviction threshold), so a bounded cache's tables must also hold what only the index still holds: the call fails
+ * with GORGO_ERR_CAPACITY, naming the options.table_factor_percent that is enough, when the tables of the
+ * workspace are too small for index_blocks (or, with index_blocks = 0, for every id of the trace). */
 typedef struct gorgo_proxy {
     int32_t epochs;               /* 1..65536 probe epochs given                                              */
     int32_t probe_interval_ms;    /* >= 1                                                                     */

@@ -1,4 +1,5 @@
 // Evaluation entry points of the C ABI: argument validation, workspace layout, launches, ES generation.
+#include <algorithm>
 #include <atomic>
 #include <cmath>
 #include <cstring>
@@ -58,6 +59,10 @@ int check_model(const gorgo_trace* t, const gorgo_model* m) {
     return GORGO_OK;
 }
 
+// Fewest slots of a block table that holds `resident` entries while a request of up to d distinct blocks is being
+// inserted, given that the replay compacts a table once 7/8 of its slots have been used.
+int64_t least_table_slots(int64_t resident, int64_t d) { return ((resident + d) * 8 + 6) / 7 + 64; }
+
 // Table geometry and workspace carve-up.
 int make_plan(const gorgo_trace* t, const gorgo_model* m, const gorgo_options* options, int32_t P, const gorgo_outputs* o,
               Plan* pl) {
@@ -89,7 +94,7 @@ int make_plan(const gorgo_trace* t, const gorgo_model* m, const gorgo_options* o
     const int64_t resident = (pl->C > 0 ? pl->C : t->unique_ids) + d;
     const int64_t factor = opt.table_factor_percent;
     int64_t need = (resident * factor + 99) / 100;
-    const int64_t floor_need = ((resident + d) * 8 + 6) / 7 + 64;
+    const int64_t floor_need = least_table_slots(resident, d);
     if (need < floor_need) need = floor_need;
     int64_t cap = 128;
     while (cap < need) cap <<= 1;
@@ -110,7 +115,7 @@ int make_plan(const gorgo_trace* t, const gorgo_model* m, const gorgo_options* o
     off += up256((size_t)P * N * 16);
     const bool want_p95_t = !o || o->p95_ttft_ms, want_p95_e = !o || o->p95_e2e_ms;
     pl->off_route = off;
-    if ((!o || !o->route) && pl->path == PATH_BLOCKS) off += up256((size_t)P * N);   // the block kernel reads it back
+    if (pl->path == PATH_BLOCKS) off += up256((size_t)P * N);   // the block kernel's log of choices (its eviction walks it)
     pl->off_ttft = off;
     if (!o || (!o->ttft_ms && want_p95_t)) off += up256((size_t)P * N * 8);
     pl->off_e2e = off;
@@ -245,17 +250,21 @@ int evaluate(const gorgo_trace* t, const gorgo_model* m, const gorgo_options* op
     for (int32_t p = 0; p < P; ++p)
         if (!std::isfinite(scale[p]) || scale[p] < 0 || scale[p] > 1e6)
             return fail(GORGO_ERR_NONFINITE, "scale[" + std::to_string(p) + "] must be finite and in 0..1e6");
-    if (policy != 0 && pl.path != PATH_SEGMENTS)
-        return fail(GORGO_ERR_INVALID_ARG, "the baseline policies need a chain-consistent trace (segment formulation)");
-    if (engine && pl.path != PATH_SEGMENTS)
-        return fail(GORGO_ERR_INVALID_ARG, "the engine model needs a chain-consistent trace (segment formulation)");
-    if (proxy && pl.path != PATH_SEGMENTS)
-        return fail(GORGO_ERR_INVALID_ARG, "imperfect proxy knowledge needs a chain-consistent trace (segment formulation)");
+    if (proxy && proxy->index_blocks >= 0 && pl.path == PATH_BLOCKS && pl.C > 0) {
+        // the tables also hold what only the proxy's index still holds: more entries than the cache's, all the
+        // trace's when the index never forgets
+        const int64_t held = proxy->index_blocks > 0 ? std::max<int64_t>(pl.C, proxy->index_blocks) : t->unique_ids;
+        const int64_t least = least_table_slots(held + t->max_distinct, t->max_distinct);
+        if (pl.cap < least)
+            return fail(GORGO_ERR_CAPACITY,
+                        "the block tables have " + std::to_string(pl.cap) + " slots, the proxy's index needs " +
+                            std::to_string(least) + ": raise options.table_factor_percent to at least " +
+                            std::to_string((least * 100 + pl.C + t->max_distinct - 1) / (pl.C + t->max_distinct) + 1) +
+                            " (for the workspace size and for this call)");
+    }
     std::vector<double> tuner;      // constants, then ln theta0[P][3]
     int64_t steps = 0;
     if (online) {
-        if (pl.path != PATH_SEGMENTS)
-            return fail(GORGO_ERR_INVALID_ARG, "the online tuner needs a chain-consistent trace (segment formulation)");
         steps = gorgo_online_steps(pl.N, online->window, online->hop);
         if (steps < 0 || online->window > 1024) return fail(GORGO_ERR_INVALID_ARG, "window must be in 1..1024 and hop >= 1");
         if (steps > 0 && !online->z) return fail(GORGO_ERR_INVALID_ARG, "online->z is NULL");
@@ -350,7 +359,6 @@ int evaluate(const gorgo_trace* t, const gorgo_model* m, const gorgo_options* op
     }
 
     uint8_t* route = outputs->route;
-    if (!route && pl.path == PATH_BLOCKS) route = reinterpret_cast<uint8_t*>(ws + pl.off_route);
     double* ttft = outputs->ttft_ms;
     if (!ttft && outputs->p95_ttft_ms) ttft = reinterpret_cast<double*>(ws + pl.off_ttft);
     double* e2e = outputs->e2e_ms;

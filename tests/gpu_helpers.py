@@ -1,5 +1,7 @@
 """Shared pieces of the GPU parity tests: run the HIP library and the CPU oracle on the same inputs and
 compare element by element.  Routes and hit counts must be bit-exact; latencies agree to 1e-9 relative."""
+import contextlib
+
 import numpy as np
 
 import paper_2602_11688_amd as g
@@ -13,6 +15,21 @@ def load(tr):
 
 
 PATH_NAMES = {0: "auto", 1: "block-tables", 2: "segment-rows"}
+
+
+@contextlib.contextmanager
+def formulation(path, table_factor_percent=None):
+    """Calls inside run the given formulation of the cache state (1 = hashed block tables, 2 = dense segment rows),
+    optionally with larger block tables, whatever the trace would get by itself."""
+    before = g.default_options().table_factor_percent
+    g.set_replay_path(path)
+    if table_factor_percent is not None:
+        g.set_table_factor_percent(table_factor_percent)
+    try:
+        yield
+    finally:
+        g.set_replay_path(0)
+        g.set_table_factor_percent(before)
 
 
 def gpu_eval(tr, model: g.Model, rtt, params, scale, handle=None, path=0, packing=True):

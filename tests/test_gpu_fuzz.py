@@ -47,8 +47,7 @@ def _setup(seed):
 def test_random_cases(seed):
     rng, tr, model, rtt, par, scale = _setup(seed)
     check_population(tr, model, rtt, par, scale, label=f"fuzz {seed}")
-    if not load(tr).info()["chain_consistent"]:
-        return
+    # (traces that are not chain-consistent run the variants below on block tables)
     window, hop = int(rng.integers(1, 200)), int(rng.integers(1, 70))
     steps = g.online_steps(tr.N, window, hop)
     theta0 = np.clip(par, 0.05, 2.0)

@@ -74,6 +74,5 @@ def test_policy_arguments():
     wl = tg.config(1, 100)
     with pytest.raises(g.GorgoError):
         g.eval_policy(load(wl.trace), _model(wl), wl.rtt_ms, "random", [1.0])            # no seeds
-    bad = tg.random_small(3, 200, 3, consistent=False)
-    with pytest.raises(g.GorgoError):
-        g.eval_policy(load(bad), g.Model(3, 2, 0, 0.05, 20.0), [10.0, 20.0, 30.0], "least-request", [1.0])
+    with pytest.raises(KeyError):
+        g.eval_policy(load(wl.trace), _model(wl), wl.rtt_ms, "round-robin", [1.0])       # not a policy of Sec. 4
