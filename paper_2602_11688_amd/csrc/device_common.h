@@ -440,8 +440,9 @@ __device__ __forceinline__ unsigned long long ballot(bool c) { return __builtin_
 // pass.  Every slot keeps its list of in-flight requests as Queues does, but nothing has to be searched: "which
 // slots' oldest request has completed by t" is one comparison per pass for all slots at once, and an idle slot of
 // the chosen replica is one ballot.  The oldest request of every slot and the number in flight are in registers
-// (one set per pass), so that the usual request -- nothing or one request retired, an idle slot taken -- needs no
-// LDS round trip; the second oldest, the free times and the list ends are in LDS at index g (every lane only ever
+// (one set per pass), and so are the time the slot becomes free and the youngest request of its list, so that the
+// usual request -- nothing or one request retired, an idle slot taken -- needs no LDS access at all and the search
+// for the earliest free slot no LDS round trip; the second oldest is in LDS at index g (every lane only ever
 // addresses its own slots: no conflicts), deeper requests are Rec records in global memory.  The load signal and
 // the request count stay per replica (lane = replica), as the cache side reads them.  Same arithmetic as Queues,
 // operation for operation.
@@ -450,6 +451,8 @@ struct SlotHead {
     int tok;             // its tokens
     int depth;           // requests in flight on the slot
     int rep;             // replica of the slot (-1 where there is no slot)
+    double free;         // time the slot becomes free (+inf where there is no slot)
+    int tail;            // youngest request of the slot's list
 };
 
 struct SlotQueues {
@@ -457,12 +460,8 @@ struct SlotQueues {
     static constexpr int SLOTS = PASSES * WAVE;
     SlotHead H0, H1, H2, H3;
     double* s_done;      // [SLOTS] completion time of the second oldest
-    double* free_at;     // [SLOTS] time the slot becomes free (+inf where there is no slot)
     int32_t* s_tok;      // [SLOTS] tokens of the second oldest
     int32_t* s_next;     // [SLOTS] request after the second oldest (-1: none)
-    int32_t* tail;       // [SLOTS] youngest request of the slot
-    double* spare8;      // [WAVE] where the lanes that have nothing to store write
-    int32_t* spare4;     // [WAVE]
     double my_q;         // outstanding tokens of replica = lane (an integer below 2^53, exact in fp64)
     double my_cnt;       // requests in flight on replica = lane
     int log2bp;
@@ -473,7 +472,7 @@ struct SlotQueues {
         while (bp < B) bp <<= 1;
         return R * bp <= SLOTS;
     }
-    static __host__ __device__ size_t bytes() { return (size_t)SLOTS * (2 * 8 + 3 * 4) + WAVE * (8 + 4); }
+    static __host__ __device__ size_t bytes() { return (size_t)SLOTS * (8 + 2 * 4); }
 
     __device__ __forceinline__ void init_head(SlotHead& h, int pass, int R, int B, int lane) {
         const int g = pass * WAVE + lane;
@@ -482,19 +481,16 @@ struct SlotQueues {
         h.done = INFINITY;
         h.tok = 0;
         h.depth = 0;
-        free_at[g] = h.rep >= 0 ? 0.0 : INFINITY;
+        h.free = h.rep >= 0 ? 0.0 : INFINITY;
+        h.tail = -1;
         s_done[g] = INFINITY;
         s_tok[g] = 0;
-        s_next[g] = tail[g] = -1;
+        s_next[g] = -1;
     }
     __device__ __forceinline__ void init(unsigned char* lds, int R, int B, int lane) {
         s_done = reinterpret_cast<double*>(lds);
-        free_at = s_done + SLOTS;
-        s_tok = reinterpret_cast<int32_t*>(free_at + SLOTS);
+        s_tok = reinterpret_cast<int32_t*>(s_done + SLOTS);
         s_next = s_tok + SLOTS;
-        tail = s_next + SLOTS;
-        spare8 = reinterpret_cast<double*>(tail + SLOTS);
-        spare4 = reinterpret_cast<int32_t*>(spare8 + WAVE);
         log2bp = 0;
         while ((1 << log2bp) < B) ++log2bp;
         init_head(H0, 0, R, B, lane);
@@ -600,14 +596,20 @@ struct SlotQueues {
         if (idle != 0) {
             k = __builtin_ctzll(idle);
         } else {
-            // every slot is busy: the earliest free one (times are >= 0: the order of the bits is the order of the values)
-            const double f = mine ? free_at[g] : INFINITY;
+            // every slot is busy: the earliest free one (times are >= 0: the order of the bits is the order of the
+            // values; mostly one slot alone holds the smallest high word and the low words need not be looked at)
+            const double f = mine ? h.free : INFINITY;
             const unsigned long long bits = (unsigned long long)__double_as_longlong(f);
             const unsigned hi = (unsigned)(bits >> 32), lo = (unsigned)bits;
             const unsigned mhi = wave_min_u32(hi);
             const bool tie = hi == mhi;
-            const unsigned mlo = wave_min_u32(tie ? lo : 0xffffffffu);
-            k = __builtin_ctzll(ballot(tie && lo == mlo));
+            const unsigned long long ties = ballot(tie);
+            if (__builtin_popcountll(ties) == 1) {
+                k = __builtin_ctzll(ties);
+            } else {
+                const unsigned mlo = wave_min_u32(tie ? lo : 0xffffffffu);
+                k = __builtin_ctzll(ballot(tie && lo == mlo));
+            }
             const double fv = readlane_f64(f, k);
             start = arrive > fv ? arrive : fv;
         }
@@ -633,13 +635,12 @@ struct SlotQueues {
                     st(&rec[r].next, (int32_t)-1);
                     st(&rec[r].tokens, (int32_t)L);
                     if (d == 2) s_next[g] = (int32_t)r;
-                    else st(&rec[tail[g]].next, (int32_t)r);
+                    else st(&rec[h.tail].next, (int32_t)r);
                 }
             }
         }
-        // (every lane stores: the chosen slot's lane into the slot, the others into a spare word of their own)
-        *(on ? &free_at[g] : &spare8[lane]) = end;
-        *(on ? &tail[g] : &spare4[lane]) = (int32_t)r;
+        h.free = on ? end : h.free;
+        h.tail = on ? (int)r : h.tail;
         h.done = on && d == 0 ? done : h.done;
         h.tok = on && d == 0 ? L : h.tok;
         h.depth = on ? d + 1 : d;

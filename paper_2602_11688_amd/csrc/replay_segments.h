@@ -551,7 +551,6 @@ __device__ __forceinline__ void queue_wave(const SegArgs& a, int p, int lane, un
         b.O = a.out_len[xx];
     };
     Batch cur, nxt;
-    int64_t b0 = 0;
     load_batch(0, cur);
     load_batch(WAVE, nxt);
     meet(false);        // (the front end's first descriptors are there: the cache wavefront may start)
@@ -561,139 +560,142 @@ __device__ __forceinline__ void queue_wave(const SegArgs& a, int p, int lane, un
     double own_done = INFINITY;               // (one lane per slot) when the previous request's completion reaches the proxy
     SectionClock<TIMED> clk;
     clk.start();
-    for (int64_t r = 0; r < N; ++r) {
-        const int i = (int)(r - b0);
-        const double t = readlane_f64(cur.t, i);
-        const int L = __builtin_amdgcn_readlane(cur.L, i);
-        const int O = __builtin_amdgcn_readlane(cur.O, i);
-        if (PROXY) {
-            bool moved = false;
-            while (epoch + 1 < a.epochs && next_probe <= t) {       // (timestamps do not decrease)
-                ++epoch;
-                next_probe = (double)(epoch + 1) * (double)a.probe_ms;
-                moved = true;
+    // (a loop over the batches around a loop over a batch's requests: inside the inner one the batches do not change,
+    // so nothing there has to wait for the loads of the batch after next, or, with them, for the stores of the
+    // service step)
+    for (int64_t b0 = 0; b0 < N; b0 += WAVE) {
+        const int in_batch = N - b0 < WAVE ? (int)(N - b0) : WAVE;
+        for (int i = 0; i < in_batch; ++i) {
+            const int64_t r = b0 + i;
+            const double t = readlane_f64(cur.t, i);
+            const int L = __builtin_amdgcn_readlane(cur.L, i);
+            const int O = __builtin_amdgcn_readlane(cur.O, i);
+            if (PROXY) {
+                bool moved = false;
+                while (epoch + 1 < a.epochs && next_probe <= t) {       // (timestamps do not decrease)
+                    ++epoch;
+                    next_probe = (double)(epoch + 1) * (double)a.probe_ms;
+                    moved = true;
+                }
+                if (moved) {
+                    const size_t at = (size_t)epoch * R + (lane < R ? lane : 0);
+                    my_rtt = a.rtt_true[at];
+                    comm->rtt[lane] = a.rtt_est[at];
+                }
             }
-            if (moved) {
-                const size_t at = (size_t)epoch * R + (lane < R ? lane : 0);
-                my_rtt = a.rtt_true[at];
-                comm->rtt[lane] = a.rtt_est[at];
+            // (one lane per slot: everything that completes by t was retired ahead, while the cache wavefront decided the
+            // previous request -- except that request itself, whose completion time is known since it was served)
+            if constexpr (SLOTS) {
+                if (own_done <= t) Q.retire(t, rec, lane);
+            } else {
+                Q.retire(t, rec);
             }
-        }
-        // (one lane per slot: everything that completes by t was retired ahead, while the cache wavefront decided the
-        // previous request -- except that request itself, whose completion time is known since it was served)
-        if constexpr (SLOTS) {
-            if (own_done <= t) Q.retire(t, rec, lane);
-        } else {
-            Q.retire(t, rec);
-        }
-        clk.tick(10);                                                // (finer: readlanes and retiring)
-        // the queue term of Eq. 3, products rounded one by one (the least-request policy asks for the requests in
-        // flight instead; the dictated policies ignore it)
-        if (MODE == MODE_LEAST_REQUEST) comm->sq[lane] = Q.my_cnt;
-        else if (MODE == MODE_COST_MODEL || MODE == MODE_ONLINE) {
-            const double qd = a.a_pf * Q.my_q;
-            comm->sq[lane] = w_queue * qd;
-        }
-        clk.tick(0);                                                 // retire, publish
-        // The completions up to the next request's time do not depend on where this request goes (only this
-        // request's own completion does, which is left for the retire above, next time round): they are retired
-        // ahead, where this wavefront would otherwise wait -- with the slots in LDS (a retirement there is a search)
-        // before the meeting, while the cache wavefront is still busy with the previous request; with a lane per
-        // slot after it, while the cache wavefront decides.  The service step still has to see the slots that were
-        // idle at this request's time, so their set is kept.
-        unsigned long long idle_now = 0;
-        SlotQueues::Idle idle_then{0, 0, 0, 0};
-        if constexpr (SLOTS) {
-            idle_then = Q.idle_slots();
-        } else {
-            idle_now = Q.idle;
-            const double t_ahead = i + 1 < WAVE ? readlane_f64(cur.t, i + 1) : readlane_f64(nxt.t, 0);
-            if (r + 1 < N) Q.retire(t_ahead, rec);
-        }
-        clk.tick(2);                                                 // retire ahead
-        clk.tick(3);                                                 // (nothing: what reading the clock costs)
-        meet(true);                                                  // A(r)
-        clk.tick(1);                                                 // waiting at A
-        if constexpr (SLOTS) {
-            const double t_ahead = i + 1 < WAVE ? readlane_f64(cur.t, i + 1) : readlane_f64(nxt.t, 0);
-            if (r + 1 < N) Q.retire(t_ahead, rec, lane);
-        }
-        meet(false);                                                 // B(r)
-        clk.tick(4);                                                 // waiting at B
-        const unsigned long long w = comm->choice;
-        const unsigned hi = __builtin_amdgcn_readfirstlane((unsigned)(w >> 32));
-        const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)w);
-        const int best = (int)(hi & 63u);
-        clk.tick(8);                                                 // (finer: the choice read)
-        double ttft, e2e;
-        if constexpr (SLOTS)
-            Q.serve(r, best, t, readlane_f64(my_rtt, best), (int)lo, L, O, a.a_pf, a.a_dec, rec, lane, idle_then, &ttft, &e2e, &own_done);
-        else if constexpr (ENGINE)
-            Q.template serve_engine<PROXY>(r, best, t, my_rtt, (int64_t)(int)lo, L, O, my_a_pf, my_a_dec, my_budget, a.eng_slowdown,
-                           rec, lane, &ttft, &e2e);
-        else
-            Q.template serve<PROXY>(r, best, t, my_rtt, (int64_t)(int)lo, L, O, a.a_pf, a.a_dec, rec, lane, idle_now,
-                                    &ttft, &e2e);
-        clk.tick(9);                                                 // (finer: service)
-        o_ttft = lane == i ? ttft : o_ttft;
-        o_e2e = lane == i ? e2e : o_e2e;
-        o_route = lane == i ? best : o_route;
-        o_hit = lane == i ? (int)(hi >> 8) : o_hit;
-        if (PROXY && a.believed) o_believed = lane == i ? __builtin_amdgcn_readfirstlane(comm->seen) : o_believed;
-        if (ONLINE) {
-            if (lane == 0) ring[ring_pos] = ttft;
-            ring_pos = ring_pos + 1 == W ? 0 : ring_pos + 1;
-            if (--until_step == 0) {
-                until_step = H;
-                wave_sync();
-                const double f = window_kth(ring, W, kth, lane);
-                if (!have_parent) {
-                    f_par = f;                 // the first window measures the initial weights: the parent
-                    have_parent = true;
-                } else {
-                    const bool success = f < f_par;
-                    if (success) {
-                        for (int k = 0; k < 3; ++k) ln_par[k] = ln_cur[k];
-                        f_par = f;
-                        ++accepted;
+            clk.tick(10);                                                // (finer: readlanes and retiring)
+            // the queue term of Eq. 3, products rounded one by one (the least-request policy asks for the requests in
+            // flight instead; the dictated policies ignore it)
+            if (MODE == MODE_LEAST_REQUEST) comm->sq[lane] = Q.my_cnt;
+            else if (MODE == MODE_COST_MODEL || MODE == MODE_ONLINE) {
+                const double qd = a.a_pf * Q.my_q;
+                comm->sq[lane] = w_queue * qd;
+            }
+            clk.tick(0);                                                 // retire, publish
+            // The completions up to the next request's time do not depend on where this request goes (only this
+            // request's own completion does, which is left for the retire above, next time round): they are retired
+            // ahead, where this wavefront would otherwise wait -- with the slots in LDS (a retirement there is a search)
+            // before the meeting, while the cache wavefront is still busy with the previous request; with a lane per
+            // slot after it, while the cache wavefront decides.  The service step still has to see the slots that were
+            // idle at this request's time, so their set is kept.
+            unsigned long long idle_now = 0;
+            SlotQueues::Idle idle_then{0, 0, 0, 0};
+            if constexpr (SLOTS) {
+                idle_then = Q.idle_slots();
+            } else {
+                idle_now = Q.idle;
+                const double t_ahead = i + 1 < WAVE ? readlane_f64(cur.t, i + 1) : readlane_f64(nxt.t, 0);
+                if (r + 1 < N) Q.retire(t_ahead, rec);
+            }
+            clk.tick(2);                                                 // retire ahead
+            clk.tick(3);                                                 // (nothing: what reading the clock costs)
+            meet(true);                                                  // A(r)
+            clk.tick(1);                                                 // waiting at A
+            if constexpr (SLOTS) {
+                const double t_ahead = i + 1 < WAVE ? readlane_f64(cur.t, i + 1) : readlane_f64(nxt.t, 0);
+                if (r + 1 < N) Q.retire(t_ahead, rec, lane);
+            }
+            meet(false);                                                 // B(r)
+            clk.tick(4);                                                 // waiting at B
+            const unsigned long long w = comm->choice;
+            const unsigned hi = __builtin_amdgcn_readfirstlane((unsigned)(w >> 32));
+            const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)w);
+            const int best = (int)(hi & 63u);
+            clk.tick(8);                                                 // (finer: the choice read)
+            double ttft, e2e;
+            if constexpr (SLOTS)
+                Q.serve(r, best, t, readlane_f64(my_rtt, best), (int)lo, L, O, a.a_pf, a.a_dec, rec, lane, idle_then, &ttft, &e2e, &own_done);
+            else if constexpr (ENGINE)
+                Q.template serve_engine<PROXY>(r, best, t, my_rtt, (int64_t)(int)lo, L, O, my_a_pf, my_a_dec, my_budget, a.eng_slowdown,
+                               rec, lane, &ttft, &e2e);
+            else
+                Q.template serve<PROXY>(r, best, t, my_rtt, (int64_t)(int)lo, L, O, a.a_pf, a.a_dec, rec, lane, idle_now,
+                                        &ttft, &e2e);
+            clk.tick(9);                                                 // (finer: service)
+            o_ttft = lane == i ? ttft : o_ttft;
+            o_e2e = lane == i ? e2e : o_e2e;
+            o_route = lane == i ? best : o_route;
+            o_hit = lane == i ? (int)(hi >> 8) : o_hit;
+            if (PROXY && a.believed) o_believed = lane == i ? __builtin_amdgcn_readfirstlane(comm->seen) : o_believed;
+            if (ONLINE) {
+                if (lane == 0) ring[ring_pos] = ttft;
+                ring_pos = ring_pos + 1 == W ? 0 : ring_pos + 1;
+                if (--until_step == 0) {
+                    until_step = H;
+                    wave_sync();
+                    const double f = window_kth(ring, W, kth, lane);
+                    if (!have_parent) {
+                        f_par = f;                 // the first window measures the initial weights: the parent
+                        have_parent = true;
+                    } else {
+                        const bool success = f < f_par;
+                        if (success) {
+                            for (int k = 0; k < 3; ++k) ln_par[k] = ln_cur[k];
+                            f_par = f;
+                            ++accepted;
+                        }
+                        sigma = sigma * (success ? a.tuner[13] : a.tuner[14]);
                     }
-                    sigma = sigma * (success ? a.tuner[13] : a.tuner[14]);
+                    double th[3];
+                    for (int k = 0; k < 3; ++k) {
+                        const double zk = a.z[((size_t)p * a.steps + step) * 3 + k];
+                        const double moved = ln_par[k] + sigma * zk;
+                        ln_cur[k] = clip(moved, a.tuner[6 + k], a.tuner[9 + k]);
+                        th[k] = clip(tuner_exp(ln_cur[k]), a.tuner[k], a.tuner[3 + k]);
+                    }
+                    w_queue = th[2];                                     // in use from the next request on
+                    if (lane == 0) {
+                        comm->w[0] = th[0];
+                        comm->w[1] = th[1];
+                        if (a.fitness_step) a.fitness_step[(size_t)p * a.steps + step] = f;
+                        if (a.theta_step)
+                            for (int k = 0; k < 3; ++k) a.theta_step[((size_t)p * a.steps + step) * 3 + k] = th[k];
+                    }
+                    ++step;
+                    wave_sync();
                 }
-                double th[3];
-                for (int k = 0; k < 3; ++k) {
-                    const double zk = a.z[((size_t)p * a.steps + step) * 3 + k];
-                    const double moved = ln_par[k] + sigma * zk;
-                    ln_cur[k] = clip(moved, a.tuner[6 + k], a.tuner[9 + k]);
-                    th[k] = clip(tuner_exp(ln_cur[k]), a.tuner[k], a.tuner[3 + k]);
-                }
-                w_queue = th[2];                                     // in use from the next request on
-                if (lane == 0) {
-                    comm->w[0] = th[0];
-                    comm->w[1] = th[1];
-                    if (a.fitness_step) a.fitness_step[(size_t)p * a.steps + step] = f;
-                    if (a.theta_step)
-                        for (int k = 0; k < 3; ++k) a.theta_step[((size_t)p * a.steps + step) * 3 + k] = th[k];
-                }
-                ++step;
-                wave_sync();
             }
+            clk.tick(5);                                                 // serve, outputs, tuner
         }
-        clk.tick(5);                                                 // serve, outputs, tuner
-        if (i == WAVE - 1 || r == N - 1) {
-            // the batch is done: its outputs go out, the next batch moves up and the one after it is requested
-            if (lane <= i) {
-                const size_t o = (size_t)p * N + b0 + lane;
-                if (a.ttft) a.ttft[o] = o_ttft;
-                if (a.e2e) a.e2e[o] = o_e2e;
-                if (a.route) a.route[o] = (uint8_t)o_route;
-                if (a.hit) a.hit[o] = (uint16_t)o_hit;
-                if (PROXY && a.believed) a.believed[o] = (uint16_t)o_believed;
-            }
-            cur = nxt;
-            b0 += WAVE;
-            load_batch(b0 + WAVE, nxt);
-            clk.tick(6);                                             // batch turnover
+        // the batch is done: its outputs go out, the next batch moves up and the one after it is requested
+        if (lane < in_batch) {
+            const size_t o = (size_t)p * N + b0 + lane;
+            if (a.ttft) a.ttft[o] = o_ttft;
+            if (a.e2e) a.e2e[o] = o_e2e;
+            if (a.route) a.route[o] = (uint8_t)o_route;
+            if (a.hit) a.hit[o] = (uint16_t)o_hit;
+            if (PROXY && a.believed) a.believed[o] = (uint16_t)o_believed;
         }
+        cur = nxt;
+        load_batch(b0 + 2 * WAVE, nxt);
+        clk.tick(6);                                                   // batch turnover
     }
     clk.write(a.sections ? a.sections + ((size_t)p * 3 + 1) * SECTIONS : nullptr, lane);
     tuner_results();
