@@ -465,6 +465,14 @@ struct SlotQueues {
     double my_q;         // outstanding tokens of replica = lane (an integer below 2^53, exact in fp64)
     double my_cnt;       // requests in flight on replica = lane
     int log2bp;
+    // One record per lane can be on its way from global memory: the new second oldest of slot f_slot (-1: none), whose
+    // LDS words are not valid until settle() has written them -- one request later, so that a slot whose list goes
+    // deeper than two does not make the wavefront wait for memory when its oldest request completes.  (While the
+    // record is on its way the slot's `next` word in LDS already works: -1, or the request queued behind the record
+    // since; the loaded `next` replaces it only if the record had a successor when it was requested.)
+    int f_slot, f_tok, f_next;
+    double f_done;
+    bool f_any;          // some lane has a record on its way (the same in every lane)
 
     // whether a model's slots fit: Bp = B rounded up to a power of two, R * Bp <= SLOTS
     static __host__ __device__ bool fits(int R, int B) {
@@ -499,6 +507,22 @@ struct SlotQueues {
         init_head(H3, 3, R, B, lane);
         my_q = 0.0;
         my_cnt = 0.0;
+        f_slot = f_next = -1;
+        f_any = false;
+        f_tok = 0;
+        f_done = INFINITY;
+    }
+
+    // The record that was requested by an earlier pop has arrived: it becomes the slot's second oldest.
+    __device__ __forceinline__ void settle() {
+        if (!f_any) return;
+        f_any = false;
+        if (f_slot >= 0) {
+            s_done[f_slot] = f_done;
+            s_tok[f_slot] = f_tok;
+            if (f_next >= 0) s_next[f_slot] = f_next;
+        }
+        f_slot = -1;
     }
 
     // The slots of one pass whose oldest request has completed by t drop it (and whatever else of theirs has
@@ -525,32 +549,42 @@ struct SlotQueues {
                 n_tok = s_tok[g];
                 n_depth = d - 1;
                 int x = n_depth >= 2 ? s_next[g] : -1;      // the request that moves into second position
-                for (;;) {
-                    const bool again = n_depth > 0 && n_done <= t;     // the new head has completed too
-                    if (again) {
-                        dq += (double)n_tok;
-                        dc += 1.0;
-                        --n_depth;
+                if (!(n_done <= t) && x >= 0 && f_slot < 0) {
+                    // the usual case of a deep list: the new head stays, its successor is requested and settled later
+                    f_slot = g;
+                    s_next[g] = -1;
+                    f_done = ld(&rec[x].done);
+                    f_tok = ld(&rec[x].tokens);
+                    f_next = ld(&rec[x].next);
+                } else {
+                    for (;;) {
+                        const bool again = n_depth > 0 && n_done <= t;     // the new head has completed too
+                        if (again) {
+                            dq += (double)n_tok;
+                            dc += 1.0;
+                            --n_depth;
+                        }
+                        double x_done = INFINITY;
+                        int x_tok = 0, x_next = -1;
+                        if (x >= 0) {
+                            x_done = ld(&rec[x].done);
+                            x_tok = ld(&rec[x].tokens);
+                            x_next = ld(&rec[x].next);
+                        }
+                        if (!again) {
+                            // settled: x (if any) is the second oldest
+                            s_done[g] = x_done;
+                            s_tok[g] = x_tok;
+                            s_next[g] = x_next;
+                            break;
+                        }
+                        n_done = x_done;            // x moves up to the head (+inf when the list is empty)
+                        n_tok = x_tok;
+                        x = x_next;
                     }
-                    double x_done = INFINITY;
-                    int x_tok = 0, x_next = -1;
-                    if (x >= 0) {
-                        x_done = ld(&rec[x].done);
-                        x_tok = ld(&rec[x].tokens);
-                        x_next = ld(&rec[x].next);
-                    }
-                    if (!again) {
-                        // settled: x (if any) is the second oldest
-                        s_done[g] = x_done;
-                        s_tok[g] = x_tok;
-                        s_next[g] = x_next;
-                        break;
-                    }
-                    n_done = x_done;            // x moves up to the head (+inf when the list is empty)
-                    n_tok = x_tok;
-                    x = x_next;
                 }
             }
+            f_any = f_any || ballot(f_slot >= 0) != 0;
             // (further completions are rare: their tokens reach the replicas' lanes one slot at a time)
             for (unsigned long long rest = ballot(dc != 0.0); rest != 0; rest &= rest - 1) {
                 const int l = __builtin_ctzll(rest);
@@ -569,6 +603,7 @@ struct SlotQueues {
     __device__ __forceinline__ void retire(double t, const Rec* rec, int lane) {
         const bool due0 = H0.done <= t, due1 = H1.done <= t, due2 = H2.done <= t, due3 = H3.done <= t;
         if (ballot(due0 || due1 || due2 || due3) == 0) return;
+        settle();
         pop(H0, lane, due0, t, rec, lane);
         pop(H1, WAVE + lane, due1, t, rec, lane);
         pop(H2, 2 * WAVE + lane, due2, t, rec, lane);
@@ -634,7 +669,7 @@ struct SlotQueues {
                     st(&rec[r].done, done);
                     st(&rec[r].next, (int32_t)-1);
                     st(&rec[r].tokens, (int32_t)L);
-                    if (d == 2) s_next[g] = (int32_t)r;
+                    if (d == 2) s_next[g] = (int32_t)r;      // (behind the second oldest, whose record may still be on its way)
                     else st(&rec[h.tail].next, (int32_t)r);
                 }
             }
