@@ -363,3 +363,24 @@ def test_row_slots_handed_on_between_segments(seed, R, B, turns_max, branch, cac
     par = rng.uniform(0.0, 2.0, (6, 3))
     par[0] = [0.0, 1.0, 0.0]            # prefix-cache routing: follows the cached prefix wherever it is
     check_population(tr, model, rtt, par, [1.0, 0.3, 4.0, 1.0, 1.0, 2.0], label=f"churn {seed}")
+
+
+@pytest.mark.parametrize("R,B,burst", [(8, 8, 700), (32, 8, 2200), (5, 3, 300)])
+def test_deep_in_flight_lists_in_bursts(R, B, burst):
+    """Bursts of arrivals a millisecond apart with a minute of silence between them: during a burst every service
+    slot's list of in-flight requests goes many deep and loses its oldest request one at a time (the record that
+    moves up comes from memory); the first request after the silence finds every list completed at once."""
+    rng = np.random.default_rng(R * 100 + B)
+    N = 3 * burst + 50
+    gaps = rng.integers(0, 3, size=N).astype(np.int64)
+    gaps[burst::burst] = 60000
+    sessions = 4 * R
+    nblk = rng.integers(1, 6, size=N)
+    who = rng.integers(0, sessions, size=N)
+    lists = [[1 + int(who[r]) * 8 + k for k in range(int(nblk[r]))] for r in range(N)]
+    blk_off = np.concatenate([[0], np.cumsum(nblk)]).astype(np.int64)
+    ids = np.array([x for l in lists for x in l], np.int64)
+    tr = tg.Trace(np.cumsum(gaps), (nblk * 512).astype(np.int32), rng.integers(1, 6, size=N).astype(np.int32), blk_off, ids)
+    rtt = np.linspace(5.0, 60.0, R)
+    params = [[0.5, 1.0, 0.1], [0.0, 0.0, 1.0], [1.0, 0.1, 0.01]]
+    check_population(tr, g.Model(R, B, 0, 0.05, 40.0), rtt, params, [1.0, 1.0, 0.5])
