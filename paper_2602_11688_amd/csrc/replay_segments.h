@@ -1244,8 +1244,11 @@ __device__ __forceinline__ void cache_wave(const SegArgs& a, int p, int lane, Ha
     clk.write(a.sections ? a.sections + (size_t)p * 3 * SECTIONS : nullptr, lane);
 }
 
+// (At most 128 vector registers: four wavefronts per SIMD.  The 1,024 replays of a population are 3,072 wavefronts,
+// three per SIMD on 256 CUs; with registers for exactly three per SIMD a workgroup only fits where the wavefronts
+// happen to be spread evenly, and part of the population waits for a second round.)
 template <int MODE, bool ENGINE, bool PROXY, bool SLOTS = false, bool TIMED = false>
-__global__ void __launch_bounds__(SEG3_THREADS) replay_segments_kernel(SegArgs a) {
+__global__ void __launch_bounds__(SEG3_THREADS, 4) replay_segments_kernel(SegArgs a) {
     extern __shared__ __align__(16) unsigned char lds_raw[];
     __shared__ __align__(16) Handover comm;
     const int lane = threadIdx.x & (WAVE - 1);
