@@ -275,6 +275,20 @@ def test_proxy_entry_point_rejects_bad_arguments_before_touching_a_device():
     bad = _trace(tg.random_small(3, 50, 2, consistent=False))
     mb = g.Model(2, 2, 0, 0.05, 20.0).c()
     assert proxy(rt=ok[:, :2].copy(), tr=bad, mm=mb) == -7                        # any trace will do
+    # on block tables the index lives in the replicas' tables: a bounded cache's tables must be large enough for it
+    tangled = _trace(tg.random_small(6, 300, 6, consistent=False, n_ids=300, max_blocks=24))
+    assert not tangled.info()["chain_consistent"]
+    mt = g.Model(6, 4, 30, 0.05, 20.0).c()
+    rt6 = np.tile(np.linspace(5.0, 80.0, 6), (3, 1))
+    assert proxy(rt=rt6, tr=tangled, mm=mt, index=-1) == -7 and proxy(rt=rt6, tr=tangled, mm=mt, index=30) == -7
+    assert proxy(rt=rt6, tr=tangled, mm=mt, index=0) == -5                        # it never forgets: every id of the trace
+    assert b"table_factor_percent" in L.gorgo_last_error()
+    big = gb.Options()
+    L.gorgo_options_default(C.byref(big))
+    big.table_factor_percent = 1200
+    x = gb._Proxy(3, 30000, gb._ptr(rt6), 0.5, 0, C.c_void_p(256), None)
+    assert L.gorgo_eval_proxy(tangled._h, C.byref(mt), C.byref(big), C.byref(x), None, gb._ptr(par), None, gb._ptr(sc), 2,
+                              C.byref(o), None, 1 << 40, None) == -7
 
 
 # ------------------------------------------------------------------------------------------------ tuner
