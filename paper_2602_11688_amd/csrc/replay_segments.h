@@ -601,26 +601,27 @@ __device__ __forceinline__ void queue_wave(const SegArgs& a, int p, int lane, un
             clk.tick(0);                                                 // retire, publish
             // The completions up to the next request's time do not depend on where this request goes (only this
             // request's own completion does, which is left for the retire above, next time round): they are retired
-            // ahead, where this wavefront would otherwise wait -- with the slots in LDS (a retirement there is a search)
-            // before the meeting, while the cache wavefront is still busy with the previous request; with a lane per
-            // slot after it, while the cache wavefront decides.  The service step still has to see the slots that were
-            // idle at this request's time, so their set is kept.
+            // ahead, after the meeting, where this wavefront would otherwise wait while the cache wavefront decides.
+            // The service step still has to see the slots that were idle at this request's time, so their set is
+            // kept.
             unsigned long long idle_now = 0;
             SlotQueues::Idle idle_then{0, 0, 0, 0};
             if constexpr (SLOTS) {
                 idle_then = Q.idle_slots();
             } else {
                 idle_now = Q.idle;
-                const double t_ahead = i + 1 < WAVE ? readlane_f64(cur.t, i + 1) : readlane_f64(nxt.t, 0);
-                if (r + 1 < N) Q.retire(t_ahead, rec);
             }
             clk.tick(2);                                                 // retire ahead
             clk.tick(3);                                                 // (nothing: what reading the clock costs)
             meet(true);                                                  // A(r)
             clk.tick(1);                                                 // waiting at A
-            if constexpr (SLOTS) {
+            {
                 const double t_ahead = i + 1 < WAVE ? readlane_f64(cur.t, i + 1) : readlane_f64(nxt.t, 0);
-                if (r + 1 < N) Q.retire(t_ahead, rec, lane);
+                if constexpr (SLOTS) {
+                    if (r + 1 < N) Q.retire(t_ahead, rec, lane);
+                } else {
+                    if (r + 1 < N) Q.retire(t_ahead, rec);
+                }
             }
             meet(false);                                                 // B(r)
             clk.tick(4);                                                 // waiting at B
