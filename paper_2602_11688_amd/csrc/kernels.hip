@@ -29,10 +29,14 @@ __global__ void __launch_bounds__(256) fill_last_rows(int32_t* x, int32_t P, int
 }
 
 // ---- exact nearest-rank percentile: k-th smallest of x[p][0..N) by most-significant-digit radix selection
-// on the order-preserving integer image of the doubles.  One 256-thread workgroup per row.
+// on the order-preserving integer image of the doubles.  One 256-thread workgroup per row.  Every digit is a pass
+// over the row; as soon as the bin that holds the k-th element has few enough elements they are gathered into LDS
+// in one more pass and the element is picked there by counting (latencies of a replay differ in the first two or
+// three digits: three passes instead of six).
 constexpr int SEL_THREADS = 256;
 constexpr int SEL_BITS = 11;
 constexpr int SEL_BINS = 1 << SEL_BITS;
+constexpr int SEL_GATHER = 2048;      // candidates that are finished in LDS
 
 __device__ __forceinline__ uint64_t ordered_bits(double x) {
     uint64_t b = (uint64_t)__double_as_longlong(x);
@@ -43,8 +47,10 @@ __global__ void __launch_bounds__(SEL_THREADS) select_kth(const double* x, int64
                                                           double* out) {
     __shared__ uint32_t hist[SEL_BINS];
     __shared__ uint32_t part[SEL_THREADS];
+    __shared__ uint64_t cand[SEL_GATHER];
     __shared__ uint64_t s_prefix;
     __shared__ int64_t s_k;
+    __shared__ uint32_t s_in_bin, n_cand;
     const int tid = threadIdx.x;
     const double* row = x + (size_t)blockIdx.x * N;
     if (N <= 0) {
@@ -83,9 +89,33 @@ __global__ void __launch_bounds__(SEL_THREADS) select_kth(const double* x, int64
             while (b < SEL_BINS - 1 && acc + hist[b] < k) acc += hist[b++];
             s_prefix = prefix | ((uint64_t)b << shift);
             s_k = k - acc;
+            s_in_bin = hist[b];
+            n_cand = 0;
         }
         prefix_mask |= ((bits == 64 ? ~0ull : ((1ull << bits) - 1)) << shift);
         __syncthreads();
+        if (shift > 0 && s_in_bin <= (uint32_t)SEL_GATHER) {
+            // few enough left: gather them, and take the one with fewer than k below it and at least k not above it
+            const uint64_t want = s_prefix;
+            for (int64_t i = tid; i < N; i += SEL_THREADS) {
+                const uint64_t v = ordered_bits(row[i]);
+                if ((v & prefix_mask) == want) cand[atomicAdd(&n_cand, 1u)] = v;
+            }
+            __syncthreads();
+            const int n = (int)n_cand;
+            const int64_t kk = s_k;
+            for (int c = tid; c < n; c += SEL_THREADS) {
+                const uint64_t mine = cand[c];
+                int64_t less = 0, leq = 0;
+                for (int j = 0; j < n; ++j) {
+                    less += cand[j] < mine ? 1 : 0;
+                    leq += cand[j] <= mine ? 1 : 0;
+                }
+                if (less < kk && kk <= leq) s_prefix = mine;      // (every such element has the same value)
+            }
+            __syncthreads();
+            break;
+        }
     }
     if (tid == 0) {
         uint64_t v = s_prefix;
