@@ -70,7 +70,17 @@ __global__ void __launch_bounds__(SEL_THREADS) select_kth(const double* x, int64
         __syncthreads();
         const uint64_t prefix = s_prefix;
         const int64_t k = s_k;
-        for (int64_t i = tid; i < N; i += SEL_THREADS) {
+        // (four loads in flight per thread)
+        int64_t i = tid;
+        for (; i + 3 * SEL_THREADS < N; i += 4 * SEL_THREADS) {
+            uint64_t v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) v[u] = ordered_bits(row[i + u * SEL_THREADS]);
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                if ((v[u] & prefix_mask) == prefix) atomicAdd(&hist[(v[u] >> shift) & ((1u << bits) - 1)], 1u);
+        }
+        for (; i < N; i += SEL_THREADS) {
             const uint64_t v = ordered_bits(row[i]);
             if ((v & prefix_mask) == prefix) atomicAdd(&hist[(v >> shift) & ((1u << bits) - 1)], 1u);
         }
@@ -97,7 +107,16 @@ __global__ void __launch_bounds__(SEL_THREADS) select_kth(const double* x, int64
         if (shift > 0 && s_in_bin <= (uint32_t)SEL_GATHER) {
             // few enough left: gather them, and take the one with fewer than k below it and at least k not above it
             const uint64_t want = s_prefix;
-            for (int64_t i = tid; i < N; i += SEL_THREADS) {
+            int64_t i = tid;
+            for (; i + 3 * SEL_THREADS < N; i += 4 * SEL_THREADS) {
+                uint64_t v[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) v[u] = ordered_bits(row[i + u * SEL_THREADS]);
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    if ((v[u] & prefix_mask) == want) cand[atomicAdd(&n_cand, 1u)] = v[u];
+            }
+            for (; i < N; i += SEL_THREADS) {
                 const uint64_t v = ordered_bits(row[i]);
                 if ((v & prefix_mask) == want) cand[atomicAdd(&n_cand, 1u)] = v;
             }
