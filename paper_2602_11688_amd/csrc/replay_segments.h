@@ -1177,22 +1177,24 @@ __device__ __forceinline__ void cache_wave(const SegArgs& a, int p, int lane, Ha
             const int32_t val = reset_lane && rep != best ? NEVER_CACHED : rv;
             st(cell_of(mine.my_off, rep), val);
         }
-        if (mine.flags & DESC_FRESH_MORE) {
-            const int first_fresh = (mine.flags >> 16) & 15;
-            const int stop = (s < 8 ? s : 8) - ((mine.flags & DESC_FRESH_TAIL) ? 1 : 0);
-            const int32_t fresh_cell = is_best ? (int32_t)r : NEVER_CACHED;
-            for (int k = first_fresh; k < stop; ++k) {
-                const uint32_t off = ld(&dr->slot[k]);
-                st(cell_at(in ? off : spare_row), fresh_cell);
+        if (mine.flags & (DESC_FRESH_MORE | DESC_DEEP)) {      // (one test on the usual path for the two rare cases)
+            if (mine.flags & DESC_FRESH_MORE) {
+                const int first_fresh = (mine.flags >> 16) & 15;
+                const int stop = (s < 8 ? s : 8) - ((mine.flags & DESC_FRESH_TAIL) ? 1 : 0);
+                const int32_t fresh_cell = is_best ? (int32_t)r : NEVER_CACHED;
+                for (int k = first_fresh; k < stop; ++k) {
+                    const uint32_t off = ld(&dr->slot[k]);
+                    st(cell_at(in ? off : spare_row), fresh_cell);
+                }
             }
-        }
-        if (mine.flags & DESC_DEEP) {
-            const int64_t j0 = dr->j0;
-            for (int j = 8; j < s; ++j) {
-                const SegRef sr = a.seg[j0 + j];
-                const uint32_t off = (uint32_t)sr.id * row_bytes;
-                if (sr.end & SEG_FRESH) st(cell_at(in ? off : spare_row), is_best ? (int32_t)r : NEVER_CACHED);
-                else if (is_best) st(cell_at(off), (int32_t)r);
+            if (mine.flags & DESC_DEEP) {
+                const int64_t j0 = dr->j0;
+                for (int j = 8; j < s; ++j) {
+                    const SegRef sr = a.seg[j0 + j];
+                    const uint32_t off = (uint32_t)sr.id * row_bytes;
+                    if (sr.end & SEG_FRESH) st(cell_at(in ? off : spare_row), is_best ? (int32_t)r : NEVER_CACHED);
+                    else if (is_best) st(cell_at(off), (int32_t)r);
+                }
             }
         }
 
