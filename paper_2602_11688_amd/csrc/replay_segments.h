@@ -182,19 +182,19 @@ __device__ __forceinline__ double clip(double x, double lo, double hi) {
     return hi < up ? hi : up;
 }
 
-// k-th smallest (1-based) of the W values of `ring` (LDS), by counting: the element with fewer than k values
-// below it and at least k not above it.  Every lane takes the elements lane, lane + 64, ..., two at a time;
-// the values they are counted against are read eight at a time (the ring is padded with +inf up to a multiple
-// of eight, which no count sees).
+// k-th smallest (1-based) of the W values of `ring` (LDS), by counting: every lane takes the elements lane,
+// lane + 64, ..., two at a time, and counts the values below each (values read eight at a time; the ring is padded
+// with +inf up to a multiple of eight, which no count sees).  An element is at most the k-th smallest iff fewer than
+// k values are below it, and among those the k-th smallest has the most values below it.
 __device__ __forceinline__ double window_kth(const double* ring, int W, int kth, int lane) {
     double found = 0.0;
-    bool have = false;
+    int most = -1;              // most values below an element of this lane that has fewer than kth below it
     const int W8 = (W + 7) & ~7;
     for (int e0 = 0; e0 < W; e0 += 2 * WAVE) {
         const int ea = e0 + lane, eb = e0 + WAVE + lane;
         const bool va = ea < W, vb = eb < W;
         const double xa = ring[va ? ea : 0], xb = ring[vb ? eb : 0];
-        int less_a = 0, leq_a = 0, less_b = 0, leq_b = 0;
+        int less_a = 0, less_b = 0;
         for (int i = 0; i < W8; i += 8) {
             double v[8];
 #pragma unroll
@@ -202,21 +202,20 @@ __device__ __forceinline__ double window_kth(const double* ring, int W, int kth,
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
                 less_a += v[j] < xa ? 1 : 0;
-                leq_a += v[j] <= xa ? 1 : 0;
                 less_b += v[j] < xb ? 1 : 0;
-                leq_b += v[j] <= xb ? 1 : 0;
             }
         }
-        if (va && less_a < kth && kth <= leq_a) {
+        if (va && less_a < kth && less_a > most) {
             found = xa;
-            have = true;
+            most = less_a;
         }
-        if (vb && less_b < kth && kth <= leq_b) {
+        if (vb && less_b < kth && less_b > most) {
             found = xb;
-            have = true;
+            most = less_b;
         }
     }
-    const unsigned long long who = __ballot(have);      // every holder has the same value
+    const unsigned key = ~(unsigned)(most + 1);                 // (the largest `most` is the smallest key)
+    const unsigned long long who = __ballot(key == wave_min_u32(key));         // every holder has the same value
     return readlane_f64(found, __ffsll(who) - 1);
 }
 
