@@ -455,7 +455,16 @@ struct SlotHead {
     int tail;            // youngest request of the slot's list
 };
 
-struct SlotQueues {
+// the slots with nothing in flight, per pass (to be handed to serve after the lists have been retired further)
+struct SlotIdle {
+    unsigned long long m0, m1, m2, m3;
+};
+
+// DEFER: the record that moves up in a deep list is fetched without waiting (see f_slot below).  The registers it
+// arrives in live across the request loop; an instantiation in which the compiler copies them around on the usual
+// path (it then has to wait for memory there, with whatever stores are under way) does better without.
+template <bool DEFER>
+struct SlotQueuesT {
     static constexpr int PASSES = 4;
     static constexpr int SLOTS = PASSES * WAVE;
     SlotHead H0, H1, H2, H3;
@@ -515,7 +524,7 @@ struct SlotQueues {
 
     // The record that was requested by an earlier pop has arrived: it becomes the slot's second oldest.
     __device__ __forceinline__ void settle() {
-        if (!f_any) return;
+        if (!DEFER || !f_any) return;
         f_any = false;
         if (f_slot >= 0) {
             s_done[f_slot] = f_done;
@@ -549,7 +558,7 @@ struct SlotQueues {
                 n_tok = s_tok[g];
                 n_depth = d - 1;
                 int x = n_depth >= 2 ? s_next[g] : -1;      // the request that moves into second position
-                if (!(n_done <= t) && x >= 0 && f_slot < 0) {
+                if (DEFER && !(n_done <= t) && x >= 0 && f_slot < 0) {
                     // the usual case of a deep list: the new head stays, its successor is requested and settled later
                     f_slot = g;
                     s_next[g] = -1;
@@ -584,7 +593,7 @@ struct SlotQueues {
                     }
                 }
             }
-            f_any = f_any || ballot(f_slot >= 0) != 0;
+            if (DEFER) f_any = f_any || ballot(f_slot >= 0) != 0;
             // (further completions are rare: their tokens reach the replicas' lanes one slot at a time)
             for (unsigned long long rest = ballot(dc != 0.0); rest != 0; rest &= rest - 1) {
                 const int l = __builtin_ctzll(rest);
@@ -682,15 +691,11 @@ struct SlotQueues {
         my_q += lane == best ? (double)L : 0.0;
         my_cnt += lane == best ? 1.0 : 0.0;
     }
-    // the slots with nothing in flight, per pass (to be handed to serve after the lists have been retired further)
-    struct Idle {
-        unsigned long long m0, m1, m2, m3;
-    };
-    __device__ __forceinline__ Idle idle_slots() const {
-        return Idle{ballot(H0.depth == 0), ballot(H1.depth == 0), ballot(H2.depth == 0), ballot(H3.depth == 0)};
+    __device__ __forceinline__ SlotIdle idle_slots() const {
+        return SlotIdle{ballot(H0.depth == 0), ballot(H1.depth == 0), ballot(H2.depth == 0), ballot(H3.depth == 0)};
     }
     __device__ __forceinline__ void serve(int64_t r, int best, double t, double rtt_best, int uncached, int L, int O,
-                                          double a_pf, double a_dec, Rec* rec, int lane, const Idle& idle_then,
+                                          double a_pf, double a_dec, Rec* rec, int lane, const SlotIdle& idle_then,
                                           double* ttft_out, double* e2e_out, double* done_out) {
         switch ((best << log2bp) >> 6) {       // the pass that holds the replica's slots
             case 0: serve_in(H0, lane, idle_then.m0, r, best, t, rtt_best, uncached, L, O, a_pf, a_dec, rec, lane, ttft_out, e2e_out, done_out); break;
@@ -700,6 +705,8 @@ struct SlotQueues {
         }
     }
 };
+
+using SlotQueues = SlotQueuesT<true>;
 
 // Weighted score of Eq. 3 for one replica, in the fixed association (w_rtt*rtt + w_prefill*pf) + w_queue*qd
 // with every product and sum rounded on its own.  The first two terms do not depend on the load signal and

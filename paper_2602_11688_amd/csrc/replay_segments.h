@@ -482,7 +482,8 @@ __device__ __forceinline__ void queue_wave(const SegArgs& a, int p, int lane, un
     const int64_t N = a.N;
     // the queue state: one lane per service slot where the model's shape allows it, else one lane per replica
     // with the slots in LDS
-    typename std::conditional<SLOTS, SlotQueues, Queues>::type Q;
+    // (the online tuner's instantiation does without the deferred fetch of deep lists: see SlotQueuesT)
+    typename std::conditional<SLOTS, SlotQueuesT<MODE != MODE_ONLINE>, Queues>::type Q;
     if constexpr (SLOTS) {
         Q.init(lds_raw, R, a.B, lane);
     } else {
@@ -604,7 +605,7 @@ __device__ __forceinline__ void queue_wave(const SegArgs& a, int p, int lane, un
             // The service step still has to see the slots that were idle at this request's time, so their set is
             // kept.
             unsigned long long idle_now = 0;
-            SlotQueues::Idle idle_then{0, 0, 0, 0};
+            SlotIdle idle_then{0, 0, 0, 0};
             if constexpr (SLOTS) {
                 idle_then = Q.idle_slots();
             } else {
