@@ -182,41 +182,47 @@ __device__ __forceinline__ double clip(double x, double lo, double hi) {
     return hi < up ? hi : up;
 }
 
-// k-th smallest (1-based) of the W values of `ring` (LDS), by counting: every lane takes the elements lane,
-// lane + 64, ..., two at a time, and counts the values below each (values read eight at a time; the ring is padded
-// with +inf up to a multiple of eight, which no count sees).  An element is at most the k-th smallest iff fewer than
-// k values are below it, and among those the k-th smallest has the most values below it.
+// k-th smallest (1-based) of the W values of `ring` (LDS, W <= 1024), by taking elements out from the nearer end: the
+// largest W + 1 - k times, or the smallest k times (the tuner's k is the 95th percentile's: 7 rounds for a window
+// of 128, against 128 comparisons for every element when the elements are ranked by counting).  Lane l looks after
+// the elements l, l + 64, ...; a round takes this lane's best remaining element, finds the best over the wavefront
+// (two 32-bit cross-lane reductions on the order-preserving integer image of the doubles, the second one only when
+// the high words tie) and marks it as taken in the lowest lane that holds it.  Equal values are taken one by one, as
+// a sorted list would have them.
 __device__ __forceinline__ double window_kth(const double* ring, int W, int kth, int lane) {
-    double found = 0.0;
-    int most = -1;              // most values below an element of this lane that has fewer than kth below it
-    const int W8 = (W + 7) & ~7;
-    for (int e0 = 0; e0 < W; e0 += 2 * WAVE) {
-        const int ea = e0 + lane, eb = e0 + WAVE + lane;
-        const bool va = ea < W, vb = eb < W;
-        const double xa = ring[va ? ea : 0], xb = ring[vb ? eb : 0];
-        int less_a = 0, less_b = 0;
-        for (int i = 0; i < W8; i += 8) {
-            double v[8];
-#pragma unroll
-            for (int j = 0; j < 8; ++j) v[j] = ring[i + j];
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                less_a += v[j] < xa ? 1 : 0;
-                less_b += v[j] < xb ? 1 : 0;
-            }
+    const bool from_top = W + 1 - kth <= kth;
+    const int rounds = from_top ? W + 1 - kth : kth;
+    unsigned taken = 0;                 // bit c: element c * 64 + lane is out
+    unsigned last_hi = 0, last_lo = 0;
+    for (int round = 0; round < rounds; ++round) {
+        unsigned long long best = 0;
+        int best_c = -1;
+        for (int c = 0, e = lane; e < W; ++c, e += WAVE) {
+            const unsigned long long b = (unsigned long long)__double_as_longlong(ring[e]);
+            const unsigned long long up = (b >> 63) ? ~b : (b | 0x8000000000000000ull);      // increasing with the value
+            const unsigned long long key = from_top ? up : ~up;                               // the wanted end is the largest key
+            const bool better = ((taken >> c) & 1u) == 0 && (best_c < 0 || key > best);
+            best = better ? key : best;
+            best_c = better ? c : best_c;
         }
-        if (va && less_a < kth && less_a > most) {
-            found = xa;
-            most = less_a;
+        const bool have = best_c >= 0;
+        const unsigned hi = (unsigned)(best >> 32), lo = (unsigned)best;
+        const unsigned top_hi = ~wave_min_u32(~(have ? hi : 0u));
+        const bool tie = have && hi == top_hi;
+        unsigned long long who = __ballot(tie);
+        if (__builtin_popcountll(who) > 1) {
+            const unsigned top_lo = ~wave_min_u32(~(tie ? lo : 0u));
+            who = __ballot(tie && lo == top_lo);
         }
-        if (vb && less_b < kth && less_b > most) {
-            found = xb;
-            most = less_b;
-        }
+        const int winner = __ffsll(who) - 1;
+        last_hi = (unsigned)__builtin_amdgcn_readlane((int)hi, winner);
+        last_lo = (unsigned)__builtin_amdgcn_readlane((int)lo, winner);
+        taken |= lane == winner ? 1u << (best_c & 31) : 0u;
     }
-    const unsigned key = ~(unsigned)(most + 1);                 // (the largest `most` is the smallest key)
-    const unsigned long long who = __ballot(key == wave_min_u32(key));         // every holder has the same value
-    return readlane_f64(found, __ffsll(who) - 1);
+    const unsigned long long key = ((unsigned long long)last_hi << 32) | last_lo;
+    const unsigned long long up = from_top ? key : ~key;
+    const unsigned long long b = (up >> 63) ? (up & 0x7FFFFFFFFFFFFFFFull) : ~up;
+    return __longlong_as_double((long long)b);
 }
 
 // Rows of one request's first SEG_CHUNK segments as seen by this lane (= replica), with the segments' end
