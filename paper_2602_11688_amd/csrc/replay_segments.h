@@ -194,13 +194,24 @@ __device__ __forceinline__ double window_kth(const double* ring, int W, int kth,
     const int rounds = from_top ? W + 1 - kth : kth;
     unsigned taken = 0;                 // bit c: element c * 64 + lane is out
     unsigned last_hi = 0, last_lo = 0;
+    // the wanted end is the largest key: the order-preserving integer image of the value, complemented from the bottom
+    auto key_of = [&](int e) {
+        const unsigned long long b = (unsigned long long)__double_as_longlong(ring[e]);
+        const unsigned long long up = (b >> 63) ? ~b : (b | 0x8000000000000000ull);      // increasing with the value
+        return from_top ? up : ~up;
+    };
+    // (this lane's first two elements stay in registers: windows of up to 128 values read LDS once)
+    const bool has0 = lane < W, has1 = lane + WAVE < W;
+    const unsigned long long key0 = has0 ? key_of(lane) : 0, key1 = has1 ? key_of(lane + WAVE) : 0;
     for (int round = 0; round < rounds; ++round) {
-        unsigned long long best = 0;
-        int best_c = -1;
-        for (int c = 0, e = lane; e < W; ++c, e += WAVE) {
-            const unsigned long long b = (unsigned long long)__double_as_longlong(ring[e]);
-            const unsigned long long up = (b >> 63) ? ~b : (b | 0x8000000000000000ull);      // increasing with the value
-            const unsigned long long key = from_top ? up : ~up;                               // the wanted end is the largest key
+        const bool use0 = has0 && (taken & 1u) == 0;
+        unsigned long long best = use0 ? key0 : 0;
+        int best_c = use0 ? 0 : -1;
+        const bool use1 = has1 && (taken & 2u) == 0 && (best_c < 0 || key1 > best);
+        best = use1 ? key1 : best;
+        best_c = use1 ? 1 : best_c;
+        for (int c = 2, e = lane + 2 * WAVE; e < W; ++c, e += WAVE) {
+            const unsigned long long key = key_of(e);
             const bool better = ((taken >> c) & 1u) == 0 && (best_c < 0 || key > best);
             best = better ? key : best;
             best_c = better ? c : best_c;
