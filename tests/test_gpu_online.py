@@ -117,6 +117,21 @@ def test_window_and_hop_shapes(window, hop, n):
     _check(tr, _model(wl), wl.rtt_ms, theta0, z, [3.0, 1.0, 5.0], window, hop, sigma0=1.5)
 
 
+@pytest.mark.parametrize("window,hop", [(2, 1), (65, 3), (128, 32), (129, 16), (300, 50), (1024, 100)])
+def test_windows_full_of_equal_latencies(window, hop):
+    """Every request is the same and arrives when the fleet is idle, every replica is equally far: the windows hold
+    a handful of distinct TTFT values many times over (one per hit length), so the window's order statistic has to
+    come out right among equal values, for windows that span one, two and many elements per lane."""
+    n = 2600
+    blocks = 3
+    tr = Trace(np.arange(n, dtype=np.int64) * 100000, np.full(n, blocks * 512, np.int32), np.full(n, 2, np.int32),
+               np.arange(n + 1, dtype=np.int64) * blocks, np.tile(np.arange(1, blocks + 1, dtype=np.int64), n))
+    steps = g.online_steps(n, window, hop)
+    z = np.random.default_rng(window).standard_normal((2, steps, 3))
+    theta0 = np.array([[0.5, 1.0, 0.1], [1.0, 1.0, 0.3]])
+    _check(tr, g.Model(4, 2, 0, 0.05, 20.0), [25.0, 25.0, 25.0, 25.0], theta0, z, 1.0, window, hop, sigma0=1.0)
+
+
 def test_all_weights_tuned_and_wide_range():
     wl = tg.config(3, 3000)
     steps = g.online_steps(3000, 128, 32)
